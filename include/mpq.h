@@ -1,0 +1,131 @@
+/*
+ * mpq.h - C ABI of the 2/4/16-bit mixed-precision weight library for MI355X (gfx950).
+ *
+ * The library implements the decode-time hot path of arXiv 2311.16442 ("Fast and Efficient 2-bit
+ * LLM Inference on GPU: 2/4/16-bit in a Weight Matrix with Asynchronous Dequantization"):
+ * y = W x (and Y = X W^T for a small batch) where W is stored as
+ *   - per-K-group 2-bit or 4-bit integer codes (Sec. 3.3 "Intra-weight Quantization": the bit width
+ *     is chosen per group of input channels and is the same for every output channel),
+ *   - a quantized first-order scale and an integer first-order zero point per (row, group), the
+ *     scale being recovered by a second-order dequantization with an fp16 (scale, zero) pair
+ *     (Sec. 2.2 eq. 5; Sec. 3.3; Algorithm 1 "1st s <- dequantize(1st s_int, 2nd z, 2nd s)"),
+ *   - fp16 outliers in CSR form, one 32-bit word (fp16 value, 16-bit column) per outlier plus one
+ *     32-bit running count per row, located only inside 2-bit groups (Sec. 2.3, Sec. 4.3).
+ *
+ * Conventions.  W is N x K (N output channels = rows, K input channels = columns).  g1 = first
+ * order group size along K, G = K/g1 groups per row, g2 = first-order groups per second-order
+ * pair, S = ceil(G/g2).  All fp16 values cross this boundary as their 16-bit patterns (uint16_t).
+ *
+ * What one weight decodes to (all arithmetic IEEE, round-to-nearest-even, no fused operations):
+ *   s1        = fp16( (fp32(s_int) - fp32(z2)) * fp32(s2) )          second-order dequantization
+ *   Wd[n][k]  = fp16( fp32(code - z1) * fp32(s1) )                   first-order dequantization
+ *   Wfull     = fp16( fp32(Wd) + fp32(val) ) at outlier positions    outliers are additive
+ *   y[n]      = sum_k Wd[n][k] x[k] + sum_{outliers of row n} val x[col]
+ *
+ * Memory.  The library never allocates, frees or retains device memory and keeps no state between
+ * calls.  Host entry points take HOST pointers; device entry points take DEVICE pointers for bulk
+ * data and a HOST pointer to the blob header (the first MPQ_HEADER_BYTES bytes of the packed
+ * blob), so that no call ever needs a device-to-host copy.  All pointers are owned by the caller.
+ * Device entry points only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
+ * default stream) and return without waiting for it.
+ *
+ * Errors.  Every entry point returns an mpq_status; nothing is launched unless all arguments
+ * validate.  No entry point throws or aborts.
+ */
+#ifndef MPQ_H_
+#define MPQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MPQ_HEADER_BYTES 256u
+#define MPQ_MAX_M 32          /* largest batch the small-M product accepts */
+
+typedef enum {
+  MPQ_OK = 0,
+  MPQ_ERR_NULL = 1,            /* a required pointer is NULL */
+  MPQ_ERR_SHAPE = 2,           /* N, K, g1, g2, M outside what the format allows */
+  MPQ_ERR_ALIGN = 3,           /* a device pointer is not 16-byte aligned */
+  MPQ_ERR_CODE_RANGE = 4,      /* a code exceeds 2^b - 1 for its group's bit width b */
+  MPQ_ERR_OUTLIER_IN_4BIT = 5, /* an outlier column lies in a 4-bit group (Sec. 4.3 forbids it) */
+  MPQ_ERR_CSR = 6,             /* row_ptr not monotone / columns not strictly increasing / col >= K */
+  MPQ_ERR_BLOB = 7,            /* header magic, version or recorded sizes do not match */
+  MPQ_ERR_SIZE = 8,            /* caller's buffer is smaller than required */
+  MPQ_ERR_UNSUPPORTED = 9,     /* valid format that this build's kernels do not implement */
+  MPQ_ERR_HIP = 10             /* the HIP runtime reported a launch error */
+} mpq_status;
+
+/* Shape of a matrix in the logical format. g2_axis: 0 = a second-order pair covers g2 consecutive
+ * groups along K of one row (the layout the kernels implement); 1 = it covers the same K-group of
+ * g2 consecutive rows (the paper's "direction of output channels", Sec. 2.2; host/pack only). */
+typedef struct {
+  int32_t N, K, g1, g2, g2_axis;
+} mpq_desc;
+
+/* Logical (unpacked) matrix: what a quantizer hands to mpq_pack_host. HOST pointers, read-only. */
+typedef struct {
+  const uint8_t* is4;      /* [G]     1 = the group is 4-bit for all rows, 0 = 2-bit            */
+  const uint8_t* codes;    /* [N*K]   one code per byte, row-major                               */
+  const uint8_t* s_int;    /* [N*G]   quantized first-order scale                                */
+  const uint8_t* z1;       /* [N*G]   first-order zero point                                     */
+  const uint16_t* s2;      /* [N*S]   fp16 second-order scale (g2_axis 0), else [ceil(N/g2)*G]   */
+  const uint16_t* z2;      /* same shape, fp16 second-order zero                                 */
+  const int32_t* row_ptr;  /* [N+1]   CSR row pointer, row_ptr[0] = 0                            */
+  const uint16_t* col;     /* [nnz]   column index, strictly increasing inside a row             */
+  const uint16_t* val;     /* [nnz]   fp16 outlier value                                         */
+} mpq_logical;
+
+/* Human-readable name of a status code; never NULL. */
+const char* mpq_status_str(mpq_status s);
+
+/* Average stored bits per weight.
+ * mode 0: bits actually stored by this format without alignment padding:
+ *         8 * (codes + 2 B per (row,group) + 4 B per (row,super-group) + 4 B per outlier
+ *              + 4 B per row pointer) / (N*K).
+ * mode 1: the paper's mixed-precision formula (Sec. 3.3, the display after "the average bit-width
+ *         of each weight element"): alpha*(2 + (2+Ns)/g1 + (Ns+16)/(g1*g2)) + (1-alpha)*4 with
+ *         alpha = 1 - n4/G and Ns = `ns_bits`, plus the outlier increment (16+16-2)*nnz/(N*K)
+ *         (Sec. 4.2).
+ * Returns a negative value on invalid arguments. */
+double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns_bits);
+
+/* Size in bytes of the packed blob for this shape, 4-bit map and outlier count.
+ * `is4` is a HOST array of G bytes. */
+mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, int64_t nnz, size_t* bytes);
+
+/* Sec. 3.3 "Memory Alignment": split the codes into a 2-bit stream and a 4-bit stream whose
+ * per-lane units are 16 bytes, homogeneous in bit width and 16-byte aligned, interleave the
+ * per-group (s_int, z1) bytes and the (s2, z2) halves, and store the outliers as 32-bit words.
+ * Validates the logical matrix completely (code ranges, CSR order, outliers only in 2-bit groups)
+ * before writing.  `blob_host` must hold `bytes` >= mpq_packed_size(...) bytes; all of them are
+ * written (padding is zero).  The blob is position independent and may be copied byte for byte. */
+mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_host, size_t bytes);
+
+/* Read back the shape recorded in a blob header (HOST pointer to at least MPQ_HEADER_BYTES). */
+mpq_status mpq_blob_info(const void* hdr_host, mpq_desc* out, int64_t* nnz, int32_t* n4,
+                         uint64_t* total_bytes);
+
+/* Dequantize the whole matrix to row-major fp16 W_out[N*K] (device), bit-exact to the definition
+ * at the top of this file (eq. 5 applied twice).  add_outliers != 0 adds the CSR values. */
+mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_out_dev,
+                       int add_outliers, void* stream);
+
+/* Algorithm 1 (GEMV with asynchronous dequantization) with the outlier product of Sec. 4.3 fused
+ * in: y[n] = fp16( sum_k Wd[n][k] x[k] + sum_j val_j x[col_j] ), fp32 accumulation.
+ * x_dev: K fp16 values, y_dev: N fp16 values (overwritten), both 16-byte aligned, not aliased. */
+mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev,
+                    uint16_t* y_dev, void* stream);
+
+/* Small-batch product Y[m][n] = sum_k X[m][k] W[n][k] (+ outliers), 1 <= M <= MPQ_MAX_M.
+ * X_dev is M x K row-major fp16, Y_dev is M x N row-major fp16 (overwritten). */
+mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev,
+                    uint16_t* Y_dev, int32_t M, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPQ_H_ */
