@@ -1,0 +1,196 @@
+"""Python binding of libmpq (2/4/16-bit mixed-precision weights on MI355X).
+
+Argument marshalling only: every function here forwards to the C entry point of the same name
+declared in include/mpq.h.  There is no Python or CPU fallback; if the compiled library is
+missing the import of a device function raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmpq.so")
+HEADER_BYTES = 256
+MAX_M = 32
+
+STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ_ERR_CODE_RANGE",
+                "MPQ_ERR_OUTLIER_IN_4BIT", "MPQ_ERR_CSR", "MPQ_ERR_BLOB", "MPQ_ERR_SIZE",
+                "MPQ_ERR_UNSUPPORTED", "MPQ_ERR_HIP"]
+(MPQ_OK, MPQ_ERR_NULL, MPQ_ERR_SHAPE, MPQ_ERR_ALIGN, MPQ_ERR_CODE_RANGE, MPQ_ERR_OUTLIER_IN_4BIT,
+ MPQ_ERR_CSR, MPQ_ERR_BLOB, MPQ_ERR_SIZE, MPQ_ERR_UNSUPPORTED, MPQ_ERR_HIP) = range(11)
+
+EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_packed_size", "mpq_pack_host", "mpq_blob_info",
+           "mpq_dequant", "mpq_gemv", "mpq_gemm"]
+
+
+class MpqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        name = STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else str(status)
+        super().__init__(f"{where}: {name} ({status_str(status)})")
+
+
+class Desc(C.Structure):
+    _fields_ = [("N", C.c_int32), ("K", C.c_int32), ("g1", C.c_int32), ("g2", C.c_int32),
+                ("g2_axis", C.c_int32)]
+
+
+class LogicalPtrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("is4", "codes", "s_int", "z1", "s2", "z2", "row_ptr", "col", "val")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        L.mpq_status_str.restype = C.c_char_p
+        L.mpq_status_str.argtypes = [C.c_int]
+        L.mpq_avg_bits.restype = C.c_double
+        L.mpq_avg_bits.argtypes = [C.POINTER(Desc), C.c_int32, C.c_int64, C.c_int, C.c_int]
+        L.mpq_packed_size.restype = C.c_int
+        L.mpq_packed_size.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_int64, C.POINTER(C.c_size_t)]
+        L.mpq_pack_host.restype = C.c_int
+        L.mpq_pack_host.argtypes = [C.POINTER(Desc), C.POINTER(LogicalPtrs), C.c_void_p, C.c_size_t]
+        L.mpq_blob_info.restype = C.c_int
+        L.mpq_blob_info.argtypes = [C.c_void_p, C.POINTER(Desc), C.POINTER(C.c_int64),
+                                    C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
+        L.mpq_dequant.restype = C.c_int
+        L.mpq_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        L.mpq_gemv.restype = C.c_int
+        L.mpq_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.mpq_gemm.restype = C.c_int
+        L.mpq_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().mpq_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != MPQ_OK:
+        raise MpqError(status, where)
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def avg_bits(N, K, g1, g2, n4, nnz, mode=0, ns_bits=4, g2_axis=0) -> float:
+    d = Desc(N, K, g1, g2, g2_axis)
+    return float(lib().mpq_avg_bits(C.byref(d), int(n4), int(nnz), int(mode), int(ns_bits)))
+
+
+def packed_size(N, K, g1, g2, is4, nnz, g2_axis=0) -> int:
+    d = Desc(N, K, g1, g2, g2_axis)
+    is4 = _np(is4, np.uint8)
+    out = C.c_size_t(0)
+    _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p), int(nnz), C.byref(out)),
+           "mpq_packed_size")
+    return int(out.value)
+
+
+@dataclass
+class Packed:
+    """A packed matrix on the host: `blob` (uint8 array, starts with the 256-byte header)."""
+    blob: np.ndarray
+    N: int
+    K: int
+    g1: int
+    g2: int
+    n4: int
+    nnz: int
+
+    @property
+    def header(self) -> np.ndarray:
+        return self.blob[:HEADER_BYTES]
+
+
+def pack(N, K, g1, g2, is4, codes, s_int, z1, s2, z2, row_ptr, col, val, g2_axis=0) -> Packed:
+    """mpq_packed_size + mpq_pack_host on host arrays in the logical format."""
+    d = Desc(int(N), int(K), int(g1), int(g2), int(g2_axis))
+    is4 = _np(is4, np.uint8)
+    arrs = dict(is4=is4, codes=_np(codes, np.uint8), s_int=_np(s_int, np.uint8), z1=_np(z1, np.uint8),
+                s2=_np(s2, np.uint16), z2=_np(z2, np.uint16), row_ptr=_np(row_ptr, np.int32),
+                col=_np(col, np.uint16), val=_np(val, np.uint16))
+    nnz = int(arrs["row_ptr"][-1]) if arrs["row_ptr"].size else 0
+    size = C.c_size_t(0)
+    _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p), max(nnz, 0), C.byref(size)),
+           "mpq_packed_size")
+    blob = np.empty(size.value, dtype=np.uint8)
+    ptrs = LogicalPtrs(**{k: (v.ctypes.data if v.size else None) for k, v in arrs.items()})
+    _check(lib().mpq_pack_host(C.byref(d), C.byref(ptrs), blob.ctypes.data_as(C.c_void_p), size.value),
+           "mpq_pack_host")
+    info = blob_info(blob)
+    return Packed(blob, int(N), int(K), int(g1), int(g2), info["n4"], info["nnz"])
+
+
+def pack_logical(lg, g2_axis=0) -> Packed:
+    s = lg.spec
+    return pack(s.N, s.K, s.g1, s.g2, lg.is4, lg.codes, lg.s_int, lg.z1, lg.s2, lg.z2,
+                lg.row_ptr, lg.col, lg.val, g2_axis)
+
+
+def blob_info(header) -> dict:
+    h = _np(header, np.uint8)
+    if h.size < HEADER_BYTES:
+        raise MpqError(MPQ_ERR_SIZE, "mpq_blob_info")
+    d = Desc()
+    nnz, n4, tot = C.c_int64(0), C.c_int32(0), C.c_uint64(0)
+    _check(lib().mpq_blob_info(h.ctypes.data_as(C.c_void_p), C.byref(d), C.byref(nnz), C.byref(n4),
+                               C.byref(tot)), "mpq_blob_info")
+    return dict(N=d.N, K=d.K, g1=d.g1, g2=d.g2, g2_axis=d.g2_axis, nnz=int(nnz.value), n4=int(n4.value),
+                total_bytes=int(tot.value))
+
+
+# ----------------------------------------------------------------------------- device entry points
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if hasattr(stream, "cuda_stream"):
+        return int(stream.cuda_stream) or None
+    return int(stream) or None
+
+
+def _hdr_ptr(header: np.ndarray):
+    h = _np(header, np.uint8)
+    return h, h.ctypes.data_as(C.c_void_p)
+
+
+def dequant(header, blob_dev, W_out_dev, add_outliers=False, stream=None):
+    """mpq_dequant: blob_dev / W_out_dev are torch CUDA tensors (uint8 / 16-bit)."""
+    h, hp = _hdr_ptr(header)
+    _check(lib().mpq_dequant(hp, blob_dev.data_ptr(), W_out_dev.data_ptr(), int(bool(add_outliers)),
+                             _stream_ptr(stream)), "mpq_dequant")
+
+
+def gemv(header, blob_dev, x_dev, y_dev, stream=None):
+    h, hp = _hdr_ptr(header)
+    _check(lib().mpq_gemv(hp, blob_dev.data_ptr(), x_dev.data_ptr(), y_dev.data_ptr(),
+                          _stream_ptr(stream)), "mpq_gemv")
+
+
+def gemm(header, blob_dev, X_dev, Y_dev, M, stream=None):
+    h, hp = _hdr_ptr(header)
+    _check(lib().mpq_gemm(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M),
+                          _stream_ptr(stream)), "mpq_gemm")
+
+
+def raw_status(name: str, *args) -> int:
+    """Call an entry point with raw integers/pointers and return its status (used by error-path tests)."""
+    return int(getattr(lib(), name)(*args))

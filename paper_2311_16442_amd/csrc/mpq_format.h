@@ -1,0 +1,65 @@
+// mpq_format.h - private description of the packed blob (shared by the host packer and the kernels).
+//
+// The blob follows the paper's memory-alignment rule (Sec. 3.3 "Memory Alignment"): the codes are
+// split into two matrices, one per bit width, so that what one thread loads is one aligned vector
+// unit holding codes of a single width.  The unit here is the widest per-lane load of gfx950,
+// 16 bytes: 64 two-bit codes or 32 four-bit codes, always of one row and of consecutive columns.
+//
+// Rows are tiled by 16 (MPQ_TILE_ROWS) and units by 4 along K, so that one 64-lane wavefront load
+// of 1 KiB ("block") is contiguous and covers 16 rows x 4 units with lane = unit_in_block*16 + row
+// - the operand order of the 16x16x32 MFMA, which the small-batch product uses directly and the
+// matrix-vector product reads equally well.
+//
+//   header    256 B                                      (MpqHeader)
+//   unit2     uint32 [4*B2]   per 2-bit unit in stream order: (k0/32) | (super_group << 16);
+//                             0xFFFFFFFF marks a padding unit
+//   unit4     uint32 [4*B4]   the same for 4-bit units
+//   codes2    T x B2 x 64 x 16 B    2-bit stream:  [tile][block][lane] 16-byte units
+//   codes4    T x B4 x 64 x 16 B    4-bit stream
+//   meta1     T x G x 16 x 2 B      (s_int | z1 << 8) per (tile, stream group, row); stream group
+//                                   order = all 2-bit groups in K order, then all 4-bit groups
+//   meta2     T x S x 16 x 4 B      (s2 | z2 << 16) per (tile, super-group, row)
+//   row_ptr   int32 [16*T + 1]      CSR row pointer, rows beyond N repeat nnz
+//   outl      uint32 [nnz]          col | val << 16   (Sec. 2.3: one 32-bit word per outlier)
+//
+// Bit positions inside a unit (4 little-endian dwords):
+//   2-bit: column k0 + kl (kl = 0..63) sits in dword (kl % 8) / 2, bits 16*(kl % 2) + 2*(kl / 8) ..+1
+//   4-bit: column k0 + kl (kl = 0..31) sits in dword (kl % 8) / 2, bits 16*(kl % 2) + 4*(kl / 8) ..+3
+// so that one mask applied to a dword isolates the codes of columns (2r, 2r+1) in the low and high
+// half-word, ready to be turned into a pair of fp16 values.
+//
+// Every section starts on a 256-byte boundary; padding bytes are zero.
+#ifndef MPQ_FORMAT_H_
+#define MPQ_FORMAT_H_
+
+#include <stdint.h>
+
+#define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
+#define MPQ_VERSION 2u
+#define MPQ_TILE_ROWS 16
+#define MPQ_UNITS_PER_BLOCK 4
+#define MPQ_BLOCK_BYTES 1024
+#define MPQ_SECTION_ALIGN 256
+#define MPQ_INVALID_UNIT 0xFFFFFFFFu
+
+typedef struct {
+  uint32_t magic, version;
+  int32_t N, K, g1, g2, g2_axis;
+  int32_t G, S, n2, n4;
+  int32_t U2, U4;  /* 16-byte units per row in the 2-bit / 4-bit stream */
+  int32_t B2, B4;  /* blocks (4 units x 16 rows) per row tile in each stream */
+  int32_t T;       /* row tiles */
+  int64_t nnz;
+  uint64_t off_unit2, off_unit4, off_codes2, off_codes4, off_meta1, off_meta2, off_rowptr, off_outl;
+  uint64_t total_bytes;
+  uint8_t pad[256 - 4 * 16 - 8 - 8 * 8 - 8];
+} MpqHeader;
+
+#ifdef __cplusplus
+static_assert(sizeof(MpqHeader) == 256, "header must be 256 bytes");
+#include "../../include/mpq.h"
+// Accepts a header only if it is byte for byte what the packer writes for the shape it records.
+mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out);
+#endif
+
+#endif /* MPQ_FORMAT_H_ */

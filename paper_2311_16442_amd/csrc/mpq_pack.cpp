@@ -1,0 +1,232 @@
+// mpq_pack.cpp - host side of the library: validation of the logical format, the packed-blob
+// builder (Sec. 3.3 "Memory Alignment": two code matrices with aligned, width-homogeneous vector
+// units), blob inspection and the average-bit formulas (Sec. 2.2, Sec. 3.3, Sec. 4.2).
+#include <string.h>
+
+#include <vector>
+
+#include "../../include/mpq.h"
+#include "mpq_format.h"
+
+namespace {
+
+uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+bool desc_ok(const mpq_desc* d) {
+  if (d->N <= 0 || d->K <= 0 || d->g1 <= 0 || d->g2 <= 0) return false;
+  if (d->K % d->g1 != 0) return false;
+  if (d->K > 65535) return false;  // 16-bit column index (Sec. 2.3)
+  if (d->g2_axis != 0 && d->g2_axis != 1) return false;
+  return true;
+}
+
+// Fills every derived field of the header from the shape, the number of 4-bit groups and nnz.
+mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, MpqHeader* h) {
+  if (!desc_ok(d) || nnz < 0 || n4 < 0 || n4 > d->K / d->g1) return MPQ_ERR_SHAPE;
+  if (d->g1 != 64 && d->g1 != 128) return MPQ_ERR_UNSUPPORTED;  // a unit must not straddle groups
+  if (d->g2_axis != 0) return MPQ_ERR_UNSUPPORTED;
+  memset(h, 0, sizeof(*h));
+  h->magic = MPQ_MAGIC;
+  h->version = MPQ_VERSION;
+  h->N = d->N; h->K = d->K; h->g1 = d->g1; h->g2 = d->g2; h->g2_axis = d->g2_axis;
+  h->G = d->K / d->g1;
+  h->S = (h->G + d->g2 - 1) / d->g2;
+  h->n4 = n4;
+  h->n2 = h->G - n4;
+  h->U2 = h->n2 * (d->g1 / 64);
+  h->U4 = h->n4 * (d->g1 / 32);
+  h->B2 = (h->U2 + MPQ_UNITS_PER_BLOCK - 1) / MPQ_UNITS_PER_BLOCK;
+  h->B4 = (h->U4 + MPQ_UNITS_PER_BLOCK - 1) / MPQ_UNITS_PER_BLOCK;
+  h->T = (d->N + MPQ_TILE_ROWS - 1) / MPQ_TILE_ROWS;
+  h->nnz = nnz;
+  uint64_t off = MPQ_HEADER_BYTES;
+  h->off_unit2 = off; off = align_up(off + 4ull * 4 * h->B2, MPQ_SECTION_ALIGN);
+  h->off_unit4 = off; off = align_up(off + 4ull * 4 * h->B4, MPQ_SECTION_ALIGN);
+  h->off_codes2 = off; off = align_up(off + (uint64_t)h->T * h->B2 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
+  h->off_codes4 = off; off = align_up(off + (uint64_t)h->T * h->B4 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
+  h->off_meta1 = off; off = align_up(off + (uint64_t)h->T * h->G * MPQ_TILE_ROWS * 2, MPQ_SECTION_ALIGN);
+  h->off_meta2 = off; off = align_up(off + (uint64_t)h->T * h->S * MPQ_TILE_ROWS * 4, MPQ_SECTION_ALIGN);
+  h->off_rowptr = off; off = align_up(off + 4ull * ((uint64_t)h->T * MPQ_TILE_ROWS + 1), MPQ_SECTION_ALIGN);
+  h->off_outl = off; off = align_up(off + 4ull * (uint64_t)nnz, MPQ_SECTION_ALIGN);
+  h->total_bytes = off;
+  return MPQ_OK;
+}
+
+int32_t count4(const mpq_desc* d, const uint8_t* is4) {
+  int32_t n4 = 0;
+  for (int32_t g = 0; g < d->K / d->g1; ++g) n4 += is4[g] ? 1 : 0;
+  return n4;
+}
+
+}  // namespace
+
+// Used by the device entry points: a header is accepted only if it is exactly what the packer
+// would have written for the shape it records.
+mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out) {
+  if (!hdr_host) return MPQ_ERR_NULL;
+  MpqHeader h, want;
+  memcpy(&h, hdr_host, sizeof(h));
+  if (h.magic != MPQ_MAGIC || h.version != MPQ_VERSION) return MPQ_ERR_BLOB;
+  mpq_desc d = {h.N, h.K, h.g1, h.g2, h.g2_axis};
+  if (!desc_ok(&d)) return MPQ_ERR_BLOB;
+  if (plan(&d, h.n4, h.nnz, &want) != MPQ_OK) return MPQ_ERR_BLOB;
+  if (memcmp(&h, &want, sizeof(h)) != 0) return MPQ_ERR_BLOB;
+  *out = h;
+  return MPQ_OK;
+}
+
+extern "C" {
+
+const char* mpq_status_str(mpq_status s) {
+  switch (s) {
+    case MPQ_OK: return "ok";
+    case MPQ_ERR_NULL: return "null pointer";
+    case MPQ_ERR_SHAPE: return "invalid shape";
+    case MPQ_ERR_ALIGN: return "pointer not 16-byte aligned";
+    case MPQ_ERR_CODE_RANGE: return "code out of range for its group's bit width";
+    case MPQ_ERR_OUTLIER_IN_4BIT: return "outlier inside a 4-bit group";
+    case MPQ_ERR_CSR: return "malformed CSR";
+    case MPQ_ERR_BLOB: return "bad blob header";
+    case MPQ_ERR_SIZE: return "buffer too small";
+    case MPQ_ERR_UNSUPPORTED: return "format not supported by this build";
+    case MPQ_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns_bits) {
+  if (!d || !desc_ok(d) || n4 < 0 || nnz < 0) return -1.0;
+  const double G = (double)(d->K / d->g1);
+  if (n4 > (int32_t)G) return -1.0;
+  const double NK = (double)d->N * (double)d->K;
+  if (mode == 0) {
+    const double pairs = d->g2_axis == 0
+                             ? (double)d->N * (double)(((int64_t)G + d->g2 - 1) / d->g2)
+                             : (double)((d->N + d->g2 - 1) / d->g2) * G;
+    const double bytes = (double)d->N * ((G - n4) * d->g1 / 4.0 + n4 * d->g1 / 2.0)  // codes
+                         + 2.0 * d->N * G                                            // s_int, z1
+                         + 4.0 * pairs                                               // s2, z2
+                         + 4.0 * (double)nnz + 4.0 * ((double)d->N + 1.0);           // CSR
+    return 8.0 * bytes / NK;
+  }
+  if (mode == 1) {
+    if (ns_bits <= 0) return -1.0;
+    const double alpha = 1.0 - n4 / G;
+    const double two_bit = 2.0 + (2.0 + ns_bits) / d->g1 + (ns_bits + 16.0) / ((double)d->g1 * d->g2);
+    return alpha * two_bit + (1.0 - alpha) * 4.0 + (16.0 + 16.0 - 2.0) * (double)nnz / NK;
+  }
+  return -1.0;
+}
+
+mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, int64_t nnz, size_t* bytes) {
+  if (!d || !is4 || !bytes) return MPQ_ERR_NULL;
+  if (!desc_ok(d)) return MPQ_ERR_SHAPE;
+  MpqHeader h;
+  mpq_status st = plan(d, count4(d, is4), nnz, &h);
+  if (st != MPQ_OK) return st;
+  *bytes = (size_t)h.total_bytes;
+  return MPQ_OK;
+}
+
+mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_host, size_t bytes) {
+  if (!d || !w || !blob_host) return MPQ_ERR_NULL;
+  if (!w->is4 || !w->codes || !w->s_int || !w->z1 || !w->s2 || !w->z2 || !w->row_ptr) return MPQ_ERR_NULL;
+  if (!desc_ok(d)) return MPQ_ERR_SHAPE;
+  const int64_t N = d->N, K = d->K, g1 = d->g1;
+  const int64_t G = K / g1;
+  // ---- validation of the logical matrix, before anything is written
+  if (w->row_ptr[0] != 0) return MPQ_ERR_CSR;
+  for (int64_t n = 0; n < N; ++n)
+    if (w->row_ptr[n + 1] < w->row_ptr[n]) return MPQ_ERR_CSR;
+  const int64_t nnz = w->row_ptr[N];
+  if (nnz > 0 && (!w->col || !w->val)) return MPQ_ERR_NULL;
+  MpqHeader h;
+  mpq_status st = plan(d, count4(d, w->is4), nnz, &h);
+  if (st != MPQ_OK) return st;
+  if (bytes < h.total_bytes) return MPQ_ERR_SIZE;
+  for (int64_t n = 0; n < N; ++n) {
+    const uint8_t* row = w->codes + n * K;
+    for (int64_t g = 0; g < G; ++g) {
+      const uint8_t hi = w->is4[g] ? 15 : 3;
+      for (int64_t k = g * g1; k < (g + 1) * g1; ++k)
+        if (row[k] > hi) return MPQ_ERR_CODE_RANGE;
+    }
+    for (int32_t e = w->row_ptr[n]; e < w->row_ptr[n + 1]; ++e) {
+      if (w->col[e] >= K) return MPQ_ERR_CSR;
+      if (e > w->row_ptr[n] && w->col[e] <= w->col[e - 1]) return MPQ_ERR_CSR;
+      if (w->is4[w->col[e] / g1]) return MPQ_ERR_OUTLIER_IN_4BIT;  // Sec. 4.3: only in 2-bit groups
+    }
+  }
+  // ---- layout
+  uint8_t* blob = (uint8_t*)blob_host;
+  memset(blob, 0, (size_t)h.total_bytes);
+  memcpy(blob, &h, sizeof(h));
+  // stream order of the groups and the unit tables
+  std::vector<int32_t> groups2, groups4, stream_index(G);
+  for (int32_t g = 0; g < G; ++g) (w->is4[g] ? groups4 : groups2).push_back(g);
+  for (size_t i = 0; i < groups2.size(); ++i) stream_index[groups2[i]] = (int32_t)i;
+  for (size_t i = 0; i < groups4.size(); ++i) stream_index[groups4[i]] = (int32_t)(h.n2 + i);
+  uint32_t* unit2 = (uint32_t*)(blob + h.off_unit2);
+  uint32_t* unit4 = (uint32_t*)(blob + h.off_unit4);
+  const int32_t upg2 = (int32_t)(g1 / 64), upg4 = (int32_t)(g1 / 32);
+  for (int32_t u = 0; u < 4 * h.B2; ++u) {
+    if (u >= h.U2) { unit2[u] = MPQ_INVALID_UNIT; continue; }
+    const int32_t g = groups2[u / upg2];
+    const int64_t k0 = (int64_t)g * g1 + 64 * (u % upg2);
+    unit2[u] = (uint32_t)(k0 / 32) | ((uint32_t)(g / d->g2) << 16);
+  }
+  for (int32_t u = 0; u < 4 * h.B4; ++u) {
+    if (u >= h.U4) { unit4[u] = MPQ_INVALID_UNIT; continue; }
+    const int32_t g = groups4[u / upg4];
+    const int64_t k0 = (int64_t)g * g1 + 32 * (u % upg4);
+    unit4[u] = (uint32_t)(k0 / 32) | ((uint32_t)(g / d->g2) << 16);
+  }
+  uint32_t* codes2 = (uint32_t*)(blob + h.off_codes2);
+  uint32_t* codes4 = (uint32_t*)(blob + h.off_codes4);
+  uint16_t* meta1 = (uint16_t*)(blob + h.off_meta1);
+  uint32_t* meta2 = (uint32_t*)(blob + h.off_meta2);
+  for (int64_t n = 0; n < N; ++n) {
+    const int64_t t = n / MPQ_TILE_ROWS, i = n % MPQ_TILE_ROWS;
+    const uint8_t* row = w->codes + n * K;
+    for (int32_t u = 0; u < h.U2; ++u) {
+      const int64_t k0 = (int64_t)(unit2[u] & 0xFFFFu) * 32;
+      const int64_t b = u / 4, j = u % 4;
+      uint32_t* q = codes2 + (((t * h.B2 + b) * 64 + j * 16 + i) * 4);
+      for (int kl = 0; kl < 64; ++kl)
+        q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 2 * (kl / 8));
+    }
+    for (int32_t u = 0; u < h.U4; ++u) {
+      const int64_t k0 = (int64_t)(unit4[u] & 0xFFFFu) * 32;
+      const int64_t b = u / 4, j = u % 4;
+      uint32_t* q = codes4 + (((t * h.B4 + b) * 64 + j * 16 + i) * 4);
+      for (int kl = 0; kl < 32; ++kl)
+        q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 4 * (kl / 8));
+    }
+    for (int64_t g = 0; g < G; ++g)
+      meta1[(t * G + stream_index[g]) * MPQ_TILE_ROWS + i] =
+          (uint16_t)(w->s_int[n * G + g] | ((uint16_t)w->z1[n * G + g] << 8));
+    for (int64_t s = 0; s < h.S; ++s)
+      meta2[(t * h.S + s) * MPQ_TILE_ROWS + i] =
+          (uint32_t)w->s2[n * h.S + s] | ((uint32_t)w->z2[n * h.S + s] << 16);
+  }
+  int32_t* rp = (int32_t*)(blob + h.off_rowptr);
+  for (int64_t n = 0; n <= (int64_t)h.T * MPQ_TILE_ROWS; ++n) rp[n] = n <= N ? w->row_ptr[n] : (int32_t)nnz;
+  uint32_t* outl = (uint32_t*)(blob + h.off_outl);
+  for (int64_t e = 0; e < nnz; ++e) outl[e] = (uint32_t)w->col[e] | ((uint32_t)w->val[e] << 16);
+  return MPQ_OK;
+}
+
+mpq_status mpq_blob_info(const void* hdr_host, mpq_desc* out, int64_t* nnz, int32_t* n4,
+                         uint64_t* total_bytes) {
+  if (!hdr_host) return MPQ_ERR_NULL;
+  MpqHeader h;
+  memcpy(&h, hdr_host, sizeof(h));
+  if (h.magic != MPQ_MAGIC || h.version != MPQ_VERSION) return MPQ_ERR_BLOB;
+  if (out) { out->N = h.N; out->K = h.K; out->g1 = h.g1; out->g2 = h.g2; out->g2_axis = h.g2_axis; }
+  if (nnz) *nnz = h.nnz;
+  if (n4) *n4 = h.n4;
+  if (total_bytes) *total_bytes = h.total_bytes;
+  return MPQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,159 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Dequantized weights must be bit-exact; products must stay within 2e-3 of the
+oracle's binary64 accumulation (relative, with the small-output floor of gpu_util.rel_err)."""
+import numpy as np
+import pytest
+
+import mpq_synth as synth
+import oracle
+import paper_2311_16442_amd as mpq
+from gpu_util import Guarded, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    return t
+
+
+CASES = [
+    # name, N, K, g1, g2, f4, p_o, z1_full
+    ("config0", 1024, 1024, 64, 16, 0.10, 0.005, False),
+    ("ragged_rows", 1000, 704, 64, 4, 0.30, 0.02, True),     # N % 16 = 8, G = 11, S = 3 (short tail group)
+    ("g128", 208, 2048, 128, 16, 0.15, 0.005, True),
+    ("only_2bit", 64, 512, 64, 16, 0.0, 0.01, False),
+    ("only_4bit", 64, 512, 64, 16, 1.0, 0.0, True),
+    ("one_group", 5, 64, 64, 1, 0.0, 0.2, False),
+    ("down_like", 272, 11008, 64, 16, 0.10, 0.005, False),   # G = 172 = 10*16 + 12
+    ("wide", 48, 28672, 64, 16, 0.10, 0.005, False),         # largest K of the configurations
+    ("dense_outliers", 96, 1024, 64, 16, 0.10, 0.30, False), # rows with hundreds of outliers
+]
+
+
+def make(case):
+    name, N, K, g1, g2, f4, p_o, z1_full = case
+    lg = synth.make_matrix(synth.MatrixSpec(name, N, K, g1, g2, f4, p_o, 4242 + N + K), z1_full_range=z1_full)
+    return lg, oracle.Matrix.from_logical(lg), mpq.pack_logical(lg)
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_dequant_bit_exact(torch, case):
+    lg, om, pk = make(case)
+    print("case", case, flush=True)
+    blob = to_dev(torch, pk.blob)
+    for add in (False, True):
+        out = Guarded(torch, pk.N * pk.K)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+        got = out.check_and_get().reshape(pk.N, pk.K)
+        ref = om.dequant(add)
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, (add, bad[:5], got[tuple(bad[0])], ref[tuple(bad[0])])
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_gemv_within_tolerance(torch, case):
+    lg, om, pk = make(case)
+    print("case", case, flush=True)
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(99, 1, pk.K)
+    x = to_dev(torch, X[0].view(np.int16))
+    y = Guarded(torch, pk.N)
+    mpq.gemv(pk.header, blob, x, y.view)
+    got = y.check_and_get()
+    ref = om.gemm(X, threads=8)[0]
+    e_floor, e_max = rel_err(got, ref)
+    assert e_floor <= TOL, (e_floor, e_max)
+    # a second launch gives the same bits (fixed reduction order, no races)
+    y2 = Guarded(torch, pk.N)
+    mpq.gemv(pk.header, blob, x, y2.view)
+    assert np.array_equal(y2.check_and_get(), got)
+
+
+def test_gemv_exact_for_integer_problem(torch):
+    # identity scales and small integer activations: y = codes @ x in integers, exactly representable
+    lg = synth.make_matrix(synth.MatrixSpec("int", 64, 256, 64, 2, 0.25, 0.0, 31))
+    lg.s_int[:] = 1; lg.z1[:] = 0; lg.s2[:] = 0x3C00; lg.z2[:] = 0
+    pk = mpq.pack_logical(lg)
+    rng = np.random.default_rng(32)
+    xi = rng.integers(-1, 2, size=256)
+    ref = lg.codes.astype(np.int64) @ xi
+    assert np.max(np.abs(ref)) < 2048
+    y = Guarded(torch, 64)
+    mpq.gemv(pk.header, to_dev(torch, pk.blob), to_dev(torch, xi.astype(np.float16).view(np.int16)), y.view)
+    assert np.array_equal(y.check_and_get().view(np.float16).astype(np.int64), ref)
+
+
+def test_special_scale_values_bit_exact(torch):
+    # any uint8 s_int / z1 and any finite fp16 pair must decode: negative scales, results that are
+    # subnormal, zero with either sign, or overflow to infinity
+    N, K, g1, g2 = 64, 1024, 64, 1
+    lg = synth.make_matrix(synth.MatrixSpec("edge", N, K, g1, g2, 0.25, 0.01, 33), z1_full_range=True)
+    rng = np.random.default_rng(34)
+    specials = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x03FF, 0x0400, 0x7BFF, 0xFBFF, 0x3C00, 0xBC00,
+                         0x0200, 0x1400, 0x5BF8, 0x57F8, 0x4248, 0x2E66], dtype=np.uint16)
+    lg.s2[:] = rng.choice(specials, size=lg.s2.shape)
+    lg.z2[:] = rng.choice(specials, size=lg.z2.shape)
+    lg.s_int[:, :4] = np.array([0, 1, 254, 255], dtype=np.uint8)
+    om, pk = oracle.Matrix.from_logical(lg), mpq.pack_logical(lg)
+    blob = to_dev(torch, pk.blob)
+    for add in (False, True):
+        out = Guarded(torch, N * K)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+        got, ref = out.check_and_get().reshape(N, K), om.dequant(add)
+        nan = (ref & 0x7FFF) > 0x7C00
+        assert np.array_equal((got & 0x7FFF) > 0x7C00, nan)       # NaN (inf - inf, 0 * inf) where the oracle has NaN
+        assert np.array_equal(got[~nan], ref[~nan])
+        kinds = ref[~nan] & 0x7FFF
+        assert (kinds == 0x7C00).any() and ((kinds > 0) & (kinds < 0x0400)).any() and (kinds == 0).any()
+
+
+def test_padding_bytes_are_never_used(torch):
+    import unpack as up
+    lg = synth.make_matrix(synth.MatrixSpec("pad", 40, 704, 64, 4, 0.30, 0.02, 35))
+    om, pk = oracle.Matrix.from_logical(lg), mpq.pack_logical(lg)
+    h = up.read_header(pk.blob)
+    poisoned = pk.blob.copy()
+    # padding units of both streams (unit index >= U2 / U4) in every tile
+    for off, B, U in ((h["off_codes2"], h["B2"], h["U2"]), (h["off_codes4"], h["B4"], h["U4"])):
+        v = poisoned[off: off + h["T"] * B * 1024].reshape(h["T"], B, 4, 16, 16)
+        for u in range(U, 4 * B):
+            v[:, u // 4, u % 4] = 0xFF
+    blob = to_dev(torch, poisoned)
+    X = synth.make_x(36, 1, 704)
+    y = Guarded(torch, 40)
+    mpq.gemv(pk.header, blob, to_dev(torch, X[0].view(np.int16)), y.view)
+    assert rel_err(y.check_and_get(), om.gemm(X)[0])[0] <= TOL
+    out = Guarded(torch, 40 * 704)
+    mpq.dequant(pk.header, blob, out.view, add_outliers=True)
+    assert np.array_equal(out.check_and_get().reshape(40, 704), om.dequant(True))
+
+
+@pytest.mark.parametrize("M", [1, 2, 4, 8, 16, 32])
+def test_gemm_within_tolerance(torch, M):
+    lg, om, pk = make(CASES[1])
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(123 + M, M, pk.K)
+    Y = Guarded(torch, M * pk.N)
+    mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+    got = Y.check_and_get().reshape(M, pk.N)
+    ref = om.gemm(X, threads=8)
+    e_floor, e_max = rel_err(got, ref)
+    assert e_floor <= TOL, (M, e_floor, e_max)
+
+
+def test_outliers_reduce_to_csr_product(torch):
+    import scipy.sparse as sp
+    lg = synth.make_matrix(synth.MatrixSpec("csr", 160, 1024, 64, 16, 0.10, 0.02, 37))
+    lg.codes[:] = np.repeat(lg.z1, 64, axis=1)      # dense part decodes to zero
+    pk = mpq.pack_logical(lg)
+    X = synth.make_x(38, 1, 1024)
+    y = Guarded(torch, 160)
+    mpq.gemv(pk.header, to_dev(torch, pk.blob), to_dev(torch, X[0].view(np.int16)), y.view)
+    A = sp.csr_matrix((lg.val.view(np.float16).astype(np.float64), lg.col.astype(np.int64),
+                       lg.row_ptr.astype(np.int64)), shape=(160, 1024))
+    ref = A @ X[0].view(np.float16).astype(np.float64)
+    assert rel_err(y.check_and_get(), ref)[0] <= TOL

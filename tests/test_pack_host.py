@@ -1,0 +1,160 @@
+"""Host-side logic of the library (no GPU): the shared object loads and exports every declared
+symbol, the packer round-trips through an independent reader, validation rejects malformed input,
+and the average-bit function reproduces the paper's printed values."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import mpq_synth as synth
+import paper_2311_16442_amd as mpq
+import unpack as up
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "mpq.h")).read()
+    declared = sorted(set(re.findall(r"\b(mpq_[a-z_0-9]+)\s*\(", text)))
+    assert set(declared) == set(mpq.EXPORTS)
+    L = mpq.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert mpq.status_str(0) == "ok" and mpq.status_str(5).startswith("outlier")
+
+
+CASES = [
+    # N, K, g1, g2, f4, p_o, z1_full
+    (48, 1024, 64, 16, 0.10, 0.005, False),
+    (37, 704, 64, 4, 0.30, 0.02, True),      # ragged: N % 16 != 0, G = 11, S = 3 with a short tail
+    (20, 1024, 128, 2, 0.25, 0.01, True),    # g1 = 128
+    (16, 512, 64, 16, 0.0, 0.01, False),     # no 4-bit group
+    (16, 512, 64, 16, 1.0, 0.0, False),      # only 4-bit groups
+    (5, 64, 64, 1, 0.0, 0.2, False),         # a single group
+]
+
+
+@pytest.mark.parametrize("N,K,g1,g2,f4,p_o,z1_full", CASES)
+def test_pack_round_trips_through_independent_reader(N, K, g1, g2, f4, p_o, z1_full):
+    lg = synth.make_matrix(synth.MatrixSpec("t", N, K, g1, g2, f4, p_o, 77 + N + K), z1_full_range=z1_full)
+    pk = mpq.pack_logical(lg)
+    assert pk.blob.size == mpq.packed_size(N, K, g1, g2, lg.is4, lg.nnz)
+    info = mpq.blob_info(pk.header)
+    assert (info["N"], info["K"], info["g1"], info["g2"], info["nnz"], info["n4"]) == \
+        (N, K, g1, g2, lg.nnz, int(lg.is4.sum()))
+    assert info["total_bytes"] == pk.blob.size
+    u = up.unpack(pk.blob)
+    assert np.array_equal(u["is4"], lg.is4)
+    for name in ("codes", "s_int", "z1", "s2", "z2", "row_ptr", "col", "val"):
+        assert np.array_equal(u[name], getattr(lg, name)), name
+    assert np.all(u["row_ptr_pad"] == lg.nnz)
+    assert not u["pad_rows_codes"].any() and not u["pad_s"].any()
+    # every section offset is 256-byte aligned, every unit 16-byte aligned
+    for k, v in u["h"].items():
+        if k.startswith("off_"):
+            assert v % 256 == 0
+    # padding overhead of the layout stays small next to the algorithmic bytes
+    algo = synth.stored_bytes(lg.spec, int(lg.is4.sum()), lg.nnz)["total"]
+    if N % 16 == 0 and N * K >= 16 * 1024:
+        assert pk.blob.size <= algo * 1.25 + 4096
+
+
+def test_pack_is_deterministic_and_position_independent():
+    lg = synth.make_matrix(synth.MatrixSpec("t", 32, 512, 64, 16, 0.25, 0.01, 5))
+    a = mpq.pack_logical(lg).blob
+    b = mpq.pack_logical(lg).blob
+    assert np.array_equal(a, b)
+
+
+def _ptrs(lg):
+    return dict(N=lg.spec.N, K=lg.spec.K, g1=lg.spec.g1, g2=lg.spec.g2, is4=lg.is4, codes=lg.codes,
+                s_int=lg.s_int, z1=lg.z1, s2=lg.s2, z2=lg.z2, row_ptr=lg.row_ptr, col=lg.col, val=lg.val)
+
+
+def _status(**kw):
+    try:
+        mpq.pack(**kw)
+    except mpq.MpqError as e:
+        return e.status
+    return mpq.MPQ_OK
+
+
+def test_pack_rejects_malformed_input():
+    lg = synth.make_matrix(synth.MatrixSpec("t", 32, 512, 64, 4, 0.25, 0.05, 6))
+    base = _ptrs(lg)
+    assert _status(**base) == mpq.MPQ_OK
+    g2bit = int(np.nonzero(lg.is4 == 0)[0][0])
+    g4bit = int(np.nonzero(lg.is4)[0][0])
+    bad = dict(base); bad["codes"] = lg.codes.copy(); bad["codes"][3, g2bit * 64 + 5] = 4
+    assert _status(**bad) == mpq.MPQ_ERR_CODE_RANGE
+    bad = dict(base); bad["codes"] = lg.codes.copy(); bad["codes"][3, g4bit * 64 + 5] = 16
+    assert _status(**bad) == mpq.MPQ_ERR_CODE_RANGE
+    r = int(np.nonzero(np.diff(lg.row_ptr) > 1)[0][0])
+    e = int(lg.row_ptr[r])
+    bad = dict(base); bad["col"] = lg.col.copy(); bad["col"][e + 1] = bad["col"][e]
+    assert _status(**bad) == mpq.MPQ_ERR_CSR                      # not strictly increasing
+    bad = dict(base); bad["col"] = lg.col.copy(); bad["col"][lg.row_ptr[r + 1] - 1] = g4bit * 64 + 63 if g4bit * 64 + 63 > lg.col[lg.row_ptr[r + 1] - 2] else 0
+    assert _status(**bad) in (mpq.MPQ_ERR_OUTLIER_IN_4BIT, mpq.MPQ_ERR_CSR)
+    bad = dict(base); bad["row_ptr"] = lg.row_ptr.copy(); bad["row_ptr"][4] = bad["row_ptr"][3] - 1
+    assert _status(**bad) == mpq.MPQ_ERR_CSR
+    bad = dict(base); bad["row_ptr"] = lg.row_ptr.copy(); bad["row_ptr"][0] = 1
+    assert _status(**bad) == mpq.MPQ_ERR_CSR
+    bad = dict(base); bad["col"] = lg.col.copy(); bad["col"][e] = 600
+    assert _status(**bad) == mpq.MPQ_ERR_CSR                      # col >= K
+    assert _status(**dict(base, K=500)) == mpq.MPQ_ERR_SHAPE      # K % g1 != 0
+    assert _status(**dict(base, g1=32)) == mpq.MPQ_ERR_UNSUPPORTED
+    assert _status(**dict(base, g2_axis=1)) == mpq.MPQ_ERR_UNSUPPORTED
+    assert _status(**dict(base, g2=0)) == mpq.MPQ_ERR_SHAPE
+
+
+def test_outlier_in_4bit_group_is_its_own_error():
+    lg = synth.make_matrix(synth.MatrixSpec("t", 16, 256, 64, 4, 0.25, 0.0, 8))
+    g4bit = int(np.nonzero(lg.is4)[0][0])
+    rp = np.zeros(17, np.int32); rp[1:] = 1
+    st = _status(**dict(_ptrs(lg), row_ptr=rp, col=np.array([g4bit * 64 + 1], np.uint16),
+                        val=np.array([0x3C00], np.uint16)))
+    assert st == mpq.MPQ_ERR_OUTLIER_IN_4BIT
+
+
+def test_small_buffer_and_bad_header_are_reported():
+    lg = synth.make_matrix(synth.MatrixSpec("t", 16, 256, 64, 4, 0.25, 0.01, 9))
+    pk = mpq.pack_logical(lg)
+    L = mpq.lib()
+    d = mpq.Desc(16, 256, 64, 4, 0)
+    arrs = [np.ascontiguousarray(a) for a in (lg.is4, lg.codes, lg.s_int, lg.z1, lg.s2, lg.z2, lg.row_ptr, lg.col, lg.val)]
+    ptrs = mpq.LogicalPtrs(*[a.ctypes.data for a in arrs])
+    small = np.zeros(pk.blob.size - 1, np.uint8)
+    assert L.mpq_pack_host(C.byref(d), C.byref(ptrs), small.ctypes.data_as(C.c_void_p), small.size) == mpq.MPQ_ERR_SIZE
+    assert L.mpq_pack_host(None, C.byref(ptrs), small.ctypes.data_as(C.c_void_p), small.size) == mpq.MPQ_ERR_NULL
+    hdr = pk.header.copy(); hdr[0] ^= 0xFF
+    with pytest.raises(mpq.MpqError) as ei:
+        mpq.blob_info(hdr)
+    assert ei.value.status == mpq.MPQ_ERR_BLOB
+    # device entry points validate the header on the host before touching the GPU
+    hdr = pk.header.copy(); hdr[8] ^= 1          # N changed: recorded offsets no longer match
+    fake = C.c_void_p(4096)
+    assert L.mpq_gemv(hdr.ctypes.data_as(C.c_void_p), fake, fake, fake, None) == mpq.MPQ_ERR_BLOB
+    assert L.mpq_gemv(pk.header.ctypes.data_as(C.c_void_p), None, fake, fake, None) == mpq.MPQ_ERR_NULL
+    assert L.mpq_gemv(pk.header.ctypes.data_as(C.c_void_p), C.c_void_p(4100), fake, fake, None) == mpq.MPQ_ERR_ALIGN
+    assert L.mpq_gemm(pk.header.ctypes.data_as(C.c_void_p), fake, fake, fake, 0, None) == mpq.MPQ_ERR_SHAPE
+    assert L.mpq_gemm(pk.header.ctypes.data_as(C.c_void_p), fake, fake, fake, 33, None) == mpq.MPQ_ERR_SHAPE
+    assert L.mpq_dequant(pk.header.ctypes.data_as(C.c_void_p), fake, None, 0, None) == mpq.MPQ_ERR_NULL
+
+
+def test_avg_bits_reproduces_the_papers_values():
+    # Sec. 3.3 formula at the paper's operating point (g1 = g2 = 16, Ns = 4, 25 % / 10 % 4-bit)
+    assert abs(mpq.avg_bits(1024, 1024, 16, 16, n4=16, nnz=0, mode=1, ns_bits=4) - 2.83984375) < 1e-12
+    v10 = mpq.avg_bits(1280, 1280, 16, 16, n4=8, nnz=0, mode=1, ns_bits=4)
+    assert abs(v10 - 2.6078125) < 1e-12
+    # Sec. 4.2: 1.5 % outliers cost 0.45 bit
+    with_o = mpq.avg_bits(1000, 1600, 16, 16, n4=25, nnz=24000, mode=1, ns_bits=4)
+    assert abs(with_o - mpq.avg_bits(1000, 1600, 16, 16, n4=25, nnz=0, mode=1, ns_bits=4) - 0.45) < 1e-12
+    # stored bits: the benchmark's headline layer is about 2.62 bits per weight
+    spec = synth.config_specs(1)[1]
+    nnz = int(round(spec.p_o * spec.N * (spec.G - spec.n4) * spec.g1))
+    by = synth.stored_bytes(spec, spec.n4, nnz)["total"]
+    got = mpq.avg_bits(spec.N, spec.K, spec.g1, spec.g2, spec.n4, nnz, mode=0)
+    assert abs(got - 8.0 * by / (spec.N * spec.K)) < 1e-9 and abs(got - 2.62) < 0.01
+    assert mpq.avg_bits(0, 1024, 64, 16, 0, 0) < 0

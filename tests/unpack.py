@@ -1,0 +1,79 @@
+"""Independent reader of the packed blob, written from the layout description alone
+(numpy indexing; shares no code with the library).  Used to check the packer."""
+import struct
+
+import numpy as np
+
+TILE = 16
+
+
+def read_header(blob: np.ndarray) -> dict:
+    raw = bytes(blob[:256])
+    names = ["magic", "version", "N", "K", "g1", "g2", "g2_axis", "G", "S", "n2", "n4", "U2", "U4", "B2", "B4", "T"]
+    vals = struct.unpack_from("<II14i", raw, 0)
+    h = dict(zip(names, vals))
+    h["nnz"] = struct.unpack_from("<q", raw, 64)[0]
+    offs = struct.unpack_from("<9Q", raw, 72)
+    for n, v in zip(["unit2", "unit4", "codes2", "codes4", "meta1", "meta2", "rowptr", "outl", "total"], offs):
+        h["off_" + n] = v
+    return h
+
+
+def unpack(blob: np.ndarray) -> dict:
+    h = read_header(blob)
+    N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
+    unit2 = blob[h["off_unit2"]: h["off_unit2"] + 16 * h["B2"]].view(np.uint32)
+    unit4 = blob[h["off_unit4"]: h["off_unit4"] + 16 * h["B4"]].view(np.uint32)
+    c2 = blob[h["off_codes2"]: h["off_codes2"] + T * h["B2"] * 1024].view(np.uint32).reshape(T, h["B2"], 4, 16, 4)
+    c4 = blob[h["off_codes4"]: h["off_codes4"] + T * h["B4"] * 1024].view(np.uint32).reshape(T, h["B4"], 4, 16, 4)
+    codes = np.zeros((T * TILE, K), dtype=np.uint8)
+    is4 = np.full(G, 255, dtype=np.uint8)
+    stream_groups = []                       # K-group of each stream group, 2-bit stream first
+    group_of_super = {}
+    for u in range(4 * h["B2"]):
+        e = int(unit2[u])
+        if e == 0xFFFFFFFF:
+            assert u >= h["U2"]
+            assert not c2[:, u // 4, u % 4].any()        # padding units are zero
+            continue
+        k0 = (e & 0xFFFF) * 32
+        g = k0 // g1
+        is4[g] = 0
+        assert (e >> 16) == g // g2
+        if k0 % g1 == 0:
+            stream_groups.append(g)
+        words = c2[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
+        for kl in range(64):
+            d, sh = (kl % 8) // 2, 16 * (kl % 2) + 2 * (kl // 8)
+            codes[:, k0 + kl] = ((words[:, :, d] >> sh) & 3).reshape(-1)
+    for u in range(4 * h["B4"]):
+        e = int(unit4[u])
+        if e == 0xFFFFFFFF:
+            assert u >= h["U4"]
+            assert not c4[:, u // 4, u % 4].any()
+            continue
+        k0 = (e & 0xFFFF) * 32
+        g = k0 // g1
+        is4[g] = 1
+        assert (e >> 16) == g // g2
+        if k0 % g1 == 0:
+            stream_groups.append(g)
+        words = c4[:, u // 4, u % 4]
+        for kl in range(32):
+            d, sh = (kl % 8) // 2, 16 * (kl % 2) + 4 * (kl // 8)
+            codes[:, k0 + kl] = ((words[:, :, d] >> sh) & 15).reshape(-1)
+    assert len(stream_groups) == G and sorted(stream_groups) == list(range(G))
+    m1 = blob[h["off_meta1"]: h["off_meta1"] + T * G * TILE * 2].view(np.uint16).reshape(T, G, TILE)
+    s_int = np.zeros((T * TILE, G), dtype=np.uint8)
+    z1 = np.zeros((T * TILE, G), dtype=np.uint8)
+    for sg, g in enumerate(stream_groups):
+        s_int[:, g] = (m1[:, sg, :] & 0xFF).reshape(-1)
+        z1[:, g] = (m1[:, sg, :] >> 8).reshape(-1)
+    m2 = blob[h["off_meta2"]: h["off_meta2"] + T * S * TILE * 4].view(np.uint32).reshape(T, S, TILE)
+    s2 = (m2 & 0xFFFF).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
+    z2 = (m2 >> 16).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
+    rp = blob[h["off_rowptr"]: h["off_rowptr"] + 4 * (T * TILE + 1)].view(np.int32)
+    outl = blob[h["off_outl"]: h["off_outl"] + 4 * h["nnz"]].view(np.uint32)
+    return dict(h=h, is4=is4, codes=codes[:N], s_int=s_int[:N], z1=z1[:N], s2=s2[:N], z2=z2[:N],
+                row_ptr=rp[:N + 1].copy(), row_ptr_pad=rp[N:].copy(), col=(outl & 0xFFFF).astype(np.uint16),
+                val=(outl >> 16).astype(np.uint16), pad_rows_codes=codes[N:], pad_s=s_int[N:])
