@@ -11,9 +11,12 @@
 // matrix-vector product reads equally well.
 //
 //   header    256 B                                      (MpqHeader)
-//   unit2     uint32 [4*B2]   per 2-bit unit in stream order: (k0/32) | (super_group << 16);
-//                             0xFFFFFFFF marks a padding unit
-//   unit4     uint32 [4*B4]   the same for 4-bit units
+//   unit2     2 x uint32 [4*B2]  per 2-bit unit in stream order, ready for the kernels:
+//                             word 0 = byte offset of the unit's first activation in an fp16 row
+//                                      (2*k0), bit 31 set for a padding unit (then all else is 0)
+//                             word 1 = (stream_group * 32) | (super_group * 64) << 16, the byte
+//                                      offsets of the group's rows inside a tile of meta1 / meta2
+//   unit4     2 x uint32 [4*B4]  the same for 4-bit units
 //   codes2    T x B2 x 64 x 16 B    2-bit stream:  [tile][block][lane] 16-byte units
 //   codes4    T x B4 x 64 x 16 B    4-bit stream
 //   meta1     T x G x 16 x 2 B      (s_int | z1 << 8) per (tile, stream group, row); stream group
@@ -35,12 +38,12 @@
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 2u
+#define MPQ_VERSION 3u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024
 #define MPQ_SECTION_ALIGN 256
-#define MPQ_INVALID_UNIT 0xFFFFFFFFu
+#define MPQ_PAD_UNIT 0x80000000u
 
 typedef struct {
   uint32_t magic, version;

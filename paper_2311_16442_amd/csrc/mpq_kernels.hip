@@ -1,22 +1,23 @@
 // mpq_kernels.hip - gfx950 kernels and device entry points of the mixed-precision weight library.
 //
 // Kernels (all read the packed blob described in mpq_format.h):
-//   mpq_gemv_kernel     Algorithm 1 (GEMV with asynchronous dequantization) re-designed for CDNA4,
-//                       with the outlier product of Sec. 4.3 fused in as a per-row correction.
-//   mpq_dequant_kernel  eq. 5 applied twice (scale, then weight), written out as row-major fp16.
+//   mpq_mm_kernel        Algorithm 1 (GEMV with asynchronous dequantization) re-designed for CDNA4,
+//                        for a batch of 1..32 activation rows, with the outlier product of
+//                        Sec. 4.3 fused in as a per-row correction.
+//   mpq_dequant_kernel   eq. 5 applied twice (scale, then weight), written out as row-major fp16.
 //   mpq_outlier_add_kernel  adds the CSR values to a dequantized matrix (dense + sparse, Sec. 2.3).
 //
 // Mapping shared by the kernels.  A workgroup owns one tile of 16 rows for all of K.  A wavefront
 // load of 1 KiB is one block: lane = j*16 + i holds the 16-byte unit j (of 4) of row i (of 16).
-// The waves of the workgroup take the tile's blocks round-robin, first the 2-bit stream, then the
-// 4-bit stream.  A lane therefore always decodes codes of ONE row and ONE first-order group, so
-// the group's scale and zero point are per-lane scalars.
+// The four waves of the workgroup take the tile's blocks round-robin, first the 2-bit stream,
+// then the 4-bit stream.  A lane therefore always decodes codes of ONE row and ONE first-order
+// group, so the group's scale and zero point are per-lane scalars.
 //
 // Per-weight arithmetic (bit-exact to the definition in mpq.h):
 //   a mask isolates two codes (low / high half-word of a dword); OR-ing 0x6400 into each half
 //   makes the fp16 numbers 1024 + c*4^p; one packed fma (x 4^-p, - (1024*4^-p + z1)) gives the
 //   exact integers c - z1; one packed fp16 multiply by s1 is the rounding the definition asks
-//   for.  The GEMV then feeds the pair to v_dot2_f32_f16 (fp32 accumulation).
+//   for.  The product kernel hands the resulting pairs to the matrix core.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,12 +26,13 @@
 
 typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-
-#define XS_STRIDE 144 /* LDS bytes per 64 activations: 128 B + 16 B skew against bank conflicts */
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 struct DevBlob {
-  const uint32_t* unit2;
-  const uint32_t* unit4;
+  const uint2* unit2;
+  const uint2* unit4;
   const uint4* codes2;
   const uint4* codes4;
   const uint16_t* meta1;
@@ -38,6 +40,7 @@ struct DevBlob {
   const int32_t* rowptr;
   const uint32_t* outl;
   int32_t N, K, G, S, n2, U2, U4, B2, B4, T;
+  int64_t nnz;
 };
 
 __device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
@@ -46,9 +49,57 @@ __device__ __forceinline__ half_t bits_to_half(uint16_t u) { return __builtin_bi
 __device__ __forceinline__ uint16_t half_to_bits(half_t h) { return __builtin_bit_cast(uint16_t, h); }
 
 // Waits for this wave's LDS traffic only, then meets the other waves.  Global loads that are still
-// in flight (prefetched code blocks) stay in flight, which __syncthreads() would not allow.
+// in flight (code blocks on their way to LDS) stay in flight, which __syncthreads() would not allow.
 __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// s_waitcnt vmcnt(n) for a wave-uniform n known only at run time (gfx9 encoding: vmcnt in bits
+// 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "do not wait").  Larger n wait for vmcnt(9),
+// which is stricter and therefore safe.
+#define MPQ_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
+__device__ __forceinline__ void wait_vm(int n) {
+  switch (n) {
+    case 0: MPQ_VMCNT(0); break;
+    case 1: MPQ_VMCNT(1); break;
+    case 2: MPQ_VMCNT(2); break;
+    case 3: MPQ_VMCNT(3); break;
+    case 4: MPQ_VMCNT(4); break;
+    case 5: MPQ_VMCNT(5); break;
+    case 6: MPQ_VMCNT(6); break;
+    case 7: MPQ_VMCNT(7); break;
+    case 8: MPQ_VMCNT(8); break;
+    default: MPQ_VMCNT(9); break;
+  }
+}
+
+// The product kernel issues its global loads with inline asm and waits for them with explicit
+// s_waitcnt vmcnt(n): the compiler's own wait insertion cannot count requests issued in loops and
+// would otherwise wait for ALL outstanding loads (vmcnt(0)) whenever LDS written by a direct load
+// is read, which serialises the whole pipeline.  Values loaded this way must not be used before
+// the matching wait_vm().
+
+// 16 bytes per lane straight from global memory into LDS at lds + 16*lane (no register staging).
+__device__ __forceinline__ void dma16(const void* g, unsigned char* lds_wave_uniform) {
+  const uint32_t l = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_wave_uniform);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(g) : "memory");
+}
+
+// One dword per lane into a register, asynchronously.
+__device__ __forceinline__ uint32_t load_b32_async(const void* g) {
+  uint32_t r;
+  asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(g) : "memory");
+  return r;
+}
+
+// Copies `bytes` (a multiple of 16) to LDS with the waves of a 256-thread workgroup taking 1 KiB
+// pieces in turn.
+__device__ __forceinline__ void dma_region(const void* g, unsigned char* l, int bytes, int wv, int lane) {
+  for (int ch = wv; ch * 1024 < bytes; ch += 4) {
+    const int off = ch * 1024 + lane * 16;
+    if (off < bytes) dma16((const unsigned char*)g + off, l + ch * 1024);
+  }
 }
 
 // Second-order dequantization of a first-order scale: fp16((fp32(s_int) - fp32(z2)) * fp32(s2)).
@@ -66,243 +117,285 @@ __device__ __forceinline__ half_t scale_dequant(uint32_t s_int, uint32_t m2) {
   return (half_t)u;
 }
 
-// First-order dequantization (eq. 5) of one 2-bit unit: 64 codes -> 32 fp16 pairs, pair r holding
-// columns (2r, 2r+1) of the unit.
-__device__ __forceinline__ void decode2(const uint4 q, const half_t s1, const half_t z1h, half2_t (&w)[32]) {
-#pragma clang fp contract(off)
-  const uint32_t magic = 0x64006400u;  // fp16 1024.0 in both halves
-  const half2_t s1p = {s1, s1};
-  half2_t nb[5], sc[5];
-  const float inv[5] = {1.0f, 0.25f, 0.0625f, 0.015625f, 0.00390625f};
-#pragma unroll
-  for (int p = 0; p < 5; ++p) {
-    const half_t b = (half_t)(-1024.0f * inv[p]) - z1h;  // exact: integer below 2048
-    nb[p] = half2_t{b, b};
-    sc[p] = half2_t{(half_t)inv[p], (half_t)inv[p]};
-  }
-  const uint32_t qd[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    const uint32_t lo = qd[d];
-    const uint32_t hi = qd[d] >> 10;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      const int pp = p < 5 ? p : p - 5;
-      const uint32_t src = p < 5 ? lo : hi;
-      const half2_t h = as_h2((src & (0x00030003u << (2 * pp))) | magic);
-      const half2_t dz = __builtin_elementwise_fma(h, sc[pp], nb[pp]);  // exact c - z1
-      w[4 * p + d] = dz * s1p;
-    }
-  }
+// Constants of the decode kept in scalar registers so that v_and_or_b32 / v_pk_fma_f16 can take
+// them as operands (VOP3 encodings on gfx9 have no literal operands).
+__device__ __forceinline__ uint32_t sgpr_const(uint32_t v) {
+  uint32_t r;
+  asm volatile("s_mov_b32 %0, %1" : "=s"(r) : "i"(v));
+  return r;
 }
 
-// The same for one 4-bit unit: 32 codes -> 16 pairs.
-__device__ __forceinline__ void decode4(const uint4 q, const half_t s1, const half_t z1h, half2_t (&w)[16]) {
-#pragma clang fp contract(off)
-  const uint32_t magic = 0x64006400u;
-  const half2_t s1p = {s1, s1};
-  const half_t b0 = (half_t)(-1024.0f) - z1h, b1 = (half_t)(-64.0f) - z1h;
-  const half2_t nb[2] = {half2_t{b0, b0}, half2_t{b1, b1}};
-  const half2_t sc[2] = {half2_t{(half_t)1.0f, (half_t)1.0f}, half2_t{(half_t)0.0625f, (half_t)0.0625f}};
-  const uint32_t qd[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    const uint32_t lo = qd[d];
-    const uint32_t hi = qd[d] >> 8;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int pp = p & 1;
-      const uint32_t src = p < 2 ? lo : hi;
-      const half2_t h = as_h2((src & (0x000F000Fu << (4 * pp))) | magic);
-      const half2_t dz = __builtin_elementwise_fma(h, sc[pp], nb[pp]);
-      w[4 * p + d] = dz * s1p;
-    }
-  }
-}
-
-__device__ __forceinline__ float dot2(half2_t a, uint32_t xb, float acc) {
-  return __builtin_amdgcn_fdot2(a, as_h2(xb), acc, false);
-}
-
-// Description of what one lane has to do for block c of the current tile.
-struct LaneBlock {
-  uint4 q;
-  uint32_t m1;
+struct DecodeConsts {
+  uint32_t mask2[5], mask4[2], sc2[5], sc4[2];
+  uint32_t magic;
 };
 
-template <int G1>
-__device__ __forceinline__ void issue_block(const DevBlob& b, int tile, int c, int lane, LaneBlock& out) {
-  const int i = lane & 15, j = lane >> 4;
-  const uint16_t* m1t = b.meta1 + (size_t)tile * b.G * 16 + i;
-  if (c < b.B2) {
-    out.q = b.codes2[((size_t)tile * b.B2 + c) * 64 + lane];
-    const int u = 4 * c + j;
-    const int sg = G1 == 64 ? u : (u >> 1);
-    out.m1 = u < b.U2 ? (uint32_t)m1t[sg * 16] : 0u;
-  } else {
-    const int c4 = c - b.B2;
-    out.q = b.codes4[((size_t)tile * b.B4 + c4) * 64 + lane];
-    const int u = 4 * c4 + j;
-    const int sg = b.n2 + (G1 == 64 ? (u >> 1) : (u >> 2));
-    out.m1 = u < b.U4 ? (uint32_t)m1t[sg * 16] : 0u;
-  }
+__device__ __forceinline__ DecodeConsts make_consts() {
+  DecodeConsts k;
+  k.mask2[0] = sgpr_const(0x00030003u); k.mask2[1] = sgpr_const(0x000C000Cu); k.mask2[2] = sgpr_const(0x00300030u);
+  k.mask2[3] = sgpr_const(0x00C000C0u); k.mask2[4] = sgpr_const(0x03000300u);
+  k.mask4[0] = sgpr_const(0x000F000Fu); k.mask4[1] = sgpr_const(0x00F000F0u);
+  k.sc2[0] = sgpr_const(0x3C003C00u);  // 1
+  k.sc2[1] = sgpr_const(0x34003400u);  // 1/4
+  k.sc2[2] = sgpr_const(0x2C002C00u);  // 1/16
+  k.sc2[3] = sgpr_const(0x24002400u);  // 1/64
+  k.sc2[4] = sgpr_const(0x1C001C00u);  // 1/256
+  k.sc4[0] = k.sc2[0];
+  k.sc4[1] = k.sc2[2];
+  asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(k.magic));  // fp16 1024.0 in both halves
+  return k;
 }
 
-// ------------------------------------------------------------------------------------ GEMV
+// First-order dequantization (eq. 5) of step P of a unit: the four dwords give the four fp16 pairs
+// of columns 8P .. 8P+7.  TWO_BIT selects 2-bit (P = 0..7) or 4-bit (P = 0..3) fields.
+// zb = fp16(1024 + z1); lo / hi = the unit's dwords and the same shifted right by 10 (2-bit) or 8
+// (4-bit) so that every field sits in mantissa bits.
+template <bool TWO_BIT, int P>
+__device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint32_t (&hi)[4], const half2_t s1p,
+                                             const half_t zb, const DecodeConsts& kc) {
+#pragma clang fp contract(off)
+  constexpr int pp = TWO_BIT ? (P < 5 ? P : P - 5) : (P & 1);
+  constexpr bool shifted = TWO_BIT ? (P >= 5) : (P >= 2);
+  // -(1024 * f + z1) with f = 4^-pp (2-bit) or 16^-pp (4-bit): exact, an integer below 2048
+  constexpr float off = TWO_BIT ? (pp == 0 ? 0.f : pp == 1 ? 768.f : pp == 2 ? 960.f : pp == 3 ? 1008.f : 1020.f)
+                                : (pp == 0 ? 0.f : 960.f);
+  const half_t t = (half_t)off - zb;
+  const half2_t nb = {t, t};
+  const uint32_t mask = TWO_BIT ? kc.mask2[pp] : kc.mask4[pp];
+  const half2_t sc = as_h2(TWO_BIT ? kc.sc2[pp] : kc.sc4[pp]);
+  uint32_t a[4];
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t src = shifted ? hi[d] : lo[d];
+    const half2_t h = as_h2((src & mask) | kc.magic);           // 1024 + c / f
+    const half2_t dz = __builtin_elementwise_fma(h, sc, nb);    // exact c - z1
+    a[d] = as_u32(dz * s1p);                                    // fp16((c - z1) * s1)
+  }
+  return uint4{a[0], a[1], a[2], a[3]};
+}
+
+// ------------------------------------------------------------------------------------ product
 //
-// LDS: activations (skewed), unit tables of both streams, the tile's second-order pairs, and the
-// cross-wave reduction slots.
-template <int G1>
-__global__ void __launch_bounds__(1024)
-mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ x, uint16_t* __restrict__ y) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  const int tid = threadIdx.x, nthr = blockDim.x;
-  const int lane = tid & 63, wv = tid >> 6, W = nthr >> 6;
+// Y[m][n] = sum_k X[m][k] W[n][k] + outliers, 1 <= M <= 16*NT, one 16-row tile per workgroup.
+//
+// Data movement (the "asynchronous dequantization" of Sec. 5 on this hardware): everything the
+// tile needs is requested in the first instructions of the workgroup and lands in LDS without
+// passing through registers (global_load_lds_dwordx4): the activations, the unit tables, the
+// tile's (s_int, z1) and (s2, z2) words, and PD code blocks per wave.  While the code blocks are
+// still in flight the waves meet once, and then every wave consumes its blocks in order, waiting
+// with s_waitcnt vmcnt(n) only for the block it needs next and refilling the freed slot.  The
+// second-order scale reconstruction of a block runs while the later blocks are still on their way.
+//
+// Compute: the decoded fp16 weights of a block are exactly the A operand of
+// v_mfma_f32_16x16x32_f16 (lane j*16+i holds 8 consecutive columns of row i), the activations of
+// the same columns are the B operand (lane j*16+m holds X[m][same 8 columns]), and the 16x16 fp32
+// accumulator holds Y[m][row] for the whole tile.  The matrix core does the multiply-accumulate
+// and the reduction over the four unit columns, so the vector ALU only decodes.  Batch columns
+// beyond M compute garbage that is never stored.
+//
+// LDS: `ring` (PD slots of 1 KiB per wave, reused for the cross-wave reduction at the end) and
+// `stage` are separate objects so that the compiler can tell reads of `stage` from the direct
+// loads into `ring`; ring slots are read with inline asm after an explicit wait.
+template <int NT, int PD, int STB>
+__global__ void __launch_bounds__(256)
+mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
+#pragma clang fp contract(off)
+  static_assert(PD >= NT && PD <= 8, "ring depth");
+  __shared__ __align__(16) unsigned char ring[4 * PD * 1024];
+  __shared__ __align__(16) unsigned char stage[STB];
+  constexpr int W = 4;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i = lane & 15, j = lane >> 4;
   const int C = b.B2 + b.B4;
-  unsigned char* xs = smem;
-  const int xs_bytes = (b.K >> 6) * XS_STRIDE;
-  uint32_t* units = (uint32_t*)(smem + xs_bytes);
-  uint32_t* m2s = units + 4 * C;
-  float* red = (float*)(m2s + b.S * 16);
-  float* ored = red + W * 16;
+  const int tile = blockIdx.x;
+  // stage layout: unit tables | meta1 of the tile | meta2 of the tile | activation rows
+  const int units_bytes = 32 * C, m1_bytes = 32 * b.G, m2_bytes = 64 * b.S;
+  const int rowbytes = 2 * b.K + 16;  // + 16: rows of a batch start in different LDS banks
+  unsigned char* units = stage;
+  unsigned char* m1s = units + units_bytes;
+  unsigned char* m2s = m1s + m1_bytes;
+  unsigned char* xs = m2s + m2_bytes;
+  unsigned char* myring = ring + wv * (PD * 1024);
+  const DecodeConsts kc = make_consts();
 
-  // threads-per-row mapping of the outlier phase: 16 rows share the workgroup's threads
-  const int tpr = nthr >> 4;
-  const int orow = tid / tpr, oq = tid % tpr;
+  // outlier / output mapping: 16 consecutive lanes share a row; lane q handles batch column q % Mp
+  // and every (16/Mp)-th outlier of the row
+  const int orow = tid >> 4, oq = tid & 15;
+  int Mp = 1;
+  while (Mp < M && Mp < 16) Mp <<= 1;
+  const int om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
 
-  bool staged = false;
-  for (int tile = blockIdx.x; tile < b.T; tile += gridDim.x) {
-    // (1) everything this tile needs from global memory is requested up front: row pointers, the
-    //     first code block of this wave, then the small operands that go to LDS.
-    const int32_t rp0 = b.rowptr[tile * 16 + orow];
-    const int32_t rp1 = b.rowptr[tile * 16 + orow + 1];
-    LaneBlock cur, nxt;
-    int c = wv;
-    if (c < C) issue_block<G1>(b, tile, c, lane, cur);
-    if (c + W < C) issue_block<G1>(b, tile, c + W, lane, nxt);
-    if (!staged) {
-      for (int ch = tid; ch < (b.K >> 3); ch += nthr) {
-        const uint4 v = ((const uint4*)x)[ch];
-        const int k = ch << 3;
-        *(uint4*)(xs + (k >> 6) * XS_STRIDE + (k & 63) * 2) = v;
-      }
-      for (int u = tid; u < 4 * b.B2; u += nthr) units[u] = b.unit2[u];
-      for (int u = tid; u < 4 * b.B4; u += nthr) units[4 * b.B2 + u] = b.unit4[u];
-      staged = true;
-    }
-    for (int e = tid; e < b.S * 16; e += nthr) m2s[e] = b.meta2[(size_t)tile * b.S * 16 + e];
-    lds_barrier();
-
-    // (2) first outlier words of this thread's row (the rest are fetched in the tail loop)
-    uint32_t o0 = 0, o1 = 0;
-    const int32_t e0 = rp0 + oq, e1 = e0 + tpr;
-    if (e0 < rp1) o0 = b.outl[e0];
-    if (e1 < rp1) o1 = b.outl[e1];
-
-    // (3) main loop over this wave's blocks: the next block's loads are in flight while the
-    //     current block's scale is reconstructed and its codes are decoded and multiplied.
-    float acc0 = 0.f, acc1 = 0.f;
-    for (; c < C; c += W) {
-      const LaneBlock blk = cur;
-      cur = nxt;
-      if (c + 2 * W < C) issue_block<G1>(b, tile, c + 2 * W, lane, nxt);
-      const uint32_t ue = units[4 * c + j];
-      const bool valid = ue != MPQ_INVALID_UNIT;
-      const uint32_t k0 = valid ? (ue & 0xFFFFu) * 32u : 0u;
-      const uint32_t sgp = valid ? (ue >> 16) : 0u;
-      const uint32_t m2 = m2s[sgp * 16 + i];
-      half_t s1 = scale_dequant(blk.m1 & 0xFFu, m2);
-      if (!valid) s1 = (half_t)0.0f;
-      const half_t z1h = (half_t)(float)(blk.m1 >> 8);
-      const unsigned char* xu = xs + (k0 >> 6) * XS_STRIDE + (k0 & 63u) * 2u;
-      if (c < b.B2) {
-        half2_t w[32];
-        decode2(blk.q, s1, z1h, w);
+  // ---- (1) all requests of the tile, oldest first: row pointers, staged operands, code blocks
+  int32_t rp0 = (int32_t)load_b32_async(b.rowptr + tile * 16 + orow);
+  int32_t rp1 = (int32_t)load_b32_async(b.rowptr + tile * 16 + orow + 1);
+  dma_region(b.unit2, units, 32 * b.B2, wv, lane);
+  dma_region(b.unit4, units + 32 * b.B2, 32 * b.B4, wv, lane);
+  dma_region(b.meta1 + (size_t)tile * b.G * 16, m1s, m1_bytes, wv, lane);
+  dma_region(b.meta2 + (size_t)tile * b.S * 16, m2s, m2_bytes, wv, lane);
+  for (int m = 0; m < M; ++m) dma_region(X + (size_t)m * b.K, xs + (size_t)m * rowbytes, 2 * b.K, wv, lane);
+  const int nblk = wv < C ? (C - wv + W - 1) / W : 0;  // blocks of this wave
+  const int nb0 = nblk < PD ? nblk : PD;               // requested now
+  const int nrefill = nblk - nb0;                      // requested as slots free up
+  auto block_src = [&](int c) -> const uint4* {
+    return c < b.B2 ? b.codes2 + ((size_t)tile * b.B2 + c) * 64 + lane
+                    : b.codes4 + ((size_t)tile * b.B4 + (c - b.B2)) * 64 + lane;
+  };
 #pragma unroll
-        for (int p = 0; p < 8; ++p) {
-          const uint4 xv = *(const uint4*)(xu + 16 * p);
-          acc0 = dot2(w[4 * p + 0], xv.x, acc0);
-          acc1 = dot2(w[4 * p + 1], xv.y, acc1);
-          acc0 = dot2(w[4 * p + 2], xv.z, acc0);
-          acc1 = dot2(w[4 * p + 3], xv.w, acc1);
-        }
-      } else {
-        half2_t w[16];
-        decode4(blk.q, s1, z1h, w);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const uint4 xv = *(const uint4*)(xu + 16 * p);
-          acc0 = dot2(w[4 * p + 0], xv.x, acc0);
-          acc1 = dot2(w[4 * p + 1], xv.y, acc1);
-          acc0 = dot2(w[4 * p + 2], xv.z, acc0);
-          acc1 = dot2(w[4 * p + 3], xv.w, acc1);
-        }
-      }
-    }
-    float acc = acc0 + acc1;
-    // (4) the four unit columns of a row sit in lanes i, i+16, i+32, i+48
-    acc += __shfl_xor(acc, 16);
-    acc += __shfl_xor(acc, 32);
-    if (lane < 16) red[wv * 16 + lane] = acc;
+  for (int r = 0; r < PD; ++r)
+    if (r < nb0) dma16(block_src(wv + r * W), myring + r * 1024);
+  wait_vm(nb0);  // the staged operands have landed; the code blocks may still be in flight
+  asm volatile("" : "+v"(rp0), "+v"(rp1)::"memory");
+  lds_barrier();
 
-    // (5) outliers of row `orow`: sum val * x[col] over the row's CSR words (Sec. 4.3, fused)
-    float oacc = 0.f;
+  // ---- (2) first outlier words of this thread's row (addresses depend on the row pointers);
+  //      always two loads so that the number of requests in flight is the same for every wave
+  const int64_t last = b.nnz > 0 ? b.nnz - 1 : 0;
+  const int32_t e0 = rp0 + oes, e1 = e0 + ostride;
+  uint32_t o0 = 0, o1 = 0;
+  if (b.nnz > 0) {
+    o0 = load_b32_async(b.outl + (e0 < last ? e0 : last));
+    o1 = load_b32_async(b.outl + (e1 < last ? e1 : last));
+  }
+  const int nout = b.nnz > 0 ? 2 : 0;
+
+  // ---- (3) this wave's blocks, in order
+  const unsigned char* xrow0 = xs + (size_t)(i < M ? i : 0) * rowbytes;
+  const unsigned char* xrow1 = xs + (size_t)((NT > 1 && i + 16 < M) ? i + 16 : 0) * rowbytes;
+  float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+  int slot = 0;
+  for (int it = 0; it < nblk; ++it) {
+    const int c = wv + it * W;
+    // requests younger than block `it`: the rest of the first batch, the outlier words, refills
+    const int refilled = it < nrefill ? it : nrefill;
+    const int younger = it < nb0 ? (nb0 - 1 - it) + nout + refilled : refilled - 1 - (it - nb0);
+    wait_vm(younger);
+    uint4 q;
     {
-      auto use = [&](uint32_t word) {
-        const uint32_t col = word & 0xFFFFu;
-        const half_t xv = *(const half_t*)(xs + (col >> 6) * XS_STRIDE + (col & 63u) * 2u);
-        oacc += (float)bits_to_half((uint16_t)(word >> 16)) * (float)xv;
-      };
-      if (e0 < rp1) use(o0);
-      if (e1 < rp1) use(o1);
-      for (int32_t e = e1 + tpr; e < rp1; e += tpr) use(b.outl[e]);
-      for (int off = tpr >> 1; off > 0; off >>= 1) oacc += __shfl_xor(oacc, off);
-      if (oq == 0) ored[orow] = oacc;
+      const uint32_t a =
+          (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(myring + slot * 1024) + lane * 16;
+      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(a) : "memory");
     }
-    lds_barrier();
-    if (tid < 16) {
-      float tot = ored[tid];
-      for (int w2 = 0; w2 < W; ++w2) tot += red[w2 * 16 + tid];
-      const int row = tile * 16 + tid;
-      if (row < b.N) y[row] = half_to_bits((half_t)tot);
+    if (it + PD < nblk) dma16(block_src(c + PD * W), myring + slot * 1024);
+    slot = slot + 1 == PD ? 0 : slot + 1;
+
+    const uint2 ue = *(const uint2*)(units + (4 * c + j) * 8);
+    const uint32_t m1 = *(const uint16_t*)(m1s + (ue.y & 0xFFFFu) + i * 2);
+    const uint32_t m2 = *(const uint32_t*)(m2s + (ue.y >> 16) + i * 4);
+    half_t s1 = scale_dequant(m1 & 0xFFu, m2);
+    if (ue.x & MPQ_PAD_UNIT) s1 = (half_t)0.0f;
+    const half2_t s1p = {s1, s1};
+    const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
+    const uint32_t xo = ue.x & 0x7FFFFFFFu;
+    const unsigned char* xb0 = xrow0 + xo;
+    const unsigned char* xb1 = xrow1 + xo;
+    const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+#define MPQ_MM_STEP(TWO, P)                                                                           \
+  {                                                                                                   \
+    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
+    const uint4 bv0 = *(const uint4*)(xb0 + 16 * (P));                                                \
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
+                                                  __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
+    if (NT > 1) {                                                                                     \
+      const uint4 bv1 = *(const uint4*)(xb1 + 16 * (P));                                              \
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                  \
+                                                    __builtin_bit_cast(half8_t, bv1), acc1, 0, 0, 0); \
+    }                                                                                                 \
+  }
+    if (c < b.B2) {
+      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
+      MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
+    } else {
+      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+      MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
     }
-    if (tile + (int)gridDim.x < b.T) lds_barrier();  // red / m2s are rewritten by the next tile
+#undef MPQ_MM_STEP
+  }
+  wait_vm(0);
+  asm volatile("" : "+v"(o0), "+v"(o1)::"memory");
+  // ---- (4) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share; the
+  //      wave parks it in its own (now idle) ring slots: red[NT][16 m][16 rows]
+  float* red = (float*)myring;
+  *(float4_t*)(red + i * 16 + 4 * j) = acc0;
+  if (NT > 1) *(float4_t*)(red + 256 + i * 16 + 4 * j) = acc1;
+
+  // ---- (5) outliers of row `orow` for batch column om (and om + 16): sum val * X[m][col]
+  float oa0 = 0.f, oa1 = 0.f;
+  {
+    const unsigned char* xo0 = xs + (size_t)(om < M ? om : 0) * rowbytes;
+    const unsigned char* xo1 = xs + (size_t)((NT > 1 && om + 16 < M) ? om + 16 : 0) * rowbytes;
+    auto use = [&](uint32_t word) {
+      const uint32_t off = (word & 0xFFFFu) * 2u;
+      const float v = (float)bits_to_half((uint16_t)(word >> 16));
+      oa0 += v * (float)*(const half_t*)(xo0 + off);
+      if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
+    };
+    if (e0 < rp1) use(o0);
+    if (e1 < rp1) use(o1);
+    for (int32_t e = e1 + ostride; e < rp1; e += ostride) use(b.outl[e]);
+    for (int off = Mp; off < 16; off <<= 1) {
+      oa0 += __shfl_xor(oa0, off);
+      if (NT > 1) oa1 += __shfl_xor(oa1, off);
+    }
+  }
+  __syncthreads();
+  {
+    const int row = tile * 16 + orow;
+    float t0 = oa0, t1 = oa1;
+#pragma unroll
+    for (int w2 = 0; w2 < W; ++w2) {
+      const float* r2 = (const float*)(ring + w2 * (PD * 1024));
+      t0 += r2[oq * 16 + orow];
+      if (NT > 1) t1 += r2[256 + oq * 16 + orow];
+    }
+    if (row < b.N) {
+      if (oq < M) Y[(size_t)oq * b.N + row] = half_to_bits((half_t)t0);
+      if (NT > 1 && oq + 16 < M) Y[(size_t)(oq + 16) * b.N + row] = half_to_bits((half_t)t1);
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------ dequant
-template <int G1>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
+#pragma clang fp contract(off)
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6, W = blockDim.x >> 6;
   const int i = lane & 15, j = lane >> 4;
   const int C = b.B2 + b.B4;
   const int tile = blockIdx.x;
   const int row = tile * 16 + i;
+  const DecodeConsts kc = make_consts();
   for (int c = wv; c < C; c += W) {
-    LaneBlock blk;
-    issue_block<G1>(b, tile, c, lane, blk);
-    const uint32_t ue = c < b.B2 ? b.unit2[4 * c + j] : b.unit4[4 * (c - b.B2) + j];
-    if (ue == MPQ_INVALID_UNIT || row >= b.N) continue;
-    const uint32_t k0 = (ue & 0xFFFFu) * 32u;
-    const uint32_t m2 = b.meta2[((size_t)tile * b.S + (ue >> 16)) * 16 + i];
-    const half_t s1 = scale_dequant(blk.m1 & 0xFFu, m2);
-    const half_t z1h = (half_t)(float)(blk.m1 >> 8);
-    uint4* dst = (uint4*)(Wout + (size_t)row * b.K + k0);
-    if (c < b.B2) {
-      half2_t w[32];
-      decode2(blk.q, s1, z1h, w);
-#pragma unroll
-      for (int p = 0; p < 8; ++p)
-        dst[p] = uint4{as_u32(w[4 * p]), as_u32(w[4 * p + 1]), as_u32(w[4 * p + 2]), as_u32(w[4 * p + 3])};
+    const bool two = c < b.B2;
+    const uint4 q = two ? b.codes2[((size_t)tile * b.B2 + c) * 64 + lane]
+                        : b.codes4[((size_t)tile * b.B4 + (c - b.B2)) * 64 + lane];
+    const uint2 ue = two ? b.unit2[4 * c + j] : b.unit4[4 * (c - b.B2) + j];
+    if ((ue.x & MPQ_PAD_UNIT) || row >= b.N) continue;
+    const uint32_t m1 = b.meta1[(size_t)tile * b.G * 16 + (ue.y & 0xFFFFu) / 2 + i];
+    const uint32_t m2 = b.meta2[(size_t)tile * b.S * 16 + (ue.y >> 16) / 4 + i];
+    const half_t s1 = scale_dequant(m1 & 0xFFu, m2);
+    const half2_t s1p = {s1, s1};
+    const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));
+    uint4* dst = (uint4*)(Wout + (size_t)row * b.K + ue.x / 2);
+    const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+    if (two) {
+      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      dst[0] = decode_step<true, 0>(lo, hi, s1p, zb, kc);
+      dst[1] = decode_step<true, 1>(lo, hi, s1p, zb, kc);
+      dst[2] = decode_step<true, 2>(lo, hi, s1p, zb, kc);
+      dst[3] = decode_step<true, 3>(lo, hi, s1p, zb, kc);
+      dst[4] = decode_step<true, 4>(lo, hi, s1p, zb, kc);
+      dst[5] = decode_step<true, 5>(lo, hi, s1p, zb, kc);
+      dst[6] = decode_step<true, 6>(lo, hi, s1p, zb, kc);
+      dst[7] = decode_step<true, 7>(lo, hi, s1p, zb, kc);
     } else {
-      half2_t w[16];
-      decode4(blk.q, s1, z1h, w);
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-        dst[p] = uint4{as_u32(w[4 * p]), as_u32(w[4 * p + 1]), as_u32(w[4 * p + 2]), as_u32(w[4 * p + 3])};
+      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+      dst[0] = decode_step<false, 0>(lo, hi, s1p, zb, kc);
+      dst[1] = decode_step<false, 1>(lo, hi, s1p, zb, kc);
+      dst[2] = decode_step<false, 2>(lo, hi, s1p, zb, kc);
+      dst[3] = decode_step<false, 3>(lo, hi, s1p, zb, kc);
     }
   }
 }
@@ -334,8 +427,8 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   if (st != MPQ_OK) return st;
   if (((uintptr_t)blob_dev & 15u) != 0) return MPQ_ERR_ALIGN;
   const unsigned char* p = (const unsigned char*)blob_dev;
-  d->unit2 = (const uint32_t*)(p + h->off_unit2);
-  d->unit4 = (const uint32_t*)(p + h->off_unit4);
+  d->unit2 = (const uint2*)(p + h->off_unit2);
+  d->unit4 = (const uint2*)(p + h->off_unit4);
   d->codes2 = (const uint4*)(p + h->off_codes2);
   d->codes4 = (const uint4*)(p + h->off_codes4);
   d->meta1 = (const uint16_t*)(p + h->off_meta1);
@@ -344,25 +437,54 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   d->outl = (const uint32_t*)(p + h->off_outl);
   d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->n2 = h->n2;
   d->U2 = h->U2; d->U4 = h->U4; d->B2 = h->B2; d->B4 = h->B4; d->T = h->T;
+  d->nnz = h->nnz;
   return MPQ_OK;
 }
 
-int g_gemv_threads = 0;  // 0 = choose from K
-int g_gemv_max_blocks = 0;
-
-size_t gemv_lds_bytes(const MpqHeader& h, int threads) {
-  const size_t W = threads / 64;
-  return (size_t)(h.K / 64) * XS_STRIDE + 16ull * (h.B2 + h.B4) + 64ull * h.S + (W * 16 + 16) * 4;
+// Bytes of the `stage` array a batch of M rows needs (unit tables, the tile's meta words, activations).
+size_t stage_bytes(const MpqHeader& h, int M) {
+  return 32ull * (h.B2 + h.B4) + 32ull * h.G + 64ull * h.S + (size_t)M * (2ull * h.K + 16);
 }
 
-template <typename Kern>
-mpq_status allow_lds(Kern kern, size_t bytes) {
-  if (bytes > 160 * 1024) return MPQ_ERR_UNSUPPORTED;
-  if (bytes > 48 * 1024) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
-      (void)hipGetLastError();
-      return MPQ_ERR_HIP;
-    }
+int g_ring_depth = 0;  // 0 = automatic
+
+template <int NT, int PD, int STB>
+mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, STB>), dim3(h.T), dim3(256), 0, s, d, X, Y, M);
+  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+}
+
+// Static LDS size classes of the product kernel (bytes of `stage`); the ring depth per class
+// keeps several workgroups resident per compute unit (160 KiB of LDS).
+template <int NT>
+mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  const size_t need = stage_bytes(h, M);
+  const int pd = g_ring_depth;
+  if (need <= 11520) {
+    if (pd == 2) return launch_mm<NT, 2, 11520>(h, d, X, Y, M, s);
+    if (pd == 4) return launch_mm<NT, 4, 11520>(h, d, X, Y, M, s);
+    if (pd == 5) return launch_mm<NT, 5, 11520>(h, d, X, Y, M, s);
+    return launch_mm<NT, 3, 11520>(h, d, X, Y, M, s);
+  }
+  if (need <= 24 * 1024) return launch_mm<NT, 4, 24 * 1024>(h, d, X, Y, M, s);
+  if (need <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024>(h, d, X, Y, M, s);
+  if (need <= 80 * 1024) return launch_mm<NT, 4, 80 * 1024>(h, d, X, Y, M, s);
+  if (need <= 144 * 1024) return launch_mm<NT, 3, 144 * 1024>(h, d, X, Y, M, s);
+  return MPQ_ERR_UNSUPPORTED;
+}
+
+mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  constexpr size_t kStageMax = 144 * 1024;
+  if (stage_bytes(h, 1) > kStageMax) return MPQ_ERR_UNSUPPORTED;
+  int Mc = M;  // largest batch chunk whose activations fit LDS together with the tables
+  while (Mc > 1 && stage_bytes(h, Mc) > kStageMax) --Mc;
+  if (Mc > 16 && Mc < M) Mc = 16;
+  for (int m0 = 0; m0 < M; m0 += Mc) {
+    const int mc = M - m0 < Mc ? M - m0 : Mc;
+    const uint16_t* Xc = X + (size_t)m0 * h.K;
+    uint16_t* Yc = Y + (size_t)m0 * h.N;
+    mpq_status st = mc > 16 ? mm_chunk<2>(h, d, Xc, Yc, mc, s) : mm_chunk<1>(h, d, Xc, Yc, mc, s);
+    if (st != MPQ_OK) return st;
   }
   return MPQ_OK;
 }
@@ -371,36 +493,27 @@ mpq_status allow_lds(Kern kern, size_t bytes) {
 
 extern "C" {
 
-// Launch-shape override for tuning sweeps (0 restores the built-in choice). Not thread safe.
-void mpq_debug_set_gemv_launch(int threads, int max_blocks) {
-  g_gemv_threads = threads;
-  g_gemv_max_blocks = max_blocks;
+// Tuning hook for sweeps; not part of the supported interface and not thread safe.
+// key 0: ring depth (code blocks in flight per wave) for the smallest LDS class, 0 = automatic.
+void mpq_debug_set(int key, int value) {
+  if (key == 0) g_ring_depth = value;
 }
 
-mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev, uint16_t* y_dev,
-                    void* stream) {
-  if (!x_dev || !y_dev) return MPQ_ERR_NULL;
+mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                    int32_t M, void* stream) {
+  if (!X_dev || !Y_dev) return MPQ_ERR_NULL;
+  if (M < 1 || M > MPQ_MAX_M) return MPQ_ERR_SHAPE;
   MpqHeader h;
   DevBlob d;
   mpq_status st = make_dev(hdr_host, blob_dev, &h, &d);
   if (st != MPQ_OK) return st;
-  if ((((uintptr_t)x_dev | (uintptr_t)y_dev) & 15u) != 0) return MPQ_ERR_ALIGN;
-  int threads = g_gemv_threads > 0 ? g_gemv_threads : (h.K > 16384 ? 512 : 256);
-  if (threads % 64 != 0 || threads < 64 || threads > 1024) return MPQ_ERR_SHAPE;
-  const size_t lds = gemv_lds_bytes(h, threads);
-  int blocks = h.T;
-  if (g_gemv_max_blocks > 0 && blocks > g_gemv_max_blocks) blocks = g_gemv_max_blocks;
-  hipStream_t s = (hipStream_t)stream;
-  if (h.g1 == 64) {
-    st = allow_lds(mpq_gemv_kernel<64>, lds);
-    if (st != MPQ_OK) return st;
-    hipLaunchKernelGGL(mpq_gemv_kernel<64>, dim3(blocks), dim3(threads), lds, s, d, x_dev, y_dev);
-  } else {
-    st = allow_lds(mpq_gemv_kernel<128>, lds);
-    if (st != MPQ_OK) return st;
-    hipLaunchKernelGGL(mpq_gemv_kernel<128>, dim3(blocks), dim3(threads), lds, s, d, x_dev, y_dev);
-  }
-  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+  if ((((uintptr_t)X_dev | (uintptr_t)Y_dev) & 15u) != 0) return MPQ_ERR_ALIGN;
+  return mm_all(h, d, X_dev, Y_dev, M, (hipStream_t)stream);
+}
+
+mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev, uint16_t* y_dev,
+                    void* stream) {
+  return mpq_gemm(hdr_host, blob_dev, x_dev, y_dev, 1, stream);
 }
 
 mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_out_dev, int add_outliers,
@@ -412,10 +525,7 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   if (st != MPQ_OK) return st;
   if (((uintptr_t)W_out_dev & 15u) != 0) return MPQ_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  if (h.g1 == 64)
-    hipLaunchKernelGGL(mpq_dequant_kernel<64>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
-  else
-    hipLaunchKernelGGL(mpq_dequant_kernel<128>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  hipLaunchKernelGGL(mpq_dequant_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
   if (add_outliers && h.nnz > 0) {
     hipLaunchKernelGGL(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
@@ -425,18 +535,3 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
 }
 
 }  // extern "C"
-
-extern "C" mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev,
-                               uint16_t* Y_dev, int32_t M, void* stream) {
-  if (!X_dev || !Y_dev) return MPQ_ERR_NULL;
-  if (M < 1 || M > MPQ_MAX_M) return MPQ_ERR_SHAPE;
-  MpqHeader h;
-  mpq_status st = mpq_internal_check_header(hdr_host, &h);
-  if (st != MPQ_OK) return st;
-  // Row m of the batch is an independent matrix-vector product.
-  for (int32_t m = 0; m < M; ++m) {
-    st = mpq_gemv(hdr_host, blob_dev, X_dev + (size_t)m * h.K, Y_dev + (size_t)m * h.N, stream);
-    if (st != MPQ_OK) return st;
-  }
-  return MPQ_OK;
-}

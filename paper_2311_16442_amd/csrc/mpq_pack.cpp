@@ -40,8 +40,8 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, MpqHeader* h) {
   h->T = (d->N + MPQ_TILE_ROWS - 1) / MPQ_TILE_ROWS;
   h->nnz = nnz;
   uint64_t off = MPQ_HEADER_BYTES;
-  h->off_unit2 = off; off = align_up(off + 4ull * 4 * h->B2, MPQ_SECTION_ALIGN);
-  h->off_unit4 = off; off = align_up(off + 4ull * 4 * h->B4, MPQ_SECTION_ALIGN);
+  h->off_unit2 = off; off = align_up(off + 8ull * 4 * h->B2, MPQ_SECTION_ALIGN);
+  h->off_unit4 = off; off = align_up(off + 8ull * 4 * h->B4, MPQ_SECTION_ALIGN);
   h->off_codes2 = off; off = align_up(off + (uint64_t)h->T * h->B2 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
   h->off_codes4 = off; off = align_up(off + (uint64_t)h->T * h->B4 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
   h->off_meta1 = off; off = align_up(off + (uint64_t)h->T * h->G * MPQ_TILE_ROWS * 2, MPQ_SECTION_ALIGN);
@@ -169,17 +169,22 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   uint32_t* unit2 = (uint32_t*)(blob + h.off_unit2);
   uint32_t* unit4 = (uint32_t*)(blob + h.off_unit4);
   const int32_t upg2 = (int32_t)(g1 / 64), upg4 = (int32_t)(g1 / 32);
+  std::vector<int64_t> k0_2(4 * h.B2, -1), k0_4(4 * h.B4, -1);
   for (int32_t u = 0; u < 4 * h.B2; ++u) {
-    if (u >= h.U2) { unit2[u] = MPQ_INVALID_UNIT; continue; }
+    if (u >= h.U2) { unit2[2 * u] = MPQ_PAD_UNIT; unit2[2 * u + 1] = 0; continue; }
     const int32_t g = groups2[u / upg2];
     const int64_t k0 = (int64_t)g * g1 + 64 * (u % upg2);
-    unit2[u] = (uint32_t)(k0 / 32) | ((uint32_t)(g / d->g2) << 16);
+    k0_2[u] = k0;
+    unit2[2 * u] = (uint32_t)(2 * k0);
+    unit2[2 * u + 1] = (uint32_t)(stream_index[g] * 32) | ((uint32_t)((g / d->g2) * 64) << 16);
   }
   for (int32_t u = 0; u < 4 * h.B4; ++u) {
-    if (u >= h.U4) { unit4[u] = MPQ_INVALID_UNIT; continue; }
+    if (u >= h.U4) { unit4[2 * u] = MPQ_PAD_UNIT; unit4[2 * u + 1] = 0; continue; }
     const int32_t g = groups4[u / upg4];
     const int64_t k0 = (int64_t)g * g1 + 32 * (u % upg4);
-    unit4[u] = (uint32_t)(k0 / 32) | ((uint32_t)(g / d->g2) << 16);
+    k0_4[u] = k0;
+    unit4[2 * u] = (uint32_t)(2 * k0);
+    unit4[2 * u + 1] = (uint32_t)(stream_index[g] * 32) | ((uint32_t)((g / d->g2) * 64) << 16);
   }
   uint32_t* codes2 = (uint32_t*)(blob + h.off_codes2);
   uint32_t* codes4 = (uint32_t*)(blob + h.off_codes4);
@@ -189,14 +194,14 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     const int64_t t = n / MPQ_TILE_ROWS, i = n % MPQ_TILE_ROWS;
     const uint8_t* row = w->codes + n * K;
     for (int32_t u = 0; u < h.U2; ++u) {
-      const int64_t k0 = (int64_t)(unit2[u] & 0xFFFFu) * 32;
+      const int64_t k0 = k0_2[u];
       const int64_t b = u / 4, j = u % 4;
       uint32_t* q = codes2 + (((t * h.B2 + b) * 64 + j * 16 + i) * 4);
       for (int kl = 0; kl < 64; ++kl)
         q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 2 * (kl / 8));
     }
     for (int32_t u = 0; u < h.U4; ++u) {
-      const int64_t k0 = (int64_t)(unit4[u] & 0xFFFFu) * 32;
+      const int64_t k0 = k0_4[u];
       const int64_t b = u / 4, j = u % 4;
       uint32_t* q = codes4 + (((t * h.B4 + b) * 64 + j * 16 + i) * 4);
       for (int kl = 0; kl < 32; ++kl)

@@ -22,8 +22,8 @@ def read_header(blob: np.ndarray) -> dict:
 def unpack(blob: np.ndarray) -> dict:
     h = read_header(blob)
     N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
-    unit2 = blob[h["off_unit2"]: h["off_unit2"] + 16 * h["B2"]].view(np.uint32)
-    unit4 = blob[h["off_unit4"]: h["off_unit4"] + 16 * h["B4"]].view(np.uint32)
+    unit2 = blob[h["off_unit2"]: h["off_unit2"] + 32 * h["B2"]].view(np.uint32).reshape(-1, 2)
+    unit4 = blob[h["off_unit4"]: h["off_unit4"] + 32 * h["B4"]].view(np.uint32).reshape(-1, 2)
     c2 = blob[h["off_codes2"]: h["off_codes2"] + T * h["B2"] * 1024].view(np.uint32).reshape(T, h["B2"], 4, 16, 4)
     c4 = blob[h["off_codes4"]: h["off_codes4"] + T * h["B4"] * 1024].view(np.uint32).reshape(T, h["B4"], 4, 16, 4)
     codes = np.zeros((T * TILE, K), dtype=np.uint8)
@@ -31,32 +31,34 @@ def unpack(blob: np.ndarray) -> dict:
     stream_groups = []                       # K-group of each stream group, 2-bit stream first
     group_of_super = {}
     for u in range(4 * h["B2"]):
-        e = int(unit2[u])
-        if e == 0xFFFFFFFF:
-            assert u >= h["U2"]
+        e, e1 = int(unit2[u, 0]), int(unit2[u, 1])
+        if e & 0x80000000:
+            assert u >= h["U2"] and e == 0x80000000 and e1 == 0
             assert not c2[:, u // 4, u % 4].any()        # padding units are zero
             continue
-        k0 = (e & 0xFFFF) * 32
+        k0 = e // 2
         g = k0 // g1
         is4[g] = 0
-        assert (e >> 16) == g // g2
+        assert (e1 >> 16) == (g // g2) * 64
         if k0 % g1 == 0:
+            assert (e1 & 0xFFFF) == 32 * len(stream_groups)
             stream_groups.append(g)
         words = c2[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
         for kl in range(64):
             d, sh = (kl % 8) // 2, 16 * (kl % 2) + 2 * (kl // 8)
             codes[:, k0 + kl] = ((words[:, :, d] >> sh) & 3).reshape(-1)
     for u in range(4 * h["B4"]):
-        e = int(unit4[u])
-        if e == 0xFFFFFFFF:
-            assert u >= h["U4"]
+        e, e1 = int(unit4[u, 0]), int(unit4[u, 1])
+        if e & 0x80000000:
+            assert u >= h["U4"] and e == 0x80000000 and e1 == 0
             assert not c4[:, u // 4, u % 4].any()
             continue
-        k0 = (e & 0xFFFF) * 32
+        k0 = e // 2
         g = k0 // g1
         is4[g] = 1
-        assert (e >> 16) == g // g2
+        assert (e1 >> 16) == (g // g2) * 64
         if k0 % g1 == 0:
+            assert (e1 & 0xFFFF) == 32 * len(stream_groups)
             stream_groups.append(g)
         words = c4[:, u // 4, u % 4]
         for kl in range(32):
