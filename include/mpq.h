@@ -93,13 +93,15 @@ const char* mpq_status_str(mpq_status s);
  * Returns a negative value on invalid arguments. */
 double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns_bits);
 
-/* Size in bytes of the packed blob for this shape, 4-bit map and outlier count.
- * `is4` is a HOST array of G bytes. */
-mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, int64_t nnz, size_t* bytes);
+/* Size in bytes of the packed blob for this shape, 4-bit map and outlier row pointer.
+ * `is4` is a HOST array of G bytes, `row_ptr` a HOST array of N+1 entries (the blob stores the
+ * outliers of every 16-row tile in a record padded to the fullest tile). */
+mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, const int32_t* row_ptr, size_t* bytes);
 
 /* Sec. 3.3 "Memory Alignment": split the codes into a 2-bit stream and a 4-bit stream whose
  * per-lane units are 16 bytes, homogeneous in bit width and 16-byte aligned, interleave the
- * per-group (s_int, z1) bytes and the (s2, z2) halves, and store the outliers as 32-bit words.
+ * per-group (s_int, z1) bytes and the (s2, z2) halves, and store the outliers as 32-bit words
+ * (fp16 value, 16-bit column) with a 32-bit running count per row (Sec. 2.3), grouped by row tile.
  * Validates the logical matrix completely (code ranges, CSR order, outliers only in 2-bit groups)
  * before writing.  `blob_host` must hold `bytes` >= mpq_packed_size(...) bytes; all of them are
  * written (padding is zero).  The blob is position independent and may be copied byte for byte. */

@@ -60,7 +60,7 @@ def lib():
         L.mpq_avg_bits.restype = C.c_double
         L.mpq_avg_bits.argtypes = [C.POINTER(Desc), C.c_int32, C.c_int64, C.c_int, C.c_int]
         L.mpq_packed_size.restype = C.c_int
-        L.mpq_packed_size.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_int64, C.POINTER(C.c_size_t)]
+        L.mpq_packed_size.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(C.c_size_t)]
         L.mpq_pack_host.restype = C.c_int
         L.mpq_pack_host.argtypes = [C.POINTER(Desc), C.POINTER(LogicalPtrs), C.c_void_p, C.c_size_t]
         L.mpq_blob_info.restype = C.c_int
@@ -94,12 +94,15 @@ def avg_bits(N, K, g1, g2, n4, nnz, mode=0, ns_bits=4, g2_axis=0) -> float:
     return float(lib().mpq_avg_bits(C.byref(d), int(n4), int(nnz), int(mode), int(ns_bits)))
 
 
-def packed_size(N, K, g1, g2, is4, nnz, g2_axis=0) -> int:
+def packed_size(N, K, g1, g2, is4, row_ptr, g2_axis=0) -> int:
     d = Desc(N, K, g1, g2, g2_axis)
     is4 = _np(is4, np.uint8)
+    rp = _np(row_ptr, np.int32)
+    if rp.size != N + 1:
+        raise MpqError(MPQ_ERR_SHAPE, "mpq_packed_size")
     out = C.c_size_t(0)
-    _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p), int(nnz), C.byref(out)),
-           "mpq_packed_size")
+    _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p), rp.ctypes.data_as(C.c_void_p),
+                                 C.byref(out)), "mpq_packed_size")
     return int(out.value)
 
 
@@ -126,10 +129,11 @@ def pack(N, K, g1, g2, is4, codes, s_int, z1, s2, z2, row_ptr, col, val, g2_axis
     arrs = dict(is4=is4, codes=_np(codes, np.uint8), s_int=_np(s_int, np.uint8), z1=_np(z1, np.uint8),
                 s2=_np(s2, np.uint16), z2=_np(z2, np.uint16), row_ptr=_np(row_ptr, np.int32),
                 col=_np(col, np.uint16), val=_np(val, np.uint16))
-    nnz = int(arrs["row_ptr"][-1]) if arrs["row_ptr"].size else 0
+    if arrs["row_ptr"].size != int(N) + 1:
+        raise MpqError(MPQ_ERR_SHAPE, "mpq_pack_host")
     size = C.c_size_t(0)
-    _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p), max(nnz, 0), C.byref(size)),
-           "mpq_packed_size")
+    _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p),
+                                 arrs["row_ptr"].ctypes.data_as(C.c_void_p), C.byref(size)), "mpq_packed_size")
     blob = np.empty(size.value, dtype=np.uint8)
     ptrs = LogicalPtrs(**{k: (v.ctypes.data if v.size else None) for k, v in arrs.items()})
     _check(lib().mpq_pack_host(C.byref(d), C.byref(ptrs), blob.ctypes.data_as(C.c_void_p), size.value),

@@ -22,8 +22,13 @@
 //   meta1     T x G x 16 x 2 B      (s_int | z1 << 8) per (tile, stream group, row); stream group
 //                                   order = all 2-bit groups in K order, then all 4-bit groups
 //   meta2     T x S x 16 x 4 B      (s2 | z2 << 16) per (tile, super-group, row)
-//   row_ptr   int32 [16*T + 1]      CSR row pointer, rows beyond N repeat nnz
-//   outl      uint32 [nnz]          col | val << 16   (Sec. 2.3: one 32-bit word per outlier)
+//   otile     T x (128 + 4*ocap) B  the outliers of each row tile as one self-contained record, so that
+//                                   a kernel can request it without first reading a row pointer:
+//                                     uint32 start[17] (then zeros up to 128 B): start[r] = index of the
+//                                       first word of row r of the tile, start[16] = number of words
+//                                     uint32 word[ocap]: col | val << 16   (Sec. 2.3: one 32-bit word per
+//                                       outlier, one 32-bit running count per row), rows in order
+//                                   ocap = the largest number of outliers in any tile, rounded up to 32
 //
 // Bit positions inside a unit (4 little-endian dwords):
 //   2-bit: column k0 + kl (kl = 0..63) sits in dword (kl % 8) / 2, bits 16*(kl % 2) + 2*(kl / 8) ..+1
@@ -38,12 +43,13 @@
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 3u
+#define MPQ_VERSION 4u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024
 #define MPQ_SECTION_ALIGN 256
 #define MPQ_PAD_UNIT 0x80000000u
+#define MPQ_OTILE_HEAD 128 /* bytes of the row-start table at the head of a tile's outlier record */
 
 typedef struct {
   uint32_t magic, version;
@@ -53,7 +59,8 @@ typedef struct {
   int32_t B2, B4;  /* blocks (4 units x 16 rows) per row tile in each stream */
   int32_t T;       /* row tiles */
   int64_t nnz;
-  uint64_t off_unit2, off_unit4, off_codes2, off_codes4, off_meta1, off_meta2, off_rowptr, off_outl;
+  uint64_t off_unit2, off_unit4, off_codes2, off_codes4, off_meta1, off_meta2, off_otile;
+  uint64_t ocap;   /* words per tile in the outlier records (multiple of 32) */
   uint64_t total_bytes;
   uint8_t pad[256 - 4 * 16 - 8 - 8 * 8 - 8];
 } MpqHeader;

@@ -37,10 +37,11 @@ struct DevBlob {
   const uint4* codes4;
   const uint16_t* meta1;
   const uint32_t* meta2;
-  const int32_t* rowptr;
-  const uint32_t* outl;
+  const unsigned char* otile;  // per-tile outlier records
   int32_t N, K, G, S, n2, U2, U4, B2, B4, T;
+  int32_t orec_bytes;          // bytes of one outlier record (row-start table + words), 0 if no outliers
   int64_t nnz;
+  int32_t dbg;  // tuning experiments only: bit 0 skips the decode/multiply, bit 1 skips the code-block loads
 };
 
 __device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
@@ -181,7 +182,7 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // Data movement (the "asynchronous dequantization" of Sec. 5 on this hardware): everything the
 // tile needs is requested in the first instructions of the workgroup and lands in LDS without
 // passing through registers (global_load_lds_dwordx4): the activations, the unit tables, the
-// tile's (s_int, z1) and (s2, z2) words, and PD code blocks per wave.  While the code blocks are
+// tile's (s_int, z1) and (s2, z2) words, the tile's outlier record, and PD code blocks per wave.  While the code blocks are
 // still in flight the waves meet once, and then every wave consumes its blocks in order, waiting
 // with s_waitcnt vmcnt(n) only for the block it needs next and refilling the freed slot.  The
 // second-order scale reconstruction of a block runs while the later blocks are still on their way.
@@ -209,13 +210,14 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   const int i = lane & 15, j = lane >> 4;
   const int C = b.B2 + b.B4;
   const int tile = blockIdx.x;
-  // stage layout: unit tables | meta1 of the tile | meta2 of the tile | activation rows
+  // stage layout: unit tables | meta1 of the tile | meta2 of the tile | outlier record | activation rows
   const int units_bytes = 32 * C, m1_bytes = 32 * b.G, m2_bytes = 64 * b.S;
   const int rowbytes = 2 * b.K + 16;  // + 16: rows of a batch start in different LDS banks
   unsigned char* units = stage;
   unsigned char* m1s = units + units_bytes;
   unsigned char* m2s = m1s + m1_bytes;
-  unsigned char* xs = m2s + m2_bytes;
+  unsigned char* ots = m2s + m2_bytes;
+  unsigned char* xs = ots + b.orec_bytes;
   unsigned char* myring = ring + wv * (PD * 1024);
   const DecodeConsts kc = make_consts();
 
@@ -226,58 +228,47 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   while (Mp < M && Mp < 16) Mp <<= 1;
   const int om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
 
-  // ---- (1) all requests of the tile, oldest first: row pointers, staged operands, code blocks
-  int32_t rp0 = (int32_t)load_b32_async(b.rowptr + tile * 16 + orow);
-  int32_t rp1 = (int32_t)load_b32_async(b.rowptr + tile * 16 + orow + 1);
+  // ---- (1) all requests of the tile, oldest first: staged operands, then code blocks
   dma_region(b.unit2, units, 32 * b.B2, wv, lane);
   dma_region(b.unit4, units + 32 * b.B2, 32 * b.B4, wv, lane);
-  dma_region(b.meta1 + (size_t)tile * b.G * 16, m1s, m1_bytes, wv, lane);
+  if (!(b.dbg & 8)) dma_region(b.meta1 + (size_t)tile * b.G * 16, m1s, m1_bytes, wv, lane);
   dma_region(b.meta2 + (size_t)tile * b.S * 16, m2s, m2_bytes, wv, lane);
-  for (int m = 0; m < M; ++m) dma_region(X + (size_t)m * b.K, xs + (size_t)m * rowbytes, 2 * b.K, wv, lane);
+  if (!(b.dbg & 16)) dma_region(b.otile + (size_t)tile * b.orec_bytes, ots, b.orec_bytes, wv, lane);
+  if (!(b.dbg & 4))
+    for (int m = 0; m < M; ++m) dma_region(X + (size_t)m * b.K, xs + (size_t)m * rowbytes, 2 * b.K, wv, lane);
   const int nblk = wv < C ? (C - wv + W - 1) / W : 0;  // blocks of this wave
   const int nb0 = nblk < PD ? nblk : PD;               // requested now
-  const int nrefill = nblk - nb0;                      // requested as slots free up
   auto block_src = [&](int c) -> const uint4* {
     return c < b.B2 ? b.codes2 + ((size_t)tile * b.B2 + c) * 64 + lane
                     : b.codes4 + ((size_t)tile * b.B4 + (c - b.B2)) * 64 + lane;
   };
 #pragma unroll
   for (int r = 0; r < PD; ++r)
-    if (r < nb0) dma16(block_src(wv + r * W), myring + r * 1024);
+    if (r < nb0 && !(b.dbg & 2)) dma16(block_src(wv + r * W), myring + r * 1024);
   wait_vm(nb0);  // the staged operands have landed; the code blocks may still be in flight
-  asm volatile("" : "+v"(rp0), "+v"(rp1)::"memory");
   lds_barrier();
 
-  // ---- (2) first outlier words of this thread's row (addresses depend on the row pointers);
-  //      always two loads so that the number of requests in flight is the same for every wave
-  const int64_t last = b.nnz > 0 ? b.nnz - 1 : 0;
-  const int32_t e0 = rp0 + oes, e1 = e0 + ostride;
-  uint32_t o0 = 0, o1 = 0;
-  if (b.nnz > 0) {
-    o0 = load_b32_async(b.outl + (e0 < last ? e0 : last));
-    o1 = load_b32_async(b.outl + (e1 < last ? e1 : last));
-  }
-  const int nout = b.nnz > 0 ? 2 : 0;
-
-  // ---- (3) this wave's blocks, in order
+  // ---- (2) this wave's blocks, in order
   const unsigned char* xrow0 = xs + (size_t)(i < M ? i : 0) * rowbytes;
   const unsigned char* xrow1 = xs + (size_t)((NT > 1 && i + 16 < M) ? i + 16 : 0) * rowbytes;
   float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
   int slot = 0;
   for (int it = 0; it < nblk; ++it) {
     const int c = wv + it * W;
-    // requests younger than block `it`: the rest of the first batch, the outlier words, refills
-    const int refilled = it < nrefill ? it : nrefill;
-    const int younger = it < nb0 ? (nb0 - 1 - it) + nout + refilled : refilled - 1 - (it - nb0);
-    wait_vm(younger);
+    // Requests of this wave that are younger than block `it` (each freed slot is refilled at
+    // once, so PD - 1 blocks follow until the stream runs dry): loads complete in order, hence
+    // "at most that many outstanding" means block `it` has landed.
+    const int left = nblk - 1 - it;
+    if (left >= PD - 1) MPQ_VMCNT(PD - 1); else wait_vm(left);
     uint4 q;
     {
       const uint32_t a =
           (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(myring + slot * 1024) + lane * 16;
       asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(a) : "memory");
     }
-    if (it + PD < nblk) dma16(block_src(c + PD * W), myring + slot * 1024);
+    if (it + PD < nblk && !(b.dbg & 2)) dma16(block_src(c + PD * W), myring + slot * 1024);
     slot = slot + 1 == PD ? 0 : slot + 1;
+    if (b.dbg & 1) { acc0[0] += (float)q.x; continue; }
 
     const uint2 ue = *(const uint2*)(units + (4 * c + j) * 8);
     const uint32_t m1 = *(const uint16_t*)(m1s + (ue.y & 0xFFFFu) + i * 2);
@@ -312,17 +303,19 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
     }
 #undef MPQ_MM_STEP
   }
-  wait_vm(0);
-  asm volatile("" : "+v"(o0), "+v"(o1)::"memory");
-  // ---- (4) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share; the
+  // ---- (3) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share; the
   //      wave parks it in its own (now idle) ring slots: red[NT][16 m][16 rows]
   float* red = (float*)myring;
   *(float4_t*)(red + i * 16 + 4 * j) = acc0;
   if (NT > 1) *(float4_t*)(red + 256 + i * 16 + 4 * j) = acc1;
 
-  // ---- (5) outliers of row `orow` for batch column om (and om + 16): sum val * X[m][col]
+  // ---- (4) outliers of row `orow` for batch column om (and om + 16): sum val * X[m][col], all
+  //      operands already in LDS (Sec. 4.3, fused: no second kernel, no second trip to memory)
   float oa0 = 0.f, oa1 = 0.f;
-  {
+  if (b.orec_bytes > 0) {
+    const uint32_t* ostart = (const uint32_t*)ots;
+    const uint32_t* owords = (const uint32_t*)(ots + MPQ_OTILE_HEAD);
+    const int32_t rp0 = (int32_t)ostart[orow], rp1 = (int32_t)ostart[orow + 1];
     const unsigned char* xo0 = xs + (size_t)(om < M ? om : 0) * rowbytes;
     const unsigned char* xo1 = xs + (size_t)((NT > 1 && om + 16 < M) ? om + 16 : 0) * rowbytes;
     auto use = [&](uint32_t word) {
@@ -331,9 +324,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
       oa0 += v * (float)*(const half_t*)(xo0 + off);
       if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
     };
-    if (e0 < rp1) use(o0);
-    if (e1 < rp1) use(o1);
-    for (int32_t e = e1 + ostride; e < rp1; e += ostride) use(b.outl[e]);
+    for (int32_t e = rp0 + oes; e < rp1; e += ostride) use(owords[e]);
     for (int off = Mp; off < 16; off <<= 1) {
       oa0 += __shfl_xor(oa0, off);
       if (NT > 1) oa1 += __shfl_xor(oa1, off);
@@ -400,17 +391,18 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   }
 }
 
-// One thread per (row, slot): W[row][col] = fp16(W[row][col] + val)  (native fp16 add = the fp32
-// add followed by one rounding that the definition states).
+// W[row][col] = fp16(W[row][col] + val) for every outlier word of the tile (native fp16 add = the
+// fp32 add followed by one rounding that the definition states); 16 threads per row.
 __global__ void __launch_bounds__(256)
 mpq_outlier_add_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
-  const int tpr = blockDim.x >> 4;
-  const int row = blockIdx.x * 16 + threadIdx.x / tpr;
-  const int oq = threadIdx.x % tpr;
-  if (row >= b.N) return;
-  const int32_t rp0 = b.rowptr[row], rp1 = b.rowptr[row + 1];
-  for (int32_t e = rp0 + oq; e < rp1; e += tpr) {
-    const uint32_t word = b.outl[e];
+  const int orow = threadIdx.x >> 4, oq = threadIdx.x & 15;
+  const int row = blockIdx.x * 16 + orow;
+  if (row >= b.N || b.orec_bytes == 0) return;
+  const uint32_t* rec = (const uint32_t*)(b.otile + (size_t)blockIdx.x * b.orec_bytes);
+  const uint32_t* words = rec + MPQ_OTILE_HEAD / 4;
+  const int32_t rp0 = (int32_t)rec[orow], rp1 = (int32_t)rec[orow + 1];
+  for (int32_t e = rp0 + oq; e < rp1; e += 16) {
+    const uint32_t word = words[e];
     uint16_t* at = Wout + (size_t)row * b.K + (word & 0xFFFFu);
     const half_t s = bits_to_half(*at) + bits_to_half((uint16_t)(word >> 16));
     *at = half_to_bits(s);
@@ -433,24 +425,29 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   d->codes4 = (const uint4*)(p + h->off_codes4);
   d->meta1 = (const uint16_t*)(p + h->off_meta1);
   d->meta2 = (const uint32_t*)(p + h->off_meta2);
-  d->rowptr = (const int32_t*)(p + h->off_rowptr);
-  d->outl = (const uint32_t*)(p + h->off_outl);
+  d->otile = p + h->off_otile;
+  d->orec_bytes = h->ocap > 0 ? (int32_t)(MPQ_OTILE_HEAD + 4 * h->ocap) : 0;
   d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->n2 = h->n2;
   d->U2 = h->U2; d->U4 = h->U4; d->B2 = h->B2; d->B4 = h->B4; d->T = h->T;
   d->nnz = h->nnz;
+  d->dbg = 0;
   return MPQ_OK;
 }
 
 // Bytes of the `stage` array a batch of M rows needs (unit tables, the tile's meta words, activations).
 size_t stage_bytes(const MpqHeader& h, int M) {
-  return 32ull * (h.B2 + h.B4) + 32ull * h.G + 64ull * h.S + (size_t)M * (2ull * h.K + 16);
+  const size_t orec = h.ocap > 0 ? MPQ_OTILE_HEAD + 4 * h.ocap : 0;
+  return 32ull * (h.B2 + h.B4) + 32ull * h.G + 64ull * h.S + orec + (size_t)M * (2ull * h.K + 16);
 }
 
 int g_ring_depth = 0;  // 0 = automatic
+int g_dbg = 0;
 
 template <int NT, int PD, int STB>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, STB>), dim3(h.T), dim3(256), 0, s, d, X, Y, M);
+  DevBlob dd = d;
+  dd.dbg = g_dbg;
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, STB>), dim3(h.T), dim3(256), 0, s, dd, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
@@ -460,11 +457,11 @@ template <int NT>
 mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   const size_t need = stage_bytes(h, M);
   const int pd = g_ring_depth;
-  if (need <= 11520) {
-    if (pd == 2) return launch_mm<NT, 2, 11520>(h, d, X, Y, M, s);
-    if (pd == 4) return launch_mm<NT, 4, 11520>(h, d, X, Y, M, s);
-    if (pd == 5) return launch_mm<NT, 5, 11520>(h, d, X, Y, M, s);
-    return launch_mm<NT, 3, 11520>(h, d, X, Y, M, s);
+  if (need <= 13312) {
+    if (pd == 2) return launch_mm<NT, 2, 13312>(h, d, X, Y, M, s);
+    if (pd == 4) return launch_mm<NT, 4, 13312>(h, d, X, Y, M, s);
+    if (pd == 5) return launch_mm<NT, 5, 13312>(h, d, X, Y, M, s);
+    return launch_mm<NT, 3, 13312>(h, d, X, Y, M, s);
   }
   if (need <= 24 * 1024) return launch_mm<NT, 4, 24 * 1024>(h, d, X, Y, M, s);
   if (need <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024>(h, d, X, Y, M, s);
@@ -497,6 +494,7 @@ extern "C" {
 // key 0: ring depth (code blocks in flight per wave) for the smallest LDS class, 0 = automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
+  if (key == 1) g_dbg = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,

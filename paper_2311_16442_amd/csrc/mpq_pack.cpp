@@ -21,8 +21,9 @@ bool desc_ok(const mpq_desc* d) {
 }
 
 // Fills every derived field of the header from the shape, the number of 4-bit groups and nnz.
-mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, MpqHeader* h) {
+mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHeader* h) {
   if (!desc_ok(d) || nnz < 0 || n4 < 0 || n4 > d->K / d->g1) return MPQ_ERR_SHAPE;
+  if (ocap < 0 || ocap % 32 != 0 || ocap > (int64_t)MPQ_TILE_ROWS * d->K + 32) return MPQ_ERR_SHAPE;
   if (d->g1 != 64 && d->g1 != 128) return MPQ_ERR_UNSUPPORTED;  // a unit must not straddle groups
   if (d->g2_axis != 0) return MPQ_ERR_UNSUPPORTED;
   memset(h, 0, sizeof(*h));
@@ -46,10 +47,25 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, MpqHeader* h) {
   h->off_codes4 = off; off = align_up(off + (uint64_t)h->T * h->B4 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
   h->off_meta1 = off; off = align_up(off + (uint64_t)h->T * h->G * MPQ_TILE_ROWS * 2, MPQ_SECTION_ALIGN);
   h->off_meta2 = off; off = align_up(off + (uint64_t)h->T * h->S * MPQ_TILE_ROWS * 4, MPQ_SECTION_ALIGN);
-  h->off_rowptr = off; off = align_up(off + 4ull * ((uint64_t)h->T * MPQ_TILE_ROWS + 1), MPQ_SECTION_ALIGN);
-  h->off_outl = off; off = align_up(off + 4ull * (uint64_t)nnz, MPQ_SECTION_ALIGN);
+  h->ocap = (uint64_t)ocap;
+  h->off_otile = off; off = align_up(off + (uint64_t)h->T * (MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap), MPQ_SECTION_ALIGN);
   h->total_bytes = off;
   return MPQ_OK;
+}
+
+// Largest number of outliers in any 16-row tile, rounded up to a multiple of 32; -1 if row_ptr is
+// not a monotone sequence starting at 0.
+int64_t tile_capacity(const mpq_desc* d, const int32_t* row_ptr) {
+  if (row_ptr[0] != 0) return -1;
+  for (int64_t n = 0; n < d->N; ++n)
+    if (row_ptr[n + 1] < row_ptr[n]) return -1;
+  int64_t cap = 0;
+  for (int64_t n0 = 0; n0 < d->N; n0 += MPQ_TILE_ROWS) {
+    const int64_t n1 = n0 + MPQ_TILE_ROWS < d->N ? n0 + MPQ_TILE_ROWS : d->N;
+    const int64_t c = (int64_t)row_ptr[n1] - row_ptr[n0];
+    if (c > cap) cap = c;
+  }
+  return (cap + 31) / 32 * 32;
 }
 
 int32_t count4(const mpq_desc* d, const uint8_t* is4) {
@@ -69,7 +85,7 @@ mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out) {
   if (h.magic != MPQ_MAGIC || h.version != MPQ_VERSION) return MPQ_ERR_BLOB;
   mpq_desc d = {h.N, h.K, h.g1, h.g2, h.g2_axis};
   if (!desc_ok(&d)) return MPQ_ERR_BLOB;
-  if (plan(&d, h.n4, h.nnz, &want) != MPQ_OK) return MPQ_ERR_BLOB;
+  if (plan(&d, h.n4, h.nnz, (int64_t)h.ocap, &want) != MPQ_OK) return MPQ_ERR_BLOB;
   if (memcmp(&h, &want, sizeof(h)) != 0) return MPQ_ERR_BLOB;
   *out = h;
   return MPQ_OK;
@@ -118,11 +134,13 @@ double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns
   return -1.0;
 }
 
-mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, int64_t nnz, size_t* bytes) {
-  if (!d || !is4 || !bytes) return MPQ_ERR_NULL;
+mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, const int32_t* row_ptr, size_t* bytes) {
+  if (!d || !is4 || !row_ptr || !bytes) return MPQ_ERR_NULL;
   if (!desc_ok(d)) return MPQ_ERR_SHAPE;
+  const int64_t ocap = tile_capacity(d, row_ptr);
+  if (ocap < 0) return MPQ_ERR_CSR;
   MpqHeader h;
-  mpq_status st = plan(d, count4(d, is4), nnz, &h);
+  mpq_status st = plan(d, count4(d, is4), row_ptr[d->N], ocap, &h);
   if (st != MPQ_OK) return st;
   *bytes = (size_t)h.total_bytes;
   return MPQ_OK;
@@ -135,13 +153,12 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   const int64_t N = d->N, K = d->K, g1 = d->g1;
   const int64_t G = K / g1;
   // ---- validation of the logical matrix, before anything is written
-  if (w->row_ptr[0] != 0) return MPQ_ERR_CSR;
-  for (int64_t n = 0; n < N; ++n)
-    if (w->row_ptr[n + 1] < w->row_ptr[n]) return MPQ_ERR_CSR;
+  const int64_t ocap = tile_capacity(d, w->row_ptr);
+  if (ocap < 0) return MPQ_ERR_CSR;
   const int64_t nnz = w->row_ptr[N];
   if (nnz > 0 && (!w->col || !w->val)) return MPQ_ERR_NULL;
   MpqHeader h;
-  mpq_status st = plan(d, count4(d, w->is4), nnz, &h);
+  mpq_status st = plan(d, count4(d, w->is4), nnz, ocap, &h);
   if (st != MPQ_OK) return st;
   if (bytes < h.total_bytes) return MPQ_ERR_SIZE;
   for (int64_t n = 0; n < N; ++n) {
@@ -214,10 +231,20 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
       meta2[(t * h.S + s) * MPQ_TILE_ROWS + i] =
           (uint32_t)w->s2[n * h.S + s] | ((uint32_t)w->z2[n * h.S + s] << 16);
   }
-  int32_t* rp = (int32_t*)(blob + h.off_rowptr);
-  for (int64_t n = 0; n <= (int64_t)h.T * MPQ_TILE_ROWS; ++n) rp[n] = n <= N ? w->row_ptr[n] : (int32_t)nnz;
-  uint32_t* outl = (uint32_t*)(blob + h.off_outl);
-  for (int64_t e = 0; e < nnz; ++e) outl[e] = (uint32_t)w->col[e] | ((uint32_t)w->val[e] << 16);
+  const uint64_t rec_bytes = MPQ_OTILE_HEAD + 4ull * h.ocap;
+  for (int64_t t = 0; t < h.T; ++t) {
+    uint32_t* rec = (uint32_t*)(blob + h.off_otile + (uint64_t)t * rec_bytes);
+    const int64_t n0 = t * MPQ_TILE_ROWS;
+    const int32_t base = w->row_ptr[n0];
+    for (int r = 0; r <= MPQ_TILE_ROWS; ++r) {
+      const int64_t n = n0 + r < N ? n0 + r : N;
+      rec[r] = (uint32_t)(w->row_ptr[n] - base);
+    }
+    const int64_t nend = n0 + MPQ_TILE_ROWS < N ? n0 + MPQ_TILE_ROWS : N;
+    uint32_t* words = rec + MPQ_OTILE_HEAD / 4;
+    for (int32_t e = base; e < w->row_ptr[nend]; ++e)
+      words[e - base] = (uint32_t)w->col[e] | ((uint32_t)w->val[e] << 16);
+  }
   return MPQ_OK;
 }
 

@@ -14,8 +14,9 @@ def read_header(blob: np.ndarray) -> dict:
     h = dict(zip(names, vals))
     h["nnz"] = struct.unpack_from("<q", raw, 64)[0]
     offs = struct.unpack_from("<9Q", raw, 72)
-    for n, v in zip(["unit2", "unit4", "codes2", "codes4", "meta1", "meta2", "rowptr", "outl", "total"], offs):
+    for n, v in zip(["unit2", "unit4", "codes2", "codes4", "meta1", "meta2", "otile"], offs[:7]):
         h["off_" + n] = v
+    h["ocap"], h["off_total"] = offs[7], offs[8]
     return h
 
 
@@ -74,8 +75,28 @@ def unpack(blob: np.ndarray) -> dict:
     m2 = blob[h["off_meta2"]: h["off_meta2"] + T * S * TILE * 4].view(np.uint32).reshape(T, S, TILE)
     s2 = (m2 & 0xFFFF).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
     z2 = (m2 >> 16).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
-    rp = blob[h["off_rowptr"]: h["off_rowptr"] + 4 * (T * TILE + 1)].view(np.int32)
-    outl = blob[h["off_outl"]: h["off_outl"] + 4 * h["nnz"]].view(np.uint32)
+    # outliers: one record per tile = 32 words of row starts (17 used) + ocap words
+    rec_words = 32 + h["ocap"]
+    recs = blob[h["off_otile"]: h["off_otile"] + 4 * T * rec_words].view(np.uint32).reshape(T, rec_words)
+    assert h["ocap"] % 32 == 0
+    row_ptr = [0]
+    words = []
+    fullest = 0
+    for t in range(T):
+        start = recs[t, :17].astype(np.int64)
+        assert start[0] == 0 and np.all(np.diff(start) >= 0) and not recs[t, 17:32].any()
+        cnt = int(start[16])
+        fullest = max(fullest, cnt)
+        assert cnt <= h["ocap"] and not recs[t, 32 + cnt:].any()        # padding words are zero
+        for r in range(TILE):
+            if t * TILE + r < N:
+                row_ptr.append(row_ptr[-1] + int(start[r + 1] - start[r]))
+            else:
+                assert start[r + 1] == start[r]                         # rows beyond N are empty
+        words.append(recs[t, 32: 32 + cnt])
+    assert h["ocap"] == -(-fullest // 32) * 32
+    outl = np.concatenate(words) if words else np.zeros(0, np.uint32)
+    assert outl.size == h["nnz"]
     return dict(h=h, is4=is4, codes=codes[:N], s_int=s_int[:N], z1=z1[:N], s2=s2[:N], z2=z2[:N],
-                row_ptr=rp[:N + 1].copy(), row_ptr_pad=rp[N:].copy(), col=(outl & 0xFFFF).astype(np.uint16),
+                row_ptr=np.array(row_ptr, dtype=np.int32), col=(outl & 0xFFFF).astype(np.uint16),
                 val=(outl >> 16).astype(np.uint16), pad_rows_codes=codes[N:], pad_s=s_int[N:])
