@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--detail", action="store_true", help="also time every shape alone (stderr)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="do one 1 GiB device-to-device copy first (reference for FETCH_SIZE / WRITE_SIZE runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1")
@@ -84,6 +86,15 @@ def main():
     torch.cuda.synchronize()
     log(f"[setup] {copies} layer copies resident: {copies * total_copy_bytes / 1e9:.2f} GB; "
         f"algorithmic bytes per step {step_bytes / 1e6:.3f} MB")
+
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"[calibration] device copy of {src.numel() * 4} bytes done")
+        del src, dst
 
     stream = torch.cuda.Stream()
 
@@ -132,7 +143,7 @@ def main():
     achieved = (step_bytes / len(mats)) / (avg_launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "mpq_gemv_kernel<64>", "avg_launch_us": round(avg_launch_us, 3),
+                "kernel": "mpq_mm_kernel<1, PD, STB> (every GEMV of the step)", "avg_launch_us": round(avg_launch_us, 3),
                 "bytes_per_launch": round(step_bytes / len(mats))}
     traffic_file = os.path.join(ROOT, "profiles", "gemv_llama2_7b_traffic.json")
     if os.path.exists(traffic_file):

@@ -1,0 +1,114 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times: the
+Llama2-7B, Llama3-8B and Llama2-70B layer shapes of the benchmark configurations.  Products are
+checked on every row against the oracle where that takes seconds, else on sampled rows (the
+oracle computes any row on its own); dequantized weights are checked bit for bit on sampled rows."""
+import numpy as np
+import pytest
+
+import mpq_synth as synth
+import oracle
+import paper_2311_16442_amd as mpq
+from gpu_util import Guarded, rel_err, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    return t
+
+
+def sample_rows(N, count, seed):
+    rng = np.random.default_rng(seed)
+    rows = set(range(16)) | set(range(N - 16, N)) | set(int(r) for r in rng.integers(0, N, size=count))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def sub_matrix(lg, rows):
+    """Oracle matrix holding only `rows` of the logical matrix (rows decode independently)."""
+    s = lg.spec
+    counts = (lg.row_ptr[rows + 1] - lg.row_ptr[rows]).astype(np.int64)
+    rp = np.zeros(rows.size + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(counts)
+    idx = np.concatenate([np.arange(lg.row_ptr[r], lg.row_ptr[r + 1]) for r in rows]) if rows.size else np.zeros(0, int)
+    idx = idx.astype(np.int64)
+    return oracle.Matrix(rows.size, s.K, s.g1, s.g2, lg.is4, lg.codes[rows], lg.s_int[rows], lg.z1[rows],
+                         lg.s2[rows], lg.z2[rows], rp, lg.col[idx], lg.val[idx])
+
+
+def check_products(torch, lg, pk, blob, Ms, all_rows):
+    s = lg.spec
+    rows = np.arange(s.N) if all_rows else sample_rows(s.N, 96, s.seed)
+    om = oracle.Matrix.from_logical(lg) if all_rows else sub_matrix(lg, rows)
+    for M in Ms:
+        X = synth.make_x(s.seed + M, M, s.K)
+        Y = Guarded(torch, M * s.N)
+        if M == 1:
+            mpq.gemv(pk.header, blob, to_dev(torch, X[0].view(np.int16)), Y.view)
+        else:
+            mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+        got = Y.check_and_get().reshape(M, s.N)
+        ref = om.gemm(X, threads=8)
+        # the floor of the error measure uses the rms over the rows that were checked
+        e_floor, e_max = rel_err(got[:, rows], ref)
+        print(f"{s.name} {s.N}x{s.K} M={M}: rows checked {rows.size}, err {e_floor:.2e}", flush=True)
+        assert e_floor <= TOL, (s.name, M, e_floor, e_max)
+
+
+def check_dequant_rows(torch, lg, pk, blob):
+    s = lg.spec
+    if s.N * s.K > 250e6:      # keep the fp16 output below 500 MB
+        return
+    rows = sample_rows(s.N, 48, s.seed + 7)
+    out = Guarded(torch, s.N * s.K)
+    mpq.dequant(pk.header, blob, out.view, add_outliers=True)
+    torch.cuda.synchronize()
+    got = out.buf[128:128 + s.N * s.K].view(s.N, s.K)[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16)
+    host_head = out.buf[:128].cpu().numpy().view(np.uint16)
+    host_tail = out.buf[128 + s.N * s.K:].cpu().numpy().view(np.uint16)
+    assert np.all(host_head == 0x7B7B) and np.all(host_tail == 0x7B7B)
+    ref = sub_matrix(lg, rows).dequant(True)
+    assert np.array_equal(got, ref), s.name
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_llama2_7b_layer_every_row(torch, idx):
+    spec = synth.config_specs(1)[idx]
+    lg = synth.make_matrix(spec)
+    pk = mpq.pack_logical(lg)
+    blob = to_dev(torch, pk.blob)
+    check_products(torch, lg, pk, blob, [1], all_rows=True)
+    check_products(torch, lg, pk, blob, [4, 16, 32], all_rows=False)
+    check_dequant_rows(torch, lg, pk, blob)
+
+
+@pytest.mark.parametrize("f4,p_o", [(0.0, 0.0), (0.25, 0.015), (0.0, 0.015), (0.25, 0.0)])
+def test_llama2_7b_format_sweep_corners(torch, f4, p_o):
+    # corners of the sweep over the 4-bit fraction and the outlier fraction (configuration 2)
+    spec = synth.config_specs(2, f4=f4, p_o=p_o)[1]
+    lg = synth.make_matrix(spec)
+    pk = mpq.pack_logical(lg)
+    blob = to_dev(torch, pk.blob)
+    check_products(torch, lg, pk, blob, [1, 16], all_rows=True)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3, 4])
+def test_llama3_8b_shapes_group_128(torch, idx):
+    spec = synth.config_specs(3)[idx]
+    lg = synth.make_matrix(spec)
+    pk = mpq.pack_logical(lg)
+    blob = to_dev(torch, pk.blob)
+    check_products(torch, lg, pk, blob, [1], all_rows=spec.N * spec.K < 150e6)
+    check_dequant_rows(torch, lg, pk, blob)
+
+
+@pytest.mark.parametrize("idx", [0, 1, 3])
+def test_llama2_70b_shapes_sampled(torch, idx):
+    spec = synth.config_specs(4)[idx]
+    lg = synth.make_matrix(spec)
+    pk = mpq.pack_logical(lg)
+    blob = to_dev(torch, pk.blob)
+    check_products(torch, lg, pk, blob, [1, 8], all_rows=False)
