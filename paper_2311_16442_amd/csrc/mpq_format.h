@@ -10,25 +10,28 @@
 // - the operand order of the 16x16x32 MFMA, which the small-batch product uses directly and the
 // matrix-vector product reads equally well.
 //
-//   header    256 B                                      (MpqHeader)
-//   unit2     2 x uint32 [4*B2]  per 2-bit unit in stream order, ready for the kernels:
-//                             word 0 = byte offset of the unit's first activation in an fp16 row
-//                                      (2*k0), bit 31 set for a padding unit (then all else is 0)
-//                             word 1 = (stream_group * 32) | (super_group * 64) << 16, the byte
-//                                      offsets of the group's rows inside a tile of meta1 / meta2
-//   unit4     2 x uint32 [4*B4]  the same for 4-bit units
-//   codes2    T x B2 x 64 x 16 B    2-bit stream:  [tile][block][lane] 16-byte units
-//   codes4    T x B4 x 64 x 16 B    4-bit stream
-//   meta1     T x G x 16 x 2 B      (s_int | z1 << 8) per (tile, stream group, row); stream group
-//                                   order = all 2-bit groups in K order, then all 4-bit groups
-//   meta2     T x S x 16 x 4 B      (s2 | z2 << 16) per (tile, super-group, row)
-//   otile     T x (128 + 4*ocap) B  the outliers of each row tile as one self-contained record, so that
-//                                   a kernel can request it without first reading a row pointer:
-//                                     uint32 start[17] (then zeros up to 128 B): start[r] = index of the
-//                                       first word of row r of the tile, start[16] = number of words
-//                                     uint32 word[ocap]: col | val << 16   (Sec. 2.3: one 32-bit word per
-//                                       outlier, one 32-bit running count per row), rows in order
-//                                   ocap = the largest number of outliers in any tile, rounded up to 32
+//   header    256 B                       (MpqHeader)
+//   units     2 x uint32 [4*(B2+B4)]      per unit in stream order (2-bit units, then 4-bit units),
+//                                         ready for the kernels:
+//                 word 0 = byte offset of the unit's first activation in an fp16 row (2*k0),
+//                          bit 31 set for a padding unit (then everything else is 0)
+//                 word 1 = (stream_group * 32) | (super_group * 64) << 16: byte offsets of the
+//                          group's 16 rows inside the tile's meta1 / meta2 arrays
+//   tiles     T x tile_stride B           one self-contained record per 16-row tile, so that a
+//                                         workgroup finds everything it needs at one base address:
+//       side (side_bytes):
+//         meta1   G x 16 x 2 B    (s_int | z1 << 8) per (stream group, row); stream group order = all
+//                                 2-bit groups in K order, then all 4-bit groups
+//         meta2   S x 16 x 4 B    (s2 | z2 << 16) per (super-group, row)
+//         outl    128 + 4*ocap B  uint32 start[17] (then zeros up to 128 B): start[r] = index of the first
+//                                 word of row r of the tile, start[16] = number of words; then
+//                                 uint32 word[ocap] = col | val << 16 (Sec. 2.3: one 32-bit word per
+//                                 outlier, one 32-bit running count per row), rows in order;
+//                                 ocap = the largest number of outliers in any tile, rounded up to 32.
+//                                 A kernel can request a tile's outliers without first reading a
+//                                 row pointer: no dependent load.
+//       codes at codes_off (128-byte aligned): (B2 + B4) x 64 x 16 B, the 2-bit blocks then the 4-bit
+//                                 blocks of the tile, [block][lane] 16-byte units
 //
 // Bit positions inside a unit (4 little-endian dwords):
 //   2-bit: column k0 + kl (kl = 0..63) sits in dword (kl % 8) / 2, bits 16*(kl % 2) + 2*(kl / 8) ..+1
@@ -36,14 +39,14 @@
 // so that one mask applied to a dword isolates the codes of columns (2r, 2r+1) in the low and high
 // half-word, ready to be turned into a pair of fp16 values.
 //
-// Every section starts on a 256-byte boundary; padding bytes are zero.
+// Sections and tile records start on 256-byte boundaries; padding bytes are zero.
 #ifndef MPQ_FORMAT_H_
 #define MPQ_FORMAT_H_
 
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 4u
+#define MPQ_VERSION 5u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024
@@ -59,8 +62,12 @@ typedef struct {
   int32_t B2, B4;  /* blocks (4 units x 16 rows) per row tile in each stream */
   int32_t T;       /* row tiles */
   int64_t nnz;
-  uint64_t off_unit2, off_unit4, off_codes2, off_codes4, off_meta1, off_meta2, off_otile;
-  uint64_t ocap;   /* words per tile in the outlier records (multiple of 32) */
+  uint64_t off_units, off_tiles;
+  uint64_t tile_stride; /* bytes from one tile record to the next */
+  uint64_t side_bytes;  /* meta1 + meta2 + outlier record of a tile */
+  uint64_t codes_off;   /* offset of the code blocks inside a tile record */
+  uint64_t ocap;        /* words per tile in the outlier records (multiple of 32) */
+  uint64_t reserved0, reserved1;
   uint64_t total_bytes;
   uint8_t pad[256 - 4 * 16 - 8 - 8 * 8 - 8];
 } MpqHeader;

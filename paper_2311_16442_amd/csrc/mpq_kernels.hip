@@ -31,17 +31,13 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 struct DevBlob {
-  const uint2* unit2;
-  const uint2* unit4;
-  const uint4* codes2;
-  const uint4* codes4;
-  const uint16_t* meta1;
-  const uint32_t* meta2;
-  const unsigned char* otile;  // per-tile outlier records
-  int32_t N, K, G, S, n2, U2, U4, B2, B4, T;
-  int32_t orec_bytes;          // bytes of one outlier record (row-start table + words), 0 if no outliers
-  int64_t nnz;
-  int32_t dbg;  // tuning experiments only: bit 0 skips the decode/multiply, bit 1 skips the code-block loads
+  const unsigned char* tiles;  // first tile record
+  const unsigned char* units;  // unit table (2-bit units, then 4-bit units), 8 bytes per unit
+  uint32_t tile_stride;        // bytes between tile records
+  uint32_t side_bytes;         // meta1 | meta2 | outlier record at the head of a tile record
+  uint32_t codes_off;          // offset of the code blocks inside a tile record
+  uint32_t off_m2, off_ot;     // offsets of meta2 and of the outlier record inside the side part
+  int32_t N, K, G, S, B2, C, T;
 };
 
 __device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
@@ -80,26 +76,28 @@ __device__ __forceinline__ void wait_vm(int n) {
 // is read, which serialises the whole pipeline.  Values loaded this way must not be used before
 // the matching wait_vm().
 
-// 16 bytes per lane straight from global memory into LDS at lds + 16*lane (no register staging).
-__device__ __forceinline__ void dma16(const void* g, unsigned char* lds_wave_uniform) {
-  const uint32_t l = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)lds_wave_uniform);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(g) : "memory");
+// 16 bytes per lane straight from global memory into LDS (no register staging): lane l reads
+// gbase + voff(l) and writes LDS byte lds + 16*l.  gbase and lds are wave-uniform and live in
+// scalar registers, so the address arithmetic of the caller stays on the scalar unit.
+__device__ __forceinline__ void dma16(const unsigned char* gbase, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase)
+               : "memory");
 }
 
-// One dword per lane into a register, asynchronously.
-__device__ __forceinline__ uint32_t load_b32_async(const void* g) {
-  uint32_t r;
-  asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(g) : "memory");
-  return r;
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
 }
 
-// Copies `bytes` (a multiple of 16) to LDS with the waves of a 256-thread workgroup taking 1 KiB
-// pieces in turn.
-__device__ __forceinline__ void dma_region(const void* g, unsigned char* l, int bytes, int wv, int lane) {
-  for (int ch = wv; ch * 1024 < bytes; ch += 4) {
-    const int off = ch * 1024 + lane * 16;
-    if (off < bytes) dma16((const unsigned char*)g + off, l + ch * 1024);
+// Copies `bytes` (a multiple of 16) from gbase to LDS byte address lds; the four waves of the
+// workgroup take 1 KiB pieces in turn.  lane16 = 16 * lane.
+__device__ __forceinline__ void dma_linear(const unsigned char* gbase, uint32_t lds, uint32_t bytes, uint32_t wv,
+                                           uint32_t lane16) {
+  for (uint32_t off = wv * 1024u; off < bytes; off += 4096u) {
+    if (off + 1024u <= bytes) {
+      dma16(gbase + off, lane16, lds + off);
+    } else if (off + lane16 < bytes) {
+      dma16(gbase + off, lane16, lds + off);
+    }
   }
 }
 
@@ -204,82 +202,69 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   static_assert(PD >= NT && PD <= 8, "ring depth");
   __shared__ __align__(16) unsigned char ring[4 * PD * 1024];
   __shared__ __align__(16) unsigned char stage[STB];
-  constexpr int W = 4;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int i = lane & 15, j = lane >> 4;
-  const int C = b.B2 + b.B4;
-  const int tile = blockIdx.x;
-  // stage layout: unit tables | meta1 of the tile | meta2 of the tile | outlier record | activation rows
-  const int units_bytes = 32 * C, m1_bytes = 32 * b.G, m2_bytes = 64 * b.S;
-  const int rowbytes = 2 * b.K + 16;  // + 16: rows of a batch start in different LDS banks
-  unsigned char* units = stage;
-  unsigned char* m1s = units + units_bytes;
-  unsigned char* m2s = m1s + m1_bytes;
-  unsigned char* ots = m2s + m2_bytes;
-  unsigned char* xs = ots + b.orec_bytes;
+  constexpr uint32_t W = 4;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
+  const uint32_t C = b.C;
+  // stage layout: side part of the tile (meta1 | meta2 | outlier record) | unit table | activation rows
+  const uint32_t units_bytes = 32u * C;
+  const uint32_t rowbytes = 2u * b.K + 16u;  // + 16: rows of a batch start in different LDS banks
+  unsigned char* m1s = stage;
+  unsigned char* m2s = stage + b.off_m2;
+  unsigned char* ots = stage + b.off_ot;
+  unsigned char* units = stage + b.side_bytes;
+  unsigned char* xs = units + units_bytes;
   unsigned char* myring = ring + wv * (PD * 1024);
   const DecodeConsts kc = make_consts();
 
-  // outlier / output mapping: 16 consecutive lanes share a row; lane q handles batch column q % Mp
-  // and every (16/Mp)-th outlier of the row
-  const int orow = tid >> 4, oq = tid & 15;
-  int Mp = 1;
-  while (Mp < M && Mp < 16) Mp <<= 1;
-  const int om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
-
-  // ---- (1) all requests of the tile, oldest first: staged operands, then code blocks
-  dma_region(b.unit2, units, 32 * b.B2, wv, lane);
-  dma_region(b.unit4, units + 32 * b.B2, 32 * b.B4, wv, lane);
-  if (!(b.dbg & 8)) dma_region(b.meta1 + (size_t)tile * b.G * 16, m1s, m1_bytes, wv, lane);
-  dma_region(b.meta2 + (size_t)tile * b.S * 16, m2s, m2_bytes, wv, lane);
-  if (!(b.dbg & 16)) dma_region(b.otile + (size_t)tile * b.orec_bytes, ots, b.orec_bytes, wv, lane);
-  if (!(b.dbg & 4))
-    for (int m = 0; m < M; ++m) dma_region(X + (size_t)m * b.K, xs + (size_t)m * rowbytes, 2 * b.K, wv, lane);
-  const int nblk = wv < C ? (C - wv + W - 1) / W : 0;  // blocks of this wave
-  const int nb0 = nblk < PD ? nblk : PD;               // requested now
-  auto block_src = [&](int c) -> const uint4* {
-    return c < b.B2 ? b.codes2 + ((size_t)tile * b.B2 + c) * 64 + lane
-                    : b.codes4 + ((size_t)tile * b.B4 + (c - b.B2)) * 64 + lane;
-  };
+  // ---- (1) all requests of the tile, oldest first: staged operands, then this wave's code blocks
+  const unsigned char* tile = b.tiles + (size_t)blockIdx.x * b.tile_stride;
+  dma_linear(tile, lds_addr(stage), b.side_bytes, wv, lane16);
+  dma_linear(b.units, lds_addr(units), units_bytes, wv, lane16);
+  for (int m = 0; m < M; ++m)
+    dma_linear((const unsigned char*)(X + (size_t)m * b.K), lds_addr(xs) + m * rowbytes, 2u * b.K, wv, lane16);
+  const uint32_t nblk = wv < C ? (C - wv + W - 1) / W : 0;  // blocks of this wave
+  const uint32_t nb0 = nblk < PD ? nblk : PD;               // requested now
+  const unsigned char* codes = tile + b.codes_off;
+  const uint32_t ring0 = lds_addr(myring);
 #pragma unroll
-  for (int r = 0; r < PD; ++r)
-    if (r < nb0 && !(b.dbg & 2)) dma16(block_src(wv + r * W), myring + r * 1024);
+  for (uint32_t r = 0; r < PD; ++r)
+    if (r < nb0) dma16(codes + (wv + r * W) * 1024u, lane16, ring0 + r * 1024u);
   wait_vm(nb0);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
   // ---- (2) this wave's blocks, in order
-  const unsigned char* xrow0 = xs + (size_t)(i < M ? i : 0) * rowbytes;
-  const unsigned char* xrow1 = xs + (size_t)((NT > 1 && i + 16 < M) ? i + 16 : 0) * rowbytes;
+  const unsigned char* xrow0 = xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
+  const unsigned char* xrow1 = xs + ((NT > 1 && i + 16 < (uint32_t)M) ? i + 16 : 0u) * rowbytes;
+  const unsigned char* m1i = m1s + i * 2, *m2i = m2s + i * 4;
+  const unsigned char* unitj = units + j * 8;
+  const uint32_t ringl = ring0 + lane16;
   float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-  int slot = 0;
-  for (int it = 0; it < nblk; ++it) {
-    const int c = wv + it * W;
+  uint32_t slot = 0;
+  for (uint32_t it = 0, c = wv; it < nblk; ++it, c += W) {
     // Requests of this wave that are younger than block `it` (each freed slot is refilled at
     // once, so PD - 1 blocks follow until the stream runs dry): loads complete in order, hence
     // "at most that many outstanding" means block `it` has landed.
-    const int left = nblk - 1 - it;
-    if (left >= PD - 1) MPQ_VMCNT(PD - 1); else wait_vm(left);
+    const uint32_t left = nblk - 1 - it;
+    if (left >= PD - 1) MPQ_VMCNT(PD - 1); else wait_vm((int)left);
     uint4 q;
-    {
-      const uint32_t a =
-          (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)(myring + slot * 1024) + lane * 16;
-      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(a) : "memory");
-    }
-    if (it + PD < nblk && !(b.dbg & 2)) dma16(block_src(c + PD * W), myring + slot * 1024);
+    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory");
+    if (it + PD < nblk) dma16(codes + (c + PD * W) * 1024u, lane16, ring0 + slot * 1024u);
     slot = slot + 1 == PD ? 0 : slot + 1;
-    if (b.dbg & 1) { acc0[0] += (float)q.x; continue; }
 
-    const uint2 ue = *(const uint2*)(units + (4 * c + j) * 8);
-    const uint32_t m1 = *(const uint16_t*)(m1s + (ue.y & 0xFFFFu) + i * 2);
-    const uint32_t m2 = *(const uint32_t*)(m2s + (ue.y >> 16) + i * 4);
+    uint2 ue = *(const uint2*)(unitj + c * 32u);
+    const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));
+    const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));
     half_t s1 = scale_dequant(m1 & 0xFFu, m2);
-    if (ue.x & MPQ_PAD_UNIT) s1 = (half_t)0.0f;
+    if (c + 1 == (uint32_t)b.B2 || c + 1 == C) {  // only the last block of a stream can hold padding units
+      if (ue.x & MPQ_PAD_UNIT) s1 = (half_t)0.0f;
+      ue.x &= ~MPQ_PAD_UNIT;
+    }
     const half2_t s1p = {s1, s1};
     const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
-    const uint32_t xo = ue.x & 0x7FFFFFFFu;
-    const unsigned char* xb0 = xrow0 + xo;
-    const unsigned char* xb1 = xrow1 + xo;
+    const unsigned char* xb0 = xrow0 + ue.x;
+    const unsigned char* xb1 = xrow1 + ue.x;
     const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
 #define MPQ_MM_STEP(TWO, P)                                                                           \
   {                                                                                                   \
@@ -293,7 +278,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
                                                     __builtin_bit_cast(half8_t, bv1), acc1, 0, 0, 0); \
     }                                                                                                 \
   }
-    if (c < b.B2) {
+    if (c < (uint32_t)b.B2) {
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
       MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
       MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
@@ -309,40 +294,45 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   *(float4_t*)(red + i * 16 + 4 * j) = acc0;
   if (NT > 1) *(float4_t*)(red + 256 + i * 16 + 4 * j) = acc1;
 
-  // ---- (4) outliers of row `orow` for batch column om (and om + 16): sum val * X[m][col], all
-  //      operands already in LDS (Sec. 4.3, fused: no second kernel, no second trip to memory)
+  // ---- (4) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory): 16 consecutive
+  //      lanes share row `orow`; lane q takes batch column q % Mp (and + 16) and every (16/Mp)-th
+  //      word of the row; all operands are already in LDS
+  const uint32_t orow = tid >> 4, oq = tid & 15u;
+  uint32_t Mp = 1;
+  while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
+  const uint32_t om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
   float oa0 = 0.f, oa1 = 0.f;
-  if (b.orec_bytes > 0) {
+  {
     const uint32_t* ostart = (const uint32_t*)ots;
     const uint32_t* owords = (const uint32_t*)(ots + MPQ_OTILE_HEAD);
-    const int32_t rp0 = (int32_t)ostart[orow], rp1 = (int32_t)ostart[orow + 1];
-    const unsigned char* xo0 = xs + (size_t)(om < M ? om : 0) * rowbytes;
-    const unsigned char* xo1 = xs + (size_t)((NT > 1 && om + 16 < M) ? om + 16 : 0) * rowbytes;
-    auto use = [&](uint32_t word) {
+    const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
+    const unsigned char* xo0 = xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
+    const unsigned char* xo1 = xs + ((NT > 1 && om + 16 < (uint32_t)M) ? om + 16 : 0u) * rowbytes;
+    for (uint32_t e = rp0 + oes; e < rp1; e += ostride) {
+      const uint32_t word = owords[e];
       const uint32_t off = (word & 0xFFFFu) * 2u;
       const float v = (float)bits_to_half((uint16_t)(word >> 16));
       oa0 += v * (float)*(const half_t*)(xo0 + off);
       if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
-    };
-    for (int32_t e = rp0 + oes; e < rp1; e += ostride) use(owords[e]);
-    for (int off = Mp; off < 16; off <<= 1) {
+    }
+    for (uint32_t off = Mp; off < 16; off <<= 1) {
       oa0 += __shfl_xor(oa0, off);
       if (NT > 1) oa1 += __shfl_xor(oa1, off);
     }
   }
   __syncthreads();
   {
-    const int row = tile * 16 + orow;
+    const uint32_t row = blockIdx.x * 16 + orow;
     float t0 = oa0, t1 = oa1;
 #pragma unroll
-    for (int w2 = 0; w2 < W; ++w2) {
+    for (uint32_t w2 = 0; w2 < W; ++w2) {
       const float* r2 = (const float*)(ring + w2 * (PD * 1024));
       t0 += r2[oq * 16 + orow];
       if (NT > 1) t1 += r2[256 + oq * 16 + orow];
     }
-    if (row < b.N) {
-      if (oq < M) Y[(size_t)oq * b.N + row] = half_to_bits((half_t)t0);
-      if (NT > 1 && oq + 16 < M) Y[(size_t)(oq + 16) * b.N + row] = half_to_bits((half_t)t1);
+    if (row < (uint32_t)b.N) {
+      if (oq < (uint32_t)M) Y[(size_t)oq * b.N + row] = half_to_bits((half_t)t0);
+      if (NT > 1 && oq + 16 < (uint32_t)M) Y[(size_t)(oq + 16) * b.N + row] = half_to_bits((half_t)t1);
     }
   }
 }
@@ -354,24 +344,22 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6, W = blockDim.x >> 6;
   const int i = lane & 15, j = lane >> 4;
-  const int C = b.B2 + b.B4;
-  const int tile = blockIdx.x;
-  const int row = tile * 16 + i;
+  const int row = blockIdx.x * 16 + i;
+  const unsigned char* tile = b.tiles + (size_t)blockIdx.x * b.tile_stride;
+  const uint2* units = (const uint2*)b.units;
   const DecodeConsts kc = make_consts();
-  for (int c = wv; c < C; c += W) {
-    const bool two = c < b.B2;
-    const uint4 q = two ? b.codes2[((size_t)tile * b.B2 + c) * 64 + lane]
-                        : b.codes4[((size_t)tile * b.B4 + (c - b.B2)) * 64 + lane];
-    const uint2 ue = two ? b.unit2[4 * c + j] : b.unit4[4 * (c - b.B2) + j];
+  for (int c = wv; c < b.C; c += W) {
+    const uint4 q = ((const uint4*)(tile + b.codes_off))[c * 64 + lane];
+    const uint2 ue = units[4 * c + j];
     if ((ue.x & MPQ_PAD_UNIT) || row >= b.N) continue;
-    const uint32_t m1 = b.meta1[(size_t)tile * b.G * 16 + (ue.y & 0xFFFFu) / 2 + i];
-    const uint32_t m2 = b.meta2[(size_t)tile * b.S * 16 + (ue.y >> 16) / 4 + i];
+    const uint32_t m1 = *(const uint16_t*)(tile + (ue.y & 0xFFFFu) + i * 2);
+    const uint32_t m2 = *(const uint32_t*)(tile + b.off_m2 + (ue.y >> 16) + i * 4);
     const half_t s1 = scale_dequant(m1 & 0xFFu, m2);
     const half2_t s1p = {s1, s1};
     const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));
     uint4* dst = (uint4*)(Wout + (size_t)row * b.K + ue.x / 2);
     const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-    if (two) {
+    if (c < b.B2) {
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
       dst[0] = decode_step<true, 0>(lo, hi, s1p, zb, kc);
       dst[1] = decode_step<true, 1>(lo, hi, s1p, zb, kc);
@@ -397,8 +385,8 @@ __global__ void __launch_bounds__(256)
 mpq_outlier_add_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const int orow = threadIdx.x >> 4, oq = threadIdx.x & 15;
   const int row = blockIdx.x * 16 + orow;
-  if (row >= b.N || b.orec_bytes == 0) return;
-  const uint32_t* rec = (const uint32_t*)(b.otile + (size_t)blockIdx.x * b.orec_bytes);
+  if (row >= b.N) return;
+  const uint32_t* rec = (const uint32_t*)(b.tiles + (size_t)blockIdx.x * b.tile_stride + b.off_ot);
   const uint32_t* words = rec + MPQ_OTILE_HEAD / 4;
   const int32_t rp0 = (int32_t)rec[orow], rp1 = (int32_t)rec[orow + 1];
   for (int32_t e = rp0 + oq; e < rp1; e += 16) {
@@ -419,35 +407,28 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   if (st != MPQ_OK) return st;
   if (((uintptr_t)blob_dev & 15u) != 0) return MPQ_ERR_ALIGN;
   const unsigned char* p = (const unsigned char*)blob_dev;
-  d->unit2 = (const uint2*)(p + h->off_unit2);
-  d->unit4 = (const uint2*)(p + h->off_unit4);
-  d->codes2 = (const uint4*)(p + h->off_codes2);
-  d->codes4 = (const uint4*)(p + h->off_codes4);
-  d->meta1 = (const uint16_t*)(p + h->off_meta1);
-  d->meta2 = (const uint32_t*)(p + h->off_meta2);
-  d->otile = p + h->off_otile;
-  d->orec_bytes = h->ocap > 0 ? (int32_t)(MPQ_OTILE_HEAD + 4 * h->ocap) : 0;
-  d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->n2 = h->n2;
-  d->U2 = h->U2; d->U4 = h->U4; d->B2 = h->B2; d->B4 = h->B4; d->T = h->T;
-  d->nnz = h->nnz;
-  d->dbg = 0;
+  d->tiles = p + h->off_tiles;
+  d->units = p + h->off_units;
+  d->tile_stride = (uint32_t)h->tile_stride;
+  d->side_bytes = (uint32_t)h->side_bytes;
+  d->codes_off = (uint32_t)h->codes_off;
+  d->off_m2 = 32u * (uint32_t)h->G;
+  d->off_ot = d->off_m2 + 64u * (uint32_t)h->S;
+  d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->B2 = h->B2; d->C = h->B2 + h->B4; d->T = h->T;
+  if (h->tile_stride > 0xFFFFFFFFull) return MPQ_ERR_UNSUPPORTED;
   return MPQ_OK;
 }
 
 // Bytes of the `stage` array a batch of M rows needs (unit tables, the tile's meta words, activations).
 size_t stage_bytes(const MpqHeader& h, int M) {
-  const size_t orec = h.ocap > 0 ? MPQ_OTILE_HEAD + 4 * h.ocap : 0;
-  return 32ull * (h.B2 + h.B4) + 32ull * h.G + 64ull * h.S + orec + (size_t)M * (2ull * h.K + 16);
+  return h.side_bytes + 32ull * (h.B2 + h.B4) + (size_t)M * (2ull * h.K + 16);
 }
 
 int g_ring_depth = 0;  // 0 = automatic
-int g_dbg = 0;
 
 template <int NT, int PD, int STB>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  DevBlob dd = d;
-  dd.dbg = g_dbg;
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, STB>), dim3(h.T), dim3(256), 0, s, dd, X, Y, M);
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, STB>), dim3(h.T), dim3(256), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
@@ -494,7 +475,6 @@ extern "C" {
 // key 0: ring depth (code blocks in flight per wave) for the smallest LDS class, 0 = automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
-  if (key == 1) g_dbg = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,

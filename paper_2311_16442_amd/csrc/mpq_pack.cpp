@@ -40,15 +40,14 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
   h->B4 = (h->U4 + MPQ_UNITS_PER_BLOCK - 1) / MPQ_UNITS_PER_BLOCK;
   h->T = (d->N + MPQ_TILE_ROWS - 1) / MPQ_TILE_ROWS;
   h->nnz = nnz;
-  uint64_t off = MPQ_HEADER_BYTES;
-  h->off_unit2 = off; off = align_up(off + 8ull * 4 * h->B2, MPQ_SECTION_ALIGN);
-  h->off_unit4 = off; off = align_up(off + 8ull * 4 * h->B4, MPQ_SECTION_ALIGN);
-  h->off_codes2 = off; off = align_up(off + (uint64_t)h->T * h->B2 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
-  h->off_codes4 = off; off = align_up(off + (uint64_t)h->T * h->B4 * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
-  h->off_meta1 = off; off = align_up(off + (uint64_t)h->T * h->G * MPQ_TILE_ROWS * 2, MPQ_SECTION_ALIGN);
-  h->off_meta2 = off; off = align_up(off + (uint64_t)h->T * h->S * MPQ_TILE_ROWS * 4, MPQ_SECTION_ALIGN);
+  const uint64_t C = (uint64_t)h->B2 + h->B4;
   h->ocap = (uint64_t)ocap;
-  h->off_otile = off; off = align_up(off + (uint64_t)h->T * (MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap), MPQ_SECTION_ALIGN);
+  h->side_bytes = 32ull * h->G + 64ull * h->S + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
+  h->codes_off = align_up(h->side_bytes, 128);
+  h->tile_stride = align_up(h->codes_off + C * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
+  uint64_t off = MPQ_HEADER_BYTES;
+  h->off_units = off; off = align_up(off + 8ull * 4 * C, MPQ_SECTION_ALIGN);
+  h->off_tiles = off; off = align_up(off + (uint64_t)h->T * h->tile_stride, MPQ_SECTION_ALIGN);
   h->total_bytes = off;
   return MPQ_OK;
 }
@@ -183,8 +182,8 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   for (int32_t g = 0; g < G; ++g) (w->is4[g] ? groups4 : groups2).push_back(g);
   for (size_t i = 0; i < groups2.size(); ++i) stream_index[groups2[i]] = (int32_t)i;
   for (size_t i = 0; i < groups4.size(); ++i) stream_index[groups4[i]] = (int32_t)(h.n2 + i);
-  uint32_t* unit2 = (uint32_t*)(blob + h.off_unit2);
-  uint32_t* unit4 = (uint32_t*)(blob + h.off_unit4);
+  uint32_t* unit2 = (uint32_t*)(blob + h.off_units);
+  uint32_t* unit4 = unit2 + 2 * 4 * h.B2;
   const int32_t upg2 = (int32_t)(g1 / 64), upg4 = (int32_t)(g1 / 32);
   std::vector<int64_t> k0_2(4 * h.B2, -1), k0_4(4 * h.B4, -1);
   for (int32_t u = 0; u < 4 * h.B2; ++u) {
@@ -203,37 +202,35 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     unit4[2 * u] = (uint32_t)(2 * k0);
     unit4[2 * u + 1] = (uint32_t)(stream_index[g] * 32) | ((uint32_t)((g / d->g2) * 64) << 16);
   }
-  uint32_t* codes2 = (uint32_t*)(blob + h.off_codes2);
-  uint32_t* codes4 = (uint32_t*)(blob + h.off_codes4);
-  uint16_t* meta1 = (uint16_t*)(blob + h.off_meta1);
-  uint32_t* meta2 = (uint32_t*)(blob + h.off_meta2);
   for (int64_t n = 0; n < N; ++n) {
     const int64_t t = n / MPQ_TILE_ROWS, i = n % MPQ_TILE_ROWS;
+    uint8_t* tile = blob + h.off_tiles + (uint64_t)t * h.tile_stride;
+    uint16_t* meta1 = (uint16_t*)tile;
+    uint32_t* meta2 = (uint32_t*)(tile + 32ull * G);
+    uint32_t* codes2 = (uint32_t*)(tile + h.codes_off);
+    uint32_t* codes4 = codes2 + (uint64_t)h.B2 * 256;
     const uint8_t* row = w->codes + n * K;
     for (int32_t u = 0; u < h.U2; ++u) {
       const int64_t k0 = k0_2[u];
       const int64_t b = u / 4, j = u % 4;
-      uint32_t* q = codes2 + (((t * h.B2 + b) * 64 + j * 16 + i) * 4);
+      uint32_t* q = codes2 + ((b * 64 + j * 16 + i) * 4);
       for (int kl = 0; kl < 64; ++kl)
         q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 2 * (kl / 8));
     }
     for (int32_t u = 0; u < h.U4; ++u) {
       const int64_t k0 = k0_4[u];
       const int64_t b = u / 4, j = u % 4;
-      uint32_t* q = codes4 + (((t * h.B4 + b) * 64 + j * 16 + i) * 4);
+      uint32_t* q = codes4 + ((b * 64 + j * 16 + i) * 4);
       for (int kl = 0; kl < 32; ++kl)
         q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 4 * (kl / 8));
     }
     for (int64_t g = 0; g < G; ++g)
-      meta1[(t * G + stream_index[g]) * MPQ_TILE_ROWS + i] =
-          (uint16_t)(w->s_int[n * G + g] | ((uint16_t)w->z1[n * G + g] << 8));
+      meta1[stream_index[g] * MPQ_TILE_ROWS + i] = (uint16_t)(w->s_int[n * G + g] | ((uint16_t)w->z1[n * G + g] << 8));
     for (int64_t s = 0; s < h.S; ++s)
-      meta2[(t * h.S + s) * MPQ_TILE_ROWS + i] =
-          (uint32_t)w->s2[n * h.S + s] | ((uint32_t)w->z2[n * h.S + s] << 16);
+      meta2[s * MPQ_TILE_ROWS + i] = (uint32_t)w->s2[n * h.S + s] | ((uint32_t)w->z2[n * h.S + s] << 16);
   }
-  const uint64_t rec_bytes = MPQ_OTILE_HEAD + 4ull * h.ocap;
   for (int64_t t = 0; t < h.T; ++t) {
-    uint32_t* rec = (uint32_t*)(blob + h.off_otile + (uint64_t)t * rec_bytes);
+    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + 32ull * G + 64ull * h.S);
     const int64_t n0 = t * MPQ_TILE_ROWS;
     const int32_t base = w->row_ptr[n0];
     for (int r = 0; r <= MPQ_TILE_ROWS; ++r) {

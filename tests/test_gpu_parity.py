@@ -118,10 +118,14 @@ def test_padding_bytes_are_never_used(torch):
     h = up.read_header(pk.blob)
     poisoned = pk.blob.copy()
     # padding units of both streams (unit index >= U2 / U4) in every tile
-    for off, B, U in ((h["off_codes2"], h["B2"], h["U2"]), (h["off_codes4"], h["B4"], h["U4"])):
-        v = poisoned[off: off + h["T"] * B * 1024].reshape(h["T"], B, 4, 16, 16)
-        for u in range(U, 4 * B):
-            v[:, u // 4, u % 4] = 0xFF
+    C = h["B2"] + h["B4"]
+    tiles = poisoned[h["off_tiles"]: h["off_tiles"] + h["T"] * h["tile_stride"]].reshape(h["T"], h["tile_stride"])
+    npad = 0
+    for u in list(range(h["U2"], 4 * h["B2"])) + list(range(4 * h["B2"] + h["U4"], 4 * C)):
+        at = h["codes_off"] + (u // 4) * 1024 + (u % 4) * 256      # 16 rows x 16 bytes of unit u
+        tiles[:, at: at + 256] = 0xFF
+        npad += 1
+    assert npad > 0 and np.count_nonzero(poisoned != pk.blob) > 0
     blob = to_dev(torch, poisoned)
     X = synth.make_x(36, 1, 704)
     y = Guarded(torch, 40)

@@ -14,71 +14,60 @@ def read_header(blob: np.ndarray) -> dict:
     h = dict(zip(names, vals))
     h["nnz"] = struct.unpack_from("<q", raw, 64)[0]
     offs = struct.unpack_from("<9Q", raw, 72)
-    for n, v in zip(["unit2", "unit4", "codes2", "codes4", "meta1", "meta2", "otile"], offs[:7]):
-        h["off_" + n] = v
-    h["ocap"], h["off_total"] = offs[7], offs[8]
+    for n, v in zip(["off_units", "off_tiles", "tile_stride", "side_bytes", "codes_off", "ocap", "r0", "r1", "total"], offs):
+        h[n] = v
     return h
 
 
 def unpack(blob: np.ndarray) -> dict:
     h = read_header(blob)
     N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
-    unit2 = blob[h["off_unit2"]: h["off_unit2"] + 32 * h["B2"]].view(np.uint32).reshape(-1, 2)
-    unit4 = blob[h["off_unit4"]: h["off_unit4"] + 32 * h["B4"]].view(np.uint32).reshape(-1, 2)
-    c2 = blob[h["off_codes2"]: h["off_codes2"] + T * h["B2"] * 1024].view(np.uint32).reshape(T, h["B2"], 4, 16, 4)
-    c4 = blob[h["off_codes4"]: h["off_codes4"] + T * h["B4"] * 1024].view(np.uint32).reshape(T, h["B4"], 4, 16, 4)
+    B2, B4 = h["B2"], h["B4"]
+    C = B2 + B4
+    assert h["side_bytes"] == 32 * G + 64 * S + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
+    assert h["codes_off"] % 128 == 0 and h["codes_off"] >= h["side_bytes"] and h["tile_stride"] % 256 == 0
+    assert h["tile_stride"] >= h["codes_off"] + C * 1024 and h["total"] == blob.size
+    units = blob[h["off_units"]: h["off_units"] + 32 * C].view(np.uint32).reshape(-1, 2)
+    tiles = blob[h["off_tiles"]: h["off_tiles"] + T * h["tile_stride"]].reshape(T, h["tile_stride"])
+    # gaps inside a tile record are zero
+    assert not tiles[:, h["side_bytes"]: h["codes_off"]].any() and not tiles[:, h["codes_off"] + C * 1024:].any()
+    cw = np.ascontiguousarray(tiles[:, h["codes_off"]: h["codes_off"] + C * 1024]).view(np.uint32).reshape(T, C, 4, 16, 4)
     codes = np.zeros((T * TILE, K), dtype=np.uint8)
     is4 = np.full(G, 255, dtype=np.uint8)
     stream_groups = []                       # K-group of each stream group, 2-bit stream first
-    group_of_super = {}
-    for u in range(4 * h["B2"]):
-        e, e1 = int(unit2[u, 0]), int(unit2[u, 1])
+    for u in range(4 * C):
+        four = u >= 4 * B2
+        ul = u - 4 * B2 if four else u
+        e, e1 = int(units[u, 0]), int(units[u, 1])
+        words = cw[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
         if e & 0x80000000:
-            assert u >= h["U2"] and e == 0x80000000 and e1 == 0
-            assert not c2[:, u // 4, u % 4].any()        # padding units are zero
+            assert ul >= (h["U4"] if four else h["U2"]) and e == 0x80000000 and e1 == 0
+            assert not words.any()                        # padding units are zero
             continue
         k0 = e // 2
         g = k0 // g1
-        is4[g] = 0
+        is4[g] = 1 if four else 0
         assert (e1 >> 16) == (g // g2) * 64
         if k0 % g1 == 0:
             assert (e1 & 0xFFFF) == 32 * len(stream_groups)
             stream_groups.append(g)
-        words = c2[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
-        for kl in range(64):
-            d, sh = (kl % 8) // 2, 16 * (kl % 2) + 2 * (kl // 8)
-            codes[:, k0 + kl] = ((words[:, :, d] >> sh) & 3).reshape(-1)
-    for u in range(4 * h["B4"]):
-        e, e1 = int(unit4[u, 0]), int(unit4[u, 1])
-        if e & 0x80000000:
-            assert u >= h["U4"] and e == 0x80000000 and e1 == 0
-            assert not c4[:, u // 4, u % 4].any()
-            continue
-        k0 = e // 2
-        g = k0 // g1
-        is4[g] = 1
-        assert (e1 >> 16) == (g // g2) * 64
-        if k0 % g1 == 0:
-            assert (e1 & 0xFFFF) == 32 * len(stream_groups)
-            stream_groups.append(g)
-        words = c4[:, u // 4, u % 4]
-        for kl in range(32):
-            d, sh = (kl % 8) // 2, 16 * (kl % 2) + 4 * (kl // 8)
-            codes[:, k0 + kl] = ((words[:, :, d] >> sh) & 15).reshape(-1)
+        width, per = (4, 32) if four else (2, 64)
+        for kl in range(per):
+            d, sh = (kl % 8) // 2, 16 * (kl % 2) + width * (kl // 8)
+            codes[:, k0 + kl] = ((words[:, :, d] >> sh) & ((1 << width) - 1)).reshape(-1)
     assert len(stream_groups) == G and sorted(stream_groups) == list(range(G))
-    m1 = blob[h["off_meta1"]: h["off_meta1"] + T * G * TILE * 2].view(np.uint16).reshape(T, G, TILE)
+    m1 = np.ascontiguousarray(tiles[:, : 32 * G]).view(np.uint16).reshape(T, G, TILE)
     s_int = np.zeros((T * TILE, G), dtype=np.uint8)
     z1 = np.zeros((T * TILE, G), dtype=np.uint8)
     for sg, g in enumerate(stream_groups):
         s_int[:, g] = (m1[:, sg, :] & 0xFF).reshape(-1)
         z1[:, g] = (m1[:, sg, :] >> 8).reshape(-1)
-    m2 = blob[h["off_meta2"]: h["off_meta2"] + T * S * TILE * 4].view(np.uint32).reshape(T, S, TILE)
+    m2 = np.ascontiguousarray(tiles[:, 32 * G: 32 * G + 64 * S]).view(np.uint32).reshape(T, S, TILE)
     s2 = (m2 & 0xFFFF).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
     z2 = (m2 >> 16).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
     # outliers: one record per tile = 32 words of row starts (17 used) + ocap words
-    rec_words = 32 + h["ocap"]
-    recs = blob[h["off_otile"]: h["off_otile"] + 4 * T * rec_words].view(np.uint32).reshape(T, rec_words)
-    assert h["ocap"] % 32 == 0
+    o0 = 32 * G + 64 * S
+    recs = np.ascontiguousarray(tiles[:, o0: o0 + 128 + 4 * h["ocap"]]).view(np.uint32).reshape(T, 32 + h["ocap"])
     row_ptr = [0]
     words = []
     fullest = 0
