@@ -175,15 +175,23 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 
 // ------------------------------------------------------------------------------------ product
 //
-// Y[m][n] = sum_k X[m][k] W[n][k] + outliers, 1 <= M <= 16*NT, one 16-row tile per workgroup.
+// Y[m][n] = sum_k X[m][k] W[n][k] + outliers, 1 <= M <= 16*NT.  Persistent workgroups of four
+// waves: workgroup g handles the 16-row tiles g, g + grid, g + 2*grid, ...
 //
-// Data movement (the "asynchronous dequantization" of Sec. 5 on this hardware): everything the
-// tile needs is requested in the first instructions of the workgroup and lands in LDS without
-// passing through registers (global_load_lds_dwordx4): the activations, the unit tables, the
-// tile's (s_int, z1) and (s2, z2) words, the tile's outlier record, and PD code blocks per wave.  While the code blocks are
-// still in flight the waves meet once, and then every wave consumes its blocks in order, waiting
-// with s_waitcnt vmcnt(n) only for the block it needs next and refilling the freed slot.  The
-// second-order scale reconstruction of a block runs while the later blocks are still on their way.
+// Data movement (the "asynchronous dequantization" of Sec. 5 on this hardware).  Every global
+// load of the kernel is a direct global->LDS load (global_load_lds_dwordx4, no registers):
+//   - once per workgroup: the activations (one LDS row per batch row) and the unit tables;
+//   - once per tile, one tile ahead: the tile's side record (scale words + outlier record) into one
+//     of two buffers;
+//   - continuously: the code blocks.  Each wave owns PD ring slots of 1 KiB and walks its own
+//     sequence of blocks (its share of tile g, then of tile g + grid, ...).  A consumed slot is
+//     refilled at once with the next block of the sequence, across tile boundaries, so PD blocks per
+//     wave are in flight from the first instruction to the last.
+// Loads complete in order, so "block is there" is s_waitcnt vmcnt(number of younger requests of this
+// wave): PD - 1 in steady state.  The second-order scale of a block is reconstructed while the
+// later blocks are on their way.  The waits are written by hand (inline asm loads are invisible to
+// the compiler's own wait insertion, which cannot count requests issued in loops and would wait
+// for ALL outstanding loads before every LDS read).
 //
 // Compute: the decoded fp16 weights of a block are exactly the A operand of
 // v_mfma_f32_16x16x32_f16 (lane j*16+i holds 8 consecutive columns of row i), the activations of
@@ -192,80 +200,119 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // and the reduction over the four unit columns, so the vector ALU only decodes.  Batch columns
 // beyond M compute garbage that is never stored.
 //
-// LDS: `ring` (PD slots of 1 KiB per wave, reused for the cross-wave reduction at the end) and
-// `stage` are separate objects so that the compiler can tell reads of `stage` from the direct
-// loads into `ring`; ring slots are read with inline asm after an explicit wait.
-template <int NT, int PD, int STB>
+// Two barriers per tile: one before a tile's side record is read (every wave has waited for its
+// own share of that record), one before the four waves' accumulators are summed.
+//
+// PERSIST = false is the same kernel launched with one workgroup per tile (grid = T): one side
+// buffer, and the accumulators are parked in the wave's own idle ring slots, which saves 8 KiB of
+// LDS per workgroup and lets six workgroups share a compute unit.  It wins when the activations
+// are small (M = 1) because the vector ALU needs many waves per SIMD to stay busy; the persistent
+// form wins when staging the activations once per tile would dominate (M > 1).
+template <int NT, int PD, int LDSB, bool PERSIST>
 __global__ void __launch_bounds__(256)
 mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
 #pragma clang fp contract(off)
-  static_assert(PD >= NT && PD <= 8, "ring depth");
-  __shared__ __align__(16) unsigned char ring[4 * PD * 1024];
-  __shared__ __align__(16) unsigned char stage[STB];
+  static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT), "ring depth");
+  __shared__ __align__(16) unsigned char lds[LDSB];
   constexpr uint32_t W = 4;
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
-  const uint32_t C = b.C;
-  // stage layout: side part of the tile (meta1 | meta2 | outlier record) | unit table | activation rows
+  const uint32_t C = b.C, T = b.T, grid = gridDim.x;
+  // LDS layout: ring | reduction slots | side record x 2 | unit table | activation rows
   const uint32_t units_bytes = 32u * C;
   const uint32_t rowbytes = 2u * b.K + 16u;  // + 16: rows of a batch start in different LDS banks
-  unsigned char* m1s = stage;
-  unsigned char* m2s = stage + b.off_m2;
-  unsigned char* ots = stage + b.off_ot;
-  unsigned char* units = stage + b.side_bytes;
-  unsigned char* xs = units + units_bytes;
-  unsigned char* myring = ring + wv * (PD * 1024);
+  unsigned char* const ring = lds;
+  unsigned char* const side0 = lds + W * PD * 1024 + (PERSIST ? NT * 4096 : 0);
+  unsigned char* const units = side0 + (PERSIST ? 2 : 1) * b.side_bytes;
+  unsigned char* const xs = units + units_bytes;
   const DecodeConsts kc = make_consts();
 
-  // ---- (1) all requests of the tile, oldest first: staged operands, then this wave's code blocks
-  const unsigned char* tile = b.tiles + (size_t)blockIdx.x * b.tile_stride;
-  dma_linear(tile, lds_addr(stage), b.side_bytes, wv, lane16);
+  // ---- (1) requests of the first tile, oldest first: staged operands, then this wave's code blocks
+  const uint32_t tile0 = blockIdx.x;
+  const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
+  const size_t tilestep = (size_t)grid * b.tile_stride;
+  dma_linear(tileptr, lds_addr(side0), b.side_bytes, wv, lane16);
   dma_linear(b.units, lds_addr(units), units_bytes, wv, lane16);
   for (int m = 0; m < M; ++m)
     dma_linear((const unsigned char*)(X + (size_t)m * b.K), lds_addr(xs) + m * rowbytes, 2u * b.K, wv, lane16);
-  const uint32_t nblk = wv < C ? (C - wv + W - 1) / W : 0;  // blocks of this wave
-  const uint32_t nb0 = nblk < PD ? nblk : PD;               // requested now
-  const unsigned char* codes = tile + b.codes_off;
-  const uint32_t ring0 = lds_addr(myring);
+  // this wave's sequence of blocks: (tile0, wv), (tile0, wv + 4), ..., (tile0 + grid, wv), ...
+  const uint32_t ring0 = lds_addr(ring) + wv * (PD * 1024);
+  const unsigned char* rbase = tileptr + b.codes_off;  // code blocks of the tile being requested
+  uint32_t rtile = wv < C ? tile0 : T;                 // T = nothing left to request
+  uint32_t rc = wv;
+  uint32_t inflight = 0;
 #pragma unroll
-  for (uint32_t r = 0; r < PD; ++r)
-    if (r < nb0) dma16(codes + (wv + r * W) * 1024u, lane16, ring0 + r * 1024u);
-  wait_vm(nb0);  // the staged operands have landed; the code blocks may still be in flight
+  for (uint32_t r = 0; r < PD; ++r) {
+    if (rtile < T) {
+      dma16(rbase + rc * 1024u, lane16, ring0 + r * 1024u);
+      ++inflight;
+      rc += W;
+      if (rc >= C) { rc = wv; rtile += grid; rbase += tilestep; }
+    }
+  }
+  wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
-  // ---- (2) this wave's blocks, in order
   const unsigned char* xrow0 = xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
   const unsigned char* xrow1 = xs + ((NT > 1 && i + 16 < (uint32_t)M) ? i + 16 : 0u) * rowbytes;
-  const unsigned char* m1i = m1s + i * 2, *m2i = m2s + i * 4;
   const unsigned char* unitj = units + j * 8;
   const uint32_t ringl = ring0 + lane16;
-  float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-  uint32_t slot = 0;
-  for (uint32_t it = 0, c = wv; it < nblk; ++it, c += W) {
-    // Requests of this wave that are younger than block `it` (each freed slot is refilled at
-    // once, so PD - 1 blocks follow until the stream runs dry): loads complete in order, hence
-    // "at most that many outstanding" means block `it` has landed.
-    const uint32_t left = nblk - 1 - it;
-    if (left >= PD - 1) MPQ_VMCNT(PD - 1); else wait_vm((int)left);
-    uint4 q;
-    asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory");
-    if (it + PD < nblk) dma16(codes + (c + PD * W) * 1024u, lane16, ring0 + slot * 1024u);
-    slot = slot + 1 == PD ? 0 : slot + 1;
+  // outlier / output mapping: 16 consecutive lanes share row `orow`; lane q takes batch column
+  // q % Mp (and + 16) and every (16/Mp)-th word of the row
+  const uint32_t orow = tid >> 4, oq = tid & 15u;
+  uint32_t Mp = 1;
+  while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
+  const uint32_t om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
+  const unsigned char* xo0 = xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
+  const unsigned char* xo1 = xs + ((NT > 1 && om + 16 < (uint32_t)M) ? om + 16 : 0u) * rowbytes;
 
-    uint2 ue = *(const uint2*)(unitj + c * 32u);
-    const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));
-    const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));
-    half_t s1 = scale_dequant(m1 & 0xFFu, m2);
-    if (c + 1 == (uint32_t)b.B2 || c + 1 == C) {  // only the last block of a stream can hold padding units
-      if (ue.x & MPQ_PAD_UNIT) s1 = (half_t)0.0f;
-      ue.x &= ~MPQ_PAD_UNIT;
+  uint32_t slot = 0;        // ring slot of the next block to consume
+  uint32_t since_side = 0;  // requests of this wave issued after its share of the next side record
+  uint32_t par = 0;
+  for (uint32_t tile = tile0; tile < T; tile += grid, par ^= 1u) {
+    const unsigned char* side = side0 + par * b.side_bytes;
+    if (tile != tile0) {
+      wait_vm((int)since_side);  // this wave's share of the side record has landed
+      lds_barrier();             // ... and everybody else's; everybody is done with the previous tile
     }
-    const half2_t s1p = {s1, s1};
-    const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
-    const unsigned char* xb0 = xrow0 + ue.x;
-    const unsigned char* xb1 = xrow1 + ue.x;
-    const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+    tileptr += tilestep;
+    if (tile + grid < T) dma_linear(tileptr, lds_addr(side0 + (par ^ 1u) * b.side_bytes), b.side_bytes, wv, lane16);
+    since_side = 0;
+    const unsigned char* m1i = side + i * 2;
+    const unsigned char* m2i = side + b.off_m2 + i * 4;
+
+    // ---- (2) this wave's blocks of the tile, in order
+    float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    for (uint32_t c = wv; c < C; c += W) {
+      // Requests younger than the block needed now: the other blocks in flight (stricter than
+      // necessary when a side-record request sits between them, never laxer).
+      if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);
+      uint4 q;
+      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory");
+      --inflight;
+      if (rtile < T) {  // refill the freed slot with the next block of this wave's sequence
+        dma16(rbase + rc * 1024u, lane16, ring0 + slot * 1024u);
+        ++inflight;
+        ++since_side;
+        rc += W;
+        if (rc >= C) { rc = wv; rtile += grid; rbase += tilestep; }
+      }
+      slot = slot + 1 == PD ? 0 : slot + 1;
+
+      uint2 ue = *(const uint2*)(unitj + c * 32u);
+      const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));
+      const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));
+      half_t s1 = scale_dequant(m1 & 0xFFu, m2);
+      if (c + 1 == (uint32_t)b.B2 || c + 1 == C) {  // only the last block of a stream can hold padding units
+        if (ue.x & MPQ_PAD_UNIT) s1 = (half_t)0.0f;
+        ue.x &= ~MPQ_PAD_UNIT;
+      }
+      const half2_t s1p = {s1, s1};
+      const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
+      const unsigned char* xb0 = xrow0 + ue.x;
+      const unsigned char* xb1 = xrow1 + ue.x;
+      const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
 #define MPQ_MM_STEP(TWO, P)                                                                           \
   {                                                                                                   \
     const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
@@ -278,61 +325,58 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
                                                     __builtin_bit_cast(half8_t, bv1), acc1, 0, 0, 0); \
     }                                                                                                 \
   }
-    if (c < (uint32_t)b.B2) {
-      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
-      MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
-      MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
-    } else {
-      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
-      MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
-    }
+      if (c < (uint32_t)b.B2) {
+        const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+        MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
+        MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
+      } else {
+        const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+        MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
+      }
 #undef MPQ_MM_STEP
-  }
-  // ---- (3) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share; the
-  //      wave parks it in its own (now idle) ring slots: red[NT][16 m][16 rows]
-  float* red = (float*)myring;
-  *(float4_t*)(red + i * 16 + 4 * j) = acc0;
-  if (NT > 1) *(float4_t*)(red + 256 + i * 16 + 4 * j) = acc1;
+    }
+    // ---- (3) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share:
+    //      red[wave][NT][16 m][16 rows]
+    // (persistent: dedicated slots; else the wave's own ring slots, idle by now)
+    constexpr uint32_t red_stride = PERSIST ? NT * 1024 : PD * 1024;  // bytes between waves
+    unsigned char* const red = PERSIST ? lds + W * PD * 1024 : ring;
+    float* myred = (float*)(red + wv * red_stride);
+    *(float4_t*)(myred + i * 16 + 4 * j) = acc0;
+    if (NT > 1) *(float4_t*)(myred + 256 + i * 16 + 4 * j) = acc1;
 
-  // ---- (4) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory): 16 consecutive
-  //      lanes share row `orow`; lane q takes batch column q % Mp (and + 16) and every (16/Mp)-th
-  //      word of the row; all operands are already in LDS
-  const uint32_t orow = tid >> 4, oq = tid & 15u;
-  uint32_t Mp = 1;
-  while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
-  const uint32_t om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
-  float oa0 = 0.f, oa1 = 0.f;
-  {
-    const uint32_t* ostart = (const uint32_t*)ots;
-    const uint32_t* owords = (const uint32_t*)(ots + MPQ_OTILE_HEAD);
-    const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
-    const unsigned char* xo0 = xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
-    const unsigned char* xo1 = xs + ((NT > 1 && om + 16 < (uint32_t)M) ? om + 16 : 0u) * rowbytes;
-    for (uint32_t e = rp0 + oes; e < rp1; e += ostride) {
-      const uint32_t word = owords[e];
-      const uint32_t off = (word & 0xFFFFu) * 2u;
-      const float v = (float)bits_to_half((uint16_t)(word >> 16));
-      oa0 += v * (float)*(const half_t*)(xo0 + off);
-      if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
+    // ---- (4) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
+    //      are already in LDS
+    float oa0 = 0.f, oa1 = 0.f;
+    {
+      const uint32_t* ostart = (const uint32_t*)(side + b.off_ot);
+      const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
+      const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
+      for (uint32_t e = rp0 + oes; e < rp1; e += ostride) {
+        const uint32_t word = owords[e];
+        const uint32_t off = (word & 0xFFFFu) * 2u;
+        const float v = (float)bits_to_half((uint16_t)(word >> 16));
+        oa0 += v * (float)*(const half_t*)(xo0 + off);
+        if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
+      }
+      for (uint32_t off = Mp; off < 16; off <<= 1) {
+        oa0 += __shfl_xor(oa0, off);
+        if (NT > 1) oa1 += __shfl_xor(oa1, off);
+      }
     }
-    for (uint32_t off = Mp; off < 16; off <<= 1) {
-      oa0 += __shfl_xor(oa0, off);
-      if (NT > 1) oa1 += __shfl_xor(oa1, off);
-    }
-  }
-  __syncthreads();
-  {
-    const uint32_t row = blockIdx.x * 16 + orow;
-    float t0 = oa0, t1 = oa1;
+    lds_barrier();
+    {
+      const uint32_t row = tile * 16 + orow;
+      float t0 = oa0, t1 = oa1;
 #pragma unroll
-    for (uint32_t w2 = 0; w2 < W; ++w2) {
-      const float* r2 = (const float*)(ring + w2 * (PD * 1024));
-      t0 += r2[oq * 16 + orow];
-      if (NT > 1) t1 += r2[256 + oq * 16 + orow];
-    }
-    if (row < (uint32_t)b.N) {
-      if (oq < (uint32_t)M) Y[(size_t)oq * b.N + row] = half_to_bits((half_t)t0);
-      if (NT > 1 && oq + 16 < (uint32_t)M) Y[(size_t)(oq + 16) * b.N + row] = half_to_bits((half_t)t1);
+      for (uint32_t w2 = 0; w2 < W; ++w2) {
+        const float* r2 = (const float*)(red + w2 * red_stride);
+        t0 += r2[oq * 16 + orow];
+        if (NT > 1) t1 += r2[256 + oq * 16 + orow];
+      }
+      if (row < (uint32_t)b.N) {
+        if (oq < (uint32_t)M) Y[(size_t)oq * b.N + row] = half_to_bits((half_t)t0);
+        if (NT > 1 && oq + 16 < (uint32_t)M) Y[(size_t)(oq + 16) * b.N + row] = half_to_bits((half_t)t1);
+      }
     }
   }
 }
@@ -419,43 +463,78 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   return MPQ_OK;
 }
 
-// Bytes of the `stage` array a batch of M rows needs (unit tables, the tile's meta words, activations).
-size_t stage_bytes(const MpqHeader& h, int M) {
-  return h.side_bytes + 32ull * (h.B2 + h.B4) + (size_t)M * (2ull * h.K + 16);
+// LDS bytes the product kernel needs for a batch of M rows at ring depth PD: ring, (persistent:
+// reduction slots and a second side-record buffer), side record, unit table, activation rows.
+size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, bool persist) {
+  const size_t NT = M > 16 ? 2 : 1;
+  return 4ull * PD * 1024 + (persist ? NT * 4096 + 2 * h.side_bytes : h.side_bytes) + 32ull * (h.B2 + h.B4) +
+         (size_t)M * (2ull * h.K + 16);
 }
 
-int g_ring_depth = 0;  // 0 = automatic
+constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
 
-template <int NT, int PD, int STB>
+int g_ring_depth = 0;   // 0 = automatic
+int g_max_blocks = 0;   // 0 = automatic
+int g_persist = -1;     // -1 = automatic (persistent workgroups for M > 1)
+int g_cu_count = 0;
+
+int cu_count() {
+  if (g_cu_count == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    g_cu_count = n;
+  }
+  return g_cu_count;
+}
+
+template <int NT, int PD, int LDSB, bool PERSIST>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, STB>), dim3(h.T), dim3(256), 0, s, d, X, Y, M);
+  long grid = h.T;
+  if (PERSIST) {  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
+    size_t per_cu = kLdsPerCu / LDSB;
+    if (per_cu > 8) per_cu = 8;
+    if (per_cu < 1) per_cu = 1;
+    grid = (long)cu_count() * (long)per_cu;
+    if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
+    if (grid > h.T) grid = h.T;
+  }
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
-// Static LDS size classes of the product kernel (bytes of `stage`); the ring depth per class
-// keeps several workgroups resident per compute unit (160 KiB of LDS).
+// Static LDS size classes of the product kernel; each has the ring depth that keeps enough bytes
+// in flight for the number of workgroups that fit a compute unit.
 template <int NT>
 mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  const size_t need = stage_bytes(h, M);
   const int pd = g_ring_depth;
-  if (need <= 13312) {
-    if (pd == 2) return launch_mm<NT, 2, 13312>(h, d, X, Y, M, s);
-    if (pd == 4) return launch_mm<NT, 4, 13312>(h, d, X, Y, M, s);
-    if (pd == 5) return launch_mm<NT, 5, 13312>(h, d, X, Y, M, s);
-    return launch_mm<NT, 3, 13312>(h, d, X, Y, M, s);
+  const bool persist = g_persist < 0 ? M > 1 : g_persist != 0;
+  if (!persist) {
+    if (pd == 2 && mm_lds_bytes(h, M, 2, false) <= 26 * 1024) return launch_mm<NT, 2, 26 * 1024, false>(h, d, X, Y, M, s);
+    if (pd == 4 && mm_lds_bytes(h, M, 4, false) <= 32 * 1024) return launch_mm<NT, 4, 32 * 1024, false>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 3, false) <= 26 * 1024) return launch_mm<NT, 3, 26 * 1024, false>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 3, false) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024, false>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 4, false) <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024, false>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 4, false) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024, false>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 6, false) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024, false>(h, d, X, Y, M, s);
   }
-  if (need <= 24 * 1024) return launch_mm<NT, 4, 24 * 1024>(h, d, X, Y, M, s);
-  if (need <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024>(h, d, X, Y, M, s);
-  if (need <= 80 * 1024) return launch_mm<NT, 4, 80 * 1024>(h, d, X, Y, M, s);
-  if (need <= 144 * 1024) return launch_mm<NT, 3, 144 * 1024>(h, d, X, Y, M, s);
+  if (pd == 2 && mm_lds_bytes(h, M, 2, true) <= 40 * 1024) return launch_mm<NT, 2, 40 * 1024, true>(h, d, X, Y, M, s);
+  if (pd == 4 && mm_lds_bytes(h, M, 4, true) <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3, true) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3, true) <= 40 * 1024) return launch_mm<NT, 3, 40 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 4, true) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 6, true) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 8, true) <= 160 * 1024) return launch_mm<NT, 8, 160 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3, true) <= 160 * 1024) return launch_mm<NT, 3, 160 * 1024, true>(h, d, X, Y, M, s);
   return MPQ_ERR_UNSUPPORTED;
 }
 
 mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  constexpr size_t kStageMax = 144 * 1024;
-  if (stage_bytes(h, 1) > kStageMax) return MPQ_ERR_UNSUPPORTED;
-  int Mc = M;  // largest batch chunk whose activations fit LDS together with the tables
-  while (Mc > 1 && stage_bytes(h, Mc) > kStageMax) --Mc;
+  if (mm_lds_bytes(h, 1, 3, true) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
+  int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
+  while (Mc > 1 && mm_lds_bytes(h, Mc, 3, true) > kLdsPerCu) --Mc;
   if (Mc > 16 && Mc < M) Mc = 16;
   for (int m0 = 0; m0 < M; m0 += Mc) {
     const int mc = M - m0 < Mc ? M - m0 : Mc;
@@ -472,9 +551,13 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
 extern "C" {
 
 // Tuning hook for sweeps; not part of the supported interface and not thread safe.
-// key 0: ring depth (code blocks in flight per wave) for the smallest LDS class, 0 = automatic.
+// key 0: ring depth (code blocks in flight per wave) where it fits the small LDS classes, 0 = automatic;
+// key 2: cap on the number of persistent workgroups, 0 = automatic; key 3: 0 one workgroup per tile,
+// 1 persistent workgroups, -1 automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
+  if (key == 2) g_max_blocks = value;
+  if (key == 3) g_persist = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
