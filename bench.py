@@ -43,8 +43,8 @@ def algorithmic_bytes(spec, n4, nnz):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1024)
-    ap.add_argument("--warmup", type=int, default=128)
+    ap.add_argument("--steps", type=int, default=4096)
+    ap.add_argument("--warmup", type=int, default=1024)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration (1 = Llama2-7B layer, 3 = Llama3-8B)")
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")

@@ -13,16 +13,18 @@
 //   header    256 B                       (MpqHeader)
 //   units     2 x uint32 [4*(B2+B4)]      per unit in stream order (2-bit units, then 4-bit units),
 //                                         ready for the kernels:
-//                 word 0 = byte offset of the unit's first activation in an fp16 row (2*k0),
-//                          bit 31 set for a padding unit (then everything else is 0)
+//                 word 0 = byte offset of the unit's first activation in an fp16 row (2*k0)
 //                 word 1 = (stream_group * 32) | (super_group * 64) << 16: byte offsets of the
 //                          group's 16 rows inside the tile's meta1 / meta2 arrays
+//                 a padding unit (stream padded to a multiple of 4 units) has word 0 = 0 and
+//                 points at stream group G and super-group S, two extra all-zero entries of
+//                 meta1 / meta2: its scale decodes to exactly 0 without any test in the kernel
 //   tiles     T x tile_stride B           one self-contained record per 16-row tile, so that a
 //                                         workgroup finds everything it needs at one base address:
 //       side (side_bytes):
-//         meta1   G x 16 x 2 B    (s_int | z1 << 8) per (stream group, row); stream group order = all
-//                                 2-bit groups in K order, then all 4-bit groups
-//         meta2   S x 16 x 4 B    (s2 | z2 << 16) per (super-group, row)
+//         meta1   (G+1) x 16 x 2 B  (s_int | z1 << 8) per (stream group, row); stream group order = all
+//                                 2-bit groups in K order, then all 4-bit groups, then one zero entry
+//         meta2   (S+1) x 16 x 4 B  (s2 | z2 << 16) per (super-group, row), then one zero entry
 //         outl    128 + 4*ocap B  uint32 start[17] (then zeros up to 128 B): start[r] = index of the first
 //                                 word of row r of the tile, start[16] = number of words; then
 //                                 uint32 word[ocap] = col | val << 16 (Sec. 2.3: one 32-bit word per
@@ -46,12 +48,11 @@
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 5u
+#define MPQ_VERSION 6u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024
 #define MPQ_SECTION_ALIGN 256
-#define MPQ_PAD_UNIT 0x80000000u
 #define MPQ_OTILE_HEAD 128 /* bytes of the row-start table at the head of a tile's outlier record */
 
 typedef struct {

@@ -208,11 +208,16 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // LDS per workgroup and lets six workgroups share a compute unit.  It wins when the activations
 // are small (M = 1) because the vector ALU needs many waves per SIMD to stay busy; the persistent
 // form wins when staging the activations once per tile would dominate (M > 1).
-template <int NT, int PD, int LDSB, bool PERSIST>
+//
+// GEMV = true compiles the M = 1 case (the matrix-vector product of Algorithm 1) with everything
+// batch-related folded away: one activation row, only batch column 0 of the accumulator is parked
+// and summed, 16 lanes per row for the outliers with a DPP row reduction.
+template <int NT, int PD, int LDSB, bool PERSIST, bool GEMV>
 __global__ void __launch_bounds__(256)
-mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
+mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M_arg) {
 #pragma clang fp contract(off)
-  static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT), "ring depth");
+  static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT) && (!GEMV || NT == 1), "ring depth / batch tiles");
+  const int M = GEMV ? 1 : M_arg;
   __shared__ __align__(16) unsigned char lds[LDSB];
   constexpr uint32_t W = 4;
   const uint32_t tid = threadIdx.x;
@@ -254,7 +259,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
-  const unsigned char* xrow0 = xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
+  const unsigned char* xrow0 = GEMV ? xs : xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
   const unsigned char* xrow1 = xs + ((NT > 1 && i + 16 < (uint32_t)M) ? i + 16 : 0u) * rowbytes;
   const unsigned char* unitj = units + j * 8;
   const uint32_t ringl = ring0 + lane16;
@@ -262,9 +267,10 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   // q % Mp (and + 16) and every (16/Mp)-th word of the row
   const uint32_t orow = tid >> 4, oq = tid & 15u;
   uint32_t Mp = 1;
-  while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
+  if (!GEMV)
+    while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
   const uint32_t om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
-  const unsigned char* xo0 = xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
+  const unsigned char* xo0 = GEMV ? xs : xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
   const unsigned char* xo1 = xs + ((NT > 1 && om + 16 < (uint32_t)M) ? om + 16 : 0u) * rowbytes;
 
   uint32_t slot = 0;        // ring slot of the next block to consume
@@ -284,35 +290,6 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 
     // ---- (2) this wave's blocks of the tile, in order
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-    for (uint32_t c = wv; c < C; c += W) {
-      // Requests younger than the block needed now: the other blocks in flight (stricter than
-      // necessary when a side-record request sits between them, never laxer).
-      if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);
-      uint4 q;
-      asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory");
-      --inflight;
-      if (rtile < T) {  // refill the freed slot with the next block of this wave's sequence
-        dma16(rbase + rc * 1024u, lane16, ring0 + slot * 1024u);
-        ++inflight;
-        ++since_side;
-        rc += W;
-        if (rc >= C) { rc = wv; rtile += grid; rbase += tilestep; }
-      }
-      slot = slot + 1 == PD ? 0 : slot + 1;
-
-      uint2 ue = *(const uint2*)(unitj + c * 32u);
-      const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));
-      const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));
-      half_t s1 = scale_dequant(m1 & 0xFFu, m2);
-      if (c + 1 == (uint32_t)b.B2 || c + 1 == C) {  // only the last block of a stream can hold padding units
-        if (ue.x & MPQ_PAD_UNIT) s1 = (half_t)0.0f;
-        ue.x &= ~MPQ_PAD_UNIT;
-      }
-      const half2_t s1p = {s1, s1};
-      const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
-      const unsigned char* xb0 = xrow0 + ue.x;
-      const unsigned char* xb1 = xrow1 + ue.x;
-      const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
 #define MPQ_MM_STEP(TWO, P)                                                                           \
   {                                                                                                   \
     const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
@@ -325,24 +302,59 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
                                                     __builtin_bit_cast(half8_t, bv1), acc1, 0, 0, 0); \
     }                                                                                                 \
   }
-      if (c < (uint32_t)b.B2) {
-        const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
-        MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
-        MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
-      } else {
-        const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
-        MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
-      }
-#undef MPQ_MM_STEP
+// Fetch of the next block of this wave (wait, read its ring slot, refill the slot) and the
+// per-unit set-up; the 2-bit blocks of a tile come first in the wave's sequence, then the 4-bit ones.
+#define MPQ_MM_BLOCK_HEAD                                                                              \
+  /* Requests younger than the block needed now: the other blocks in flight (stricter than            \
+     necessary when a side-record request sits between them, never laxer). */                         \
+  if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
+  uint4 q;                                                                                            \
+  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
+  --inflight;                                                                                         \
+  if (rtile < T) { /* refill the freed slot with the next block of this wave's sequence */            \
+    dma16(rbase + rc * 1024u, lane16, ring0 + slot * 1024u);                                          \
+    ++inflight;                                                                                       \
+    ++since_side;                                                                                     \
+    rc += W;                                                                                          \
+    if (rc >= C) { rc = wv; rtile += grid; rbase += tilestep; }                                       \
+  }                                                                                                   \
+  slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
+  const uint2 ue = *(const uint2*)(unitj + c * 32u);                                                  \
+  const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));                                     \
+  const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));                                         \
+  const half_t s1 = scale_dequant(m1 & 0xFFu, m2); /* exactly 0 for a padding unit (zero meta entries) */ \
+  const half2_t s1p = {s1, s1};                                                                       \
+  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8))); /* 1024 + z1 */                    \
+  const unsigned char* xb0 = xrow0 + ue.x;                                                            \
+  const unsigned char* xb1 = xrow1 + ue.x;                                                            \
+  (void)xb1;                                                                                          \
+  const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+    uint32_t c = wv;
+    for (; c < (uint32_t)b.B2; c += W) {
+      MPQ_MM_BLOCK_HEAD
+      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
+      MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
     }
+    for (; c < C; c += W) {
+      MPQ_MM_BLOCK_HEAD
+      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+      MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
+    }
+#undef MPQ_MM_BLOCK_HEAD
+#undef MPQ_MM_STEP
     // ---- (3) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share:
     //      red[wave][NT][16 m][16 rows]
     // (persistent: dedicated slots; else the wave's own ring slots, idle by now)
     constexpr uint32_t red_stride = PERSIST ? NT * 1024 : PD * 1024;  // bytes between waves
     unsigned char* const red = PERSIST ? lds + W * PD * 1024 : ring;
     float* myred = (float*)(red + wv * red_stride);
-    *(float4_t*)(myred + i * 16 + 4 * j) = acc0;
-    if (NT > 1) *(float4_t*)(myred + 256 + i * 16 + 4 * j) = acc1;
+    if (GEMV) {
+      if (i == 0) *(float4_t*)(myred + 4 * j) = acc0;  // batch column 0 only: red[wave][16 rows]
+    } else {
+      *(float4_t*)(myred + i * 16 + 4 * j) = acc0;
+      if (NT > 1) *(float4_t*)(myred + 256 + i * 16 + 4 * j) = acc1;
+    }
 
     // ---- (4) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
     //      are already in LDS
@@ -358,13 +370,30 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
         oa0 += v * (float)*(const half_t*)(xo0 + off);
         if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
       }
-      for (uint32_t off = Mp; off < 16; off <<= 1) {
-        oa0 += __shfl_xor(oa0, off);
-        if (NT > 1) oa1 += __shfl_xor(oa1, off);
+      if (GEMV) {
+        // sum over the 16 lanes of the row with DPP row shifts; lane 15 of the row ends with the total
+        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x118, 0xf, 0xf, true));
+        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x114, 0xf, 0xf, true));
+        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x112, 0xf, 0xf, true));
+        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x111, 0xf, 0xf, true));
+        if (oq == 15) myred[16 + (orow & 3u)] = oa0;  // this wave's rows are orow = 4*wave .. 4*wave+3
+      } else {
+        for (uint32_t off = Mp; off < 16; off <<= 1) {
+          oa0 += __shfl_xor(oa0, off);
+          if (NT > 1) oa1 += __shfl_xor(oa1, off);
+        }
       }
     }
     lds_barrier();
-    {
+    if (GEMV) {
+      if (tid < 16) {  // row tid of the tile: four partial sums and the outlier term, in a fixed order
+        float t0 = ((const float*)(red + (tid >> 2) * red_stride))[16 + (tid & 3u)];
+#pragma unroll
+        for (uint32_t w2 = 0; w2 < W; ++w2) t0 += ((const float*)(red + w2 * red_stride))[tid];
+        const uint32_t row = tile * 16 + tid;
+        if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)t0);
+      }
+    } else {
       const uint32_t row = tile * 16 + orow;
       float t0 = oa0, t1 = oa1;
 #pragma unroll
@@ -395,7 +424,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   for (int c = wv; c < b.C; c += W) {
     const uint4 q = ((const uint4*)(tile + b.codes_off))[c * 64 + lane];
     const uint2 ue = units[4 * c + j];
-    if ((ue.x & MPQ_PAD_UNIT) || row >= b.N) continue;
+    if ((ue.y & 0xFFFFu) == 32u * (uint32_t)b.G || row >= b.N) continue;  // padding unit / padding row
     const uint32_t m1 = *(const uint16_t*)(tile + (ue.y & 0xFFFFu) + i * 2);
     const uint32_t m2 = *(const uint32_t*)(tile + b.off_m2 + (ue.y >> 16) + i * 4);
     const half_t s1 = scale_dequant(m1 & 0xFFu, m2);
@@ -456,8 +485,8 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   d->tile_stride = (uint32_t)h->tile_stride;
   d->side_bytes = (uint32_t)h->side_bytes;
   d->codes_off = (uint32_t)h->codes_off;
-  d->off_m2 = 32u * (uint32_t)h->G;
-  d->off_ot = d->off_m2 + 64u * (uint32_t)h->S;
+  d->off_m2 = 32u * ((uint32_t)h->G + 1);
+  d->off_ot = d->off_m2 + 64u * ((uint32_t)h->S + 1);
   d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->B2 = h->B2; d->C = h->B2 + h->B4; d->T = h->T;
   if (h->tile_stride > 0xFFFFFFFFull) return MPQ_ERR_UNSUPPORTED;
   return MPQ_OK;
@@ -492,6 +521,7 @@ int cu_count() {
 
 template <int NT, int PD, int LDSB, bool PERSIST>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  constexpr bool kGemvOk = NT == 1;
   long grid = h.T;
   if (PERSIST) {  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
     size_t per_cu = kLdsPerCu / LDSB;
@@ -501,7 +531,10 @@ mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, ui
     if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
     if (grid > h.T) grid = h.T;
   }
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
+  if (kGemvOk && M == 1)
+    hipLaunchKernelGGL((mpq_mm_kernel<1, PD, LDSB, PERSIST, true>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
+  else
+    hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST, false>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 

@@ -42,7 +42,8 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
   h->nnz = nnz;
   const uint64_t C = (uint64_t)h->B2 + h->B4;
   h->ocap = (uint64_t)ocap;
-  h->side_bytes = 32ull * h->G + 64ull * h->S + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
+  if (64ull * ((uint64_t)h->S + 1) > 0xFFFFull) return MPQ_ERR_UNSUPPORTED;  // 16-bit offsets in the unit table
+  h->side_bytes = 32ull * (h->G + 1) + 64ull * (h->S + 1) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
   h->codes_off = align_up(h->side_bytes, 128);
   h->tile_stride = align_up(h->codes_off + C * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
   uint64_t off = MPQ_HEADER_BYTES;
@@ -187,7 +188,7 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   const int32_t upg2 = (int32_t)(g1 / 64), upg4 = (int32_t)(g1 / 32);
   std::vector<int64_t> k0_2(4 * h.B2, -1), k0_4(4 * h.B4, -1);
   for (int32_t u = 0; u < 4 * h.B2; ++u) {
-    if (u >= h.U2) { unit2[2 * u] = MPQ_PAD_UNIT; unit2[2 * u + 1] = 0; continue; }
+    if (u >= h.U2) { unit2[2 * u] = 0; unit2[2 * u + 1] = (uint32_t)(G * 32) | ((uint32_t)(h.S * 64) << 16); continue; }
     const int32_t g = groups2[u / upg2];
     const int64_t k0 = (int64_t)g * g1 + 64 * (u % upg2);
     k0_2[u] = k0;
@@ -195,7 +196,7 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     unit2[2 * u + 1] = (uint32_t)(stream_index[g] * 32) | ((uint32_t)((g / d->g2) * 64) << 16);
   }
   for (int32_t u = 0; u < 4 * h.B4; ++u) {
-    if (u >= h.U4) { unit4[2 * u] = MPQ_PAD_UNIT; unit4[2 * u + 1] = 0; continue; }
+    if (u >= h.U4) { unit4[2 * u] = 0; unit4[2 * u + 1] = (uint32_t)(G * 32) | ((uint32_t)(h.S * 64) << 16); continue; }
     const int32_t g = groups4[u / upg4];
     const int64_t k0 = (int64_t)g * g1 + 32 * (u % upg4);
     k0_4[u] = k0;
@@ -206,7 +207,7 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     const int64_t t = n / MPQ_TILE_ROWS, i = n % MPQ_TILE_ROWS;
     uint8_t* tile = blob + h.off_tiles + (uint64_t)t * h.tile_stride;
     uint16_t* meta1 = (uint16_t*)tile;
-    uint32_t* meta2 = (uint32_t*)(tile + 32ull * G);
+    uint32_t* meta2 = (uint32_t*)(tile + 32ull * (G + 1));
     uint32_t* codes2 = (uint32_t*)(tile + h.codes_off);
     uint32_t* codes4 = codes2 + (uint64_t)h.B2 * 256;
     const uint8_t* row = w->codes + n * K;
@@ -230,7 +231,7 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
       meta2[s * MPQ_TILE_ROWS + i] = (uint32_t)w->s2[n * h.S + s] | ((uint32_t)w->z2[n * h.S + s] << 16);
   }
   for (int64_t t = 0; t < h.T; ++t) {
-    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + 32ull * G + 64ull * h.S);
+    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + 32ull * (G + 1) + 64ull * (h.S + 1));
     const int64_t n0 = t * MPQ_TILE_ROWS;
     const int32_t base = w->row_ptr[n0];
     for (int r = 0; r <= MPQ_TILE_ROWS; ++r) {

@@ -24,7 +24,7 @@ def unpack(blob: np.ndarray) -> dict:
     N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
     B2, B4 = h["B2"], h["B4"]
     C = B2 + B4
-    assert h["side_bytes"] == 32 * G + 64 * S + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
+    assert h["side_bytes"] == 32 * (G + 1) + 64 * (S + 1) + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
     assert h["codes_off"] % 128 == 0 and h["codes_off"] >= h["side_bytes"] and h["tile_stride"] % 256 == 0
     assert h["tile_stride"] >= h["codes_off"] + C * 1024 and h["total"] == blob.size
     units = blob[h["off_units"]: h["off_units"] + 32 * C].view(np.uint32).reshape(-1, 2)
@@ -40,10 +40,11 @@ def unpack(blob: np.ndarray) -> dict:
         ul = u - 4 * B2 if four else u
         e, e1 = int(units[u, 0]), int(units[u, 1])
         words = cw[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
-        if e & 0x80000000:
-            assert ul >= (h["U4"] if four else h["U2"]) and e == 0x80000000 and e1 == 0
+        if (e1 & 0xFFFF) == 32 * G:                        # padding unit: points at the zero entries
+            assert ul >= (h["U4"] if four else h["U2"]) and e == 0 and (e1 >> 16) == 64 * S
             assert not words.any()                        # padding units are zero
             continue
+        assert ul < (h["U4"] if four else h["U2"])
         k0 = e // 2
         g = k0 // g1
         is4[g] = 1 if four else 0
@@ -56,17 +57,20 @@ def unpack(blob: np.ndarray) -> dict:
             d, sh = (kl % 8) // 2, 16 * (kl % 2) + width * (kl // 8)
             codes[:, k0 + kl] = ((words[:, :, d] >> sh) & ((1 << width) - 1)).reshape(-1)
     assert len(stream_groups) == G and sorted(stream_groups) == list(range(G))
-    m1 = np.ascontiguousarray(tiles[:, : 32 * G]).view(np.uint16).reshape(T, G, TILE)
+    m1 = np.ascontiguousarray(tiles[:, : 32 * (G + 1)]).view(np.uint16).reshape(T, G + 1, TILE)
+    assert not m1[:, G].any()                             # the zero entry padding units point at
     s_int = np.zeros((T * TILE, G), dtype=np.uint8)
     z1 = np.zeros((T * TILE, G), dtype=np.uint8)
     for sg, g in enumerate(stream_groups):
         s_int[:, g] = (m1[:, sg, :] & 0xFF).reshape(-1)
         z1[:, g] = (m1[:, sg, :] >> 8).reshape(-1)
-    m2 = np.ascontiguousarray(tiles[:, 32 * G: 32 * G + 64 * S]).view(np.uint32).reshape(T, S, TILE)
+    m2 = np.ascontiguousarray(tiles[:, 32 * (G + 1): 32 * (G + 1) + 64 * (S + 1)]).view(np.uint32).reshape(T, S + 1, TILE)
+    assert not m2[:, S].any()
+    m2 = m2[:, :S]
     s2 = (m2 & 0xFFFF).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
     z2 = (m2 >> 16).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
     # outliers: one record per tile = 32 words of row starts (17 used) + ocap words
-    o0 = 32 * G + 64 * S
+    o0 = 32 * (G + 1) + 64 * (S + 1)
     recs = np.ascontiguousarray(tiles[:, o0: o0 + 128 + 4 * h["ocap"]]).view(np.uint32).reshape(T, 32 + h["ocap"])
     row_ptr = [0]
     words = []
