@@ -88,11 +88,12 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
 }
 
-// Copies `bytes` (a multiple of 16) from gbase to LDS byte address lds; the four waves of the
+// Copies `bytes` (a multiple of 16) from gbase to LDS byte address lds; the NW waves of the
 // workgroup take 1 KiB pieces in turn.  lane16 = 16 * lane.
+template <uint32_t NW>
 __device__ __forceinline__ void dma_linear(const unsigned char* gbase, uint32_t lds, uint32_t bytes, uint32_t wv,
                                            uint32_t lane16) {
-  for (uint32_t off = wv * 1024u; off < bytes; off += 4096u) {
+  for (uint32_t off = wv * 1024u; off < bytes; off += NW * 1024u) {
     if (off + 1024u <= bytes) {
       dma16(gbase + off, lane16, lds + off);
     } else if (off + lane16 < bytes) {
@@ -212,14 +213,19 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // GEMV = true compiles the M = 1 case (the matrix-vector product of Algorithm 1) with everything
 // batch-related folded away: one activation row, only batch column 0 of the accumulator is parked
 // and summed, 16 lanes per row for the outliers with a DPP row reduction.
-template <int NT, int PD, int LDSB, bool PERSIST, bool GEMV>
-__global__ void __launch_bounds__(256)
+//
+// WV = waves per workgroup.  Four by default; the per-tile GEMV uses 8 or 16 when the matrix has so
+// few row tiles that four waves per tile would leave most of a compute unit's SIMD slots empty
+// (4096 rows = 256 tiles = one tile per compute unit).
+template <int NT, int PD, int LDSB, bool PERSIST, bool GEMV, int WV = 4>
+__global__ void __launch_bounds__(WV * 64)
 mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M_arg) {
 #pragma clang fp contract(off)
   static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT) && (!GEMV || NT == 1), "ring depth / batch tiles");
   const int M = GEMV ? 1 : M_arg;
   __shared__ __align__(16) unsigned char lds[LDSB];
-  constexpr uint32_t W = 4;
+  static_assert(WV == 4 || (GEMV && !PERSIST), "more than four waves only for the per-tile GEMV");
+  constexpr uint32_t W = WV;
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
@@ -237,10 +243,10 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   const uint32_t tile0 = blockIdx.x;
   const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
   const size_t tilestep = (size_t)grid * b.tile_stride;
-  dma_linear(tileptr, lds_addr(side0), b.side_bytes, wv, lane16);
-  dma_linear(b.units, lds_addr(units), units_bytes, wv, lane16);
+  dma_linear<W>(tileptr, lds_addr(side0), b.side_bytes, wv, lane16);
+  dma_linear<W>(b.units, lds_addr(units), units_bytes, wv, lane16);
   for (int m = 0; m < M; ++m)
-    dma_linear((const unsigned char*)(X + (size_t)m * b.K), lds_addr(xs) + m * rowbytes, 2u * b.K, wv, lane16);
+    dma_linear<W>((const unsigned char*)(X + (size_t)m * b.K), lds_addr(xs) + m * rowbytes, 2u * b.K, wv, lane16);
   // this wave's sequence of blocks: (tile0, wv), (tile0, wv + 4), ..., (tile0 + grid, wv), ...
   const uint32_t ring0 = lds_addr(ring) + wv * (PD * 1024);
   const unsigned char* rbase = tileptr + b.codes_off;  // code blocks of the tile being requested
@@ -283,7 +289,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
       lds_barrier();             // ... and everybody else's; everybody is done with the previous tile
     }
     tileptr += tilestep;
-    if (tile + grid < T) dma_linear(tileptr, lds_addr(side0 + (par ^ 1u) * b.side_bytes), b.side_bytes, wv, lane16);
+    if (tile + grid < T) dma_linear<W>(tileptr, lds_addr(side0 + (par ^ 1u) * b.side_bytes), b.side_bytes, wv, lane16);
     since_side = 0;
     const unsigned char* m1i = side + i * 2;
     const unsigned char* m2i = side + b.off_m2 + i * 4;
@@ -359,7 +365,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
     // ---- (4) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
     //      are already in LDS
     float oa0 = 0.f, oa1 = 0.f;
-    {
+    if (WV == 4 || wv < 4) {  // the first 256 threads cover the 16 rows
       const uint32_t* ostart = (const uint32_t*)(side + b.off_ot);
       const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
       const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
@@ -494,9 +500,9 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
 
 // LDS bytes the product kernel needs for a batch of M rows at ring depth PD: ring, (persistent:
 // reduction slots and a second side-record buffer), side record, unit table, activation rows.
-size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, bool persist) {
+size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, bool persist, int waves = 4) {
   const size_t NT = M > 16 ? 2 : 1;
-  return 4ull * PD * 1024 + (persist ? NT * 4096 + 2 * h.side_bytes : h.side_bytes) + 32ull * (h.B2 + h.B4) +
+  return (size_t)waves * PD * 1024 + (persist ? NT * 4096 + 2 * h.side_bytes : h.side_bytes) + 32ull * (h.B2 + h.B4) +
          (size_t)M * (2ull * h.K + 16);
 }
 
@@ -505,6 +511,7 @@ constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
 int g_ring_depth = 0;   // 0 = automatic
 int g_max_blocks = 0;   // 0 = automatic
 int g_persist = -1;     // -1 = automatic (persistent workgroups for M > 1)
+int g_gemv_waves = 0;   // 0 = automatic (4, 8 or 16 waves per tile for the per-tile GEMV)
 int g_cu_count = 0;
 
 int cu_count() {
@@ -517,6 +524,13 @@ int cu_count() {
     g_cu_count = n;
   }
   return g_cu_count;
+}
+
+// Per-tile GEMV with WV waves per workgroup.
+template <int PD, int LDSB, int WV>
+mpq_status launch_gemv(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, hipStream_t s) {
+  hipLaunchKernelGGL((mpq_mm_kernel<1, PD, LDSB, false, true, WV>), dim3((unsigned)h.T), dim3(WV * 64), 0, s, d, X, Y, 1);
+  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
 template <int NT, int PD, int LDSB, bool PERSIST>
@@ -544,6 +558,24 @@ template <int NT>
 mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   const int pd = g_ring_depth;
   const bool persist = g_persist < 0 ? M > 1 : g_persist != 0;
+  if (!persist && M == 1 && NT == 1) {
+    // few row tiles: more waves per tile so that every SIMD has work
+    const int cus = cu_count();
+    // measured on the benchmark shapes: 16 waves per tile up to 1.5 tiles per compute unit, else 8
+    // (four workgroups of 8 waves fill the 32 wave slots of a compute unit)
+    int waves = g_gemv_waves > 0 ? g_gemv_waves : (2 * h.T <= 3 * cus ? 16 : 8);
+    if (waves == 16) {
+      if (mm_lds_bytes(h, 1, 2, false, 16) <= 53 * 1024) return launch_gemv<2, 53 * 1024, 16>(h, d, X, Y, s);
+      if (mm_lds_bytes(h, 1, 2, false, 16) <= 80 * 1024) return launch_gemv<2, 80 * 1024, 16>(h, d, X, Y, s);
+      if (mm_lds_bytes(h, 1, 2, false, 16) <= 160 * 1024) return launch_gemv<2, 160 * 1024, 16>(h, d, X, Y, s);
+    }
+    if (waves >= 8) {
+      if (mm_lds_bytes(h, 1, 2, false, 8) <= 32 * 1024) return launch_gemv<2, 32 * 1024, 8>(h, d, X, Y, s);
+      if (mm_lds_bytes(h, 1, 2, false, 8) <= 53 * 1024) return launch_gemv<2, 53 * 1024, 8>(h, d, X, Y, s);
+      if (mm_lds_bytes(h, 1, 2, false, 8) <= 80 * 1024) return launch_gemv<2, 80 * 1024, 8>(h, d, X, Y, s);
+      if (mm_lds_bytes(h, 1, 2, false, 8) <= 160 * 1024) return launch_gemv<2, 160 * 1024, 8>(h, d, X, Y, s);
+    }
+  }
   if (!persist) {
     if (pd == 2 && mm_lds_bytes(h, M, 2, false) <= 26 * 1024) return launch_mm<NT, 2, 26 * 1024, false>(h, d, X, Y, M, s);
     if (pd == 4 && mm_lds_bytes(h, M, 4, false) <= 32 * 1024) return launch_mm<NT, 4, 32 * 1024, false>(h, d, X, Y, M, s);
@@ -586,11 +618,12 @@ extern "C" {
 // Tuning hook for sweeps; not part of the supported interface and not thread safe.
 // key 0: ring depth (code blocks in flight per wave) where it fits the small LDS classes, 0 = automatic;
 // key 2: cap on the number of persistent workgroups, 0 = automatic; key 3: 0 one workgroup per tile,
-// 1 persistent workgroups, -1 automatic.
+// 1 persistent workgroups, -1 automatic; key 4: waves per tile of the per-tile GEMV (4, 8, 16), 0 automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
   if (key == 2) g_max_blocks = value;
   if (key == 3) g_persist = value;
+  if (key == 4) g_gemv_waves = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
