@@ -214,9 +214,10 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // batch-related folded away: one activation row, only batch column 0 of the accumulator is parked
 // and summed, 16 lanes per row for the outliers with a DPP row reduction.
 //
-// WV = waves per workgroup.  Four by default; the per-tile GEMV uses 8 or 16 when the matrix has so
-// few row tiles that four waves per tile would leave most of a compute unit's SIMD slots empty
-// (4096 rows = 256 tiles = one tile per compute unit).
+// WV = waves per workgroup (4, 8 or 16), all working on the same tile.  More waves per tile fill
+// the 32 wave slots of a compute unit with fewer workgroups (less LDS for staged operands per
+// wave) and keep every SIMD busy when the matrix has few row tiles (4096 rows = 256 tiles = one
+// tile per compute unit).
 template <int NT, int PD, int LDSB, bool PERSIST, bool GEMV, int WV = 4>
 __global__ void __launch_bounds__(WV * 64)
 mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M_arg) {
@@ -224,7 +225,6 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT) && (!GEMV || NT == 1), "ring depth / batch tiles");
   const int M = GEMV ? 1 : M_arg;
   __shared__ __align__(16) unsigned char lds[LDSB];
-  static_assert(WV == 4 || (GEMV && !PERSIST), "more than four waves only for the per-tile GEMV");
   constexpr uint32_t W = WV;
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -234,7 +234,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   const uint32_t units_bytes = 32u * C;
   const uint32_t rowbytes = 2u * b.K + 16u;  // + 16: rows of a batch start in different LDS banks
   unsigned char* const ring = lds;
-  unsigned char* const side0 = lds + W * PD * 1024 + (PERSIST ? NT * 4096 : 0);
+  unsigned char* const side0 = lds + W * PD * 1024 + (PERSIST ? W * NT * 1024 : 0);
   unsigned char* const units = side0 + (PERSIST ? 2 : 1) * b.side_bytes;
   unsigned char* const xs = units + units_bytes;
   const DecodeConsts kc = make_consts();
@@ -399,7 +399,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
         const uint32_t row = tile * 16 + tid;
         if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)t0);
       }
-    } else {
+    } else if (WV == 4 || wv < 4) {
       const uint32_t row = tile * 16 + orow;
       float t0 = oa0, t1 = oa1;
 #pragma unroll
@@ -502,7 +502,8 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
 // reduction slots and a second side-record buffer), side record, unit table, activation rows.
 size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, bool persist, int waves = 4) {
   const size_t NT = M > 16 ? 2 : 1;
-  return (size_t)waves * PD * 1024 + (persist ? NT * 4096 + 2 * h.side_bytes : h.side_bytes) + 32ull * (h.B2 + h.B4) +
+  return (size_t)waves * PD * 1024 + (persist ? waves * NT * 1024 + 2 * h.side_bytes : h.side_bytes) +
+         32ull * (h.B2 + h.B4) +
          (size_t)M * (2ull * h.K + 16);
 }
 
@@ -512,6 +513,7 @@ int g_ring_depth = 0;   // 0 = automatic
 int g_max_blocks = 0;   // 0 = automatic
 int g_persist = -1;     // -1 = automatic (persistent workgroups for M > 1)
 int g_gemv_waves = 0;   // 0 = automatic (4, 8 or 16 waves per tile for the per-tile GEMV)
+int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
 int g_cu_count = 0;
 
 int cu_count() {
@@ -530,6 +532,19 @@ int cu_count() {
 template <int PD, int LDSB, int WV>
 mpq_status launch_gemv(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, hipStream_t s) {
   hipLaunchKernelGGL((mpq_mm_kernel<1, PD, LDSB, false, true, WV>), dim3((unsigned)h.T), dim3(WV * 64), 0, s, d, X, Y, 1);
+  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+}
+
+// Persistent batch kernel with WV waves per workgroup; one or two workgroups per compute unit.
+template <int NT, int PD, int LDSB, int WV>
+mpq_status launch_batch(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  size_t per_cu = kLdsPerCu / LDSB;
+  if (per_cu * WV > 32) per_cu = 32 / WV;
+  if (per_cu < 1) per_cu = 1;
+  long grid = (long)cu_count() * (long)per_cu;
+  if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
+  if (grid > h.T) grid = h.T;
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, true, false, WV>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
@@ -585,6 +600,16 @@ mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
     if (mm_lds_bytes(h, M, 4, false) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024, false>(h, d, X, Y, M, s);
     if (mm_lds_bytes(h, M, 6, false) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024, false>(h, d, X, Y, M, s);
   }
+  if (persist && M > 1 && g_batch_waves != 4) {
+    // many waves share one copy of the activations: 16 (or 8) waves per workgroup
+    if (g_batch_waves != 8) {
+      if (mm_lds_bytes(h, M, 2, true, 16) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 16>(h, d, X, Y, M, s);
+      if (mm_lds_bytes(h, M, 2, true, 16) <= 160 * 1024) return launch_batch<NT, 2, 160 * 1024, 16>(h, d, X, Y, M, s);
+    }
+    if (mm_lds_bytes(h, M, 2, true, 8) <= 53 * 1024) return launch_batch<NT, 2, 53 * 1024, 8>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 2, true, 8) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 8>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 3, true, 8) <= 160 * 1024) return launch_batch<NT, 3, 160 * 1024, 8>(h, d, X, Y, M, s);
+  }
   if (pd == 2 && mm_lds_bytes(h, M, 2, true) <= 40 * 1024) return launch_mm<NT, 2, 40 * 1024, true>(h, d, X, Y, M, s);
   if (pd == 4 && mm_lds_bytes(h, M, 4, true) <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024, true>(h, d, X, Y, M, s);
   if (mm_lds_bytes(h, M, 3, true) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024, true>(h, d, X, Y, M, s);
@@ -618,12 +643,14 @@ extern "C" {
 // Tuning hook for sweeps; not part of the supported interface and not thread safe.
 // key 0: ring depth (code blocks in flight per wave) where it fits the small LDS classes, 0 = automatic;
 // key 2: cap on the number of persistent workgroups, 0 = automatic; key 3: 0 one workgroup per tile,
-// 1 persistent workgroups, -1 automatic; key 4: waves per tile of the per-tile GEMV (4, 8, 16), 0 automatic.
+// 1 persistent workgroups, -1 automatic; key 4: waves per tile of the per-tile GEMV (4, 8, 16), 0 automatic;
+// key 5: waves per workgroup of the persistent batch kernel (4, 8, 16), 0 automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
   if (key == 2) g_max_blocks = value;
   if (key == 3) g_persist = value;
   if (key == 4) g_gemv_waves = value;
+  if (key == 5) g_batch_waves = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
