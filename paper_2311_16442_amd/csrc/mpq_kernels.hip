@@ -210,20 +210,15 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // are small (M = 1) because the vector ALU needs many waves per SIMD to stay busy; the persistent
 // form wins when staging the activations once per tile would dominate (M > 1).
 //
-// GEMV = true compiles the M = 1 case (the matrix-vector product of Algorithm 1) with everything
-// batch-related folded away: one activation row, only batch column 0 of the accumulator is parked
-// and summed, 16 lanes per row for the outliers with a DPP row reduction.
-//
 // WV = waves per workgroup (4, 8 or 16), all working on the same tile.  More waves per tile fill
 // the 32 wave slots of a compute unit with fewer workgroups (less LDS for staged operands per
 // wave) and keep every SIMD busy when the matrix has few row tiles (4096 rows = 256 tiles = one
 // tile per compute unit).
-template <int NT, int PD, int LDSB, bool PERSIST, bool GEMV, int WV = 4>
+template <int NT, int PD, int LDSB, bool PERSIST, int WV = 4>
 __global__ void __launch_bounds__(WV * 64)
-mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M_arg) {
+mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
 #pragma clang fp contract(off)
-  static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT) && (!GEMV || NT == 1), "ring depth / batch tiles");
-  const int M = GEMV ? 1 : M_arg;
+  static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT), "ring depth / batch tiles");
   __shared__ __align__(16) unsigned char lds[LDSB];
   constexpr uint32_t W = WV;
   const uint32_t tid = threadIdx.x;
@@ -265,7 +260,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
-  const unsigned char* xrow0 = GEMV ? xs : xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
+  const unsigned char* xrow0 = xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
   const unsigned char* xrow1 = xs + ((NT > 1 && i + 16 < (uint32_t)M) ? i + 16 : 0u) * rowbytes;
   const unsigned char* unitj = units + j * 8;
   const uint32_t ringl = ring0 + lane16;
@@ -273,10 +268,9 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   // q % Mp (and + 16) and every (16/Mp)-th word of the row
   const uint32_t orow = tid >> 4, oq = tid & 15u;
   uint32_t Mp = 1;
-  if (!GEMV)
-    while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
+  while (Mp < (uint32_t)M && Mp < 16) Mp <<= 1;
   const uint32_t om = oq & (Mp - 1), oes = oq / Mp, ostride = 16 / Mp;
-  const unsigned char* xo0 = GEMV ? xs : xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
+  const unsigned char* xo0 = xs + (om < (uint32_t)M ? om : 0u) * rowbytes;
   const unsigned char* xo1 = xs + ((NT > 1 && om + 16 < (uint32_t)M) ? om + 16 : 0u) * rowbytes;
 
   uint32_t slot = 0;        // ring slot of the next block to consume
@@ -355,12 +349,8 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
     constexpr uint32_t red_stride = PERSIST ? NT * 1024 : PD * 1024;  // bytes between waves
     unsigned char* const red = PERSIST ? lds + W * PD * 1024 : ring;
     float* myred = (float*)(red + wv * red_stride);
-    if (GEMV) {
-      if (i == 0) *(float4_t*)(myred + 4 * j) = acc0;  // batch column 0 only: red[wave][16 rows]
-    } else {
-      *(float4_t*)(myred + i * 16 + 4 * j) = acc0;
-      if (NT > 1) *(float4_t*)(myred + 256 + i * 16 + 4 * j) = acc1;
-    }
+    *(float4_t*)(myred + i * 16 + 4 * j) = acc0;
+    if (NT > 1) *(float4_t*)(myred + 256 + i * 16 + 4 * j) = acc1;
 
     // ---- (4) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
     //      are already in LDS
@@ -376,30 +366,13 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
         oa0 += v * (float)*(const half_t*)(xo0 + off);
         if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
       }
-      if (GEMV) {
-        // sum over the 16 lanes of the row with DPP row shifts; lane 15 of the row ends with the total
-        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x118, 0xf, 0xf, true));
-        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x114, 0xf, 0xf, true));
-        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x112, 0xf, 0xf, true));
-        oa0 += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa0), 0x111, 0xf, 0xf, true));
-        if (oq == 15) myred[16 + (orow & 3u)] = oa0;  // this wave's rows are orow = 4*wave .. 4*wave+3
-      } else {
-        for (uint32_t off = Mp; off < 16; off <<= 1) {
-          oa0 += __shfl_xor(oa0, off);
-          if (NT > 1) oa1 += __shfl_xor(oa1, off);
-        }
+      for (uint32_t off = Mp; off < 16; off <<= 1) {
+        oa0 += __shfl_xor(oa0, off);
+        if (NT > 1) oa1 += __shfl_xor(oa1, off);
       }
     }
     lds_barrier();
-    if (GEMV) {
-      if (tid < 16) {  // row tid of the tile: four partial sums and the outlier term, in a fixed order
-        float t0 = ((const float*)(red + (tid >> 2) * red_stride))[16 + (tid & 3u)];
-#pragma unroll
-        for (uint32_t w2 = 0; w2 < W; ++w2) t0 += ((const float*)(red + w2 * red_stride))[tid];
-        const uint32_t row = tile * 16 + tid;
-        if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)t0);
-      }
-    } else if (WV == 4 || wv < 4) {
+    if (WV == 4 || wv < 4) {
       const uint32_t row = tile * 16 + orow;
       float t0 = oa0, t1 = oa1;
 #pragma unroll
@@ -413,6 +386,160 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
         if (NT > 1 && oq + 16 < (uint32_t)M) Y[(size_t)(oq + 16) * b.N + row] = half_to_bits((half_t)t1);
       }
     }
+  }
+}
+
+// ------------------------------------------------------------------------------------ GEMV
+//
+// y = W x (Algorithm 1, the matrix-vector product at batch 1) with the outlier product of Sec. 4.3
+// fused in.  Same data movement and per-block arithmetic as the batch kernel above, with everything
+// batch-related folded away, and a different work split:
+//
+//   A workgroup of WV waves owns n consecutive 16-row tiles and treats their code blocks as ONE
+//   sequence (tile 0 block 0, ..., tile 0 block C-1, tile 1 block 0, ...) that goes round-robin to
+//   its waves.  A wave walks its share with a ring that stays full across tile boundaries, parks its
+//   partial sums of a tile (batch column 0 of the accumulator, 16 floats) when it crosses into the
+//   next tile and never waits for the other waves on the way: the workgroup meets once after the
+//   staged operands have landed and once before the partial sums are added up.  The longer sequence
+//   evens out the load of the waves (a tile of 19 blocks on 8 waves alone leaves five of them idle
+//   for a third of the time), and the activations, the unit table and the wave's own set-up are
+//   paid once per n tiles.
+//
+//   Outliers: groups of four waves (256 threads, 16 lanes per row) take the tiles in turn; the 16
+//   lanes of a row each take every 16th word of the row and are summed with DPP row shifts.
+template <int PD, int LDSB, int WV>
+__global__ void __launch_bounds__(WV * 64)
+mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg) {
+#pragma clang fp contract(off)
+  static_assert(PD >= 1 && PD <= 8 && WV % 4 == 0, "ring depth / waves");
+  __shared__ __align__(16) unsigned char lds[LDSB];
+  constexpr uint32_t W = WV;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
+  const uint32_t C = b.C, T = b.T;
+  const uint32_t tile0 = blockIdx.x * (uint32_t)n_arg;
+  const uint32_t n = T - tile0 < (uint32_t)n_arg ? T - tile0 : (uint32_t)n_arg;  // tiles of this workgroup
+  // LDS layout: ring | partial sums [n][W + 1][16] | side records [n] | unit table | activations
+  const uint32_t units_bytes = 32u * C;
+  unsigned char* const ring = lds;
+  float* const red = (float*)(lds + W * PD * 1024);
+  unsigned char* const side0 = lds + W * PD * 1024 + (uint32_t)n_arg * (W + 1) * 64;
+  unsigned char* const units = side0 + (uint32_t)n_arg * b.side_bytes;
+  unsigned char* const xs = units + units_bytes;
+  const DecodeConsts kc = make_consts();
+
+  // ---- (1) requests, oldest first: staged operands, then this wave's first code blocks
+  const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
+  for (uint32_t t = 0; t < n; ++t)
+    dma_linear<W>(tileptr + (size_t)t * b.tile_stride, lds_addr(side0) + t * b.side_bytes, b.side_bytes, wv, lane16);
+  dma_linear<W>(b.units, lds_addr(units), units_bytes, wv, lane16);
+  dma_linear<W>((const unsigned char*)X, lds_addr(xs), 2u * b.K, wv, lane16);
+  // this wave's blocks: positions wv, wv + W, wv + 2W, ... of the n*C blocks of the workgroup
+  const uint32_t ring0 = lds_addr(ring) + wv * (PD * 1024);
+  const unsigned char* rbase = tileptr + b.codes_off;  // code blocks of the tile being requested
+  uint32_t rc = wv, rt = 0;                            // next request: block rc of tile rt (rt = n: none left)
+  while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
+  uint32_t inflight = 0;
+#pragma unroll
+  for (uint32_t r = 0; r < PD; ++r) {
+    if (rt < n) {
+      dma16(rbase + rc * 1024u, lane16, ring0 + r * 1024u);
+      ++inflight;
+      rc += W;
+      while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
+    }
+  }
+  wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
+  lds_barrier();
+
+  const unsigned char* unitj = units + j * 8;
+  const uint32_t ringl = ring0 + lane16;
+  uint32_t slot = 0;  // ring slot of the next block to consume
+  uint32_t c = wv;    // next block of this wave inside the current tile (>= C: none in this tile)
+  for (uint32_t t = 0; t < n; ++t) {
+    const unsigned char* side = side0 + t * b.side_bytes;
+    const unsigned char* m1i = side + i * 2;
+    const unsigned char* m2i = side + b.off_m2 + i * 4;
+    float4_t acc0 = {0.f, 0.f, 0.f, 0.f};
+#define MPQ_GEMV_STEP(TWO, P)                                                                         \
+  {                                                                                                   \
+    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
+    const uint4 bv0 = *(const uint4*)(xb0 + 16 * (P));                                                \
+    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
+                                                  __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
+  }
+#define MPQ_GEMV_BLOCK_HEAD                                                                            \
+  /* requests younger than the block needed now: the other blocks in flight */                        \
+  if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
+  uint4 q;                                                                                            \
+  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
+  --inflight;                                                                                         \
+  if (rt < n) { /* refill the freed slot with the next block of this wave's sequence */               \
+    dma16(rbase + rc * 1024u, lane16, ring0 + slot * 1024u);                                          \
+    ++inflight;                                                                                       \
+    rc += W;                                                                                          \
+    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }                              \
+  }                                                                                                   \
+  slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
+  const uint2 ue = *(const uint2*)(unitj + c * 32u);                                                  \
+  const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));                                     \
+  const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));                                         \
+  const half_t s1 = scale_dequant(m1 & 0xFFu, m2); /* exactly 0 for a padding unit (zero meta entries) */ \
+  const half2_t s1p = {s1, s1};                                                                       \
+  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8))); /* 1024 + z1 */                    \
+  const unsigned char* xb0 = xs + ue.x;                                                               \
+  const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+    for (; c < (uint32_t)b.B2; c += W) {
+      MPQ_GEMV_BLOCK_HEAD
+      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      MPQ_GEMV_STEP(true, 0) MPQ_GEMV_STEP(true, 1) MPQ_GEMV_STEP(true, 2) MPQ_GEMV_STEP(true, 3)
+      MPQ_GEMV_STEP(true, 4) MPQ_GEMV_STEP(true, 5) MPQ_GEMV_STEP(true, 6) MPQ_GEMV_STEP(true, 7)
+    }
+    for (; c < C; c += W) {
+      MPQ_GEMV_BLOCK_HEAD
+      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+      MPQ_GEMV_STEP(false, 0) MPQ_GEMV_STEP(false, 1) MPQ_GEMV_STEP(false, 2) MPQ_GEMV_STEP(false, 3)
+    }
+#undef MPQ_GEMV_BLOCK_HEAD
+#undef MPQ_GEMV_STEP
+    c -= C;  // the sequence continues in the next tile
+    // accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3]; only batch column 0 is real
+    if (i == 0) *(float4_t*)(red + (t * (W + 1) + wv) * 16 + 4 * j) = acc0;
+  }
+
+  // ---- (2) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
+  //      are already in LDS.  Four waves per tile, 16 lanes per row.
+  {
+    const uint32_t otid = tid & 255u, orow = otid >> 4, oq = otid & 15u;
+    for (uint32_t t = wv >> 2; t < n; t += W / 4) {
+      const uint32_t* ostart = (const uint32_t*)(side0 + t * b.side_bytes + b.off_ot);
+      const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
+      const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
+      float oa = 0.f;
+      for (uint32_t e = rp0 + oq; e < rp1; e += 16) {
+        const uint32_t word = owords[e];
+        const float v = (float)bits_to_half((uint16_t)(word >> 16));
+        oa += v * (float)*(const half_t*)(xs + (word & 0xFFFFu) * 2u);
+      }
+      // sum over the 16 lanes of the row with DPP row shifts; lane 15 of the row ends with the total
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x118, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x114, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x112, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x111, 0xf, 0xf, true));
+      if (oq == 15) red[(t * (W + 1) + W) * 16 + orow] = oa;
+    }
+  }
+  lds_barrier();
+  // ---- (3) row r of tile t: the outlier term and the W partial sums, in a fixed order
+  if (tid < 16 * n) {
+    const uint32_t t = tid >> 4, r = tid & 15u;
+    const float* rt0 = red + t * (W + 1) * 16 + r;
+    float sum = rt0[W * 16];
+#pragma unroll
+    for (uint32_t w2 = 0; w2 < W; ++w2) sum += rt0[w2 * 16];
+    const uint32_t row = (tile0 + t) * 16 + r;
+    if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)sum);
   }
 }
 
@@ -536,7 +663,8 @@ constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
 int g_ring_depth = 0;   // 0 = automatic
 int g_max_blocks = 0;   // 0 = automatic
 int g_persist = -1;     // -1 = automatic (persistent workgroups for M > 1)
-int g_gemv_waves = 0;   // 0 = automatic (4, 8 or 16 waves per tile for the per-tile GEMV)
+int g_gemv_waves = 0;   // 0 = automatic (8 or 16 waves per workgroup of the GEMV)
+int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
 int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
 int g_cu_count = 0;
 
@@ -552,11 +680,63 @@ int cu_count() {
   return g_cu_count;
 }
 
-// Per-tile GEMV with WV waves per workgroup.
+// LDS bytes of the GEMV kernel: ring, partial sums, n side records, unit table, activations.
+size_t gemv_lds_bytes(const MpqHeader& h, int PD, int waves, int n) {
+  return (size_t)waves * PD * 1024 + (size_t)n * (waves + 1) * 64 + (size_t)n * h.side_bytes + 32ull * (h.B2 + h.B4) +
+         2ull * h.K;
+}
+
 template <int PD, int LDSB, int WV>
-mpq_status launch_gemv(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, hipStream_t s) {
-  hipLaunchKernelGGL((mpq_mm_kernel<1, PD, LDSB, false, true, WV>), dim3((unsigned)h.T), dim3(WV * 64), 0, s, d, X, Y, 1);
+mpq_status launch_gemv(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
+  const unsigned grid = (unsigned)((h.T + n - 1) / n);
+  hipLaunchKernelGGL((mpq_gemv_kernel<PD, LDSB, WV>), dim3(grid), dim3(WV * 64), 0, s, d, X, Y, n);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+}
+
+// GEMV with WV waves per workgroup and n tiles per workgroup in the smallest LDS class that holds
+// it.  Two code blocks per wave in flight: deeper rings were measured and change nothing.
+template <int WV>
+mpq_status gemv_waves(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
+  const size_t need = gemv_lds_bytes(h, 2, WV, n);
+  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV>(h, d, X, Y, n, s);
+  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV>(h, d, X, Y, n, s);
+  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV>(h, d, X, Y, n, s);
+  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV>(h, d, X, Y, n, s);
+  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV>(h, d, X, Y, n, s);
+  return MPQ_ERR_UNSUPPORTED;
+}
+
+// Work split of the GEMV (waves per workgroup, tiles per workgroup), from measurements on the
+// Llama2-7B / Llama3-8B / Llama2-70B shapes:
+//   - up to 1.5 tiles per compute unit: 16 waves on one tile, so that every SIMD has several waves;
+//   - else 8 waves on one tile if four such workgroups fit a compute unit (all 32 wave slots busy
+//     and the most workgroups to balance);
+//   - else (long rows: the staged activations crowd the LDS) 16 waves on two tiles when the
+//     workgroups still spread evenly over the compute units, which halves the staging per tile.
+mpq_status gemv_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, hipStream_t s) {
+  const int cus = cu_count();
+  int waves, n = 1;
+  if (2 * h.T <= 3 * cus) {
+    waves = 16;
+  } else if (gemv_lds_bytes(h, 2, 8, 1) <= 40 * 1024) {
+    waves = 8;
+  } else {
+    const int half = (h.T + 1) / 2;
+    if ((half % cus == 0 || half >= 4 * cus) && gemv_lds_bytes(h, 2, 16, 2) <= kLdsPerCu) {
+      waves = 16;
+      n = 2;
+    } else {
+      waves = gemv_lds_bytes(h, 2, 8, 1) <= 53 * 1024 ? 8 : 16;
+    }
+  }
+  if (g_gemv_waves > 0) waves = g_gemv_waves;
+  if (g_gemv_tiles > 0) n = g_gemv_tiles > 8 ? 8 : g_gemv_tiles;
+  while (n > 1 && gemv_lds_bytes(h, 2, waves, n) > kLdsPerCu) --n;
+  if (waves == 16) {
+    const mpq_status st = gemv_waves<16>(h, d, X, Y, n, s);
+    if (st != MPQ_ERR_UNSUPPORTED) return st;
+  }
+  return gemv_waves<8>(h, d, X, Y, n, s);
 }
 
 // Persistent batch kernel with WV waves per workgroup; one or two workgroups per compute unit.
@@ -568,13 +748,12 @@ mpq_status launch_batch(const MpqHeader& h, const DevBlob& d, const uint16_t* X,
   long grid = (long)cu_count() * (long)per_cu;
   if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
   if (grid > h.T) grid = h.T;
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, true, false, WV>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, true, WV>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
 template <int NT, int PD, int LDSB, bool PERSIST>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  constexpr bool kGemvOk = NT == 1;
   long grid = h.T;
   if (PERSIST) {  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
     size_t per_cu = kLdsPerCu / LDSB;
@@ -584,10 +763,7 @@ mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, ui
     if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
     if (grid > h.T) grid = h.T;
   }
-  if (kGemvOk && M == 1)
-    hipLaunchKernelGGL((mpq_mm_kernel<1, PD, LDSB, PERSIST, true>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
-  else
-    hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST, false>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
@@ -597,24 +773,6 @@ template <int NT>
 mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   const int pd = g_ring_depth;
   const bool persist = g_persist < 0 ? M > 1 : g_persist != 0;
-  if (!persist && M == 1 && NT == 1) {
-    // few row tiles: more waves per tile so that every SIMD has work
-    const int cus = cu_count();
-    // measured on the benchmark shapes: 16 waves per tile up to 1.5 tiles per compute unit, else 8
-    // (four workgroups of 8 waves fill the 32 wave slots of a compute unit)
-    int waves = g_gemv_waves > 0 ? g_gemv_waves : (2 * h.T <= 3 * cus ? 16 : 8);
-    if (waves == 16) {
-      if (mm_lds_bytes(h, 1, 2, false, 16) <= 53 * 1024) return launch_gemv<2, 53 * 1024, 16>(h, d, X, Y, s);
-      if (mm_lds_bytes(h, 1, 2, false, 16) <= 80 * 1024) return launch_gemv<2, 80 * 1024, 16>(h, d, X, Y, s);
-      if (mm_lds_bytes(h, 1, 2, false, 16) <= 160 * 1024) return launch_gemv<2, 160 * 1024, 16>(h, d, X, Y, s);
-    }
-    if (waves >= 8) {
-      if (mm_lds_bytes(h, 1, 2, false, 8) <= 32 * 1024) return launch_gemv<2, 32 * 1024, 8>(h, d, X, Y, s);
-      if (mm_lds_bytes(h, 1, 2, false, 8) <= 53 * 1024) return launch_gemv<2, 53 * 1024, 8>(h, d, X, Y, s);
-      if (mm_lds_bytes(h, 1, 2, false, 8) <= 80 * 1024) return launch_gemv<2, 80 * 1024, 8>(h, d, X, Y, s);
-      if (mm_lds_bytes(h, 1, 2, false, 8) <= 160 * 1024) return launch_gemv<2, 160 * 1024, 8>(h, d, X, Y, s);
-    }
-  }
   if (!persist) {
     if (pd == 2 && mm_lds_bytes(h, M, 2, false) <= 26 * 1024) return launch_mm<NT, 2, 26 * 1024, false>(h, d, X, Y, M, s);
     if (pd == 4 && mm_lds_bytes(h, M, 4, false) <= 32 * 1024) return launch_mm<NT, 4, 32 * 1024, false>(h, d, X, Y, M, s);
@@ -646,6 +804,7 @@ mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
 }
 
 mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  if (M == 1) return gemv_all(h, d, X, Y, s);
   if (mm_lds_bytes(h, 1, 3, true) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
   int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
   while (Mc > 1 && mm_lds_bytes(h, Mc, 3, true) > kLdsPerCu) --Mc;
@@ -667,14 +826,16 @@ extern "C" {
 // Tuning hook for sweeps; not part of the supported interface and not thread safe.
 // key 0: ring depth (code blocks in flight per wave) where it fits the small LDS classes, 0 = automatic;
 // key 2: cap on the number of persistent workgroups, 0 = automatic; key 3: 0 one workgroup per tile,
-// 1 persistent workgroups, -1 automatic; key 4: waves per tile of the per-tile GEMV (4, 8, 16), 0 automatic;
-// key 5: waves per workgroup of the persistent batch kernel (4, 8, 16), 0 automatic.
+// 1 persistent workgroups, -1 automatic (batch kernel); key 4: waves per workgroup of the GEMV (8, 16), 0 automatic;
+// key 5: waves per workgroup of the persistent batch kernel (4, 8, 16), 0 automatic; key 6: tiles per
+// workgroup of the GEMV (1..8), 0 automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
   if (key == 2) g_max_blocks = value;
   if (key == 3) g_persist = value;
   if (key == 4) g_gemv_waves = value;
   if (key == 5) g_batch_waves = value;
+  if (key == 6) g_gemv_tiles = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,

@@ -161,3 +161,30 @@ def test_outliers_reduce_to_csr_product(torch):
                        lg.row_ptr.astype(np.int64)), shape=(160, 1024))
     ref = A @ X[0].view(np.float16).astype(np.float64)
     assert rel_err(y.check_and_get(), ref)[0] <= TOL
+
+
+@pytest.mark.parametrize("waves,tiles", [(8, 1), (8, 2), (8, 3), (16, 1), (16, 2), (16, 5), (8, 8)])
+def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
+    # every work split of the matrix-vector product the library can choose (waves per workgroup x
+    # tiles per workgroup, forced through the tuning hook) on a ragged shape: 63 tiles, last one
+    # with 8 rows, a short tail super-group, fewer code blocks per tile (6) than waves
+    import ctypes
+    lg, om, pk = make(("ragged_rows", 1000, 704, 64, 4, 0.30, 0.02, True))
+    hook = mpq.lib().mpq_debug_set
+    hook.argtypes = [ctypes.c_int, ctypes.c_int]
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(7, 1, pk.K)
+    x = to_dev(torch, X[0].view(np.int16))
+    ref = om.gemm(X, threads=8)[0]
+    try:
+        hook(4, waves)
+        hook(6, tiles)
+        print("waves", waves, "tiles", tiles, flush=True)
+        y = Guarded(torch, pk.N)
+        mpq.gemv(pk.header, blob, x, y.view)
+        got = y.check_and_get()
+    finally:
+        hook(4, 0)
+        hook(6, 0)
+    e_floor, e_max = rel_err(got, ref)
+    assert e_floor <= TOL, (e_floor, e_max)
