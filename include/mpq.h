@@ -61,7 +61,8 @@ typedef enum {
 
 /* Shape of a matrix in the logical format. g2_axis: 0 = a second-order pair covers g2 consecutive
  * groups along K of one row (the layout the kernels implement); 1 = it covers the same K-group of
- * g2 consecutive rows (the paper's "direction of output channels", Sec. 2.2; host/pack only). */
+ * g2 consecutive rows (the paper's "direction of output channels", Sec. 2.2): described by the
+ * logical format, but this build's packer and kernels return MPQ_ERR_UNSUPPORTED for it. */
 typedef struct {
   int32_t N, K, g1, g2, g2_axis;
 } mpq_desc;

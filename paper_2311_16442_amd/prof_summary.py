@@ -2,7 +2,7 @@
 
   python -m paper_2311_16442_amd.prof_summary stats   <dir-of-kernel-trace-run>
   python -m paper_2311_16442_amd.prof_summary traffic <dir-of-FETCH_SIZE-run> <dir-of-WRITE_SIZE-run> \
-         --copy-bytes <bytes the calibration copy moved> [--kernel mpq_mm_kernel]
+         --copy-bytes <bytes the calibration copy moved> [--kernel mpq_gemv_kernel]
 
 `stats` prints calls / average / min / max duration per kernel from *_kernel_stats.csv and, for the
 product kernel, the same split by grid size from *_kernel_trace.csv.
@@ -79,12 +79,12 @@ def main():
     sub = ap.add_subparsers(dest="cmd", required=True)
     a = sub.add_parser("stats")
     a.add_argument("dir")
-    a.add_argument("--kernel", default="mpq_mm_kernel")
+    a.add_argument("--kernel", default="mpq_gemv_kernel")
     b = sub.add_parser("traffic")
     b.add_argument("fetch_dir")
     b.add_argument("write_dir")
     b.add_argument("--copy-bytes", type=float, required=True)
-    b.add_argument("--kernel", default="mpq_mm_kernel")
+    b.add_argument("--kernel", default="mpq_gemv_kernel")
     args = ap.parse_args()
     if args.cmd == "stats":
         stats(args.dir, args.kernel)
