@@ -188,3 +188,31 @@ def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
         hook(6, 0)
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (e_floor, e_max)
+
+
+@pytest.mark.parametrize("M", [2, 7, 16, 17, 32])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_large_batch_kernel_within_tolerance(torch, case, M):
+    # the kernel that stages the activations range by range, forced for every batch size through
+    # the tuning hook (by itself the library takes it for M > 8 or long rows)
+    import ctypes
+    lg, om, pk = make(case)
+    hook = mpq.lib().mpq_debug_set
+    hook.argtypes = [ctypes.c_int, ctypes.c_int]
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(500 + M, M, pk.K)
+    ref = om.gemm(X, threads=8)
+    print("case", case, "M", M, flush=True)
+    try:
+        hook(7, 1)
+        Y = Guarded(torch, M * pk.N)
+        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+        got = Y.check_and_get().reshape(M, pk.N)
+        Y2 = Guarded(torch, M * pk.N)
+        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M)
+        again = Y2.check_and_get().reshape(M, pk.N)
+    finally:
+        hook(7, -1)
+    e_floor, e_max = rel_err(got, ref)
+    assert e_floor <= TOL, (e_floor, e_max)
+    assert np.array_equal(got, again)
