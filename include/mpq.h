@@ -5,7 +5,7 @@
  * LLM Inference on GPU: 2/4/16-bit in a Weight Matrix with Asynchronous Dequantization"):
  * y = W x (and Y = X W^T for a small batch) where W is stored as
  *   - per-K-group 2-bit or 4-bit integer codes (Sec. 3.3 "Intra-weight Quantization": the bit width
- *     is chosen per group of input channels and is the same for every output channel),
+ *     is chosen per group of g1 input channels and is the same for every output channel),
  *   - a quantized first-order scale and an integer first-order zero point per (row, group), the
  *     scale being recovered by a second-order dequantization with an fp16 (scale, zero) pair
  *     (Sec. 2.2 eq. 5; Sec. 3.3; Algorithm 1 "1st s <- dequantize(1st s_int, 2nd z, 2nd s)"),
@@ -59,10 +59,10 @@ typedef enum {
   MPQ_ERR_HIP = 10             /* the HIP runtime reported a launch error */
 } mpq_status;
 
-/* Shape of a matrix in the logical format. g2_axis: 0 = a second-order pair covers g2 consecutive
- * groups along K of one row (the layout the kernels implement); 1 = it covers the same K-group of
- * g2 consecutive rows (the paper's "direction of output channels", Sec. 2.2): described by the
- * logical format, but this build's packer and kernels return MPQ_ERR_UNSUPPORTED for it. */
+/* Shape of a matrix in the logical format. g1 must be 16, 32, 64 or 128 (MPQ_ERR_UNSUPPORTED
+ * otherwise). g2_axis: 0 = a second-order pair covers g2 consecutive groups along K of one row (what
+ * the benchmark configurations state); 1 = it covers the same K-group of g2 consecutive rows (the
+ * paper's "direction of output channels", Sec. 2.2), with g2 a divisor or a multiple of 16. */
 typedef struct {
   int32_t N, K, g1, g2, g2_axis;
 } mpq_desc;

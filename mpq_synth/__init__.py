@@ -45,6 +45,7 @@ class MatrixSpec:
     f4: float = 0.10      # fraction of K-groups that are 4-bit
     p_o: float = 0.005    # outlier probability per weight inside 2-bit groups
     seed: int = BASE_SEED
+    g2_axis: int = 0      # 0: a second-order pair per g2 groups along K of a row; 1: per K-group of g2 rows
 
     @property
     def G(self) -> int:
@@ -149,8 +150,9 @@ def make_matrix(spec: MatrixSpec, z1_full_range: bool = False,
         z1 = rng.integers(0, 256, size=(N, G), dtype=np.uint8)
     else:
         z1 = (rng.integers(0, 256, size=(N, G), dtype=np.uint8) % hi_g.astype(np.uint8)[None, :]).astype(np.uint8)
-    s2 = f16_bits(np.exp(rng.normal(-6.0, 0.5, size=(N, S))))
-    z2 = f16_bits(rng.random(size=(N, S)))
+    shape2 = (N, S) if spec.g2_axis == 0 else (-(-N // spec.g2), G)
+    s2 = f16_bits(np.exp(rng.normal(-6.0, 0.5, size=shape2)))
+    z2 = f16_bits(rng.random(size=shape2))
     cols2 = np.nonzero(np.repeat(is4, g1) == 0)[0]
     row_ptr, col, val = draw_outliers(rng, N, cols2, spec.p_o)
     return Logical(spec, is4, codes, s_int, z1, s2, z2, row_ptr, col, val)
@@ -197,7 +199,7 @@ def stored_bytes(spec: MatrixSpec, n4: int, nnz: int) -> Dict[str, int]:
     out = {
         "codes": N * (n2 * g1 // 4 + n4 * g1 // 2),
         "s_int_z1": 2 * N * G,
-        "s2_z2": 4 * N * S,
+        "s2_z2": 4 * N * S if spec.g2_axis == 0 else 4 * (-(-N // spec.g2)) * G,
         "outliers": 4 * nnz,
         "row_ptr": 4 * (N + 1),
     }

@@ -87,7 +87,9 @@ class Matrix:
         self.val = _c(val, np.uint16)
 
     @classmethod
-    def from_logical(cls, lg, g2_axis=0):
+    def from_logical(cls, lg, g2_axis=None):
+        if g2_axis is None:
+            g2_axis = getattr(lg.spec, "g2_axis", 0)
         s = lg.spec
         return cls(s.N, s.K, s.g1, s.g2, lg.is4, lg.codes, lg.s_int, lg.z1, lg.s2, lg.z2,
                    lg.row_ptr, lg.col, lg.val, g2_axis)

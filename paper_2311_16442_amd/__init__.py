@@ -142,8 +142,10 @@ def pack(N, K, g1, g2, is4, codes, s_int, z1, s2, z2, row_ptr, col, val, g2_axis
     return Packed(blob, int(N), int(K), int(g1), int(g2), info["n4"], info["nnz"])
 
 
-def pack_logical(lg, g2_axis=0) -> Packed:
+def pack_logical(lg, g2_axis=None) -> Packed:
     s = lg.spec
+    if g2_axis is None:
+        g2_axis = getattr(s, "g2_axis", 0)
     return pack(s.N, s.K, s.g1, s.g2, lg.is4, lg.codes, lg.s_int, lg.z1, lg.s2, lg.z2,
                 lg.row_ptr, lg.col, lg.val, g2_axis)
 

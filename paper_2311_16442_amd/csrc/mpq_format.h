@@ -10,21 +10,33 @@
 // - the operand order of the 16x16x32 MFMA, which the small-batch product uses directly and the
 // matrix-vector product reads equally well.
 //
+// A unit always holds codes of one bit width, but for first-order groups shorter than a unit
+// (g1 = 16 or 32) it holds several groups: a "piece" is the part of a unit that belongs to one
+// group - PU2 = max(1, 64/g1) pieces per 2-bit unit, PU4 = max(1, 32/g1) per 4-bit unit.  The
+// pieces of a unit are consecutive groups of the unit's STREAM (all 2-bit groups in K order, or all
+// 4-bit groups in K order), so they need not be neighbours in K; every piece covers whole decode
+// steps of 8 columns.  For g1 >= 64 a unit is one piece (a half or quarter of a group).
+//
 //   header    256 B                       (MpqHeader)
-//   units     2 x uint32 [4*(B2+B4)]      per unit in stream order (2-bit units, then 4-bit units),
-//                                         ready for the kernels:
-//                 word 0 = byte offset of the unit's first activation in an fp16 row (2*k0)
-//                 word 1 = (stream_group * 32) | (super_group * 64) << 16: byte offsets of the
-//                          group's 16 rows inside the tile's meta1 / meta2 arrays
-//                 a padding unit (stream padded to a multiple of 4 units) has word 0 = 0 and
-//                 points at stream group G and super-group S, two extra all-zero entries of
-//                 meta1 / meta2: its scale decodes to exactly 0 without any test in the kernel
+//   units     2 x uint32 [4*(B2+B4)][PU2] per unit in stream order (2-bit units, then 4-bit units)
+//                                         and per piece, ready for the kernels (a 4-bit unit uses
+//                                         the first PU4 of its PU2 slots):
+//                 word 0 = byte offset of the piece's first activation in an fp16 row (2*k0)
+//                 word 1 = meta1 offset | meta2 offset << 16: byte offsets of the group's entry
+//                          inside the tile's meta1 / meta2 arrays (before the per-lane part)
+//                 a padding piece (stream padded to whole blocks, unused slots) has word 0 = 0
+//                 and points at the extra all-zero last entries of meta1 / meta2: its scale
+//                 decodes to exactly 0 without any test in the kernel
 //   tiles     T x tile_stride B           one self-contained record per 16-row tile, so that a
 //                                         workgroup finds everything it needs at one base address:
 //       side (side_bytes):
 //         meta1   (G+1) x 16 x 2 B  (s_int | z1 << 8) per (stream group, row); stream group order = all
 //                                 2-bit groups in K order, then all 4-bit groups, then one zero entry
-//         meta2   (S+1) x 16 x 4 B  (s2 | z2 << 16) per (super-group, row), then one zero entry
+//         meta2   (s2 | z2 << 16), 4 B each, then one zero entry; mpq_meta2_bytes() in all:
+//                   g2_axis 0: (S+1) x 16, per (super-group along K, row); lane part = 4*row
+//                   g2_axis 1: (G+1) x nsub, per (stream group, block of g2 rows inside the tile),
+//                              nsub = max(1, 16/g2) (g2 divides 16 or is a multiple of 16);
+//                              lane part = 4*(row / g2) (0 for g2 >= 16)
 //         outl    128 + 4*ocap B  uint32 start[17] (then zeros up to 128 B): start[r] = index of the first
 //                                 word of row r of the tile, start[16] = number of words; then
 //                                 uint32 word[ocap] = col | val << 16 (Sec. 2.3: one 32-bit word per
@@ -48,7 +60,7 @@
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 6u
+#define MPQ_VERSION 7u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024
@@ -72,6 +84,19 @@ typedef struct {
   uint64_t total_bytes;
   uint8_t pad[256 - 4 * 16 - 8 - 8 * 8 - 8];
 } MpqHeader;
+
+/* pieces (groups) per 2-bit / 4-bit unit, entries of meta2 per group for g2_axis 1, bytes of meta2 */
+static inline int32_t mpq_pu2(int32_t g1) { return g1 >= 64 ? 1 : 64 / g1; }
+static inline int32_t mpq_pu4(int32_t g1) { return g1 >= 32 ? 1 : 32 / g1; }
+static inline int32_t mpq_nsub(int32_t g2) { return g2 >= MPQ_TILE_ROWS ? 1 : MPQ_TILE_ROWS / g2; }
+static inline uint64_t mpq_meta2_bytes(const MpqHeader* h) {
+  return h->g2_axis == 0 ? 64ull * ((uint64_t)h->S + 1)
+                         : (4ull * (uint64_t)mpq_nsub(h->g2) * ((uint64_t)h->G + 1) + 15ull) / 16ull * 16ull;
+}
+/* offset of the all-zero entry of meta2 (what padding pieces point at) */
+static inline uint32_t mpq_meta2_zero(const MpqHeader* h) {
+  return h->g2_axis == 0 ? 64u * (uint32_t)h->S : 4u * (uint32_t)mpq_nsub(h->g2) * (uint32_t)h->G;
+}
 
 #ifdef __cplusplus
 static_assert(sizeof(MpqHeader) == 256, "header must be 256 bytes");

@@ -1,17 +1,18 @@
 // mpq_kernels.hip - gfx950 kernels and device entry points of the mixed-precision weight library.
 //
 // Kernels (all read the packed blob described in mpq_format.h):
-//   mpq_mm_kernel        Algorithm 1 (GEMV with asynchronous dequantization) re-designed for CDNA4,
-//                        for a batch of 1..32 activation rows, with the outlier product of
-//                        Sec. 4.3 fused in as a per-row correction.
+//   mpq_gemv_kernel      Algorithm 1 (GEMV with asynchronous dequantization) re-designed for CDNA4,
+//                        with the outlier product of Sec. 4.3 fused in as a per-row correction.
+//   mpq_mm_kernel        the same product for a batch of 2..32 activation rows that fit the LDS.
+//   mpq_mmr_kernel       the same for batches that do not: activations staged range by range.
 //   mpq_dequant_kernel   eq. 5 applied twice (scale, then weight), written out as row-major fp16.
 //   mpq_outlier_add_kernel  adds the CSR values to a dequantized matrix (dense + sparse, Sec. 2.3).
 //
-// Mapping shared by the kernels.  A workgroup owns one tile of 16 rows for all of K.  A wavefront
-// load of 1 KiB is one block: lane = j*16 + i holds the 16-byte unit j (of 4) of row i (of 16).
-// The four waves of the workgroup take the tile's blocks round-robin, first the 2-bit stream,
-// then the 4-bit stream.  A lane therefore always decodes codes of ONE row and ONE first-order
-// group, so the group's scale and zero point are per-lane scalars.
+// Mapping shared by the kernels.  A wavefront load of 1 KiB is one block: lane = j*16 + i holds the
+// 16-byte unit j (of 4) of row i (of a 16-row tile).  The blocks of a tile, first the 2-bit stream,
+// then the 4-bit stream, go round-robin to the waves that work on the tile.  A lane therefore
+// always decodes codes of ONE row and ONE first-order group, so the group's scale and zero point
+// are per-lane scalars.
 //
 // Per-weight arithmetic (bit-exact to the definition in mpq.h):
 //   a mask isolates two codes (low / high half-word of a dword); OR-ing 0x6400 into each half
@@ -37,6 +38,7 @@ struct DevBlob {
   uint32_t side_bytes;         // meta1 | meta2 | outlier record at the head of a tile record
   uint32_t codes_off;          // offset of the code blocks inside a tile record
   uint32_t off_m2, off_ot;     // offsets of meta2 and of the outlier record inside the side part
+  uint32_t m2_shift;           // lane part of a meta2 address = 4 * (row >> m2_shift)
   int32_t N, K, G, S, B2, C, T;
 };
 
@@ -174,6 +176,23 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
   return uint4{a[0], a[1], a[2], a[3]};
 }
 
+// Scale, zero point and activation offset of the NP pieces of a unit (one piece per first-order
+// group that the unit touches; one piece for g1 >= 64).  ue points at the unit's table entries.
+template <int NP>
+__device__ __forceinline__ void load_pieces(const unsigned char* ue, const unsigned char* m1i, const unsigned char* m2i,
+                                            half2_t (&s1p)[NP], half_t (&zb)[NP], uint32_t (&xoff)[NP]) {
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    const uint2 e = *(const uint2*)(ue + 8 * q);
+    const uint32_t m1 = *(const uint16_t*)(m1i + (e.y & 0xFFFFu));
+    const uint32_t m2 = *(const uint32_t*)(m2i + (e.y >> 16));
+    const half_t s1 = scale_dequant(m1 & 0xFFu, m2);  // exactly 0 for a padding piece (zero meta entries)
+    s1p[q] = half2_t{s1, s1};
+    zb[q] = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
+    xoff[q] = e.x;
+  }
+}
+
 // ------------------------------------------------------------------------------------ product
 //
 // Y[m][n] = sum_k X[m][k] W[n][k] + outliers, 1 <= M <= 16*NT.  Persistent workgroups of four
@@ -214,7 +233,7 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 // the 32 wave slots of a compute unit with fewer workgroups (less LDS for staged operands per
 // wave) and keep every SIMD busy when the matrix has few row tiles (4096 rows = 256 tiles = one
 // tile per compute unit).
-template <int NT, int PD, int LDSB, bool PERSIST, int WV = 4>
+template <int NT, int PD, int LDSB, bool PERSIST, int WV = 4, int PU = 1>
 __global__ void __launch_bounds__(WV * 64)
 mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
 #pragma clang fp contract(off)
@@ -226,7 +245,8 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
   const uint32_t C = b.C, T = b.T, grid = gridDim.x;
   // LDS layout: ring | reduction slots | side record x 2 | unit table | activation rows
-  const uint32_t units_bytes = 32u * C;
+  constexpr int PU4 = PU > 1 ? PU / 2 : 1;   // pieces per 2-bit unit (PU) and per 4-bit unit
+  const uint32_t units_bytes = 32u * PU * C;
   const uint32_t rowbytes = 2u * b.K + 16u;  // + 16: rows of a batch start in different LDS banks
   unsigned char* const ring = lds;
   unsigned char* const side0 = lds + W * PD * 1024 + (PERSIST ? W * NT * 1024 : 0);
@@ -262,7 +282,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 
   const unsigned char* xrow0 = xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
   const unsigned char* xrow1 = xs + ((NT > 1 && i + 16 < (uint32_t)M) ? i + 16 : 0u) * rowbytes;
-  const unsigned char* unitj = units + j * 8;
+  const unsigned char* unitj = units + j * (8 * PU);
   const uint32_t ringl = ring0 + lane16;
   // outlier / output mapping: 16 consecutive lanes share row `orow`; lane q takes batch column
   // q % Mp (and + 16) and every (16/Mp)-th word of the row
@@ -286,25 +306,26 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
     if (tile + grid < T) dma_linear<W>(tileptr, lds_addr(side0 + (par ^ 1u) * b.side_bytes), b.side_bytes, wv, lane16);
     since_side = 0;
     const unsigned char* m1i = side + i * 2;
-    const unsigned char* m2i = side + b.off_m2 + i * 4;
+    const unsigned char* m2i = side + b.off_m2 + (i >> b.m2_shift) * 4;
 
     // ---- (2) this wave's blocks of the tile, in order
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #define MPQ_MM_STEP(TWO, P)                                                                           \
   {                                                                                                   \
-    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
-    const uint4 bv0 = *(const uint4*)(xb0 + 16 * (P));                                                \
+    constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP, PO = (P) % SPP;          \
+    const uint4 av = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                                  \
+    const uint4 bv0 = *(const uint4*)(xrow0 + xoff[Q] + 16 * PO);                                     \
     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
                                                   __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
     if (NT > 1) {                                                                                     \
-      const uint4 bv1 = *(const uint4*)(xb1 + 16 * (P));                                              \
+      const uint4 bv1 = *(const uint4*)(xrow1 + xoff[Q] + 16 * PO);                                   \
       acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                  \
                                                     __builtin_bit_cast(half8_t, bv1), acc1, 0, 0, 0); \
     }                                                                                                 \
   }
 // Fetch of the next block of this wave (wait, read its ring slot, refill the slot) and the
-// per-unit set-up; the 2-bit blocks of a tile come first in the wave's sequence, then the 4-bit ones.
-#define MPQ_MM_BLOCK_HEAD                                                                              \
+// per-piece set-up; the 2-bit blocks of a tile come first in the wave's sequence, then the 4-bit ones.
+#define MPQ_MM_BLOCK_HEAD(NP)                                                                          \
   /* Requests younger than the block needed now: the other blocks in flight (stricter than            \
      necessary when a side-record request sits between them, never laxer). */                         \
   if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
@@ -319,25 +340,20 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
     if (rc >= C) { rc = wv; rtile += grid; rbase += tilestep; }                                       \
   }                                                                                                   \
   slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
-  const uint2 ue = *(const uint2*)(unitj + c * 32u);                                                  \
-  const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));                                     \
-  const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));                                         \
-  const half_t s1 = scale_dequant(m1 & 0xFFu, m2); /* exactly 0 for a padding unit (zero meta entries) */ \
-  const half2_t s1p = {s1, s1};                                                                       \
-  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8))); /* 1024 + z1 */                    \
-  const unsigned char* xb0 = xrow0 + ue.x;                                                            \
-  const unsigned char* xb1 = xrow1 + ue.x;                                                            \
-  (void)xb1;                                                                                          \
+  half2_t s1p[NP];                                                                                    \
+  half_t zb[NP];                                                                                      \
+  uint32_t xoff[NP];                                                                                  \
+  load_pieces<NP>(unitj + c * (32u * PU), m1i, m2i, s1p, zb, xoff);                                   \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     uint32_t c = wv;
     for (; c < (uint32_t)b.B2; c += W) {
-      MPQ_MM_BLOCK_HEAD
+      MPQ_MM_BLOCK_HEAD(PU)
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
       MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
       MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
     }
     for (; c < C; c += W) {
-      MPQ_MM_BLOCK_HEAD
+      MPQ_MM_BLOCK_HEAD(PU4)
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
     }
@@ -588,7 +604,7 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
 #define MPQ_R_TILE(TT, A0, A1)                                                                         \
   if ((TT) < Rn) {                                                                                    \
     const unsigned char* m1i = sides + (TT) * b.side_bytes + i * 2;                                   \
-    const unsigned char* m2i = sides + (TT) * b.side_bytes + b.off_m2 + i * 4;                        \
+    const unsigned char* m2i = sides + (TT) * b.side_bytes + b.off_m2 + (i >> b.m2_shift) * 4;        \
     for (; c < n2; c += W) {                                                                          \
       MPQ_R_HEAD(a2 + c)                                                                              \
       const unsigned char* xb0 = xb2 + c * (8192u * NT);                                              \
@@ -692,7 +708,7 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
 //
 //   Outliers: groups of four waves (256 threads, 16 lanes per row) take the tiles in turn; the 16
 //   lanes of a row each take every 16th word of the row and are summed with DPP row shifts.
-template <int PD, int LDSB, int WV>
+template <int PD, int LDSB, int WV, int PU = 1>
 __global__ void __launch_bounds__(WV * 64)
 mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg) {
 #pragma clang fp contract(off)
@@ -706,7 +722,8 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
   const uint32_t tile0 = blockIdx.x * (uint32_t)n_arg;
   const uint32_t n = T - tile0 < (uint32_t)n_arg ? T - tile0 : (uint32_t)n_arg;  // tiles of this workgroup
   // LDS layout: ring | partial sums [n][W + 1][16] | side records [n] | unit table | activations
-  const uint32_t units_bytes = 32u * C;
+  constexpr int PU4 = PU > 1 ? PU / 2 : 1;  // pieces per 2-bit unit (PU) and per 4-bit unit
+  const uint32_t units_bytes = 32u * PU * C;
   unsigned char* const ring = lds;
   float* const red = (float*)(lds + W * PD * 1024);
   unsigned char* const side0 = lds + W * PD * 1024 + (uint32_t)n_arg * (W + 1) * 64;
@@ -738,23 +755,24 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
   wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
-  const unsigned char* unitj = units + j * 8;
+  const unsigned char* unitj = units + j * (8 * PU);
   const uint32_t ringl = ring0 + lane16;
   uint32_t slot = 0;  // ring slot of the next block to consume
   uint32_t c = wv;    // next block of this wave inside the current tile (>= C: none in this tile)
   for (uint32_t t = 0; t < n; ++t) {
     const unsigned char* side = side0 + t * b.side_bytes;
     const unsigned char* m1i = side + i * 2;
-    const unsigned char* m2i = side + b.off_m2 + i * 4;
+    const unsigned char* m2i = side + b.off_m2 + (i >> b.m2_shift) * 4;
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f};
 #define MPQ_GEMV_STEP(TWO, P)                                                                         \
   {                                                                                                   \
-    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
-    const uint4 bv0 = *(const uint4*)(xb0 + 16 * (P));                                                \
+    constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP, PO = (P) % SPP;          \
+    const uint4 av = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                                  \
+    const uint4 bv0 = *(const uint4*)(xs + xoff[Q] + 16 * PO);                                        \
     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
                                                   __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
   }
-#define MPQ_GEMV_BLOCK_HEAD                                                                            \
+#define MPQ_GEMV_BLOCK_HEAD(NP)                                                                        \
   /* requests younger than the block needed now: the other blocks in flight */                        \
   if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
   uint4 q;                                                                                            \
@@ -767,22 +785,19 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
     while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }                              \
   }                                                                                                   \
   slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
-  const uint2 ue = *(const uint2*)(unitj + c * 32u);                                                  \
-  const uint32_t m1 = *(const uint16_t*)(m1i + (ue.y & 0xFFFFu));                                     \
-  const uint32_t m2 = *(const uint32_t*)(m2i + (ue.y >> 16));                                         \
-  const half_t s1 = scale_dequant(m1 & 0xFFu, m2); /* exactly 0 for a padding unit (zero meta entries) */ \
-  const half2_t s1p = {s1, s1};                                                                       \
-  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8))); /* 1024 + z1 */                    \
-  const unsigned char* xb0 = xs + ue.x;                                                               \
+  half2_t s1p[NP];                                                                                    \
+  half_t zb[NP];                                                                                      \
+  uint32_t xoff[NP];                                                                                  \
+  load_pieces<NP>(unitj + c * (32u * PU), m1i, m2i, s1p, zb, xoff);                                   \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     for (; c < (uint32_t)b.B2; c += W) {
-      MPQ_GEMV_BLOCK_HEAD
+      MPQ_GEMV_BLOCK_HEAD(PU)
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
       MPQ_GEMV_STEP(true, 0) MPQ_GEMV_STEP(true, 1) MPQ_GEMV_STEP(true, 2) MPQ_GEMV_STEP(true, 3)
       MPQ_GEMV_STEP(true, 4) MPQ_GEMV_STEP(true, 5) MPQ_GEMV_STEP(true, 6) MPQ_GEMV_STEP(true, 7)
     }
     for (; c < C; c += W) {
-      MPQ_GEMV_BLOCK_HEAD
+      MPQ_GEMV_BLOCK_HEAD(PU4)
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_GEMV_STEP(false, 0) MPQ_GEMV_STEP(false, 1) MPQ_GEMV_STEP(false, 2) MPQ_GEMV_STEP(false, 3)
     }
@@ -836,10 +851,12 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
 // (four) neighbouring lanes write the 128 (64) contiguous bytes of one (row, unit) - full cache
 // lines per store instruction instead of 64 scattered 16-byte pieces.  The kernel is bound by
 // HBM writes: 2 bytes out per weight against 0.33 bytes in.
+template <int PU>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 #pragma clang fp contract(off)
   constexpr int PAIR = 144;  // LDS bytes per (row, unit): 128 + 16 so that lanes fall into different banks
+  constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
@@ -848,47 +865,50 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const uint2* units = (const uint2*)b.units;
   const DecodeConsts kc = make_consts();
   unsigned char* mine = turn[wv];
+  const unsigned char* m1i = tile + i * 2;
+  const unsigned char* m2i = tile + b.off_m2 + (i >> b.m2_shift) * 4;
   for (int c = wv; c < b.C; c += 4) {
     const bool two = c < b.B2;
     const uint4 q = ((const uint4*)(tile + b.codes_off))[c * 64 + lane];
-    const uint2 ue = units[4 * c + j];
-    const uint32_t m1 = *(const uint16_t*)(tile + (ue.y & 0xFFFFu) + i * 2);
-    const uint32_t m2 = *(const uint32_t*)(tile + b.off_m2 + (ue.y >> 16) + i * 4);
-    const half_t s1 = scale_dequant(m1 & 0xFFu, m2);
-    const half2_t s1p = {s1, s1};
-    const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));
+    const unsigned char* ue = b.units + (size_t)(4 * c + j) * (8 * PU);
     const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     uint4* dst = (uint4*)(mine + lane * PAIR);
+#define MPQ_DQ_STEP(TWO, P)                                                                   \
+  {                                                                                           \
+    constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                  \
+    dst[P] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                                  \
+  }
     if (two) {
+      half2_t s1p[PU];
+      half_t zb[PU];
+      uint32_t xoff[PU];
+      load_pieces<PU>(ue, m1i, m2i, s1p, zb, xoff);
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
-      dst[0] = decode_step<true, 0>(lo, hi, s1p, zb, kc);
-      dst[1] = decode_step<true, 1>(lo, hi, s1p, zb, kc);
-      dst[2] = decode_step<true, 2>(lo, hi, s1p, zb, kc);
-      dst[3] = decode_step<true, 3>(lo, hi, s1p, zb, kc);
-      dst[4] = decode_step<true, 4>(lo, hi, s1p, zb, kc);
-      dst[5] = decode_step<true, 5>(lo, hi, s1p, zb, kc);
-      dst[6] = decode_step<true, 6>(lo, hi, s1p, zb, kc);
-      dst[7] = decode_step<true, 7>(lo, hi, s1p, zb, kc);
+      MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
+      MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
     } else {
+      half2_t s1p[PU4];
+      half_t zb[PU4];
+      uint32_t xoff[PU4];
+      load_pieces<PU4>(ue, m1i, m2i, s1p, zb, xoff);
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
-      dst[0] = decode_step<false, 0>(lo, hi, s1p, zb, kc);
-      dst[1] = decode_step<false, 1>(lo, hi, s1p, zb, kc);
-      dst[2] = decode_step<false, 2>(lo, hi, s1p, zb, kc);
-      dst[3] = decode_step<false, 3>(lo, hi, s1p, zb, kc);
+      MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
     }
+#undef MPQ_DQ_STEP
     // the wave's own LDS area: its lanes run in lockstep, only the LDS counter has to drain
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    const int pieces = two ? 8 : 4;           // 16-byte pieces per (row, unit)
+    const int chunks = two ? 8 : 4;           // 16-byte chunks (decode steps) per (row, unit)
     const int shift = two ? 3 : 2;
-    const int piece = lane & (pieces - 1);
-    for (int s = 0; s < pieces; ++s) {
+    const int spp = chunks / (two ? PU : PU4);  // chunks per piece
+    const int chunk = lane & (chunks - 1);
+    for (int s = 0; s < chunks; ++s) {
       const int pair = (lane >> shift) + s * (64 >> shift);  // lane index (unit * 16 + row) that decoded it
       const int prow = blockIdx.x * 16 + (pair & 15);
-      const uint2 pu = units[4 * c + (pair >> 4)];
-      const uint4 v = *(const uint4*)(mine + pair * PAIR + piece * 16);
-      // padding units point at the zero scale entries; padding rows lie beyond N
+      const uint2 pu = units[(4 * c + (pair >> 4)) * PU + chunk / spp];  // the chunk's piece
+      const uint4 v = *(const uint4*)(mine + pair * PAIR + chunk * 16);
+      // padding pieces point at the zero scale entries; padding rows lie beyond N
       if ((pu.y & 0xFFFFu) != 32u * (uint32_t)b.G && prow < b.N)
-        *(uint4*)((unsigned char*)Wout + ((size_t)prow * b.K) * 2 + pu.x + piece * 16) = v;
+        *(uint4*)((unsigned char*)Wout + ((size_t)prow * b.K) * 2 + pu.x + (chunk % spp) * 16) = v;
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next block overwrites the area
   }
@@ -928,7 +948,10 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   d->side_bytes = (uint32_t)h->side_bytes;
   d->codes_off = (uint32_t)h->codes_off;
   d->off_m2 = 32u * ((uint32_t)h->G + 1);
-  d->off_ot = d->off_m2 + 64u * ((uint32_t)h->S + 1);
+  d->off_ot = d->off_m2 + (uint32_t)mpq_meta2_bytes(h);
+  d->m2_shift = 0;  // g2_axis 0: one pair per row; g2_axis 1: one pair per block of g2 rows
+  if (h->g2_axis == 1)
+    for (int g = h->g2 < MPQ_TILE_ROWS ? h->g2 : MPQ_TILE_ROWS; g > 1; g >>= 1) ++d->m2_shift;
   d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->B2 = h->B2; d->C = h->B2 + h->B4; d->T = h->T;
   if (h->tile_stride > 0xFFFFFFFFull) return MPQ_ERR_UNSUPPORTED;
   return MPQ_OK;
@@ -939,7 +962,7 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
 size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, bool persist, int waves = 4) {
   const size_t NT = M > 16 ? 2 : 1;
   return (size_t)waves * PD * 1024 + (persist ? waves * NT * 1024 + 2 * h.side_bytes : h.side_bytes) +
-         32ull * (h.B2 + h.B4) +
+         32ull * mpq_pu2(h.g1) * (h.B2 + h.B4) +
          (size_t)M * (2ull * h.K + 16);
 }
 
@@ -970,28 +993,37 @@ int cu_count() {
 
 // LDS bytes of the GEMV kernel: ring, partial sums, n side records, unit table, activations.
 size_t gemv_lds_bytes(const MpqHeader& h, int PD, int waves, int n) {
-  return (size_t)waves * PD * 1024 + (size_t)n * (waves + 1) * 64 + (size_t)n * h.side_bytes + 32ull * (h.B2 + h.B4) +
-         2ull * h.K;
+  return (size_t)waves * PD * 1024 + (size_t)n * (waves + 1) * 64 + (size_t)n * h.side_bytes +
+         32ull * mpq_pu2(h.g1) * (h.B2 + h.B4) + 2ull * h.K;
 }
 
-template <int PD, int LDSB, int WV>
+template <int PD, int LDSB, int WV, int PU>
 mpq_status launch_gemv(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
   const unsigned grid = (unsigned)((h.T + n - 1) / n);
-  hipLaunchKernelGGL((mpq_gemv_kernel<PD, LDSB, WV>), dim3(grid), dim3(WV * 64), 0, s, d, X, Y, n);
+  hipLaunchKernelGGL((mpq_gemv_kernel<PD, LDSB, WV, PU>), dim3(grid), dim3(WV * 64), 0, s, d, X, Y, n);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
 // GEMV with WV waves per workgroup and n tiles per workgroup in the smallest LDS class that holds
 // it.  Two code blocks per wave in flight: deeper rings were measured and change nothing.
+template <int WV, int PU>
+mpq_status gemv_class(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
+  const size_t need = gemv_lds_bytes(h, 2, WV, n);
+  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU>(h, d, X, Y, n, s);
+  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU>(h, d, X, Y, n, s);
+  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV, PU>(h, d, X, Y, n, s);
+  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU>(h, d, X, Y, n, s);
+  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU>(h, d, X, Y, n, s);
+  return MPQ_ERR_UNSUPPORTED;
+}
+
 template <int WV>
 mpq_status gemv_waves(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
-  const size_t need = gemv_lds_bytes(h, 2, WV, n);
-  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV>(h, d, X, Y, n, s);
-  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV>(h, d, X, Y, n, s);
-  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV>(h, d, X, Y, n, s);
-  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV>(h, d, X, Y, n, s);
-  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV>(h, d, X, Y, n, s);
-  return MPQ_ERR_UNSUPPORTED;
+  switch (mpq_pu2(h.g1)) {  // first-order groups per 2-bit unit
+    case 1: return gemv_class<WV, 1>(h, d, X, Y, n, s);
+    case 2: return gemv_class<WV, 2>(h, d, X, Y, n, s);
+    default: return gemv_class<WV, 4>(h, d, X, Y, n, s);
+  }
 }
 
 // Work split of the GEMV (waves per workgroup, tiles per workgroup), from measurements on the
@@ -1028,7 +1060,7 @@ mpq_status gemv_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
 }
 
 // Persistent batch kernel with WV waves per workgroup; one or two workgroups per compute unit.
-template <int NT, int PD, int LDSB, int WV>
+template <int NT, int PD, int LDSB, int WV, int PU = 1>
 mpq_status launch_batch(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   size_t per_cu = kLdsPerCu / LDSB;
   if (per_cu * WV > 32) per_cu = 32 / WV;
@@ -1036,11 +1068,11 @@ mpq_status launch_batch(const MpqHeader& h, const DevBlob& d, const uint16_t* X,
   long grid = (long)cu_count() * (long)per_cu;
   if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
   if (grid > h.T) grid = h.T;
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, true, WV>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, true, WV, PU>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
-template <int NT, int PD, int LDSB, bool PERSIST>
+template <int NT, int PD, int LDSB, bool PERSIST, int PU = 1>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   long grid = h.T;
   if (PERSIST) {  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
@@ -1051,7 +1083,7 @@ mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, ui
     if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
     if (grid > h.T) grid = h.T;
   }
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST, 4, PU>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
@@ -1059,6 +1091,19 @@ mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, ui
 // in flight for the number of workgroups that fit a compute unit.
 template <int NT>
 mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  if (mpq_pu2(h.g1) > 1) {
+    // first-order groups shorter than a unit (g1 = 16, 32): persistent workgroups in a few classes
+    const bool four = mpq_pu2(h.g1) == 4;
+#define MPQ_PIECES(CALL2, CALL4) return four ? CALL4 : CALL2
+    if (mm_lds_bytes(h, M, 2, true, 8) <= 80 * 1024)
+      MPQ_PIECES((launch_batch<NT, 2, 80 * 1024, 8, 2>(h, d, X, Y, M, s)), (launch_batch<NT, 2, 80 * 1024, 8, 4>(h, d, X, Y, M, s)));
+    if (mm_lds_bytes(h, M, 3, true, 8) <= 160 * 1024)
+      MPQ_PIECES((launch_batch<NT, 3, 160 * 1024, 8, 2>(h, d, X, Y, M, s)), (launch_batch<NT, 3, 160 * 1024, 8, 4>(h, d, X, Y, M, s)));
+    if (mm_lds_bytes(h, M, 3, true) <= 160 * 1024)
+      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, true, 2>(h, d, X, Y, M, s)), (launch_mm<NT, 3, 160 * 1024, true, 4>(h, d, X, Y, M, s)));
+#undef MPQ_PIECES
+    return MPQ_ERR_UNSUPPORTED;
+  }
   const int pd = g_ring_depth;
   const bool persist = g_persist < 0 ? M > 1 : g_persist != 0;
   if (!persist) {
@@ -1122,6 +1167,7 @@ bool plan_ranges(const MpqHeader& h, int NT, uint32_t budget, uint32_t Rwant, Ra
 // Two workgroups per compute unit (80 KiB each) when that fits, so that one stages while the other
 // computes; tiles per group so that the groups about fill the workgroup slots.
 mpq_status launch_ranges(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
   const int NT = M > 16 ? 2 : 1;
   const long cus = cu_count();
   RangePlan pl;
@@ -1225,7 +1271,10 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   if (st != MPQ_OK) return st;
   if (((uintptr_t)W_out_dev & 15u) != 0) return MPQ_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
-  hipLaunchKernelGGL(mpq_dequant_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  const int pu = mpq_pu2(h.g1);
+  if (pu == 1) hipLaunchKernelGGL(mpq_dequant_kernel<1>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  else if (pu == 2) hipLaunchKernelGGL(mpq_dequant_kernel<2>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  else hipLaunchKernelGGL(mpq_dequant_kernel<4>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
   if (add_outliers && h.nnz > 0) {
     hipLaunchKernelGGL(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);

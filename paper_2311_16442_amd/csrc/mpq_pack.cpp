@@ -24,8 +24,11 @@ bool desc_ok(const mpq_desc* d) {
 mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHeader* h) {
   if (!desc_ok(d) || nnz < 0 || n4 < 0 || n4 > d->K / d->g1) return MPQ_ERR_SHAPE;
   if (ocap < 0 || ocap % 32 != 0 || ocap > (int64_t)MPQ_TILE_ROWS * d->K + 32) return MPQ_ERR_SHAPE;
-  if (d->g1 != 64 && d->g1 != 128) return MPQ_ERR_UNSUPPORTED;  // a unit must not straddle groups
-  if (d->g2_axis != 0) return MPQ_ERR_UNSUPPORTED;
+  // a piece (the part of a 16-byte unit inside one group) must cover whole decode steps of 8 columns
+  if (d->g1 != 16 && d->g1 != 32 && d->g1 != 64 && d->g1 != 128) return MPQ_ERR_UNSUPPORTED;
+  // rows that share a second-order pair must not straddle 16-row tiles in an irregular way
+  if (d->g2_axis == 1 && (d->g2 < MPQ_TILE_ROWS ? MPQ_TILE_ROWS % d->g2 != 0 : d->g2 % MPQ_TILE_ROWS != 0))
+    return MPQ_ERR_UNSUPPORTED;
   memset(h, 0, sizeof(*h));
   h->magic = MPQ_MAGIC;
   h->version = MPQ_VERSION;
@@ -34,20 +37,21 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
   h->S = (h->G + d->g2 - 1) / d->g2;
   h->n4 = n4;
   h->n2 = h->G - n4;
-  h->U2 = h->n2 * (d->g1 / 64);
-  h->U4 = h->n4 * (d->g1 / 32);
+  h->U2 = d->g1 >= 64 ? h->n2 * (d->g1 / 64) : (h->n2 + mpq_pu2(d->g1) - 1) / mpq_pu2(d->g1);
+  h->U4 = d->g1 >= 32 ? h->n4 * (d->g1 / 32) : (h->n4 + mpq_pu4(d->g1) - 1) / mpq_pu4(d->g1);
   h->B2 = (h->U2 + MPQ_UNITS_PER_BLOCK - 1) / MPQ_UNITS_PER_BLOCK;
   h->B4 = (h->U4 + MPQ_UNITS_PER_BLOCK - 1) / MPQ_UNITS_PER_BLOCK;
   h->T = (d->N + MPQ_TILE_ROWS - 1) / MPQ_TILE_ROWS;
   h->nnz = nnz;
   const uint64_t C = (uint64_t)h->B2 + h->B4;
   h->ocap = (uint64_t)ocap;
-  if (64ull * ((uint64_t)h->S + 1) > 0xFFFFull) return MPQ_ERR_UNSUPPORTED;  // 16-bit offsets in the unit table
-  h->side_bytes = 32ull * (h->G + 1) + 64ull * (h->S + 1) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
+  // 16-bit offsets in the unit table
+  if (32ull * (uint64_t)h->G > 0xFFFFull || (uint64_t)mpq_meta2_zero(h) > 0xFFFFull) return MPQ_ERR_UNSUPPORTED;
+  h->side_bytes = 32ull * (h->G + 1) + mpq_meta2_bytes(h) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
   h->codes_off = align_up(h->side_bytes, 128);
   h->tile_stride = align_up(h->codes_off + C * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
   uint64_t off = MPQ_HEADER_BYTES;
-  h->off_units = off; off = align_up(off + 8ull * 4 * C, MPQ_SECTION_ALIGN);
+  h->off_units = off; off = align_up(off + 8ull * mpq_pu2(d->g1) * 4 * C, MPQ_SECTION_ALIGN);
   h->off_tiles = off; off = align_up(off + (uint64_t)h->T * h->tile_stride, MPQ_SECTION_ALIGN);
   h->total_bytes = off;
   return MPQ_OK;
@@ -183,55 +187,73 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   for (int32_t g = 0; g < G; ++g) (w->is4[g] ? groups4 : groups2).push_back(g);
   for (size_t i = 0; i < groups2.size(); ++i) stream_index[groups2[i]] = (int32_t)i;
   for (size_t i = 0; i < groups4.size(); ++i) stream_index[groups4[i]] = (int32_t)(h.n2 + i);
-  uint32_t* unit2 = (uint32_t*)(blob + h.off_units);
-  uint32_t* unit4 = unit2 + 2 * 4 * h.B2;
-  const int32_t upg2 = (int32_t)(g1 / 64), upg4 = (int32_t)(g1 / 32);
-  std::vector<int64_t> k0_2(4 * h.B2, -1), k0_4(4 * h.B4, -1);
-  for (int32_t u = 0; u < 4 * h.B2; ++u) {
-    if (u >= h.U2) { unit2[2 * u] = 0; unit2[2 * u + 1] = (uint32_t)(G * 32) | ((uint32_t)(h.S * 64) << 16); continue; }
-    const int32_t g = groups2[u / upg2];
-    const int64_t k0 = (int64_t)g * g1 + 64 * (u % upg2);
-    k0_2[u] = k0;
-    unit2[2 * u] = (uint32_t)(2 * k0);
-    unit2[2 * u + 1] = (uint32_t)(stream_index[g] * 32) | ((uint32_t)((g / d->g2) * 64) << 16);
+  // pieces: for every unit slot the K-group it decodes (-1 = padding) and its first column
+  const int32_t PU2 = mpq_pu2(d->g1), PU4 = mpq_pu4(d->g1);
+  const int32_t cpp2 = g1 >= 64 ? 64 : (int32_t)g1, cpp4 = g1 >= 32 ? 32 : (int32_t)g1;  // columns per piece
+  const int32_t nsub = mpq_nsub(d->g2);
+  const uint32_t zero_word1 = (uint32_t)(G * 32) | (mpq_meta2_zero(&h) << 16);
+  const int64_t nunits = 4ll * (h.B2 + h.B4);
+  std::vector<int32_t> piece_g((size_t)nunits * PU2, -1);
+  std::vector<int64_t> piece_k0((size_t)nunits * PU2, 0);
+  for (int64_t u = 0; u < nunits; ++u) {
+    const bool four = u >= 4ll * h.B2;
+    const int64_t ul = four ? u - 4ll * h.B2 : u;
+    const std::vector<int32_t>& groups = four ? groups4 : groups2;
+    const int32_t PU = four ? PU4 : PU2, cpp = four ? cpp4 : cpp2;
+    if (ul >= (four ? h.U4 : h.U2)) continue;
+    for (int32_t q = 0; q < PU; ++q) {
+      int64_t gi, koff;
+      if (g1 >= (four ? 32 : 64)) { const int64_t upg = g1 / cpp; gi = ul / upg; koff = cpp * (ul % upg); }
+      else { gi = ul * PU + q; koff = 0; }
+      if (gi >= (int64_t)groups.size()) continue;
+      piece_g[(size_t)(u * PU2 + q)] = groups[(size_t)gi];
+      piece_k0[(size_t)(u * PU2 + q)] = (int64_t)groups[(size_t)gi] * g1 + koff;
+    }
   }
-  for (int32_t u = 0; u < 4 * h.B4; ++u) {
-    if (u >= h.U4) { unit4[2 * u] = 0; unit4[2 * u + 1] = (uint32_t)(G * 32) | ((uint32_t)(h.S * 64) << 16); continue; }
-    const int32_t g = groups4[u / upg4];
-    const int64_t k0 = (int64_t)g * g1 + 32 * (u % upg4);
-    k0_4[u] = k0;
-    unit4[2 * u] = (uint32_t)(2 * k0);
-    unit4[2 * u + 1] = (uint32_t)(stream_index[g] * 32) | ((uint32_t)((g / d->g2) * 64) << 16);
+  uint32_t* unit_tab = (uint32_t*)(blob + h.off_units);
+  for (int64_t p = 0; p < nunits * PU2; ++p) {
+    const int32_t g = piece_g[(size_t)p];
+    if (g < 0) { unit_tab[2 * p] = 0; unit_tab[2 * p + 1] = zero_word1; continue; }
+    const uint32_t m2off = d->g2_axis == 0 ? (uint32_t)((g / d->g2) * 64) : (uint32_t)(stream_index[g] * 4 * nsub);
+    unit_tab[2 * p] = (uint32_t)(2 * piece_k0[(size_t)p]);
+    unit_tab[2 * p + 1] = (uint32_t)(stream_index[g] * 32) | (m2off << 16);
   }
+  const uint64_t m2_bytes = mpq_meta2_bytes(&h);
   for (int64_t n = 0; n < N; ++n) {
     const int64_t t = n / MPQ_TILE_ROWS, i = n % MPQ_TILE_ROWS;
     uint8_t* tile = blob + h.off_tiles + (uint64_t)t * h.tile_stride;
     uint16_t* meta1 = (uint16_t*)tile;
     uint32_t* meta2 = (uint32_t*)(tile + 32ull * (G + 1));
-    uint32_t* codes2 = (uint32_t*)(tile + h.codes_off);
-    uint32_t* codes4 = codes2 + (uint64_t)h.B2 * 256;
+    uint32_t* codes = (uint32_t*)(tile + h.codes_off);
     const uint8_t* row = w->codes + n * K;
-    for (int32_t u = 0; u < h.U2; ++u) {
-      const int64_t k0 = k0_2[u];
-      const int64_t b = u / 4, j = u % 4;
-      uint32_t* q = codes2 + ((b * 64 + j * 16 + i) * 4);
-      for (int kl = 0; kl < 64; ++kl)
-        q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 2 * (kl / 8));
-    }
-    for (int32_t u = 0; u < h.U4; ++u) {
-      const int64_t k0 = k0_4[u];
-      const int64_t b = u / 4, j = u % 4;
-      uint32_t* q = codes4 + ((b * 64 + j * 16 + i) * 4);
-      for (int kl = 0; kl < 32; ++kl)
-        q[(kl % 8) / 2] |= (uint32_t)row[k0 + kl] << (16 * (kl % 2) + 4 * (kl / 8));
+    for (int64_t u = 0; u < nunits; ++u) {
+      const bool four = u >= 4ll * h.B2;
+      const int32_t PU = four ? PU4 : PU2, cpp = four ? cpp4 : cpp2, width = four ? 4 : 2;
+      uint32_t* q4 = codes + (((u / 4) * 64 + (u % 4) * 16 + i) * 4);
+      for (int32_t q = 0; q < PU; ++q) {
+        if (piece_g[(size_t)(u * PU2 + q)] < 0) continue;
+        const int64_t k0 = piece_k0[(size_t)(u * PU2 + q)];
+        for (int32_t kp = 0; kp < cpp; ++kp) {
+          const int32_t kl = q * cpp + kp;  // column inside the unit
+          q4[(kl % 8) / 2] |= (uint32_t)row[k0 + kp] << (16 * (kl % 2) + width * (kl / 8));
+        }
+      }
     }
     for (int64_t g = 0; g < G; ++g)
       meta1[stream_index[g] * MPQ_TILE_ROWS + i] = (uint16_t)(w->s_int[n * G + g] | ((uint16_t)w->z1[n * G + g] << 8));
-    for (int64_t s = 0; s < h.S; ++s)
-      meta2[s * MPQ_TILE_ROWS + i] = (uint32_t)w->s2[n * h.S + s] | ((uint32_t)w->z2[n * h.S + s] << 16);
+    if (d->g2_axis == 0) {
+      for (int64_t s2i = 0; s2i < h.S; ++s2i)
+        meta2[s2i * MPQ_TILE_ROWS + i] = (uint32_t)w->s2[n * h.S + s2i] | ((uint32_t)w->z2[n * h.S + s2i] << 16);
+    } else if (i % d->g2 == 0 || (d->g2 >= MPQ_TILE_ROWS && i == 0)) {
+      // first row of a block of g2 rows inside the tile: the block's pair for every group
+      const int64_t nb = n / d->g2, sub = d->g2 >= MPQ_TILE_ROWS ? 0 : i / d->g2;
+      for (int64_t g = 0; g < G; ++g)
+        meta2[stream_index[g] * nsub + sub] = (uint32_t)w->s2[nb * G + g] | ((uint32_t)w->z2[nb * G + g] << 16);
+    }
   }
+  (void)m2_bytes;
   for (int64_t t = 0; t < h.T; ++t) {
-    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + 32ull * (G + 1) + 64ull * (h.S + 1));
+    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + 32ull * (G + 1) + mpq_meta2_bytes(&h));
     const int64_t n0 = t * MPQ_TILE_ROWS;
     const int32_t base = w->row_ptr[n0];
     for (int r = 0; r <= MPQ_TILE_ROWS; ++r) {

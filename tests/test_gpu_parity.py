@@ -31,12 +31,19 @@ CASES = [
     ("down_like", 272, 11008, 64, 16, 0.10, 0.005, False),   # G = 172 = 10*16 + 12
     ("wide", 48, 28672, 64, 16, 0.10, 0.005, False),         # largest K of the configurations
     ("dense_outliers", 96, 1024, 64, 16, 0.10, 0.30, False), # rows with hundreds of outliers
+    # first-order groups shorter than a 16-byte unit and second-order pairs shared by rows (last field:
+    # 1 = a pair covers the same K-group of g2 rows, the paper's axis, Sec. 2.2)
+    ("paper_point", 1000, 1024, 16, 16, 0.25, 0.005, True, 1),   # g1 = g2 = 16, 25 % 4-bit
+    ("g32_rows32", 208, 2048, 32, 32, 0.15, 0.005, True, 1),     # a pair spans two tiles
+    ("g16_along_k", 272, 1520, 16, 16, 0.10, 0.01, False, 0),    # 95 groups: ragged units in both streams
+    ("g64_rows4", 100, 1024, 64, 4, 0.10, 0.005, True, 1),       # four blocks of rows per tile
 ]
 
 
 def make(case):
-    name, N, K, g1, g2, f4, p_o, z1_full = case
-    lg = synth.make_matrix(synth.MatrixSpec(name, N, K, g1, g2, f4, p_o, 4242 + N + K), z1_full_range=z1_full)
+    name, N, K, g1, g2, f4, p_o, z1_full = case[:8]
+    axis = case[8] if len(case) > 8 else 0
+    lg = synth.make_matrix(synth.MatrixSpec(name, N, K, g1, g2, f4, p_o, 4242 + N + K, axis), z1_full_range=z1_full)
     return lg, oracle.Matrix.from_logical(lg), mpq.pack_logical(lg)
 
 

@@ -26,21 +26,27 @@ def test_library_exports_every_declared_symbol():
 
 
 CASES = [
-    # N, K, g1, g2, f4, p_o, z1_full
-    (48, 1024, 64, 16, 0.10, 0.005, False),
-    (37, 704, 64, 4, 0.30, 0.02, True),      # ragged: N % 16 != 0, G = 11, S = 3 with a short tail
-    (20, 1024, 128, 2, 0.25, 0.01, True),    # g1 = 128
-    (16, 512, 64, 16, 0.0, 0.01, False),     # no 4-bit group
-    (16, 512, 64, 16, 1.0, 0.0, False),      # only 4-bit groups
-    (5, 64, 64, 1, 0.0, 0.2, False),         # a single group
+    # N, K, g1, g2, f4, p_o, z1_full, g2_axis
+    (48, 1024, 64, 16, 0.10, 0.005, False, 0),
+    (37, 704, 64, 4, 0.30, 0.02, True, 0),      # ragged: N % 16 != 0, G = 11, S = 3 with a short tail
+    (20, 1024, 128, 2, 0.25, 0.01, True, 0),    # g1 = 128
+    (16, 512, 64, 16, 0.0, 0.01, False, 0),     # no 4-bit group
+    (16, 512, 64, 16, 1.0, 0.0, False, 0),      # only 4-bit groups
+    (5, 64, 64, 1, 0.0, 0.2, False, 0),         # a single group
+    (40, 512, 16, 16, 0.25, 0.01, True, 1),     # the paper's operating point: g1 = g2 = 16, pairs shared by 16 rows
+    (40, 432, 16, 4, 0.26, 0.02, True, 1),      # 27 groups: 20 two-bit (5 units), 7 four-bit (3.5 units); 4 blocks of rows per tile
+    (70, 480, 32, 32, 0.20, 0.01, True, 1),     # g1 = 32; a pair spans two tiles
+    (33, 480, 32, 3, 0.20, 0.01, False, 0),     # g1 = 32 with pairs along K
+    (24, 320, 16, 16, 0.0, 0.05, False, 0),     # g1 = 16, only 2-bit groups
+    (24, 1024, 64, 8, 0.10, 0.005, False, 1),   # one piece per unit, pairs shared by 8 rows
 ]
 
 
-@pytest.mark.parametrize("N,K,g1,g2,f4,p_o,z1_full", CASES)
-def test_pack_round_trips_through_independent_reader(N, K, g1, g2, f4, p_o, z1_full):
-    lg = synth.make_matrix(synth.MatrixSpec("t", N, K, g1, g2, f4, p_o, 77 + N + K), z1_full_range=z1_full)
+@pytest.mark.parametrize("N,K,g1,g2,f4,p_o,z1_full,axis", CASES)
+def test_pack_round_trips_through_independent_reader(N, K, g1, g2, f4, p_o, z1_full, axis):
+    lg = synth.make_matrix(synth.MatrixSpec("t", N, K, g1, g2, f4, p_o, 77 + N + K, axis), z1_full_range=z1_full)
     pk = mpq.pack_logical(lg)
-    assert pk.blob.size == mpq.packed_size(N, K, g1, g2, lg.is4, lg.row_ptr)
+    assert pk.blob.size == mpq.packed_size(N, K, g1, g2, lg.is4, lg.row_ptr, axis)
     info = mpq.blob_info(pk.header)
     assert (info["N"], info["K"], info["g1"], info["g2"], info["nnz"], info["n4"]) == \
         (N, K, g1, g2, lg.nnz, int(lg.is4.sum()))
@@ -101,8 +107,9 @@ def test_pack_rejects_malformed_input():
     bad = dict(base); bad["col"] = lg.col.copy(); bad["col"][e] = 600
     assert _status(**bad) == mpq.MPQ_ERR_CSR                      # col >= K
     assert _status(**dict(base, K=500)) == mpq.MPQ_ERR_SHAPE      # K % g1 != 0
-    assert _status(**dict(base, g1=32)) == mpq.MPQ_ERR_UNSUPPORTED
-    assert _status(**dict(base, g2_axis=1)) == mpq.MPQ_ERR_UNSUPPORTED
+    assert _status(**dict(base, g1=8)) == mpq.MPQ_ERR_UNSUPPORTED       # a piece shorter than a decode step
+    assert _status(**dict(base, g2_axis=1, g2=3)) == mpq.MPQ_ERR_UNSUPPORTED   # blocks of 3 rows straddle tiles
+    assert _status(**dict(base, g2_axis=2)) == mpq.MPQ_ERR_SHAPE
     assert _status(**dict(base, g2=0)) == mpq.MPQ_ERR_SHAPE
 
 

@@ -21,13 +21,21 @@ def read_header(blob: np.ndarray) -> dict:
 
 def unpack(blob: np.ndarray) -> dict:
     h = read_header(blob)
+    assert h["version"] == 7
     N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
+    axis = h["g2_axis"]
     B2, B4 = h["B2"], h["B4"]
     C = B2 + B4
-    assert h["side_bytes"] == 32 * (G + 1) + 64 * (S + 1) + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
+    PU2, PU4 = max(1, 64 // g1), max(1, 32 // g1)            # pieces (groups) per unit
+    nsub = 1 if g2 >= TILE else TILE // g2                    # g2_axis 1: blocks of g2 rows per tile
+    m2_bytes = 64 * (S + 1) if axis == 0 else -(-(4 * nsub * (G + 1)) // 16) * 16
+    zero2 = 64 * S if axis == 0 else 4 * nsub * G
+    assert h["side_bytes"] == 32 * (G + 1) + m2_bytes + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
     assert h["codes_off"] % 128 == 0 and h["codes_off"] >= h["side_bytes"] and h["tile_stride"] % 256 == 0
     assert h["tile_stride"] >= h["codes_off"] + C * 1024 and h["total"] == blob.size
-    units = blob[h["off_units"]: h["off_units"] + 32 * C].view(np.uint32).reshape(-1, 2)
+    assert h["U2"] == (h["n2"] * (g1 // 64) if g1 >= 64 else -(-h["n2"] // PU2))
+    assert h["U4"] == (h["n4"] * (g1 // 32) if g1 >= 32 else -(-h["n4"] // PU4))
+    units = blob[h["off_units"]: h["off_units"] + 32 * PU2 * C].view(np.uint32).reshape(4 * C, PU2, 2)
     tiles = blob[h["off_tiles"]: h["off_tiles"] + T * h["tile_stride"]].reshape(T, h["tile_stride"])
     # gaps inside a tile record are zero
     assert not tiles[:, h["side_bytes"]: h["codes_off"]].any() and not tiles[:, h["codes_off"] + C * 1024:].any()
@@ -35,42 +43,75 @@ def unpack(blob: np.ndarray) -> dict:
     codes = np.zeros((T * TILE, K), dtype=np.uint8)
     is4 = np.full(G, 255, dtype=np.uint8)
     stream_groups = []                       # K-group of each stream group, 2-bit stream first
+    m2off = {}                               # K-group -> meta2 offset recorded in the unit table
     for u in range(4 * C):
         four = u >= 4 * B2
         ul = u - 4 * B2 if four else u
-        e, e1 = int(units[u, 0]), int(units[u, 1])
-        words = cw[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
-        if (e1 & 0xFFFF) == 32 * G:                        # padding unit: points at the zero entries
-            assert ul >= (h["U4"] if four else h["U2"]) and e == 0 and (e1 >> 16) == 64 * S
-            assert not words.any()                        # padding units are zero
-            continue
-        assert ul < (h["U4"] if four else h["U2"])
-        k0 = e // 2
-        g = k0 // g1
-        is4[g] = 1 if four else 0
-        assert (e1 >> 16) == (g // g2) * 64
-        if k0 % g1 == 0:
-            assert (e1 & 0xFFFF) == 32 * len(stream_groups)
-            stream_groups.append(g)
+        PU = PU4 if four else PU2
         width, per = (4, 32) if four else (2, 64)
+        cpp = per // PU                                   # columns per piece
+        words = cw[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
+        field = np.zeros((T * TILE, per), dtype=np.uint8)
         for kl in range(per):
             d, sh = (kl % 8) // 2, 16 * (kl % 2) + width * (kl // 8)
-            codes[:, k0 + kl] = ((words[:, :, d] >> sh) & ((1 << width) - 1)).reshape(-1)
+            field[:, kl] = ((words[:, :, d] >> sh) & ((1 << width) - 1)).reshape(-1)
+        for q in range(PU2):
+            e, e1 = int(units[u, q, 0]), int(units[u, q, 1])
+            if (e1 & 0xFFFF) == 32 * G:                    # padding piece: points at the zero entries
+                assert e == 0 and (e1 >> 16) == zero2
+                if q < PU:
+                    assert not field[:, q * cpp: (q + 1) * cpp].any()   # padding pieces hold zero codes
+                continue
+            assert q < PU and ul < (h["U4"] if four else h["U2"])
+            k0 = e // 2
+            g = k0 // g1
+            assert is4[g] in (255, 1 if four else 0)
+            is4[g] = 1 if four else 0
+            if k0 % g1 == 0:
+                assert (e1 & 0xFFFF) == 32 * len(stream_groups)
+                stream_groups.append(g)
+                m2off[g] = e1 >> 16
+            else:
+                assert m2off[g] == e1 >> 16 and (e1 & 0xFFFF) == 32 * stream_groups.index(g)
+            codes[:, k0: k0 + cpp] = field[:, q * cpp: (q + 1) * cpp]
     assert len(stream_groups) == G and sorted(stream_groups) == list(range(G))
     m1 = np.ascontiguousarray(tiles[:, : 32 * (G + 1)]).view(np.uint16).reshape(T, G + 1, TILE)
-    assert not m1[:, G].any()                             # the zero entry padding units point at
+    assert not m1[:, G].any()                             # the zero entry padding pieces point at
     s_int = np.zeros((T * TILE, G), dtype=np.uint8)
     z1 = np.zeros((T * TILE, G), dtype=np.uint8)
     for sg, g in enumerate(stream_groups):
         s_int[:, g] = (m1[:, sg, :] & 0xFF).reshape(-1)
         z1[:, g] = (m1[:, sg, :] >> 8).reshape(-1)
-    m2 = np.ascontiguousarray(tiles[:, 32 * (G + 1): 32 * (G + 1) + 64 * (S + 1)]).view(np.uint32).reshape(T, S + 1, TILE)
-    assert not m2[:, S].any()
-    m2 = m2[:, :S]
-    s2 = (m2 & 0xFFFF).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
-    z2 = (m2 >> 16).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)
+    raw2 = np.ascontiguousarray(tiles[:, 32 * (G + 1): 32 * (G + 1) + m2_bytes])
+    if axis == 0:
+        m2 = raw2.view(np.uint32).reshape(T, S + 1, TILE)
+        assert not m2[:, S].any()
+        m2 = m2[:, :S]
+        for g in range(G):
+            assert m2off[g] == (g // g2) * 64
+        s2 = (m2 & 0xFFFF).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)[:N]
+        z2 = (m2 >> 16).astype(np.uint16).transpose(0, 2, 1).reshape(T * TILE, S)[:N]
+    else:
+        m2 = raw2[:, : 4 * nsub * (G + 1)].copy().view(np.uint32).reshape(T, G + 1, nsub)
+        assert not m2[:, G].any() and not raw2[:, 4 * nsub * (G + 1):].any()
+        NB = -(-N // g2)
+        s2 = np.zeros((NB, G), dtype=np.uint16)
+        z2 = np.zeros((NB, G), dtype=np.uint16)
+        for sg, g in enumerate(stream_groups):
+            assert m2off[g] == sg * 4 * nsub
+            for t in range(T):
+                for sub in range(nsub):
+                    n0 = t * TILE + (sub * g2 if g2 < TILE else 0)
+                    if n0 >= N:
+                        assert m2[t, sg, sub] == 0        # blocks of rows beyond N stay zero
+                        continue
+                    nb = n0 // g2
+                    v = int(m2[t, sg, sub])
+                    if g2 > TILE and (t * TILE) % g2 != 0:
+                        assert (s2[nb, g], z2[nb, g]) == (v & 0xFFFF, v >> 16)   # every tile of a block holds a copy
+                    s2[nb, g], z2[nb, g] = v & 0xFFFF, v >> 16
     # outliers: one record per tile = 32 words of row starts (17 used) + ocap words
-    o0 = 32 * (G + 1) + 64 * (S + 1)
+    o0 = 32 * (G + 1) + m2_bytes
     recs = np.ascontiguousarray(tiles[:, o0: o0 + 128 + 4 * h["ocap"]]).view(np.uint32).reshape(T, 32 + h["ocap"])
     row_ptr = [0]
     words = []
@@ -90,6 +131,6 @@ def unpack(blob: np.ndarray) -> dict:
     assert h["ocap"] == -(-fullest // 32) * 32
     outl = np.concatenate(words) if words else np.zeros(0, np.uint32)
     assert outl.size == h["nnz"]
-    return dict(h=h, is4=is4, codes=codes[:N], s_int=s_int[:N], z1=z1[:N], s2=s2[:N], z2=z2[:N],
+    return dict(h=h, is4=is4, codes=codes[:N], s_int=s_int[:N], z1=z1[:N], s2=s2, z2=z2,
                 row_ptr=np.array(row_ptr, dtype=np.int32), col=(outl & 0xFFFF).astype(np.uint16),
                 val=(outl >> 16).astype(np.uint16), pad_rows_codes=codes[N:], pad_s=s_int[N:])
