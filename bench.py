@@ -128,6 +128,12 @@ def main():
     ap.add_argument("--batch", type=int, default=1, help="batch rows M (1 = GEMV)")
     ap.add_argument("--sweep", action="store_true",
                     help="configs[2]: M x 4-bit fraction x outlier fraction on the Llama2-7B layer")
+    ap.add_argument("--g1", type=int, default=None, help="first-order group size instead of the configuration's (16, 32, 64, 128)")
+    ap.add_argument("--g2", type=int, default=None, help="second-order group size instead of the configuration's")
+    ap.add_argument("--g2-axis", type=int, default=None, choices=[0, 1],
+                    help="0 = second-order pairs along K (the configurations), 1 = shared by g2 rows (the paper's axis)")
+    ap.add_argument("--f4", type=float, default=None, help="fraction of 4-bit groups instead of the configuration's")
+    ap.add_argument("--p-o", type=float, default=None, help="outlier probability instead of the configuration's")
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -175,7 +181,11 @@ def main():
                 torch.cuda.empty_cache()
 
     copies = 80 if args.config == 4 else 32
-    layer = Layer(torch, mpq, synth, synth.config_specs(args.config), copies, M, dev)
+    import dataclasses
+    specs = synth.config_specs(args.config, f4=args.f4, p_o=args.p_o)
+    over = {k: v for k, v in (("g1", args.g1), ("g2", args.g2), ("g2_axis", args.g2_axis)) if v is not None}
+    specs = [dataclasses.replace(sp, **over) for sp in specs]
+    layer = Layer(torch, mpq, synth, specs, copies, M, dev)
     log(f"[setup] {copies} layer copies resident: {copies * layer.packed_bytes / 1e9:.2f} GB; "
         f"algorithmic bytes per layer {layer.step_bytes / 1e6:.3f} MB")
     # a step: one layer (configs 1, 3) or one decode sweep over all 80 resident layers (config 4)
@@ -203,7 +213,7 @@ def main():
                 "kernel": ("mpq_gemv_kernel" if M == 1 else "mpq_mm_kernel") + " (every launch of the step)", "avg_launch_us": round(avg_launch_us, 3),
                 "bytes_per_launch": round(bytes_per_launch)}
     traffic_file = os.path.join(ROOT, "profiles", "gemv_llama2_7b_traffic.json")
-    if args.config == 1 and M == 1 and os.path.exists(traffic_file):
+    if args.config == 1 and M == 1 and not over and args.f4 is None and args.p_o is None and os.path.exists(traffic_file):
         try:
             roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
         except Exception:  # noqa: BLE001 - a malformed note must not break the benchmark line
@@ -233,13 +243,13 @@ def main():
                          f"{sample['spec'].name} matrix of the same layer at M={M}, {reps} repetitions, {cpu_s * 1e3:.1f} ms each"}
 
     spec0 = layer.mats[0]["spec"]
-    workload = ("configs[%d]: %s %s, %d launches per step (%s), batch M=%d, g1=%d g2=%d f4=%.0f%% p_o=%.1f%%, "
+    workload = ("configs[%d]: %s %s, %d launches per step (%s), batch M=%d, g1=%d g2=%d%s f4=%.0f%% p_o=%.1f%%, "
                 "%d layer copies %s" % (
                     args.config, MODEL[args.config],
                     "decode sweep over 80 resident layers" if args.config == 4 else "decoder layer",
                     len(layer.mats) * layers_per_step,
                     ", ".join(f"{m['spec'].N}x{m['spec'].K}" for m in layer.mats), M, spec0.g1, spec0.g2,
-                    100 * spec0.f4, 100 * spec0.p_o, copies,
+                    " (pairs shared by g2 rows)" if spec0.g2_axis == 1 else "", 100 * spec0.f4, 100 * spec0.p_o, copies,
                     "resident (22.5 GB), each read once per step" if args.config == 4 else "rotated (cold last-level cache)"))
     config = {"workload": workload, "bytes_per_step": step_bytes,
               "launch": "hipGraph replay" if graphed else "python", "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2)}

@@ -35,6 +35,10 @@ def sub_matrix(lg, rows):
     rp[1:] = np.cumsum(counts)
     idx = np.concatenate([np.arange(lg.row_ptr[r], lg.row_ptr[r + 1]) for r in rows]) if rows.size else np.zeros(0, int)
     idx = idx.astype(np.int64)
+    if getattr(s, "g2_axis", 0) == 1:
+        # pairs shared by g2 rows: give every sampled row its own copy (blocks of one row)
+        return oracle.Matrix(rows.size, s.K, s.g1, 1, lg.is4, lg.codes[rows], lg.s_int[rows], lg.z1[rows],
+                             lg.s2[rows // s.g2], lg.z2[rows // s.g2], rp, lg.col[idx], lg.val[idx], g2_axis=1)
     return oracle.Matrix(rows.size, s.K, s.g1, s.g2, lg.is4, lg.codes[rows], lg.s_int[rows], lg.z1[rows],
                          lg.s2[rows], lg.z2[rows], rp, lg.col[idx], lg.val[idx])
 
@@ -112,3 +116,16 @@ def test_llama2_70b_shapes_sampled(torch, idx):
     pk = mpq.pack_logical(lg)
     blob = to_dev(torch, pk.blob)
     check_products(torch, lg, pk, blob, [1, 8], all_rows=False)
+
+
+@pytest.mark.parametrize("idx", [1, 3])
+def test_llama2_7b_shapes_at_the_papers_operating_point(torch, idx):
+    # g1 = g2 = 16, second-order pairs shared by 16 rows (Sec. 2.2), 25 % 4-bit groups (Sec. 3.3)
+    base = synth.config_specs(1)[idx]
+    spec = synth.MatrixSpec(base.name, base.N, base.K, 16, 16, 0.25, 0.005, base.seed, 1)
+    lg = synth.make_matrix(spec)
+    pk = mpq.pack_logical(lg)
+    blob = to_dev(torch, pk.blob)
+    check_products(torch, lg, pk, blob, [1], all_rows=True)
+    check_products(torch, lg, pk, blob, [4, 32], all_rows=False)
+    check_dequant_rows(torch, lg, pk, blob)
