@@ -846,16 +846,18 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
 // ------------------------------------------------------------------------------------ dequant
 //
 // Row-major fp16 copy of the dense part: W_out[n][k] = fp16((code - z1) * s1), bit-exact eq. 5.
-// One workgroup per tile, blocks round-robin over the four waves.  A lane decodes its unit (64 or
-// 32 consecutive columns of one row); the wave then turns the block through LDS so that eight
-// (four) neighbouring lanes write the 128 (64) contiguous bytes of one (row, unit) - full cache
-// lines per store instruction instead of 64 scattered 16-byte pieces.  The kernel is bound by
-// HBM writes: 2 bytes out per weight against 0.33 bytes in.
+// One or several workgroups per tile, blocks round-robin over their waves, the next block's codes
+// requested before the current one is decoded.  A lane decodes its unit (64 or 32 columns of one row) four
+// steps at a time; the wave turns those 64 bytes per lane through a small LDS area so that four
+// neighbouring lanes write the 64 contiguous bytes of one (row, half unit) and a store instruction
+// covers whole 64-byte segments instead of 64 scattered 16-byte pieces.  20 KiB of LDS per
+// workgroup, so that 32 waves share a compute unit.  The kernel is bound by HBM writes: 2 bytes
+// out per weight against 0.33 bytes in.
 template <int PU>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 #pragma clang fp contract(off)
-  constexpr int PAIR = 144;  // LDS bytes per (row, unit): 128 + 16 so that lanes fall into different banks
+  constexpr int PAIR = 80;  // LDS bytes per (row, half unit): 64 + 16 so that lanes fall into different banks
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
   const int tid = threadIdx.x;
@@ -863,20 +865,40 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const int i = lane & 15, j = lane >> 4;
   const unsigned char* tile = b.tiles + (size_t)blockIdx.x * b.tile_stride;
   const uint2* units = (const uint2*)b.units;
+  const uint4* codes = (const uint4*)(tile + b.codes_off);
   const DecodeConsts kc = make_consts();
   unsigned char* mine = turn[wv];
   const unsigned char* m1i = tile + i * 2;
   const unsigned char* m2i = tile + b.off_m2 + (i >> b.m2_shift) * 4;
-  for (int c = wv; c < b.C; c += 4) {
+  uint4* dst = (uint4*)(mine + lane * PAIR);
+  const int chunk = lane & 3;  // 16-byte chunk (decode step) of a half unit that this lane stores
+  // the blocks of a tile are shared by gridDim.y workgroups (matrices with few row tiles)
+  const int c0 = (int)blockIdx.y * 4 + wv, cstep = 4 * (int)gridDim.y;
+  uint4 qn = c0 < b.C ? codes[c0 * 64 + lane] : uint4{0, 0, 0, 0};
+  for (int c = c0; c < b.C; c += cstep) {
     const bool two = c < b.B2;
-    const uint4 q = ((const uint4*)(tile + b.codes_off))[c * 64 + lane];
+    const uint4 q = qn;
+    if (c + cstep < b.C) qn = codes[(c + cstep) * 64 + lane];
     const unsigned char* ue = b.units + (size_t)(4 * c + j) * (8 * PU);
     const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-    uint4* dst = (uint4*)(mine + lane * PAIR);
+    // stores of one half: (row, unit) pairs 16*s .. 16*s + 15 in round s, four lanes per pair
+#define MPQ_DQ_STORE_HALF(HALF, SPP)                                                                     \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* the wave's own LDS area: lanes run in lockstep */ \
+  for (int s = 0; s < 4; ++s) {                                                                          \
+    const int pair = (lane >> 2) + s * 16; /* lane index (unit * 16 + row) that decoded it */            \
+    const int prow = blockIdx.x * 16 + (pair & 15);                                                      \
+    const int cg = (HALF) * 4 + chunk;     /* step inside the unit */                                    \
+    const uint2 pu = units[(4 * c + (pair >> 4)) * PU + cg / (SPP)]; /* the step's piece */               \
+    const uint4 v = *(const uint4*)(mine + pair * PAIR + chunk * 16);                                    \
+    /* padding pieces point at the zero scale entries; padding rows lie beyond N */                      \
+    if ((pu.y & 0xFFFFu) != 32u * (uint32_t)b.G && prow < b.N)                                           \
+      *(uint4*)((unsigned char*)Wout + ((size_t)prow * b.K) * 2 + pu.x + (cg % (SPP)) * 16) = v;          \
+  }                                                                                                      \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* reads done before the area is overwritten */
 #define MPQ_DQ_STEP(TWO, P)                                                                   \
   {                                                                                           \
     constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                  \
-    dst[P] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                                  \
+    dst[(P) & 3] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                            \
   }
     if (two) {
       half2_t s1p[PU];
@@ -885,7 +907,9 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
       load_pieces<PU>(ue, m1i, m2i, s1p, zb, xoff);
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
       MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
+      MPQ_DQ_STORE_HALF(0, 8 / PU)
       MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
+      MPQ_DQ_STORE_HALF(1, 8 / PU)
     } else {
       half2_t s1p[PU4];
       half_t zb[PU4];
@@ -893,24 +917,10 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
       load_pieces<PU4>(ue, m1i, m2i, s1p, zb, xoff);
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
+      MPQ_DQ_STORE_HALF(0, 4 / PU4)
     }
 #undef MPQ_DQ_STEP
-    // the wave's own LDS area: its lanes run in lockstep, only the LDS counter has to drain
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    const int chunks = two ? 8 : 4;           // 16-byte chunks (decode steps) per (row, unit)
-    const int shift = two ? 3 : 2;
-    const int spp = chunks / (two ? PU : PU4);  // chunks per piece
-    const int chunk = lane & (chunks - 1);
-    for (int s = 0; s < chunks; ++s) {
-      const int pair = (lane >> shift) + s * (64 >> shift);  // lane index (unit * 16 + row) that decoded it
-      const int prow = blockIdx.x * 16 + (pair & 15);
-      const uint2 pu = units[(4 * c + (pair >> 4)) * PU + chunk / spp];  // the chunk's piece
-      const uint4 v = *(const uint4*)(mine + pair * PAIR + chunk * 16);
-      // padding pieces point at the zero scale entries; padding rows lie beyond N
-      if ((pu.y & 0xFFFFu) != 32u * (uint32_t)b.G && prow < b.N)
-        *(uint4*)((unsigned char*)Wout + ((size_t)prow * b.K) * 2 + pu.x + (chunk % spp) * 16) = v;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next block overwrites the area
+#undef MPQ_DQ_STORE_HALF
   }
 }
 
@@ -1272,9 +1282,15 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   if (((uintptr_t)W_out_dev & 15u) != 0) return MPQ_ERR_ALIGN;
   hipStream_t s = (hipStream_t)stream;
   const int pu = mpq_pu2(h.g1);
-  if (pu == 1) hipLaunchKernelGGL(mpq_dequant_kernel<1>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
-  else if (pu == 2) hipLaunchKernelGGL(mpq_dequant_kernel<2>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
-  else hipLaunchKernelGGL(mpq_dequant_kernel<4>, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  // enough workgroups for eight per compute unit: tiles with many blocks are shared
+  int slices = (8 * cu_count() + h.T - 1) / h.T;
+  const int most = (h.B2 + h.B4 + 3) / 4;
+  slices = slices > most ? most : slices;
+  slices = slices > 8 ? 8 : slices < 1 ? 1 : slices;
+  const dim3 grid((unsigned)h.T, (unsigned)slices);
+  if (pu == 1) hipLaunchKernelGGL(mpq_dequant_kernel<1>, grid, dim3(256), 0, s, d, W_out_dev);
+  else if (pu == 2) hipLaunchKernelGGL(mpq_dequant_kernel<2>, grid, dim3(256), 0, s, d, W_out_dev);
+  else hipLaunchKernelGGL(mpq_dequant_kernel<4>, grid, dim3(256), 0, s, d, W_out_dev);
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
   if (add_outliers && h.nnz > 0) {
     hipLaunchKernelGGL(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);

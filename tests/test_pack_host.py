@@ -162,3 +162,17 @@ def test_avg_bits_reproduces_the_papers_values():
     got = mpq.avg_bits(spec.N, spec.K, spec.g1, spec.g2, spec.n4, nnz, mode=0)
     assert abs(got - 8.0 * by / (spec.N * spec.K)) < 1e-9 and abs(got - 2.62) < 0.01
     assert mpq.avg_bits(0, 1024, 64, 16, 0, 0) < 0
+
+
+def test_group_count_beyond_the_table_offsets_is_unsupported():
+    # the unit table addresses a group's scale entries with 16-bit byte offsets: 32 * G <= 65535
+    rp = np.zeros(17, dtype=np.int32)
+    assert mpq.packed_size(16, 2047 * 16, 16, 16, np.zeros(2047, np.uint8), rp, 1) > 0
+    with pytest.raises(mpq.MpqError) as e:
+        mpq.packed_size(16, 2049 * 16, 16, 16, np.zeros(2049, np.uint8), rp, 1)
+    assert e.value.status == mpq.MPQ_ERR_UNSUPPORTED
+    # pairs shared by single rows: 16 entries per group and tile, so the limit comes earlier
+    with pytest.raises(mpq.MpqError) as e:
+        mpq.packed_size(16, 1100 * 16, 16, 1, np.zeros(1100, np.uint8), rp, 1)
+    assert e.value.status == mpq.MPQ_ERR_UNSUPPORTED
+    assert mpq.packed_size(16, 1000 * 16, 16, 1, np.zeros(1000, np.uint8), rp, 1) > 0
