@@ -51,6 +51,7 @@ class Layer:
     def __init__(self, torch, mpq, synth, specs, copies, M, dev):
         self.mats = []
         self.copies = copies
+        self.multi = False   # True: the layer's products go out as one multi-problem launch
         t0 = time.time()
         for spec in specs:
             lg = synth.make_matrix(spec)
@@ -77,6 +78,11 @@ class Layer:
         torch.cuda.synchronize()
 
     def launch_layer(self, mpq, layer, stream):
+        if self.multi:
+            k = layer % len(self.mats[0]["y"])
+            mpq.gemv_multi([m["hdr"] for m in self.mats], [m["blobs"][layer] for m in self.mats],
+                           [m["x"] for m in self.mats], [m["y"][k] for m in self.mats], stream=stream)
+            return
         for m in self.mats:
             y = m["y"][layer % len(m["y"])]
             if self.M == 1:
@@ -134,6 +140,8 @@ def main():
                     help="0 = second-order pairs along K (the configurations), 1 = shared by g2 rows (the paper's axis)")
     ap.add_argument("--f4", type=float, default=None, help="fraction of 4-bit groups instead of the configuration's")
     ap.add_argument("--p-o", type=float, default=None, help="outlier probability instead of the configuration's")
+    ap.add_argument("--multi", action="store_true",
+                    help="one multi-problem launch per step (mpq_gemv_multi) instead of one launch per matrix; M = 1 only")
     ap.add_argument("--no-graph", action="store_true", help="launch from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -186,6 +194,8 @@ def main():
     over = {k: v for k, v in (("g1", args.g1), ("g2", args.g2), ("g2_axis", args.g2_axis)) if v is not None}
     specs = [dataclasses.replace(sp, **over) for sp in specs]
     layer = Layer(torch, mpq, synth, specs, copies, M, dev)
+    layer.multi = bool(args.multi)
+    assert not (args.multi and M != 1), "--multi is the matrix-vector product only"
     log(f"[setup] {copies} layer copies resident: {copies * layer.packed_bytes / 1e9:.2f} GB; "
         f"algorithmic bytes per layer {layer.step_bytes / 1e6:.3f} MB")
     # a step: one layer (configs 1, 3) or one decode sweep over all 80 resident layers (config 4)
@@ -200,20 +210,21 @@ def main():
     steps = rotations * copies // layers_per_step
     warm = warm_rot * copies // layers_per_step
     step_bytes = layer.step_bytes * layers_per_step
-    launches = rotations * copies * len(layer.mats)
+    per_layer = 1 if args.multi else len(layer.mats)
+    launches = rotations * copies * per_layer
     ms_per_step = wall * 1e3 / steps
     value = step_bytes / (wall / steps) / 1e9
     # dominant kernel = the product kernel (the only kernel in the timed region); its average launch
     # duration from HIP events on the launch stream over the timed region
     avg_launch_us = ev_ms * 1e3 / launches
-    bytes_per_launch = layer.step_bytes / len(layer.mats)
+    bytes_per_launch = layer.step_bytes / per_layer
     achieved = bytes_per_launch / (avg_launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": ("mpq_gemv_kernel" if M == 1 else "mpq_mm_kernel") + " (every launch of the step)", "avg_launch_us": round(avg_launch_us, 3),
+                "kernel": ("mpq_gemv_multi_kernel" if args.multi else "mpq_gemv_kernel" if M == 1 else "mpq_mm_kernel") + " (every launch of the step)", "avg_launch_us": round(avg_launch_us, 3),
                 "bytes_per_launch": round(bytes_per_launch)}
     traffic_file = os.path.join(ROOT, "profiles", "gemv_llama2_7b_traffic.json")
-    if args.config == 1 and M == 1 and not over and args.f4 is None and args.p_o is None and os.path.exists(traffic_file):
+    if args.config == 1 and M == 1 and not over and not args.multi and args.f4 is None and args.p_o is None and os.path.exists(traffic_file):
         try:
             roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
         except Exception:  # noqa: BLE001 - a malformed note must not break the benchmark line
@@ -247,7 +258,7 @@ def main():
                 "%d layer copies %s" % (
                     args.config, MODEL[args.config],
                     "decode sweep over 80 resident layers" if args.config == 4 else "decoder layer",
-                    len(layer.mats) * layers_per_step,
+                    per_layer * layers_per_step,
                     ", ".join(f"{m['spec'].N}x{m['spec'].K}" for m in layer.mats), M, spec0.g1, spec0.g2,
                     " (pairs shared by g2 rows)" if spec0.g2_axis == 1 else "", 100 * spec0.f4, 100 * spec0.p_o, copies,
                     "resident (22.5 GB), each read once per step" if args.config == 4 else "rotated (cold last-level cache)"))

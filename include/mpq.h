@@ -44,6 +44,7 @@ extern "C" {
 
 #define MPQ_HEADER_BYTES 256u
 #define MPQ_MAX_M 32          /* largest batch the small-M product accepts */
+#define MPQ_MAX_MULTI 8       /* most products one mpq_gemv_multi call accepts */
 
 typedef enum {
   MPQ_OK = 0,
@@ -122,6 +123,16 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
  * x_dev: K fp16 values, y_dev: N fp16 values (overwritten), both 16-byte aligned, not aliased. */
 mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev,
                     uint16_t* y_dev, void* stream);
+
+/* `count` independent matrix-vector products (1 <= count <= MPQ_MAX_MULTI) in ONE kernel launch:
+ * y_p = W_p x_p for every p, each exactly as mpq_gemv defines it (Algorithm 1, Sec. 4.3).  For
+ * products that do not depend on each other - separate projections of a layer, the experts a token
+ * is routed to - this saves the fixed cost of a launch per product.  The four arrays are HOST
+ * arrays of `count` entries: header pointers (HOST), blob / x / y pointers (DEVICE).  The matrices
+ * may differ in shape but must have the same g1; no y may alias anything else.
+ * MPQ_ERR_UNSUPPORTED if the products cannot share one launch configuration. */
+mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void* const* blob_dev,
+                          const uint16_t* const* x_dev, uint16_t* const* y_dev, void* stream);
 
 /* Small-batch product Y[m][n] = sum_k X[m][k] W[n][k] (+ outliers), 1 <= M <= MPQ_MAX_M.
  * X_dev is M x K row-major fp16, Y_dev is M x N row-major fp16 (overwritten). */

@@ -25,7 +25,8 @@ STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ
  MPQ_ERR_CSR, MPQ_ERR_BLOB, MPQ_ERR_SIZE, MPQ_ERR_UNSUPPORTED, MPQ_ERR_HIP) = range(11)
 
 EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_packed_size", "mpq_pack_host", "mpq_blob_info",
-           "mpq_dequant", "mpq_gemv", "mpq_gemm"]
+           "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm"]
+MAX_MULTI = 8
 
 
 class MpqError(RuntimeError):
@@ -70,6 +71,9 @@ def lib():
         L.mpq_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         L.mpq_gemv.restype = C.c_int
         L.mpq_gemv.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.mpq_gemv_multi.restype = C.c_int
+        L.mpq_gemv_multi.argtypes = [C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                     C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]
         L.mpq_gemm.restype = C.c_int
         L.mpq_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         _lib = L
@@ -189,6 +193,18 @@ def gemv(header, blob_dev, x_dev, y_dev, stream=None):
     h, hp = _hdr_ptr(header)
     _check(lib().mpq_gemv(hp, blob_dev.data_ptr(), x_dev.data_ptr(), y_dev.data_ptr(),
                           _stream_ptr(stream)), "mpq_gemv")
+
+
+def gemv_multi(headers, blobs_dev, xs_dev, ys_dev, stream=None):
+    """mpq_gemv_multi: lists of headers (host arrays) and of CUDA tensors, one entry per product."""
+    n = len(headers)
+    if not (n == len(blobs_dev) == len(xs_dev) == len(ys_dev)):
+        raise MpqError(MPQ_ERR_SHAPE, "mpq_gemv_multi")
+    keep = [_np(h, np.uint8) for h in headers]
+    arr = lambda vals: (C.c_void_p * n)(*vals)
+    _check(lib().mpq_gemv_multi(n, arr([k.ctypes.data for k in keep]), arr([b.data_ptr() for b in blobs_dev]),
+                                arr([x.data_ptr() for x in xs_dev]), arr([y.data_ptr() for y in ys_dev]),
+                                _stream_ptr(stream)), "mpq_gemv_multi")
 
 
 def gemm(header, blob_dev, X_dev, Y_dev, M, stream=None):

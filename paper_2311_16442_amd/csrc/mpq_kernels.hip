@@ -21,6 +21,7 @@
 //   for.  The product kernel hands the resulting pairs to the matrix core.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "../../include/mpq.h"
 #include "mpq_format.h"
@@ -708,9 +709,9 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
 //
 //   Outliers: groups of four waves (256 threads, 16 lanes per row) take the tiles in turn; the 16
 //   lanes of a row each take every 16th word of the row and are summed with DPP row shifts.
-template <int PD, int LDSB, int WV, int PU = 1>
-__global__ void __launch_bounds__(WV * 64)
-mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg) {
+template <int PD, int LDSB, int WV, int PU>
+__device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
+                                               const int n_arg, const uint32_t wg) {
 #pragma clang fp contract(off)
   static_assert(PD >= 1 && PD <= 8 && WV >= 4 && WV <= 16, "ring depth / waves");
   __shared__ __align__(16) unsigned char lds[LDSB];
@@ -719,7 +720,7 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
   const uint32_t C = b.C, T = b.T;
-  const uint32_t tile0 = blockIdx.x * (uint32_t)n_arg;
+  const uint32_t tile0 = wg * (uint32_t)n_arg;
   const uint32_t n = T - tile0 < (uint32_t)n_arg ? T - tile0 : (uint32_t)n_arg;  // tiles of this workgroup
   // LDS layout: ring | partial sums [n][W + 1][16] | side records [n] | unit table | activations
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;  // pieces per 2-bit unit (PU) and per 4-bit unit
@@ -841,6 +842,32 @@ mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __res
     const uint32_t row = (tile0 + t) * 16 + r;
     if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)sum);
   }
+}
+
+template <int PD, int LDSB, int WV, int PU = 1>
+__global__ void __launch_bounds__(WV * 64)
+mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg) {
+  gemv_workgroup<PD, LDSB, WV, PU>(b, X, Y, n_arg, blockIdx.x);
+}
+
+// Several independent matrix-vector products in one launch (separate projections of a layer, the
+// experts a token is routed to): workgroups [first[p], first[p + 1]) work on problem p, one tile
+// each.  Saves the fixed cost of a launch (about 2.5 us here) per product after the first.
+struct MultiArgs {
+  DevBlob b[MPQ_MAX_MULTI];
+  const uint16_t* X[MPQ_MAX_MULTI];
+  uint16_t* Y[MPQ_MAX_MULTI];
+  uint32_t first[MPQ_MAX_MULTI + 1];
+  int32_t count;
+};
+
+template <int PD, int LDSB, int WV, int PU = 1>
+__global__ void __launch_bounds__(WV * 64)
+mpq_gemv_multi_kernel(const MultiArgs a) {
+  uint32_t p = 0;
+  while ((int32_t)p + 1 < a.count && blockIdx.x >= a.first[p + 1]) ++p;
+  const DevBlob b = a.b[p];
+  gemv_workgroup<PD, LDSB, WV, PU>(b, a.X[p], a.Y[p], 1, blockIdx.x - a.first[p]);
 }
 
 // ------------------------------------------------------------------------------------ dequant
@@ -1270,6 +1297,45 @@ mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* 
 mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev, uint16_t* y_dev,
                     void* stream) {
   return mpq_gemm(hdr_host, blob_dev, x_dev, y_dev, 1, stream);
+}
+
+mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void* const* blob_dev,
+                          const uint16_t* const* x_dev, uint16_t* const* y_dev, void* stream) {
+  if (!hdr_host || !blob_dev || !x_dev || !y_dev) return MPQ_ERR_NULL;
+  if (count < 1 || count > MPQ_MAX_MULTI) return MPQ_ERR_SHAPE;
+  MultiArgs a;
+  memset(&a, 0, sizeof(a));
+  a.count = count;
+  size_t need = 0;
+  int pu = 0;
+  for (int p = 0; p < count; ++p) {
+    if (!x_dev[p] || !y_dev[p]) return MPQ_ERR_NULL;
+    MpqHeader h;
+    mpq_status st = make_dev(hdr_host[p], blob_dev[p], &h, &a.b[p]);
+    if (st != MPQ_OK) return st;
+    if ((((uintptr_t)x_dev[p] | (uintptr_t)y_dev[p]) & 15u) != 0) return MPQ_ERR_ALIGN;
+    if (p > 0 && mpq_pu2(h.g1) != pu) return MPQ_ERR_UNSUPPORTED;
+    pu = mpq_pu2(h.g1);
+    const size_t lds = gemv_lds_bytes(h, 2, 8, 1);
+    need = lds > need ? lds : need;
+    a.X[p] = x_dev[p];
+    a.Y[p] = y_dev[p];
+    a.first[p + 1] = a.first[p] + (uint32_t)h.T;
+  }
+  const dim3 grid(a.first[count]), block(8 * 64);
+  hipStream_t s = (hipStream_t)stream;
+#define MPQ_MULTI_CLASS(BYTES)                                                                          \
+  if (need <= (BYTES)) {                                                                                \
+    if (pu == 1) hipLaunchKernelGGL((mpq_gemv_multi_kernel<2, (BYTES), 8, 1>), grid, block, 0, s, a);   \
+    else if (pu == 2) hipLaunchKernelGGL((mpq_gemv_multi_kernel<2, (BYTES), 8, 2>), grid, block, 0, s, a); \
+    else hipLaunchKernelGGL((mpq_gemv_multi_kernel<2, (BYTES), 8, 4>), grid, block, 0, s, a);           \
+    return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;                                      \
+  }
+  MPQ_MULTI_CLASS(40 * 1024)
+  MPQ_MULTI_CLASS(80 * 1024)
+  MPQ_MULTI_CLASS(160 * 1024)
+#undef MPQ_MULTI_CLASS
+  return MPQ_ERR_UNSUPPORTED;
 }
 
 mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_out_dev, int add_outliers,

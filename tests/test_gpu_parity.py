@@ -223,3 +223,35 @@ def test_large_batch_kernel_within_tolerance(torch, case, M):
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (e_floor, e_max)
     assert np.array_equal(got, again)
+
+
+def test_several_products_in_one_launch(torch):
+    # mpq_gemv_multi: independent products of different shapes (ragged rows, long rows, many outliers)
+    cases = [CASES[0], CASES[1], CASES[6], CASES[8], CASES[2]]
+    built = [make(c) for c in cases]
+    blobs = [to_dev(torch, pk.blob) for _, _, pk in built]
+    Xs = [synth.make_x(900 + p, 1, pk.K) for p, (_, _, pk) in enumerate(built)]
+    xs = [to_dev(torch, X[0].view(np.int16)) for X in Xs]
+    ys = [Guarded(torch, pk.N) for _, _, pk in built]
+    mpq.gemv_multi([pk.header for _, _, pk in built], blobs, xs, [y.view for y in ys])
+    for (lg, om, pk), X, y in zip(built, Xs, ys):
+        got = y.check_and_get()
+        e_floor, e_max = rel_err(got, om.gemm(X, threads=8)[0])
+        assert e_floor <= TOL, (lg.spec.name, e_floor, e_max)
+    # a single product through the same entry point, and the error paths that need no launch
+    y1 = Guarded(torch, built[0][2].N)
+    mpq.gemv_multi([built[0][2].header], blobs[:1], xs[:1], [y1.view])
+    assert np.array_equal(y1.check_and_get(), ys[0].check_and_get())
+    lg16, om16, pk16 = make(CASES[9])                      # g1 = 16 next to g1 = 64: no common configuration
+    b16 = to_dev(torch, pk16.blob)
+    x16 = to_dev(torch, synth.make_x(1, 1, pk16.K)[0].view(np.int16))
+    y16 = Guarded(torch, pk16.N)
+    with pytest.raises(mpq.MpqError) as e:
+        mpq.gemv_multi([built[0][2].header, pk16.header], [blobs[0], b16], [xs[0], x16], [ys[0].view, y16.view])
+    assert e.value.status == mpq.MPQ_ERR_UNSUPPORTED
+    with pytest.raises(mpq.MpqError) as e:
+        mpq.gemv_multi([built[0][2].header] * 9, blobs[:1] * 9, xs[:1] * 9, [ys[0].view] * 9)
+    assert e.value.status == mpq.MPQ_ERR_SHAPE
+    mpq.gemv_multi([pk16.header], [b16], [x16], [y16.view])  # and g1 = 16 on its own
+    e_floor, e_max = rel_err(y16.check_and_get(), om16.gemm(synth.make_x(1, 1, pk16.K), threads=8)[0])
+    assert e_floor <= TOL, (e_floor, e_max)
