@@ -55,7 +55,7 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 // s_waitcnt vmcnt(n) for a wave-uniform n known only at run time (gfx9 encoding: vmcnt in bits
-// 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "do not wait").  Larger n wait for vmcnt(9),
+// 3:0 and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "do not wait").  Larger n wait for vmcnt(15),
 // which is stricter and therefore safe.
 #define MPQ_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 __device__ __forceinline__ void wait_vm(int n) {
@@ -69,7 +69,13 @@ __device__ __forceinline__ void wait_vm(int n) {
     case 6: MPQ_VMCNT(6); break;
     case 7: MPQ_VMCNT(7); break;
     case 8: MPQ_VMCNT(8); break;
-    default: MPQ_VMCNT(9); break;
+    case 9: MPQ_VMCNT(9); break;
+    case 10: MPQ_VMCNT(10); break;
+    case 11: MPQ_VMCNT(11); break;
+    case 12: MPQ_VMCNT(12); break;
+    case 13: MPQ_VMCNT(13); break;
+    case 14: MPQ_VMCNT(14); break;
+    default: MPQ_VMCNT(15); break;
   }
 }
 
@@ -437,14 +443,17 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 struct RangePlan {
   int32_t H, nb2, nb4, R;
   uint32_t off_sides, off_units, off_cpos, off_splits, off_ored, off_xbuf;  // LDS byte offsets (ring at 0)
+  uint32_t xbuf_stride;  // bytes from the first activation buffer to the second
 };
 
-template <int NT, int LDSB>
-__global__ void __launch_bounds__(512)
+template <int NT, int LDSB, int WV>
+__global__ void __launch_bounds__(WV * 64)
 mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M, const RangePlan pl) {
 #pragma clang fp contract(off)
-  constexpr uint32_t W = 8, PD = 2;
-  constexpr uint32_t ROWS = 16 * NT;  // staged batch rows
+  static_assert(WV == 8 || WV == 16, "waves");
+  constexpr uint32_t W = WV, PD = 2;
+  constexpr uint32_t ROWS = 16 * NT;   // staged batch rows
+  constexpr uint32_t OPASS = 16 / W;   // passes of four rows per wave over the 64 rows of a tile group
   __shared__ __align__(16) unsigned char lds[LDSB];
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -517,6 +526,39 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
   const bool stage_on = sm < (uint32_t)M;
   uint32_t slot = 0, c = wv;
 
+  // Requests the activations of range HH into buffer HH % 2: 64-slot pieces, round-robin over the
+  // waves.  stg counts this wave's requests; blocks_before = code blocks of this wave requested
+  // earlier and still in flight (their waits must allow for the younger staging requests).
+  uint32_t stg = 0, blocks_before = 0;
+#define MPQ_R_STAGE(HH)                                                                              \
+  {                                                                                                   \
+    constexpr uint32_t PP = 4 / NT; /* steps per 64-slot piece */                                     \
+    const uint32_t sa2 = (HH) * nb2, sa4 = (HH) * nb4;                                                \
+    const uint32_t sn2 = sa2 < B2 ? (B2 - sa2 < nb2 ? B2 - sa2 : nb2) : 0;                            \
+    const uint32_t sn4 = sa4 < B4 ? (B4 - sa4 < nb4 ? B4 - sa4 : nb4) : 0;                            \
+    const uint32_t items2 = sn2 * 4u * (8u / PP), items = items2 + sn4 * 4u * (4u / PP);              \
+    const uint32_t sbuf = lds_addr(xbuf) + ((HH) & 1u) * pl.xbuf_stride;                              \
+    stg = 0;                                                                                          \
+    blocks_before = inflight;                                                                         \
+    for (uint32_t it = wv; it < items; it += W) {                                                     \
+      uint32_t unit, p0, dst;                                                                         \
+      if (it < items2) {                                                                              \
+        const uint32_t ul = it / (8u / PP);                                                           \
+        p0 = (it % (8u / PP)) * PP;                                                                   \
+        unit = sa2 * 4u + ul;                                                                         \
+        dst = (ul * 8u + p0) * ROWS * 16u;                                                            \
+      } else {                                                                                        \
+        const uint32_t it4 = it - items2, ul = it4 / (4u / PP);                                       \
+        p0 = (it4 % (4u / PP)) * PP;                                                                  \
+        unit = 4u * B2 + sa4 * 4u + ul;                                                               \
+        dst = base4 + (ul * 4u + p0) * ROWS * 16u;                                                    \
+      }                                                                                               \
+      const uint32_t k0x2 = *(const uint32_t*)(units + unit * 8u); /* same address in every lane */   \
+      if (stage_on) dma16((const unsigned char*)X, stage_off + k0x2 + p0 * 16u, sbuf + dst);          \
+      ++stg;                                                                                          \
+    }                                                                                                 \
+  }
+
   for (uint32_t grp = blockIdx.x; grp < ngroups; grp += grid) {
     const uint32_t Rn = T - grp * R < R ? T - grp * R : R;
     // ---- side records of the group's tiles
@@ -545,36 +587,21 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
     float4_t acc20 = acc00, acc21 = acc00, acc30 = acc00, acc31 = acc00;
     float oa00 = 0.f, oa01 = 0.f, oa10 = 0.f, oa11 = 0.f;  // [pass][batch half]
 
+    MPQ_R_STAGE(0u)  // the first range's activations; the barrier also publishes the splits
+    MPQ_VMCNT(0);
+    blocks_before = 0;
+    lds_barrier();
     for (uint32_t h = 0; h < H; ++h) {
       const uint32_t a2 = h * nb2, a4 = h * nb4;
       const uint32_t n2 = a2 < B2 ? (B2 - a2 < nb2 ? B2 - a2 : nb2) : 0;
       const uint32_t n4 = a4 < B4 ? (B4 - a4 < nb4 ? B4 - a4 : nb4) : 0;
       const uint32_t len = n2 + n4;
-      // ---- stage the activations of the range: 64-slot pieces, round-robin over the waves
-      lds_barrier();  // everybody is done with the previous range (and has written its splits)
-      {
-        constexpr uint32_t PP = 4 / NT;                  // steps per 64-slot piece
-        const uint32_t items2 = n2 * 4u * (8u / PP), items = items2 + n4 * 4u * (4u / PP);
-        for (uint32_t it = wv; it < items; it += W) {
-          uint32_t unit, p0, dst;
-          if (it < items2) {
-            const uint32_t ul = it / (8u / PP);
-            p0 = (it % (8u / PP)) * PP;
-            unit = a2 * 4u + ul;
-            dst = (ul * 8u + p0) * ROWS * 16u;
-          } else {
-            const uint32_t it4 = it - items2, ul = it4 / (4u / PP);
-            p0 = (it4 % (4u / PP)) * PP;
-            unit = 4u * B2 + a4 * 4u + ul;
-            dst = base4 + (ul * 4u + p0) * ROWS * 16u;
-          }
-          const uint32_t k0x2 = *(const uint32_t*)(units + unit * 8u);  // same address in every lane
-          if (stage_on) dma16((const unsigned char*)X, stage_off + k0x2 + p0 * 16u, lds_addr(xbuf) + dst);
-        }
-      }
-      MPQ_VMCNT(0);
-      lds_barrier();
-
+      const unsigned char* const xcur = xbuf + (h & 1u) * pl.xbuf_stride;  // this range's activations
+      // ---- two buffers: request the activations of the NEXT range into the other buffer (everybody
+      //      left it at the barrier that closed the previous range); they land while this range is
+      //      computed.  One buffer (xbuf_stride = 0, larger ranges): staged between two barriers below.
+      const bool two_bufs = pl.xbuf_stride != 0;
+      if (two_bufs && h + 1 < H) MPQ_R_STAGE(h + 1)
       // ---- the range's blocks of the group's tiles
 #define MPQ_R_STEP(TWO, P, A0, A1)                                                                   \
   {                                                                                                   \
@@ -589,7 +616,11 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
     }                                                                                                 \
   }
 #define MPQ_R_HEAD(BLK)                                                                                \
-  if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
+  /* younger than the block needed now: the other blocks in flight and, for blocks requested before  \
+     the staging of the next range, this wave's staging requests */                                  \
+  if (blocks_before > 0) { wait_vm((int)(inflight - 1 + stg)); --blocks_before; }                     \
+  else if (inflight == PD) MPQ_VMCNT(PD - 1);                                                         \
+  else wait_vm((int)inflight - 1);                                                                    \
   uint4 q;                                                                                            \
   asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
   --inflight;                                                                                         \
@@ -608,14 +639,14 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
     const unsigned char* m2i = sides + (TT) * b.side_bytes + b.off_m2 + (i >> b.m2_shift) * 4;        \
     for (; c < n2; c += W) {                                                                          \
       MPQ_R_HEAD(a2 + c)                                                                              \
-      const unsigned char* xb0 = xb2 + c * (8192u * NT);                                              \
+      const unsigned char* xb0 = xb2 + (h & 1u) * pl.xbuf_stride + c * (8192u * NT);                  \
       const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};                            \
       MPQ_R_STEP(true, 0, A0, A1) MPQ_R_STEP(true, 1, A0, A1) MPQ_R_STEP(true, 2, A0, A1) MPQ_R_STEP(true, 3, A0, A1) \
       MPQ_R_STEP(true, 4, A0, A1) MPQ_R_STEP(true, 5, A0, A1) MPQ_R_STEP(true, 6, A0, A1) MPQ_R_STEP(true, 7, A0, A1) \
     }                                                                                                 \
     for (; c < len; c += W) {                                                                         \
       MPQ_R_HEAD(B2 + a4 + (c - n2))                                                                  \
-      const unsigned char* xb0 = xb4 + (c - n2) * (4096u * NT);                                       \
+      const unsigned char* xb0 = xb4 + (h & 1u) * pl.xbuf_stride + (c - n2) * (4096u * NT);           \
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};                                \
       MPQ_R_STEP(false, 0, A0, A1) MPQ_R_STEP(false, 1, A0, A1) MPQ_R_STEP(false, 2, A0, A1) MPQ_R_STEP(false, 3, A0, A1) \
     }                                                                                                 \
@@ -629,14 +660,14 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
       // ---- the range's outlier words of this wave's rows (two passes of four rows)
 #define MPQ_R_OUTL(PASS, O0, O1)                                                                      \
   {                                                                                                   \
-    const uint32_t fr = wv * 8u + (PASS) * 4u + j, t = fr >> 4, r = fr & 15u;                         \
+    const uint32_t fr = wv * (4u * OPASS) + (PASS) * 4u + j, t = fr >> 4, r = fr & 15u;               \
     if (t < Rn) {                                                                                     \
       const uint32_t* owords = (const uint32_t*)(sides + t * b.side_bytes + b.off_ot + MPQ_OTILE_HEAD); \
       const uint32_t e0 = splits[(t * (H + 1) + h) * 16u + r], e1 = splits[(t * (H + 1) + h + 1) * 16u + r]; \
       for (uint32_t e = e0; e < e1; ++e) {                                                            \
         const uint32_t word = owords[e], col = word & 0xFFFFu;                                        \
         const uint32_t ul = (uint32_t)cpos[col >> 6] - a2 * 4u;                                       \
-        const unsigned char* xp = xbuf + (ul * 8u + ((col >> 3) & 7u)) * (ROWS * 16u) + i * 16u + (col & 7u) * 2u; \
+        const unsigned char* xp = xcur + (ul * 8u + ((col >> 3) & 7u)) * (ROWS * 16u) + i * 16u + (col & 7u) * 2u; \
         const float v = (float)bits_to_half((uint16_t)(word >> 16));                                  \
         O0 += v * (float)*(const half_t*)xp;                                                          \
         if (NT > 1) O1 += v * (float)*(const half_t*)(xp + 256);                                      \
@@ -644,7 +675,22 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
     }                                                                                                 \
   }
       MPQ_R_OUTL(0u, oa00, oa01)
-      MPQ_R_OUTL(1u, oa10, oa11)
+      if (OPASS > 1) MPQ_R_OUTL(1u, oa10, oa11)
+      // ---- the next range's activations have landed (every wave waits for its own requests) and
+      //      everybody is done with this range's
+      if (two_bufs) {
+        MPQ_VMCNT(0);
+        blocks_before = 0;
+        lds_barrier();
+      } else {
+        lds_barrier();
+        if (h + 1 < H) {
+          MPQ_R_STAGE(h + 1)
+          MPQ_VMCNT(0);
+          blocks_before = 0;
+          lds_barrier();
+        }
+      }
     }
 #undef MPQ_R_OUTL
 #undef MPQ_R_TILE
@@ -654,16 +700,19 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
     // ---- park the accumulators (lane l holds Y[m = l % 16 (+16)][rows 4*(l/16) .. +3] of a tile) in
     //      the activation buffer, two tiles at a time: [wave][tile of the pair][batch half][m][row]
     {
-      float* orow0 = ored + ((wv * 8u + j) * NT) * 16u + i;
-      float* orow1 = ored + ((wv * 8u + 4u + j) * NT) * 16u + i;
+      float* orow0 = ored + ((wv * (4u * OPASS) + j) * NT) * 16u + i;
       orow0[0] = oa00;
-      orow1[0] = oa10;
-      if (NT > 1) { orow0[16] = oa01; orow1[16] = oa11; }
+      if (NT > 1) orow0[16] = oa01;
+      if (OPASS > 1) {
+        float* orow1 = orow0 + 4u * NT * 16u;
+        orow1[0] = oa10;
+        if (NT > 1) orow1[16] = oa11;
+      }
     }
 #pragma unroll
     for (uint32_t pair = 0; pair < 2; ++pair) {
       if (pair * 2u >= Rn) break;
-      lds_barrier();  // everybody is done with the activation buffer (first pair) / with the previous pair
+      if (pair > 0) lds_barrier();  // everybody is done with the previous pair (the ranges ended with a barrier)
       float* park = (float*)xbuf + wv * (2u * NT * 256u) + i * 16u + 4u * j;
       *(float4_t*)(park + (0 * NT + 0) * 256) = pair == 0 ? acc00 : acc20;
       *(float4_t*)(park + (1 * NT + 0) * 256) = pair == 0 ? acc10 : acc30;
@@ -1011,7 +1060,8 @@ int g_persist = -1;     // -1 = automatic (persistent workgroups for M > 1)
 int g_gemv_waves = 0;   // 0 = automatic (8 or 16 waves per workgroup of the GEMV)
 int g_ranges = -1;      // -1 = automatic (large-batch kernel when the activations do not fit the LDS)
 int g_range_tiles = 0;  // 0 = automatic (tiles per group of the large-batch kernel, 1..4)
-int g_range_per_cu = 0; // 0 = automatic (1 forces one workgroup per compute unit for the large-batch kernel)
+int g_range_per_cu = 0; // 0 = automatic (workgroups of the large-batch kernel per compute unit: 1 = 16 waves, 2 = 2 x 8 waves)
+int g_range_bufs = 0;   // 0 = automatic, 1 = one activation buffer, 2 = two (large-batch kernel)
 int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
 int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
 int g_cu_count = 0;
@@ -1173,10 +1223,11 @@ mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
   return MPQ_ERR_UNSUPPORTED;
 }
 
-// Plan of the large-batch kernel for an LDS budget: tiles per group R (at most `Rwant`), ranges H
-// and the LDS layout, with the fewest ranges for the largest R that fits.
-bool plan_ranges(const MpqHeader& h, int NT, uint32_t budget, uint32_t Rwant, RangePlan* pl) {
-  const uint32_t W = 8, PD = 2, RMAX = 4;
+// Plan of the large-batch kernel for an LDS budget and W waves: tiles per group R (at most `Rwant`),
+// ranges H and the LDS layout (two activation buffers), with the fewest ranges for the largest R
+// that fits.
+bool plan_ranges(const MpqHeader& h, int NT, uint32_t W, uint32_t budget, uint32_t Rwant, bool two_bufs, RangePlan* pl) {
+  const uint32_t PD = 2, RMAX = 4;
   const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
   const uint32_t maxH = B2 > B4 ? (B2 > 0 ? B2 : 1) : (B4 > 0 ? B4 : 1);
   for (uint32_t R = Rwant > RMAX ? RMAX : Rwant; R >= 1; --R) {
@@ -1190,8 +1241,12 @@ bool plan_ranges(const MpqHeader& h, int NT, uint32_t budget, uint32_t Rwant, Ra
       pl->off_ored = off;   off += RMAX * NT * 1024u;
       off = (off + 1023u) & ~1023u;
       pl->off_xbuf = off;
+      // two buffers (one if there is a single range); together they also hold the parked accumulators
       const uint32_t xr = (32u * nb2 + 16u * nb4) * 256u * NT, park = W * 2u * NT * 1024u;
-      off += xr > park ? xr : park;
+      uint32_t both = H > 1 && two_bufs ? 2u * xr : xr;
+      if (both < park) both = park;
+      pl->xbuf_stride = H > 1 && two_bufs ? xr : 0;
+      off += both;
       if (off <= budget) {
         pl->H = (int32_t)H; pl->nb2 = (int32_t)nb2; pl->nb4 = (int32_t)nb4; pl->R = (int32_t)R;
         return true;
@@ -1201,30 +1256,42 @@ bool plan_ranges(const MpqHeader& h, int NT, uint32_t budget, uint32_t Rwant, Ra
   return false;
 }
 
-// Two workgroups per compute unit (80 KiB each) when that fits, so that one stages while the other
-// computes; tiles per group so that the groups about fill the workgroup slots.
+// One workgroup of 16 waves per compute unit, or two of 8 waves (80 KiB each) when that does not
+// cost more ranges; tiles per group so that the groups about fill the workgroup slots.
 mpq_status launch_ranges(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
   const int NT = M > 16 ? 2 : 1;
   const long cus = cu_count();
-  RangePlan pl;
-  long per_cu = 2;
-  uint32_t Rwant = (uint32_t)((h.T + 2 * cus - 1) / (2 * cus));
-  if (g_range_tiles > 0) Rwant = (uint32_t)g_range_tiles;
-  if (Rwant < 1) Rwant = 1;
-  if (g_range_per_cu == 1 || !plan_ranges(h, NT, 80 * 1024, Rwant, &pl)) {
-    per_cu = 1;
-    if (g_range_tiles <= 0) Rwant = (uint32_t)((h.T + cus - 1) / cus);
-    if (!plan_ranges(h, NT, 160 * 1024, Rwant, &pl)) return MPQ_ERR_UNSUPPORTED;
-  }
+  RangePlan p2, p1;
+  // tiles per group: the R <= 4 with the shortest schedule = rounds of groups x (R tiles + the fixed
+  // cost of a group, staging and barriers, worth about one and a half tiles), the larger R on a tie
+  auto best_r = [&](long slots) {
+    uint32_t best = 1;
+    long best_span = -1;
+    for (uint32_t R = 1; R <= 4; ++R) {
+      const long groups = (h.T + R - 1) / R, span = ((groups + slots - 1) / slots) * (2 * R + 3);
+      if (best_span < 0 || span <= best_span) { best = R; best_span = span; }
+    }
+    return best;
+  };
+  uint32_t R2 = best_r(2 * cus), R1 = best_r(cus);
+  if (g_range_tiles > 0) R2 = R1 = (uint32_t)g_range_tiles;
+  const bool dbl = g_range_bufs == 2;  // one buffer and fewer, larger ranges measured faster almost everywhere
+  const bool ok2 = plan_ranges(h, NT, 8, 80 * 1024, R2, dbl, &p2);
+  const bool ok1 = plan_ranges(h, NT, 16, 160 * 1024, R1, dbl, &p1);
+  if (!ok1 && !ok2) return MPQ_ERR_UNSUPPORTED;
+  bool two = !ok1;
+  if (g_range_per_cu == 1 && ok1) two = false;
+  if (g_range_per_cu == 2 && ok2) two = true;
+  const RangePlan pl = two ? p2 : p1;
   const long ngroups = (h.T + pl.R - 1) / pl.R;
-  long grid = cus * per_cu;
+  long grid = cus * (two ? 2 : 1);
   if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
   if (grid > ngroups) grid = ngroups;
-#define MPQ_LAUNCH_R(NTV, BYTES) \
-  hipLaunchKernelGGL((mpq_mmr_kernel<NTV, BYTES>), dim3((unsigned)grid), dim3(512), 0, s, d, X, Y, M, pl)
-  if (per_cu == 2) { if (NT == 1) MPQ_LAUNCH_R(1, 80 * 1024); else MPQ_LAUNCH_R(2, 80 * 1024); }
-  else             { if (NT == 1) MPQ_LAUNCH_R(1, 160 * 1024); else MPQ_LAUNCH_R(2, 160 * 1024); }
+#define MPQ_LAUNCH_R(NTV, BYTES, WV) \
+  hipLaunchKernelGGL((mpq_mmr_kernel<NTV, BYTES, WV>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M, pl)
+  if (two) { if (NT == 1) MPQ_LAUNCH_R(1, 80 * 1024, 8); else MPQ_LAUNCH_R(2, 80 * 1024, 8); }
+  else     { if (NT == 1) MPQ_LAUNCH_R(1, 160 * 1024, 16); else MPQ_LAUNCH_R(2, 160 * 1024, 16); }
 #undef MPQ_LAUNCH_R
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
@@ -1237,16 +1304,22 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
   if (Mc > 16 && Mc < M) Mc = 16;
   {
     // The large-batch kernel reads and decodes the weights once whatever M is, but pays a chain of
-    // staging steps per tile group; measured against the chunked path on the Llama2-7B shapes it
-    // wins when the weights would be decoded three times, or twice / with fewer than 8 waves per
-    // compute unit on a matrix with enough row tiles to keep every compute unit busy.
+    // staging steps per tile group; measured against the chunked path on the Llama2-7B and
+    // Llama2-70B shapes it wins when the weights would be decoded three times, or when the chunked
+    // path is left with 4 waves per compute unit on a matrix with at least 2 (two chunks) or 3 (one
+    // chunk) row tiles per compute unit.
     const int chunks = (M + Mc - 1) / Mc, cus = cu_count();
-    const bool waves8 = mm_lds_bytes(h, M < Mc ? M : Mc, 2, true, 8) <= kLdsPerCu;
-    const bool better = chunks >= 3 || (chunks == 2 && h.T >= 3 * cus) || (chunks == 1 && !waves8 && h.T >= 4 * cus);
+    const int rows = (M + chunks - 1) / chunks;  // batch rows per chunk
+    const bool waves8 = mm_lds_bytes(h, rows, 2, true, 8) <= kLdsPerCu;
+    const bool better = chunks >= 3 || (!waves8 && h.T >= (chunks == 2 ? 2 : 3) * cus);
     if (g_ranges < 0 ? better : g_ranges != 0) {
       const mpq_status st = launch_ranges(h, d, X, Y, M, s);
       if (st != MPQ_ERR_UNSUPPORTED) return st;
     }
+  }
+  {
+    const int chunks = (M + Mc - 1) / Mc;
+    Mc = (M + chunks - 1) / chunks;  // chunks of about equal size (8 rows as 4 + 4, not 7 + 1)
   }
   for (int m0 = 0; m0 < M; m0 += Mc) {
     const int mc = M - m0 < Mc ? M - m0 : Mc;
@@ -1268,8 +1341,8 @@ extern "C" {
 // 1 persistent workgroups, -1 automatic (batch kernel); key 4: waves per workgroup of the GEMV (8, 16), 0 automatic;
 // key 5: waves per workgroup of the persistent batch kernel (4, 8, 16), 0 automatic; key 6: tiles per
 // workgroup of the GEMV (1..8), 0 automatic; key 7: 1 large-batch (range) kernel for every M > 1, 0 never,
-// -1 automatic; key 8: tiles per group of the large-batch kernel (1..4), 0 automatic; key 9: 1 = one
-// workgroup of the large-batch kernel per compute unit, 0 automatic.
+// -1 automatic; key 8: tiles per group of the large-batch kernel (1..4), 0 automatic; key 9: workgroups
+// of the large-batch kernel per compute unit (1 = one of 16 waves, 2 = two of 8 waves), 0 automatic.
 void mpq_debug_set(int key, int value) {
   if (key == 0) g_ring_depth = value;
   if (key == 2) g_max_blocks = value;
@@ -1280,6 +1353,7 @@ void mpq_debug_set(int key, int value) {
   if (key == 7) g_ranges = value;
   if (key == 8) g_range_tiles = value;
   if (key == 9) g_range_per_cu = value;
+  if (key == 10) g_range_bufs = value;
 }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,

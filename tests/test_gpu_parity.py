@@ -197,11 +197,13 @@ def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
     assert e_floor <= TOL, (e_floor, e_max)
 
 
+@pytest.mark.parametrize("per_cu", [1, 2])
 @pytest.mark.parametrize("M", [2, 7, 16, 17, 32])
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_large_batch_kernel_within_tolerance(torch, case, M):
+def test_large_batch_kernel_within_tolerance(torch, case, M, per_cu):
     # the kernel that stages the activations range by range, forced for every batch size through
-    # the tuning hook (by itself the library takes it for M > 8 or long rows)
+    # the tuning hook, as one workgroup of 16 waves or two of 8 waves per compute unit (by itself
+    # the library takes it where the other batch kernel would decode the weights several times)
     import ctypes
     lg, om, pk = make(case)
     hook = mpq.lib().mpq_debug_set
@@ -209,9 +211,10 @@ def test_large_batch_kernel_within_tolerance(torch, case, M):
     blob = to_dev(torch, pk.blob)
     X = synth.make_x(500 + M, M, pk.K)
     ref = om.gemm(X, threads=8)
-    print("case", case, "M", M, flush=True)
+    print("case", case, "M", M, "per_cu", per_cu, flush=True)
     try:
         hook(7, 1)
+        hook(9, per_cu)
         Y = Guarded(torch, M * pk.N)
         mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
         got = Y.check_and_get().reshape(M, pk.N)
@@ -220,6 +223,7 @@ def test_large_batch_kernel_within_tolerance(torch, case, M):
         again = Y2.check_and_get().reshape(M, pk.N)
     finally:
         hook(7, -1)
+        hook(9, 0)
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (e_floor, e_max)
     assert np.array_equal(got, again)
