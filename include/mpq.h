@@ -81,6 +81,20 @@ typedef struct {
   const uint16_t* val;     /* [nnz]   fp16 outlier value                                         */
 } mpq_logical;
 
+/* The arrays of mpq_logical as outputs (HOST, caller-allocated, same shapes; col / val hold
+ * `outlier_capacity` entries). */
+typedef struct {
+  uint8_t* is4;
+  uint8_t* codes;
+  uint8_t* s_int;
+  uint8_t* z1;
+  uint16_t* s2;
+  uint16_t* z2;
+  int32_t* row_ptr;
+  uint16_t* col;
+  uint16_t* val;
+} mpq_logical_out;
+
 /* Human-readable name of a status code; never NULL. */
 const char* mpq_status_str(mpq_status s);
 
@@ -94,6 +108,27 @@ const char* mpq_status_str(mpq_status s);
  *         (Sec. 4.2).
  * Returns a negative value on invalid arguments. */
 double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns_bits);
+
+/* Reference quantizer: float weights W[N*K] (row-major, HOST) -> the logical format.
+ *   - Sec. 3.3 (eq. 9 with the Hessian term set to one: no calibration data): the n4 groups of input
+ *     channels with the largest sum of squared weights over all rows become 4-bit (ties: lower index);
+ *   - Sec. 4.3: per row the round(p_o * number of 2-bit columns) weights of largest magnitude among
+ *     the row's 2-bit columns are outliers (ties: lower column); they do not widen their group's
+ *     range, and their stored value is fp16(w - dequantized dense value) (dense + sparse, Sec. 2.3);
+ *   - Sec. 2.2 eqs. 2-4 per (row, group) over the non-outlier weights: s = (max - min) / (2^N - 1)
+ *     (a constant group: s = |w|, or 1), z = clamp(round(-min / s), 0, 2^N - 1),
+ *     code = clamp(round(w / s) + z, 0, 2^N - 1);
+ *   - second-order quantization of the scales to 8 bits along d->g2_axis in groups of g2:
+ *     s2 = fp16(max((s_max - s_min) / 255, s_max / 2047)) (the second term keeps |z2| <= 2047, which
+ *     fp16 holds exactly, when the scales are nearly equal), z2 = fp16(round(-s_min / s2)),
+ *     s_int = clamp(round(s / s2) + z2, 0, 255); zero points and codes are then computed against the
+ *     scale as the decoder reconstructs it, fp16((s_int - z2) * s2).
+ * All arithmetic in binary64, round() = round half to even, fp16 conversions through binary32.
+ * `*nnz` receives the number of outliers; MPQ_ERR_SIZE if it exceeds `outlier_capacity`
+ * (N * round(p_o * (G - n4) * g1) entries are needed).  MPQ_ERR_SHAPE for n4 outside [0, G] or
+ * p_o outside [0, 1]. */
+mpq_status mpq_quantize_host(const mpq_desc* d, const float* W, int32_t n4, double p_o,
+                             const mpq_logical_out* out, int64_t outlier_capacity, int64_t* nnz);
 
 /* Size in bytes of the packed blob for this shape, 4-bit map and outlier row pointer.
  * `is4` is a HOST array of G bytes, `row_ptr` a HOST array of N+1 entries (the blob stores the

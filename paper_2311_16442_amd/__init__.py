@@ -24,7 +24,7 @@ STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ
 (MPQ_OK, MPQ_ERR_NULL, MPQ_ERR_SHAPE, MPQ_ERR_ALIGN, MPQ_ERR_CODE_RANGE, MPQ_ERR_OUTLIER_IN_4BIT,
  MPQ_ERR_CSR, MPQ_ERR_BLOB, MPQ_ERR_SIZE, MPQ_ERR_UNSUPPORTED, MPQ_ERR_HIP) = range(11)
 
-EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_packed_size", "mpq_pack_host", "mpq_blob_info",
+EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_quantize_host", "mpq_packed_size", "mpq_pack_host", "mpq_blob_info",
            "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm"]
 MAX_MULTI = 8
 
@@ -39,6 +39,11 @@ class MpqError(RuntimeError):
 class Desc(C.Structure):
     _fields_ = [("N", C.c_int32), ("K", C.c_int32), ("g1", C.c_int32), ("g2", C.c_int32),
                 ("g2_axis", C.c_int32)]
+
+
+class LogicalOutPtrs(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("is4", "codes", "s_int", "z1", "s2", "z2", "row_ptr", "col", "val")]
 
 
 class LogicalPtrs(C.Structure):
@@ -60,6 +65,9 @@ def lib():
         L.mpq_status_str.argtypes = [C.c_int]
         L.mpq_avg_bits.restype = C.c_double
         L.mpq_avg_bits.argtypes = [C.POINTER(Desc), C.c_int32, C.c_int64, C.c_int, C.c_int]
+        L.mpq_quantize_host.restype = C.c_int
+        L.mpq_quantize_host.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_int32, C.c_double,
+                                        C.POINTER(LogicalOutPtrs), C.c_int64, C.POINTER(C.c_int64)]
         L.mpq_packed_size.restype = C.c_int
         L.mpq_packed_size.argtypes = [C.POINTER(Desc), C.c_void_p, C.c_void_p, C.POINTER(C.c_size_t)]
         L.mpq_pack_host.restype = C.c_int
@@ -108,6 +116,29 @@ def packed_size(N, K, g1, g2, is4, row_ptr, g2_axis=0) -> int:
     _check(lib().mpq_packed_size(C.byref(d), is4.ctypes.data_as(C.c_void_p), rp.ctypes.data_as(C.c_void_p),
                                  C.byref(out)), "mpq_packed_size")
     return int(out.value)
+
+
+def quantize(W, g1, g2, n4, p_o, g2_axis=0) -> dict:
+    """mpq_quantize_host: float weights [N, K] -> dict of the logical arrays (the keyword arguments of pack)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    if W.ndim != 2:
+        raise MpqError(MPQ_ERR_SHAPE, "mpq_quantize_host")
+    N, K = W.shape
+    d = Desc(int(N), int(K), int(g1), int(g2), int(g2_axis))
+    if g1 <= 0 or g2 <= 0 or K % g1 != 0 or not 0 <= n4 <= K // g1 or not 0.0 <= p_o <= 1.0:
+        raise MpqError(MPQ_ERR_SHAPE, "mpq_quantize_host")
+    G = K // g1
+    cap = N * int(np.floor(p_o * (G - n4) * g1 + 0.5))
+    shape2 = (N, -(-G // g2)) if g2_axis == 0 else (-(-N // g2), G)
+    out = dict(is4=np.zeros(G, np.uint8), codes=np.zeros((N, K), np.uint8), s_int=np.zeros((N, G), np.uint8),
+               z1=np.zeros((N, G), np.uint8), s2=np.zeros(shape2, np.uint16), z2=np.zeros(shape2, np.uint16),
+               row_ptr=np.zeros(N + 1, np.int32), col=np.zeros(max(cap, 1), np.uint16), val=np.zeros(max(cap, 1), np.uint16))
+    ptrs = LogicalOutPtrs(**{k: v.ctypes.data for k, v in out.items()})
+    nnz = C.c_int64(0)
+    _check(lib().mpq_quantize_host(C.byref(d), W.ctypes.data_as(C.c_void_p), int(n4), float(p_o), C.byref(ptrs),
+                                   cap, C.byref(nnz)), "mpq_quantize_host")
+    out["col"], out["val"] = out["col"][: nnz.value], out["val"][: nnz.value]
+    return out
 
 
 @dataclass

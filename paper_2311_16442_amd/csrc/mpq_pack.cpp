@@ -1,8 +1,10 @@
 // mpq_pack.cpp - host side of the library: validation of the logical format, the packed-blob
 // builder (Sec. 3.3 "Memory Alignment": two code matrices with aligned, width-homogeneous vector
 // units), blob inspection and the average-bit formulas (Sec. 2.2, Sec. 3.3, Sec. 4.2).
+#include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "../../include/mpq.h"
@@ -78,6 +80,61 @@ int32_t count4(const mpq_desc* d, const uint8_t* is4) {
   return n4;
 }
 
+// ---- software fp16 (IEEE binary16, round to nearest even) for the host quantizer
+float half_to_float(uint16_t hbits) {
+  const uint32_t sign = (uint32_t)(hbits & 0x8000u) << 16;
+  const uint32_t e = (hbits >> 10) & 0x1Fu, m = hbits & 0x3FFu;
+  uint32_t f;
+  if (e == 0) {
+    if (m == 0) { f = sign; }
+    else {  // subnormal: value m * 2^-24
+      float v = (float)m * 5.9604644775390625e-08f;
+      memcpy(&f, &v, 4);
+      f |= sign;
+    }
+  } else if (e == 31) {
+    f = sign | 0x7F800000u | (m << 13);
+  } else {
+    f = sign | ((e + 112u) << 23) | (m << 13);
+  }
+  float out;
+  memcpy(&out, &f, 4);
+  return out;
+}
+
+uint16_t float_to_half(float v) {
+  uint32_t f;
+  memcpy(&f, &v, 4);
+  const uint16_t sign = (uint16_t)((f >> 16) & 0x8000u);
+  const uint32_t a = f & 0x7FFFFFFFu;
+  if (a >= 0x7F800000u) return (uint16_t)(sign | 0x7C00u | (a > 0x7F800000u ? 0x200u : 0u));  // inf / NaN
+  if (a >= 0x477FF000u) return (uint16_t)(sign | 0x7C00u);  // rounds to 2^16 or above: infinity
+  if (a < 0x33000001u) return sign;                          // at most half of the smallest subnormal
+  const int32_t e = (int32_t)(a >> 23) - 127;
+  uint32_t mant = (a & 0x7FFFFFu) | 0x800000u;  // 24 significant bits
+  int shift = e >= -14 ? 13 : 13 + (-14 - e);   // bits dropped (normal: 13; subnormal: more)
+  const uint32_t kept = mant >> shift, rest = mant & ((1u << shift) - 1u), halfway = 1u << (shift - 1);
+  uint32_t r = kept;
+  if (rest > halfway || (rest == halfway && (kept & 1u))) ++r;
+  if (e >= -14) {
+    // r has 11 bits (implicit one at bit 10) or carried to 12 bits; adding the exponent absorbs the carry
+    return (uint16_t)(sign | (uint16_t)((((uint32_t)(e + 15) << 10) - 0x400u) + r));
+  }
+  return (uint16_t)(sign | (uint16_t)r);  // subnormal (a carry into bit 10 is the smallest normal)
+}
+
+// the decoder's two steps on the host (definition at the top of mpq.h): separate binary32 operations
+uint16_t host_scale_dequant(uint8_t s_int, uint16_t z2, uint16_t s2) {
+  volatile float t = (float)s_int - half_to_float(z2);
+  volatile float u = t * half_to_float(s2);
+  return float_to_half(u);
+}
+
+uint16_t host_weight_dequant(uint8_t code, uint8_t z1, uint16_t s1) {
+  volatile float p = (float)((int)code - (int)z1) * half_to_float(s1);
+  return float_to_half(p);
+}
+
 }  // namespace
 
 // Used by the device entry points: a header is accepted only if it is exactly what the packer
@@ -136,6 +193,126 @@ double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns
     return alpha * two_bit + (1.0 - alpha) * 4.0 + (16.0 + 16.0 - 2.0) * (double)nnz / NK;
   }
   return -1.0;
+}
+
+mpq_status mpq_quantize_host(const mpq_desc* d, const float* W, int32_t n4, double p_o,
+                             const mpq_logical_out* o, int64_t outlier_capacity, int64_t* nnz_out) {
+  if (!d || !W || !o || !nnz_out) return MPQ_ERR_NULL;
+  if (!o->is4 || !o->codes || !o->s_int || !o->z1 || !o->s2 || !o->z2 || !o->row_ptr) return MPQ_ERR_NULL;
+  if (!desc_ok(d)) return MPQ_ERR_SHAPE;
+  const int64_t N = d->N, K = d->K, g1 = d->g1, g2 = d->g2, G = K / g1;
+  if (n4 < 0 || n4 > G || !(p_o >= 0.0 && p_o <= 1.0) || outlier_capacity < 0) return MPQ_ERR_SHAPE;
+  // ---- Sec. 3.3, eq. 9 with a unit Hessian: the n4 most sensitive groups are 4-bit
+  std::vector<double> S((size_t)G, 0.0);
+  for (int64_t g = 0; g < G; ++g) {
+    double acc = 0.0;
+    for (int64_t n = 0; n < N; ++n)
+      for (int64_t k = g * g1; k < (g + 1) * g1; ++k) acc += (double)W[n * K + k] * (double)W[n * K + k];
+    S[(size_t)g] = acc;
+  }
+  std::vector<int32_t> order((size_t)G);
+  for (int64_t g = 0; g < G; ++g) order[(size_t)g] = (int32_t)g;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return S[(size_t)a] > S[(size_t)b]; });
+  memset(o->is4, 0, (size_t)G);
+  for (int32_t r = 0; r < n4; ++r) o->is4[order[(size_t)r]] = 1;
+  // ---- Sec. 4.3: outliers only inside 2-bit groups, largest magnitudes of each row
+  std::vector<int32_t> cols2;
+  for (int64_t k = 0; k < K; ++k)
+    if (!o->is4[k / g1]) cols2.push_back((int32_t)k);
+  const int64_t cnt = (int64_t)floor(p_o * (double)cols2.size() + 0.5);
+  if (N * cnt > outlier_capacity) return MPQ_ERR_SIZE;
+  if (N * cnt > 0 && (!o->col || !o->val)) return MPQ_ERR_NULL;
+  std::vector<uint8_t> is_out((size_t)(N * K), 0);
+  std::vector<int32_t> pick(cols2);
+  o->row_ptr[0] = 0;
+  for (int64_t n = 0; n < N; ++n) {
+    const float* w = W + n * K;
+    if (cnt > 0) {
+      pick = cols2;
+      std::stable_sort(pick.begin(), pick.end(), [&](int32_t a, int32_t b) { return fabs((double)w[a]) > fabs((double)w[b]); });
+      for (int64_t r = 0; r < cnt; ++r) is_out[(size_t)(n * K + pick[(size_t)r])] = 1;
+    }
+    o->row_ptr[n + 1] = (int32_t)((n + 1) * cnt);
+  }
+  // ---- eq. 2: the scale of every (row, group) from the range of its non-outlier weights
+  std::vector<double> sc((size_t)(N * G)), lo((size_t)(N * G));
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t g = 0; g < G; ++g) {
+      double mn = INFINITY, mx = -INFINITY;
+      for (int64_t k = g * g1; k < (g + 1) * g1; ++k)
+        if (!is_out[(size_t)(n * K + k)]) {
+          const double v = (double)W[n * K + k];
+          mn = v < mn ? v : mn;
+          mx = v > mx ? v : mx;
+        }
+      if (mn > mx) mn = mx = 0.0;  // every weight of the group is an outlier
+      const double levels = o->is4[g] ? 15.0 : 3.0;
+      double s = (mx - mn) / levels;
+      if (s == 0.0) s = mn != 0.0 ? fabs(mn) : 1.0;
+      sc[(size_t)(n * G + g)] = s;
+      lo[(size_t)(n * G + g)] = mn;
+    }
+  // ---- second-order quantization of the scales to 8 bits, then the decoder's view of every scale
+  const int64_t S2 = (G + g2 - 1) / g2, NB = (N + g2 - 1) / g2;
+  const int64_t nblocks = d->g2_axis == 0 ? N * S2 : NB * G;
+  std::vector<uint16_t> s1((size_t)(N * G));
+  for (int64_t b = 0; b < nblocks; ++b) {
+    int64_t n0, n1, ga, gb;
+    if (d->g2_axis == 0) { n0 = b / S2; n1 = n0 + 1; ga = (b % S2) * g2; gb = ga + g2 < G ? ga + g2 : G; }
+    else { n0 = (b / G) * g2; n1 = n0 + g2 < N ? n0 + g2 : N; ga = b % G; gb = ga + 1; }
+    double smin = INFINITY, smax = -INFINITY;
+    for (int64_t n = n0; n < n1; ++n)
+      for (int64_t g = ga; g < gb; ++g) {
+        const double s = sc[(size_t)(n * G + g)];
+        smin = s < smin ? s : smin;
+        smax = s > smax ? s : smax;
+      }
+    const double step = (smax - smin) / 255.0, floor_step = smax / 2047.0;  // |z2| <= 2047: exact in fp16
+    const uint16_t s2h = float_to_half((float)(step > floor_step ? step : floor_step));
+    const double s2f = (double)half_to_float(s2h), safe = s2f == 0.0 ? 1.0 : s2f;
+    const uint16_t z2h = float_to_half((float)nearbyint(-smin / safe));
+    const double z2f = (double)half_to_float(z2h);
+    o->s2[b] = s2h;
+    o->z2[b] = z2h;
+    for (int64_t n = n0; n < n1; ++n)
+      for (int64_t g = ga; g < gb; ++g) {
+        double q = nearbyint(sc[(size_t)(n * G + g)] / safe) + z2f;
+        q = q < 0.0 ? 0.0 : q > 255.0 ? 255.0 : q;
+        o->s_int[n * G + g] = (uint8_t)q;
+        s1[(size_t)(n * G + g)] = host_scale_dequant((uint8_t)q, z2h, s2h);
+      }
+  }
+  // ---- eqs. 3-4 against the reconstructed scale; outliers carry what the dense code does not
+  int64_t e = 0;
+  for (int64_t n = 0; n < N; ++n)
+    for (int64_t g = 0; g < G; ++g) {
+      const double levels = o->is4[g] ? 15.0 : 3.0;
+      const uint16_t s1h = s1[(size_t)(n * G + g)];
+      const double s1f = (double)half_to_float(s1h);
+      const bool ok = s1f != 0.0;
+      double z = 0.0;
+      if (ok) {
+        z = nearbyint(-lo[(size_t)(n * G + g)] / s1f);
+        z = z < 0.0 ? 0.0 : z > levels ? levels : z;
+      }
+      o->z1[n * G + g] = (uint8_t)z;
+      for (int64_t k = g * g1; k < (g + 1) * g1; ++k) {
+        double c = 0.0;
+        if (ok) {
+          c = nearbyint((double)W[n * K + k] / s1f) + z;
+          c = c < 0.0 ? 0.0 : c > levels ? levels : c;
+        }
+        o->codes[n * K + k] = (uint8_t)c;
+        if (is_out[(size_t)(n * K + k)]) {
+          const double wd = (double)half_to_float(host_weight_dequant((uint8_t)c, (uint8_t)z, s1h));
+          o->col[e] = (uint16_t)k;
+          o->val[e] = float_to_half((float)((double)W[n * K + k] - wd));
+          ++e;
+        }
+      }
+    }
+  *nnz_out = e;
+  return MPQ_OK;
 }
 
 mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, const int32_t* row_ptr, size_t* bytes) {

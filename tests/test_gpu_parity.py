@@ -259,3 +259,28 @@ def test_several_products_in_one_launch(torch):
     mpq.gemv_multi([pk16.header], [b16], [x16], [y16.view])  # and g1 = 16 on its own
     e_floor, e_max = rel_err(y16.check_and_get(), om16.gemm(synth.make_x(1, 1, pk16.K), threads=8)[0])
     assert e_floor <= TOL, (e_floor, e_max)
+
+
+def test_quantized_float_weights_end_to_end(torch):
+    # float weights -> reference quantizer (library, host) -> pack -> GEMV on the GPU: parity with the
+    # oracle on the quantized matrix, and the product stays near the float product (Sec. 2.2, 3.3, 4.3)
+    rng = np.random.default_rng(77)
+    N, K, g1, g2 = 512, 2048, 64, 16
+    W = (rng.standard_t(df=5, size=(N, K)) * 0.02).astype(np.float32)
+    W[:, 5 * g1:6 * g1] *= 6.0
+    q = mpq.quantize(W, g1, g2, n4=int(round(0.1 * K / g1)), p_o=0.005)
+    assert q["is4"][5] == 1
+    pk = mpq.pack(N, K, g1, g2, **q)
+    om = oracle.Matrix(N, K, g1, g2, q["is4"], q["codes"], q["s_int"], q["z1"], q["s2"], q["z2"],
+                       q["row_ptr"], q["col"], q["val"])
+    X = synth.make_x(5, 1, K)
+    y = Guarded(torch, N)
+    mpq.gemv(pk.header, to_dev(torch, pk.blob), to_dev(torch, X[0].view(np.int16)), y.view)
+    got = y.check_and_get()
+    ref = om.gemm(X, threads=8)[0]
+    e_floor, e_max = rel_err(got, ref)
+    assert e_floor <= TOL, (e_floor, e_max)
+    y_float = W.astype(np.float64) @ X[0].view(np.float16).astype(np.float64)
+    rel = np.linalg.norm(got.view(np.float16).astype(np.float64) - y_float) / np.linalg.norm(y_float)
+    print("relative error of the quantized product against the float product:", rel, flush=True)
+    assert rel < 0.5    # 2-bit groups of 64: coarse, but the product follows the float one
