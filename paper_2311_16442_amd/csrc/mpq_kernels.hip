@@ -202,7 +202,7 @@ __device__ __forceinline__ void load_pieces(const unsigned char* ue, const unsig
 
 // ------------------------------------------------------------------------------------ product
 //
-// Y[m][n] = sum_k X[m][k] W[n][k] + outliers, 1 <= M <= 16*NT.  Persistent workgroups of four
+// Y[m][n] = sum_k X[m][k] W[n][k] + outliers, 2 <= M <= 16*NT.  Persistent workgroups of WV
 // waves: workgroup g handles the 16-row tiles g, g + grid, g + 2*grid, ...
 //
 // Data movement (the "asynchronous dequantization" of Sec. 5 on this hardware).  Every global
@@ -228,23 +228,17 @@ __device__ __forceinline__ void load_pieces(const unsigned char* ue, const unsig
 // beyond M compute garbage that is never stored.
 //
 // Two barriers per tile: one before a tile's side record is read (every wave has waited for its
-// own share of that record), one before the four waves' accumulators are summed.
-//
-// PERSIST = false is the same kernel launched with one workgroup per tile (grid = T): one side
-// buffer, and the accumulators are parked in the wave's own idle ring slots, which saves 8 KiB of
-// LDS per workgroup and lets six workgroups share a compute unit.  It wins when the activations
-// are small (M = 1) because the vector ALU needs many waves per SIMD to stay busy; the persistent
-// form wins when staging the activations once per tile would dominate (M > 1).
+// own share of that record), one before the waves' accumulators are summed.
 //
 // WV = waves per workgroup (4, 8 or 16), all working on the same tile.  More waves per tile fill
 // the 32 wave slots of a compute unit with fewer workgroups (less LDS for staged operands per
 // wave) and keep every SIMD busy when the matrix has few row tiles (4096 rows = 256 tiles = one
 // tile per compute unit).
-template <int NT, int PD, int LDSB, bool PERSIST, int WV = 4, int PU = 1>
+template <int NT, int PD, int LDSB, int WV = 4, int PU = 1>
 __global__ void __launch_bounds__(WV * 64)
 mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
 #pragma clang fp contract(off)
-  static_assert(PD >= 1 && PD <= 8 && (PERSIST || PD >= NT), "ring depth / batch tiles");
+  static_assert(PD >= 1 && PD <= 8, "ring depth");
   __shared__ __align__(16) unsigned char lds[LDSB];
   constexpr uint32_t W = WV;
   const uint32_t tid = threadIdx.x;
@@ -256,8 +250,8 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   const uint32_t units_bytes = 32u * PU * C;
   const uint32_t rowbytes = 2u * b.K + 16u;  // + 16: rows of a batch start in different LDS banks
   unsigned char* const ring = lds;
-  unsigned char* const side0 = lds + W * PD * 1024 + (PERSIST ? W * NT * 1024 : 0);
-  unsigned char* const units = side0 + (PERSIST ? 2 : 1) * b.side_bytes;
+  unsigned char* const side0 = lds + W * PD * 1024 + W * NT * 1024;
+  unsigned char* const units = side0 + 2 * b.side_bytes;
   unsigned char* const xs = units + units_bytes;
   const DecodeConsts kc = make_consts();
 
@@ -368,9 +362,8 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 #undef MPQ_MM_STEP
     // ---- (3) accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3] of this wave's share:
     //      red[wave][NT][16 m][16 rows]
-    // (persistent: dedicated slots; else the wave's own ring slots, idle by now)
-    constexpr uint32_t red_stride = PERSIST ? NT * 1024 : PD * 1024;  // bytes between waves
-    unsigned char* const red = PERSIST ? lds + W * PD * 1024 : ring;
+    constexpr uint32_t red_stride = NT * 1024;  // bytes between waves
+    unsigned char* const red = lds + W * PD * 1024;
     float* myred = (float*)(red + wv * red_stride);
     *(float4_t*)(myred + i * 16 + 4 * j) = acc0;
     if (NT > 1) *(float4_t*)(myred + 256 + i * 16 + 4 * j) = acc1;
@@ -1043,20 +1036,17 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   return MPQ_OK;
 }
 
-// LDS bytes the product kernel needs for a batch of M rows at ring depth PD: ring, (persistent:
-// reduction slots and a second side-record buffer), side record, unit table, activation rows.
-size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, bool persist, int waves = 4) {
+// LDS bytes the batch kernel needs for M rows at ring depth PD: ring, reduction slots, two
+// side-record buffers, unit table, activation rows.
+size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, int waves = 4) {
   const size_t NT = M > 16 ? 2 : 1;
-  return (size_t)waves * PD * 1024 + (persist ? waves * NT * 1024 + 2 * h.side_bytes : h.side_bytes) +
-         32ull * mpq_pu2(h.g1) * (h.B2 + h.B4) +
+  return (size_t)waves * PD * 1024 + waves * NT * 1024 + 2 * h.side_bytes + 32ull * mpq_pu2(h.g1) * (h.B2 + h.B4) +
          (size_t)M * (2ull * h.K + 16);
 }
 
 constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
 
-int g_ring_depth = 0;   // 0 = automatic
 int g_max_blocks = 0;   // 0 = automatic
-int g_persist = -1;     // -1 = automatic (persistent workgroups for M > 1)
 int g_gemv_waves = 0;   // 0 = automatic (8 or 16 waves per workgroup of the GEMV)
 int g_ranges = -1;      // -1 = automatic (large-batch kernel when the activations do not fit the LDS)
 int g_range_tiles = 0;  // 0 = automatic (tiles per group of the large-batch kernel, 1..4)
@@ -1155,22 +1145,20 @@ mpq_status launch_batch(const MpqHeader& h, const DevBlob& d, const uint16_t* X,
   long grid = (long)cu_count() * (long)per_cu;
   if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
   if (grid > h.T) grid = h.T;
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, true, WV, PU>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, WV, PU>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
-template <int NT, int PD, int LDSB, bool PERSIST, int PU = 1>
+// Persistent batch kernel with 4 waves per workgroup (the most workgroups per compute unit).
+template <int NT, int PD, int LDSB, int PU = 1>
 mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  long grid = h.T;
-  if (PERSIST) {  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
-    size_t per_cu = kLdsPerCu / LDSB;
-    if (per_cu > 8) per_cu = 8;
-    if (per_cu < 1) per_cu = 1;
-    grid = (long)cu_count() * (long)per_cu;
-    if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
-    if (grid > h.T) grid = h.T;
-  }
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, PERSIST, 4, PU>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
+  size_t per_cu = kLdsPerCu / LDSB;  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
+  if (per_cu > 8) per_cu = 8;
+  if (per_cu < 1) per_cu = 1;
+  long grid = (long)cu_count() * (long)per_cu;
+  if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
+  if (grid > h.T) grid = h.T;
+  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, 4, PU>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
@@ -1182,44 +1170,31 @@ mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
     // first-order groups shorter than a unit (g1 = 16, 32): persistent workgroups in a few classes
     const bool four = mpq_pu2(h.g1) == 4;
 #define MPQ_PIECES(CALL2, CALL4) return four ? CALL4 : CALL2
-    if (mm_lds_bytes(h, M, 2, true, 8) <= 80 * 1024)
+    if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024)
       MPQ_PIECES((launch_batch<NT, 2, 80 * 1024, 8, 2>(h, d, X, Y, M, s)), (launch_batch<NT, 2, 80 * 1024, 8, 4>(h, d, X, Y, M, s)));
-    if (mm_lds_bytes(h, M, 3, true, 8) <= 160 * 1024)
+    if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024)
       MPQ_PIECES((launch_batch<NT, 3, 160 * 1024, 8, 2>(h, d, X, Y, M, s)), (launch_batch<NT, 3, 160 * 1024, 8, 4>(h, d, X, Y, M, s)));
-    if (mm_lds_bytes(h, M, 3, true) <= 160 * 1024)
-      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, true, 2>(h, d, X, Y, M, s)), (launch_mm<NT, 3, 160 * 1024, true, 4>(h, d, X, Y, M, s)));
+    if (mm_lds_bytes(h, M, 3) <= 160 * 1024)
+      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, 2>(h, d, X, Y, M, s)), (launch_mm<NT, 3, 160 * 1024, 4>(h, d, X, Y, M, s)));
 #undef MPQ_PIECES
     return MPQ_ERR_UNSUPPORTED;
   }
-  const int pd = g_ring_depth;
-  const bool persist = g_persist < 0 ? M > 1 : g_persist != 0;
-  if (!persist) {
-    if (pd == 2 && mm_lds_bytes(h, M, 2, false) <= 26 * 1024) return launch_mm<NT, 2, 26 * 1024, false>(h, d, X, Y, M, s);
-    if (pd == 4 && mm_lds_bytes(h, M, 4, false) <= 32 * 1024) return launch_mm<NT, 4, 32 * 1024, false>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 3, false) <= 26 * 1024) return launch_mm<NT, 3, 26 * 1024, false>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 3, false) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024, false>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 4, false) <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024, false>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 4, false) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024, false>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 6, false) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024, false>(h, d, X, Y, M, s);
-  }
-  if (persist && M > 1 && g_batch_waves != 4) {
+  if (g_batch_waves != 4) {
     // many waves share one copy of the activations: 16 (or 8) waves per workgroup
     if (g_batch_waves != 8) {
-      if (mm_lds_bytes(h, M, 2, true, 16) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 16>(h, d, X, Y, M, s);
-      if (mm_lds_bytes(h, M, 2, true, 16) <= 160 * 1024) return launch_batch<NT, 2, 160 * 1024, 16>(h, d, X, Y, M, s);
+      if (mm_lds_bytes(h, M, 2, 16) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 16>(h, d, X, Y, M, s);
+      if (mm_lds_bytes(h, M, 2, 16) <= 160 * 1024) return launch_batch<NT, 2, 160 * 1024, 16>(h, d, X, Y, M, s);
     }
-    if (mm_lds_bytes(h, M, 2, true, 8) <= 53 * 1024) return launch_batch<NT, 2, 53 * 1024, 8>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 2, true, 8) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 8>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 3, true, 8) <= 160 * 1024) return launch_batch<NT, 3, 160 * 1024, 8>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 2, 8) <= 53 * 1024) return launch_batch<NT, 2, 53 * 1024, 8>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 8>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024) return launch_batch<NT, 3, 160 * 1024, 8>(h, d, X, Y, M, s);
   }
-  if (pd == 2 && mm_lds_bytes(h, M, 2, true) <= 40 * 1024) return launch_mm<NT, 2, 40 * 1024, true>(h, d, X, Y, M, s);
-  if (pd == 4 && mm_lds_bytes(h, M, 4, true) <= 40 * 1024) return launch_mm<NT, 4, 40 * 1024, true>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 3, true) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024, true>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 3, true) <= 40 * 1024) return launch_mm<NT, 3, 40 * 1024, true>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 4, true) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024, true>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 6, true) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024, true>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 8, true) <= 160 * 1024) return launch_mm<NT, 8, 160 * 1024, true>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 3, true) <= 160 * 1024) return launch_mm<NT, 3, 160 * 1024, true>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3) <= 40 * 1024) return launch_mm<NT, 3, 40 * 1024>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 4) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 6) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 8) <= 160 * 1024) return launch_mm<NT, 8, 160 * 1024>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3) <= 160 * 1024) return launch_mm<NT, 3, 160 * 1024>(h, d, X, Y, M, s);
   return MPQ_ERR_UNSUPPORTED;
 }
 
@@ -1298,9 +1273,9 @@ mpq_status launch_ranges(const MpqHeader& h, const DevBlob& d, const uint16_t* X
 
 mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   if (M == 1) return gemv_all(h, d, X, Y, s);
-  if (mm_lds_bytes(h, 1, 3, true) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
+  if (mm_lds_bytes(h, 1, 3) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
   int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
-  while (Mc > 1 && mm_lds_bytes(h, Mc, 3, true) > kLdsPerCu) --Mc;
+  while (Mc > 1 && mm_lds_bytes(h, Mc, 3) > kLdsPerCu) --Mc;
   if (Mc > 16 && Mc < M) Mc = 16;
   {
     // The large-batch kernel reads and decodes the weights once whatever M is, but pays a chain of
@@ -1310,7 +1285,7 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
     // chunk) row tiles per compute unit.
     const int chunks = (M + Mc - 1) / Mc, cus = cu_count();
     const int rows = (M + chunks - 1) / chunks;  // batch rows per chunk
-    const bool waves8 = mm_lds_bytes(h, rows, 2, true, 8) <= kLdsPerCu;
+    const bool waves8 = mm_lds_bytes(h, rows, 2, 8) <= kLdsPerCu;
     const bool better = chunks >= 3 || (!waves8 && h.T >= (chunks == 2 ? 2 : 3) * cus);
     if (g_ranges < 0 ? better : g_ranges != 0) {
       const mpq_status st = launch_ranges(h, d, X, Y, M, s);
@@ -1335,18 +1310,16 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
 
 extern "C" {
 
-// Tuning hook for sweeps; not part of the supported interface and not thread safe.
-// key 0: ring depth (code blocks in flight per wave) where it fits the small LDS classes, 0 = automatic;
-// key 2: cap on the number of persistent workgroups, 0 = automatic; key 3: 0 one workgroup per tile,
-// 1 persistent workgroups, -1 automatic (batch kernel); key 4: waves per workgroup of the GEMV (8, 16), 0 automatic;
-// key 5: waves per workgroup of the persistent batch kernel (4, 8, 16), 0 automatic; key 6: tiles per
-// workgroup of the GEMV (1..8), 0 automatic; key 7: 1 large-batch (range) kernel for every M > 1, 0 never,
-// -1 automatic; key 8: tiles per group of the large-batch kernel (1..4), 0 automatic; key 9: workgroups
-// of the large-batch kernel per compute unit (1 = one of 16 waves, 2 = two of 8 waves), 0 automatic.
+// Tuning hook for sweeps and for the tests that force every code path; not part of the supported
+// interface and not thread safe.  0 = automatic for every key.
+//   2: cap on the number of persistent workgroups
+//   4: waves per workgroup of the GEMV (8, 16)          6: tiles per workgroup of the GEMV (1..8)
+//   5: waves per workgroup of the batch kernel (4, 8, 16)
+//   7: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic
+//   8: its tiles per group (1..4)   9: its workgroups per compute unit (1 = 16 waves, 2 = 2 x 8 waves)
+//  10: its activation buffers (1, 2)
 void mpq_debug_set(int key, int value) {
-  if (key == 0) g_ring_depth = value;
   if (key == 2) g_max_blocks = value;
-  if (key == 3) g_persist = value;
   if (key == 4) g_gemv_waves = value;
   if (key == 5) g_batch_waves = value;
   if (key == 6) g_gemv_tiles = value;
