@@ -816,6 +816,9 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
                                                   __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
   }
 #define MPQ_GEMV_BLOCK_HEAD(NP)                                                                        \
+  /* waves in their decode steps go before waves that fetch their next block: measured 5 % faster   \
+     on the long Llama2-70B shapes, neutral on the short ones */                                     \
+  __builtin_amdgcn_s_setprio(0);                                                                      \
   /* requests younger than the block needed now: the other blocks in flight */                        \
   if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
   uint4 q;                                                                                            \
@@ -832,6 +835,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   half_t zb[NP];                                                                                      \
   uint32_t xoff[NP];                                                                                  \
   load_pieces<NP>(unitj + c * (32u * PU), m1i, m2i, s1p, zb, xoff);                                   \
+  __builtin_amdgcn_s_setprio(2);                                                                      \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     for (; c < (uint32_t)b.B2; c += W) {
       MPQ_GEMV_BLOCK_HEAD(PU)
@@ -846,6 +850,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     }
 #undef MPQ_GEMV_BLOCK_HEAD
 #undef MPQ_GEMV_STEP
+    __builtin_amdgcn_s_setprio(0);
     c -= C;  // the sequence continues in the next tile
     // accumulator lane l holds Y[m = l % 16][rows 4*(l/16) .. +3]; only batch column 0 is real
     if (i == 0) *(float4_t*)(red + (t * (W + 1) + wv) * 16 + 4 * j) = acc0;
