@@ -79,6 +79,18 @@ __device__ __forceinline__ void wait_vm(int n) {
   }
 }
 
+// The same for 0 <= n <= MAXN known at compile time to be small: two compares instead of the switch.
+template <int MAXN>
+__device__ __forceinline__ void wait_vm_upto(int n) {
+  if (MAXN <= 2) {
+    if (n >= 2) MPQ_VMCNT(2);
+    else if (n == 1) MPQ_VMCNT(1);
+    else MPQ_VMCNT(0);
+  } else {
+    wait_vm(n);
+  }
+}
+
 // The product kernel issues its global loads with inline asm and waits for them with explicit
 // s_waitcnt vmcnt(n): the compiler's own wait insertion cannot count requests issued in loops and
 // would otherwise wait for ALL outstanding loads (vmcnt(0)) whenever LDS written by a direct load
@@ -185,6 +197,22 @@ __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint
 
 // Scale, zero point and activation offset of the NP pieces of a unit (one piece per first-order
 // group that the unit touches; one piece for g1 >= 64).  ue points at the unit's table entries.
+// The same from unit table entries that were fetched earlier.
+template <int NP>
+__device__ __forceinline__ void finish_pieces(const uint2 (&ent)[NP], const unsigned char* m1i, const unsigned char* m2i,
+                                              half2_t (&s1p)[NP], half_t (&zb)[NP], uint32_t (&xoff)[NP]) {
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    const uint2 e = ent[q];
+    const uint32_t m1 = *(const uint16_t*)(m1i + (e.y & 0xFFFFu));
+    const uint32_t m2 = *(const uint32_t*)(m2i + (e.y >> 16));
+    const half_t s1 = scale_dequant(m1 & 0xFFu, m2);  // exactly 0 for a padding piece (zero meta entries)
+    s1p[q] = half2_t{s1, s1};
+    zb[q] = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
+    xoff[q] = e.x;
+  }
+}
+
 template <int NP>
 __device__ __forceinline__ void load_pieces(const unsigned char* ue, const unsigned char* m1i, const unsigned char* m2i,
                                             half2_t (&s1p)[NP], half_t (&zb)[NP], uint32_t (&xoff)[NP]) {
@@ -278,7 +306,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
       if (rc >= C) { rc = wv; rtile += grid; rbase += tilestep; }
     }
   }
-  wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
+  wait_vm_upto<PD>((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
   const unsigned char* xrow0 = xs + (i < (uint32_t)M ? i : 0u) * rowbytes;
@@ -329,7 +357,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 #define MPQ_MM_BLOCK_HEAD(NP)                                                                          \
   /* Requests younger than the block needed now: the other blocks in flight (stricter than            \
      necessary when a side-record request sits between them, never laxer). */                         \
-  if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
+  if (inflight == PD) MPQ_VMCNT(PD - 1); else if (PD == 2) MPQ_VMCNT(0); else wait_vm((int)inflight - 1); \
   uint4 q;                                                                                            \
   asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
   --inflight;                                                                                         \
@@ -613,7 +641,7 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
      the staging of the next range, this wave's staging requests */                                  \
   if (blocks_before > 0) { wait_vm((int)(inflight - 1 + stg)); --blocks_before; }                     \
   else if (inflight == PD) MPQ_VMCNT(PD - 1);                                                         \
-  else wait_vm((int)inflight - 1);                                                                    \
+  else MPQ_VMCNT(0); /* PD = 2: nothing else of this wave can be in flight */                         \
   uint4 q;                                                                                            \
   asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
   --inflight;                                                                                         \
@@ -795,7 +823,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
       while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
     }
   }
-  wait_vm((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
+  wait_vm_upto<PD>((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
   lds_barrier();
 
   const unsigned char* unitj = units + j * (8 * PU);
@@ -821,8 +849,13 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   }
 #define MPQ_GEMV_BLOCK_HEAD(NP)                                                                        \
   __builtin_amdgcn_s_setprio(0);                                                                      \
-  /* requests younger than the block needed now: the other blocks in flight */                        \
-  if (inflight == PD) MPQ_VMCNT(PD - 1); else wait_vm((int)inflight - 1);                             \
+  /* the block's unit table entries are requested first: the wait inside the ring read below covers  \
+     them, so the scale words can be requested right after it */                                     \
+  uint2 ent[NP];                                                                                      \
+  _Pragma("unroll") for (int qq = 0; qq < NP; ++qq) ent[qq] = *(const uint2*)(unitj + c * (32u * PU) + 8 * qq); \
+  /* requests younger than the block needed now: the other blocks in flight (the run-time switch of  \
+     wait_vm is kept out of the two-slot ring: its compare chain sat on the tail of every workgroup) */ \
+  if (inflight == PD) MPQ_VMCNT(PD - 1); else if (PD == 2) MPQ_VMCNT(0); else wait_vm((int)inflight - 1); \
   uint4 q;                                                                                            \
   asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
   --inflight;                                                                                         \
@@ -836,7 +869,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   half2_t s1p[NP];                                                                                    \
   half_t zb[NP];                                                                                      \
   uint32_t xoff[NP];                                                                                  \
-  load_pieces<NP>(unitj + c * (32u * PU), m1i, m2i, s1p, zb, xoff);                                   \
+  finish_pieces<NP>(ent, m1i, m2i, s1p, zb, xoff);                                                    \
   if (decode_first) __builtin_amdgcn_s_setprio(2);                                                    \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     for (; c < (uint32_t)b.B2; c += W) {
