@@ -814,17 +814,23 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   uint32_t rc = wv, rt = 0;                            // next request: block rc of tile rt (rt = n: none left)
   while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
   uint32_t inflight = 0;
-#pragma unroll
-  for (uint32_t r = 0; r < PD; ++r) {
-    if (rt < n) {
-      dma16(rbase + rc * 1024u, lane16, ring0 + r * 1024u);
-      ++inflight;
-      rc += W;
-      while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
-    }
+#define MPQ_GEMV_FILL(R)                                                     \
+  if (rt < n) {                                                              \
+    dma16(rbase + rc * 1024u, lane16, ring0 + (R) * 1024u);                  \
+    ++inflight;                                                              \
+    rc += W;                                                                 \
+    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }     \
   }
-  wait_vm_upto<PD>((int)inflight);  // the staged operands have landed; the code blocks may still be in flight
+  MPQ_GEMV_FILL(0)
+  wait_vm_upto<PD>((int)inflight);  // the staged operands have landed; the code block may still be in flight
   lds_barrier();
+  // The other ring slots are requested only now.  With every request of every workgroup issued in
+  // its first instructions, the memory system serves workgroup after workgroup and the last ones
+  // sit idle for most of the burst; this way every workgroup gets its first block early
+  // (interleaved A/B runs: 2 % on the Llama2-7B layer, 6 % on the 4096x11008 matrix).
+#pragma unroll
+  for (uint32_t r = 1; r < PD; ++r) MPQ_GEMV_FILL(r)
+#undef MPQ_GEMV_FILL
 
   const unsigned char* unitj = units + j * (8 * PU);
   const uint32_t ringl = ring0 + lane16;
