@@ -778,7 +778,14 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
 //   paid once per n tiles.
 //
 //   Outliers: groups of four waves (256 threads, 16 lanes per row) take the tiles in turn; the 16
-//   lanes of a row each take every 16th word of the row and are summed with DPP row shifts.
+//   lanes of a row each take every 16th word of the row and are summed with DPP row shifts.  This
+//   is done right after the first barrier, while the first code blocks are still on their way, so
+//   that the end of a workgroup is only: park, barrier, sum.
+//
+//   Order of the requests (each choice from interleaved A/B timing on one box): staged operands and
+//   ONE code block per wave first; the second ring slot only after the first barrier - with every
+//   request of every workgroup issued at once the memory system serves workgroup after workgroup
+//   and the last ones start late.
 template <int PD, int LDSB, int WV, int PU>
 __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
                                                const int n_arg, const uint32_t wg) {
@@ -832,6 +839,29 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   for (uint32_t r = 1; r < PD; ++r) MPQ_GEMV_FILL(r)
 #undef MPQ_GEMV_FILL
 
+  // ---- (2) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
+  //      are already in LDS.  Four waves per tile, 16 lanes per row.  Done first, while the first
+  //      code blocks are still on their way.
+  {
+    const uint32_t otid = tid & 255u, orow = otid >> 4, oq = otid & 15u;
+    for (uint32_t t = wv >> 2; t < n && wv < (W / 4) * 4; t += W / 4) {
+      const uint32_t* ostart = (const uint32_t*)(side0 + t * b.side_bytes + b.off_ot);
+      const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
+      const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
+      float oa = 0.f;
+      for (uint32_t e = rp0 + oq; e < rp1; e += 16) {
+        const uint32_t word = owords[e];
+        const float v = (float)bits_to_half((uint16_t)(word >> 16));
+        oa += v * (float)*(const half_t*)(xs + (word & 0xFFFFu) * 2u);
+      }
+      // sum over the 16 lanes of the row with DPP row shifts; lane 15 of the row ends with the total
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x118, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x114, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x112, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x111, 0xf, 0xf, true));
+      if (oq == 15) red[(t * (W + 1) + W) * 16 + orow] = oa;
+    }
+  }
   const unsigned char* unitj = units + j * (8 * PU);
   const uint32_t ringl = ring0 + lane16;
   // With three or more blocks per wave, waves in their decode steps go before waves that fetch
@@ -897,28 +927,6 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     if (i == 0) *(float4_t*)(red + (t * (W + 1) + wv) * 16 + 4 * j) = acc0;
   }
 
-  // ---- (2) outliers (Sec. 4.3, fused: no second kernel, no second trip to memory); all operands
-  //      are already in LDS.  Four waves per tile, 16 lanes per row.
-  {
-    const uint32_t otid = tid & 255u, orow = otid >> 4, oq = otid & 15u;
-    for (uint32_t t = wv >> 2; t < n && wv < (W / 4) * 4; t += W / 4) {
-      const uint32_t* ostart = (const uint32_t*)(side0 + t * b.side_bytes + b.off_ot);
-      const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
-      const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
-      float oa = 0.f;
-      for (uint32_t e = rp0 + oq; e < rp1; e += 16) {
-        const uint32_t word = owords[e];
-        const float v = (float)bits_to_half((uint16_t)(word >> 16));
-        oa += v * (float)*(const half_t*)(xs + (word & 0xFFFFu) * 2u);
-      }
-      // sum over the 16 lanes of the row with DPP row shifts; lane 15 of the row ends with the total
-      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x118, 0xf, 0xf, true));
-      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x114, 0xf, 0xf, true));
-      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x112, 0xf, 0xf, true));
-      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x111, 0xf, 0xf, true));
-      if (oq == 15) red[(t * (W + 1) + W) * 16 + orow] = oa;
-    }
-  }
   lds_barrier();
   // ---- (3) row r of tile t: the outlier term and the W partial sums, in a fixed order
   if (tid < 16 * n) {
