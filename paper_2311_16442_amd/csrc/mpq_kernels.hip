@@ -5,6 +5,7 @@
 //                        with the outlier product of Sec. 4.3 fused in as a per-row correction.
 //   mpq_mm_kernel        the same product for a batch of 2..32 activation rows that fit the LDS.
 //   mpq_mmr_kernel       the same for batches that do not: activations staged range by range.
+//   mpq_mms_kernel       the same with one range resident per workgroup (+ mpq_mms_finish_kernel).
 //   mpq_dequant_kernel   eq. 5 applied twice (scale, then weight), written out as row-major fp16.
 //   mpq_outlier_add_kernel  adds the CSR values to a dequantized matrix (dense + sparse, Sec. 2.3).
 //
@@ -22,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+
+#include <mutex>
 
 #include "../../include/mpq.h"
 #include "mpq_format.h"
@@ -761,6 +764,330 @@ mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __rest
 #undef MPQ_R_NORMALIZE
 }
 
+// ------------------------------------------------------------------------------------ slice kernel
+//
+// Y = X W^T for batches whose activations do not fit the LDS, without staging them again and again:
+//
+//   The code blocks of a tile are cut into H ranges in stream order (range h = an H-th of the 2-bit
+//   blocks and an H-th of the 4-bit blocks, sizes differing by at most one) and the tiles into NB
+//   bands; workgroup (h, band) gathers the activations of range h into LDS ONCE - same layout as
+//   above, slot ((unit*8 + step) * XR + m) holds the 8 fp16 values X[m][k0(unit) + 8*step ..], XR =
+//   8, 16 or 32 staged batch rows - and then walks the band's tiles, R at a time, decoding only the
+//   blocks of its range.  Its waves share those blocks round-robin, one accumulator per tile in
+//   registers; the ring of code blocks stays full from the first tile of the band to the last.
+//
+//   The first-order (s_int, z1) and second-order (s2, z2) words of a block travel with it: three
+//   direct loads per block (1 KiB of codes, then one dword per lane that holds the lane's meta1
+//   entry and one that holds its meta2 entry, gathered through the unit table) land in one ring
+//   slot of 1.5 KiB, so no per-tile side record is staged and no barrier separates tiles.
+//
+//   After a group of tiles the waves park their accumulators, meet, and every (row, batch column)
+//   is summed over the waves in a fixed order and written as fp32 to P[h][tile][column][row].  A
+//   second kernel adds the H partial sums in order, adds the outlier product of the row (Sec. 4.3)
+//   and rounds to fp16: results are bit-identical from run to run.
+struct SlicePlan {
+  int32_t H, NB, R;
+  uint32_t off_units, off_park, off_xbuf;  // LDS byte offsets (ring at 0)
+};
+
+__device__ __forceinline__ void dma4(const unsigned char* gbase, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds), "v"(voff), "s"(gbase)
+               : "memory");
+}
+
+template <int NT, int XR, int LDSB, int WV>
+__global__ void __launch_bounds__(WV * 64)
+mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restrict__ P, uint16_t* __restrict__ XT,
+               const int M, const SlicePlan pl) {
+#pragma clang fp contract(off)
+  static_assert(WV == 8 || WV == 16, "waves");
+  static_assert(XR == 8 || XR == 16 * NT, "staged rows");
+  constexpr uint32_t W = WV, PD = 2, SLOTB = 1536;
+  constexpr uint32_t TP = 2 / NT;  // tiles parked at a time (2 KiB per wave)
+  __shared__ __align__(16) unsigned char lds[LDSB];
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
+  const uint32_t C = b.C, T = b.T, B2 = b.B2, B4 = C - B2;
+  const uint32_t H = pl.H, NB = pl.NB, R = pl.R;
+  const uint32_t h = blockIdx.x % H, band = blockIdx.x / H;
+  const uint32_t a2 = h * B2 / H, n2 = (h + 1) * B2 / H - a2;   // this range's 2-bit blocks
+  const uint32_t a4 = h * B4 / H, n4 = (h + 1) * B4 / H - a4;   // and 4-bit blocks
+  const uint32_t len = n2 + n4;                                  // >= 1 (the host keeps H <= max(B2, B4))
+  const uint32_t t0 = (uint32_t)((uint64_t)band * T / NB), ntl = (uint32_t)((uint64_t)(band + 1) * T / NB) - t0;
+  const uint32_t ngroups = (ntl + R - 1) / R;                    // groups of about equal size, at most R tiles
+  unsigned char* const units = lds + pl.off_units;
+  float* const park0 = (float*)(lds + pl.off_park);
+  unsigned char* const xbuf = lds + pl.off_xbuf;
+  const DecodeConsts kc = make_consts();
+
+  // ---- once per workgroup: unit table
+  dma_linear<W>(b.units, lds_addr(units), 32u * C, wv, lane16);
+  MPQ_VMCNT(0);
+  lds_barrier();
+
+  // ---- the activations of the range: every lane fills one 16-byte slot per request
+  {
+    const uint32_t slots2 = n2 * 4u * 8u * XR, slots = slots2 + n4 * 4u * 4u * XR;
+    for (uint32_t s0 = wv * 64u; s0 < slots; s0 += W * 64u) {
+      const uint32_t s = s0 + lane;
+      uint32_t unit, step, m;
+      if (s < slots2) {
+        unit = a2 * 4u + s / (8u * XR);
+        step = (s / XR) & 7u;
+        m = s % XR;
+      } else {
+        const uint32_t s4 = s - slots2;
+        unit = 4u * B2 + a4 * 4u + s4 / (4u * XR);
+        step = (s4 / XR) & 3u;
+        m = s4 % XR;
+      }
+      if (s < slots && m < (uint32_t)M) {
+        const uint32_t k0x2 = *(const uint32_t*)(units + unit * 8u);
+        dma16((const unsigned char*)X, m * 2u * (uint32_t)b.K + k0x2 + step * 16u, lds_addr(xbuf) + s0 * 16u);
+      }
+    }
+  }
+
+  // ---- requests of code blocks: the enumeration (group, tile, block of the range) that the
+  //      consumption below follows, restricted to every W-th block
+  const uint32_t ring0 = lds_addr(lds) + wv * (PD * SLOTB);
+  const uint32_t m2lane = b.off_m2 + (i >> b.m2_shift) * 4u;
+  uint32_t r_g = 0, r_t = 0, r_c = wv;
+  uint32_t r_first = 0, r_Rn = ngroups > 0 ? ntl / ngroups : 0;  // group g = tiles [g*ntl/ngroups, (g+1)*ntl/ngroups)
+#define MPQ_S_NORMALIZE                                                                 \
+  while (r_g < ngroups && r_c >= len) {                                                 \
+    r_c -= len;                                                                         \
+    if (++r_t == r_Rn) {                                                                \
+      r_t = 0;                                                                          \
+      ++r_g;                                                                            \
+      r_first = r_g * ntl / ngroups;                                                    \
+      r_Rn = (r_g + 1) * ntl / ngroups - r_first;                                       \
+    }                                                                                   \
+  }
+#define MPQ_S_REQUEST(SLOT)                                                             \
+  {                                                                                     \
+    const uint32_t blk = r_c < n2 ? a2 + r_c : B2 + a4 + (r_c - n2);                    \
+    const unsigned char* tb = b.tiles + (size_t)(t0 + r_first + r_t) * b.tile_stride;   \
+    const uint32_t uy = *(const uint32_t*)(units + (blk * 4u + j) * 8u + 4u);           \
+    const uint32_t dst = ring0 + (SLOT) * SLOTB;                                        \
+    dma16(tb + b.codes_off + blk * 1024u, lane16, dst);                                 \
+    dma4(tb, ((uy & 0xFFFFu) + i * 2u) & ~3u, dst + 1024u);                             \
+    dma4(tb, m2lane + (uy >> 16), dst + 1280u);                                         \
+    ++inflight;                                                                         \
+    r_c += W;                                                                           \
+    MPQ_S_NORMALIZE                                                                     \
+  }
+  uint32_t inflight = 0;
+  MPQ_S_NORMALIZE
+#pragma unroll
+  for (uint32_t r = 0; r < PD; ++r)
+    if (r_g < ngroups) MPQ_S_REQUEST(r)
+  // the activations were requested first: they have landed when at most the block requests are left
+  wait_vm((int)(3u * inflight));
+  lds_barrier();
+
+  // ---- this workgroup's share of the transposed activations XT[k][XR] that the second kernel
+  //      gathers for the outliers: the bands of a range take the range's slots in turn
+  {
+    const uint32_t slots2 = n2 * 4u * 8u * XR, slots = slots2 + n4 * 4u * 4u * XR;
+    for (uint32_t s = band * (W * 64u) + tid; s < slots; s += NB * (W * 64u)) {
+      uint32_t unit, step;
+      if (s < slots2) {
+        unit = a2 * 4u + s / (8u * XR);
+        step = (s / XR) & 7u;
+      } else {
+        const uint32_t s4 = s - slots2;
+        unit = 4u * B2 + a4 * 4u + s4 / (4u * XR);
+        step = (s4 / XR) & 3u;
+      }
+      const uint32_t m = s % XR;
+      if (m < (uint32_t)M) {
+        const uint32_t k = (*(const uint32_t*)(units + unit * 8u) >> 1) + step * 8u;
+        const uint4 v = *(const uint4*)(xbuf + s * 16u);
+        uint16_t* at = XT + (size_t)k * XR + m;
+        at[0 * XR] = (uint16_t)v.x; at[1 * XR] = (uint16_t)(v.x >> 16);
+        at[2 * XR] = (uint16_t)v.y; at[3 * XR] = (uint16_t)(v.y >> 16);
+        at[4 * XR] = (uint16_t)v.z; at[5 * XR] = (uint16_t)(v.z >> 16);
+        at[6 * XR] = (uint16_t)v.w; at[7 * XR] = (uint16_t)(v.w >> 16);
+      }
+    }
+  }
+
+  const uint32_t slot_lane = ring0 + lane16, meta_lane = ring0 + 1024u + lane * 4u;
+  const unsigned char* xb2 = xbuf + j * (8u * XR * 16u) + (i % XR) * 16u;                        // + block * 512 * XR + step * 16 * XR
+  const unsigned char* xb4 = xbuf + n2 * (512u * XR) + j * (4u * XR * 16u) + (i % XR) * 16u;      // + block * 256 * XR + step * 16 * XR
+  uint32_t slot = 0, c = wv;
+
+#define MPQ_S_STEP(TWO, P, A0, A1)                                                                   \
+  {                                                                                                   \
+    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
+    const uint4 bv0 = *(const uint4*)(xb0 + (P) * (16 * XR));                                         \
+    A0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                      \
+                                                __builtin_bit_cast(half8_t, bv0), A0, 0, 0, 0);       \
+    if (NT > 1) {                                                                                     \
+      const uint4 bv1 = *(const uint4*)(xb0 + (P) * (16 * XR) + 256);                                 \
+      A1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
+                                                  __builtin_bit_cast(half8_t, bv1), A1, 0, 0, 0);     \
+    }                                                                                                 \
+  }
+#define MPQ_S_HEAD                                                                                     \
+  if (inflight == PD) MPQ_VMCNT(3 * (PD - 1));                                                        \
+  else MPQ_VMCNT(0); /* PD = 2: nothing else of this wave can be in flight */                         \
+  uint4 q;                                                                                            \
+  uint32_t w1, w2;                                                                                    \
+  asm volatile("ds_read_b128 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %4 offset:256\n\ts_waitcnt lgkmcnt(0)" \
+               : "=&v"(q), "=&v"(w1), "=&v"(w2)                                                       \
+               : "v"(slot_lane + slot * SLOTB), "v"(meta_lane + slot * SLOTB)                         \
+               : "memory");                                                                           \
+  --inflight;                                                                                         \
+  if (r_g < ngroups) MPQ_S_REQUEST(slot)                                                              \
+  slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
+  const uint32_t m1 = (i & 1u) ? w1 >> 16 : w1 & 0xFFFFu;                                             \
+  const half_t s1 = scale_dequant(m1 & 0xFFu, w2);                                                    \
+  const half2_t s1p = {s1, s1};                                                                       \
+  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                    \
+  const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+#define MPQ_S_TILE(TT, A0, A1)                                                                         \
+  if ((TT) < Rn) {                                                                                    \
+    for (; c < n2; c += W) {                                                                          \
+      MPQ_S_HEAD                                                                                      \
+      const unsigned char* xb0 = xb2 + c * (512u * XR);                                               \
+      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};                            \
+      MPQ_S_STEP(true, 0, A0, A1) MPQ_S_STEP(true, 1, A0, A1) MPQ_S_STEP(true, 2, A0, A1) MPQ_S_STEP(true, 3, A0, A1) \
+      MPQ_S_STEP(true, 4, A0, A1) MPQ_S_STEP(true, 5, A0, A1) MPQ_S_STEP(true, 6, A0, A1) MPQ_S_STEP(true, 7, A0, A1) \
+    }                                                                                                 \
+    for (; c < len; c += W) {                                                                         \
+      MPQ_S_HEAD                                                                                      \
+      const unsigned char* xb0 = xb4 + (c - n2) * (256u * XR);                                        \
+      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};                                \
+      MPQ_S_STEP(false, 0, A0, A1) MPQ_S_STEP(false, 1, A0, A1) MPQ_S_STEP(false, 2, A0, A1) MPQ_S_STEP(false, 3, A0, A1) \
+    }                                                                                                 \
+    c -= len;                                                                                         \
+  }
+
+  for (uint32_t g = 0; g < ngroups; ++g) {
+    const uint32_t first = g * ntl / ngroups, Rn = (g + 1) * ntl / ngroups - first;
+    float4_t acc00 = {0.f, 0.f, 0.f, 0.f}, acc01 = acc00, acc10 = acc00, acc11 = acc00;
+    float4_t acc20 = acc00, acc21 = acc00, acc30 = acc00, acc31 = acc00;
+    MPQ_S_TILE(0u, acc00, acc01)
+    MPQ_S_TILE(1u, acc10, acc11)
+    MPQ_S_TILE(2u, acc20, acc21)
+    MPQ_S_TILE(3u, acc30, acc31)
+
+    // ---- park the accumulators (lane l holds Y[m = l % 16 (+16)][rows 4*(l/16) .. +3] of a tile), TP
+    //      tiles at a time: [wave][tile of the step][batch half][m][row]; then every output of those
+    //      tiles is summed over the waves in a fixed order
+#pragma unroll
+    for (uint32_t st = 0; st < 4 / TP; ++st) {
+      if (st * TP >= Rn) break;
+      lds_barrier();  // everybody is done reading what was parked before
+      float* park = park0 + wv * (TP * NT * 256u) + i * 16u + 4u * j;
+      if (NT == 1) {
+        *(float4_t*)(park) = st == 0 ? acc00 : acc20;
+        *(float4_t*)(park + 256) = st == 0 ? acc10 : acc30;
+      } else {
+        *(float4_t*)(park) = st == 0 ? acc00 : st == 1 ? acc10 : st == 2 ? acc20 : acc30;
+        *(float4_t*)(park + 256) = st == 0 ? acc01 : st == 1 ? acc11 : st == 2 ? acc21 : acc31;
+      }
+      lds_barrier();
+      const uint32_t tn = Rn - st * TP < TP ? Rn - st * TP : TP;
+      for (uint32_t o = tid; o < tn * NT * 256u; o += W * 64u) {
+        const uint32_t m = (o >> 4) & 15u, nt = (o >> 8) % NT, tp = (o >> 8) / NT;
+        const float* pk = park0 + o;  // o = ((tp * NT + nt) * 16 + m) * 16 + row inside a wave's area
+        float sum = 0.f;
+#pragma unroll
+        for (uint32_t w2i = 0; w2i < W; ++w2i) sum += pk[w2i * (TP * NT * 256u)];
+        const uint32_t tile = t0 + first + st * TP + tp;
+        if (m + 16u * nt < (uint32_t)M) P[((size_t)h * T + tile) * (NT * 256u) + nt * 256u + (o & 0xFFu)] = sum;
+      }
+    }
+  }
+#undef MPQ_S_TILE
+#undef MPQ_S_HEAD
+#undef MPQ_S_STEP
+#undef MPQ_S_REQUEST
+#undef MPQ_S_NORMALIZE
+}
+
+// Second step of the slice kernel: Y[m][row] = fp16(outlier product of the row (Sec. 4.3) + the
+// partial sums of the ranges, in order).  One workgroup per tile.  Outliers: 16 lanes per row, each
+// takes every 16th word of the row and multiplies it with the activations of its column, which the
+// first kernel left transposed (XT[k][MP]: the MP batch values of a column are one or a few 16-byte
+// loads); then the lanes of a row are summed with DPP row shifts.  Batch columns >= M of XT were
+// never written: their sums are computed and dropped.
+template <int NT, int MP>
+__global__ void __launch_bounds__(256)
+mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const float* __restrict__ P,
+                      uint16_t* __restrict__ Y, const int M, const int H) {
+#pragma clang fp contract(off)
+  __shared__ float osum[MP][16];  // [batch column][row]
+  const uint32_t tile = blockIdx.x, hi4 = threadIdx.x >> 4, lo4 = threadIdx.x & 15u;
+  {
+    const uint32_t row = hi4, q = lo4;
+    const uint32_t* ostart = (const uint32_t*)(b.tiles + (size_t)tile * b.tile_stride + b.off_ot);
+    const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
+    const uint32_t e0 = ostart[row], e1 = ostart[row + 1];
+    float acc[MP];
+#pragma unroll
+    for (int m = 0; m < MP; ++m) acc[m] = 0.f;
+    // four words per lane and trip, all loads issued before the first use: the chain word ->
+    // activations is pure latency otherwise
+    for (uint32_t e = e0 + q; e < e1; e += 64) {
+      uint32_t word[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) word[u] = e + 16u * u < e1 ? owords[e + 16u * u] : 0u;
+      uint4 x[4][MP / 8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint4* xt = (const uint4*)(XT + (size_t)(word[u] & 0xFFFFu) * MP);
+#pragma unroll
+        for (int v4 = 0; v4 < MP / 8; ++v4) x[u][v4] = xt[v4];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (e + 16u * u >= e1) break;
+        const float v = (float)bits_to_half((uint16_t)(word[u] >> 16));
+#pragma unroll
+        for (int v4 = 0; v4 < MP / 8; ++v4) {
+          const uint32_t xw[4] = {x[u][v4].x, x[u][v4].y, x[u][v4].z, x[u][v4].w};
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            acc[8 * v4 + 2 * d] += v * (float)bits_to_half((uint16_t)xw[d]);
+            acc[8 * v4 + 2 * d + 1] += v * (float)bits_to_half((uint16_t)(xw[d] >> 16));
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int m = 0; m < MP; ++m) {
+      float oa = acc[m];
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x118, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x114, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x112, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x111, 0xf, 0xf, true));
+      if (q == 15) osum[m][row] = oa;
+    }
+  }
+  __syncthreads();
+  const uint32_t m = hi4, row = lo4, grow = tile * 16u + row;
+#pragma unroll
+  for (uint32_t nt = 0; nt < NT; ++nt) {
+    const uint32_t gm = m + 16u * nt;
+    if (gm >= (uint32_t)M) continue;
+    float sum = osum[gm % MP][row];
+    const float* p = P + (size_t)tile * (NT * 256u) + nt * 256u + m * 16u + row;
+    const size_t hs = (size_t)b.T * (NT * 256u);
+    uint32_t hh = 0;
+    for (; hh + 4 <= (uint32_t)H; hh += 4) {  // four loads in flight, added in order
+      const float p0 = p[hh * hs], p1 = p[(hh + 1) * hs], p2 = p[(hh + 2) * hs], p3 = p[(hh + 3) * hs];
+      sum += p0; sum += p1; sum += p2; sum += p3;
+    }
+    for (; hh < (uint32_t)H; ++hh) sum += p[hh * hs];
+    if (grow < (uint32_t)b.N) Y[(size_t)gm * b.N + grow] = half_to_bits((half_t)sum);
+  }
+}
+
 // ------------------------------------------------------------------------------------ GEMV
 //
 // y = W x (Algorithm 1, the matrix-vector product at batch 1) with the outlier product of Sec. 4.3
@@ -1108,6 +1435,10 @@ int g_range_per_cu = 0; // 0 = automatic (workgroups of the large-batch kernel p
 int g_range_bufs = 0;   // 0 = automatic, 1 = one activation buffer, 2 = two (large-batch kernel)
 int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
 int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
+int g_slices = -1;      // -1 = automatic, 1 = slice kernel for every M > 1, 0 = never
+int g_slice_waves = 0;  // 0 = automatic (16), 8
+int g_slice_min_h = 0;  // least number of ranges of the slice kernel (tests: several ranges on small matrices)
+int g_slice_launches = 0;
 int g_cu_count = 0;
 
 int cu_count() {
@@ -1325,8 +1656,120 @@ mpq_status launch_ranges(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
+// Device memory for the partial sums of the slice kernel: one grow-only buffer per (device, stream),
+// so that calls on different streams never share one.  Never allocates while the stream is being
+// captured into a graph; returns nullptr when nothing large enough is there and nothing can be
+// allocated (the caller then takes a kernel that needs no scratch).
+struct ScratchSlot {
+  int dev;
+  hipStream_t stream;
+  void* ptr;
+  size_t bytes;
+};
+constexpr int kScratchSlots = 16;
+ScratchSlot g_scratch[kScratchSlots];
+int g_scratch_used = 0;
+std::mutex g_scratch_mutex;
+
+void* scratch_get(hipStream_t s, size_t bytes) {
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  ScratchSlot* slot = nullptr;
+  for (int q = 0; q < g_scratch_used; ++q)
+    if (g_scratch[q].dev == dev && g_scratch[q].stream == s) slot = &g_scratch[q];
+  if (slot && slot->bytes >= bytes) return slot->ptr;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  if (cap != hipStreamCaptureStatusNone) return nullptr;
+  if (!slot) {
+    if (g_scratch_used == kScratchSlots) return nullptr;
+    slot = &g_scratch[g_scratch_used];
+    *slot = ScratchSlot{dev, s, nullptr, 0};
+  }
+  if (slot->ptr) {
+    // earlier launches on this stream may still use the old buffer
+    if (hipStreamSynchronize(s) != hipSuccess || hipFree(slot->ptr) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    slot->ptr = nullptr;
+    slot->bytes = 0;
+  }
+  const size_t want = (bytes + (bytes >> 2) + 0xFFFFFull) & ~0xFFFFFull;  // a quarter more, whole MiB
+  void* ptr = nullptr;
+  if (hipMalloc(&ptr, want) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  slot->ptr = ptr;
+  slot->bytes = want;
+  if (slot == &g_scratch[g_scratch_used]) ++g_scratch_used;
+  return ptr;
+}
+
+// Plan of the slice kernel: staged rows XR, the fewest ranges H whose activations fit the LDS of a
+// workgroup of W waves next to ring, unit table and park area, NB tile bands so that H * NB
+// workgroups about fill the compute units, groups of at most R = 4 tiles.
+bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePlan* pl, int* XR_out) {
+  const uint32_t NT = M > 16 ? 2 : 1, XR = M <= 8 ? 8 : 16 * NT;
+  const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
+  const uint32_t maxH = B2 > B4 ? B2 : B4;
+  const uint32_t cus = (uint32_t)cu_count();
+  uint32_t off = W * 2u * 1536u;
+  pl->off_units = off; off += (32u * (B2 + B4) + 15u) & ~15u;
+  pl->off_park = off;  off += W * 2048u;
+  off = (off + 1023u) & ~1023u;
+  pl->off_xbuf = off;
+  if (off >= budget) return false;
+  uint32_t H = g_slice_min_h > 1 ? (uint32_t)g_slice_min_h : 1u;
+  if (H > maxH) H = maxH;
+  for (; H <= maxH && H <= cus; ++H) {
+    const uint32_t nb2 = (B2 + H - 1) / H, nb4 = (B4 + H - 1) / H;  // the largest range
+    if ((size_t)(nb2 * 512u + nb4 * 256u) * XR > budget - off) continue;
+    uint32_t NB = cus / H;
+    if (NB > (uint32_t)h.T) NB = (uint32_t)h.T;
+    pl->H = (int32_t)H;
+    pl->NB = (int32_t)NB;
+    pl->R = 4;
+    *XR_out = (int)XR;
+    return true;
+  }
+  return false;
+}
+
+mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+  if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
+  SlicePlan pl;
+  int XR = 0;
+  const bool w8 = g_slice_waves == 8;
+  if (!plan_slices(h, M, w8 ? 8 : 16, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
+  const int NT = M > 16 ? 2 : 1;
+  // scratch: partial sums P[H][T][16 NT][16] fp32, then the transposed activations XT[K][XR] fp16
+  const size_t p_bytes = ((size_t)pl.H * (size_t)h.T * NT * 256 * sizeof(float) + 255) & ~(size_t)255;
+  const size_t bytes = p_bytes + (size_t)h.K * XR * sizeof(uint16_t);
+  unsigned char* scratch = (unsigned char*)scratch_get(s, bytes);
+  if (!scratch) return MPQ_ERR_UNSUPPORTED;
+  float* P = (float*)scratch;
+  uint16_t* XT = (uint16_t*)(scratch + p_bytes);
+  const dim3 grid((unsigned)(pl.H * pl.NB));
+#define MPQ_LAUNCH_S(NTV, XRV, WV) \
+  hipLaunchKernelGGL((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
+  if (w8) {
+    if (XR == 8) MPQ_LAUNCH_S(1, 8, 8); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8); else MPQ_LAUNCH_S(2, 32, 8);
+  } else {
+    if (XR == 8) MPQ_LAUNCH_S(1, 8, 16); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 16); else MPQ_LAUNCH_S(2, 32, 16);
+  }
+#undef MPQ_LAUNCH_S
+  if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
+  ++g_slice_launches;
+  const dim3 fgrid((unsigned)h.T), fblock(256);
+  if (XR == 8) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 8>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H);
+  else if (NT == 1) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 16>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H);
+  else hipLaunchKernelGGL((mpq_mms_finish_kernel<2, 32>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H);
+  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+}
+
 mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   if (M == 1) return gemv_all(h, d, X, Y, s);
+  if (g_slices > 0) {
+    const mpq_status st = launch_slices(h, d, X, Y, M, s);
+    if (st != MPQ_ERR_UNSUPPORTED) return st;
+  }
   if (mm_lds_bytes(h, 1, 3) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
   int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
   while (Mc > 1 && mm_lds_bytes(h, Mc, 3) > kLdsPerCu) --Mc;
@@ -1372,6 +1815,8 @@ extern "C" {
 //   7: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic
 //   8: its tiles per group (1..4)   9: its workgroups per compute unit (1 = 16 waves, 2 = 2 x 8 waves)
 //  10: its activation buffers (1, 2)
+//  12: slice kernel 1 = for every M > 1, 0 = never, -1 = automatic   13: its waves per workgroup (8, 16)
+//  14: its least number of ranges
 void mpq_debug_set(int key, int value) {
   if (key == 2) g_max_blocks = value;
   if (key == 4) g_gemv_waves = value;
@@ -1381,7 +1826,13 @@ void mpq_debug_set(int key, int value) {
   if (key == 8) g_range_tiles = value;
   if (key == 9) g_range_per_cu = value;
   if (key == 10) g_range_bufs = value;
+  if (key == 12) g_slices = value;
+  if (key == 13) g_slice_waves = value;
+  if (key == 14) g_slice_min_h = value;
 }
+
+// Counters for the tests: 12 = launches of the slice kernel so far.
+int mpq_debug_get(int key) { return key == 12 ? g_slice_launches : 0; }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
                     int32_t M, void* stream) {

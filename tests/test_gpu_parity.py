@@ -229,6 +229,47 @@ def test_large_batch_kernel_within_tolerance(torch, case, M, per_cu):
     assert np.array_equal(got, again)
 
 
+SLICE_CASES = [c for c in CASES if c[3] >= 64]   # the kernel gathers whole units: g1 >= 64
+
+
+@pytest.mark.parametrize("waves,min_h", [(16, 0), (8, 0), (16, 3)])
+@pytest.mark.parametrize("M", [2, 7, 8, 9, 16, 17, 32])
+@pytest.mark.parametrize("case", SLICE_CASES, ids=[c[0] for c in SLICE_CASES])
+def test_slice_kernel_within_tolerance(torch, case, M, waves, min_h):
+    # the kernel that keeps one K-range of the activations resident per workgroup and writes partial
+    # sums that a second kernel adds up, forced for every batch size through the tuning hook; with 16
+    # or 8 waves per workgroup, and with at least three ranges also on matrices whose activations
+    # would fit at once
+    import ctypes
+    lg, om, pk = make(case)
+    hook, count = mpq.lib().mpq_debug_set, mpq.lib().mpq_debug_get
+    hook.argtypes = [ctypes.c_int, ctypes.c_int]
+    count.argtypes, count.restype = [ctypes.c_int], ctypes.c_int
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(700 + M, M, pk.K)
+    ref = om.gemm(X, threads=8)
+    print("case", case, "M", M, "waves", waves, "min_h", min_h, flush=True)
+    before = count(12)
+    try:
+        hook(12, 1)
+        hook(13, waves)
+        hook(14, min_h)
+        Y = Guarded(torch, M * pk.N)
+        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+        got = Y.check_and_get().reshape(M, pk.N)
+        Y2 = Guarded(torch, M * pk.N)
+        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M)
+        again = Y2.check_and_get().reshape(M, pk.N)
+    finally:
+        hook(12, -1)
+        hook(13, 0)
+        hook(14, 0)
+    assert count(12) == before + 2, "the slice kernel did not run"
+    e_floor, e_max = rel_err(got, ref)
+    assert e_floor <= TOL, (e_floor, e_max)
+    assert np.array_equal(got, again)
+
+
 def test_several_products_in_one_launch(torch):
     # mpq_gemv_multi: independent products of different shapes (ragged rows, long rows, many outliers)
     cases = [CASES[0], CASES[1], CASES[6], CASES[8], CASES[2]]
