@@ -802,7 +802,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #pragma clang fp contract(off)
   static_assert(WV == 8 || WV == 16, "waves");
   static_assert(XR == 8 || XR == 16 * NT, "staged rows");
-  constexpr uint32_t W = WV, PD = 2, SLOTB = 1536;
+  constexpr uint32_t W = WV, PD = 2, SLOTB = 1536, RMAX = 8;
   constexpr uint32_t TP = 2 / NT;  // tiles parked at a time (2 KiB per wave)
   __shared__ __align__(16) unsigned char lds[LDSB];
   const uint32_t tid = threadIdx.x;
@@ -968,27 +968,26 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 
   for (uint32_t g = 0; g < ngroups; ++g) {
     const uint32_t first = g * ntl / ngroups, Rn = (g + 1) * ntl / ngroups - first;
-    float4_t acc00 = {0.f, 0.f, 0.f, 0.f}, acc01 = acc00, acc10 = acc00, acc11 = acc00;
-    float4_t acc20 = acc00, acc21 = acc00, acc30 = acc00, acc31 = acc00;
-    MPQ_S_TILE(0u, acc00, acc01)
-    MPQ_S_TILE(1u, acc10, acc11)
-    MPQ_S_TILE(2u, acc20, acc21)
-    MPQ_S_TILE(3u, acc30, acc31)
+    float4_t acc[RMAX][2];
+#pragma unroll
+    for (uint32_t tt = 0; tt < RMAX; ++tt) acc[tt][0] = acc[tt][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (uint32_t tt = 0; tt < RMAX; ++tt) MPQ_S_TILE(tt, acc[tt][0], acc[tt][1])
 
     // ---- park the accumulators (lane l holds Y[m = l % 16 (+16)][rows 4*(l/16) .. +3] of a tile), TP
     //      tiles at a time: [wave][tile of the step][batch half][m][row]; then every output of those
     //      tiles is summed over the waves in a fixed order
 #pragma unroll
-    for (uint32_t st = 0; st < 4 / TP; ++st) {
+    for (uint32_t st = 0; st < RMAX / TP; ++st) {
       if (st * TP >= Rn) break;
       lds_barrier();  // everybody is done reading what was parked before
       float* park = park0 + wv * (TP * NT * 256u) + i * 16u + 4u * j;
       if (NT == 1) {
-        *(float4_t*)(park) = st == 0 ? acc00 : acc20;
-        *(float4_t*)(park + 256) = st == 0 ? acc10 : acc30;
+        *(float4_t*)(park) = acc[st * TP][0];
+        *(float4_t*)(park + 256) = acc[(st * TP + 1) % RMAX][0];
       } else {
-        *(float4_t*)(park) = st == 0 ? acc00 : st == 1 ? acc10 : st == 2 ? acc20 : acc30;
-        *(float4_t*)(park + 256) = st == 0 ? acc01 : st == 1 ? acc11 : st == 2 ? acc21 : acc31;
+        *(float4_t*)(park) = acc[st][0];
+        *(float4_t*)(park + 256) = acc[st][1];
       }
       lds_barrier();
       const uint32_t tn = Rn - st * TP < TP ? Rn - st * TP : TP;
@@ -1019,15 +1018,36 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 template <int NT, int MP>
 __global__ void __launch_bounds__(256)
 mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const float* __restrict__ P,
-                      uint16_t* __restrict__ Y, const int M, const int H) {
+                      uint16_t* __restrict__ Y, const int M, const int H, const uint32_t ocap) {
 #pragma clang fp contract(off)
-  __shared__ float osum[MP][16];  // [batch column][row]
+  constexpr uint32_t WCAP = 2048;      // outlier words of the tile kept in LDS (the rest is read from memory)
+  __shared__ float osum[MP][16];       // [batch column][row]
+  __shared__ uint32_t wlds[WCAP];
   const uint32_t tile = blockIdx.x, hi4 = threadIdx.x >> 4, lo4 = threadIdx.x & 15u;
+  const uint32_t* ostart = (const uint32_t*)(b.tiles + (size_t)tile * b.tile_stride + b.off_ot);
+  const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
+  // ---- everything that does not depend on another load is requested first: the row starts, the
+  //      tile's words (into LDS: which row they belong to is not known yet) and the partial sums
+  const uint32_t e0 = ostart[hi4], e1 = ostart[hi4 + 1];
+  {
+    const uint32_t nw = ocap < WCAP ? ocap : WCAP;  // the record holds ocap words (zeros after the last one)
+    uint32_t wreg[WCAP / 256];
+#pragma unroll
+    for (uint32_t u = 0; u < WCAP / 256; ++u) wreg[u] = threadIdx.x + 256u * u < nw ? owords[threadIdx.x + 256u * u] : 0u;
+#pragma unroll
+    for (uint32_t u = 0; u < WCAP / 256; ++u) wlds[threadIdx.x + 256u * u] = wreg[u];
+  }
+  const float* p = P + (size_t)tile * (NT * 256u) + threadIdx.x;  // + nt * 256 + range * hs
+  const size_t hs = (size_t)b.T * (NT * 256u);
+  float pfirst[NT][2];
+#pragma unroll
+  for (uint32_t nt = 0; nt < NT; ++nt) {
+    pfirst[nt][0] = hi4 + 16u * nt < (uint32_t)M ? p[nt * 256u] : 0.f;
+    pfirst[nt][1] = hi4 + 16u * nt < (uint32_t)M && H > 1 ? p[nt * 256u + hs] : 0.f;
+  }
+  __syncthreads();
   {
     const uint32_t row = hi4, q = lo4;
-    const uint32_t* ostart = (const uint32_t*)(b.tiles + (size_t)tile * b.tile_stride + b.off_ot);
-    const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
-    const uint32_t e0 = ostart[row], e1 = ostart[row + 1];
     float acc[MP];
 #pragma unroll
     for (int m = 0; m < MP; ++m) acc[m] = 0.f;
@@ -1036,7 +1056,10 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
     for (uint32_t e = e0 + q; e < e1; e += 64) {
       uint32_t word[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) word[u] = e + 16u * u < e1 ? owords[e + 16u * u] : 0u;
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t eu = e + 16u * u;
+        word[u] = eu >= e1 ? 0u : eu < WCAP ? wlds[eu] : owords[eu];
+      }
       uint4 x[4][MP / 8];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -1076,14 +1099,15 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
     const uint32_t gm = m + 16u * nt;
     if (gm >= (uint32_t)M) continue;
     float sum = osum[gm % MP][row];
-    const float* p = P + (size_t)tile * (NT * 256u) + nt * 256u + m * 16u + row;
-    const size_t hs = (size_t)b.T * (NT * 256u);
-    uint32_t hh = 0;
+    sum += pfirst[nt][0];
+    if (H > 1) sum += pfirst[nt][1];
+    const float* pn = p + nt * 256u;
+    uint32_t hh = 2;
     for (; hh + 4 <= (uint32_t)H; hh += 4) {  // four loads in flight, added in order
-      const float p0 = p[hh * hs], p1 = p[(hh + 1) * hs], p2 = p[(hh + 2) * hs], p3 = p[(hh + 3) * hs];
+      const float p0 = pn[hh * hs], p1 = pn[(hh + 1) * hs], p2 = pn[(hh + 2) * hs], p3 = pn[(hh + 3) * hs];
       sum += p0; sum += p1; sum += p2; sum += p3;
     }
-    for (; hh < (uint32_t)H; ++hh) sum += p[hh * hs];
+    for (; hh < (uint32_t)H; ++hh) sum += pn[hh * hs];
     if (grow < (uint32_t)b.N) Y[(size_t)gm * b.N + grow] = half_to_bits((half_t)sum);
   }
 }
@@ -1436,9 +1460,10 @@ int g_range_bufs = 0;   // 0 = automatic, 1 = one activation buffer, 2 = two (la
 int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
 int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
 int g_slices = -1;      // -1 = automatic, 1 = slice kernel for every M > 1, 0 = never
-int g_slice_waves = 0;  // 0 = automatic (16), 8
+int g_slice_waves = 0;  // 0 = automatic (8), 16
 int g_slice_min_h = 0;  // least number of ranges of the slice kernel (tests: several ranges on small matrices)
 int g_slice_launches = 0;
+int g_slice_tiles = 0;  // 0 = automatic (tiles per group of the slice kernel, 1..8)
 int g_cu_count = 0;
 
 int cu_count() {
@@ -1704,7 +1729,7 @@ void* scratch_get(hipStream_t s, size_t bytes) {
 
 // Plan of the slice kernel: staged rows XR, the fewest ranges H whose activations fit the LDS of a
 // workgroup of W waves next to ring, unit table and park area, NB tile bands so that H * NB
-// workgroups about fill the compute units, groups of at most R = 4 tiles.
+// workgroups about fill the compute units, groups of at most R = 8 tiles.
 bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePlan* pl, int* XR_out) {
   const uint32_t NT = M > 16 ? 2 : 1, XR = M <= 8 ? 8 : 16 * NT;
   const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
@@ -1725,7 +1750,7 @@ bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePl
     if (NB > (uint32_t)h.T) NB = (uint32_t)h.T;
     pl->H = (int32_t)H;
     pl->NB = (int32_t)NB;
-    pl->R = 4;
+    pl->R = g_slice_tiles > 0 && g_slice_tiles <= 8 ? g_slice_tiles : 8;
     *XR_out = (int)XR;
     return true;
   }
@@ -1736,7 +1761,7 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
   SlicePlan pl;
   int XR = 0;
-  const bool w8 = g_slice_waves == 8;
+  const bool w8 = g_slice_waves != 16;  // 8 waves leave more LDS for the activations: faster on every shape measured
   if (!plan_slices(h, M, w8 ? 8 : 16, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   const int NT = M > 16 ? 2 : 1;
   // scratch: partial sums P[H][T][16 NT][16] fp32, then the transposed activations XT[K][XR] fp16
@@ -1758,22 +1783,30 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
   ++g_slice_launches;
   const dim3 fgrid((unsigned)h.T), fblock(256);
-  if (XR == 8) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 8>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H);
-  else if (NT == 1) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 16>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H);
-  else hipLaunchKernelGGL((mpq_mms_finish_kernel<2, 32>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H);
+  if (XR == 8) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 8>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
+  else if (NT == 1) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 16>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
+  else hipLaunchKernelGGL((mpq_mms_finish_kernel<2, 32>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
 mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
   if (M == 1) return gemv_all(h, d, X, Y, s);
-  if (g_slices > 0) {
-    const mpq_status st = launch_slices(h, d, X, Y, M, s);
-    if (st != MPQ_ERR_UNSUPPORTED) return st;
-  }
   if (mm_lds_bytes(h, 1, 3) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
   int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
   while (Mc > 1 && mm_lds_bytes(h, Mc, 3) > kLdsPerCu) --Mc;
   if (Mc > 16 && Mc < M) Mc = 16;
+  {
+    // The slice kernel reads and decodes the weights once whatever M is and costs about 1.25 x the
+    // matrix-vector product plus 7 us for its second kernel; the chunked path below costs one pass
+    // over the weights per chunk.  Measured on the Llama2-7B and Llama2-70B shapes, M = 2..32, the
+    // slice kernel wins from three chunks on, and with two chunks unless the matrix is small.
+    const int chunks = (M + Mc - 1) / Mc;
+    const bool better = chunks >= 3 || (chunks == 2 && h.total_bytes >= (12u << 20));
+    if (g_slices < 0 ? better : g_slices != 0) {
+      const mpq_status st = launch_slices(h, d, X, Y, M, s);
+      if (st != MPQ_ERR_UNSUPPORTED) return st;
+    }
+  }
   {
     // The large-batch kernel reads and decodes the weights once whatever M is, but pays a chain of
     // staging steps per tile group; measured against the chunked path on the Llama2-7B and
@@ -1816,7 +1849,7 @@ extern "C" {
 //   8: its tiles per group (1..4)   9: its workgroups per compute unit (1 = 16 waves, 2 = 2 x 8 waves)
 //  10: its activation buffers (1, 2)
 //  12: slice kernel 1 = for every M > 1, 0 = never, -1 = automatic   13: its waves per workgroup (8, 16)
-//  14: its least number of ranges
+//  14: its least number of ranges   15: its tiles per group (1..8)
 void mpq_debug_set(int key, int value) {
   if (key == 2) g_max_blocks = value;
   if (key == 4) g_gemv_waves = value;
@@ -1829,6 +1862,7 @@ void mpq_debug_set(int key, int value) {
   if (key == 12) g_slices = value;
   if (key == 13) g_slice_waves = value;
   if (key == 14) g_slice_min_h = value;
+  if (key == 15) g_slice_tiles = value;
 }
 
 // Counters for the tests: 12 = launches of the slice kernel so far.
