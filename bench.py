@@ -221,7 +221,7 @@ def main():
     achieved = bytes_per_launch / (avg_launch_us * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": ("mpq_gemv_multi_kernel" if args.multi else "mpq_gemv_kernel" if M == 1 else "mpq_mm_kernel") + " (every launch of the step)", "avg_launch_us": round(avg_launch_us, 3),
+                "kernel": ("mpq_gemv_multi_kernel" if args.multi else "mpq_gemv_kernel" if M == 1 else "mpq_mm_kernel or mpq_mms_kernel + mpq_mms_finish_kernel") + " (every product of the step)", "avg_launch_us": round(avg_launch_us, 3),
                 "bytes_per_launch": round(bytes_per_launch)}
     traffic_file = os.path.join(ROOT, "profiles", "gemv_llama2_7b_traffic.json")
     if args.config == 1 and M == 1 and not over and not args.multi and args.f4 is None and args.p_o is None and os.path.exists(traffic_file):

@@ -170,7 +170,13 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
                           const uint16_t* const* x_dev, uint16_t* const* y_dev, void* stream);
 
 /* Small-batch product Y[m][n] = sum_k X[m][k] W[n][k] (+ outliers), 1 <= M <= MPQ_MAX_M.
- * X_dev is M x K row-major fp16, Y_dev is M x N row-major fp16 (overwritten). */
+ * X_dev is M x K row-major fp16, Y_dev is M x N row-major fp16 (overwritten).
+ * Device memory: for batches whose activations do not fit the on-chip memory the library keeps a
+ * scratch buffer per (device, stream) for partial sums - a few MiB to a few tens of MiB, allocated
+ * (and grown) at a call on that stream, owned by the library until the process ends.  It never
+ * allocates while `stream` is being captured into a graph: a captured call uses the scratch that an
+ * earlier call on the same stream left, or else a slower path that needs none.  Calls on one
+ * stream are ordered by the stream; calls on different streams use different buffers. */
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev,
                     uint16_t* Y_dev, int32_t M, void* stream);
 

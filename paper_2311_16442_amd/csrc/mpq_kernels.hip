@@ -4,8 +4,8 @@
 //   mpq_gemv_kernel      Algorithm 1 (GEMV with asynchronous dequantization) re-designed for CDNA4,
 //                        with the outlier product of Sec. 4.3 fused in as a per-row correction.
 //   mpq_mm_kernel        the same product for a batch of 2..32 activation rows that fit the LDS.
-//   mpq_mmr_kernel       the same for batches that do not: activations staged range by range.
-//   mpq_mms_kernel       the same with one range resident per workgroup (+ mpq_mms_finish_kernel).
+//   mpq_mms_kernel       the same for batches that do not: one K-range of the activations resident
+//                        per workgroup, partial sums added up by mpq_mms_finish_kernel.
 //   mpq_dequant_kernel   eq. 5 applied twice (scale, then weight), written out as row-major fp16.
 //   mpq_outlier_add_kernel  adds the CSR values to a dequantized matrix (dense + sparse, Sec. 2.3).
 //
@@ -438,341 +438,14 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 
 // ------------------------------------------------------------------------------------ product, large batches
 //
-// Y = X W^T for batches whose activations do not fit the LDS next to everything else
-// (M * K * 2 bytes above roughly 100 KiB).  Same block arithmetic as above; what changes is how the
-// activations are staged:
-//
-//   The code blocks of a tile are cut into H ranges in stream order (range h = 2-bit blocks
-//   [h*nb2, (h+1)*nb2) and 4-bit blocks [h*nb4, (h+1)*nb4)).  The activations that a range needs
-//   are gathered into LDS in the order the blocks use them: slot ((unit*8 + step) * rows + m) holds
-//   the 8 fp16 values X[m][k0(unit) + 8*step ..], so the B operand of block c, unit j, step P is a
-//   linear function of (c, j, P) and the 16 batch rows of a step are 256 contiguous bytes.
-//   One persistent workgroup (8 waves) per compute unit works on R = 4 consecutive tiles at a time:
-//   for every range it stages the activations once, then its waves share the range's blocks of the
-//   R tiles round-robin, each wave adding into one accumulator per tile that it keeps in registers
-//   over all ranges.  The weights are read and decoded exactly once whatever M is; the staged
-//   activations cost M*K*2 bytes of L2 traffic per R tiles.  The ring of code blocks stays full
-//   across ranges, tiles and tile groups (the requests follow the same enumeration as the
-//   consumption, two blocks ahead).
-//
-//   Outliers (Sec. 4.3): a row's words are sorted by column and the 2-bit units are in K order, so
-//   the words that fall into a range are a contiguous piece of the row's list; the pieces are found
-//   once per tile group by binary search (16 rows x (H-1) boundaries per tile, all in parallel) and
-//   each piece is multiplied while its activations are staged.  Lane (m, q) of wave w owns batch
-//   column m (and m + 16) of rows 8w + q and 8w + 4 + q of the tile group.
-//
-//   At the end of a tile group every wave parks its accumulators, two tiles at a time, in the
-//   activation buffer (idle by then), the workgroup meets, and each output is summed over the waves
-//   in a fixed order.
-struct RangePlan {
-  int32_t H, nb2, nb4, R;
-  uint32_t off_sides, off_units, off_cpos, off_splits, off_ored, off_xbuf;  // LDS byte offsets (ring at 0)
-  uint32_t xbuf_stride;  // bytes from the first activation buffer to the second
-};
-
-template <int NT, int LDSB, int WV>
-__global__ void __launch_bounds__(WV * 64)
-mpq_mmr_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M, const RangePlan pl) {
-#pragma clang fp contract(off)
-  static_assert(WV == 8 || WV == 16, "waves");
-  constexpr uint32_t W = WV, PD = 2;
-  constexpr uint32_t ROWS = 16 * NT;   // staged batch rows
-  constexpr uint32_t OPASS = 16 / W;   // passes of four rows per wave over the 64 rows of a tile group
-  __shared__ __align__(16) unsigned char lds[LDSB];
-  const uint32_t tid = threadIdx.x;
-  const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
-  const uint32_t C = b.C, T = b.T, B2 = b.B2, B4 = C - B2, grid = gridDim.x;
-  const uint32_t H = pl.H, nb2 = pl.nb2, nb4 = pl.nb4, R = pl.R;
-  const uint32_t ngroups = (T + R - 1) / R;
-  unsigned char* const ring = lds;
-  unsigned char* const sides = lds + pl.off_sides;
-  unsigned char* const units = lds + pl.off_units;
-  uint16_t* const cpos = (uint16_t*)(lds + pl.off_cpos);       // 64-column chunk -> 2-bit unit index
-  uint32_t* const splits = (uint32_t*)(lds + pl.off_splits);   // [R][H + 1][16]
-  float* const ored = (float*)(lds + pl.off_ored);             // [R * 16 rows][NT][16 m]
-  unsigned char* const xbuf = lds + pl.off_xbuf;
-  const uint32_t base4 = nb2 * 4u * 8u * ROWS * 16u;           // 4-bit part of the activation buffer
-  const DecodeConsts kc = make_consts();
-
-  // ---- requests of code blocks: the enumeration (tile group, range, tile, block) that the
-  //      consumption below follows, restricted to every W-th block
-  const uint32_t ring0 = lds_addr(ring) + wv * (PD * 1024);
-  uint32_t r_grp = blockIdx.x, r_h = 0, r_t = 0, r_c = wv;
-  uint32_t r_n2 = B2 < nb2 ? B2 : nb2, r_len = r_n2 + (B4 < nb4 ? B4 : nb4);
-  uint32_t r_Rn = r_grp < ngroups ? (T - r_grp * R < R ? T - r_grp * R : R) : 0;
-#define MPQ_R_NORMALIZE                                                                 \
-  while (r_grp < ngroups && r_c >= r_len) {                                             \
-    r_c -= r_len;                                                                       \
-    if (++r_t == r_Rn) {                                                                \
-      r_t = 0;                                                                          \
-      if (++r_h == H) {                                                                 \
-        r_h = 0;                                                                        \
-        r_grp += grid;                                                                  \
-        r_Rn = r_grp < ngroups ? (T - r_grp * R < R ? T - r_grp * R : R) : 0;           \
-      }                                                                                 \
-      const uint32_t a2 = r_h * nb2, a4 = r_h * nb4;                                    \
-      r_n2 = a2 < B2 ? (B2 - a2 < nb2 ? B2 - a2 : nb2) : 0;                             \
-      r_len = r_n2 + (a4 < B4 ? (B4 - a4 < nb4 ? B4 - a4 : nb4) : 0);                   \
-    }                                                                                   \
-  }
-#define MPQ_R_REQUEST(SLOT)                                                             \
-  {                                                                                     \
-    const uint32_t blk = r_c < r_n2 ? r_h * nb2 + r_c : B2 + r_h * nb4 + (r_c - r_n2);  \
-    const unsigned char* src = b.tiles + (size_t)(r_grp * R + r_t) * b.tile_stride + b.codes_off + blk * 1024u; \
-    dma16(src, lane16, ring0 + (SLOT) * 1024u);                                         \
-    ++inflight;                                                                         \
-    r_c += W;                                                                           \
-    MPQ_R_NORMALIZE                                                                     \
-  }
-  uint32_t inflight = 0;
-  MPQ_R_NORMALIZE
-#pragma unroll
-  for (uint32_t r = 0; r < PD; ++r)
-    if (r_grp < ngroups) MPQ_R_REQUEST(r)
-
-  // ---- once per workgroup: unit table, then the chunk -> unit map for the outlier columns
-  dma_linear<W>(b.units, lds_addr(units), 32u * C, wv, lane16);
-  MPQ_VMCNT(0);
-  lds_barrier();
-  for (uint32_t u = tid; u < 4u * B2; u += W * 64u) {
-    const uint2 ue = ((const uint2*)units)[u];
-    if ((ue.y & 0xFFFFu) != 32u * (uint32_t)b.G) cpos[ue.x >> 7] = (uint16_t)u;
-  }
-
-  const unsigned char* unitj = units + j * 8;
-  const uint32_t ringl = ring0 + lane16;
-  const unsigned char* xb2 = xbuf + j * (2048u * NT) + i * 16u;           // + block * 8192 * NT + step * 256 * NT
-  const unsigned char* xb4 = xbuf + base4 + j * (1024u * NT) + i * 16u;   // + block * 4096 * NT + step * 256 * NT
-  // staging: lane -> (batch row, piece) of a 64-slot piece of the activation buffer
-  const uint32_t sm = lane % ROWS, sp = lane / ROWS;
-  const uint32_t stage_off = sm * 2u * (uint32_t)b.K + sp * 16u;
-  const bool stage_on = sm < (uint32_t)M;
-  uint32_t slot = 0, c = wv;
-
-  // Requests the activations of range HH into buffer HH % 2: 64-slot pieces, round-robin over the
-  // waves.  stg counts this wave's requests; blocks_before = code blocks of this wave requested
-  // earlier and still in flight (their waits must allow for the younger staging requests).
-  uint32_t stg = 0, blocks_before = 0;
-#define MPQ_R_STAGE(HH)                                                                              \
-  {                                                                                                   \
-    constexpr uint32_t PP = 4 / NT; /* steps per 64-slot piece */                                     \
-    const uint32_t sa2 = (HH) * nb2, sa4 = (HH) * nb4;                                                \
-    const uint32_t sn2 = sa2 < B2 ? (B2 - sa2 < nb2 ? B2 - sa2 : nb2) : 0;                            \
-    const uint32_t sn4 = sa4 < B4 ? (B4 - sa4 < nb4 ? B4 - sa4 : nb4) : 0;                            \
-    const uint32_t items2 = sn2 * 4u * (8u / PP), items = items2 + sn4 * 4u * (4u / PP);              \
-    const uint32_t sbuf = lds_addr(xbuf) + ((HH) & 1u) * pl.xbuf_stride;                              \
-    stg = 0;                                                                                          \
-    blocks_before = inflight;                                                                         \
-    for (uint32_t it = wv; it < items; it += W) {                                                     \
-      uint32_t unit, p0, dst;                                                                         \
-      if (it < items2) {                                                                              \
-        const uint32_t ul = it / (8u / PP);                                                           \
-        p0 = (it % (8u / PP)) * PP;                                                                   \
-        unit = sa2 * 4u + ul;                                                                         \
-        dst = (ul * 8u + p0) * ROWS * 16u;                                                            \
-      } else {                                                                                        \
-        const uint32_t it4 = it - items2, ul = it4 / (4u / PP);                                       \
-        p0 = (it4 % (4u / PP)) * PP;                                                                  \
-        unit = 4u * B2 + sa4 * 4u + ul;                                                               \
-        dst = base4 + (ul * 4u + p0) * ROWS * 16u;                                                    \
-      }                                                                                               \
-      const uint32_t k0x2 = *(const uint32_t*)(units + unit * 8u); /* same address in every lane */   \
-      if (stage_on) dma16((const unsigned char*)X, stage_off + k0x2 + p0 * 16u, sbuf + dst);          \
-      ++stg;                                                                                          \
-    }                                                                                                 \
-  }
-
-  for (uint32_t grp = blockIdx.x; grp < ngroups; grp += grid) {
-    const uint32_t Rn = T - grp * R < R ? T - grp * R : R;
-    // ---- side records of the group's tiles
-    for (uint32_t t = 0; t < Rn; ++t)
-      dma_linear<W>(b.tiles + (size_t)(grp * R + t) * b.tile_stride, lds_addr(sides) + t * b.side_bytes, b.side_bytes, wv, lane16);
-    MPQ_VMCNT(0);
-    lds_barrier();
-    // ---- where each row's outlier words cross from one range into the next
-    for (uint32_t idx = tid; idx < Rn * (H + 1) * 16u; idx += W * 64u) {
-      const uint32_t r = idx & 15u, hb = (idx >> 4) % (H + 1), t = (idx >> 4) / (H + 1);
-      const uint32_t* ostart = (const uint32_t*)(sides + t * b.side_bytes + b.off_ot);
-      const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
-      uint32_t lo = ostart[r], hi = ostart[r + 1];
-      if (hb == 0) hi = lo;
-      if (hb > 0 && hb < H) {
-        const uint32_t ub = hb * nb2 * 4u;  // first 2-bit unit of range hb
-        while (lo < hi) {
-          const uint32_t mid = (lo + hi) >> 1;
-          const uint32_t u = cpos[(owords[mid] & 0xFFFFu) >> 6];
-          if (u < ub) lo = mid + 1; else hi = mid;
-        }
-      }
-      splits[(t * (H + 1) + hb) * 16u + r] = hb == H ? hi : lo;
-    }
-    float4_t acc00 = {0.f, 0.f, 0.f, 0.f}, acc01 = acc00, acc10 = acc00, acc11 = acc00;
-    float4_t acc20 = acc00, acc21 = acc00, acc30 = acc00, acc31 = acc00;
-    float oa00 = 0.f, oa01 = 0.f, oa10 = 0.f, oa11 = 0.f;  // [pass][batch half]
-
-    MPQ_R_STAGE(0u)  // the first range's activations; the barrier also publishes the splits
-    MPQ_VMCNT(0);
-    blocks_before = 0;
-    lds_barrier();
-    for (uint32_t h = 0; h < H; ++h) {
-      const uint32_t a2 = h * nb2, a4 = h * nb4;
-      const uint32_t n2 = a2 < B2 ? (B2 - a2 < nb2 ? B2 - a2 : nb2) : 0;
-      const uint32_t n4 = a4 < B4 ? (B4 - a4 < nb4 ? B4 - a4 : nb4) : 0;
-      const uint32_t len = n2 + n4;
-      const unsigned char* const xcur = xbuf + (h & 1u) * pl.xbuf_stride;  // this range's activations
-      // ---- two buffers: request the activations of the NEXT range into the other buffer (everybody
-      //      left it at the barrier that closed the previous range); they land while this range is
-      //      computed.  One buffer (xbuf_stride = 0, larger ranges): staged between two barriers below.
-      const bool two_bufs = pl.xbuf_stride != 0;
-      if (two_bufs && h + 1 < H) MPQ_R_STAGE(h + 1)
-      // ---- the range's blocks of the group's tiles
-#define MPQ_R_STEP(TWO, P, A0, A1)                                                                   \
-  {                                                                                                   \
-    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
-    const uint4 bv0 = *(const uint4*)(xb0 + (P) * 256 * NT);                                          \
-    A0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                      \
-                                                __builtin_bit_cast(half8_t, bv0), A0, 0, 0, 0);       \
-    if (NT > 1) {                                                                                     \
-      const uint4 bv1 = *(const uint4*)(xb0 + (P) * 256 * NT + 256);                                  \
-      A1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
-                                                  __builtin_bit_cast(half8_t, bv1), A1, 0, 0, 0);     \
-    }                                                                                                 \
-  }
-#define MPQ_R_HEAD(BLK)                                                                                \
-  /* younger than the block needed now: the other blocks in flight and, for blocks requested before  \
-     the staging of the next range, this wave's staging requests */                                  \
-  if (blocks_before > 0) { wait_vm((int)(inflight - 1 + stg)); --blocks_before; }                     \
-  else if (inflight == PD) MPQ_VMCNT(PD - 1);                                                         \
-  else MPQ_VMCNT(0); /* PD = 2: nothing else of this wave can be in flight */                         \
-  uint4 q;                                                                                            \
-  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(q) : "v"(ringl + slot * 1024u) : "memory"); \
-  --inflight;                                                                                         \
-  if (r_grp < ngroups) MPQ_R_REQUEST(slot)                                                            \
-  slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
-  const uint32_t uy = *(const uint32_t*)(unitj + (BLK) * 32u + 4);                                    \
-  const uint32_t m1 = *(const uint16_t*)(m1i + (uy & 0xFFFFu));                                       \
-  const uint32_t m2 = *(const uint32_t*)(m2i + (uy >> 16));                                           \
-  const half_t s1 = scale_dequant(m1 & 0xFFu, m2);                                                    \
-  const half2_t s1p = {s1, s1};                                                                       \
-  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                    \
-  const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-#define MPQ_R_TILE(TT, A0, A1)                                                                         \
-  if ((TT) < Rn) {                                                                                    \
-    const unsigned char* m1i = sides + (TT) * b.side_bytes + i * 2;                                   \
-    const unsigned char* m2i = sides + (TT) * b.side_bytes + b.off_m2 + (i >> b.m2_shift) * 4;        \
-    for (; c < n2; c += W) {                                                                          \
-      MPQ_R_HEAD(a2 + c)                                                                              \
-      const unsigned char* xb0 = xb2 + (h & 1u) * pl.xbuf_stride + c * (8192u * NT);                  \
-      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};                            \
-      MPQ_R_STEP(true, 0, A0, A1) MPQ_R_STEP(true, 1, A0, A1) MPQ_R_STEP(true, 2, A0, A1) MPQ_R_STEP(true, 3, A0, A1) \
-      MPQ_R_STEP(true, 4, A0, A1) MPQ_R_STEP(true, 5, A0, A1) MPQ_R_STEP(true, 6, A0, A1) MPQ_R_STEP(true, 7, A0, A1) \
-    }                                                                                                 \
-    for (; c < len; c += W) {                                                                         \
-      MPQ_R_HEAD(B2 + a4 + (c - n2))                                                                  \
-      const unsigned char* xb0 = xb4 + (h & 1u) * pl.xbuf_stride + (c - n2) * (4096u * NT);           \
-      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};                                \
-      MPQ_R_STEP(false, 0, A0, A1) MPQ_R_STEP(false, 1, A0, A1) MPQ_R_STEP(false, 2, A0, A1) MPQ_R_STEP(false, 3, A0, A1) \
-    }                                                                                                 \
-    c -= len;                                                                                         \
-  }
-      MPQ_R_TILE(0u, acc00, acc01)
-      MPQ_R_TILE(1u, acc10, acc11)
-      MPQ_R_TILE(2u, acc20, acc21)
-      MPQ_R_TILE(3u, acc30, acc31)
-
-      // ---- the range's outlier words of this wave's rows (two passes of four rows)
-#define MPQ_R_OUTL(PASS, O0, O1)                                                                      \
-  {                                                                                                   \
-    const uint32_t fr = wv * (4u * OPASS) + (PASS) * 4u + j, t = fr >> 4, r = fr & 15u;               \
-    if (t < Rn) {                                                                                     \
-      const uint32_t* owords = (const uint32_t*)(sides + t * b.side_bytes + b.off_ot + MPQ_OTILE_HEAD); \
-      const uint32_t e0 = splits[(t * (H + 1) + h) * 16u + r], e1 = splits[(t * (H + 1) + h + 1) * 16u + r]; \
-      for (uint32_t e = e0; e < e1; ++e) {                                                            \
-        const uint32_t word = owords[e], col = word & 0xFFFFu;                                        \
-        const uint32_t ul = (uint32_t)cpos[col >> 6] - a2 * 4u;                                       \
-        const unsigned char* xp = xcur + (ul * 8u + ((col >> 3) & 7u)) * (ROWS * 16u) + i * 16u + (col & 7u) * 2u; \
-        const float v = (float)bits_to_half((uint16_t)(word >> 16));                                  \
-        O0 += v * (float)*(const half_t*)xp;                                                          \
-        if (NT > 1) O1 += v * (float)*(const half_t*)(xp + 256);                                      \
-      }                                                                                               \
-    }                                                                                                 \
-  }
-      MPQ_R_OUTL(0u, oa00, oa01)
-      if (OPASS > 1) MPQ_R_OUTL(1u, oa10, oa11)
-      // ---- the next range's activations have landed (every wave waits for its own requests) and
-      //      everybody is done with this range's
-      if (two_bufs) {
-        MPQ_VMCNT(0);
-        blocks_before = 0;
-        lds_barrier();
-      } else {
-        lds_barrier();
-        if (h + 1 < H) {
-          MPQ_R_STAGE(h + 1)
-          MPQ_VMCNT(0);
-          blocks_before = 0;
-          lds_barrier();
-        }
-      }
-    }
-#undef MPQ_R_OUTL
-#undef MPQ_R_TILE
-#undef MPQ_R_HEAD
-#undef MPQ_R_STEP
-
-    // ---- park the accumulators (lane l holds Y[m = l % 16 (+16)][rows 4*(l/16) .. +3] of a tile) in
-    //      the activation buffer, two tiles at a time: [wave][tile of the pair][batch half][m][row]
-    {
-      float* orow0 = ored + ((wv * (4u * OPASS) + j) * NT) * 16u + i;
-      orow0[0] = oa00;
-      if (NT > 1) orow0[16] = oa01;
-      if (OPASS > 1) {
-        float* orow1 = orow0 + 4u * NT * 16u;
-        orow1[0] = oa10;
-        if (NT > 1) orow1[16] = oa11;
-      }
-    }
-#pragma unroll
-    for (uint32_t pair = 0; pair < 2; ++pair) {
-      if (pair * 2u >= Rn) break;
-      if (pair > 0) lds_barrier();  // everybody is done with the previous pair (the ranges ended with a barrier)
-      float* park = (float*)xbuf + wv * (2u * NT * 256u) + i * 16u + 4u * j;
-      *(float4_t*)(park + (0 * NT + 0) * 256) = pair == 0 ? acc00 : acc20;
-      *(float4_t*)(park + (1 * NT + 0) * 256) = pair == 0 ? acc10 : acc30;
-      if (NT > 1) {
-        *(float4_t*)(park + (0 * NT + 1) * 256) = pair == 0 ? acc01 : acc21;
-        *(float4_t*)(park + (1 * NT + 1) * 256) = pair == 0 ? acc11 : acc31;
-      }
-      lds_barrier();
-      // every output of the two tiles: outlier sum, then the W partial sums in a fixed order
-      const uint32_t tn = Rn - pair * 2u < 2u ? Rn - pair * 2u : 2u;
-      for (uint32_t o = tid; o < tn * NT * 256u; o += W * 64u) {
-        const uint32_t row = o & 15u, m = (o >> 4) & 15u, nt = (o >> 8) % NT, tp = (o >> 8) / NT, t = pair * 2u + tp;
-        float sum = ored[((t * 16u + row) * NT + nt) * 16u + m];
-        const float* pk = (const float*)xbuf + (tp * NT + nt) * 256u + m * 16u + row;
-#pragma unroll
-        for (uint32_t w2 = 0; w2 < W; ++w2) sum += pk[w2 * (2u * NT * 256u)];
-        const uint32_t grow = (grp * R + t) * 16u + row, gm = m + 16u * nt;
-        if (grow < (uint32_t)b.N && gm < (uint32_t)M) Y[(size_t)gm * b.N + grow] = half_to_bits((half_t)sum);
-      }
-    }
-    // the next group's first barrier (after its side records) separates these reads from new writes
-    // of the side records; the activation buffer is rewritten only after the barrier that opens a range
-  }
-#undef MPQ_R_REQUEST
-#undef MPQ_R_NORMALIZE
-}
-
-// ------------------------------------------------------------------------------------ slice kernel
-//
-// Y = X W^T for batches whose activations do not fit the LDS, without staging them again and again:
+// Y = X W^T for batches whose activations do not fit the LDS next to everything else (M * K * 2
+// bytes above roughly 100 KiB), with the weights read and decoded once whatever M is:
 //
 //   The code blocks of a tile are cut into H ranges in stream order (range h = an H-th of the 2-bit
 //   blocks and an H-th of the 4-bit blocks, sizes differing by at most one) and the tiles into NB
-//   bands; workgroup (h, band) gathers the activations of range h into LDS ONCE - same layout as
-//   above, slot ((unit*8 + step) * XR + m) holds the 8 fp16 values X[m][k0(unit) + 8*step ..], XR =
-//   8, 16 or 32 staged batch rows - and then walks the band's tiles, R at a time, decoding only the
+//   bands; workgroup (h, band) gathers the activations of range h into LDS ONCE, in the order the blocks use them - slot
+//   ((unit*8 + step) * XR + m) holds the 8 fp16 values X[m][k0(unit) + 8*step ..], XR = 8, 16 or 32
+//   staged batch rows, so the B operand of a step is linear in (block, unit, step) - and then walks the band's tiles, R at a time, decoding only the
 //   blocks of its range.  Its waves share those blocks round-robin, one accumulator per tile in
 //   registers; the ring of code blocks stays full from the first tile of the band to the last.
 //
@@ -1009,7 +682,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #undef MPQ_S_NORMALIZE
 }
 
-// Second step of the slice kernel: Y[m][row] = fp16(outlier product of the row (Sec. 4.3) + the
+// Second step of the large-batch kernel: Y[m][row] = fp16(outlier product of the row (Sec. 4.3) + the
 // partial sums of the ranges, in order).  One workgroup per tile.  Outliers: 16 lanes per row, each
 // takes every 16th word of the row and multiplies it with the activations of its column, which the
 // first kernel left transposed (XT[k][MP]: the MP batch values of a column are one or a few 16-byte
@@ -1453,17 +1126,13 @@ constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
 
 int g_max_blocks = 0;   // 0 = automatic
 int g_gemv_waves = 0;   // 0 = automatic (8 or 16 waves per workgroup of the GEMV)
-int g_ranges = -1;      // -1 = automatic (large-batch kernel when the activations do not fit the LDS)
-int g_range_tiles = 0;  // 0 = automatic (tiles per group of the large-batch kernel, 1..4)
-int g_range_per_cu = 0; // 0 = automatic (workgroups of the large-batch kernel per compute unit: 1 = 16 waves, 2 = 2 x 8 waves)
-int g_range_bufs = 0;   // 0 = automatic, 1 = one activation buffer, 2 = two (large-batch kernel)
 int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
 int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
-int g_slices = -1;      // -1 = automatic, 1 = slice kernel for every M > 1, 0 = never
+int g_slices = -1;      // -1 = automatic, 1 = large-batch kernel for every M > 1, 0 = never
 int g_slice_waves = 0;  // 0 = automatic (8), 16
-int g_slice_min_h = 0;  // least number of ranges of the slice kernel (tests: several ranges on small matrices)
+int g_slice_min_h = 0;  // least number of ranges of the large-batch kernel (tests: several ranges on small matrices)
 int g_slice_launches = 0;
-int g_slice_tiles = 0;  // 0 = automatic (tiles per group of the slice kernel, 1..8)
+int g_slice_tiles = 0;  // 0 = automatic (tiles per group of the large-batch kernel, 1..8)
 int g_cu_count = 0;
 
 int cu_count() {
@@ -1608,80 +1277,7 @@ mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
   return MPQ_ERR_UNSUPPORTED;
 }
 
-// Plan of the large-batch kernel for an LDS budget and W waves: tiles per group R (at most `Rwant`),
-// ranges H and the LDS layout (two activation buffers), with the fewest ranges for the largest R
-// that fits.
-bool plan_ranges(const MpqHeader& h, int NT, uint32_t W, uint32_t budget, uint32_t Rwant, bool two_bufs, RangePlan* pl) {
-  const uint32_t PD = 2, RMAX = 4;
-  const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
-  const uint32_t maxH = B2 > B4 ? (B2 > 0 ? B2 : 1) : (B4 > 0 ? B4 : 1);
-  for (uint32_t R = Rwant > RMAX ? RMAX : Rwant; R >= 1; --R) {
-    for (uint32_t H = 1; H <= maxH; ++H) {
-      const uint32_t nb2 = (B2 + H - 1) / H, nb4 = (B4 + H - 1) / H;
-      uint32_t off = W * PD * 1024;
-      pl->off_sides = off;  off += R * (uint32_t)h.side_bytes;
-      pl->off_units = off;  off += 32u * (B2 + B4);
-      pl->off_cpos = off;   off += ((2u * (((uint32_t)h.K + 63u) / 64u)) + 15u) & ~15u;
-      pl->off_splits = off; off += R * (H + 1) * 64u;
-      pl->off_ored = off;   off += RMAX * NT * 1024u;
-      off = (off + 1023u) & ~1023u;
-      pl->off_xbuf = off;
-      // two buffers (one if there is a single range); together they also hold the parked accumulators
-      const uint32_t xr = (32u * nb2 + 16u * nb4) * 256u * NT, park = W * 2u * NT * 1024u;
-      uint32_t both = H > 1 && two_bufs ? 2u * xr : xr;
-      if (both < park) both = park;
-      pl->xbuf_stride = H > 1 && two_bufs ? xr : 0;
-      off += both;
-      if (off <= budget) {
-        pl->H = (int32_t)H; pl->nb2 = (int32_t)nb2; pl->nb4 = (int32_t)nb4; pl->R = (int32_t)R;
-        return true;
-      }
-    }
-  }
-  return false;
-}
-
-// One workgroup of 16 waves per compute unit, or two of 8 waves (80 KiB each) when that does not
-// cost more ranges; tiles per group so that the groups about fill the workgroup slots.
-mpq_status launch_ranges(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
-  const int NT = M > 16 ? 2 : 1;
-  const long cus = cu_count();
-  RangePlan p2, p1;
-  // tiles per group: the R <= 4 with the shortest schedule = rounds of groups x (R tiles + the fixed
-  // cost of a group, staging and barriers, worth about one and a half tiles), the larger R on a tie
-  auto best_r = [&](long slots) {
-    uint32_t best = 1;
-    long best_span = -1;
-    for (uint32_t R = 1; R <= 4; ++R) {
-      const long groups = (h.T + R - 1) / R, span = ((groups + slots - 1) / slots) * (2 * R + 3);
-      if (best_span < 0 || span <= best_span) { best = R; best_span = span; }
-    }
-    return best;
-  };
-  uint32_t R2 = best_r(2 * cus), R1 = best_r(cus);
-  if (g_range_tiles > 0) R2 = R1 = (uint32_t)g_range_tiles;
-  const bool dbl = g_range_bufs == 2;  // one buffer and fewer, larger ranges measured faster almost everywhere
-  const bool ok2 = plan_ranges(h, NT, 8, 80 * 1024, R2, dbl, &p2);
-  const bool ok1 = plan_ranges(h, NT, 16, 160 * 1024, R1, dbl, &p1);
-  if (!ok1 && !ok2) return MPQ_ERR_UNSUPPORTED;
-  bool two = !ok1;
-  if (g_range_per_cu == 1 && ok1) two = false;
-  if (g_range_per_cu == 2 && ok2) two = true;
-  const RangePlan pl = two ? p2 : p1;
-  const long ngroups = (h.T + pl.R - 1) / pl.R;
-  long grid = cus * (two ? 2 : 1);
-  if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
-  if (grid > ngroups) grid = ngroups;
-#define MPQ_LAUNCH_R(NTV, BYTES, WV) \
-  hipLaunchKernelGGL((mpq_mmr_kernel<NTV, BYTES, WV>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M, pl)
-  if (two) { if (NT == 1) MPQ_LAUNCH_R(1, 80 * 1024, 8); else MPQ_LAUNCH_R(2, 80 * 1024, 8); }
-  else     { if (NT == 1) MPQ_LAUNCH_R(1, 160 * 1024, 16); else MPQ_LAUNCH_R(2, 160 * 1024, 16); }
-#undef MPQ_LAUNCH_R
-  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
-}
-
-// Device memory for the partial sums of the slice kernel: one grow-only buffer per (device, stream),
+// Device memory for the partial sums of the large-batch kernel: one grow-only buffer per (device, stream),
 // so that calls on different streams never share one.  Never allocates while the stream is being
 // captured into a graph; returns nullptr when nothing large enough is there and nothing can be
 // allocated (the caller then takes a kernel that needs no scratch).
@@ -1727,7 +1323,7 @@ void* scratch_get(hipStream_t s, size_t bytes) {
   return ptr;
 }
 
-// Plan of the slice kernel: staged rows XR, the fewest ranges H whose activations fit the LDS of a
+// Plan of the large-batch kernel: staged rows XR, the fewest ranges H whose activations fit the LDS of a
 // workgroup of W waves next to ring, unit table and park area, NB tile bands so that H * NB
 // workgroups about fill the compute units, groups of at most R = 8 tiles.
 bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePlan* pl, int* XR_out) {
@@ -1796,29 +1392,14 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
   while (Mc > 1 && mm_lds_bytes(h, Mc, 3) > kLdsPerCu) --Mc;
   if (Mc > 16 && Mc < M) Mc = 16;
   {
-    // The slice kernel reads and decodes the weights once whatever M is and costs about 1.25 x the
+    // The large-batch kernel reads and decodes the weights once whatever M is and costs about 1.25 x the
     // matrix-vector product plus 7 us for its second kernel; the chunked path below costs one pass
     // over the weights per chunk.  Measured on the Llama2-7B and Llama2-70B shapes, M = 2..32, the
-    // slice kernel wins from three chunks on, and with two chunks unless the matrix is small.
+    // large-batch kernel wins from three chunks on, and with two chunks unless the matrix is small.
     const int chunks = (M + Mc - 1) / Mc;
     const bool better = chunks >= 3 || (chunks == 2 && h.total_bytes >= (12u << 20));
     if (g_slices < 0 ? better : g_slices != 0) {
       const mpq_status st = launch_slices(h, d, X, Y, M, s);
-      if (st != MPQ_ERR_UNSUPPORTED) return st;
-    }
-  }
-  {
-    // The large-batch kernel reads and decodes the weights once whatever M is, but pays a chain of
-    // staging steps per tile group; measured against the chunked path on the Llama2-7B and
-    // Llama2-70B shapes it wins when the weights would be decoded three times, or when the chunked
-    // path is left with 4 waves per compute unit on a matrix with at least 2 (two chunks) or 3 (one
-    // chunk) row tiles per compute unit.
-    const int chunks = (M + Mc - 1) / Mc, cus = cu_count();
-    const int rows = (M + chunks - 1) / chunks;  // batch rows per chunk
-    const bool waves8 = mm_lds_bytes(h, rows, 2, 8) <= kLdsPerCu;
-    const bool better = chunks >= 3 || (!waves8 && h.T >= (chunks == 2 ? 2 : 3) * cus);
-    if (g_ranges < 0 ? better : g_ranges != 0) {
-      const mpq_status st = launch_ranges(h, d, X, Y, M, s);
       if (st != MPQ_ERR_UNSUPPORTED) return st;
     }
   }
@@ -1845,27 +1426,20 @@ extern "C" {
 //   2: cap on the number of persistent workgroups
 //   4: waves per workgroup of the GEMV (8, 16)          6: tiles per workgroup of the GEMV (1..8)
 //   5: waves per workgroup of the batch kernel (4, 8, 16)
-//   7: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic
-//   8: its tiles per group (1..4)   9: its workgroups per compute unit (1 = 16 waves, 2 = 2 x 8 waves)
-//  10: its activation buffers (1, 2)
-//  12: slice kernel 1 = for every M > 1, 0 = never, -1 = automatic   13: its waves per workgroup (8, 16)
+//  12: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic   13: its waves per workgroup (8, 16)
 //  14: its least number of ranges   15: its tiles per group (1..8)
 void mpq_debug_set(int key, int value) {
   if (key == 2) g_max_blocks = value;
   if (key == 4) g_gemv_waves = value;
   if (key == 5) g_batch_waves = value;
   if (key == 6) g_gemv_tiles = value;
-  if (key == 7) g_ranges = value;
-  if (key == 8) g_range_tiles = value;
-  if (key == 9) g_range_per_cu = value;
-  if (key == 10) g_range_bufs = value;
   if (key == 12) g_slices = value;
   if (key == 13) g_slice_waves = value;
   if (key == 14) g_slice_min_h = value;
   if (key == 15) g_slice_tiles = value;
 }
 
-// Counters for the tests: 12 = launches of the slice kernel so far.
+// Counters for the tests: 12 = launches of the large-batch kernel so far.
 int mpq_debug_get(int key) { return key == 12 ? g_slice_launches : 0; }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,

@@ -197,49 +197,18 @@ def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
     assert e_floor <= TOL, (e_floor, e_max)
 
 
-@pytest.mark.parametrize("per_cu", [1, 2])
-@pytest.mark.parametrize("M", [2, 7, 16, 17, 32])
-@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
-def test_large_batch_kernel_within_tolerance(torch, case, M, per_cu):
-    # the kernel that stages the activations range by range, forced for every batch size through
-    # the tuning hook, as one workgroup of 16 waves or two of 8 waves per compute unit (by itself
-    # the library takes it where the other batch kernel would decode the weights several times)
-    import ctypes
-    lg, om, pk = make(case)
-    hook = mpq.lib().mpq_debug_set
-    hook.argtypes = [ctypes.c_int, ctypes.c_int]
-    blob = to_dev(torch, pk.blob)
-    X = synth.make_x(500 + M, M, pk.K)
-    ref = om.gemm(X, threads=8)
-    print("case", case, "M", M, "per_cu", per_cu, flush=True)
-    try:
-        hook(7, 1)
-        hook(9, per_cu)
-        Y = Guarded(torch, M * pk.N)
-        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
-        got = Y.check_and_get().reshape(M, pk.N)
-        Y2 = Guarded(torch, M * pk.N)
-        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M)
-        again = Y2.check_and_get().reshape(M, pk.N)
-    finally:
-        hook(7, -1)
-        hook(9, 0)
-    e_floor, e_max = rel_err(got, ref)
-    assert e_floor <= TOL, (e_floor, e_max)
-    assert np.array_equal(got, again)
-
-
 SLICE_CASES = [c for c in CASES if c[3] >= 64]   # the kernel gathers whole units: g1 >= 64
 
 
 @pytest.mark.parametrize("waves,min_h", [(16, 0), (8, 0), (16, 3)])
 @pytest.mark.parametrize("M", [2, 7, 8, 9, 16, 17, 32])
 @pytest.mark.parametrize("case", SLICE_CASES, ids=[c[0] for c in SLICE_CASES])
-def test_slice_kernel_within_tolerance(torch, case, M, waves, min_h):
+def test_large_batch_kernel_within_tolerance(torch, case, M, waves, min_h):
     # the kernel that keeps one K-range of the activations resident per workgroup and writes partial
-    # sums that a second kernel adds up, forced for every batch size through the tuning hook; with 16
-    # or 8 waves per workgroup, and with at least three ranges also on matrices whose activations
-    # would fit at once
+    # sums that a second kernel adds up, forced for every batch size through the tuning hook (by
+    # itself the library takes it where the other batch kernel would decode the weights several
+    # times); with 16 or 8 waves per workgroup, and with at least three ranges also on matrices
+    # whose activations would fit at once
     import ctypes
     lg, om, pk = make(case)
     hook, count = mpq.lib().mpq_debug_set, mpq.lib().mpq_debug_get
@@ -264,10 +233,56 @@ def test_slice_kernel_within_tolerance(torch, case, M, waves, min_h):
         hook(12, -1)
         hook(13, 0)
         hook(14, 0)
-    assert count(12) == before + 2, "the slice kernel did not run"
+    assert count(12) == before + 2, "the large-batch kernel did not run"
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (e_floor, e_max)
     assert np.array_equal(got, again)
+
+
+def test_large_batch_kernel_in_a_graph(torch):
+    # the large-batch kernel needs device scratch, which the library allocates per (device, stream) at
+    # an eager call and never while the stream is captured: a capture on a stream that has scratch
+    # records the kernel and every replay reproduces the eager result; a capture on a stream without
+    # scratch records the other batch kernel instead, and still gives the right product
+    import ctypes
+    lg, om, pk = make(CASES[6])
+    M = 16
+    hook, count = mpq.lib().mpq_debug_set, mpq.lib().mpq_debug_get
+    hook.argtypes = [ctypes.c_int, ctypes.c_int]
+    count.argtypes, count.restype = [ctypes.c_int], ctypes.c_int
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(900, M, pk.K)
+    Xd = to_dev(torch, X.view(np.int16))
+    ref = om.gemm(X, threads=8)
+    warm, cold = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        hook(12, 1)
+        Y = Guarded(torch, M * pk.N)
+        torch.cuda.synchronize()
+        mpq.gemm(pk.header, blob, Xd, Y.view, M, stream=warm)
+        warm.synchronize()
+        eager = Y.check_and_get().reshape(M, pk.N)
+        assert rel_err(eager, ref)[0] <= TOL
+        for stream, uses_scratch in ((warm, True), (cold, False)):
+            Yg = Guarded(torch, M * pk.N)
+            torch.cuda.synchronize()
+            before = count(12)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                mpq.gemm(pk.header, blob, Xd, Yg.view, M, stream=stream)
+            assert (count(12) == before + 1) == uses_scratch
+            for rep in range(3):
+                Yg.view.zero_()
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                got = Yg.check_and_get().reshape(M, pk.N)
+                if uses_scratch:
+                    assert np.array_equal(got, eager), rep
+                else:
+                    assert rel_err(got, ref)[0] <= TOL, rep
+    finally:
+        hook(12, -1)
 
 
 def test_several_products_in_one_launch(torch):
