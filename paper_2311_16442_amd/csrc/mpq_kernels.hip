@@ -526,16 +526,24 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   //      consumption below follows, restricted to every W-th block
   const uint32_t ring0 = lds_addr(lds) + wv * (PD * SLOTB);
   const uint32_t m2lane = b.off_m2 + (i >> b.m2_shift) * 4u;
-  uint32_t r_g = 0, r_t = 0, r_c = wv;
-  uint32_t r_first = 0, r_Rn = ngroups > 0 ? ntl / ngroups : 0;  // group g = tiles [g*ntl/ngroups, (g+1)*ntl/ngroups)
+  // Work split inside a group of Rn tiles: the Rn * len blocks in the order (position in the
+  // range, tile) are cut into W equal pieces, one per wave.  Consecutive blocks of a wave are the
+  // same position of consecutive tiles, which need the same activations: the B operands of a
+  // position are read from LDS once and stay in registers for all of its tiles.
+  uint32_t r_g = 0, r_s = 0, r_hi = 0, r_c = 0, r_t = 0, r_first = 0, r_Rn = 1;
+#define MPQ_S_GROUP(G, FIRST, RN, LO, HI)                                               \
+  {                                                                                     \
+    FIRST = (G) * ntl / ngroups;                                                        \
+    RN = ((G) + 1) * ntl / ngroups - FIRST;                                             \
+    LO = wv * (RN * len) / W;                                                           \
+    HI = (wv + 1) * (RN * len) / W;                                                     \
+  }
 #define MPQ_S_NORMALIZE                                                                 \
-  while (r_g < ngroups && r_c >= len) {                                                 \
-    r_c -= len;                                                                         \
-    if (++r_t == r_Rn) {                                                                \
-      r_t = 0;                                                                          \
-      ++r_g;                                                                            \
-      r_first = r_g * ntl / ngroups;                                                    \
-      r_Rn = (r_g + 1) * ntl / ngroups - r_first;                                       \
+  while (r_g < ngroups && r_s >= r_hi) {                                                \
+    if (++r_g < ngroups) {                                                              \
+      MPQ_S_GROUP(r_g, r_first, r_Rn, r_s, r_hi)                                        \
+      r_c = r_s / r_Rn;                                                                 \
+      r_t = r_s % r_Rn;                                                                 \
     }                                                                                   \
   }
 #define MPQ_S_REQUEST(SLOT)                                                             \
@@ -548,8 +556,14 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
     dma4(tb, ((uy & 0xFFFFu) + i * 2u) & ~3u, dst + 1024u);                             \
     dma4(tb, m2lane + (uy >> 16), dst + 1280u);                                         \
     ++inflight;                                                                         \
-    r_c += W;                                                                           \
+    ++r_s;                                                                              \
+    if (++r_t == r_Rn) { r_t = 0; ++r_c; }                                              \
     MPQ_S_NORMALIZE                                                                     \
+  }
+  if (ngroups > 0) {
+    MPQ_S_GROUP(0u, r_first, r_Rn, r_s, r_hi)
+    r_c = r_s / r_Rn;
+    r_t = r_s % r_Rn;
   }
   uint32_t inflight = 0;
   MPQ_S_NORMALIZE
@@ -590,19 +604,16 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   const uint32_t slot_lane = ring0 + lane16, meta_lane = ring0 + 1024u + lane * 4u;
   const unsigned char* xb2 = xbuf + j * (8u * XR * 16u) + (i % XR) * 16u;                        // + block * 512 * XR + step * 16 * XR
   const unsigned char* xb4 = xbuf + n2 * (512u * XR) + j * (4u * XR * 16u) + (i % XR) * 16u;      // + block * 256 * XR + step * 16 * XR
-  uint32_t slot = 0, c = wv;
+  uint32_t slot = 0;
 
 #define MPQ_S_STEP(TWO, P, A0, A1)                                                                   \
   {                                                                                                   \
     const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
-    const uint4 bv0 = *(const uint4*)(xb0 + (P) * (16 * XR));                                         \
     A0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                      \
-                                                __builtin_bit_cast(half8_t, bv0), A0, 0, 0, 0);       \
-    if (NT > 1) {                                                                                     \
-      const uint4 bv1 = *(const uint4*)(xb0 + (P) * (16 * XR) + 256);                                 \
+                                                __builtin_bit_cast(half8_t, bx[P][0]), A0, 0, 0, 0);  \
+    if (NT > 1)                                                                                       \
       A1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
-                                                  __builtin_bit_cast(half8_t, bv1), A1, 0, 0, 0);     \
-    }                                                                                                 \
+                                                  __builtin_bit_cast(half8_t, bx[P][NT - 1]), A1, 0, 0, 0); \
   }
 #define MPQ_S_HEAD                                                                                     \
   if (inflight == PD) MPQ_VMCNT(3 * (PD - 1));                                                        \
@@ -621,31 +632,56 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   const half2_t s1p = {s1, s1};                                                                       \
   const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                    \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-#define MPQ_S_TILE(TT, A0, A1)                                                                         \
-  if ((TT) < Rn) {                                                                                    \
-    for (; c < n2; c += W) {                                                                          \
-      MPQ_S_HEAD                                                                                      \
-      const unsigned char* xb0 = xb2 + c * (512u * XR);                                               \
-      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};                            \
-      MPQ_S_STEP(true, 0, A0, A1) MPQ_S_STEP(true, 1, A0, A1) MPQ_S_STEP(true, 2, A0, A1) MPQ_S_STEP(true, 3, A0, A1) \
-      MPQ_S_STEP(true, 4, A0, A1) MPQ_S_STEP(true, 5, A0, A1) MPQ_S_STEP(true, 6, A0, A1) MPQ_S_STEP(true, 7, A0, A1) \
-    }                                                                                                 \
-    for (; c < len; c += W) {                                                                         \
-      MPQ_S_HEAD                                                                                      \
-      const unsigned char* xb0 = xb4 + (c - n2) * (256u * XR);                                        \
-      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};                                \
-      MPQ_S_STEP(false, 0, A0, A1) MPQ_S_STEP(false, 1, A0, A1) MPQ_S_STEP(false, 2, A0, A1) MPQ_S_STEP(false, 3, A0, A1) \
-    }                                                                                                 \
-    c -= len;                                                                                         \
-  }
 
   for (uint32_t g = 0; g < ngroups; ++g) {
-    const uint32_t first = g * ntl / ngroups, Rn = (g + 1) * ntl / ngroups - first;
+    uint32_t first, Rn, s_at, s_hi;
+    MPQ_S_GROUP(g, first, Rn, s_at, s_hi)
     float4_t acc[RMAX][2];
 #pragma unroll
     for (uint32_t tt = 0; tt < RMAX; ++tt) acc[tt][0] = acc[tt][1] = float4_t{0.f, 0.f, 0.f, 0.f};
+    uint32_t c = s_at / Rn, t = s_at % Rn;
+    while (s_at < s_hi) {
+      const uint32_t t_end = s_hi - s_at < Rn - t ? t + (s_hi - s_at) : Rn;  // tiles [t, t_end) of position c
+      uint4 bx[8][NT];
+      if (c < n2) {
+        const unsigned char* xb0 = xb2 + c * (512u * XR);
 #pragma unroll
-    for (uint32_t tt = 0; tt < RMAX; ++tt) MPQ_S_TILE(tt, acc[tt][0], acc[tt][1])
+        for (uint32_t P = 0; P < 8; ++P) {
+          bx[P][0] = *(const uint4*)(xb0 + P * (16 * XR));
+          if (NT > 1) bx[P][NT - 1] = *(const uint4*)(xb0 + P * (16 * XR) + 256);
+        }
+#pragma unroll
+        for (uint32_t tt = 0; tt < RMAX; ++tt) {
+          if (tt >= t && tt < t_end) {
+            MPQ_S_HEAD
+            const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+            MPQ_S_STEP(true, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 1, acc[tt][0], acc[tt][1])
+            MPQ_S_STEP(true, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 3, acc[tt][0], acc[tt][1])
+            MPQ_S_STEP(true, 4, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 5, acc[tt][0], acc[tt][1])
+            MPQ_S_STEP(true, 6, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 7, acc[tt][0], acc[tt][1])
+          }
+        }
+      } else {
+        const unsigned char* xb0 = xb4 + (c - n2) * (256u * XR);
+#pragma unroll
+        for (uint32_t P = 0; P < 4; ++P) {
+          bx[P][0] = *(const uint4*)(xb0 + P * (16 * XR));
+          if (NT > 1) bx[P][NT - 1] = *(const uint4*)(xb0 + P * (16 * XR) + 256);
+        }
+#pragma unroll
+        for (uint32_t tt = 0; tt < RMAX; ++tt) {
+          if (tt >= t && tt < t_end) {
+            MPQ_S_HEAD
+            const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+            MPQ_S_STEP(false, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(false, 1, acc[tt][0], acc[tt][1])
+            MPQ_S_STEP(false, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(false, 3, acc[tt][0], acc[tt][1])
+          }
+        }
+      }
+      s_at += t_end - t;
+      t = 0;
+      ++c;
+    }
 
     // ---- park the accumulators (lane l holds Y[m = l % 16 (+16)][rows 4*(l/16) .. +3] of a tile), TP
     //      tiles at a time: [wave][tile of the step][batch half][m][row]; then every output of those
@@ -675,11 +711,11 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
       }
     }
   }
-#undef MPQ_S_TILE
 #undef MPQ_S_HEAD
 #undef MPQ_S_STEP
 #undef MPQ_S_REQUEST
 #undef MPQ_S_NORMALIZE
+#undef MPQ_S_GROUP
 }
 
 // Second step of the large-batch kernel: Y[m][row] = fp16(outlier product of the row (Sec. 4.3) + the
@@ -1357,9 +1393,11 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
   SlicePlan pl;
   int XR = 0;
-  const bool w8 = g_slice_waves != 16;  // 8 waves leave more LDS for the activations: faster on every shape measured
-  if (!plan_slices(h, M, w8 ? 8 : 16, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   const int NT = M > 16 ? 2 : 1;
+  // 8 waves leave more LDS for the activations and 256 registers per lane (two batch halves need
+  // them): faster on every shape measured; 16 waves are kept for M <= 16 behind the tuning hook
+  const bool w8 = g_slice_waves != 16 || NT == 2;
+  if (!plan_slices(h, M, w8 ? 8 : 16, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   // scratch: partial sums P[H][T][16 NT][16] fp32, then the transposed activations XT[K][XR] fp16
   const size_t p_bytes = ((size_t)pl.H * (size_t)h.T * NT * 256 * sizeof(float) + 255) & ~(size_t)255;
   const size_t bytes = p_bytes + (size_t)h.K * XR * sizeof(uint16_t);
@@ -1373,7 +1411,7 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   if (w8) {
     if (XR == 8) MPQ_LAUNCH_S(1, 8, 8); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8); else MPQ_LAUNCH_S(2, 32, 8);
   } else {
-    if (XR == 8) MPQ_LAUNCH_S(1, 8, 16); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 16); else MPQ_LAUNCH_S(2, 32, 16);
+    if (XR == 8) MPQ_LAUNCH_S(1, 8, 16); else MPQ_LAUNCH_S(1, 16, 16);
   }
 #undef MPQ_LAUNCH_S
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
