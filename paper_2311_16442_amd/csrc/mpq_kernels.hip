@@ -1430,12 +1430,15 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
   while (Mc > 1 && mm_lds_bytes(h, Mc, 3) > kLdsPerCu) --Mc;
   if (Mc > 16 && Mc < M) Mc = 16;
   {
-    // The large-batch kernel reads and decodes the weights once whatever M is and costs about 1.25 x the
-    // matrix-vector product plus 7 us for its second kernel; the chunked path below costs one pass
-    // over the weights per chunk.  Measured on the Llama2-7B and Llama2-70B shapes, M = 2..32, the
-    // large-batch kernel wins from three chunks on, and with two chunks unless the matrix is small.
+    // The large-batch kernel reads and decodes the weights once whatever M is and costs about 1.25 x
+    // the matrix-vector product plus 4-12 us for its second kernel; the chunked path below costs one
+    // pass over the weights per chunk and a per-column outlier loop that weighs from M = 9 on.
+    // Measured on the Llama2-7B and Llama2-70B shapes, M = 2..32, outlier fractions 0 / 0.5 / 1.5 %:
+    // up to M = 8 the large-batch kernel wins from three chunks on, and with two chunks unless the
+    // matrix is small; above, whenever there are two chunks or the matrix is not small.
     const int chunks = (M + Mc - 1) / Mc;
-    const bool better = chunks >= 3 || (chunks == 2 && h.total_bytes >= (12u << 20));
+    const bool large = h.total_bytes >= (12u << 20);
+    const bool better = M <= 8 ? chunks >= 3 || (chunks == 2 && large) : chunks >= 2 || large;
     if (g_slices < 0 ? better : g_slices != 0) {
       const mpq_status st = launch_slices(h, d, X, Y, M, s);
       if (st != MPQ_ERR_UNSUPPORTED) return st;
