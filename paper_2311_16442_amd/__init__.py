@@ -60,6 +60,14 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # PyTorch ships its own copy of the HIP runtime.  The caller's device memory and streams come
+        # from that copy, so it has to be the one this library binds to: load torch first (a library
+        # loaded before torch would pull in the system's runtime, and launches on torch's streams
+        # through a second runtime fail).
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         L.mpq_status_str.restype = C.c_char_p
         L.mpq_status_str.argtypes = [C.c_int]
