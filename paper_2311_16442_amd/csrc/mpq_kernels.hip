@@ -460,6 +460,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 //   and rounds to fp16: results are bit-identical from run to run.
 struct SlicePlan {
   int32_t H, NB, R;
+  uint32_t older16;  // sixteenths of a SIMD's blocks that go to the older of its two waves
   uint32_t off_units, off_park, off_xbuf;  // LDS byte offsets (ring at 0)
 };
 
@@ -535,8 +536,18 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   {                                                                                     \
     FIRST = (G) * ntl / ngroups;                                                        \
     RN = ((G) + 1) * ntl / ngroups - FIRST;                                             \
-    LO = wv * (RN * len) / W;                                                           \
-    HI = (wv + 1) * (RN * len) / W;                                                     \
+    if (W == 8) {                                                                       \
+      /* waves w and w + 4 share a SIMD and a quarter of the blocks.  The issue arbitration prefers \
+         the older wave: with equal shares it is done a quarter earlier and the SIMD runs the rest  \
+         of the group with one wave (timestamps); 10/16 : 6/16 measured best (4-6 % over 8 : 8) */    \
+      const uint32_t S_ = RN * len, qlo = (wv & 3u) * S_ / 4u, qhi = ((wv & 3u) + 1u) * S_ / 4u; \
+      const uint32_t mid = qlo + (qhi - qlo) * pl.older16 / 16u;                        \
+      LO = wv < 4u ? qlo : mid;                                                         \
+      HI = wv < 4u ? mid : qhi;                                                         \
+    } else {                                                                            \
+      LO = wv * (RN * len) / W;                                                         \
+      HI = (wv + 1) * (RN * len) / W;                                                   \
+    }                                                                                   \
   }
 #define MPQ_S_NORMALIZE                                                                 \
   while (r_g < ngroups && r_s >= r_hi) {                                                \
@@ -1168,6 +1179,7 @@ int g_slices = -1;      // -1 = automatic, 1 = large-batch kernel for every M > 
 int g_slice_waves = 0;  // 0 = automatic (8), 16
 int g_slice_min_h = 0;  // least number of ranges of the large-batch kernel (tests: several ranges on small matrices)
 int g_slice_launches = 0;
+int g_slice_older = 0;  // 0 = automatic (10): sixteenths of a SIMD's blocks that go to the older of its two waves
 int g_slice_tiles = 0;  // 0 = automatic (tiles per group of the large-batch kernel, 1..8)
 int g_cu_count = 0;
 
@@ -1381,6 +1393,7 @@ bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePl
     uint32_t NB = cus / H;
     if (NB > (uint32_t)h.T) NB = (uint32_t)h.T;
     pl->H = (int32_t)H;
+    pl->older16 = g_slice_older > 0 && g_slice_older < 16 ? (uint32_t)g_slice_older : 10u;
     pl->NB = (int32_t)NB;
     pl->R = g_slice_tiles > 0 && g_slice_tiles <= 8 ? g_slice_tiles : 8;
     *XR_out = (int)XR;
@@ -1469,6 +1482,7 @@ extern "C" {
 //   5: waves per workgroup of the batch kernel (4, 8, 16)
 //  12: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic   13: its waves per workgroup (8, 16)
 //  14: its least number of ranges   15: its tiles per group (1..8)
+//  18: sixteenths of a SIMD's blocks that go to the older of its two waves (1..15)
 void mpq_debug_set(int key, int value) {
   if (key == 2) g_max_blocks = value;
   if (key == 4) g_gemv_waves = value;
@@ -1478,6 +1492,7 @@ void mpq_debug_set(int key, int value) {
   if (key == 13) g_slice_waves = value;
   if (key == 14) g_slice_min_h = value;
   if (key == 15) g_slice_tiles = value;
+  if (key == 18) g_slice_older = value;
 }
 
 // Counters for the tests: 12 = launches of the large-batch kernel so far.
