@@ -443,11 +443,15 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 //
 //   The code blocks of a tile are cut into H ranges in stream order (range h = an H-th of the 2-bit
 //   blocks and an H-th of the 4-bit blocks, sizes differing by at most one) and the tiles into NB
-//   bands; workgroup (h, band) gathers the activations of range h into LDS ONCE, in the order the blocks use them - slot
-//   ((unit*8 + step) * XR + m) holds the 8 fp16 values X[m][k0(unit) + 8*step ..], XR = 8, 16 or 32
-//   staged batch rows, so the B operand of a step is linear in (block, unit, step) - and then walks the band's tiles, R at a time, decoding only the
-//   blocks of its range.  Its waves share those blocks round-robin, one accumulator per tile in
-//   registers; the ring of code blocks stays full from the first tile of the band to the last.
+//   bands.  Workgroup (h, band) gathers the activations of range h into LDS ONCE, in the order the
+//   blocks use them: slot ((unit*8 + step) * XR + m) holds the 8 fp16 values
+//   X[m][k0(unit) + 8*step ..], XR = 8, 16 or 32 staged batch rows, so the B operand of a step is
+//   linear in (block, unit, step).  It then walks the band's tiles in groups of up to R = 8,
+//   decoding only the blocks of its range.  The blocks of a group, in the order (position in the
+//   range, tile), are split between the waves in contiguous pieces, so that a wave reads the B
+//   operands of a position from LDS once for all tiles of the group; it keeps one accumulator per
+//   tile in registers.  The ring of code blocks stays full from the first tile of the band to the
+//   last.
 //
 //   The first-order (s_int, z1) and second-order (s2, z2) words of a block travel with it: three
 //   direct loads per block (1 KiB of codes, then one dword per lane that holds the lane's meta1
