@@ -473,14 +473,49 @@ __device__ __forceinline__ void dma4(const unsigned char* gbase, uint32_t voff, 
                : "memory");
 }
 
-template <int NT, int XR, int LDSB, int WV>
+// Reads a ring slot of the large-batch kernel: the 16 bytes of codes of the lane and the first NP of
+// its PUV (meta1, meta2) dword pairs, which sit at byte 1024 + 256 q and 1024 + 256 (PUV + q) of the
+// slot.  Reads and wait are ONE asm statement: anything the compiler places between a read and the
+// wait (a register copy, say) would see the register before the data has arrived.
+template <int NP, int PUV>
+__device__ __forceinline__ void ring_read(uint32_t code_addr, uint32_t meta_addr, uint4& q, uint32_t (&w1)[NP],
+                                          uint32_t (&w2)[NP]) {
+  static_assert(NP == 1 || NP == 2 || NP == 4, "pieces per unit");
+  constexpr int O2 = 256 * PUV;  // meta2 words follow the PUV meta1 words
+  if constexpr (NP == 1) {
+    asm volatile("ds_read_b128 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %4 offset:%5\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(q), "=&v"(w1[0]), "=&v"(w2[0])
+                 : "v"(code_addr), "v"(meta_addr), "i"(O2)
+                 : "memory");
+  } else if constexpr (NP == 2) {
+    asm volatile("ds_read_b128 %0, %5\n\tds_read_b32 %1, %6\n\tds_read_b32 %2, %6 offset:256\n\t"
+                 "ds_read_b32 %3, %6 offset:%7\n\tds_read_b32 %4, %6 offset:%8\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(q), "=&v"(w1[0]), "=&v"(w1[1]), "=&v"(w2[0]), "=&v"(w2[1])
+                 : "v"(code_addr), "v"(meta_addr), "i"(O2), "i"(O2 + 256)
+                 : "memory");
+  } else {
+    asm volatile("ds_read_b128 %0, %9\n\tds_read_b32 %1, %10\n\tds_read_b32 %2, %10 offset:256\n\t"
+                 "ds_read_b32 %3, %10 offset:512\n\tds_read_b32 %4, %10 offset:768\n\t"
+                 "ds_read_b32 %5, %10 offset:%11\n\tds_read_b32 %6, %10 offset:%12\n\t"
+                 "ds_read_b32 %7, %10 offset:%13\n\tds_read_b32 %8, %10 offset:%14\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(q), "=&v"(w1[0]), "=&v"(w1[1]), "=&v"(w1[2]), "=&v"(w1[3]), "=&v"(w2[0]), "=&v"(w2[1]),
+                   "=&v"(w2[2]), "=&v"(w2[3])
+                 : "v"(code_addr), "v"(meta_addr), "i"(O2), "i"(O2 + 256), "i"(O2 + 512), "i"(O2 + 768)
+                 : "memory");
+  }
+}
+
+template <int NT, int XR, int LDSB, int WV, int PU>
 __global__ void __launch_bounds__(WV * 64)
 mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restrict__ P, uint16_t* __restrict__ XT,
                const int M, const SlicePlan pl) {
 #pragma clang fp contract(off)
   static_assert(WV == 8 || WV == 16, "waves");
   static_assert(XR == 8 || XR == 16 * NT, "staged rows");
-  constexpr uint32_t W = WV, PD = 2, SLOTB = 1536, RMAX = 8;
+  constexpr uint32_t W = WV, PD = 2, RMAX = 8;
+  constexpr int PU4 = PU > 1 ? PU / 2 : 1;            // pieces per 2-bit unit (PU) and per 4-bit unit
+  constexpr uint32_t SLOTB = 1024 + 512 * PU;          // ring slot: codes | PU meta1 dwords per lane | PU meta2 dwords per lane
+  constexpr uint32_t OPS = 1 + 2 * PU;                 // direct loads per block
   constexpr uint32_t TP = 2 / NT;  // tiles parked at a time (2 KiB per wave)
   __shared__ __align__(16) unsigned char lds[LDSB];
   const uint32_t tid = threadIdx.x;
@@ -500,7 +535,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   const DecodeConsts kc = make_consts();
 
   // ---- once per workgroup: unit table
-  dma_linear<W>(b.units, lds_addr(units), 32u * C, wv, lane16);
+  dma_linear<W>(b.units, lds_addr(units), 32u * PU * C, wv, lane16);
   MPQ_VMCNT(0);
   lds_barrier();
 
@@ -521,8 +556,10 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
         m = s4 % XR;
       }
       if (s < slots && m < (uint32_t)M) {
-        const uint32_t k0x2 = *(const uint32_t*)(units + unit * 8u);
-        dma16((const unsigned char*)X, m * 2u * (uint32_t)b.K + k0x2 + step * 16u, lds_addr(xbuf) + s0 * 16u);
+        // the piece (first-order group) of the unit that the step belongs to, and the step inside it
+        const uint32_t spp = s < slots2 ? 8u / PU : 4u / PU4, piece = step / spp, sub = step % spp;
+        const uint32_t k0x2 = *(const uint32_t*)(units + (unit * PU + piece) * 8u);
+        dma16((const unsigned char*)X, m * 2u * (uint32_t)b.K + k0x2 + sub * 16u, lds_addr(xbuf) + s0 * 16u);
       }
     }
   }
@@ -565,11 +602,15 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   {                                                                                     \
     const uint32_t blk = r_c < n2 ? a2 + r_c : B2 + a4 + (r_c - n2);                    \
     const unsigned char* tb = b.tiles + (size_t)(t0 + r_first + r_t) * b.tile_stride;   \
-    const uint32_t uy = *(const uint32_t*)(units + (blk * 4u + j) * 8u + 4u);           \
     const uint32_t dst = ring0 + (SLOT) * SLOTB;                                        \
     dma16(tb + b.codes_off + blk * 1024u, lane16, dst);                                 \
-    dma4(tb, ((uy & 0xFFFFu) + i * 2u) & ~3u, dst + 1024u);                             \
-    dma4(tb, m2lane + (uy >> 16), dst + 1280u);                                         \
+    /* the meta words of all PU piece slots of the lane's unit (a 4-bit unit uses the first PU4; the \
+       others are padding entries that point at the zero words of the tile) */          \
+    _Pragma("unroll") for (uint32_t qq = 0; qq < (uint32_t)PU; ++qq) {                  \
+      const uint32_t uy = *(const uint32_t*)(units + ((blk * 4u + j) * PU + qq) * 8u + 4u); \
+      dma4(tb, ((uy & 0xFFFFu) + i * 2u) & ~3u, dst + 1024u + qq * 256u);               \
+      dma4(tb, m2lane + (uy >> 16), dst + 1024u + PU * 256u + qq * 256u);               \
+    }                                                                                   \
     ++inflight;                                                                         \
     ++r_s;                                                                              \
     if (++r_t == r_Rn) { r_t = 0; ++r_c; }                                              \
@@ -586,7 +627,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   for (uint32_t r = 0; r < PD; ++r)
     if (r_g < ngroups) MPQ_S_REQUEST(r)
   // the activations were requested first: they have landed when at most the block requests are left
-  wait_vm((int)(3u * inflight));
+  wait_vm((int)(OPS * inflight));
   lds_barrier();
 
   // ---- this workgroup's share of the transposed activations XT[k][XR] that the second kernel
@@ -605,7 +646,8 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
       }
       const uint32_t m = s % XR;
       if (m < (uint32_t)M) {
-        const uint32_t k = (*(const uint32_t*)(units + unit * 8u) >> 1) + step * 8u;
+        const uint32_t spp = s < slots2 ? 8u / PU : 4u / PU4, piece = step / spp, sub = step % spp;
+        const uint32_t k = (*(const uint32_t*)(units + (unit * PU + piece) * 8u) >> 1) + sub * 8u;
         const uint4 v = *(const uint4*)(xbuf + s * 16u);
         uint16_t* at = XT + (size_t)k * XR + m;
         at[0 * XR] = (uint16_t)v.x; at[1 * XR] = (uint16_t)(v.x >> 16);
@@ -623,29 +665,33 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 
 #define MPQ_S_STEP(TWO, P, A0, A1)                                                                   \
   {                                                                                                   \
-    const uint4 av = decode_step<TWO, P>(lo, hi, s1p, zb, kc);                                        \
+    constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                          \
+    const uint4 av = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                                  \
     A0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                      \
                                                 __builtin_bit_cast(half8_t, bx[P][0]), A0, 0, 0, 0);  \
     if (NT > 1)                                                                                       \
       A1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
                                                   __builtin_bit_cast(half8_t, bx[P][NT - 1]), A1, 0, 0, 0); \
   }
-#define MPQ_S_HEAD                                                                                     \
-  if (inflight == PD) MPQ_VMCNT(3 * (PD - 1));                                                        \
+// Fetch of the wave's next block: wait for it, read codes and the NP meta word pairs from its ring
+// slot, refill the slot, reconstruct (s1, z1) of every piece.
+#define MPQ_S_HEAD(NP)                                                                                 \
+  if (inflight == PD) MPQ_VMCNT(OPS * (PD - 1));                                                      \
   else MPQ_VMCNT(0); /* PD = 2: nothing else of this wave can be in flight */                         \
   uint4 q;                                                                                            \
-  uint32_t w1, w2;                                                                                    \
-  asm volatile("ds_read_b128 %0, %3\n\tds_read_b32 %1, %4\n\tds_read_b32 %2, %4 offset:256\n\ts_waitcnt lgkmcnt(0)" \
-               : "=&v"(q), "=&v"(w1), "=&v"(w2)                                                       \
-               : "v"(slot_lane + slot * SLOTB), "v"(meta_lane + slot * SLOTB)                         \
-               : "memory");                                                                           \
+  uint32_t w1[NP], w2[NP];                                                                            \
+  ring_read<NP, PU>(slot_lane + slot * SLOTB, meta_lane + slot * SLOTB, q, w1, w2);                   \
   --inflight;                                                                                         \
   if (r_g < ngroups) MPQ_S_REQUEST(slot)                                                              \
   slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
-  const uint32_t m1 = (i & 1u) ? w1 >> 16 : w1 & 0xFFFFu;                                             \
-  const half_t s1 = scale_dequant(m1 & 0xFFu, w2);                                                    \
-  const half2_t s1p = {s1, s1};                                                                       \
-  const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                    \
+  half2_t s1p[NP];                                                                                    \
+  half_t zb[NP];                                                                                      \
+  _Pragma("unroll") for (int qq = 0; qq < NP; ++qq) {                                                 \
+    const uint32_t m1 = (i & 1u) ? w1[qq] >> 16 : w1[qq] & 0xFFFFu;                                   \
+    const half_t s1 = scale_dequant(m1 & 0xFFu, w2[qq]);  /* exactly 0 for a padding piece */          \
+    s1p[qq] = half2_t{s1, s1};                                                                        \
+    zb[qq] = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                           \
+  }                                                                                                   \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
 
   for (uint32_t g = 0; g < ngroups; ++g) {
@@ -668,7 +714,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #pragma unroll
         for (uint32_t tt = 0; tt < RMAX; ++tt) {
           if (tt >= t && tt < t_end) {
-            MPQ_S_HEAD
+            MPQ_S_HEAD(PU)
             const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
             MPQ_S_STEP(true, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 1, acc[tt][0], acc[tt][1])
             MPQ_S_STEP(true, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 3, acc[tt][0], acc[tt][1])
@@ -686,7 +732,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #pragma unroll
         for (uint32_t tt = 0; tt < RMAX; ++tt) {
           if (tt >= t && tt < t_end) {
-            MPQ_S_HEAD
+            MPQ_S_HEAD(PU4)
             const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
             MPQ_S_STEP(false, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(false, 1, acc[tt][0], acc[tt][1])
             MPQ_S_STEP(false, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(false, 3, acc[tt][0], acc[tt][1])
@@ -1379,12 +1425,13 @@ void* scratch_get(hipStream_t s, size_t bytes) {
 // workgroup of W waves next to ring, unit table and park area, NB tile bands so that H * NB
 // workgroups about fill the compute units, groups of at most R = 8 tiles.
 bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePlan* pl, int* XR_out) {
+  const uint32_t PU = (uint32_t)mpq_pu2(h.g1);
   const uint32_t NT = M > 16 ? 2 : 1, XR = M <= 8 ? 8 : 16 * NT;
   const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
   const uint32_t maxH = B2 > B4 ? B2 : B4;
   const uint32_t cus = (uint32_t)cu_count();
-  uint32_t off = W * 2u * 1536u;
-  pl->off_units = off; off += (32u * (B2 + B4) + 15u) & ~15u;
+  uint32_t off = W * 2u * (1024u + 512u * PU);
+  pl->off_units = off; off += (32u * PU * (B2 + B4) + 15u) & ~15u;
   pl->off_park = off;  off += W * 2048u;
   off = (off + 1023u) & ~1023u;
   pl->off_xbuf = off;
@@ -1407,13 +1454,13 @@ bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePl
 }
 
 mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
-  if (mpq_pu2(h.g1) > 1) return MPQ_ERR_UNSUPPORTED;  // the staging gathers whole units
   SlicePlan pl;
   int XR = 0;
   const int NT = M > 16 ? 2 : 1;
   // 8 waves leave more LDS for the activations and 256 registers per lane (two batch halves need
   // them): faster on every shape measured; 16 waves are kept for M <= 16 behind the tuning hook
-  const bool w8 = g_slice_waves != 16 || NT == 2;
+  const int pu = mpq_pu2(h.g1);
+  const bool w8 = g_slice_waves != 16 || NT == 2 || pu > 1;
   if (!plan_slices(h, M, w8 ? 8 : 16, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   // scratch: partial sums P[H][T][16 NT][16] fp32, then the transposed activations XT[K][XR] fp16
   const size_t p_bytes = ((size_t)pl.H * (size_t)h.T * NT * 256 * sizeof(float) + 255) & ~(size_t)255;
@@ -1423,13 +1470,16 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   float* P = (float*)scratch;
   uint16_t* XT = (uint16_t*)(scratch + p_bytes);
   const dim3 grid((unsigned)(pl.H * pl.NB));
-#define MPQ_LAUNCH_S(NTV, XRV, WV) \
-  hipLaunchKernelGGL((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
+#define MPQ_LAUNCH_S(NTV, XRV, WV, PUV) \
+  hipLaunchKernelGGL((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV, PUV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
+#define MPQ_LAUNCH_S8(PUV) \
+  { if (XR == 8) MPQ_LAUNCH_S(1, 8, 8, PUV); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8, PUV); else MPQ_LAUNCH_S(2, 32, 8, PUV); }
   if (w8) {
-    if (XR == 8) MPQ_LAUNCH_S(1, 8, 8); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8); else MPQ_LAUNCH_S(2, 32, 8);
+    if (pu == 1) MPQ_LAUNCH_S8(1) else if (pu == 2) MPQ_LAUNCH_S8(2) else MPQ_LAUNCH_S8(4)
   } else {
-    if (XR == 8) MPQ_LAUNCH_S(1, 8, 16); else MPQ_LAUNCH_S(1, 16, 16);
+    if (XR == 8) MPQ_LAUNCH_S(1, 8, 16, 1); else MPQ_LAUNCH_S(1, 16, 16, 1);
   }
+#undef MPQ_LAUNCH_S8
 #undef MPQ_LAUNCH_S
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
   ++g_slice_launches;
