@@ -453,10 +453,11 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
 //   tile in registers.  The ring of code blocks stays full from the first tile of the band to the
 //   last.
 //
-//   The first-order (s_int, z1) and second-order (s2, z2) words of a block travel with it: three
-//   direct loads per block (1 KiB of codes, then one dword per lane that holds the lane's meta1
-//   entry and one that holds its meta2 entry, gathered through the unit table) land in one ring
-//   slot of 1.5 KiB, so no per-tile side record is staged and no barrier separates tiles.
+//   The first-order (s_int, z1) and second-order (s2, z2) words of a block travel with it: after
+//   the 1 KiB of codes, one dword per lane and piece that holds the lane's meta1 entry and one that
+//   holds its meta2 entry, gathered through the unit table, land in the same ring slot (1.5 KiB
+//   and three direct loads per block for g1 >= 64; 1 KiB + 512 B and 1 + 2 loads per piece of a
+//   unit for shorter groups), so no per-tile side record is staged and no barrier separates tiles.
 //
 //   After a group of tiles the waves park their accumulators, meet, and every (row, batch column)
 //   is summed over the waves in a fixed order and written as fp32 to P[h][tile][column][row].  A
