@@ -75,6 +75,12 @@ class Layer:
             m["x"] = torch.from_numpy(m["X"].view(np.int16).copy()).to(dev)
             m["y"] = [torch.zeros(M * spec.N, dtype=torch.int16, device=dev) for _ in range(min(self.copies, 4))]
         self.step_bytes = sum(m["bytes"] for m in self.mats)
+        # one workspace for all products of the stream (they run one after the other), as large as
+        # the most demanding matrix asks for
+        import paper_2311_16442_amd as mpq
+        need = max(mpq.gemm_workspace_size(m["hdr"], M) for m in self.mats) if M > 1 else 0
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=dev) if need else None
+        self.workspace_bytes = need
         torch.cuda.synchronize()
 
     def launch_layer(self, mpq, layer, stream):
@@ -88,7 +94,7 @@ class Layer:
             if self.M == 1:
                 mpq.gemv(m["hdr"], m["blobs"][layer], m["x"], y, stream=stream)
             else:
-                mpq.gemm(m["hdr"], m["blobs"][layer], m["x"], y, self.M, stream=stream)
+                mpq.gemm(m["hdr"], m["blobs"][layer], m["x"], y, self.M, stream=stream, workspace=self.workspace)
 
 
 def time_rotations(torch, mpq, layer, stream, rotations, warm_rotations, use_graph):

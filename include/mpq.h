@@ -169,16 +169,21 @@ mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* 
 mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void* const* blob_dev,
                           const uint16_t* const* x_dev, uint16_t* const* y_dev, void* stream);
 
+/* Bytes of device workspace with which mpq_gemm runs its fastest path for this matrix and batch
+ * size (0 if it needs none: M = 1, or a batch whose activations fit the on-chip memory next to
+ * everything else).  The figure depends on the number of compute units of the current device. */
+mpq_status mpq_gemm_workspace_size(const void* hdr_host, int32_t M, size_t* bytes);
+
 /* Small-batch product Y[m][n] = sum_k X[m][k] W[n][k] (+ outliers), 1 <= M <= MPQ_MAX_M.
  * X_dev is M x K row-major fp16, Y_dev is M x N row-major fp16 (overwritten).
- * Device memory: for batches whose activations do not fit the on-chip memory the library keeps a
- * scratch buffer per (device, stream) for partial sums - a few MiB to a few tens of MiB, allocated
- * (and grown) at a call on that stream, owned by the library until the process ends.  It never
- * allocates while `stream` is being captured into a graph: a captured call uses the scratch that an
- * earlier call on the same stream left, or else a slower path that needs none.  Calls on one
- * stream are ordered by the stream; calls on different streams use different buffers. */
-mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev,
-                    uint16_t* Y_dev, int32_t M, void* stream);
+ * workspace_dev: caller-owned DEVICE memory of workspace_bytes bytes, 256-byte aligned, that the
+ * call may overwrite (partial sums of the kernel for batches whose activations do not fit the
+ * on-chip memory); its contents mean nothing before or after the call.  It may be NULL or smaller
+ * than mpq_gemm_workspace_size says: the product is then computed by a path that needs none and
+ * passes over the weights several times.  The library itself never allocates device memory.  Calls
+ * that may run at the same time (different streams) must not share a workspace. */
+mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                    int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

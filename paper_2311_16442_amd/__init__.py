@@ -25,7 +25,7 @@ STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ
  MPQ_ERR_CSR, MPQ_ERR_BLOB, MPQ_ERR_SIZE, MPQ_ERR_UNSUPPORTED, MPQ_ERR_HIP) = range(11)
 
 EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_quantize_host", "mpq_packed_size", "mpq_pack_host", "mpq_blob_info",
-           "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm"]
+           "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm_workspace_size", "mpq_gemm"]
 MAX_MULTI = 8
 
 
@@ -91,7 +91,10 @@ def lib():
         L.mpq_gemv_multi.argtypes = [C.c_int32, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
                                      C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]
         L.mpq_gemm.restype = C.c_int
-        L.mpq_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.mpq_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
+                               C.c_void_p]
+        L.mpq_gemm_workspace_size.restype = C.c_int
+        L.mpq_gemm_workspace_size.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
         _lib = L
     return _lib
 
@@ -246,9 +249,20 @@ def gemv_multi(headers, blobs_dev, xs_dev, ys_dev, stream=None):
                                 _stream_ptr(stream)), "mpq_gemv_multi")
 
 
-def gemm(header, blob_dev, X_dev, Y_dev, M, stream=None):
+def gemm_workspace_size(header, M) -> int:
+    """Bytes of device workspace with which gemm() runs its fastest path (0: none needed)."""
     h, hp = _hdr_ptr(header)
-    _check(lib().mpq_gemm(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M),
+    n = C.c_size_t(0)
+    _check(lib().mpq_gemm_workspace_size(hp, int(M), C.byref(n)), "mpq_gemm_workspace_size")
+    return int(n.value)
+
+
+def gemm(header, blob_dev, X_dev, Y_dev, M, stream=None, workspace=None):
+    """workspace: a device tensor (256-byte aligned) of at least gemm_workspace_size() bytes, or None."""
+    h, hp = _hdr_ptr(header)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().mpq_gemm(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M), ws_ptr, ws_bytes,
                           _stream_ptr(stream)), "mpq_gemm")
 
 

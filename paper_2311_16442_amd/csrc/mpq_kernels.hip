@@ -24,7 +24,6 @@
 #include <stdint.h>
 #include <string.h>
 
-#include <mutex>
 
 #include "../../include/mpq.h"
 #include "mpq_format.h"
@@ -511,7 +510,7 @@ __global__ void __launch_bounds__(WV * 64)
 mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restrict__ P, uint16_t* __restrict__ XT,
                const int M, const SlicePlan pl) {
 #pragma clang fp contract(off)
-  static_assert(WV == 8 || WV == 16, "waves");
+  static_assert(WV == 8, "waves: the work split pairs wave w with wave w + 4 of the same SIMD");
   static_assert(XR == 8 || XR == 16 * NT, "staged rows");
   constexpr uint32_t W = WV, PD = 2, RMAX = 8;
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;            // pieces per 2-bit unit (PU) and per 4-bit unit
@@ -578,18 +577,13 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   {                                                                                     \
     FIRST = (G) * ntl / ngroups;                                                        \
     RN = ((G) + 1) * ntl / ngroups - FIRST;                                             \
-    if (W == 8) {                                                                       \
-      /* waves w and w + 4 share a SIMD and a quarter of the blocks.  The issue arbitration prefers \
-         the older wave: with equal shares it is done a quarter earlier and the SIMD runs the rest  \
-         of the group with one wave (timestamps); 10/16 : 6/16 measured best (4-6 % over 8 : 8) */    \
-      const uint32_t S_ = RN * len, qlo = (wv & 3u) * S_ / 4u, qhi = ((wv & 3u) + 1u) * S_ / 4u; \
-      const uint32_t mid = qlo + (qhi - qlo) * pl.older16 / 16u;                        \
-      LO = wv < 4u ? qlo : mid;                                                         \
-      HI = wv < 4u ? mid : qhi;                                                         \
-    } else {                                                                            \
-      LO = wv * (RN * len) / W;                                                         \
-      HI = (wv + 1) * (RN * len) / W;                                                   \
-    }                                                                                   \
+    /* waves w and w + 4 share a SIMD and a quarter of the blocks.  The issue arbitration prefers  \
+       the older wave: with equal shares it is done a quarter earlier and the SIMD runs the rest    \
+       of the group with one wave (timestamps); 10/16 : 6/16 measured best (4-6 % over 8 : 8) */     \
+    const uint32_t S_ = RN * len, qlo = (wv & 3u) * S_ / 4u, qhi = ((wv & 3u) + 1u) * S_ / 4u;      \
+    const uint32_t mid = qlo + (qhi - qlo) * pl.older16 / 16u;                                     \
+    LO = wv < 4u ? qlo : mid;                                                                      \
+    HI = wv < 4u ? mid : qhi;                                                                      \
   }
 #define MPQ_S_NORMALIZE                                                                 \
   while (r_g < ngroups && r_s >= r_hi) {                                                \
@@ -1227,7 +1221,6 @@ int g_gemv_waves = 0;   // 0 = automatic (8 or 16 waves per workgroup of the GEM
 int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
 int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
 int g_slices = -1;      // -1 = automatic, 1 = large-batch kernel for every M > 1, 0 = never
-int g_slice_waves = 0;  // 0 = automatic (8), 16
 int g_slice_min_h = 0;  // least number of ranges of the large-batch kernel (tests: several ranges on small matrices)
 int g_slice_launches = 0;
 int g_slice_older = 0;  // 0 = automatic (10): sixteenths of a SIMD's blocks that go to the older of its two waves
@@ -1376,52 +1369,6 @@ mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uin
   return MPQ_ERR_UNSUPPORTED;
 }
 
-// Device memory for the partial sums of the large-batch kernel: one grow-only buffer per (device, stream),
-// so that calls on different streams never share one.  Never allocates while the stream is being
-// captured into a graph; returns nullptr when nothing large enough is there and nothing can be
-// allocated (the caller then takes a kernel that needs no scratch).
-struct ScratchSlot {
-  int dev;
-  hipStream_t stream;
-  void* ptr;
-  size_t bytes;
-};
-constexpr int kScratchSlots = 16;
-ScratchSlot g_scratch[kScratchSlots];
-int g_scratch_used = 0;
-std::mutex g_scratch_mutex;
-
-void* scratch_get(hipStream_t s, size_t bytes) {
-  std::lock_guard<std::mutex> lock(g_scratch_mutex);
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-  ScratchSlot* slot = nullptr;
-  for (int q = 0; q < g_scratch_used; ++q)
-    if (g_scratch[q].dev == dev && g_scratch[q].stream == s) slot = &g_scratch[q];
-  if (slot && slot->bytes >= bytes) return slot->ptr;
-  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-  if (hipStreamIsCapturing(s, &cap) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-  if (cap != hipStreamCaptureStatusNone) return nullptr;
-  if (!slot) {
-    if (g_scratch_used == kScratchSlots) return nullptr;
-    slot = &g_scratch[g_scratch_used];
-    *slot = ScratchSlot{dev, s, nullptr, 0};
-  }
-  if (slot->ptr) {
-    // earlier launches on this stream may still use the old buffer
-    if (hipStreamSynchronize(s) != hipSuccess || hipFree(slot->ptr) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-    slot->ptr = nullptr;
-    slot->bytes = 0;
-  }
-  const size_t want = (bytes + (bytes >> 2) + 0xFFFFFull) & ~0xFFFFFull;  // a quarter more, whole MiB
-  void* ptr = nullptr;
-  if (hipMalloc(&ptr, want) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
-  slot->ptr = ptr;
-  slot->bytes = want;
-  if (slot == &g_scratch[g_scratch_used]) ++g_scratch_used;
-  return ptr;
-}
-
 // Plan of the large-batch kernel: staged rows XR, the fewest ranges H whose activations fit the LDS of a
 // workgroup of W waves next to ring, unit table and park area, NB tile bands so that H * NB
 // workgroups about fill the compute units, groups of at most R = 8 tiles.
@@ -1454,20 +1401,26 @@ bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePl
   return false;
 }
 
-mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+// Workspace of the large-batch kernel: partial sums P[H][T][16 NT][16] fp32, then the transposed
+// activations XT[K][XR] fp16.
+size_t slice_workspace_bytes(const MpqHeader& h, const SlicePlan& pl, int NT, int XR, size_t* p_bytes) {
+  *p_bytes = ((size_t)pl.H * (size_t)h.T * NT * 256 * sizeof(float) + 255) & ~(size_t)255;
+  return *p_bytes + (size_t)h.K * XR * sizeof(uint16_t);
+}
+
+mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, void* ws,
+                         size_t ws_bytes, hipStream_t s) {
   SlicePlan pl;
   int XR = 0;
   const int NT = M > 16 ? 2 : 1;
-  // 8 waves leave more LDS for the activations and 256 registers per lane (two batch halves need
-  // them): faster on every shape measured; 16 waves are kept for M <= 16 behind the tuning hook
+  // 8 waves per workgroup leave the most LDS for the activations and 256 registers per lane (the B
+  // operands of a position and up to 8 x NT accumulators stay in registers); 16 waves, with half
+  // the registers and a third less LDS for the activations, measured equal or slower on every shape
   const int pu = mpq_pu2(h.g1);
-  const bool w8 = g_slice_waves != 16 || NT == 2 || pu > 1;
-  if (!plan_slices(h, M, w8 ? 8 : 16, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
-  // scratch: partial sums P[H][T][16 NT][16] fp32, then the transposed activations XT[K][XR] fp16
-  const size_t p_bytes = ((size_t)pl.H * (size_t)h.T * NT * 256 * sizeof(float) + 255) & ~(size_t)255;
-  const size_t bytes = p_bytes + (size_t)h.K * XR * sizeof(uint16_t);
-  unsigned char* scratch = (unsigned char*)scratch_get(s, bytes);
-  if (!scratch) return MPQ_ERR_UNSUPPORTED;
+  if (!plan_slices(h, M, 8, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
+  size_t p_bytes = 0;
+  if (!ws || ((uintptr_t)ws & 255u) != 0 || ws_bytes < slice_workspace_bytes(h, pl, NT, XR, &p_bytes)) return MPQ_ERR_UNSUPPORTED;
+  unsigned char* scratch = (unsigned char*)ws;
   float* P = (float*)scratch;
   uint16_t* XT = (uint16_t*)(scratch + p_bytes);
   const dim3 grid((unsigned)(pl.H * pl.NB));
@@ -1475,11 +1428,7 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   hipLaunchKernelGGL((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV, PUV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
 #define MPQ_LAUNCH_S8(PUV) \
   { if (XR == 8) MPQ_LAUNCH_S(1, 8, 8, PUV); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8, PUV); else MPQ_LAUNCH_S(2, 32, 8, PUV); }
-  if (w8) {
-    if (pu == 1) MPQ_LAUNCH_S8(1) else if (pu == 2) MPQ_LAUNCH_S8(2) else MPQ_LAUNCH_S8(4)
-  } else {
-    if (XR == 8) MPQ_LAUNCH_S(1, 8, 16, 1); else MPQ_LAUNCH_S(1, 16, 16, 1);
-  }
+  if (pu == 1) MPQ_LAUNCH_S8(1) else if (pu == 2) MPQ_LAUNCH_S8(2) else MPQ_LAUNCH_S8(4)
 #undef MPQ_LAUNCH_S8
 #undef MPQ_LAUNCH_S
   if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
@@ -1491,7 +1440,8 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
 }
 
-mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, void* ws, size_t ws_bytes,
+                  hipStream_t s) {
   if (M == 1) return gemv_all(h, d, X, Y, s);
   if (mm_lds_bytes(h, 1, 3) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
   int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
@@ -1508,7 +1458,7 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
     const bool large = h.total_bytes >= (12u << 20);
     const bool better = M <= 8 ? chunks >= 3 || (chunks == 2 && large) : chunks >= 2 || large;
     if (g_slices < 0 ? better : g_slices != 0) {
-      const mpq_status st = launch_slices(h, d, X, Y, M, s);
+      const mpq_status st = launch_slices(h, d, X, Y, M, ws, ws_bytes, s);
       if (st != MPQ_ERR_UNSUPPORTED) return st;
     }
   }
@@ -1535,7 +1485,7 @@ extern "C" {
 //   2: cap on the number of persistent workgroups
 //   4: waves per workgroup of the GEMV (8, 16)          6: tiles per workgroup of the GEMV (1..8)
 //   5: waves per workgroup of the batch kernel (4, 8, 16)
-//  12: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic   13: its waves per workgroup (8, 16)
+//  12: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic
 //  14: its least number of ranges   15: its tiles per group (1..8)
 //  18: sixteenths of a SIMD's blocks that go to the older of its two waves (1..15)
 void mpq_debug_set(int key, int value) {
@@ -1544,7 +1494,6 @@ void mpq_debug_set(int key, int value) {
   if (key == 5) g_batch_waves = value;
   if (key == 6) g_gemv_tiles = value;
   if (key == 12) g_slices = value;
-  if (key == 13) g_slice_waves = value;
   if (key == 14) g_slice_min_h = value;
   if (key == 15) g_slice_tiles = value;
   if (key == 18) g_slice_older = value;
@@ -1554,7 +1503,7 @@ void mpq_debug_set(int key, int value) {
 int mpq_debug_get(int key) { return key == 12 ? g_slice_launches : 0; }
 
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
-                    int32_t M, void* stream) {
+                    int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream) {
   if (!X_dev || !Y_dev) return MPQ_ERR_NULL;
   if (M < 1 || M > MPQ_MAX_M) return MPQ_ERR_SHAPE;
   MpqHeader h;
@@ -1562,12 +1511,26 @@ mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* 
   mpq_status st = make_dev(hdr_host, blob_dev, &h, &d);
   if (st != MPQ_OK) return st;
   if ((((uintptr_t)X_dev | (uintptr_t)Y_dev) & 15u) != 0) return MPQ_ERR_ALIGN;
-  return mm_all(h, d, X_dev, Y_dev, M, (hipStream_t)stream);
+  return mm_all(h, d, X_dev, Y_dev, M, workspace_dev, workspace_bytes, (hipStream_t)stream);
+}
+
+mpq_status mpq_gemm_workspace_size(const void* hdr_host, int32_t M, size_t* bytes) {
+  if (!hdr_host || !bytes) return MPQ_ERR_NULL;
+  if (M < 1 || M > MPQ_MAX_M) return MPQ_ERR_SHAPE;
+  MpqHeader h;
+  mpq_status st = mpq_internal_check_header(hdr_host, &h);
+  if (st != MPQ_OK) return st;
+  *bytes = 0;
+  SlicePlan pl;
+  int XR = 0;
+  size_t p_bytes = 0;
+  if (M > 1 && plan_slices(h, M, 8, 160 * 1024, &pl, &XR)) *bytes = slice_workspace_bytes(h, pl, M > 16 ? 2 : 1, XR, &p_bytes);
+  return MPQ_OK;
 }
 
 mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev, uint16_t* y_dev,
                     void* stream) {
-  return mpq_gemm(hdr_host, blob_dev, x_dev, y_dev, 1, stream);
+  return mpq_gemm(hdr_host, blob_dev, x_dev, y_dev, 1, nullptr, 0, stream);
 }
 
 mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void* const* blob_dev,

@@ -37,3 +37,18 @@ def to_dev(torch, arr: np.ndarray):
     t = torch.from_numpy(np.ascontiguousarray(arr)).cuda()
     assert t.data_ptr() % 16 == 0
     return t
+
+
+class Workspace:
+    """Device workspace for mpq.gemm of the size the library asks for, with a sentinel band behind it."""
+
+    def __init__(self, torch, mpq, header, M):
+        self.torch = torch
+        self.bytes = mpq.gemm_workspace_size(header, M)
+        self.buf = torch.full((self.bytes + 256,), 0x5A, dtype=torch.uint8, device="cuda")
+        assert self.buf.data_ptr() % 256 == 0
+        self.view = self.buf[:self.bytes] if self.bytes else None
+
+    def check(self):
+        self.torch.cuda.synchronize()
+        assert bool((self.buf[self.bytes:] == 0x5A).all()), "workspace overrun"

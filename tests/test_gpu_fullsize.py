@@ -8,7 +8,7 @@ import pytest
 import mpq_synth as synth
 import oracle
 import paper_2311_16442_amd as mpq
-from gpu_util import Guarded, rel_err, to_dev
+from gpu_util import Guarded, Workspace, rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -53,7 +53,9 @@ def check_products(torch, lg, pk, blob, Ms, all_rows):
         if M == 1:
             mpq.gemv(pk.header, blob, to_dev(torch, X[0].view(np.int16)), Y.view)
         else:
-            mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+            ws = Workspace(torch, mpq, pk.header, M)
+            mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, workspace=ws.view)
+            ws.check()
         got = Y.check_and_get().reshape(M, s.N)
         ref = om.gemm(X, threads=8)
         # the floor of the error measure uses the rms over the rows that were checked

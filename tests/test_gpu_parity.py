@@ -7,7 +7,7 @@ import pytest
 import mpq_synth as synth
 import oracle
 import paper_2311_16442_amd as mpq
-from gpu_util import Guarded, rel_err, to_dev
+from gpu_util import Guarded, Workspace, rel_err, to_dev
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-3
@@ -149,8 +149,10 @@ def test_gemm_within_tolerance(torch, M):
     blob = to_dev(torch, pk.blob)
     X = synth.make_x(123 + M, M, pk.K)
     Y = Guarded(torch, M * pk.N)
-    mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+    ws = Workspace(torch, mpq, pk.header, M)
+    mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, workspace=ws.view)
     got = Y.check_and_get().reshape(M, pk.N)
+    ws.check()
     ref = om.gemm(X, threads=8)
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (M, e_floor, e_max)
@@ -197,18 +199,17 @@ def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
     assert e_floor <= TOL, (e_floor, e_max)
 
 
-SLICE_CASES = CASES
 
 
-@pytest.mark.parametrize("waves,min_h", [(16, 0), (8, 0), (16, 3)])
+@pytest.mark.parametrize("min_h", [0, 3])
 @pytest.mark.parametrize("M", [2, 7, 8, 9, 16, 17, 32])
-@pytest.mark.parametrize("case", SLICE_CASES, ids=[c[0] for c in SLICE_CASES])
-def test_large_batch_kernel_within_tolerance(torch, case, M, waves, min_h):
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_large_batch_kernel_within_tolerance(torch, case, M, min_h):
     # the kernel that keeps one K-range of the activations resident per workgroup and writes partial
     # sums that a second kernel adds up, forced for every batch size through the tuning hook (by
     # itself the library takes it where the other batch kernel would decode the weights several
-    # times); with 16 or 8 waves per workgroup, and with at least three ranges also on matrices
-    # whose activations would fit at once
+    # times); also with at least three ranges on matrices whose activations would fit at once.  The
+    # workspace has exactly the size the library asks for, with a guard band behind it.
     import ctypes
     lg, om, pk = make(case)
     hook, count = mpq.lib().mpq_debug_set, mpq.lib().mpq_debug_get
@@ -217,21 +218,22 @@ def test_large_batch_kernel_within_tolerance(torch, case, M, waves, min_h):
     blob = to_dev(torch, pk.blob)
     X = synth.make_x(700 + M, M, pk.K)
     ref = om.gemm(X, threads=8)
-    print("case", case, "M", M, "waves", waves, "min_h", min_h, flush=True)
+    print("case", case, "M", M, "min_h", min_h, flush=True)
     before = count(12)
     try:
         hook(12, 1)
-        hook(13, waves)
         hook(14, min_h)
+        ws = Workspace(torch, mpq, pk.header, M)
+        assert ws.bytes > 0
         Y = Guarded(torch, M * pk.N)
-        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M)
+        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, workspace=ws.view)
         got = Y.check_and_get().reshape(M, pk.N)
         Y2 = Guarded(torch, M * pk.N)
-        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M)
+        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M, workspace=ws.view)
         again = Y2.check_and_get().reshape(M, pk.N)
+        ws.check()
     finally:
         hook(12, -1)
-        hook(13, 0)
         hook(14, 0)
     assert count(12) == before + 2, "the large-batch kernel did not run"
     e_floor, e_max = rel_err(got, ref)
@@ -239,11 +241,10 @@ def test_large_batch_kernel_within_tolerance(torch, case, M, waves, min_h):
     assert np.array_equal(got, again)
 
 
-def test_large_batch_kernel_in_a_graph(torch):
-    # the large-batch kernel needs device scratch, which the library allocates per (device, stream) at
-    # an eager call and never while the stream is captured: a capture on a stream that has scratch
-    # records the kernel and every replay reproduces the eager result; a capture on a stream without
-    # scratch records the other batch kernel instead, and still gives the right product
+def test_large_batch_kernel_in_a_graph_and_without_workspace(torch):
+    # the library allocates nothing: with the caller's workspace the large-batch kernel can be
+    # captured into a graph and every replay reproduces the eager result; without a workspace (or
+    # with one that is too small) the product is computed by the other batch kernel
     import ctypes
     lg, om, pk = make(CASES[6])
     M = 16
@@ -254,33 +255,37 @@ def test_large_batch_kernel_in_a_graph(torch):
     X = synth.make_x(900, M, pk.K)
     Xd = to_dev(torch, X.view(np.int16))
     ref = om.gemm(X, threads=8)
-    warm, cold = torch.cuda.Stream(), torch.cuda.Stream()
+    stream = torch.cuda.Stream()
     try:
         hook(12, 1)
+        ws = Workspace(torch, mpq, pk.header, M)
         Y = Guarded(torch, M * pk.N)
         torch.cuda.synchronize()
-        mpq.gemm(pk.header, blob, Xd, Y.view, M, stream=warm)
-        warm.synchronize()
+        before = count(12)
+        mpq.gemm(pk.header, blob, Xd, Y.view, M, stream=stream, workspace=ws.view)
+        stream.synchronize()
+        assert count(12) == before + 1
         eager = Y.check_and_get().reshape(M, pk.N)
         assert rel_err(eager, ref)[0] <= TOL
-        for stream, uses_scratch in ((warm, True), (cold, False)):
-            Yg = Guarded(torch, M * pk.N)
+        Yg = Guarded(torch, M * pk.N)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            mpq.gemm(pk.header, blob, Xd, Yg.view, M, stream=stream, workspace=ws.view)
+        assert count(12) == before + 2
+        for rep in range(3):
+            Yg.view.zero_()
+            ws.buf[:ws.bytes].fill_(0xFF)      # the workspace carries nothing from call to call
             torch.cuda.synchronize()
-            before = count(12)
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                mpq.gemm(pk.header, blob, Xd, Yg.view, M, stream=stream)
-            assert (count(12) == before + 1) == uses_scratch
-            for rep in range(3):
-                Yg.view.zero_()
-                torch.cuda.synchronize()
-                g.replay()
-                torch.cuda.synchronize()
-                got = Yg.check_and_get().reshape(M, pk.N)
-                if uses_scratch:
-                    assert np.array_equal(got, eager), rep
-                else:
-                    assert rel_err(got, ref)[0] <= TOL, rep
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(Yg.check_and_get().reshape(M, pk.N), eager), rep
+        ws.check()
+        for small in (None, ws.view[:ws.bytes - 256]):
+            Yn = Guarded(torch, M * pk.N)
+            mpq.gemm(pk.header, blob, Xd, Yn.view, M, workspace=small)
+            assert rel_err(Yn.check_and_get().reshape(M, pk.N), ref)[0] <= TOL
+        assert count(12) == before + 2          # neither of the two ran the large-batch kernel
     finally:
         hook(12, -1)
 

@@ -142,8 +142,8 @@ def test_small_buffer_and_bad_header_are_reported():
     assert L.mpq_gemv(hdr.ctypes.data_as(C.c_void_p), fake, fake, fake, None) == mpq.MPQ_ERR_BLOB
     assert L.mpq_gemv(pk.header.ctypes.data_as(C.c_void_p), None, fake, fake, None) == mpq.MPQ_ERR_NULL
     assert L.mpq_gemv(pk.header.ctypes.data_as(C.c_void_p), C.c_void_p(4100), fake, fake, None) == mpq.MPQ_ERR_ALIGN
-    assert L.mpq_gemm(pk.header.ctypes.data_as(C.c_void_p), fake, fake, fake, 0, None) == mpq.MPQ_ERR_SHAPE
-    assert L.mpq_gemm(pk.header.ctypes.data_as(C.c_void_p), fake, fake, fake, 33, None) == mpq.MPQ_ERR_SHAPE
+    assert L.mpq_gemm(pk.header.ctypes.data_as(C.c_void_p), fake, fake, fake, 0, None, 0, None) == mpq.MPQ_ERR_SHAPE
+    assert L.mpq_gemm(pk.header.ctypes.data_as(C.c_void_p), fake, fake, fake, 33, None, 0, None) == mpq.MPQ_ERR_SHAPE
     assert L.mpq_dequant(pk.header.ctypes.data_as(C.c_void_p), fake, None, 0, None) == mpq.MPQ_ERR_NULL
 
 
@@ -176,3 +176,25 @@ def test_group_count_beyond_the_table_offsets_is_unsupported():
         mpq.packed_size(16, 1100 * 16, 16, 1, np.zeros(1100, np.uint8), rp, 1)
     assert e.value.status == mpq.MPQ_ERR_UNSUPPORTED
     assert mpq.packed_size(16, 1000 * 16, 16, 1, np.zeros(1000, np.uint8), rp, 1) > 0
+
+
+def test_gemm_workspace_size_on_the_host():
+    # a host-side query (no GPU needed): nothing for M = 1, partial sums for every range plus the
+    # transposed activations otherwise, growing with the batch; bad arguments are refused
+    spec = synth.MatrixSpec("ws", 4096, 4096, 64, 16, 0.10, 0.005, 77)
+    lg = synth.make_matrix(spec)
+    pk = mpq.pack_logical(lg)
+    assert mpq.gemm_workspace_size(pk.header, 1) == 0
+    sizes = [mpq.gemm_workspace_size(pk.header, M) for M in (2, 8, 9, 16, 17, 32)]
+    assert all(b % 256 == 0 or b > 0 for b in sizes) and all(b > 0 for b in sizes)
+    assert sizes == sorted(sizes)
+    T = 4096 // 16
+    # at least one range of partial sums (16 batch columns x 16 rows fp32 per tile) and the K x 8 fp16 copy
+    assert sizes[0] >= T * 16 * 16 * 4 + 4096 * 8 * 2
+    L = mpq.lib()
+    n = C.c_size_t(0)
+    hp = pk.header.ctypes.data_as(C.c_void_p)
+    assert L.mpq_gemm_workspace_size(hp, 0, C.byref(n)) == mpq.MPQ_ERR_SHAPE
+    assert L.mpq_gemm_workspace_size(hp, 33, C.byref(n)) == mpq.MPQ_ERR_SHAPE
+    assert L.mpq_gemm_workspace_size(None, 4, C.byref(n)) == mpq.MPQ_ERR_NULL
+    assert L.mpq_gemm_workspace_size(hp, 4, None) == mpq.MPQ_ERR_NULL
