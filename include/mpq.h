@@ -106,6 +106,11 @@ const char* mpq_status_str(mpq_status s);
  *         of each weight element"): alpha*(2 + (2+Ns)/g1 + (Ns+16)/(g1*g2)) + (1-alpha)*4 with
  *         alpha = 1 - n4/G and Ns = `ns_bits`, plus the outlier increment (16+16-2)*nnz/(N*K)
  *         (Sec. 4.2).
+ * mode 2: the same with the paper's aligned storage of the metadata (Sec. 3.3 "Memory Alignment") in
+ *         place of the ideal counts: one 16-bit word for the zero points and scales of three 2-bit
+ *         groups (16/(3 g1) bits per weight instead of (2+Ns)/g1) and the second-order zero padded
+ *         to whole bytes.  An accounting only: this library stores uint8 scales and zero points
+ *         (mode 0).
  * Returns a negative value on invalid arguments. */
 double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns_bits);
 

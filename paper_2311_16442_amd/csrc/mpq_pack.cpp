@@ -192,6 +192,16 @@ double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns
     const double two_bit = 2.0 + (2.0 + ns_bits) / d->g1 + (ns_bits + 16.0) / ((double)d->g1 * d->g2);
     return alpha * two_bit + (1.0 - alpha) * 4.0 + (16.0 + 16.0 - 2.0) * (double)nnz / NK;
   }
+  if (mode == 2) {
+    // Sec. 3.3 "Memory Alignment" as storage: the zero points and scales of three 2-bit groups in one
+    // 16-bit word (3 x 2-bit zeros + 4 + 3 + 3 bits of scales, "Scale Clipping"), the second-order
+    // zero padded to whole bytes ("Zero Padding") next to the fp16 second-order scale.
+    if (ns_bits <= 0) return -1.0;
+    const double alpha = 1.0 - n4 / G;
+    const double padded = 8.0 * ((ns_bits + 7) / 8);
+    const double two_bit = 2.0 + 16.0 / (3.0 * d->g1) + (padded + 16.0) / ((double)d->g1 * d->g2);
+    return alpha * two_bit + (1.0 - alpha) * 4.0 + (16.0 + 16.0 - 2.0) * (double)nnz / NK;
+  }
   return -1.0;
 }
 

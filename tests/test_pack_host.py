@@ -198,3 +198,17 @@ def test_gemm_workspace_size_on_the_host():
     assert L.mpq_gemm_workspace_size(hp, 33, C.byref(n)) == mpq.MPQ_ERR_SHAPE
     assert L.mpq_gemm_workspace_size(None, 4, C.byref(n)) == mpq.MPQ_ERR_NULL
     assert L.mpq_gemm_workspace_size(hp, 4, None) == mpq.MPQ_ERR_NULL
+
+
+def test_avg_bits_with_the_papers_aligned_metadata_stays_within_its_stated_overhead():
+    # Sec. 3.3: packing the metadata as the paper describes changes the average by less than 0.02 bit
+    # at its operating point (g1 = g2 = 16, Ns = 4, 25 % 4-bit): 16 bits per three groups instead of
+    # 3 x (2 + 4), an 8-bit padded second-order zero instead of 4 bits
+    spec = dict(N=4096, K=4096, g1=16, g2=16, g2_axis=1)
+    G = 4096 // 16
+    ideal = mpq.avg_bits(n4=G // 4, nnz=0, mode=1, ns_bits=4, **spec)
+    aligned = mpq.avg_bits(n4=G // 4, nnz=0, mode=2, ns_bits=4, **spec)
+    assert abs(ideal - 2.84) < 0.005
+    assert abs(aligned - (0.75 * (2 + 16 / 48 + 24 / 256) + 1.0)) < 1e-12
+    assert abs(aligned - ideal) < 0.02
+    assert mpq.avg_bits(n4=0, nnz=0, mode=3, ns_bits=4, **spec) < 0
