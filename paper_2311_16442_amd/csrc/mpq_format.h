@@ -47,11 +47,21 @@
 //       codes at codes_off (128-byte aligned): (B2 + B4) x 64 x 16 B, the 2-bit blocks then the 4-bit
 //                                 blocks of the tile, [block][lane] 16-byte units
 //
-// Bit positions inside a unit (4 little-endian dwords):
-//   2-bit: column k0 + kl (kl = 0..63) sits in dword (kl % 8) / 2, bits 16*(kl % 2) + 2*(kl / 8) ..+1
-//   4-bit: column k0 + kl (kl = 0..31) sits in dword (kl % 8) / 2, bits 16*(kl % 2) + 4*(kl / 8) ..+3
-// so that one mask applied to a dword isolates the codes of columns (2r, 2r+1) in the low and high
-// half-word, ready to be turned into a pair of fp16 values.
+// Bit positions inside a unit (4 little-endian dwords).  A decode step P covers the 8 columns
+// k0 + 8P .. k0 + 8P + 7; column 8P + 2d + h (d = 0..3, h = 0, 1) lives in dword d, in its low (h = 0)
+// or high (h = 1) half-word, so that one mask applied to a dword isolates the codes of columns
+// (8P + 2d, 8P + 2d + 1) in the low and high half-word, ready to be turned into a pair of fp16 values.
+//   4-bit (P = 0..3): bits 16h + 4P .. +3 of dword d.
+//   2-bit (P = 0..7): the dword is read as 8 nibbles; nibble nn = (P % 4) + 4h holds
+//       for P < 4 (the first 32 columns of the unit) the code in nibble bits 1 (code bit 0) and 2 (code bit 1);
+//       for P >= 4 (the last 32 columns) code bit 0 in nibble bit 3 and code bit 1 in bit 0 of nibble
+//       (nn + 1) % 8 of the same dword, i.e. in dword bits 4nn + 3 and (4nn + 4) % 32.
+//     Reason: bits 1, 2 of a nibble are the two exponent bits of an fp4 (E2M1) number with sign and
+//     mantissa bit cleared, so dword & 0x22222222 / 0x44444444 / 0x66666666 ARE eight fp4 numbers
+//     1.0 * bit0 / 2.0 * bit1 / {0, 1, 2, 4}[code], the B operand of v_mfma_f32_16x16x128_f8f6f4, with no
+//     unpacking; the same three masks on the dword rotated right by 2 give the last 32 columns.  The
+//     per-weight decode reads the same layout as fields at bit offsets 1, 3, 5, 7 of the half-words of
+//     the dword and of the dword rotated right by 8.
 //
 // Sections and tile records start on 256-byte boundaries; padding bytes are zero.
 #ifndef MPQ_FORMAT_H_
@@ -60,7 +70,7 @@
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 7u
+#define MPQ_VERSION 8u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024

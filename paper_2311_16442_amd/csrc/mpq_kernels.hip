@@ -17,7 +17,7 @@
 //
 // Per-weight arithmetic (bit-exact to the definition in mpq.h):
 //   a mask isolates two codes (low / high half-word of a dword); OR-ing 0x6400 into each half
-//   makes the fp16 numbers 1024 + c*4^p; one packed fma (x 4^-p, - (1024*4^-p + z1)) gives the
+//   makes the fp16 numbers 1024 + c*2^o; one packed fma (x 2^-o, - (1024*2^-o + z1)) gives the
 //   exact integers c - z1; one packed fp16 multiply by s1 is the rounding the definition asks
 //   for.  The product kernel hands the resulting pairs to the matrix core.
 #include <hip/hip_runtime.h>
@@ -149,38 +149,42 @@ __device__ __forceinline__ uint32_t sgpr_const(uint32_t v) {
 }
 
 struct DecodeConsts {
-  uint32_t mask2[5], mask4[2], sc2[5], sc4[2];
+  uint32_t mask2[4], mask4[2], sc2[4], sc4[2];
   uint32_t magic;
 };
 
 __device__ __forceinline__ DecodeConsts make_consts() {
   DecodeConsts k;
-  k.mask2[0] = sgpr_const(0x00030003u); k.mask2[1] = sgpr_const(0x000C000Cu); k.mask2[2] = sgpr_const(0x00300030u);
-  k.mask2[3] = sgpr_const(0x00C000C0u); k.mask2[4] = sgpr_const(0x03000300u);
+  // 2-bit fields sit at bit offsets 1, 3, 5, 7 of a half-word (mpq_format.h)
+  k.mask2[0] = sgpr_const(0x00060006u); k.mask2[1] = sgpr_const(0x00180018u);
+  k.mask2[2] = sgpr_const(0x00600060u); k.mask2[3] = sgpr_const(0x01800180u);
   k.mask4[0] = sgpr_const(0x000F000Fu); k.mask4[1] = sgpr_const(0x00F000F0u);
-  k.sc2[0] = sgpr_const(0x3C003C00u);  // 1
-  k.sc2[1] = sgpr_const(0x34003400u);  // 1/4
-  k.sc2[2] = sgpr_const(0x2C002C00u);  // 1/16
-  k.sc2[3] = sgpr_const(0x24002400u);  // 1/64
-  k.sc2[4] = sgpr_const(0x1C001C00u);  // 1/256
-  k.sc4[0] = k.sc2[0];
-  k.sc4[1] = k.sc2[2];
+  k.sc2[0] = sgpr_const(0x38003800u);  // 1/2
+  k.sc2[1] = sgpr_const(0x30003000u);  // 1/8
+  k.sc2[2] = sgpr_const(0x28002800u);  // 1/32
+  k.sc2[3] = sgpr_const(0x20002000u);  // 1/128
+  k.sc4[0] = sgpr_const(0x3C003C00u);  // 1
+  k.sc4[1] = sgpr_const(0x2C002C00u);  // 1/16
   asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(k.magic));  // fp16 1024.0 in both halves
   return k;
 }
 
+__device__ __forceinline__ uint32_t rotr8(uint32_t v) { return __builtin_amdgcn_alignbit(v, v, 8); }
+
 // First-order dequantization (eq. 5) of step P of a unit: the four dwords give the four fp16 pairs
 // of columns 8P .. 8P+7.  TWO_BIT selects 2-bit (P = 0..7) or 4-bit (P = 0..3) fields.
-// zb = fp16(1024 + z1); lo / hi = the unit's dwords and the same shifted right by 10 (2-bit) or 8
-// (4-bit) so that every field sits in mantissa bits.
+// zb = fp16(1024 + z1); lo = the unit's dwords, hi = the same rotated right by 8 (2-bit) or shifted
+// right by 8 (4-bit), so that every field sits in mantissa bits of its half-word: a 2-bit field of
+// step P is at bit offset (P < 4 ? 1 : 3) + 4 (P % 2) of lo (P % 4 < 2) or hi; a 4-bit field at
+// offset 4 (P % 2) of lo (P < 2) or hi.
 template <bool TWO_BIT, int P>
 __device__ __forceinline__ uint4 decode_step(const uint32_t (&lo)[4], const uint32_t (&hi)[4], const half2_t s1p,
                                              const half_t zb, const DecodeConsts& kc) {
 #pragma clang fp contract(off)
-  constexpr int pp = TWO_BIT ? (P < 5 ? P : P - 5) : (P & 1);
-  constexpr bool shifted = TWO_BIT ? (P >= 5) : (P >= 2);
-  // -(1024 * f + z1) with f = 4^-pp (2-bit) or 16^-pp (4-bit): exact, an integer below 2048
-  constexpr float off = TWO_BIT ? (pp == 0 ? 0.f : pp == 1 ? 768.f : pp == 2 ? 960.f : pp == 3 ? 1008.f : 1020.f)
+  constexpr int pp = TWO_BIT ? (P < 4 ? 0 : 1) + 2 * (P & 1) : (P & 1);
+  constexpr bool shifted = TWO_BIT ? ((P & 3) >= 2) : (P >= 2);
+  // 1024 - 1024 * f with f = 2^-offset of the field: off - zb = -(1024 * f + z1), exact, below 2048
+  constexpr float off = TWO_BIT ? (pp == 0 ? 512.f : pp == 1 ? 896.f : pp == 2 ? 992.f : 1016.f)
                                 : (pp == 0 ? 0.f : 960.f);
   const half_t t = (half_t)off - zb;
   const half2_t nb = {t, t};
@@ -379,7 +383,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
     uint32_t c = wv;
     for (; c < (uint32_t)b.B2; c += W) {
       MPQ_MM_BLOCK_HEAD(PU)
-      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
       MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
     }
@@ -710,7 +714,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
         for (uint32_t tt = 0; tt < RMAX; ++tt) {
           if (tt >= t && tt < t_end) {
             MPQ_S_HEAD(PU)
-            const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+            const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
             MPQ_S_STEP(true, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 1, acc[tt][0], acc[tt][1])
             MPQ_S_STEP(true, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 3, acc[tt][0], acc[tt][1])
             MPQ_S_STEP(true, 4, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 5, acc[tt][0], acc[tt][1])
@@ -1026,7 +1030,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     for (; c < (uint32_t)b.B2; c += W) {
       MPQ_GEMV_BLOCK_HEAD(PU)
-      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_GEMV_STEP(true, 0) MPQ_GEMV_STEP(true, 1) MPQ_GEMV_STEP(true, 2) MPQ_GEMV_STEP(true, 3)
       MPQ_GEMV_STEP(true, 4) MPQ_GEMV_STEP(true, 5) MPQ_GEMV_STEP(true, 6) MPQ_GEMV_STEP(true, 7)
     }
@@ -1144,7 +1148,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
       half_t zb[PU];
       uint32_t xoff[PU];
       load_pieces<PU>(ue, m1i, m2i, s1p, zb, xoff);
-      const uint32_t hi[4] = {q.x >> 10, q.y >> 10, q.z >> 10, q.w >> 10};
+      const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
       MPQ_DQ_STORE_HALF(0, 8 / PU)
       MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)

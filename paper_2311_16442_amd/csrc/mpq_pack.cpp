@@ -415,14 +415,23 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     const uint8_t* row = w->codes + n * K;
     for (int64_t u = 0; u < nunits; ++u) {
       const bool four = u >= 4ll * h.B2;
-      const int32_t PU = four ? PU4 : PU2, cpp = four ? cpp4 : cpp2, width = four ? 4 : 2;
+      const int32_t PU = four ? PU4 : PU2, cpp = four ? cpp4 : cpp2;
       uint32_t* q4 = codes + (((u / 4) * 64 + (u % 4) * 16 + i) * 4);
       for (int32_t q = 0; q < PU; ++q) {
         if (piece_g[(size_t)(u * PU2 + q)] < 0) continue;
         const int64_t k0 = piece_k0[(size_t)(u * PU2 + q)];
         for (int32_t kp = 0; kp < cpp; ++kp) {
           const int32_t kl = q * cpp + kp;  // column inside the unit
-          q4[(kl % 8) / 2] |= (uint32_t)row[k0 + kp] << (16 * (kl % 2) + width * (kl / 8));
+          const uint32_t code = row[k0 + kp];
+          uint32_t& dw = q4[(kl % 8) / 2];
+          if (four) {
+            dw |= code << (16 * (kl % 2) + 4 * (kl / 8));
+          } else {
+            // decode step P = kl / 8; nibble (P % 4) + 4 * (kl % 2) of the dword (see mpq_format.h)
+            const int32_t nn = (kl / 8) % 4 + 4 * (kl % 2);
+            if (kl < 32) dw |= code << (4 * nn + 1);
+            else dw |= ((code & 1u) << (4 * nn + 3)) | ((code >> 1) << ((4 * nn + 4) % 32));
+          }
         }
       }
     }

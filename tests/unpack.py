@@ -21,7 +21,7 @@ def read_header(blob: np.ndarray) -> dict:
 
 def unpack(blob: np.ndarray) -> dict:
     h = read_header(blob)
-    assert h["version"] == 7
+    assert h["version"] == 8
     N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
     axis = h["g2_axis"]
     B2, B4 = h["B2"], h["B4"]
@@ -53,8 +53,19 @@ def unpack(blob: np.ndarray) -> dict:
         words = cw[:, u // 4, u % 4]                      # [T, 16 rows, 4 dwords]
         field = np.zeros((T * TILE, per), dtype=np.uint8)
         for kl in range(per):
-            d, sh = (kl % 8) // 2, 16 * (kl % 2) + width * (kl // 8)
-            field[:, kl] = ((words[:, :, d] >> sh) & ((1 << width) - 1)).reshape(-1)
+            w = words[:, :, (kl % 8) // 2].astype(np.uint64)
+            if four:
+                v = (w >> (16 * (kl % 2) + 4 * (kl // 8))) & 15
+            else:
+                # 2-bit unit: dword = 8 nibbles; step P = kl // 8 uses nibble nn = P % 4 + 4 * (kl % 2).
+                # first 32 columns: code in nibble bits 1, 2; last 32: bit 0 of the code in nibble bit 3,
+                # bit 1 of the code in bit 0 of the next nibble (wrapping inside the dword)
+                nn = (kl // 8) % 4 + 4 * (kl % 2)
+                if kl < 32:
+                    v = (w >> (4 * nn + 1)) & 3
+                else:
+                    v = ((w >> (4 * nn + 3)) & 1) | (((w >> ((4 * nn + 4) % 32)) & 1) << 1)
+            field[:, kl] = v.astype(np.uint8).reshape(-1)
         for q in range(PU2):
             e, e1 = int(units[u, q, 0]), int(units[u, q, 1])
             if (e1 & 0xFFFF) == 32 * G:                    # padding piece: points at the zero entries
