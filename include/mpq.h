@@ -23,14 +23,18 @@
  *   y[n]      = sum_k Wd[n][k] x[k] + sum_{outliers of row n} val x[col]
  *
  * Memory.  The library never allocates, frees or retains device memory and keeps no state between
- * calls.  Host entry points take HOST pointers; device entry points take DEVICE pointers for bulk
+ * calls: every choice a call makes follows from its arguments and from the compute-unit count of the
+ * current device, which is queried in the call (MPQ_ERR_HIP if the query fails).  Host entry points take HOST pointers; device entry points take DEVICE pointers for bulk
  * data and a HOST pointer to the blob header (the first MPQ_HEADER_BYTES bytes of the packed
  * blob), so that no call ever needs a device-to-host copy.  All pointers are owned by the caller.
  * Device entry points only enqueue work on `stream` (a hipStream_t passed as void*, NULL = the
  * default stream) and return without waiting for it.
  *
  * Errors.  Every entry point returns an mpq_status; nothing is launched unless all arguments
- * validate.  No entry point throws or aborts.
+ * validate.  No entry point throws or aborts.  MPQ_ERR_HIP reports the status of the call's own
+ * launches only (an error an earlier HIP call of the caller left pending is cleared, not reported);
+ * after MPQ_ERR_HIP the output buffer is undefined, since an entry point that needs two kernels may
+ * have enqueued the first.
  */
 #ifndef MPQ_H_
 #define MPQ_H_
@@ -135,6 +139,10 @@ double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns
 mpq_status mpq_quantize_host(const mpq_desc* d, const float* W, int32_t n4, double p_o,
                              const mpq_logical_out* out, int64_t outlier_capacity, int64_t* nnz);
 
+/* Entries the col / val arrays of mpq_quantize_host must hold for these arguments:
+ * N * round(p_o * (G - n4) * g1) (Sec. 4.3: a fixed share of every row's 2-bit columns). */
+mpq_status mpq_quantize_outlier_capacity(const mpq_desc* d, int32_t n4, double p_o, int64_t* capacity);
+
 /* Size in bytes of the packed blob for this shape, 4-bit map and outlier row pointer.
  * `is4` is a HOST array of G bytes, `row_ptr` a HOST array of N+1 entries (the blob stores the
  * outliers of every 16-row tile in a record padded to the fullest tile). */
@@ -186,9 +194,52 @@ mpq_status mpq_gemm_workspace_size(const void* hdr_host, int32_t M, size_t* byte
  * on-chip memory); its contents mean nothing before or after the call.  It may be NULL or smaller
  * than mpq_gemm_workspace_size says: the product is then computed by a path that needs none and
  * passes over the weights several times.  The library itself never allocates device memory.  Calls
- * that may run at the same time (different streams) must not share a workspace. */
+ * that may run at the same time (different streams) must not share a workspace.
+ * M = 1 is mpq_gemv.  Activations must be finite (the batch-1 kernel splits them into fp8 pieces
+ * whose sum is exact only for finite values). */
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
                     int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream);
+
+/* A launch plan overrides, for ONE call, choices the library otherwise makes from the shape: it is how
+ * tests force every kernel and work split and how sweeps measure them.  0 in a field = the library's
+ * own choice; a NULL plan = all zero.  Values a kernel cannot honour (LDS, registers) fall back to the
+ * nearest it can, or return MPQ_ERR_UNSUPPORTED where the field says so. */
+typedef struct {
+  int32_t gemv_path;       /* M = 1: 0 auto, 1 plane-sum kernel (MPQ_ERR_UNSUPPORTED if it cannot run), 2 per-weight decode kernel */
+  int32_t gemv_waves;      /* M = 1: waves per workgroup (8 or 16) */
+  int32_t gemv_tiles;      /* M = 1: 16-row tiles per workgroup */
+  int32_t batch_waves;     /* M > 1, resident-activation kernel: waves per workgroup (4, 8, 16) */
+  int32_t max_workgroups;  /* M > 1, resident-activation kernel: cap on its persistent workgroups */
+  int32_t large_batch;     /* M > 1: 0 auto, 1 K-range kernel whenever a workspace allows it, -1 never */
+  int32_t lb_min_ranges;   /* K-range kernel: least number of ranges */
+  int32_t lb_tiles;        /* K-range kernel: tiles per group (1..8) */
+  int32_t lb_older16;      /* K-range kernel: sixteenths of a SIMD's blocks for the older of its two waves (1..15) */
+  int32_t reserved[7];     /* must be 0 */
+} mpq_plan;
+
+#define MPQ_KERNEL_GEMV_PLANES 1     /* batch 1, 2-bit groups by plane sums on the fp8/fp4 matrix instruction */
+#define MPQ_KERNEL_GEMV_DECODE 2     /* batch 1, every weight decoded */
+#define MPQ_KERNEL_BATCH_RESIDENT 3  /* batch with all activations resident on chip */
+#define MPQ_KERNEL_BATCH_RANGES 4    /* batch by K ranges through the workspace (two launches) */
+
+/* What a planned call enqueued. */
+typedef struct {
+  int32_t kernel;               /* MPQ_KERNEL_* of the (last) product kernel */
+  int32_t launches;             /* kernel launches enqueued by the call */
+  int32_t waves;                /* waves per workgroup */
+  int32_t tiles_per_workgroup;  /* M = 1 kernels; tiles per group for the K-range kernel; else 0 */
+  int32_t workgroups;
+  int32_t reserved[3];
+} mpq_report;
+
+/* mpq_gemm under a plan (NULL = none), reporting what ran (report may be NULL).  Same contract as
+ * mpq_gemm otherwise; mpq_gemm and mpq_gemv are this call with NULL, NULL. */
+mpq_status mpq_gemm_planned(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                            int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream,
+                            const mpq_plan* plan, mpq_report* report);
+
+/* mpq_gemm_workspace_size for a call under `plan` (the number of K ranges is a plan field). */
+mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, const mpq_plan* plan, size_t* bytes);
 
 #ifdef __cplusplus
 }

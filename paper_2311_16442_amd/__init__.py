@@ -24,8 +24,10 @@ STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ
 (MPQ_OK, MPQ_ERR_NULL, MPQ_ERR_SHAPE, MPQ_ERR_ALIGN, MPQ_ERR_CODE_RANGE, MPQ_ERR_OUTLIER_IN_4BIT,
  MPQ_ERR_CSR, MPQ_ERR_BLOB, MPQ_ERR_SIZE, MPQ_ERR_UNSUPPORTED, MPQ_ERR_HIP) = range(11)
 
-EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_quantize_host", "mpq_packed_size", "mpq_pack_host", "mpq_blob_info",
-           "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm_workspace_size", "mpq_gemm"]
+EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_quantize_host", "mpq_quantize_outlier_capacity", "mpq_packed_size",
+           "mpq_pack_host", "mpq_blob_info", "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm_workspace_size",
+           "mpq_gemm", "mpq_gemm_planned", "mpq_gemm_workspace_size_planned"]
+(KERNEL_GEMV_PLANES, KERNEL_GEMV_DECODE, KERNEL_BATCH_RESIDENT, KERNEL_BATCH_RANGES) = (1, 2, 3, 4)
 MAX_MULTI = 8
 
 
@@ -39,6 +41,19 @@ class MpqError(RuntimeError):
 class Desc(C.Structure):
     _fields_ = [("N", C.c_int32), ("K", C.c_int32), ("g1", C.c_int32), ("g2", C.c_int32),
                 ("g2_axis", C.c_int32)]
+
+
+class Plan(C.Structure):
+    """mpq_plan: 0 in a field = the library's own choice."""
+    _fields_ = [(n, C.c_int32) for n in ("gemv_path", "gemv_waves", "gemv_tiles", "batch_waves", "max_workgroups",
+                                         "large_batch", "lb_min_ranges", "lb_tiles", "lb_older16")] + \
+               [("reserved", C.c_int32 * 7)]
+
+
+class Report(C.Structure):
+    """mpq_report: what a planned call enqueued."""
+    _fields_ = [(n, C.c_int32) for n in ("kernel", "launches", "waves", "tiles_per_workgroup", "workgroups")] + \
+               [("reserved", C.c_int32 * 3)]
 
 
 class LogicalOutPtrs(C.Structure):
@@ -95,6 +110,13 @@ def lib():
                                C.c_void_p]
         L.mpq_gemm_workspace_size.restype = C.c_int
         L.mpq_gemm_workspace_size.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
+        L.mpq_gemm_planned.restype = C.c_int
+        L.mpq_gemm_planned.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t,
+                                       C.c_void_p, C.POINTER(Plan), C.POINTER(Report)]
+        L.mpq_gemm_workspace_size_planned.restype = C.c_int
+        L.mpq_gemm_workspace_size_planned.argtypes = [C.c_void_p, C.c_int32, C.POINTER(Plan), C.POINTER(C.c_size_t)]
+        L.mpq_quantize_outlier_capacity.restype = C.c_int
+        L.mpq_quantize_outlier_capacity.argtypes = [C.POINTER(Desc), C.c_int32, C.c_double, C.POINTER(C.c_int64)]
         _lib = L
     return _lib
 
@@ -139,7 +161,10 @@ def quantize(W, g1, g2, n4, p_o, g2_axis=0) -> dict:
     if g1 <= 0 or g2 <= 0 or K % g1 != 0 or not 0 <= n4 <= K // g1 or not 0.0 <= p_o <= 1.0:
         raise MpqError(MPQ_ERR_SHAPE, "mpq_quantize_host")
     G = K // g1
-    cap = N * int(np.floor(p_o * (G - n4) * g1 + 0.5))
+    cap_c = C.c_int64(0)
+    _check(lib().mpq_quantize_outlier_capacity(C.byref(d), int(n4), float(p_o), C.byref(cap_c)),
+           "mpq_quantize_outlier_capacity")
+    cap = int(cap_c.value)
     shape2 = (N, -(-G // g2)) if g2_axis == 0 else (-(-N // g2), G)
     out = dict(is4=np.zeros(G, np.uint8), codes=np.zeros((N, K), np.uint8), s_int=np.zeros((N, G), np.uint8),
                z1=np.zeros((N, G), np.uint8), s2=np.zeros(shape2, np.uint16), z2=np.zeros(shape2, np.uint16),
@@ -254,6 +279,26 @@ def gemm_workspace_size(header, M) -> int:
     h, hp = _hdr_ptr(header)
     n = C.c_size_t(0)
     _check(lib().mpq_gemm_workspace_size(hp, int(M), C.byref(n)), "mpq_gemm_workspace_size")
+    return int(n.value)
+
+
+def gemm_planned(header, blob_dev, X_dev, Y_dev, M, plan=None, stream=None, workspace=None) -> Report:
+    """mpq_gemm_planned: `plan` is a Plan (or None); returns the Report of what was enqueued."""
+    h, hp = _hdr_ptr(header)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rep = Report()
+    _check(lib().mpq_gemm_planned(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M), ws_ptr, ws_bytes,
+                                  _stream_ptr(stream), C.byref(plan) if plan is not None else None, C.byref(rep)),
+           "mpq_gemm_planned")
+    return rep
+
+
+def gemm_workspace_size_planned(header, M, plan=None) -> int:
+    h, hp = _hdr_ptr(header)
+    n = C.c_size_t(0)
+    _check(lib().mpq_gemm_workspace_size_planned(hp, int(M), C.byref(plan) if plan is not None else None, C.byref(n)),
+           "mpq_gemm_workspace_size_planned")
     return int(n.value)
 
 

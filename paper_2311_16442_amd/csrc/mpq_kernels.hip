@@ -1086,6 +1086,333 @@ mpq_gemv_multi_kernel(const MultiArgs a) {
   gemv_workgroup<PD, LDSB, WV, PU>(b, a.X[p], a.Y[p], 1, blockIdx.x - a.first[p]);
 }
 
+// ------------------------------------------------------------------------------------ GEMV, plane sums
+//
+// y = W x at batch 1 (Algorithm 1 + Sec. 4.3) with the 2-bit groups evaluated WITHOUT decoding a
+// single weight, bit-identical in its use of the per-weight fp16 rounding of eq. 5:
+//
+//   A 2-bit code c of (row, group) decodes to one of four fp16 numbers T[c] = fp16((c - z1) * s1).
+//   With b0, b1 the bits of c and g(c) = {0, 1, 2, 4}[c] = b0 + 2 b1 + b0 b1,
+//       T[c] = T0 + (T1 - T0) b0 + (T2 - T0) b1 + (T3 - T2 - T1 + T0) b0 b1,
+//   so the group's part of the row sum is
+//       T0 A + (e1 - d) S0 + (e2 / 2 - d) S1 + d Sg,   e1 = T1 - T0, e2 = T2 - T0, d = T3 - T2 - e1,
+//       A = sum x_k,  S0 = sum b0 x_k,  S1 = sum 2 b1 x_k,  Sg = sum g(c_k) x_k   over the group's columns.
+//   The four T are computed exactly as the definition rounds them; only the order of the fp32
+//   additions differs from a per-weight loop.
+//
+//   S0, S1, Sg come from v_mfma_scale_f32_16x16x128_f8f6f4.  Its B operand is fp4 (E2M1): the blob
+//   keeps the two bits of a code in the two exponent bits of a nibble (mpq_format.h), so
+//   dword & 0x22222222 / 0x44444444 / 0x66666666 are eight fp4 numbers b0 / 2 b1 / g(c) each - three
+//   vector instructions per 8 weights and plane, none per weight.  Lane (j, i) of a block holds unit j
+//   of row i = 32 nibbles = the instruction's contraction slots 32 j .. 32 j + 31 of column i; the
+//   last 32 columns of the unit are the same nibbles of the dword rotated right by 2.
+//   Its A operand is fp8 (E4M3): the activations, split once per workgroup into three pieces
+//   x = p0 + p1 + p2 (each the fp8 rounding of what the previous ones left: 12 significant bits, exact
+//   for fp16 inputs), scaled per 64-column unit by a power of two that the instruction's per-block
+//   scale operand undoes.  Row 4 g + p of A holds piece p of unit g on the slots of unit g and zeros
+//   elsewhere, so D[4 g + p][i] = sum over unit g of piece p times plane: lane (j, i) of the result
+//   holds, in its four registers, the three piece sums of ITS unit and row.  The instruction adds
+//   products in a window of about 14 bits below the largest product of a dot product before the
+//   fp32 accumulate; every piece has 4 significant bits, so columns within 2^-10 of the largest of
+//   their 32-column half unit are exact.  Activations must be finite.
+//
+//   4-bit groups have 16 values per (row, group); they take the per-weight decode and the f16 matrix
+//   instruction as in the other kernels.
+//
+// Data movement.  No request of a wave depends on data another request brings: code blocks and the
+// (s_int, z1), (s2, z2) words of their lanes travel together into a per-wave ring (three direct
+// global->LDS loads per block, addresses from unit table entries read through the scalar cache), so a wave
+// issues its first blocks in its first instructions.  A workgroup of WV waves owns n consecutive
+// tiles and treats their blocks as one sequence dealt round-robin to its waves; the activations are
+// staged and split once per workgroup while the first blocks are in flight.  Outliers of tile t are
+// summed by wave t from a record the wave fetched for itself.  Three barriers per workgroup.
+typedef int v8i_s __attribute__((ext_vector_type(8)));
+struct PlanePlan {
+  uint32_t off_park, off_units, off_xs, off_utab, off_pieces, off_zero, off_obuf;  // LDS byte offsets (ring at 0)
+  uint32_t obuf_bytes;  // outlier record of a tile: 128 + 4 * ocap
+  uint32_t n;           // tiles per workgroup (<= WV)
+};
+struct PlaneArgs {
+  DevBlob b;
+  const uint16_t* X;
+  uint16_t* Y;
+  PlanePlan pl;
+};
+
+// The table entries (2 dwords each) of the four units of block c through the scalar data cache: the
+// address is wave-uniform, and a vector load here would count against the hand-written vmcnt waits.
+__device__ __forceinline__ v8i_s unit_entries(const unsigned char* units, uint32_t c) {
+  v8i_s e;
+  asm volatile("s_load_dwordx8 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(e) : "s"(units), "s"(c * 32u) : "memory");
+  return e;
+}
+
+typedef int v8i_t __attribute__((ext_vector_type(8)));
+typedef short short2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float quad_add(float v) {  // sum over the 4 lanes of a quad, all lanes get it
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));  // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));  // quad_perm [2,3,0,1]
+  return v;
+}
+__device__ __forceinline__ uint32_t quad_max(uint32_t v) {
+  uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xf, 0xf, true);
+  v = v > o ? v : o;
+  o = (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xf, 0xf, true);
+  return v > o ? v : o;
+}
+
+template <int LDSB, int WV>
+__global__ void __launch_bounds__(WV * 64)
+mpq_gemvp_kernel(const PlaneArgs a) {
+#pragma clang fp contract(off)
+  constexpr uint32_t W = WV, PD = 2, SLOTB = 1536, OPS = 3;
+  __shared__ __align__(16) unsigned char lds[LDSB];
+  const DevBlob& b = a.b;
+  const PlanePlan& pl = a.pl;
+  const uint32_t tid = threadIdx.x;
+  const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
+  const uint32_t C = b.C, T = b.T, B2 = b.B2;
+  const uint32_t tile0 = blockIdx.x * pl.n;
+  const uint32_t n = T - tile0 < pl.n ? T - tile0 : pl.n;
+  float* const red = (float*)(lds + pl.off_park);  // [n][2 W + 1][16]
+  unsigned char* const units = lds + pl.off_units;
+  unsigned char* const xs = lds + pl.off_xs;
+  unsigned char* const utab = lds + pl.off_utab;
+  unsigned char* const pieces = lds + pl.off_pieces;
+  const DecodeConsts kc = make_consts();
+
+  // ---- (1) requests, oldest first: activations, unit table, this wave's outlier record, first blocks
+  const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
+  dma_linear<W>((const unsigned char*)a.X, lds_addr(xs), 2u * b.K, wv, lane16);
+  dma_linear<W>(b.units, lds_addr(units), 32u * C, wv, lane16);
+  if (wv < n) {
+    const unsigned char* rec = tileptr + (size_t)wv * b.tile_stride + b.off_ot;
+    const uint32_t dst = lds_addr(lds + pl.off_obuf) + wv * pl.obuf_bytes;
+    for (uint32_t off = 0; off < pl.obuf_bytes; off += 1024u)
+      if (off + lane16 < pl.obuf_bytes) dma16(rec + off, lane16, dst + off);
+  }
+  const uint32_t ring0 = lds_addr(lds) + wv * (PD * SLOTB);
+  const uint32_t m1lane = i * 2u, m2lane = b.off_m2 + (i >> b.m2_shift) * 4u;
+  const unsigned char* rbase = tileptr;  // record of the tile being requested
+  uint32_t rc = wv, rt = 0;              // next request: block rc of tile rt (rt = n: none left)
+  while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
+  uint32_t inflight = 0;
+#define MPQ_P_REQUEST(SLOT)                                                            \
+  {                                                                                    \
+    const uint32_t dst = ring0 + (SLOT) * SLOTB;                                       \
+    dma16(rbase + b.codes_off + rc * 1024u, lane16, dst);                              \
+    const v8i_s ue4 = unit_entries(b.units, __builtin_amdgcn_readfirstlane(rc));       \
+    const uint32_t uy = (uint32_t)(j == 0 ? ue4[1] : j == 1 ? ue4[3] : j == 2 ? ue4[5] : ue4[7]); \
+    dma4(rbase, ((uy & 0xFFFFu) + m1lane) & ~3u, dst + 1024u);                         \
+    dma4(rbase, m2lane + (uy >> 16), dst + 1280u);                                     \
+    ++inflight;                                                                        \
+    rc += W;                                                                           \
+    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }               \
+  }
+#pragma unroll
+  for (uint32_t r = 0; r < PD; ++r)
+    if (rt < n) MPQ_P_REQUEST(r)
+  if (tid < 32) ((uint32_t*)(lds + pl.off_zero))[tid] = 0u;  // what inactive lanes of the A operand read
+  wait_vm((int)(OPS * inflight));  // everything older than the block requests has landed
+  lds_barrier();
+
+  // ---- (2) split the activations of every 2-bit unit into three fp8 pieces, in the order of the
+  //      instruction's contraction slots: item = (unit, half of the columns, 16 of its slots)
+  {
+    const uint32_t items = 16u * B2;
+    for (uint32_t it = tid; it < items; it += W * 64u) {
+      const uint32_t u = it >> 2, pass = (it >> 1) & 1u, h = it & 1u;
+      const uint2 ue = *(const uint2*)(units + u * 8u);
+      const bool real = (ue.y & 0xFFFFu) != 32u * (uint32_t)b.G;  // padding units point at the zero entries
+      // slot 8 d + nn of the half unit <-> column 8 (nn % 4) + 2 d + nn / 4: dword (d, nn % 4) of the
+      // activations holds the columns of nibbles nn % 4 (low half) and nn % 4 + 4 (high half)
+      uint32_t xp[2][4];
+#pragma unroll
+      for (uint32_t dd = 0; dd < 2; ++dd)
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q)
+          xp[dd][q] = real ? *(const uint32_t*)(xs + ue.x + 64u * pass + 16u * q + 4u * (2u * h + dd)) : 0u;
+      float sum = 0.f;
+      uint32_t mx = 0;
+#pragma unroll
+      for (uint32_t dd = 0; dd < 2; ++dd)
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+          const half2_t v = as_h2(xp[dd][q]);
+          sum += (float)v.x;
+          sum += (float)v.y;
+          const uint32_t ab = xp[dd][q] & 0x7FFF7FFFu;
+          const uint32_t m16 = (ab >> 16) > (ab & 0xFFFFu) ? (ab >> 16) : (ab & 0xFFFFu);
+          mx = m16 > mx ? m16 : mx;
+        }
+      sum = quad_add(sum);   // the four items of a unit sit in the four lanes of a quad
+      mx = quad_max(mx);
+      uint32_t E = mx >> 10;  // exponent field of the largest magnitude of the unit
+      E = E < 1u ? 1u : E > 30u ? 30u : E;
+      // x' = x * 2^(15 - E): the largest is in [1, 2); pieces are fp8(x' 2^7), fp8(rest 2^11), fp8(rest 2^15)
+      const uint32_t mbits = E < 30u ? (30u - E) << 10 : 0x0200u;
+      const half2_t mult = as_h2(mbits | (mbits << 16));
+      uint32_t pc[3][2][2];  // [piece][dd][pairs 0,1 | pairs 2,3]: bytes = pair a low, a high, b low, b high
+#pragma unroll
+      for (uint32_t dd = 0; dd < 2; ++dd)
+#pragma unroll
+        for (uint32_t qq = 0; qq < 2; ++qq) {
+          short2_t q0 = {0, 0}, q1 = {0, 0}, q2 = {0, 0};
+          // ENC(v, s) = fp8(v / s) of both halves of v into the low or high word; DEC(p, s) = p * s
+#define MPQ_P_SPLIT(PAIR, HI)                                                                         \
+  {                                                                                                   \
+    const half2_t x1 = as_h2(xp[dd][PAIR]) * mult;                                                    \
+    q0 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q0, x1, 0.0078125f, HI);                            \
+    half2_t d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(__builtin_bit_cast(int, q0), 0.0078125f, HI); \
+    half2_t r = x1 - d;                                                                               \
+    q1 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q1, r, 0.00048828125f, HI);                         \
+    d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(__builtin_bit_cast(int, q1), 0.00048828125f, HI);    \
+    r = r - d;                                                                                        \
+    q2 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q2, r, 0.000030517578125f, HI);                     \
+  }
+          MPQ_P_SPLIT(2 * qq, false)
+          MPQ_P_SPLIT(2 * qq + 1, true)
+#undef MPQ_P_SPLIT
+          pc[0][dd][qq] = (uint32_t)__builtin_bit_cast(int, q0);
+          pc[1][dd][qq] = (uint32_t)__builtin_bit_cast(int, q1);
+          pc[2][dd][qq] = (uint32_t)__builtin_bit_cast(int, q2);
+        }
+      // bytes of a piece chunk: slots 8 dd + 0..3 = low halves of pairs 0..3, 8 dd + 4..7 = their high halves
+#pragma unroll
+      for (uint32_t p = 0; p < 3; ++p) {
+        uint4 o;
+        o.x = __builtin_amdgcn_perm(pc[p][0][1], pc[p][0][0], 0x06040200u);
+        o.y = __builtin_amdgcn_perm(pc[p][0][1], pc[p][0][0], 0x07050301u);
+        o.z = __builtin_amdgcn_perm(pc[p][1][1], pc[p][1][0], 0x06040200u);
+        o.w = __builtin_amdgcn_perm(pc[p][1][1], pc[p][1][0], 0x07050301u);
+        *(uint4*)(pieces + u * 192u + pass * 96u + p * 32u + h * 16u) = o;
+      }
+      // per unit: the sum of its activations and the exponent byte of piece 0's scale, 2^(E - 22)
+      if ((it & 3u) == 0) *(uint2*)(utab + u * 8u) = uint2{__builtin_bit_cast(uint32_t, sum), 105u + E};
+    }
+  }
+
+  // ---- (3) outliers (Sec. 4.3, fused): wave t sums the record of tile t, four lanes per row
+  if (wv < n) {
+    const uint32_t* ostart = (const uint32_t*)(lds + pl.off_obuf + wv * pl.obuf_bytes);
+    const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
+    const uint32_t orow = lane >> 2, oq = lane & 3u;
+    const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
+    float oa = 0.f;
+    for (uint32_t e = rp0 + oq; e < rp1; e += 4) {
+      const uint32_t word = owords[e];
+      const float v = (float)bits_to_half((uint16_t)(word >> 16));
+      oa = __builtin_fmaf(v, (float)*(const half_t*)(xs + (word & 0xFFFFu) * 2u), oa);
+    }
+    oa = quad_add(oa);
+    if (oq == 0) red[(wv * (2 * W + 1) + 2 * W) * 16 + orow] = oa;
+  }
+  lds_barrier();
+
+  // ---- (4) this wave's blocks, in order
+  // A operand of lane (j, m = 4 g + p): piece p of unit g of the block on the 16 slots this lane
+  // covers (low 16 bytes: slots 16 j .. 16 j + 15, high 16 bytes: slots 64 + 16 j ..), zeros elsewhere
+  const uint32_t ga = i >> 2, pa = i & 3u;
+  const bool act = (j >> 1) == (ga & 1u) && pa < 3u;
+  const uint32_t chunk = ga * 192u + pa * 32u + (j & 1u) * 16u;
+  const uint32_t zoff = pl.off_zero - pl.off_pieces;
+  const uint32_t a_lo0 = act && ga < 2u ? chunk : zoff, a_lo1 = act && ga < 2u ? 768u : 0u;
+  const uint32_t a_hi0 = act && ga >= 2u ? chunk : zoff, a_hi1 = act && ga >= 2u ? 768u : 0u;
+  const int sc_lane = -4 * (int)pa;
+  const uint32_t slot_lane = ring0 + lane16, meta_lane = ring0 + 1024u + lane * 4u;
+  uint32_t slot = 0;
+  uint32_t c = wv;  // next block of this wave inside the current tile (>= C: none in this tile)
+  for (uint32_t t = 0; t < n; ++t) {
+    float yacc = 0.f;                        // row i, units j of this wave's 2-bit blocks
+    float4_t acc4 = {0.f, 0.f, 0.f, 0.f};    // this wave's 4-bit blocks (batch column 0 of the f16 instruction)
+#define MPQ_P_HEAD                                                                                     \
+    if (inflight == PD) MPQ_VMCNT(OPS * (PD - 1)); else MPQ_VMCNT(0);                                  \
+    uint4 q;                                                                                           \
+    uint32_t w1[1], w2[1];                                                                             \
+    ring_read<1, 1>(slot_lane + slot * SLOTB, meta_lane + slot * SLOTB, q, w1, w2);                    \
+    --inflight;                                                                                        \
+    if (rt < n) MPQ_P_REQUEST(slot)                                                                    \
+    slot = slot + 1 == PD ? 0 : slot + 1;                                                              \
+    const uint32_t m1 = (i & 1u) ? w1[0] >> 16 : w1[0] & 0xFFFFu;                                      \
+    const half_t s1 = scale_dequant(m1 & 0xFFu, w2[0]);  /* exactly 0 for a padding unit */            \
+    const half2_t s1p = {s1, s1};                                                                      \
+    const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  /* 1024 + z1 */
+    for (; c < B2; c += W) {
+      MPQ_P_HEAD
+      // the four values a code of this (row, unit) decodes to, rounded as eq. 5 rounds them
+      const half2_t zbp = {zb, zb};
+      const half2_t t01 = (half2_t{(half_t)1024.f, (half_t)1025.f} - zbp) * s1p;
+      const half2_t t23 = (half2_t{(half_t)1026.f, (half_t)1027.f} - zbp) * s1p;
+      const float T0 = (float)t01.x, e1 = (float)t01.y - T0, e2 = (float)t23.x - T0;
+      const float dl = ((float)t23.y - (float)t23.x) - e1;
+      const uint2 ut = *(const uint2*)(utab + (4u * c + j) * 8u);
+      const int sca = (int)ut.y + sc_lane;
+      const unsigned char* pb = pieces;
+      const uint4 ax0 = *(const uint4*)(pb + a_lo0 + c * a_lo1), ax1 = *(const uint4*)(pb + a_hi0 + c * a_hi1);
+      const uint4 ay0 = *(const uint4*)(pb + a_lo0 + c * a_lo1 + 96u), ay1 = *(const uint4*)(pb + a_hi0 + c * a_hi1 + 96u);
+      const v8i_t ax = {(int)ax0.x, (int)ax0.y, (int)ax0.z, (int)ax0.w, (int)ax1.x, (int)ax1.y, (int)ax1.z, (int)ax1.w};
+      const v8i_t ay = {(int)ay0.x, (int)ay0.y, (int)ay0.z, (int)ay0.w, (int)ay1.x, (int)ay1.y, (int)ay1.z, (int)ay1.w};
+      const uint32_t r0 = __builtin_amdgcn_alignbit(q.x, q.x, 2), r1 = __builtin_amdgcn_alignbit(q.y, q.y, 2);
+      const uint32_t r2 = __builtin_amdgcn_alignbit(q.z, q.z, 2), r3 = __builtin_amdgcn_alignbit(q.w, q.w, 2);
+#define MPQ_P_PLANE(MASK, X0, X1, X2, X3) \
+  v8i_t{(int)((X0) & (MASK)), (int)((X1) & (MASK)), (int)((X2) & (MASK)), (int)((X3) & (MASK)), 0, 0, 0, 0}
+      const float4_t z4 = {0.f, 0.f, 0.f, 0.f};
+      float4_t s0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ax, MPQ_P_PLANE(0x22222222u, q.x, q.y, q.z, q.w), z4, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+      float4_t sb = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ax, MPQ_P_PLANE(0x44444444u, q.x, q.y, q.z, q.w), z4, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+      float4_t sg = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ax, MPQ_P_PLANE(0x66666666u, q.x, q.y, q.z, q.w), z4, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+      s0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ay, MPQ_P_PLANE(0x22222222u, r0, r1, r2, r3), s0, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+      sb = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ay, MPQ_P_PLANE(0x44444444u, r0, r1, r2, r3), sb, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+      sg = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ay, MPQ_P_PLANE(0x66666666u, r0, r1, r2, r3), sg, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+#undef MPQ_P_PLANE
+      const float S0 = (s0[0] + s0[1]) + s0[2], S1 = (sb[0] + sb[1]) + sb[2], Sg = (sg[0] + sg[1]) + sg[2];
+      yacc = __builtin_fmaf(T0, __builtin_bit_cast(float, ut.x), yacc);
+      yacc = __builtin_fmaf(e1 - dl, S0, yacc);
+      yacc = __builtin_fmaf(__builtin_fmaf(0.5f, e2, -dl), S1, yacc);
+      yacc = __builtin_fmaf(dl, Sg, yacc);
+    }
+    for (; c < C; c += W) {
+      MPQ_P_HEAD
+      const uint32_t xoff = *(const uint32_t*)(units + (4u * c + j) * 8u);
+      const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+#define MPQ_P_STEP4(P)                                                                                \
+  {                                                                                                   \
+    const uint4 av = decode_step<false, P>(lo, hi, s1p, zb, kc);                                      \
+    const uint4 bv = *(const uint4*)(xs + xoff + 16 * (P));                                           \
+    acc4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
+                                                  __builtin_bit_cast(half8_t, bv), acc4, 0, 0, 0);    \
+  }
+      MPQ_P_STEP4(0) MPQ_P_STEP4(1) MPQ_P_STEP4(2) MPQ_P_STEP4(3)
+#undef MPQ_P_STEP4
+    }
+#undef MPQ_P_HEAD
+    c -= C;  // the sequence continues in the next tile
+    // park: rows of the 2-bit part summed over the four units of a block position (fixed order), and
+    // batch column 0 of the 4-bit accumulator (lane (j, 0) holds rows 4 j .. 4 j + 3)
+    float yr = yacc;
+    yr += __shfl_xor(yr, 16);
+    yr += __shfl_xor(yr, 32);
+    float* rt_ = red + t * (2 * W + 1) * 16;
+    if (j == 0) rt_[wv * 16 + i] = yr;
+    if (i == 0) *(float4_t*)(rt_ + (W + wv) * 16 + 4 * j) = acc4;
+  }
+#undef MPQ_P_REQUEST
+
+  lds_barrier();
+  // ---- (5) row r of tile t: the outlier term, then the partial sums in a fixed order
+  if (tid < 16 * n) {
+    const uint32_t t = tid >> 4, r = tid & 15u;
+    const float* rt0 = red + t * (2 * W + 1) * 16 + r;
+    float sum = rt0[2 * W * 16];
+#pragma unroll
+    for (uint32_t w2 = 0; w2 < 2 * W; ++w2) sum += rt0[w2 * 16];
+    const uint32_t row = (tile0 + t) * 16 + r;
+    if (row < (uint32_t)b.N) a.Y[row] = half_to_bits((half_t)sum);
+  }
+}
+
 // ------------------------------------------------------------------------------------ dequant
 //
 // Row-major fp16 copy of the dense part: W_out[n][k] = fp16((code - z1) * s1), bit-exact eq. 5.
@@ -1189,6 +1516,17 @@ mpq_outlier_add_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 
 namespace {
 
+const mpq_plan kAutoPlan = {};
+
+// Launch status of THIS launch only: an error some earlier HIP call of the caller left behind is
+// cleared before the launch and so neither reported as ours nor lost to a later check of theirs.
+#define MPQ_LAUNCH(...)                                                   \
+  do {                                                                    \
+    (void)hipGetLastError();                                              \
+    hipLaunchKernelGGL(__VA_ARGS__);                                      \
+    if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;              \
+  } while (0)
+
 mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, DevBlob* d) {
   if (!hdr_host || !blob_dev) return MPQ_ERR_NULL;
   mpq_status st = mpq_internal_check_header(hdr_host, h);
@@ -1210,6 +1548,36 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   return MPQ_OK;
 }
 
+// Compute units of the current device; the work splits are sized by it.
+mpq_status cu_count(int* cus) {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      n <= 0) {
+    (void)hipGetLastError();
+    return MPQ_ERR_HIP;
+  }
+  *cus = n;
+  return MPQ_OK;
+}
+
+struct Ctx {  // what every launcher needs
+  const MpqHeader& h;
+  const DevBlob& d;
+  const mpq_plan& plan;
+  mpq_report* report;
+  int cus;
+  hipStream_t s;
+};
+
+void note(const Ctx& c, int kernel, int launches, int waves, int tiles, long workgroups) {
+  if (!c.report) return;
+  c.report->kernel = kernel;
+  c.report->launches += launches;
+  c.report->waves = waves;
+  c.report->tiles_per_workgroup = tiles;
+  c.report->workgroups = (int32_t)workgroups;
+}
+
 // LDS bytes the batch kernel needs for M rows at ring depth PD: ring, reduction slots, two
 // side-record buffers, unit table, activation rows.
 size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, int waves = 4) {
@@ -1220,28 +1588,7 @@ size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, int waves = 4) {
 
 constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
 
-int g_max_blocks = 0;   // 0 = automatic
-int g_gemv_waves = 0;   // 0 = automatic (8 or 16 waves per workgroup of the GEMV)
-int g_gemv_tiles = 0;   // 0 = automatic (tiles per workgroup of the GEMV)
-int g_batch_waves = 0;  // 0 = automatic (16, 8 or 4 waves per workgroup of the persistent batch kernel)
-int g_slices = -1;      // -1 = automatic, 1 = large-batch kernel for every M > 1, 0 = never
-int g_slice_min_h = 0;  // least number of ranges of the large-batch kernel (tests: several ranges on small matrices)
-int g_slice_launches = 0;
-int g_slice_older = 0;  // 0 = automatic (10): sixteenths of a SIMD's blocks that go to the older of its two waves
-int g_slice_tiles = 0;  // 0 = automatic (tiles per group of the large-batch kernel, 1..8)
-int g_cu_count = 0;
-
-int cu_count() {
-  if (g_cu_count == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
-      (void)hipGetLastError();
-      n = 256;
-    }
-    g_cu_count = n;
-  }
-  return g_cu_count;
-}
+// ---------------------------------------------------------------- M = 1, per-weight decode kernel
 
 // LDS bytes of the GEMV kernel: ring, partial sums, n side records, unit table, activations.
 size_t gemv_lds_bytes(const MpqHeader& h, int PD, int waves, int n) {
@@ -1250,149 +1597,219 @@ size_t gemv_lds_bytes(const MpqHeader& h, int PD, int waves, int n) {
 }
 
 template <int PD, int LDSB, int WV, int PU>
-mpq_status launch_gemv(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
-  const unsigned grid = (unsigned)((h.T + n - 1) / n);
-  hipLaunchKernelGGL((mpq_gemv_kernel<PD, LDSB, WV, PU>), dim3(grid), dim3(WV * 64), 0, s, d, X, Y, n);
-  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+mpq_status launch_gemv(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
+  const unsigned grid = (unsigned)((c.h.T + n - 1) / n);
+  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU>), dim3(grid), dim3(WV * 64), 0, c.s, c.d, X, Y, n);
+  note(c, MPQ_KERNEL_GEMV_DECODE, 1, WV, n, grid);
+  return MPQ_OK;
 }
 
 // GEMV with WV waves per workgroup and n tiles per workgroup in the smallest LDS class that holds
 // it.  Two code blocks per wave in flight: deeper rings were measured and change nothing.
 template <int WV, int PU>
-mpq_status gemv_class(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
-  const size_t need = gemv_lds_bytes(h, 2, WV, n);
-  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU>(h, d, X, Y, n, s);
-  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU>(h, d, X, Y, n, s);
-  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV, PU>(h, d, X, Y, n, s);
-  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU>(h, d, X, Y, n, s);
-  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU>(h, d, X, Y, n, s);
+mpq_status gemv_class(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
+  const size_t need = gemv_lds_bytes(c.h, 2, WV, n);
+  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU>(c, X, Y, n);
+  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU>(c, X, Y, n);
+  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV, PU>(c, X, Y, n);
+  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU>(c, X, Y, n);
+  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU>(c, X, Y, n);
   return MPQ_ERR_UNSUPPORTED;
 }
 
 template <int WV>
-mpq_status gemv_waves(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int n, hipStream_t s) {
-  switch (mpq_pu2(h.g1)) {  // first-order groups per 2-bit unit
-    case 1: return gemv_class<WV, 1>(h, d, X, Y, n, s);
-    case 2: return gemv_class<WV, 2>(h, d, X, Y, n, s);
-    default: return gemv_class<WV, 4>(h, d, X, Y, n, s);
+mpq_status gemv_waves(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
+  switch (mpq_pu2(c.h.g1)) {  // first-order groups per 2-bit unit
+    case 1: return gemv_class<WV, 1>(c, X, Y, n);
+    case 2: return gemv_class<WV, 2>(c, X, Y, n);
+    default: return gemv_class<WV, 4>(c, X, Y, n);
   }
 }
 
-// Work split of the GEMV (waves per workgroup, tiles per workgroup), from measurements on the
-// Llama2-7B / Llama3-8B / Llama2-70B shapes:
+// Work split of the per-weight GEMV (waves per workgroup, tiles per workgroup), from measurements on
+// the Llama2-7B / Llama3-8B / Llama2-70B shapes:
 //   - up to 1.5 tiles per compute unit: 16 waves on one tile, so that every SIMD has several waves;
 //   - else 8 waves on one tile if four such workgroups fit a compute unit (all 32 wave slots busy
 //     and the most workgroups to balance);
 //   - else (long rows: the staged activations crowd the LDS) 16 waves on two tiles when the
 //     workgroups still spread evenly over the compute units, which halves the staging per tile.
-mpq_status gemv_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, hipStream_t s) {
-  const int cus = cu_count();
+mpq_status gemv_decode(const Ctx& c, const uint16_t* X, uint16_t* Y) {
+  const MpqHeader& h = c.h;
   int waves, n = 1;
-  if (2 * h.T <= 3 * cus) {
+  if (2 * h.T <= 3 * c.cus) {
     waves = 16;
   } else if (gemv_lds_bytes(h, 2, 8, 1) <= 40 * 1024) {
     waves = 8;
   } else {
     const int half = (h.T + 1) / 2;
-    if ((half % cus == 0 || half >= 4 * cus) && gemv_lds_bytes(h, 2, 16, 2) <= kLdsPerCu) {
+    if ((half % c.cus == 0 || half >= 4 * c.cus) && gemv_lds_bytes(h, 2, 16, 2) <= kLdsPerCu) {
       waves = 16;
       n = 2;
     } else {
       waves = gemv_lds_bytes(h, 2, 8, 1) <= 53 * 1024 ? 8 : 16;
     }
   }
-  if (g_gemv_waves > 0) waves = g_gemv_waves;
-  if (g_gemv_tiles > 0) n = g_gemv_tiles > 8 ? 8 : g_gemv_tiles;
+  if (c.plan.gemv_waves > 0) waves = c.plan.gemv_waves;
+  if (c.plan.gemv_tiles > 0) n = c.plan.gemv_tiles > 8 ? 8 : c.plan.gemv_tiles;
   while (n > 1 && gemv_lds_bytes(h, 2, waves, n) > kLdsPerCu) --n;
   if (waves == 16) {
-    const mpq_status st = gemv_waves<16>(h, d, X, Y, n, s);
+    const mpq_status st = gemv_waves<16>(c, X, Y, n);
     if (st != MPQ_ERR_UNSUPPORTED) return st;
   }
-  return gemv_waves<8>(h, d, X, Y, n, s);
+  return gemv_waves<8>(c, X, Y, n);
 }
+
+// ---------------------------------------------------------------- M = 1, plane-sum kernel
+
+// LDS layout of the plane-sum GEMV for n tiles per workgroup of W waves; false if it does not fit.
+bool plane_layout(const MpqHeader& h, uint32_t W, uint32_t n, uint32_t budget, PlanePlan* pl) {
+  const uint32_t C = (uint32_t)(h.B2 + h.B4);
+  uint32_t off = W * 2u * 1536u;                        // ring: two slots of codes + two meta words per lane
+  pl->off_park = off;   off += n * (2u * W + 1u) * 64u;
+  pl->off_units = off;  off += 32u * C;                  // unit table
+  off = (off + 15u) & ~15u;
+  pl->off_xs = off;     off += (2u * (uint32_t)h.K + 15u) & ~15u;
+  pl->off_utab = off;   off += 32u * (uint32_t)h.B2;     // 8 bytes per 2-bit unit
+  pl->off_pieces = off; off += 768u * (uint32_t)h.B2;    // 192 bytes per 2-bit unit
+  pl->off_zero = off;   off += 128u;
+  pl->obuf_bytes = MPQ_OTILE_HEAD + 4u * (uint32_t)h.ocap;
+  pl->off_obuf = off;   off += n * pl->obuf_bytes;
+  pl->n = n;
+  return off <= budget;
+}
+
+template <int LDSB, int WV>
+mpq_status launch_planes(const Ctx& c, PlaneArgs& a) {
+  const unsigned grid = (unsigned)((c.h.T + a.pl.n - 1) / a.pl.n);
+  MPQ_LAUNCH((mpq_gemvp_kernel<LDSB, WV>), dim3(grid), dim3(WV * 64), 0, c.s, a);
+  note(c, MPQ_KERNEL_GEMV_PLANES, 1, WV, (int)a.pl.n, grid);
+  return MPQ_OK;
+}
+
+// The plane-sum kernel needs one first-order group per unit (g1 >= 64) and room in the LDS for the
+// split activations; MPQ_ERR_UNSUPPORTED otherwise.
+mpq_status gemv_planes(const Ctx& c, const uint16_t* X, uint16_t* Y) {
+  const MpqHeader& h = c.h;
+  if (mpq_pu2(h.g1) != 1) return MPQ_ERR_UNSUPPORTED;
+  const uint32_t W = c.plan.gemv_waves == 8 ? 8u : 16u;
+  // tiles per workgroup: one generation of workgroups if the LDS allows it, at most W (wave t sums the
+  // outliers of tile t), else the smallest number of equal generations
+  uint32_t n = c.plan.gemv_tiles > 0 ? (uint32_t)c.plan.gemv_tiles : ((uint32_t)h.T + (uint32_t)c.cus - 1u) / (uint32_t)c.cus;
+  if (n > W) n = W;
+  PlaneArgs a;
+  a.b = c.d;
+  a.X = X;
+  a.Y = Y;
+  if (c.plan.gemv_tiles <= 0) {
+    uint32_t gens = 1;
+    while (true) {
+      n = ((uint32_t)h.T + gens * (uint32_t)c.cus - 1u) / (gens * (uint32_t)c.cus);
+      if (n <= W && plane_layout(h, W, n, 160 * 1024, &a.pl)) break;
+      if (n <= 1) return MPQ_ERR_UNSUPPORTED;
+      ++gens;
+    }
+  } else if (!plane_layout(h, W, n, 160 * 1024, &a.pl)) {
+    return MPQ_ERR_UNSUPPORTED;
+  }
+  uint32_t need = a.pl.off_obuf + a.pl.n * a.pl.obuf_bytes;
+  if (W == 16) {
+    if (need <= 80 * 1024) return launch_planes<80 * 1024, 16>(c, a);
+    return launch_planes<160 * 1024, 16>(c, a);
+  }
+  if (need <= 53 * 1024) return launch_planes<53 * 1024, 8>(c, a);
+  if (need <= 80 * 1024) return launch_planes<80 * 1024, 8>(c, a);
+  return launch_planes<160 * 1024, 8>(c, a);
+}
+
+// ---------------------------------------------------------------- 2 <= M <= 32
 
 // Persistent batch kernel with WV waves per workgroup; one or two workgroups per compute unit.
 template <int NT, int PD, int LDSB, int WV, int PU = 1>
-mpq_status launch_batch(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+mpq_status launch_batch(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   size_t per_cu = kLdsPerCu / LDSB;
   if (per_cu * WV > 32) per_cu = 32 / WV;
   if (per_cu < 1) per_cu = 1;
-  long grid = (long)cu_count() * (long)per_cu;
-  if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
-  if (grid > h.T) grid = h.T;
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, WV, PU>), dim3((unsigned)grid), dim3(WV * 64), 0, s, d, X, Y, M);
-  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+  long grid = (long)c.cus * (long)per_cu;
+  if (c.plan.max_workgroups > 0 && grid > c.plan.max_workgroups) grid = c.plan.max_workgroups;
+  if (grid > c.h.T) grid = c.h.T;
+  MPQ_LAUNCH((mpq_mm_kernel<NT, PD, LDSB, WV, PU>), dim3((unsigned)grid), dim3(WV * 64), 0, c.s, c.d, X, Y, M);
+  note(c, MPQ_KERNEL_BATCH_RESIDENT, 1, WV, 0, grid);
+  return MPQ_OK;
 }
 
 // Persistent batch kernel with 4 waves per workgroup (the most workgroups per compute unit).
 template <int NT, int PD, int LDSB, int PU = 1>
-mpq_status launch_mm(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+mpq_status launch_mm(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   size_t per_cu = kLdsPerCu / LDSB;  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
   if (per_cu > 8) per_cu = 8;
   if (per_cu < 1) per_cu = 1;
-  long grid = (long)cu_count() * (long)per_cu;
-  if (g_max_blocks > 0 && grid > g_max_blocks) grid = g_max_blocks;
-  if (grid > h.T) grid = h.T;
-  hipLaunchKernelGGL((mpq_mm_kernel<NT, PD, LDSB, 4, PU>), dim3((unsigned)grid), dim3(256), 0, s, d, X, Y, M);
-  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+  long grid = (long)c.cus * (long)per_cu;
+  if (c.plan.max_workgroups > 0 && grid > c.plan.max_workgroups) grid = c.plan.max_workgroups;
+  if (grid > c.h.T) grid = c.h.T;
+  MPQ_LAUNCH((mpq_mm_kernel<NT, PD, LDSB, 4, PU>), dim3((unsigned)grid), dim3(256), 0, c.s, c.d, X, Y, M);
+  note(c, MPQ_KERNEL_BATCH_RESIDENT, 1, 4, 0, grid);
+  return MPQ_OK;
 }
 
 // Static LDS size classes of the product kernel; each has the ring depth that keeps enough bytes
 // in flight for the number of workgroups that fit a compute unit.
 template <int NT>
-mpq_status mm_chunk(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, hipStream_t s) {
+mpq_status mm_chunk(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
+  const MpqHeader& h = c.h;
+  const int bw = c.plan.batch_waves;
   if (mpq_pu2(h.g1) > 1) {
     // first-order groups shorter than a unit (g1 = 16, 32): persistent workgroups in a few classes
     const bool four = mpq_pu2(h.g1) == 4;
 #define MPQ_PIECES(CALL2, CALL4) return four ? CALL4 : CALL2
     if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024)
-      MPQ_PIECES((launch_batch<NT, 2, 80 * 1024, 8, 2>(h, d, X, Y, M, s)), (launch_batch<NT, 2, 80 * 1024, 8, 4>(h, d, X, Y, M, s)));
+      MPQ_PIECES((launch_batch<NT, 2, 80 * 1024, 8, 2>(c, X, Y, M)), (launch_batch<NT, 2, 80 * 1024, 8, 4>(c, X, Y, M)));
     if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024)
-      MPQ_PIECES((launch_batch<NT, 3, 160 * 1024, 8, 2>(h, d, X, Y, M, s)), (launch_batch<NT, 3, 160 * 1024, 8, 4>(h, d, X, Y, M, s)));
+      MPQ_PIECES((launch_batch<NT, 3, 160 * 1024, 8, 2>(c, X, Y, M)), (launch_batch<NT, 3, 160 * 1024, 8, 4>(c, X, Y, M)));
     if (mm_lds_bytes(h, M, 3) <= 160 * 1024)
-      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, 2>(h, d, X, Y, M, s)), (launch_mm<NT, 3, 160 * 1024, 4>(h, d, X, Y, M, s)));
+      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, 2>(c, X, Y, M)), (launch_mm<NT, 3, 160 * 1024, 4>(c, X, Y, M)));
 #undef MPQ_PIECES
     return MPQ_ERR_UNSUPPORTED;
   }
-  if (g_batch_waves != 4) {
+  if (bw != 4) {
     // many waves share one copy of the activations: 16 (or 8) waves per workgroup
-    if (g_batch_waves != 8) {
-      if (mm_lds_bytes(h, M, 2, 16) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 16>(h, d, X, Y, M, s);
+    if (bw != 8) {
+      if (mm_lds_bytes(h, M, 2, 16) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 16>(c, X, Y, M);
       // one workgroup of 16 waves per compute unit, unless two of 8 waves fit and the matrix has the
       // tiles to feed them: two independent workgroups lose less at the barriers of every tile
       // (measured: 13-14 % on the 12288x4096 and 22016x4096 matrices at M = 4)
-      const bool two_of_8 = g_batch_waves == 0 && mm_lds_bytes(h, M, 2, 8) <= 80 * 1024 && 2 * h.T >= 3 * cu_count();
-      if (!two_of_8 && mm_lds_bytes(h, M, 2, 16) <= 160 * 1024) return launch_batch<NT, 2, 160 * 1024, 16>(h, d, X, Y, M, s);
+      const bool two_of_8 = bw == 0 && mm_lds_bytes(h, M, 2, 8) <= 80 * 1024 && 2 * h.T >= 3 * c.cus;
+      if (!two_of_8 && mm_lds_bytes(h, M, 2, 16) <= 160 * 1024) return launch_batch<NT, 2, 160 * 1024, 16>(c, X, Y, M);
     }
-    if (mm_lds_bytes(h, M, 2, 8) <= 53 * 1024) return launch_batch<NT, 2, 53 * 1024, 8>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 8>(h, d, X, Y, M, s);
-    if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024) return launch_batch<NT, 3, 160 * 1024, 8>(h, d, X, Y, M, s);
+    if (mm_lds_bytes(h, M, 2, 8) <= 53 * 1024) return launch_batch<NT, 2, 53 * 1024, 8>(c, X, Y, M);
+    if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 8>(c, X, Y, M);
+    if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024) return launch_batch<NT, 3, 160 * 1024, 8>(c, X, Y, M);
   }
-  if (mm_lds_bytes(h, M, 3) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 3) <= 40 * 1024) return launch_mm<NT, 3, 40 * 1024>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 4) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 6) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 8) <= 160 * 1024) return launch_mm<NT, 8, 160 * 1024>(h, d, X, Y, M, s);
-  if (mm_lds_bytes(h, M, 3) <= 160 * 1024) return launch_mm<NT, 3, 160 * 1024>(h, d, X, Y, M, s);
+  if (mm_lds_bytes(h, M, 3) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024>(c, X, Y, M);
+  if (mm_lds_bytes(h, M, 3) <= 40 * 1024) return launch_mm<NT, 3, 40 * 1024>(c, X, Y, M);
+  if (mm_lds_bytes(h, M, 4) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024>(c, X, Y, M);
+  if (mm_lds_bytes(h, M, 6) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024>(c, X, Y, M);
+  if (mm_lds_bytes(h, M, 8) <= 160 * 1024) return launch_mm<NT, 8, 160 * 1024>(c, X, Y, M);
+  if (mm_lds_bytes(h, M, 3) <= 160 * 1024) return launch_mm<NT, 3, 160 * 1024>(c, X, Y, M);
   return MPQ_ERR_UNSUPPORTED;
 }
 
 // Plan of the large-batch kernel: staged rows XR, the fewest ranges H whose activations fit the LDS of a
 // workgroup of W waves next to ring, unit table and park area, NB tile bands so that H * NB
 // workgroups about fill the compute units, groups of at most R = 8 tiles.
-bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePlan* pl, int* XR_out) {
+bool plan_slices(const MpqHeader& h, const mpq_plan& plan, int cus_i, int M, uint32_t W, uint32_t budget, SlicePlan* pl,
+                 int* XR_out) {
   const uint32_t PU = (uint32_t)mpq_pu2(h.g1);
   const uint32_t NT = M > 16 ? 2 : 1, XR = M <= 8 ? 8 : 16 * NT;
   const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
   const uint32_t maxH = B2 > B4 ? B2 : B4;
-  const uint32_t cus = (uint32_t)cu_count();
+  const uint32_t cus = (uint32_t)cus_i;
   uint32_t off = W * 2u * (1024u + 512u * PU);
   pl->off_units = off; off += (32u * PU * (B2 + B4) + 15u) & ~15u;
   pl->off_park = off;  off += W * 2048u;
   off = (off + 1023u) & ~1023u;
   pl->off_xbuf = off;
   if (off >= budget) return false;
-  uint32_t H = g_slice_min_h > 1 ? (uint32_t)g_slice_min_h : 1u;
+  uint32_t H = plan.lb_min_ranges > 1 ? (uint32_t)plan.lb_min_ranges : 1u;
   if (H > maxH) H = maxH;
   for (; H <= maxH && H <= cus; ++H) {
     const uint32_t nb2 = (B2 + H - 1) / H, nb4 = (B4 + H - 1) / H;  // the largest range
@@ -1400,9 +1817,9 @@ bool plan_slices(const MpqHeader& h, int M, uint32_t W, uint32_t budget, SlicePl
     uint32_t NB = cus / H;
     if (NB > (uint32_t)h.T) NB = (uint32_t)h.T;
     pl->H = (int32_t)H;
-    pl->older16 = g_slice_older > 0 && g_slice_older < 16 ? (uint32_t)g_slice_older : 10u;
+    pl->older16 = plan.lb_older16 > 0 && plan.lb_older16 < 16 ? (uint32_t)plan.lb_older16 : 10u;
     pl->NB = (int32_t)NB;
-    pl->R = g_slice_tiles > 0 && g_slice_tiles <= 8 ? g_slice_tiles : 8;
+    pl->R = plan.lb_tiles > 0 && plan.lb_tiles <= 8 ? plan.lb_tiles : 8;
     *XR_out = (int)XR;
     return true;
   }
@@ -1416,8 +1833,10 @@ size_t slice_workspace_bytes(const MpqHeader& h, const SlicePlan& pl, int NT, in
   return *p_bytes + (size_t)h.K * XR * sizeof(uint16_t);
 }
 
-mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, void* ws,
-                         size_t ws_bytes, hipStream_t s) {
+mpq_status launch_slices(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, void* ws, size_t ws_bytes) {
+  const MpqHeader& h = c.h;
+  const DevBlob& d = c.d;
+  hipStream_t s = c.s;
   SlicePlan pl;
   int XR = 0;
   const int NT = M > 16 ? 2 : 1;
@@ -1425,7 +1844,7 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   // operands of a position and up to 8 x NT accumulators stay in registers); 16 waves, with half
   // the registers and a third less LDS for the activations, measured equal or slower on every shape
   const int pu = mpq_pu2(h.g1);
-  if (!plan_slices(h, M, 8, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
+  if (!plan_slices(h, c.plan, c.cus, M, 8, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   size_t p_bytes = 0;
   if (!ws || ((uintptr_t)ws & 255u) != 0 || ws_bytes < slice_workspace_bytes(h, pl, NT, XR, &p_bytes)) return MPQ_ERR_UNSUPPORTED;
   unsigned char* scratch = (unsigned char*)ws;
@@ -1433,24 +1852,32 @@ mpq_status launch_slices(const MpqHeader& h, const DevBlob& d, const uint16_t* X
   uint16_t* XT = (uint16_t*)(scratch + p_bytes);
   const dim3 grid((unsigned)(pl.H * pl.NB));
 #define MPQ_LAUNCH_S(NTV, XRV, WV, PUV) \
-  hipLaunchKernelGGL((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV, PUV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
+  MPQ_LAUNCH((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV, PUV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
 #define MPQ_LAUNCH_S8(PUV) \
   { if (XR == 8) MPQ_LAUNCH_S(1, 8, 8, PUV); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8, PUV); else MPQ_LAUNCH_S(2, 32, 8, PUV); }
   if (pu == 1) MPQ_LAUNCH_S8(1) else if (pu == 2) MPQ_LAUNCH_S8(2) else MPQ_LAUNCH_S8(4)
 #undef MPQ_LAUNCH_S8
 #undef MPQ_LAUNCH_S
-  if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
-  ++g_slice_launches;
+  // from here on Y is undefined if the second launch fails: the first kernel is already enqueued
   const dim3 fgrid((unsigned)h.T), fblock(256);
-  if (XR == 8) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 8>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
-  else if (NT == 1) hipLaunchKernelGGL((mpq_mms_finish_kernel<1, 16>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
-  else hipLaunchKernelGGL((mpq_mms_finish_kernel<2, 32>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
-  return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+  if (XR == 8) MPQ_LAUNCH((mpq_mms_finish_kernel<1, 8>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
+  else if (NT == 1) MPQ_LAUNCH((mpq_mms_finish_kernel<1, 16>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
+  else MPQ_LAUNCH((mpq_mms_finish_kernel<2, 32>), fgrid, fblock, 0, s, d, XT, P, Y, M, pl.H, (uint32_t)h.ocap);
+  note(c, MPQ_KERNEL_BATCH_RANGES, 2, 8, pl.R, (long)pl.H * pl.NB);
+  return MPQ_OK;
 }
 
-mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint16_t* Y, int M, void* ws, size_t ws_bytes,
-                  hipStream_t s) {
-  if (M == 1) return gemv_all(h, d, X, Y, s);
+mpq_status gemv_all(const Ctx& c, const uint16_t* X, uint16_t* Y) {
+  if (c.plan.gemv_path != 2) {
+    const mpq_status st = gemv_planes(c, X, Y);
+    if (st != MPQ_ERR_UNSUPPORTED || c.plan.gemv_path == 1) return st;
+  }
+  return gemv_decode(c, X, Y);
+}
+
+mpq_status mm_all(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, void* ws, size_t ws_bytes) {
+  const MpqHeader& h = c.h;
+  if (M == 1) return gemv_all(c, X, Y);
   if (mm_lds_bytes(h, 1, 3) > kLdsPerCu) return MPQ_ERR_UNSUPPORTED;
   int Mc = M;  // largest batch chunk whose activations fit LDS together with everything else
   while (Mc > 1 && mm_lds_bytes(h, Mc, 3) > kLdsPerCu) --Mc;
@@ -1465,8 +1892,8 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
     const int chunks = (M + Mc - 1) / Mc;
     const bool large = h.total_bytes >= (12u << 20);
     const bool better = M <= 8 ? chunks >= 3 || (chunks == 2 && large) : chunks >= 2 || large;
-    if (g_slices < 0 ? better : g_slices != 0) {
-      const mpq_status st = launch_slices(h, d, X, Y, M, ws, ws_bytes, s);
+    if (c.plan.large_batch == 0 ? better : c.plan.large_batch > 0) {
+      const mpq_status st = launch_slices(c, X, Y, M, ws, ws_bytes);
       if (st != MPQ_ERR_UNSUPPORTED) return st;
     }
   }
@@ -1478,7 +1905,7 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
     const int mc = M - m0 < Mc ? M - m0 : Mc;
     const uint16_t* Xc = X + (size_t)m0 * h.K;
     uint16_t* Yc = Y + (size_t)m0 * h.N;
-    mpq_status st = mc > 16 ? mm_chunk<2>(h, d, Xc, Yc, mc, s) : mm_chunk<1>(h, d, Xc, Yc, mc, s);
+    mpq_status st = mc > 16 ? mm_chunk<2>(c, Xc, Yc, mc) : mm_chunk<1>(c, Xc, Yc, mc);
     if (st != MPQ_OK) return st;
   }
   return MPQ_OK;
@@ -1488,30 +1915,10 @@ mpq_status mm_all(const MpqHeader& h, const DevBlob& d, const uint16_t* X, uint1
 
 extern "C" {
 
-// Tuning hook for sweeps and for the tests that force every code path; not part of the supported
-// interface and not thread safe.  0 = automatic for every key.
-//   2: cap on the number of persistent workgroups
-//   4: waves per workgroup of the GEMV (8, 16)          6: tiles per workgroup of the GEMV (1..8)
-//   5: waves per workgroup of the batch kernel (4, 8, 16)
-//  12: large-batch kernel 1 = for every M > 1, 0 = never, -1 = automatic
-//  14: its least number of ranges   15: its tiles per group (1..8)
-//  18: sixteenths of a SIMD's blocks that go to the older of its two waves (1..15)
-void mpq_debug_set(int key, int value) {
-  if (key == 2) g_max_blocks = value;
-  if (key == 4) g_gemv_waves = value;
-  if (key == 5) g_batch_waves = value;
-  if (key == 6) g_gemv_tiles = value;
-  if (key == 12) g_slices = value;
-  if (key == 14) g_slice_min_h = value;
-  if (key == 15) g_slice_tiles = value;
-  if (key == 18) g_slice_older = value;
-}
-
-// Counters for the tests: 12 = launches of the large-batch kernel so far.
-int mpq_debug_get(int key) { return key == 12 ? g_slice_launches : 0; }
-
-mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
-                    int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream) {
+mpq_status mpq_gemm_planned(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                            int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream, const mpq_plan* plan,
+                            mpq_report* report) {
+  if (report) memset(report, 0, sizeof(*report));
   if (!X_dev || !Y_dev) return MPQ_ERR_NULL;
   if (M < 1 || M > MPQ_MAX_M) return MPQ_ERR_SHAPE;
   MpqHeader h;
@@ -1519,26 +1926,41 @@ mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* 
   mpq_status st = make_dev(hdr_host, blob_dev, &h, &d);
   if (st != MPQ_OK) return st;
   if ((((uintptr_t)X_dev | (uintptr_t)Y_dev) & 15u) != 0) return MPQ_ERR_ALIGN;
-  return mm_all(h, d, X_dev, Y_dev, M, workspace_dev, workspace_bytes, (hipStream_t)stream);
+  int cus = 0;
+  if ((st = cu_count(&cus)) != MPQ_OK) return st;
+  const Ctx c{h, d, plan ? *plan : kAutoPlan, report, cus, (hipStream_t)stream};
+  return mm_all(c, X_dev, Y_dev, M, workspace_dev, workspace_bytes);
 }
 
-mpq_status mpq_gemm_workspace_size(const void* hdr_host, int32_t M, size_t* bytes) {
+mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                    int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream) {
+  return mpq_gemm_planned(hdr_host, blob_dev, X_dev, Y_dev, M, workspace_dev, workspace_bytes, stream, nullptr, nullptr);
+}
+
+mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, const mpq_plan* plan, size_t* bytes) {
   if (!hdr_host || !bytes) return MPQ_ERR_NULL;
   if (M < 1 || M > MPQ_MAX_M) return MPQ_ERR_SHAPE;
   MpqHeader h;
   mpq_status st = mpq_internal_check_header(hdr_host, &h);
   if (st != MPQ_OK) return st;
+  int cus = 0;
+  if ((st = cu_count(&cus)) != MPQ_OK) return st;
   *bytes = 0;
   SlicePlan pl;
   int XR = 0;
   size_t p_bytes = 0;
-  if (M > 1 && plan_slices(h, M, 8, 160 * 1024, &pl, &XR)) *bytes = slice_workspace_bytes(h, pl, M > 16 ? 2 : 1, XR, &p_bytes);
+  if (M > 1 && plan_slices(h, plan ? *plan : kAutoPlan, cus, M, 8, 160 * 1024, &pl, &XR))
+    *bytes = slice_workspace_bytes(h, pl, M > 16 ? 2 : 1, XR, &p_bytes);
   return MPQ_OK;
+}
+
+mpq_status mpq_gemm_workspace_size(const void* hdr_host, int32_t M, size_t* bytes) {
+  return mpq_gemm_workspace_size_planned(hdr_host, M, nullptr, bytes);
 }
 
 mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev, uint16_t* y_dev,
                     void* stream) {
-  return mpq_gemm(hdr_host, blob_dev, x_dev, y_dev, 1, nullptr, 0, stream);
+  return mpq_gemm_planned(hdr_host, blob_dev, x_dev, y_dev, 1, nullptr, 0, stream, nullptr, nullptr);
 }
 
 mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void* const* blob_dev,
@@ -1568,10 +1990,10 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
   hipStream_t s = (hipStream_t)stream;
 #define MPQ_MULTI_CLASS(BYTES)                                                                          \
   if (need <= (BYTES)) {                                                                                \
-    if (pu == 1) hipLaunchKernelGGL((mpq_gemv_multi_kernel<2, (BYTES), 8, 1>), grid, block, 0, s, a);   \
-    else if (pu == 2) hipLaunchKernelGGL((mpq_gemv_multi_kernel<2, (BYTES), 8, 2>), grid, block, 0, s, a); \
-    else hipLaunchKernelGGL((mpq_gemv_multi_kernel<2, (BYTES), 8, 4>), grid, block, 0, s, a);           \
-    return hipGetLastError() == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;                                      \
+    if (pu == 1) MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 1>), grid, block, 0, s, a);           \
+    else if (pu == 2) MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 2>), grid, block, 0, s, a);      \
+    else MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 4>), grid, block, 0, s, a);                   \
+    return MPQ_OK;                                                                                      \
   }
   MPQ_MULTI_CLASS(40 * 1024)
   MPQ_MULTI_CLASS(80 * 1024)
@@ -1588,22 +2010,20 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   mpq_status st = make_dev(hdr_host, blob_dev, &h, &d);
   if (st != MPQ_OK) return st;
   if (((uintptr_t)W_out_dev & 15u) != 0) return MPQ_ERR_ALIGN;
+  int cus = 0;
+  if ((st = cu_count(&cus)) != MPQ_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   const int pu = mpq_pu2(h.g1);
   // enough workgroups for eight per compute unit: tiles with many blocks are shared
-  int slices = (8 * cu_count() + h.T - 1) / h.T;
+  int slices = (8 * cus + h.T - 1) / h.T;
   const int most = (h.B2 + h.B4 + 3) / 4;
   slices = slices > most ? most : slices;
   slices = slices > 8 ? 8 : slices < 1 ? 1 : slices;
   const dim3 grid((unsigned)h.T, (unsigned)slices);
-  if (pu == 1) hipLaunchKernelGGL(mpq_dequant_kernel<1>, grid, dim3(256), 0, s, d, W_out_dev);
-  else if (pu == 2) hipLaunchKernelGGL(mpq_dequant_kernel<2>, grid, dim3(256), 0, s, d, W_out_dev);
-  else hipLaunchKernelGGL(mpq_dequant_kernel<4>, grid, dim3(256), 0, s, d, W_out_dev);
-  if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
-  if (add_outliers && h.nnz > 0) {
-    hipLaunchKernelGGL(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
-    if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;
-  }
+  if (pu == 1) MPQ_LAUNCH(mpq_dequant_kernel<1>, grid, dim3(256), 0, s, d, W_out_dev);
+  else if (pu == 2) MPQ_LAUNCH(mpq_dequant_kernel<2>, grid, dim3(256), 0, s, d, W_out_dev);
+  else MPQ_LAUNCH(mpq_dequant_kernel<4>, grid, dim3(256), 0, s, d, W_out_dev);
+  if (add_outliers && h.nnz > 0) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   return MPQ_OK;
 }
 

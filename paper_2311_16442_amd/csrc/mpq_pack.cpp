@@ -325,6 +325,15 @@ mpq_status mpq_quantize_host(const mpq_desc* d, const float* W, int32_t n4, doub
   return MPQ_OK;
 }
 
+mpq_status mpq_quantize_outlier_capacity(const mpq_desc* d, int32_t n4, double p_o, int64_t* capacity) {
+  if (!d || !capacity) return MPQ_ERR_NULL;
+  if (!desc_ok(d)) return MPQ_ERR_SHAPE;
+  const int64_t G = d->K / d->g1;
+  if (n4 < 0 || n4 > G || !(p_o >= 0.0 && p_o <= 1.0)) return MPQ_ERR_SHAPE;
+  *capacity = (int64_t)d->N * (int64_t)floor(p_o * (double)((G - n4) * d->g1) + 0.5);
+  return MPQ_OK;
+}
+
 mpq_status mpq_packed_size(const mpq_desc* d, const uint8_t* is4, const int32_t* row_ptr, size_t* bytes) {
   if (!d || !is4 || !row_ptr || !bytes) return MPQ_ERR_NULL;
   if (!desc_ok(d)) return MPQ_ERR_SHAPE;

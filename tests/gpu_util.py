@@ -42,9 +42,9 @@ def to_dev(torch, arr: np.ndarray):
 class Workspace:
     """Device workspace for mpq.gemm of the size the library asks for, with a sentinel band behind it."""
 
-    def __init__(self, torch, mpq, header, M):
+    def __init__(self, torch, mpq, header, M, plan=None):
         self.torch = torch
-        self.bytes = mpq.gemm_workspace_size(header, M)
+        self.bytes = mpq.gemm_workspace_size_planned(header, M, plan) if plan is not None else mpq.gemm_workspace_size(header, M)
         self.buf = torch.full((self.bytes + 256,), 0x5A, dtype=torch.uint8, device="cuda")
         assert self.buf.data_ptr() % 256 == 0
         self.view = self.buf[:self.bytes] if self.bytes else None

@@ -172,33 +172,82 @@ def test_outliers_reduce_to_csr_product(torch):
     assert rel_err(y.check_and_get(), ref)[0] <= TOL
 
 
+@pytest.mark.parametrize("path", [mpq.KERNEL_GEMV_PLANES, mpq.KERNEL_GEMV_DECODE])
 @pytest.mark.parametrize("waves,tiles", [(8, 1), (8, 2), (8, 3), (16, 1), (16, 2), (16, 5), (8, 8)])
-def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
-    # every work split of the matrix-vector product the library can choose (waves per workgroup x
-    # tiles per workgroup, forced through the tuning hook) on a ragged shape: 63 tiles, last one
-    # with 8 rows, a short tail super-group, fewer code blocks per tile (6) than waves
-    import ctypes
+def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles, path):
+    # every work split of both matrix-vector kernels (waves per workgroup x tiles per workgroup, forced
+    # through a launch plan) on a ragged shape: 63 tiles, last one with 8 rows, a short tail
+    # super-group, fewer code blocks per tile (6) than waves
     lg, om, pk = make(("ragged_rows", 1000, 704, 64, 4, 0.30, 0.02, True))
-    hook = mpq.lib().mpq_debug_set
-    hook.argtypes = [ctypes.c_int, ctypes.c_int]
     blob = to_dev(torch, pk.blob)
     X = synth.make_x(7, 1, pk.K)
     x = to_dev(torch, X[0].view(np.int16))
     ref = om.gemm(X, threads=8)[0]
-    try:
-        hook(4, waves)
-        hook(6, tiles)
-        print("waves", waves, "tiles", tiles, flush=True)
-        y = Guarded(torch, pk.N)
-        mpq.gemv(pk.header, blob, x, y.view)
-        got = y.check_and_get()
-    finally:
-        hook(4, 0)
-        hook(6, 0)
+    plan = mpq.Plan(gemv_path=path, gemv_waves=waves, gemv_tiles=tiles)
+    print("path", path, "waves", waves, "tiles", tiles, flush=True)
+    y = Guarded(torch, pk.N)
+    rep = mpq.gemm_planned(pk.header, blob, x, y.view, 1, plan=plan)
+    got = y.check_and_get()
+    assert (rep.kernel, rep.waves, rep.tiles_per_workgroup, rep.launches) == (path, waves, tiles, 1)
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (e_floor, e_max)
 
 
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_both_gemv_kernels_on_every_case(torch, case):
+    # the plane-sum kernel (2-bit groups through the fp8/fp4 matrix instruction) where the format allows
+    # it (one group per unit: g1 >= 64), the per-weight kernel everywhere; the automatic choice is the
+    # plane-sum kernel whenever it can run; results are the same bits from call to call
+    lg, om, pk = make(case)
+    print("case", case, flush=True)
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(41, 1, pk.K)
+    x = to_dev(torch, X[0].view(np.int16))
+    ref = om.gemm(X, threads=8)[0]
+    ran = []
+    for path in (0, mpq.KERNEL_GEMV_PLANES, mpq.KERNEL_GEMV_DECODE):
+        y = Guarded(torch, pk.N)
+        try:
+            rep = mpq.gemm_planned(pk.header, blob, x, y.view, 1, plan=mpq.Plan(gemv_path=path))
+        except mpq.MpqError as e:
+            # groups shorter than a unit, or rows so long that the split activations do not fit on chip
+            assert path == mpq.KERNEL_GEMV_PLANES and e.status == mpq.MPQ_ERR_UNSUPPORTED and (pk.g1 < 64 or pk.K > 16384)
+            continue
+        got = y.check_and_get()
+        e_floor, e_max = rel_err(got, ref)
+        assert e_floor <= TOL, (path, e_floor, e_max)
+        y2 = Guarded(torch, pk.N)
+        mpq.gemm_planned(pk.header, blob, x, y2.view, 1, plan=mpq.Plan(gemv_path=path))
+        assert np.array_equal(y2.check_and_get(), got)
+        ran.append((path, rep.kernel))
+    planes_ran = (mpq.KERNEL_GEMV_PLANES, mpq.KERNEL_GEMV_PLANES) in ran
+    assert planes_ran == (pk.g1 >= 64 and pk.K <= 16384), ran
+    assert ran[0][1] == (mpq.KERNEL_GEMV_PLANES if planes_ran else mpq.KERNEL_GEMV_DECODE), ran
+    assert (mpq.KERNEL_GEMV_DECODE, mpq.KERNEL_GEMV_DECODE) in ran
+
+
+def test_plane_sum_kernel_with_wide_ranging_activations(torch):
+    # activations spanning many binades inside one 64-column unit, zeros, subnormals and the largest
+    # finite fp16 values: the split into fp8 pieces is exact over this range
+    name, N, K, g1, g2, f4, p_o, z1_full = CASES[0]
+    lg = synth.make_matrix(synth.MatrixSpec(name, N, K, g1, g2, f4, p_o, 4242 + N + K))
+    lg.s2[:] = synth.f16_bits(np.full(lg.s2.shape, 2.0e-5))     # small weights: the outputs stay inside fp16
+    lg.val[:] = synth.f16_bits(lg.val.view(np.float16).astype(np.float64) * 1e-2)
+    om, pk = oracle.Matrix.from_logical(lg), mpq.pack_logical(lg)
+    rng = np.random.default_rng(43)
+    xf = rng.normal(0.0, 1.0, size=pk.K) * np.exp2(rng.integers(-14, 6, size=pk.K))
+    xf[::17] = 0.0
+    xf[5::64] = 6.0e-8
+    xf[9::128] = 65504.0 * np.sign(rng.normal(size=xf[9::128].size))
+    X = synth.f16_bits(xf)[None, :]
+    blob = to_dev(torch, pk.blob)
+    y = Guarded(torch, pk.N)
+    rep = mpq.gemm_planned(pk.header, blob, to_dev(torch, X[0].view(np.int16)), y.view, 1,
+                           plan=mpq.Plan(gemv_path=mpq.KERNEL_GEMV_PLANES))
+    assert rep.kernel == mpq.KERNEL_GEMV_PLANES
+    ref = om.gemm(X, threads=8)[0]
+    e_floor, e_max = rel_err(y.check_and_get(), ref)
+    assert e_floor <= TOL, (e_floor, e_max)
 
 
 @pytest.mark.parametrize("min_h", [0, 3])
@@ -206,36 +255,26 @@ def test_gemv_work_splits_agree_with_oracle(torch, waves, tiles):
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_large_batch_kernel_within_tolerance(torch, case, M, min_h):
     # the kernel that keeps one K-range of the activations resident per workgroup and writes partial
-    # sums that a second kernel adds up, forced for every batch size through the tuning hook (by
+    # sums that a second kernel adds up, forced for every batch size through a launch plan (by
     # itself the library takes it where the other batch kernel would decode the weights several
     # times); also with at least three ranges on matrices whose activations would fit at once.  The
-    # workspace has exactly the size the library asks for, with a guard band behind it.
-    import ctypes
+    # workspace has exactly the size the library asks for under the same plan, with a guard band behind it.
     lg, om, pk = make(case)
-    hook, count = mpq.lib().mpq_debug_set, mpq.lib().mpq_debug_get
-    hook.argtypes = [ctypes.c_int, ctypes.c_int]
-    count.argtypes, count.restype = [ctypes.c_int], ctypes.c_int
     blob = to_dev(torch, pk.blob)
     X = synth.make_x(700 + M, M, pk.K)
     ref = om.gemm(X, threads=8)
     print("case", case, "M", M, "min_h", min_h, flush=True)
-    before = count(12)
-    try:
-        hook(12, 1)
-        hook(14, min_h)
-        ws = Workspace(torch, mpq, pk.header, M)
-        assert ws.bytes > 0
-        Y = Guarded(torch, M * pk.N)
-        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, workspace=ws.view)
-        got = Y.check_and_get().reshape(M, pk.N)
-        Y2 = Guarded(torch, M * pk.N)
-        mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M, workspace=ws.view)
-        again = Y2.check_and_get().reshape(M, pk.N)
-        ws.check()
-    finally:
-        hook(12, -1)
-        hook(14, 0)
-    assert count(12) == before + 2, "the large-batch kernel did not run"
+    plan = mpq.Plan(large_batch=1, lb_min_ranges=min_h)
+    ws = Workspace(torch, mpq, pk.header, M, plan)
+    assert ws.bytes > 0
+    Y = Guarded(torch, M * pk.N)
+    rep = mpq.gemm_planned(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, plan=plan, workspace=ws.view)
+    got = Y.check_and_get().reshape(M, pk.N)
+    Y2 = Guarded(torch, M * pk.N)
+    rep2 = mpq.gemm_planned(pk.header, blob, to_dev(torch, X.view(np.int16)), Y2.view, M, plan=plan, workspace=ws.view)
+    again = Y2.check_and_get().reshape(M, pk.N)
+    ws.check()
+    assert rep.kernel == rep2.kernel == mpq.KERNEL_BATCH_RANGES and rep.launches == 2, "the large-batch kernel did not run"
     e_floor, e_max = rel_err(got, ref)
     assert e_floor <= TOL, (e_floor, e_max)
     assert np.array_equal(got, again)
@@ -245,49 +284,52 @@ def test_large_batch_kernel_in_a_graph_and_without_workspace(torch):
     # the library allocates nothing: with the caller's workspace the large-batch kernel can be
     # captured into a graph and every replay reproduces the eager result; without a workspace (or
     # with one that is too small) the product is computed by the other batch kernel
-    import ctypes
     lg, om, pk = make(CASES[6])
     M = 16
-    hook, count = mpq.lib().mpq_debug_set, mpq.lib().mpq_debug_get
-    hook.argtypes = [ctypes.c_int, ctypes.c_int]
-    count.argtypes, count.restype = [ctypes.c_int], ctypes.c_int
     blob = to_dev(torch, pk.blob)
     X = synth.make_x(900, M, pk.K)
     Xd = to_dev(torch, X.view(np.int16))
     ref = om.gemm(X, threads=8)
     stream = torch.cuda.Stream()
-    try:
-        hook(12, 1)
-        ws = Workspace(torch, mpq, pk.header, M)
-        Y = Guarded(torch, M * pk.N)
+    plan = mpq.Plan(large_batch=1)
+    ws = Workspace(torch, mpq, pk.header, M, plan)
+    Y = Guarded(torch, M * pk.N)
+    torch.cuda.synchronize()
+    rep = mpq.gemm_planned(pk.header, blob, Xd, Y.view, M, plan=plan, stream=stream, workspace=ws.view)
+    stream.synchronize()
+    assert rep.kernel == mpq.KERNEL_BATCH_RANGES
+    eager = Y.check_and_get().reshape(M, pk.N)
+    assert rel_err(eager, ref)[0] <= TOL
+    Yg = Guarded(torch, M * pk.N)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        rep = mpq.gemm_planned(pk.header, blob, Xd, Yg.view, M, plan=plan, stream=stream, workspace=ws.view)
+    assert rep.kernel == mpq.KERNEL_BATCH_RANGES
+    for rep_i in range(3):
+        Yg.view.zero_()
+        ws.buf[:ws.bytes].fill_(0xFF)      # the workspace carries nothing from call to call
         torch.cuda.synchronize()
-        before = count(12)
-        mpq.gemm(pk.header, blob, Xd, Y.view, M, stream=stream, workspace=ws.view)
-        stream.synchronize()
-        assert count(12) == before + 1
-        eager = Y.check_and_get().reshape(M, pk.N)
-        assert rel_err(eager, ref)[0] <= TOL
-        Yg = Guarded(torch, M * pk.N)
+        g.replay()
         torch.cuda.synchronize()
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=stream):
-            mpq.gemm(pk.header, blob, Xd, Yg.view, M, stream=stream, workspace=ws.view)
-        assert count(12) == before + 2
-        for rep in range(3):
-            Yg.view.zero_()
-            ws.buf[:ws.bytes].fill_(0xFF)      # the workspace carries nothing from call to call
-            torch.cuda.synchronize()
-            g.replay()
-            torch.cuda.synchronize()
-            assert np.array_equal(Yg.check_and_get().reshape(M, pk.N), eager), rep
-        ws.check()
-        for small in (None, ws.view[:ws.bytes - 256]):
-            Yn = Guarded(torch, M * pk.N)
-            mpq.gemm(pk.header, blob, Xd, Yn.view, M, workspace=small)
-            assert rel_err(Yn.check_and_get().reshape(M, pk.N), ref)[0] <= TOL
-        assert count(12) == before + 2          # neither of the two ran the large-batch kernel
-    finally:
-        hook(12, -1)
+        assert np.array_equal(Yg.check_and_get().reshape(M, pk.N), eager), rep_i
+    ws.check()
+    for small in (None, ws.view[:ws.bytes - 256]):
+        Yn = Guarded(torch, M * pk.N)
+        rep = mpq.gemm_planned(pk.header, blob, Xd, Yn.view, M, plan=plan, workspace=small)
+        assert rep.kernel == mpq.KERNEL_BATCH_RESIDENT      # neither of the two ran the large-batch kernel
+        assert rel_err(Yn.check_and_get().reshape(M, pk.N), ref)[0] <= TOL
+
+
+def test_workspace_sizes_on_the_device(torch):
+    # nothing for M = 1, partial sums for every range plus the transposed activations otherwise, growing
+    # with the batch and with the number of ranges a plan asks for
+    lg, om, pk = make(CASES[0])
+    assert mpq.gemm_workspace_size(pk.header, 1) == 0
+    sizes = [mpq.gemm_workspace_size(pk.header, M) for M in (2, 8, 9, 16, 17, 32)]
+    assert all(b > 0 for b in sizes) and sizes == sorted(sizes)
+    assert sizes[0] >= (pk.N // 16) * 16 * 16 * 4 + pk.K * 8 * 2
+    assert mpq.gemm_workspace_size_planned(pk.header, 8, mpq.Plan(lb_min_ranges=3)) > sizes[1]
 
 
 def test_several_products_in_one_launch(torch):

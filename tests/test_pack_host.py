@@ -178,19 +178,14 @@ def test_group_count_beyond_the_table_offsets_is_unsupported():
     assert mpq.packed_size(16, 1000 * 16, 16, 1, np.zeros(1000, np.uint8), rp, 1) > 0
 
 
-def test_gemm_workspace_size_on_the_host():
-    # a host-side query (no GPU needed): nothing for M = 1, partial sums for every range plus the
-    # transposed activations otherwise, growing with the batch; bad arguments are refused
+def test_gemm_workspace_size_validates_before_it_asks_the_device():
+    # the size depends on the compute-unit count of the current device, which the call queries: without
+    # a device a valid query fails with MPQ_ERR_HIP (never a guessed size); bad arguments are refused
+    # before the device is asked, so these checks need no GPU.  With a device the sizes are positive,
+    # grow with the batch and hold at least one range of partial sums plus the transposed activations.
     spec = synth.MatrixSpec("ws", 4096, 4096, 64, 16, 0.10, 0.005, 77)
     lg = synth.make_matrix(spec)
     pk = mpq.pack_logical(lg)
-    assert mpq.gemm_workspace_size(pk.header, 1) == 0
-    sizes = [mpq.gemm_workspace_size(pk.header, M) for M in (2, 8, 9, 16, 17, 32)]
-    assert all(b % 256 == 0 or b > 0 for b in sizes) and all(b > 0 for b in sizes)
-    assert sizes == sorted(sizes)
-    T = 4096 // 16
-    # at least one range of partial sums (16 batch columns x 16 rows fp32 per tile) and the K x 8 fp16 copy
-    assert sizes[0] >= T * 16 * 16 * 4 + 4096 * 8 * 2
     L = mpq.lib()
     n = C.c_size_t(0)
     hp = pk.header.ctypes.data_as(C.c_void_p)
@@ -198,6 +193,17 @@ def test_gemm_workspace_size_on_the_host():
     assert L.mpq_gemm_workspace_size(hp, 33, C.byref(n)) == mpq.MPQ_ERR_SHAPE
     assert L.mpq_gemm_workspace_size(None, 4, C.byref(n)) == mpq.MPQ_ERR_NULL
     assert L.mpq_gemm_workspace_size(hp, 4, None) == mpq.MPQ_ERR_NULL
+    bad = pk.header.copy()
+    bad[8] ^= 1
+    assert L.mpq_gemm_workspace_size(bad.ctypes.data_as(C.c_void_p), 4, C.byref(n)) == mpq.MPQ_ERR_BLOB
+    st = L.mpq_gemm_workspace_size(hp, 4, C.byref(n))
+    assert st in (mpq.MPQ_OK, mpq.MPQ_ERR_HIP)
+    if st == mpq.MPQ_OK:
+        assert mpq.gemm_workspace_size(pk.header, 1) == 0
+        sizes = [mpq.gemm_workspace_size(pk.header, M) for M in (2, 8, 9, 16, 17, 32)]
+        assert all(b > 0 for b in sizes) and sizes == sorted(sizes)
+        assert sizes[0] >= (4096 // 16) * 16 * 16 * 4 + 4096 * 8 * 2
+        assert mpq.gemm_workspace_size_planned(pk.header, 8, mpq.Plan(lb_min_ranges=3)) > sizes[1]
 
 
 def test_avg_bits_with_the_papers_aligned_metadata_stays_within_its_stated_overhead():
