@@ -214,7 +214,9 @@ typedef struct {
   int32_t lb_min_ranges;   /* K-range kernel: least number of ranges */
   int32_t lb_tiles;        /* K-range kernel: tiles per group (1..8) */
   int32_t lb_older16;      /* K-range kernel: sixteenths of a SIMD's blocks for the older of its two waves (1..15) */
-  int32_t reserved[7];     /* must be 0 */
+  int32_t gemv_older;      /* plane-sum kernel: 1 + the sixteenths of a SIMD's blocks that its oldest wave takes beyond an
+                              even share (1 = even split; 0 = the library's choice) */
+  int32_t reserved[6];     /* must be 0 */
 } mpq_plan;
 
 #define MPQ_KERNEL_GEMV_PLANES 1     /* batch 1, 2-bit groups by plane sums on the fp8/fp4 matrix instruction */

@@ -46,8 +46,8 @@ class Desc(C.Structure):
 class Plan(C.Structure):
     """mpq_plan: 0 in a field = the library's own choice."""
     _fields_ = [(n, C.c_int32) for n in ("gemv_path", "gemv_waves", "gemv_tiles", "batch_waves", "max_workgroups",
-                                         "large_batch", "lb_min_ranges", "lb_tiles", "lb_older16")] + \
-               [("reserved", C.c_int32 * 7)]
+                                         "large_batch", "lb_min_ranges", "lb_tiles", "lb_older16", "gemv_older")] + \
+               [("reserved", C.c_int32 * 6)]
 
 
 class Report(C.Structure):

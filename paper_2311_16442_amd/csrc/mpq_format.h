@@ -17,7 +17,7 @@
 // 4-bit groups in K order), so they need not be neighbours in K; every piece covers whole decode
 // steps of 8 columns.  For g1 >= 64 a unit is one piece (a half or quarter of a group).
 //
-//   header    256 B                       (MpqHeader)
+//   header    256 B                       (MpqHeader; its last 112 bytes are the bitmap of the 4-bit K-groups)
 //   units     2 x uint32 [4*(B2+B4)][PU2] per unit in stream order (2-bit units, then 4-bit units)
 //                                         and per piece, ready for the kernels (a 4-bit unit uses
 //                                         the first PU4 of its PU2 slots):
@@ -92,8 +92,12 @@ typedef struct {
   uint64_t ocap;        /* words per tile in the outlier records (multiple of 32) */
   uint64_t reserved0, reserved1;
   uint64_t total_bytes;
-  uint8_t pad[256 - 4 * 16 - 8 - 8 * 8 - 8];
+  /* bit g = K-group g holds 4-bit codes (all zero if G > MPQ_IS4_BITS: the header then does not say
+     which groups are 4-bit).  With it a unit's table entry follows from the header alone, so the host
+     can hand entries to a kernel as arguments instead of the kernel loading them. */
+  uint8_t is4_bits[256 - 4 * 16 - 8 - 8 * 8 - 8];
 } MpqHeader;
+#define MPQ_IS4_BITS (8 * (256 - 4 * 16 - 8 - 8 * 8 - 8))
 
 /* pieces (groups) per 2-bit / 4-bit unit, entries of meta2 per group for g2_axis 1, bytes of meta2 */
 static inline int32_t mpq_pu2(int32_t g1) { return g1 >= 64 ? 1 : 64 / g1; }
@@ -111,8 +115,12 @@ static inline uint32_t mpq_meta2_zero(const MpqHeader* h) {
 #ifdef __cplusplus
 static_assert(sizeof(MpqHeader) == 256, "header must be 256 bytes");
 #include "../../include/mpq.h"
-// Accepts a header only if it is byte for byte what the packer writes for the shape it records.
+// Accepts a header only if it is byte for byte what the packer writes for the shape it records
+// (the bitmap of 4-bit groups must have n4 bits set, none at or beyond G).
 mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out);
+// Word 1 (meta1 offset | meta2 offset << 16) of the table entries of the 4 * (B2 + B4) units, from the
+// header alone; false if the header carries no bitmap or a unit holds several groups (g1 < 64).
+bool mpq_internal_unit_words(const MpqHeader* h, uint32_t* words);
 #endif
 
 #endif /* MPQ_FORMAT_H_ */

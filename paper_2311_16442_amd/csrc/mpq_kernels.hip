@@ -21,6 +21,7 @@
 //   exact integers c - z1; one packed fp16 multiply by s1 is the rounding the definition asks
 //   for.  The product kernel hands the resulting pairs to the matrix core.
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 #include <string.h>
 
@@ -1121,31 +1122,31 @@ mpq_gemv_multi_kernel(const MultiArgs a) {
 //
 // Data movement.  No request of a wave depends on data another request brings: code blocks and the
 // (s_int, z1), (s2, z2) words of their lanes travel together into a per-wave ring (three direct
-// global->LDS loads per block, addresses from unit table entries read through the scalar cache), so a wave
+// global->LDS loads per block; the addresses of a wave's first requests come from the kernel arguments), so a wave
 // issues its first blocks in its first instructions.  A workgroup of WV waves owns n consecutive
 // tiles and treats their blocks as one sequence dealt round-robin to its waves; the activations are
 // staged and split once per workgroup while the first blocks are in flight.  Outliers of tile t are
 // summed by wave t from a record the wave fetched for itself.  Three barriers per workgroup.
-typedef int v8i_s __attribute__((ext_vector_type(8)));
 struct PlanePlan {
   uint32_t off_park, off_units, off_xs, off_utab, off_pieces, off_zero, off_obuf;  // LDS byte offsets (ring at 0)
   uint32_t obuf_bytes;  // outlier record of a tile: 128 + 4 * ocap
   uint32_t n;           // tiles per workgroup (<= WV)
+  // Dealing of the workgroup's blocks: wave w takes the run [N cum[w] / cum[W], N cum[w + 1] / cum[W]) of
+  // its N blocks.  Older waves (lower numbers; waves w, w + 4, ... share a SIMD) win the issue arbitration
+  // and run faster; they get longer runs so that all waves end together.
+  uint32_t cum[17];
 };
+#define MPQ_PLANE_MAX_UNITS 512
 struct PlaneArgs {
   DevBlob b;
   const uint16_t* X;
   uint16_t* Y;
   PlanePlan pl;
+  // word 1 (meta1 offset | meta2 offset << 16) of every unit's table entry, rebuilt on the host from the
+  // header: the first requests of a wave take their addresses from here, i.e. from the kernel arguments
+  // every wave loads anyway, and depend on no other load
+  uint32_t uw[MPQ_PLANE_MAX_UNITS];
 };
-
-// The table entries (2 dwords each) of the four units of block c through the scalar data cache: the
-// address is wave-uniform, and a vector load here would count against the hand-written vmcnt waits.
-__device__ __forceinline__ v8i_s unit_entries(const unsigned char* units, uint32_t c) {
-  v8i_s e;
-  asm volatile("s_load_dwordx8 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(e) : "s"(units), "s"(c * 32u) : "memory");
-  return e;
-}
 
 typedef int v8i_t __attribute__((ext_vector_type(8)));
 typedef short short2_t __attribute__((ext_vector_type(2)));
@@ -1162,11 +1163,28 @@ __device__ __forceinline__ uint32_t quad_max(uint32_t v) {
   return v > o ? v : o;
 }
 
+// Reads ring slot contents and one more LDS dword in one go: the 16 bytes of codes of the lane, its
+// (s_int, z1) and (s2, z2) dwords, and the unit word at `uaddr` that the next request needs.  One asm
+// statement with its wait: nothing may be scheduled between a read and the wait.
+__device__ __forceinline__ void plane_ring_read(uint32_t code_addr, uint32_t meta_addr, uint32_t uaddr, uint4& q, uint32_t& w1,
+                                                uint32_t& w2, uint32_t& uy) {
+  asm volatile("ds_read_b128 %0, %4\n\tds_read_b32 %1, %5\n\tds_read_b32 %2, %5 offset:256\n\tds_read_b32 %3, %6 offset:4\n\t"
+               "s_waitcnt lgkmcnt(0)"
+               : "=&v"(q), "=&v"(w1), "=&v"(w2), "=&v"(uy)
+               : "v"(code_addr), "v"(meta_addr), "v"(uaddr)
+               : "memory");
+}
+
 template <int LDSB, int WV>
 __global__ void __launch_bounds__(WV * 64)
 mpq_gemvp_kernel(const PlaneArgs a) {
 #pragma clang fp contract(off)
-  constexpr uint32_t W = WV, PD = 2, SLOTB = 1536, OPS = 3;
+  // Two ring slots per wave.  The wave keeps exactly two blocks in flight from its first request to its
+  // last fetch - past the end of its run it re-requests its last block - so that "the block I need has
+  // landed" is the same wait everywhere (vmcnt(3): the three requests of the other slot) and the loop
+  // carries no counters for it.  Scalar instructions cost issue slots like vector ones: the loop is
+  // written to need few of either.
+  constexpr uint32_t W = WV, SLOTB = 1536;
   __shared__ __align__(16) unsigned char lds[LDSB];
   const DevBlob& b = a.b;
   const PlanePlan& pl = a.pl;
@@ -1183,131 +1201,161 @@ mpq_gemvp_kernel(const PlaneArgs a) {
   unsigned char* const pieces = lds + pl.off_pieces;
   const DecodeConsts kc = make_consts();
 
-  // ---- (1) requests, oldest first: activations, unit table, this wave's outlier record, first blocks
+  // ---- (1) requests: the staged operands (activations first: everything waits for them), then the
+  //      wave's first two blocks, whose unit words come from the kernel arguments
   const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
   dma_linear<W>((const unsigned char*)a.X, lds_addr(xs), 2u * b.K, wv, lane16);
   dma_linear<W>(b.units, lds_addr(units), 32u * C, wv, lane16);
-  if (wv < n) {
-    const unsigned char* rec = tileptr + (size_t)wv * b.tile_stride + b.off_ot;
-    const uint32_t dst = lds_addr(lds + pl.off_obuf) + wv * pl.obuf_bytes;
+  // outliers of tile t: waves og * t .. og * t + og - 1 counted from the last wave down (the first waves
+  // have the activations to split); the first wave of a group fetches the tile's record
+  const uint32_t og = 4u * n <= W ? 4u : 1u;          // waves per tile: 16 or 4 lanes per row
+  const uint32_t ow = W - 1u - wv, ot = ow / og;      // this wave works on the outliers of tile ot (if < n)
+  if (ot < n && ow % og == 0) {
+    const unsigned char* rec = tileptr + (size_t)ot * b.tile_stride + b.off_ot;
+    const uint32_t dst = lds_addr(lds + pl.off_obuf) + ot * pl.obuf_bytes;
     for (uint32_t off = 0; off < pl.obuf_bytes; off += 1024u)
       if (off + lane16 < pl.obuf_bytes) dma16(rec + off, lane16, dst + off);
   }
-  const uint32_t ring0 = lds_addr(lds) + wv * (PD * SLOTB);
-  const uint32_t m1lane = i * 2u, m2lane = b.off_m2 + (i >> b.m2_shift) * 4u;
-  const unsigned char* rbase = tileptr;  // record of the tile being requested
-  uint32_t rc = wv, rt = 0;              // next request: block rc of tile rt (rt = n: none left)
-  while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
-  uint32_t inflight = 0;
-#define MPQ_P_REQUEST(SLOT)                                                            \
+  // this wave's blocks: the contiguous run [k0, k1) of the workgroup's n C blocks (tile after tile, the
+  // 2-bit blocks of a tile before its 4-bit blocks); the runs of older waves are longer (see PlanePlan)
+  const uint32_t nblk = n * C;
+  const uint32_t k0 = nblk * pl.cum[wv] / pl.cum[W], k1 = nblk * pl.cum[wv + 1] / pl.cum[W];
+  const uint32_t t_first = k0 / C, c_first = k0 - t_first * C;
+  const uint32_t ring0 = lds_addr(lds) + wv * (2u * SLOTB);
+  const uint32_t m1l = (i * 2u) & ~3u;  // inside a group's 32 bytes of (s_int, z1) pairs: the dword with this row's pair
+  const uint32_t m2lane = b.off_m2 + (i >> b.m2_shift) * 4u;
+  const unsigned char* rtile = tileptr + (size_t)t_first * b.tile_stride;  // record of the tile being requested
+  const unsigned char* rcode = rtile + b.codes_off + c_first * 1024u;      // its block requested next
+  uint32_t rc = c_first, rleft = k1 > k0 ? k1 - k0 - 1u : 0u;  // that block's number; blocks after it in the run
+  uint32_t rdst = ring0;                                        // ring slot the next request fills
+  uint32_t uaddr = pl.off_units + j * 8u + c_first * 32u;        // LDS address of the unit entry of lane (j, .) of block rc
+// one block: codes, then the lane's (s_int, z1) dword and (s2, z2) dword (group offsets are multiples of 32)
+#define MPQ_P_REQUEST(UY)                                                              \
   {                                                                                    \
-    const uint32_t dst = ring0 + (SLOT) * SLOTB;                                       \
-    dma16(rbase + b.codes_off + rc * 1024u, lane16, dst);                              \
-    const v8i_s ue4 = unit_entries(b.units, __builtin_amdgcn_readfirstlane(rc));       \
-    const uint32_t uy = (uint32_t)(j == 0 ? ue4[1] : j == 1 ? ue4[3] : j == 2 ? ue4[5] : ue4[7]); \
-    dma4(rbase, ((uy & 0xFFFFu) + m1lane) & ~3u, dst + 1024u);                         \
-    dma4(rbase, m2lane + (uy >> 16), dst + 1280u);                                     \
-    ++inflight;                                                                        \
-    rc += W;                                                                           \
-    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }               \
+    const uint32_t uy = (UY);                                                          \
+    dma16(rcode, lane16, rdst);                                                        \
+    dma4(rtile, (uy & 0xFFFFu) | m1l, rdst + 1024u);                                   \
+    dma4(rtile, m2lane + (uy >> 16), rdst + 1280u);                                    \
+    rdst = 2u * ring0 + SLOTB - rdst; /* the other slot */                             \
+    if (rleft > 0) { /* past the end of the run the last block is requested again */   \
+      --rleft;                                                                         \
+      rcode += 1024;                                                                   \
+      uaddr += 32u;                                                                    \
+      if (++rc == C) {                                                                 \
+        rc = 0;                                                                        \
+        rtile += b.tile_stride;                                                        \
+        rcode = rtile + b.codes_off;                                                   \
+        uaddr = pl.off_units + j * 8u;                                                 \
+      }                                                                                \
+    }                                                                                  \
   }
-#pragma unroll
-  for (uint32_t r = 0; r < PD; ++r)
-    if (rt < n) MPQ_P_REQUEST(r)
+  if (k1 > k0) {
+    // unit words of the first two blocks by scalar loads from the kernel arguments (the table has not
+    // landed in LDS yet); written out: a vector load here would count against the vmcnt waits
+    typedef uint32_t u4_s __attribute__((ext_vector_type(4)));
+    const unsigned char* kuw = (const unsigned char*)(uintptr_t)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(PlaneArgs, uw);
+    const uint32_t c_second = rleft > 0 ? (c_first + 1u == C ? 0u : c_first + 1u) : c_first;
+    u4_s u0, u1;
+    asm volatile("s_load_dwordx4 %0, %2, %3\n\ts_load_dwordx4 %1, %2, %4\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(u0), "=&s"(u1)
+                 : "s"(kuw), "s"(__builtin_amdgcn_readfirstlane(c_first) * 16u), "s"(__builtin_amdgcn_readfirstlane(c_second) * 16u)
+                 : "memory");
+    MPQ_P_REQUEST(j == 0 ? u0[0] : j == 1 ? u0[1] : j == 2 ? u0[2] : u0[3])
+    MPQ_P_REQUEST(j == 0 ? u1[0] : j == 1 ? u1[1] : j == 2 ? u1[2] : u1[3])
+  }
   if (tid < 32) ((uint32_t*)(lds + pl.off_zero))[tid] = 0u;  // what inactive lanes of the A operand read
-  wait_vm((int)(OPS * inflight));  // everything older than the block requests has landed
+  for (uint32_t o = tid; o < n * (2u * W + 1u) * 16u; o += W * 64u) red[o] = 0.f;  // a wave parks sums only for the tiles it touches
+  if (k1 > k0) MPQ_VMCNT(6); else MPQ_VMCNT(0);  // what is older than the two blocks has landed: activations, unit table, outlier record
   lds_barrier();
 
   // ---- (2) split the activations of every 2-bit unit into three fp8 pieces, in the order of the
-  //      instruction's contraction slots: item = (unit, half of the columns, 16 of its slots)
+  //      instruction's contraction slots.  16 lanes per unit: lane (pass, d, hf) takes the two dwords of
+  //      activations that hold the columns of nibbles 2 hf, 2 hf + 1 (low halves) and 2 hf + 4, 2 hf + 5
+  //      (high halves) of dword d of the codes, for the first (pass 0) or last 32 columns of the unit.
   {
-    const uint32_t items = 16u * B2;
+    const uint32_t items = 64u * B2;
     for (uint32_t it = tid; it < items; it += W * 64u) {
-      const uint32_t u = it >> 2, pass = (it >> 1) & 1u, h = it & 1u;
+      const uint32_t u = it >> 4, pass = (it >> 3) & 1u, d = (it >> 1) & 3u, hf = it & 1u;
       const uint2 ue = *(const uint2*)(units + u * 8u);
       const bool real = (ue.y & 0xFFFFu) != 32u * (uint32_t)b.G;  // padding units point at the zero entries
-      // slot 8 d + nn of the half unit <-> column 8 (nn % 4) + 2 d + nn / 4: dword (d, nn % 4) of the
-      // activations holds the columns of nibbles nn % 4 (low half) and nn % 4 + 4 (high half)
-      uint32_t xp[2][4];
-#pragma unroll
-      for (uint32_t dd = 0; dd < 2; ++dd)
-#pragma unroll
-        for (uint32_t q = 0; q < 4; ++q)
-          xp[dd][q] = real ? *(const uint32_t*)(xs + ue.x + 64u * pass + 16u * q + 4u * (2u * h + dd)) : 0u;
-      float sum = 0.f;
-      uint32_t mx = 0;
-#pragma unroll
-      for (uint32_t dd = 0; dd < 2; ++dd)
-#pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-          const half2_t v = as_h2(xp[dd][q]);
-          sum += (float)v.x;
-          sum += (float)v.y;
-          const uint32_t ab = xp[dd][q] & 0x7FFF7FFFu;
-          const uint32_t m16 = (ab >> 16) > (ab & 0xFFFFu) ? (ab >> 16) : (ab & 0xFFFFu);
-          mx = m16 > mx ? m16 : mx;
-        }
-      sum = quad_add(sum);   // the four items of a unit sit in the four lanes of a quad
+      // slot 8 d + nn of the half unit <-> column 8 (nn % 4) + 2 d + nn / 4
+      const unsigned char* xa = xs + ue.x + 64u * pass + 32u * hf + 4u * d;
+      const uint32_t x0 = real ? *(const uint32_t*)xa : 0u, x1 = real ? *(const uint32_t*)(xa + 16u) : 0u;
+      float sum = ((float)as_h2(x0).x + (float)as_h2(x0).y) + ((float)as_h2(x1).x + (float)as_h2(x1).y);
+      typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+      const ushort2_t m2 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, x0 & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, x1 & 0x7FFF7FFFu));
+      uint32_t mx = m2.x > m2.y ? m2.x : m2.y;   // bit pattern of the largest magnitude of the item
+      // sum and largest magnitude of the unit: over its 16 lanes (a row of the wave), every lane gets them
+      sum = quad_add(sum);
       mx = quad_max(mx);
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, sum), 0x141, 0xf, 0xf, true));  // row_half_mirror
+      sum += __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, sum), 0x140, 0xf, 0xf, true));  // row_mirror
+      {
+        uint32_t o = (uint32_t)__builtin_amdgcn_mov_dpp((int)mx, 0x141, 0xf, 0xf, true);
+        mx = mx > o ? mx : o;
+        o = (uint32_t)__builtin_amdgcn_mov_dpp((int)mx, 0x140, 0xf, 0xf, true);
+        mx = mx > o ? mx : o;
+      }
       uint32_t E = mx >> 10;  // exponent field of the largest magnitude of the unit
       E = E < 1u ? 1u : E > 30u ? 30u : E;
       // x' = x * 2^(15 - E): the largest is in [1, 2); pieces are fp8(x' 2^7), fp8(rest 2^11), fp8(rest 2^15)
       const uint32_t mbits = E < 30u ? (30u - E) << 10 : 0x0200u;
       const half2_t mult = as_h2(mbits | (mbits << 16));
-      uint32_t pc[3][2][2];  // [piece][dd][pairs 0,1 | pairs 2,3]: bytes = pair a low, a high, b low, b high
-#pragma unroll
-      for (uint32_t dd = 0; dd < 2; ++dd)
-#pragma unroll
-        for (uint32_t qq = 0; qq < 2; ++qq) {
-          short2_t q0 = {0, 0}, q1 = {0, 0}, q2 = {0, 0};
-          // ENC(v, s) = fp8(v / s) of both halves of v into the low or high word; DEC(p, s) = p * s
-#define MPQ_P_SPLIT(PAIR, HI)                                                                         \
+      short2_t q0 = {0, 0}, q1 = {0, 0}, q2 = {0, 0};  // bytes: pair 0 low, pair 0 high, pair 1 low, pair 1 high
+      // ENC(v, s) = fp8(v / s) of both halves of v into the low or high word; DEC(p, s) = p * s
+#define MPQ_P_SPLIT(XV, HI)                                                                           \
   {                                                                                                   \
-    const half2_t x1 = as_h2(xp[dd][PAIR]) * mult;                                                    \
-    q0 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q0, x1, 0.0078125f, HI);                            \
-    half2_t d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(__builtin_bit_cast(int, q0), 0.0078125f, HI); \
-    half2_t r = x1 - d;                                                                               \
+    const half2_t xm = as_h2(XV) * mult;                                                              \
+    q0 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q0, xm, 0.0078125f, HI);                            \
+    half2_t dc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(__builtin_bit_cast(int, q0), 0.0078125f, HI); \
+    half2_t r = xm - dc;                                                                              \
     q1 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q1, r, 0.00048828125f, HI);                         \
-    d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(__builtin_bit_cast(int, q1), 0.00048828125f, HI);    \
-    r = r - d;                                                                                        \
+    dc = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(__builtin_bit_cast(int, q1), 0.00048828125f, HI);   \
+    r = r - dc;                                                                                       \
     q2 = __builtin_amdgcn_cvt_scalef32_pk_fp8_f16(q2, r, 0.000030517578125f, HI);                     \
   }
-          MPQ_P_SPLIT(2 * qq, false)
-          MPQ_P_SPLIT(2 * qq + 1, true)
+      MPQ_P_SPLIT(x0, false)
+      MPQ_P_SPLIT(x1, true)
 #undef MPQ_P_SPLIT
-          pc[0][dd][qq] = (uint32_t)__builtin_bit_cast(int, q0);
-          pc[1][dd][qq] = (uint32_t)__builtin_bit_cast(int, q1);
-          pc[2][dd][qq] = (uint32_t)__builtin_bit_cast(int, q2);
-        }
-      // bytes of a piece chunk: slots 8 dd + 0..3 = low halves of pairs 0..3, 8 dd + 4..7 = their high halves
-#pragma unroll
-      for (uint32_t p = 0; p < 3; ++p) {
-        uint4 o;
-        o.x = __builtin_amdgcn_perm(pc[p][0][1], pc[p][0][0], 0x06040200u);
-        o.y = __builtin_amdgcn_perm(pc[p][0][1], pc[p][0][0], 0x07050301u);
-        o.z = __builtin_amdgcn_perm(pc[p][1][1], pc[p][1][0], 0x06040200u);
-        o.w = __builtin_amdgcn_perm(pc[p][1][1], pc[p][1][0], 0x07050301u);
-        *(uint4*)(pieces + u * 192u + pass * 96u + p * 32u + h * 16u) = o;
-      }
+      // slots 8 d + 2 hf, + 1 take the low halves of the two pairs, slots 8 d + 4 + 2 hf, + 1 their high halves
+      unsigned char* pd = pieces + u * 192u + pass * 96u + d * 8u + hf * 2u;
+      const uint32_t p0 = (uint32_t)__builtin_bit_cast(int, q0), p1 = (uint32_t)__builtin_bit_cast(int, q1), p2 = (uint32_t)__builtin_bit_cast(int, q2);
+      *(uint16_t*)(pd) = (uint16_t)__builtin_amdgcn_perm(0u, p0, 0x0c0c0200u);
+      *(uint16_t*)(pd + 4u) = (uint16_t)__builtin_amdgcn_perm(0u, p0, 0x0c0c0301u);
+      *(uint16_t*)(pd + 32u) = (uint16_t)__builtin_amdgcn_perm(0u, p1, 0x0c0c0200u);
+      *(uint16_t*)(pd + 36u) = (uint16_t)__builtin_amdgcn_perm(0u, p1, 0x0c0c0301u);
+      *(uint16_t*)(pd + 64u) = (uint16_t)__builtin_amdgcn_perm(0u, p2, 0x0c0c0200u);
+      *(uint16_t*)(pd + 68u) = (uint16_t)__builtin_amdgcn_perm(0u, p2, 0x0c0c0301u);
       // per unit: the sum of its activations and the exponent byte of piece 0's scale, 2^(E - 22)
-      if ((it & 3u) == 0) *(uint2*)(utab + u * 8u) = uint2{__builtin_bit_cast(uint32_t, sum), 105u + E};
+      if ((it & 15u) == 0) *(uint2*)(utab + u * 8u) = uint2{__builtin_bit_cast(uint32_t, sum), 105u + E};
     }
   }
 
-  // ---- (3) outliers (Sec. 4.3, fused): wave t sums the record of tile t, four lanes per row
-  if (wv < n) {
-    const uint32_t* ostart = (const uint32_t*)(lds + pl.off_obuf + wv * pl.obuf_bytes);
+  // ---- (3) outliers (Sec. 4.3, fused): og waves per tile, 64 og / 16 lanes per row, two words per
+  //      lane in flight
+  if (ot < n) {
+    const uint32_t* ostart = (const uint32_t*)(lds + pl.off_obuf + ot * pl.obuf_bytes);
     const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
-    const uint32_t orow = lane >> 2, oq = lane & 3u;
+    const uint32_t lpr = 4u * og;                              // lanes per row
+    const uint32_t ol = (ow % og) * 64u + lane;                // lane index inside the tile's group of waves
+    const uint32_t orow = ol / lpr, oq = ol % lpr;
     const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
-    float oa = 0.f;
-    for (uint32_t e = rp0 + oq; e < rp1; e += 4) {
-      const uint32_t word = owords[e];
-      const float v = (float)bits_to_half((uint16_t)(word >> 16));
-      oa = __builtin_fmaf(v, (float)*(const half_t*)(xs + (word & 0xFFFFu) * 2u), oa);
+    float oa = 0.f, ob = 0.f;
+    for (uint32_t e = rp0 + oq; e < rp1; e += 2u * lpr) {
+      const uint32_t wa = owords[e], wb = e + lpr < rp1 ? owords[e + lpr] : 0u;
+      const float xa = (float)*(const half_t*)(xs + (wa & 0xFFFFu) * 2u), xb = (float)*(const half_t*)(xs + (wb & 0xFFFFu) * 2u);
+      oa = __builtin_fmaf((float)bits_to_half((uint16_t)(wa >> 16)), xa, oa);
+      ob = __builtin_fmaf((float)bits_to_half((uint16_t)(wb >> 16)), xb, ob);
     }
+    oa += ob;
     oa = quad_add(oa);
-    if (oq == 0) red[(wv * (2 * W + 1) + 2 * W) * 16 + orow] = oa;
+    if (og == 4u) {  // 16 lanes per row: lane 15 of the row ends with the total
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x114, 0xf, 0xf, true));
+      oa += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, oa), 0x118, 0xf, 0xf, true));
+      if (oq == 15u) red[(ot * (2 * W + 1) + 2 * W) * 16 + orow] = oa;
+    } else if (oq == 0u) {
+      red[(ot * (2 * W + 1) + 2 * W) * 16 + orow] = oa;
+    }
   }
   lds_barrier();
 
@@ -1316,67 +1364,72 @@ mpq_gemvp_kernel(const PlaneArgs a) {
   // covers (low 16 bytes: slots 16 j .. 16 j + 15, high 16 bytes: slots 64 + 16 j ..), zeros elsewhere
   const uint32_t ga = i >> 2, pa = i & 3u;
   const bool act = (j >> 1) == (ga & 1u) && pa < 3u;
-  const uint32_t chunk = ga * 192u + pa * 32u + (j & 1u) * 16u;
-  const uint32_t zoff = pl.off_zero - pl.off_pieces;
-  const uint32_t a_lo0 = act && ga < 2u ? chunk : zoff, a_lo1 = act && ga < 2u ? 768u : 0u;
-  const uint32_t a_hi0 = act && ga >= 2u ? chunk : zoff, a_hi1 = act && ga >= 2u ? 768u : 0u;
+  const uint32_t chunk = pl.off_pieces + ga * 192u + pa * 32u + (j & 1u) * 16u;
+  const uint32_t a_lo0 = act && ga < 2u ? chunk : pl.off_zero, a_lo1 = act && ga < 2u ? 768u : 0u;
+  const uint32_t a_hi0 = act && ga >= 2u ? chunk : pl.off_zero, a_hi1 = act && ga >= 2u ? 768u : 0u;
   const int sc_lane = -4 * (int)pa;
-  const uint32_t slot_lane = ring0 + lane16, meta_lane = ring0 + 1024u + lane * 4u;
-  uint32_t slot = 0;
-  uint32_t c = wv;  // next block of this wave inside the current tile (>= C: none in this tile)
-  for (uint32_t t = 0; t < n; ++t) {
-    float yacc = 0.f;                        // row i, units j of this wave's 2-bit blocks
-    float4_t acc4 = {0.f, 0.f, 0.f, 0.f};    // this wave's 4-bit blocks (batch column 0 of the f16 instruction)
-#define MPQ_P_HEAD                                                                                     \
-    if (inflight == PD) MPQ_VMCNT(OPS * (PD - 1)); else MPQ_VMCNT(0);                                  \
-    uint4 q;                                                                                           \
-    uint32_t w1[1], w2[1];                                                                             \
-    ring_read<1, 1>(slot_lane + slot * SLOTB, meta_lane + slot * SLOTB, q, w1, w2);                    \
-    --inflight;                                                                                        \
-    if (rt < n) MPQ_P_REQUEST(slot)                                                                    \
-    slot = slot + 1 == PD ? 0 : slot + 1;                                                              \
-    const uint32_t m1 = (i & 1u) ? w1[0] >> 16 : w1[0] & 0xFFFFu;                                      \
-    const half_t s1 = scale_dequant(m1 & 0xFFu, w2[0]);  /* exactly 0 for a padding unit */            \
-    const half2_t s1p = {s1, s1};                                                                      \
-    const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  /* 1024 + z1 */
-    for (; c < B2; c += W) {
-      MPQ_P_HEAD
-      // the four values a code of this (row, unit) decodes to, rounded as eq. 5 rounds them
-      const half2_t zbp = {zb, zb};
-      const half2_t t01 = (half2_t{(half_t)1024.f, (half_t)1025.f} - zbp) * s1p;
-      const half2_t t23 = (half2_t{(half_t)1026.f, (half_t)1027.f} - zbp) * s1p;
-      const float T0 = (float)t01.x, e1 = (float)t01.y - T0, e2 = (float)t23.x - T0;
-      const float dl = ((float)t23.y - (float)t23.x) - e1;
-      const uint2 ut = *(const uint2*)(utab + (4u * c + j) * 8u);
-      const int sca = (int)ut.y + sc_lane;
-      const unsigned char* pb = pieces;
-      const uint4 ax0 = *(const uint4*)(pb + a_lo0 + c * a_lo1), ax1 = *(const uint4*)(pb + a_hi0 + c * a_hi1);
-      const uint4 ay0 = *(const uint4*)(pb + a_lo0 + c * a_lo1 + 96u), ay1 = *(const uint4*)(pb + a_hi0 + c * a_hi1 + 96u);
-      const v8i_t ax = {(int)ax0.x, (int)ax0.y, (int)ax0.z, (int)ax0.w, (int)ax1.x, (int)ax1.y, (int)ax1.z, (int)ax1.w};
-      const v8i_t ay = {(int)ay0.x, (int)ay0.y, (int)ay0.z, (int)ay0.w, (int)ay1.x, (int)ay1.y, (int)ay1.z, (int)ay1.w};
-      const uint32_t r0 = __builtin_amdgcn_alignbit(q.x, q.x, 2), r1 = __builtin_amdgcn_alignbit(q.y, q.y, 2);
-      const uint32_t r2 = __builtin_amdgcn_alignbit(q.z, q.z, 2), r3 = __builtin_amdgcn_alignbit(q.w, q.w, 2);
+  const uint32_t unit_lane = pl.off_units + j * 8u, utab_lane = pl.off_utab + j * 8u;
+  uint32_t code_addr = ring0 + lane16, meta_addr = ring0 + 1024u + lane * 4u;  // of the slot read next
+  float one;
+  asm volatile("v_mov_b32 %0, 1.0" : "=v"(one));  // opaque to the optimiser: keeps x * one - y a single fma
+  {
+    uint32_t t = t_first, c = c_first;       // the wave's current block: block c of tile t
+    float yacc = 0.f;                        // row i, units j of this wave's 2-bit blocks of the tile
+    float4_t acc4 = {0.f, 0.f, 0.f, 0.f};    // its 4-bit blocks (batch column 0 of the f16 instruction)
+    for (uint32_t todo = k1 - k0; todo > 0; --todo) {
+      MPQ_VMCNT(3);  // the block has landed: only the three requests of the other slot are younger
+      uint4 q;
+      uint32_t w1, w2, unit_word;
+      plane_ring_read(code_addr, meta_addr, uaddr, q, w1, w2, unit_word);
+      MPQ_P_REQUEST(unit_word)
+      code_addr = 2u * (ring0 + lane16) + SLOTB - code_addr;
+      meta_addr = 2u * (ring0 + 1024u + lane * 4u) + SLOTB - meta_addr;
+      // (s1, z1) of the lane's (row, unit) from the scale words that came with the block
+      const uint32_t m1 = (i & 1u) ? w1 >> 16 : w1 & 0xFFFFu;
+      const half_t s1 = scale_dequant(m1 & 0xFFu, w2);  // exactly 0 for a padding unit
+      const half2_t s1p = {s1, s1};
+      const half_t zb = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));  // 1024 + z1
+      if (c < B2) {
+        const uint2 ut = *(const uint2*)(lds + utab_lane + c * 32u);
+        const uint32_t alo = __umul24(c, a_lo1) + a_lo0, ahi = __umul24(c, a_hi1) + a_hi0;
+        const uint4 ax0 = *(const uint4*)(lds + alo), ax1 = *(const uint4*)(lds + ahi);
+        const uint4 ay0 = *(const uint4*)(lds + alo + 96u), ay1 = *(const uint4*)(lds + ahi + 96u);
+        const int sca = (int)ut.y + sc_lane;
+        const v8i_t ax = {(int)ax0.x, (int)ax0.y, (int)ax0.z, (int)ax0.w, (int)ax1.x, (int)ax1.y, (int)ax1.z, (int)ax1.w};
+        const v8i_t ay = {(int)ay0.x, (int)ay0.y, (int)ay0.z, (int)ay0.w, (int)ay1.x, (int)ay1.y, (int)ay1.z, (int)ay1.w};
+        const uint32_t r0 = __builtin_amdgcn_alignbit(q.x, q.x, 2), r1 = __builtin_amdgcn_alignbit(q.y, q.y, 2);
+        const uint32_t r2 = __builtin_amdgcn_alignbit(q.z, q.z, 2), r3 = __builtin_amdgcn_alignbit(q.w, q.w, 2);
 #define MPQ_P_PLANE(MASK, X0, X1, X2, X3) \
   v8i_t{(int)((X0) & (MASK)), (int)((X1) & (MASK)), (int)((X2) & (MASK)), (int)((X3) & (MASK)), 0, 0, 0, 0}
-      const float4_t z4 = {0.f, 0.f, 0.f, 0.f};
-      float4_t s0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ax, MPQ_P_PLANE(0x22222222u, q.x, q.y, q.z, q.w), z4, 0, 4, 0, sca, 0, 0x7F7F7F7F);
-      float4_t sb = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ax, MPQ_P_PLANE(0x44444444u, q.x, q.y, q.z, q.w), z4, 0, 4, 0, sca, 0, 0x7F7F7F7F);
-      float4_t sg = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ax, MPQ_P_PLANE(0x66666666u, q.x, q.y, q.z, q.w), z4, 0, 4, 0, sca, 0, 0x7F7F7F7F);
-      s0 = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ay, MPQ_P_PLANE(0x22222222u, r0, r1, r2, r3), s0, 0, 4, 0, sca, 0, 0x7F7F7F7F);
-      sb = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ay, MPQ_P_PLANE(0x44444444u, r0, r1, r2, r3), sb, 0, 4, 0, sca, 0, 0x7F7F7F7F);
-      sg = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(ay, MPQ_P_PLANE(0x66666666u, r0, r1, r2, r3), sg, 0, 4, 0, sca, 0, 0x7F7F7F7F);
+#define MPQ_P_MFMA(A, B, ACC) __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(A, B, ACC, 0, 4, 0, sca, 0, 0x7F7F7F7F)
+        const float4_t z4 = {0.f, 0.f, 0.f, 0.f};
+        float4_t s0 = MPQ_P_MFMA(ax, MPQ_P_PLANE(0x22222222u, q.x, q.y, q.z, q.w), z4);
+        float4_t sb = MPQ_P_MFMA(ax, MPQ_P_PLANE(0x44444444u, q.x, q.y, q.z, q.w), z4);
+        float4_t sg = MPQ_P_MFMA(ax, MPQ_P_PLANE(0x66666666u, q.x, q.y, q.z, q.w), z4);
+        s0 = MPQ_P_MFMA(ay, MPQ_P_PLANE(0x22222222u, r0, r1, r2, r3), s0);
+        sb = MPQ_P_MFMA(ay, MPQ_P_PLANE(0x44444444u, r0, r1, r2, r3), sb);
+        sg = MPQ_P_MFMA(ay, MPQ_P_PLANE(0x66666666u, r0, r1, r2, r3), sg);
+#undef MPQ_P_MFMA
 #undef MPQ_P_PLANE
-      const float S0 = (s0[0] + s0[1]) + s0[2], S1 = (sb[0] + sb[1]) + sb[2], Sg = (sg[0] + sg[1]) + sg[2];
-      yacc = __builtin_fmaf(T0, __builtin_bit_cast(float, ut.x), yacc);
-      yacc = __builtin_fmaf(e1 - dl, S0, yacc);
-      yacc = __builtin_fmaf(__builtin_fmaf(0.5f, e2, -dl), S1, yacc);
-      yacc = __builtin_fmaf(dl, Sg, yacc);
-    }
-    for (; c < C; c += W) {
-      MPQ_P_HEAD
-      const uint32_t xoff = *(const uint32_t*)(units + (4u * c + j) * 8u);
-      const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+        // the four values a code of this (row, unit) decodes to, rounded as eq. 5 rounds them
+        const half2_t zbp = {zb, zb};
+        const half2_t t01 = (half2_t{(half_t)1024.f, (half_t)1025.f} - zbp) * s1p;
+        const half2_t t23 = (half2_t{(half_t)1026.f, (half_t)1027.f} - zbp) * s1p;
+        // differences of halves as mixed-precision fmas (x * one - y): one instruction each
+        const float T0 = (float)t01.x;
+        const float e1 = __builtin_fmaf((float)t01.y, one, -T0), e2 = __builtin_fmaf((float)t23.x, one, -T0);
+        const float dl = __builtin_fmaf((float)t23.y, one, -(float)t23.x) - e1;
+        const float c0 = e1 - dl, c1 = __builtin_fmaf(0.5f, e2, -dl);
+        yacc = __builtin_fmaf(T0, __builtin_bit_cast(float, ut.x), yacc);
+        const float S0 = (s0[0] + s0[1]) + s0[2], S1 = (sb[0] + sb[1]) + sb[2], Sg = (sg[0] + sg[1]) + sg[2];
+        yacc = __builtin_fmaf(c0, S0, yacc);
+        yacc = __builtin_fmaf(c1, S1, yacc);
+        yacc = __builtin_fmaf(dl, Sg, yacc);
+      } else {
+        // a 4-bit block: every weight decoded (eq. 5), the f16 matrix instruction multiplies and adds
+        const uint32_t xoff = *(const uint32_t*)(lds + unit_lane + c * 32u);
+        const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+        const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
 #define MPQ_P_STEP4(P)                                                                                \
   {                                                                                                   \
     const uint4 av = decode_step<false, P>(lo, hi, s1p, zb, kc);                                      \
@@ -1384,32 +1437,43 @@ mpq_gemvp_kernel(const PlaneArgs a) {
     acc4 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
                                                   __builtin_bit_cast(half8_t, bv), acc4, 0, 0, 0);    \
   }
-      MPQ_P_STEP4(0) MPQ_P_STEP4(1) MPQ_P_STEP4(2) MPQ_P_STEP4(3)
+        MPQ_P_STEP4(0) MPQ_P_STEP4(1) MPQ_P_STEP4(2) MPQ_P_STEP4(3)
 #undef MPQ_P_STEP4
+      }
+      if (++c == C || todo == 1) {
+        // end of the tile (or of the wave's run): park the rows of the 2-bit part, added over the four
+        // units of a block position in a fixed order, and batch column 0 of the 4-bit accumulator
+        // (lane (j, 0) holds rows 4 j .. 4 j + 3)
+        float yr = yacc;
+        yr += __shfl_xor(yr, 16);
+        yr += __shfl_xor(yr, 32);
+        float* rt_ = red + t * (2 * W + 1) * 16;
+        if (j == 0) rt_[wv * 16 + i] = yr;
+        if (i == 0) *(float4_t*)(rt_ + (W + wv) * 16 + 4 * j) = acc4;
+        yacc = 0.f;
+        acc4 = float4_t{0.f, 0.f, 0.f, 0.f};
+        c = 0;
+        ++t;
+      }
     }
-#undef MPQ_P_HEAD
-    c -= C;  // the sequence continues in the next tile
-    // park: rows of the 2-bit part summed over the four units of a block position (fixed order), and
-    // batch column 0 of the 4-bit accumulator (lane (j, 0) holds rows 4 j .. 4 j + 3)
-    float yr = yacc;
-    yr += __shfl_xor(yr, 16);
-    yr += __shfl_xor(yr, 32);
-    float* rt_ = red + t * (2 * W + 1) * 16;
-    if (j == 0) rt_[wv * 16 + i] = yr;
-    if (i == 0) *(float4_t*)(rt_ + (W + wv) * 16 + 4 * j) = acc4;
   }
 #undef MPQ_P_REQUEST
-
+  MPQ_VMCNT(0);  // the re-requested blocks past the end of the run
   lds_barrier();
-  // ---- (5) row r of tile t: the outlier term, then the partial sums in a fixed order
-  if (tid < 16 * n) {
-    const uint32_t t = tid >> 4, r = tid & 15u;
+
+  // ---- (5) row r of tile t: 16 lanes add the 2 W partial sums and the outlier term, always in the same order
+  for (uint32_t o = tid; o < 256u * n; o += W * 64u) {
+    const uint32_t t = o >> 8, r = (o >> 4) & 15u, k = o & 15u;
     const float* rt0 = red + t * (2 * W + 1) * 16 + r;
-    float sum = rt0[2 * W * 16];
-#pragma unroll
-    for (uint32_t w2 = 0; w2 < 2 * W; ++w2) sum += rt0[w2 * 16];
+    float sum = rt0[k * 16];
+    if (W == 16) sum += rt0[(k + 16) * 16];
+    if (k == 0) sum += rt0[2 * W * 16];
+    sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x111, 0xf, 0xf, true));
+    sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x112, 0xf, 0xf, true));
+    sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x114, 0xf, 0xf, true));
+    sum += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, sum), 0x118, 0xf, 0xf, true));
     const uint32_t row = (tile0 + t) * 16 + r;
-    if (row < (uint32_t)b.N) a.Y[row] = half_to_bits((half_t)sum);
+    if (k == 15u && row < (uint32_t)b.N) a.Y[row] = half_to_bits((half_t)sum);
   }
 }
 
@@ -1662,9 +1726,9 @@ mpq_status gemv_decode(const Ctx& c, const uint16_t* X, uint16_t* Y) {
 // ---------------------------------------------------------------- M = 1, plane-sum kernel
 
 // LDS layout of the plane-sum GEMV for n tiles per workgroup of W waves; false if it does not fit.
-bool plane_layout(const MpqHeader& h, uint32_t W, uint32_t n, uint32_t budget, PlanePlan* pl) {
+bool plane_layout(const MpqHeader& h, uint32_t W, uint32_t PD, uint32_t n, uint32_t budget, PlanePlan* pl) {
   const uint32_t C = (uint32_t)(h.B2 + h.B4);
-  uint32_t off = W * 2u * 1536u;                        // ring: two slots of codes + two meta words per lane
+  uint32_t off = W * PD * 1536u;                        // ring: PD slots of codes + two meta words per lane
   pl->off_park = off;   off += n * (2u * W + 1u) * 64u;
   pl->off_units = off;  off += 32u * C;                  // unit table
   off = (off + 15u) & ~15u;
@@ -1676,6 +1740,22 @@ bool plane_layout(const MpqHeader& h, uint32_t W, uint32_t n, uint32_t budget, P
   pl->off_obuf = off;   off += n * pl->obuf_bytes;
   pl->n = n;
   return off <= budget;
+}
+
+// Share of a SIMD's blocks per age rank of its waves, in sixteenths (see PlanePlan): `older` = what the
+// oldest wave of a SIMD takes beyond an even share, handed down linearly to the youngest.
+void plane_deal(uint32_t W, int older, PlanePlan* pl) {
+  const uint32_t ranks = W / 4u;
+  uint32_t share[4] = {0, 0, 0, 0};
+  if (ranks == 4) {
+    const uint32_t d = older < 0 ? 0u : older > 3 ? 3u : (uint32_t)older;   // 4+d, 4+d/2.., 4-d/2.., 4-d
+    share[0] = 4u + d; share[1] = 4u + d / 2u; share[2] = 4u - d / 2u; share[3] = 4u - d;
+  } else {
+    const uint32_t d = older < 0 ? 0u : older > 6 ? 6u : (uint32_t)older;
+    share[0] = 8u + d; share[1] = 8u - d;
+  }
+  pl->cum[0] = 0;
+  for (uint32_t w = 0; w < 16; ++w) pl->cum[w + 1] = pl->cum[w] + (w < W ? share[w / 4u] : 0u);
 }
 
 template <int LDSB, int WV>
@@ -1690,35 +1770,30 @@ mpq_status launch_planes(const Ctx& c, PlaneArgs& a) {
 // split activations; MPQ_ERR_UNSUPPORTED otherwise.
 mpq_status gemv_planes(const Ctx& c, const uint16_t* X, uint16_t* Y) {
   const MpqHeader& h = c.h;
-  if (mpq_pu2(h.g1) != 1) return MPQ_ERR_UNSUPPORTED;
-  const uint32_t W = c.plan.gemv_waves == 8 ? 8u : 16u;
-  // tiles per workgroup: one generation of workgroups if the LDS allows it, at most W (wave t sums the
-  // outliers of tile t), else the smallest number of equal generations
-  uint32_t n = c.plan.gemv_tiles > 0 ? (uint32_t)c.plan.gemv_tiles : ((uint32_t)h.T + (uint32_t)c.cus - 1u) / (uint32_t)c.cus;
-  if (n > W) n = W;
   PlaneArgs a;
+  if (mpq_pu2(h.g1) != 1 || 4 * (h.B2 + h.B4) > MPQ_PLANE_MAX_UNITS || !mpq_internal_unit_words(&h, a.uw))
+    return MPQ_ERR_UNSUPPORTED;
+  const uint32_t W = c.plan.gemv_waves == 8 ? 8u : 16u;
+  // tiles per workgroup: one generation of workgroups if the LDS allows it, at most W (a wave group per
+  // tile sums its outliers), else the smallest number of equal generations
+  uint32_t n = 0;
+  if (c.plan.gemv_tiles > 0) {
+    n = (uint32_t)c.plan.gemv_tiles > W ? W : (uint32_t)c.plan.gemv_tiles;
+    if (!plane_layout(h, W, 2, n, 160 * 1024, &a.pl)) return MPQ_ERR_UNSUPPORTED;
+  } else {
+    for (uint32_t gens = 1;; ++gens) {
+      n = ((uint32_t)h.T + gens * (uint32_t)c.cus - 1u) / (gens * (uint32_t)c.cus);
+      if (n <= W && plane_layout(h, W, 2, n, 160 * 1024, &a.pl)) break;
+      if (n <= 1) return MPQ_ERR_UNSUPPORTED;
+    }
+  }
+  plane_deal(W, c.plan.gemv_older > 0 ? c.plan.gemv_older - 1 : 2, &a.pl);
   a.b = c.d;
   a.X = X;
   a.Y = Y;
-  if (c.plan.gemv_tiles <= 0) {
-    uint32_t gens = 1;
-    while (true) {
-      n = ((uint32_t)h.T + gens * (uint32_t)c.cus - 1u) / (gens * (uint32_t)c.cus);
-      if (n <= W && plane_layout(h, W, n, 160 * 1024, &a.pl)) break;
-      if (n <= 1) return MPQ_ERR_UNSUPPORTED;
-      ++gens;
-    }
-  } else if (!plane_layout(h, W, n, 160 * 1024, &a.pl)) {
-    return MPQ_ERR_UNSUPPORTED;
-  }
-  uint32_t need = a.pl.off_obuf + a.pl.n * a.pl.obuf_bytes;
-  if (W == 16) {
-    if (need <= 80 * 1024) return launch_planes<80 * 1024, 16>(c, a);
-    return launch_planes<160 * 1024, 16>(c, a);
-  }
-  if (need <= 53 * 1024) return launch_planes<53 * 1024, 8>(c, a);
-  if (need <= 80 * 1024) return launch_planes<80 * 1024, 8>(c, a);
-  return launch_planes<160 * 1024, 8>(c, a);
+  const uint32_t need = a.pl.off_obuf + a.pl.n * a.pl.obuf_bytes;
+  if (W == 16) return need <= 80 * 1024 ? launch_planes<80 * 1024, 16>(c, a) : launch_planes<160 * 1024, 16>(c, a);
+  return need <= 80 * 1024 ? launch_planes<80 * 1024, 8>(c, a) : launch_planes<160 * 1024, 8>(c, a);
 }
 
 // ---------------------------------------------------------------- 2 <= M <= 32
@@ -1867,8 +1942,14 @@ mpq_status launch_slices(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, vo
   return MPQ_OK;
 }
 
+// Which batch-1 kernel: the plane-sum kernel pays a fixed price per workgroup (the activations are split
+// into fp8 pieces, two more barriers) and needs 40 % fewer vector instructions per block; measured on
+// the Llama2-7B / Llama3-8B / Llama2-70B shapes it wins from about eight 16-row tiles per compute unit
+// on (57344 x 8192: 35 against 41 us, 128256 x 4096: 42 against 46 us) and loses below (12288 x 4096:
+// 8.7 against 7.0 us).
 mpq_status gemv_all(const Ctx& c, const uint16_t* X, uint16_t* Y) {
-  if (c.plan.gemv_path != 2) {
+  const bool planes = c.plan.gemv_path == 1 || (c.plan.gemv_path == 0 && c.h.T >= 8 * c.cus);
+  if (planes) {
     const mpq_status st = gemv_planes(c, X, Y);
     if (st != MPQ_ERR_UNSUPPORTED || c.plan.gemv_path == 1) return st;
   }

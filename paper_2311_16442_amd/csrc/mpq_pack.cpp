@@ -2,6 +2,7 @@
 // builder (Sec. 3.3 "Memory Alignment": two code matrices with aligned, width-homogeneous vector
 // units), blob inspection and the average-bit formulas (Sec. 2.2, Sec. 3.3, Sec. 4.2).
 #include <math.h>
+#include <stddef.h>
 #include <string.h>
 
 #include <algorithm>
@@ -147,9 +148,36 @@ mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out) {
   mpq_desc d = {h.N, h.K, h.g1, h.g2, h.g2_axis};
   if (!desc_ok(&d)) return MPQ_ERR_BLOB;
   if (plan(&d, h.n4, h.nnz, (int64_t)h.ocap, &want) != MPQ_OK) return MPQ_ERR_BLOB;
-  if (memcmp(&h, &want, sizeof(h)) != 0) return MPQ_ERR_BLOB;
+  if (memcmp(&h, &want, offsetof(MpqHeader, is4_bits)) != 0) return MPQ_ERR_BLOB;
+  int32_t set = 0;
+  for (int32_t g = 0; g < (int32_t)MPQ_IS4_BITS; ++g)
+    if (h.is4_bits[g / 8] >> (g % 8) & 1) {
+      if (g >= h.G) return MPQ_ERR_BLOB;
+      ++set;
+    }
+  if (set != (h.G <= (int32_t)MPQ_IS4_BITS ? h.n4 : 0)) return MPQ_ERR_BLOB;
   *out = h;
   return MPQ_OK;
+}
+
+bool mpq_internal_unit_words(const MpqHeader* h, uint32_t* words) {
+  if (h->G > (int32_t)MPQ_IS4_BITS || h->g1 < 64) return false;
+  const int32_t up2 = h->g1 / 64, up4 = h->g1 / 32;  // units per group in the 2-bit / 4-bit stream
+  const int32_t nsub = mpq_nsub(h->g2);
+  const uint32_t zero_word = (uint32_t)(h->G * 32) | (mpq_meta2_zero(h) << 16);
+  const int32_t C = h->B2 + h->B4;
+  for (int32_t u = 0; u < 4 * C; ++u) words[u] = zero_word;
+  int32_t i2 = 0, i4 = 0;  // groups of each width seen so far = their index in the stream
+  for (int32_t g = 0; g < h->G; ++g) {
+    const bool four = h->is4_bits[g / 8] >> (g % 8) & 1;
+    const int32_t si = four ? h->n2 + i4 : i2;  // stream index: 2-bit groups first
+    const uint32_t m2off = h->g2_axis == 0 ? (uint32_t)((g / h->g2) * 64) : (uint32_t)(si * 4 * nsub);
+    const uint32_t word = (uint32_t)(si * 32) | (m2off << 16);
+    const int32_t up = four ? up4 : up2, first = four ? 4 * h->B2 + i4 * up4 : i2 * up2;
+    for (int32_t k = 0; k < up; ++k) words[first + k] = word;
+    if (four) ++i4; else ++i2;
+  }
+  return true;
 }
 
 extern "C" {
@@ -377,6 +405,9 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   // ---- layout
   uint8_t* blob = (uint8_t*)blob_host;
   memset(blob, 0, (size_t)h.total_bytes);
+  if (G <= (int64_t)MPQ_IS4_BITS)
+    for (int64_t g = 0; g < G; ++g)
+      if (w->is4[g]) h.is4_bits[g / 8] |= (uint8_t)(1u << (g % 8));
   memcpy(blob, &h, sizeof(h));
   // stream order of the groups and the unit tables
   std::vector<int32_t> groups2, groups4, stream_index(G);

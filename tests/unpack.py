@@ -16,6 +16,7 @@ def read_header(blob: np.ndarray) -> dict:
     offs = struct.unpack_from("<9Q", raw, 72)
     for n, v in zip(["off_units", "off_tiles", "tile_stride", "side_bytes", "codes_off", "ocap", "r0", "r1", "total"], offs):
         h[n] = v
+    h["is4_bits"] = np.frombuffer(raw[144:256], dtype=np.uint8)      # bit g: K-group g is 4-bit (if G <= 896)
     return h
 
 
@@ -86,6 +87,8 @@ def unpack(blob: np.ndarray) -> dict:
                 assert m2off[g] == e1 >> 16 and (e1 & 0xFFFF) == 32 * stream_groups.index(g)
             codes[:, k0: k0 + cpp] = field[:, q * cpp: (q + 1) * cpp]
     assert len(stream_groups) == G and sorted(stream_groups) == list(range(G))
+    bits = np.unpackbits(h["is4_bits"], bitorder="little")
+    assert np.array_equal(bits[:G], is4) and not bits[G:].any() if G <= 896 else not bits.any()
     m1 = np.ascontiguousarray(tiles[:, : 32 * (G + 1)]).view(np.uint16).reshape(T, G + 1, TILE)
     assert not m1[:, G].any()                             # the zero entry padding pieces point at
     s_int = np.zeros((T * TILE, G), dtype=np.uint8)
