@@ -23,7 +23,8 @@
  *   y[n]      = sum_k Wd[n][k] x[k] + sum_{outliers of row n} val x[col]
  *
  * Memory.  The library never allocates, frees or retains device memory and keeps no state between
- * calls: every choice a call makes follows from its arguments and from the compute-unit count of the
+ * calls (mpq_gemm_static alone remembers, per device, the address of the library's own scratch array):
+ * every choice a call makes follows from its arguments and from the compute-unit count of the
  * current device, which is queried in the call (MPQ_ERR_HIP if the query fails).  Host entry points take HOST pointers; device entry points take DEVICE pointers for bulk
  * data and a HOST pointer to the blob header (the first MPQ_HEADER_BYTES bytes of the packed
  * blob), so that no call ever needs a device-to-host copy.  All pointers are owned by the caller.
@@ -49,6 +50,7 @@ extern "C" {
 #define MPQ_HEADER_BYTES 256u
 #define MPQ_MAX_M 32          /* largest batch the small-M product accepts */
 #define MPQ_MAX_MULTI 8       /* most products one mpq_gemv_multi call accepts */
+#define MPQ_STATIC_SCRATCH_BYTES (32u << 20) /* device scratch inside the library that mpq_gemm_static uses */
 
 typedef enum {
   MPQ_OK = 0,
@@ -239,6 +241,20 @@ typedef struct {
 mpq_status mpq_gemm_planned(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
                             int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream,
                             const mpq_plan* plan, mpq_report* report);
+
+/* mpq_gemm for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same kernels,
+ * same results as mpq_gemm given a workspace of mpq_gemm_workspace_size bytes; the workspace is an
+ * array of MPQ_STATIC_SCRATCH_BYTES bytes that is part of the library's device image (every GPU the
+ * library runs on holds it until the process ends).  The call allocates and frees nothing.
+ * MPQ_ERR_SIZE if this matrix and batch need more than MPQ_STATIC_SCRATCH_BYTES (57344 x 8192 needs
+ * 7.6 MiB at M = 16); MPQ_ERR_HIP if the array's address cannot be obtained on the current device (it is
+ * asked for on the first call per device and kept - the only state the library holds).
+ * All calls on one GPU share the one array: calls that may overlap on a GPU (different streams,
+ * different threads) race on it and must be serialised by the caller, or use mpq_gemm with workspaces of
+ * their own. */
+mpq_status mpq_gemm_static(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                           int32_t M, void* stream);
 
 /* mpq_gemm_workspace_size for a call under `plan` (the number of K ranges is a plan field). */
 mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, const mpq_plan* plan, size_t* bytes);

@@ -26,7 +26,8 @@ STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ
 
 EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_quantize_host", "mpq_quantize_outlier_capacity", "mpq_packed_size",
            "mpq_pack_host", "mpq_blob_info", "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm_workspace_size",
-           "mpq_gemm", "mpq_gemm_planned", "mpq_gemm_workspace_size_planned"]
+           "mpq_gemm", "mpq_gemm_planned", "mpq_gemm_workspace_size_planned", "mpq_gemm_static"]
+STATIC_SCRATCH_BYTES = 32 << 20
 (KERNEL_GEMV_PLANES, KERNEL_GEMV_DECODE, KERNEL_BATCH_RESIDENT, KERNEL_BATCH_RANGES) = (1, 2, 3, 4)
 MAX_MULTI = 8
 
@@ -115,6 +116,8 @@ def lib():
                                        C.c_void_p, C.POINTER(Plan), C.POINTER(Report)]
         L.mpq_gemm_workspace_size_planned.restype = C.c_int
         L.mpq_gemm_workspace_size_planned.argtypes = [C.c_void_p, C.c_int32, C.POINTER(Plan), C.POINTER(C.c_size_t)]
+        L.mpq_gemm_static.restype = C.c_int
+        L.mpq_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
         L.mpq_quantize_outlier_capacity.restype = C.c_int
         L.mpq_quantize_outlier_capacity.argtypes = [C.POINTER(Desc), C.c_int32, C.c_double, C.POINTER(C.c_int64)]
         _lib = L
@@ -309,6 +312,13 @@ def gemm(header, blob_dev, X_dev, Y_dev, M, stream=None, workspace=None):
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().mpq_gemm(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M), ws_ptr, ws_bytes,
                           _stream_ptr(stream)), "mpq_gemm")
+
+
+def gemm_static(header, blob_dev, X_dev, Y_dev, M, stream=None):
+    """mpq_gemm_static: the product with the library's own device scratch as workspace (no allocation)."""
+    h, hp = _hdr_ptr(header)
+    _check(lib().mpq_gemm_static(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M),
+                                 _stream_ptr(stream)), "mpq_gemm_static")
 
 
 def raw_status(name: str, *args) -> int:

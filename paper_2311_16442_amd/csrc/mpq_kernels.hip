@@ -21,6 +21,7 @@
 //   exact integers c - z1; one packed fp16 multiply by s1 is the rounding the definition asks
 //   for.  The product kernel hands the resulting pairs to the matrix core.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 #include <string.h>
@@ -2016,6 +2017,48 @@ mpq_status mpq_gemm_planned(const void* hdr_host, const void* blob_dev, const ui
 mpq_status mpq_gemm(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
                     int32_t M, void* workspace_dev, size_t workspace_bytes, void* stream) {
   return mpq_gemm_planned(hdr_host, blob_dev, X_dev, Y_dev, M, workspace_dev, workspace_bytes, stream, nullptr, nullptr);
+}
+
+// ---- mpq_gemm for callers that cannot hand over a workspace: the partial sums and the transposed
+// activations of the K-range kernel go to an array that is part of the library's device image.
+// In host code the array's name is only a stand-in: its device address is asked for once per device
+// (with that device current) and kept; only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[MPQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxDevices];  // device address of `scratch` on each device, once known
+
+mpq_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return MPQ_ERR_HIP;
+  }
+  void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return MPQ_ERR_HIP;
+    }
+    g_scratch_addr[dev].store(p, std::memory_order_release);  // every thread that asks gets the same answer
+  }
+  *out = p;
+  return MPQ_OK;
+}
+}  // namespace
+
+mpq_status mpq_gemm_static(const void* hdr_host, const void* blob_dev, const uint16_t* X_dev, uint16_t* Y_dev,
+                           int32_t M, void* stream) {
+  size_t need = 0;
+  mpq_status st = mpq_gemm_workspace_size_planned(hdr_host, M, nullptr, &need);
+  if (st != MPQ_OK) return st;
+  if (need > (size_t)MPQ_STATIC_SCRATCH_BYTES) return MPQ_ERR_SIZE;
+  void* ws = nullptr;
+  if (need > 0 && (st = static_scratch(&ws)) != MPQ_OK) return st;
+  // nothing in the array has to start at zero: the kernels write every partial sum before it is read
+  return mpq_gemm_planned(hdr_host, blob_dev, X_dev, Y_dev, M, ws, need > 0 ? (size_t)MPQ_STATIC_SCRATCH_BYTES : 0, stream,
+                          nullptr, nullptr);
 }
 
 mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, const mpq_plan* plan, size_t* bytes) {
