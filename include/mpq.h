@@ -163,6 +163,14 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
 mpq_status mpq_blob_info(const void* hdr_host, mpq_desc* out, int64_t* nnz, int32_t* n4,
                          uint64_t* total_bytes);
 
+/* Where the rows live in a blob: `count` records of `record_bytes` bytes, the first at byte
+ * `first_offset`, record t holding everything of rows 16 t .. 16 t + 15 (codes, scale words, outliers)
+ * and nothing else.  Records can be copied, reordered or dealt to several blobs with the same header
+ * fields (Sec. 3.3: the bit width of a group is the same for every row, so rows shard freely): a blob
+ * whose records are those of another in a different order is that matrix with its 16-row blocks in that
+ * order (if N is a multiple of 16). */
+mpq_status mpq_blob_tiles(const void* hdr_host, uint64_t* first_offset, uint64_t* record_bytes, int32_t* count);
+
 /* Dequantize the whole matrix to row-major fp16 W_out[N*K] (device), bit-exact to the definition
  * at the top of this file (eq. 5 applied twice).  add_outliers != 0 adds the CSR values. */
 mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_out_dev,
@@ -258,6 +266,11 @@ mpq_status mpq_gemm_static(const void* hdr_host, const void* blob_dev, const uin
 
 /* mpq_gemm_workspace_size for a call under `plan` (the number of K ranges is a plan field). */
 mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, const mpq_plan* plan, size_t* bytes);
+
+/* Measurement aid: one launch that reads `bytes` bytes (a multiple of 16 is read) at src_dev once, with
+ * 16-byte loads, and does nothing else - the bandwidth the memory system delivers to a kernel of that
+ * size, next to which the throughput of the product kernels is reported.  sink_dev may be NULL. */
+mpq_status mpq_stream_probe(const void* src_dev, size_t bytes, uint32_t* sink_dev, void* stream);
 
 #ifdef __cplusplus
 }

@@ -25,8 +25,8 @@ STATUS_NAMES = ["MPQ_OK", "MPQ_ERR_NULL", "MPQ_ERR_SHAPE", "MPQ_ERR_ALIGN", "MPQ
  MPQ_ERR_CSR, MPQ_ERR_BLOB, MPQ_ERR_SIZE, MPQ_ERR_UNSUPPORTED, MPQ_ERR_HIP) = range(11)
 
 EXPORTS = ["mpq_status_str", "mpq_avg_bits", "mpq_quantize_host", "mpq_quantize_outlier_capacity", "mpq_packed_size",
-           "mpq_pack_host", "mpq_blob_info", "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm_workspace_size",
-           "mpq_gemm", "mpq_gemm_planned", "mpq_gemm_workspace_size_planned", "mpq_gemm_static"]
+           "mpq_pack_host", "mpq_blob_info", "mpq_blob_tiles", "mpq_dequant", "mpq_gemv", "mpq_gemv_multi", "mpq_gemm_workspace_size",
+           "mpq_gemm", "mpq_gemm_planned", "mpq_gemm_workspace_size_planned", "mpq_gemm_static", "mpq_stream_probe"]
 STATIC_SCRATCH_BYTES = 32 << 20
 (KERNEL_GEMV_PLANES, KERNEL_GEMV_DECODE, KERNEL_BATCH_RESIDENT, KERNEL_BATCH_RANGES) = (1, 2, 3, 4)
 MAX_MULTI = 8
@@ -99,6 +99,8 @@ def lib():
         L.mpq_blob_info.restype = C.c_int
         L.mpq_blob_info.argtypes = [C.c_void_p, C.POINTER(Desc), C.POINTER(C.c_int64),
                                     C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
+        L.mpq_blob_tiles.restype = C.c_int
+        L.mpq_blob_tiles.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.POINTER(C.c_int32)]
         L.mpq_dequant.restype = C.c_int
         L.mpq_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         L.mpq_gemv.restype = C.c_int
@@ -118,6 +120,8 @@ def lib():
         L.mpq_gemm_workspace_size_planned.argtypes = [C.c_void_p, C.c_int32, C.POINTER(Plan), C.POINTER(C.c_size_t)]
         L.mpq_gemm_static.restype = C.c_int
         L.mpq_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+        L.mpq_stream_probe.restype = C.c_int
+        L.mpq_stream_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.mpq_quantize_outlier_capacity.restype = C.c_int
         L.mpq_quantize_outlier_capacity.argtypes = [C.POINTER(Desc), C.c_int32, C.c_double, C.POINTER(C.c_int64)]
         _lib = L
@@ -236,6 +240,14 @@ def blob_info(header) -> dict:
                 total_bytes=int(tot.value))
 
 
+def blob_tiles(header) -> tuple:
+    """mpq_blob_tiles: (offset of the first 16-row record, bytes per record, number of records)."""
+    h = _np(header, np.uint8)
+    off, rec, cnt = C.c_uint64(0), C.c_uint64(0), C.c_int32(0)
+    _check(lib().mpq_blob_tiles(h.ctypes.data_as(C.c_void_p), C.byref(off), C.byref(rec), C.byref(cnt)), "mpq_blob_tiles")
+    return int(off.value), int(rec.value), int(cnt.value)
+
+
 # ----------------------------------------------------------------------------- device entry points
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -319,6 +331,12 @@ def gemm_static(header, blob_dev, X_dev, Y_dev, M, stream=None):
     h, hp = _hdr_ptr(header)
     _check(lib().mpq_gemm_static(hp, blob_dev.data_ptr(), X_dev.data_ptr(), Y_dev.data_ptr(), int(M),
                                  _stream_ptr(stream)), "mpq_gemm_static")
+
+
+def stream_probe(src_dev, nbytes=None, stream=None):
+    """mpq_stream_probe: one read-only pass over a device tensor (or its first nbytes bytes)."""
+    n = src_dev.numel() * src_dev.element_size() if nbytes is None else int(nbytes)
+    _check(lib().mpq_stream_probe(src_dev.data_ptr(), n, None, _stream_ptr(stream)), "mpq_stream_probe")
 
 
 def raw_status(name: str, *args) -> int:

@@ -1577,6 +1577,31 @@ mpq_outlier_add_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   }
 }
 
+// ------------------------------------------------------------------------------------ bandwidth reference
+//
+// Reads `n16` 16-byte words once and does nothing else: what the memory system delivers to a kernel of
+// this size and launch pattern, the figure the product kernels' throughput is set against.  Every
+// workgroup walks its own contiguous part, eight 16-byte loads per lane in flight.
+__global__ void __launch_bounds__(256)
+mpq_stream_kernel(const uint4* __restrict__ src, const size_t n16, uint32_t* __restrict__ sink) {
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+  uint32_t acc = 0;
+  size_t i = lo + threadIdx.x;
+  for (; i + 1792 < hi; i += 2048) {  // eight loads per lane in flight
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[i + 256 * u];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  for (; i < hi; i += 256) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  if (acc == 0x9E3779B9u && sink) *sink = acc;  // keeps the loads alive; practically never taken
+}
+
 // ------------------------------------------------------------------------------------ host side
 
 namespace {
@@ -2124,6 +2149,20 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
   MPQ_MULTI_CLASS(160 * 1024)
 #undef MPQ_MULTI_CLASS
   return MPQ_ERR_UNSUPPORTED;
+}
+
+mpq_status mpq_stream_probe(const void* src_dev, size_t bytes, uint32_t* sink_dev, void* stream) {
+  if (!src_dev) return MPQ_ERR_NULL;
+  if (((uintptr_t)src_dev & 15u) != 0) return MPQ_ERR_ALIGN;
+  if (bytes < 16) return MPQ_ERR_SIZE;
+  int cus = 0;
+  mpq_status st = cu_count(&cus);
+  if (st != MPQ_OK) return st;
+  const size_t n16 = bytes / 16;
+  size_t grid = (n16 + 1023) / 1024;            // at least 16 KiB per workgroup
+  if (grid > (size_t)cus * 8) grid = (size_t)cus * 8;
+  MPQ_LAUNCH(mpq_stream_kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, (const uint4*)src_dev, n16, sink_dev);
+  return MPQ_OK;
 }
 
 mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_out_dev, int add_outliers,

@@ -517,4 +517,15 @@ mpq_status mpq_blob_info(const void* hdr_host, mpq_desc* out, int64_t* nnz, int3
   return MPQ_OK;
 }
 
+mpq_status mpq_blob_tiles(const void* hdr_host, uint64_t* first_offset, uint64_t* record_bytes, int32_t* count) {
+  if (!hdr_host || !first_offset || !record_bytes || !count) return MPQ_ERR_NULL;
+  MpqHeader h;
+  const mpq_status st = mpq_internal_check_header(hdr_host, &h);
+  if (st != MPQ_OK) return st;
+  *first_offset = h.off_tiles;
+  *record_bytes = h.tile_stride;
+  *count = h.T;
+  return MPQ_OK;
+}
+
 }  // extern "C"
