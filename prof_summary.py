@@ -1,7 +1,7 @@
 """Turn rocprofv3 CSV output into the short text / JSON summaries kept under profiles/.
 
-  python -m paper_2311_16442_amd.prof_summary stats   <dir-of-kernel-trace-run>
-  python -m paper_2311_16442_amd.prof_summary traffic <dir-of-FETCH_SIZE-run> <dir-of-WRITE_SIZE-run> \
+  python prof_summary.py stats   <dir-of-kernel-trace-run>
+  python prof_summary.py traffic <dir-of-FETCH_SIZE-run> <dir-of-WRITE_SIZE-run> \
          --copy-bytes <bytes the calibration copy moved> [--kernel mpq_gemv_kernel]
 
 `stats` prints calls / average / min / max duration per kernel from *_kernel_stats.csv and, for the

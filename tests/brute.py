@@ -92,11 +92,10 @@ def weight_dequant(code: int, z1: int, s1):
     return round_binary(Fraction(code - z1) * s1, F16)
 
 
-def second_order_index(n, g, G, g2, g2_axis):
-    if g2_axis == 0:
-        S = -(-G // g2)
-        return n * S + g // g2
-    return (n // g2) * G + g
+def second_order_pair(n, g, g2, g2_axis):
+    """(row, column) of the pair of (row n, K-group g) in the 2-D arrays s2 / z2: [N][S] when a pair covers
+    g2 groups along K, [ceil(N / g2)][G] when it covers the same K-group of g2 rows."""
+    return (n, g // g2) if g2_axis == 0 else (n // g2, g)
 
 
 def dequant(N, K, g1, g2, g2_axis, codes, s_int, z1, s2, z2):
@@ -105,8 +104,8 @@ def dequant(N, K, g1, g2, g2_axis, codes, s_int, z1, s2, z2):
     W = [[None] * K for _ in range(N)]
     for n in range(N):
         for g in range(G):
-            j = second_order_index(n, g, G, g2, g2_axis)
-            s1 = scale_dequant(int(s_int[n][g]), int(z2.flat[j]), int(s2.flat[j]))
+            r, c = second_order_pair(n, g, g2, g2_axis)
+            s1 = scale_dequant(int(s_int[n][g]), int(z2[r][c]), int(s2[r][c]))
             for k in range(g * g1, (g + 1) * g1):
                 W[n][k] = weight_dequant(int(codes[n][k]), int(z1[n][g]), s1)
     return W

@@ -1,7 +1,7 @@
 """The profile summary tool on small hand-made rocprofv3 CSV files (CPU only)."""
 import json
 
-from paper_2311_16442_amd import prof_summary
+import prof_summary
 
 
 def _write(path, header, rows):
