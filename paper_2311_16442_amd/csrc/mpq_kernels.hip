@@ -1488,13 +1488,14 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 // covers whole 64-byte segments instead of 64 scattered 16-byte pieces.  20 KiB of LDS per
 // workgroup, so that 32 waves share a compute unit.  The kernel is bound by HBM writes: 2 bytes
 // out per weight against 0.33 bytes in.
-template <int PU>
+template <int PU, bool ADD>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 #pragma clang fp contract(off)
   constexpr int PAIR = 80;  // LDS bytes per (row, half unit): 64 + 16 so that lanes fall into different banks
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
+  __shared__ uint16_t gblock[ADD ? 2048 : 2];  // ADD: code block that holds the 2-bit K-group g
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = tid >> 6;
   const int i = lane & 15, j = lane >> 4;
@@ -1509,6 +1510,14 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const int chunk = lane & 3;  // 16-byte chunk (decode step) of a half unit that this lane stores
   // the blocks of a tile are shared by gridDim.y workgroups (matrices with few row tiles)
   const int c0 = (int)blockIdx.y * 4 + wv, cstep = 4 * (int)gridDim.y;
+  const uint32_t g1_shift = 31u - (uint32_t)__builtin_clz((uint32_t)(b.K / b.G));
+  if (ADD) {
+    // every piece of a 2-bit unit names its K-group through its first column
+    for (int p = tid; p < 4 * b.B2 * PU; p += 256) {
+      const uint2 e = units[p];
+      if ((e.y & 0xFFFFu) != 32u * (uint32_t)b.G) gblock[(e.x >> 1) >> g1_shift] = (uint16_t)(p / (4 * PU));
+    }
+  }
   uint4 qn = c0 < b.C ? codes[c0 * 64 + lane] : uint4{0, 0, 0, 0};
   for (int c = c0; c < b.C; c += cstep) {
     const bool two = c < b.B2;
@@ -1556,6 +1565,29 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
     }
 #undef MPQ_DQ_STEP
 #undef MPQ_DQ_STORE_HALF
+  }
+  if (ADD) {
+    // Dense + sparse (Sec. 2.3) without a second launch: when the workgroup's weights are on their way to
+    // memory, it adds the tile's outliers that lie in ITS blocks (native fp16 add = the definition's fp32
+    // add and one rounding), 16 lanes per row.  The weight was written by this workgroup, i.e. through this
+    // compute unit's write-through L1 into the L2 both accesses go to: the barrier's wait for the stores
+    // is all the ordering needed (a device-scope fence would write back the whole L2), and the load goes
+    // past the L1, which has never held the line.
+    __syncthreads();
+    const int orow = tid >> 4, oq = tid & 15;
+    const int row = blockIdx.x * 16 + orow;
+    const uint32_t* rec = (const uint32_t*)(tile + b.off_ot);
+    const uint32_t* words = rec + MPQ_OTILE_HEAD / 4;
+    const uint32_t rp0 = rec[orow], rp1 = rec[orow + 1];
+    if (row < b.N)
+      for (uint32_t e = rp0 + oq; e < rp1; e += 16) {
+        const uint32_t word = words[e];
+        const uint32_t col = word & 0xFFFFu, blk = gblock[col >> g1_shift];
+        if ((blk % (uint32_t)cstep) / 4u != blockIdx.y) continue;  // another workgroup wrote that weight
+        uint16_t* at = Wout + (size_t)row * b.K + col;
+        const half_t sum = bits_to_half(__builtin_nontemporal_load(at)) + bits_to_half((uint16_t)(word >> 16));
+        *at = half_to_bits(sum);
+      }
   }
 }
 
@@ -2183,10 +2215,21 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   slices = slices > most ? most : slices;
   slices = slices > 8 ? 8 : slices < 1 ? 1 : slices;
   const dim3 grid((unsigned)h.T, (unsigned)slices);
-  if (pu == 1) MPQ_LAUNCH(mpq_dequant_kernel<1>, grid, dim3(256), 0, s, d, W_out_dev);
-  else if (pu == 2) MPQ_LAUNCH(mpq_dequant_kernel<2>, grid, dim3(256), 0, s, d, W_out_dev);
-  else MPQ_LAUNCH(mpq_dequant_kernel<4>, grid, dim3(256), 0, s, d, W_out_dev);
-  if (add_outliers && h.nnz > 0) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  // The outliers are added at the end of the same kernel when a 128-byte line of the output belongs to ONE
+  // unit (g1 >= 64: 64 columns of a row), so that no other workgroup of the compute unit ever touches a
+  // line this workgroup reads back; shorter groups get them from a second kernel.  Measured: the same
+  // time either way (22016 x 4096: 55 us without outliers, 70 us with) - what costs is the scattered
+  // two-byte read-modify-write itself, one per outlier, not the launch.
+  const bool add = add_outliers && h.nnz > 0;
+  const bool fused = add && pu == 1 && h.G <= 2048;
+#define MPQ_DQ_LAUNCH(PUV)                                                                             \
+  {                                                                                                    \
+    if (fused) MPQ_LAUNCH((mpq_dequant_kernel<PUV, true>), grid, dim3(256), 0, s, d, W_out_dev);       \
+    else MPQ_LAUNCH((mpq_dequant_kernel<PUV, false>), grid, dim3(256), 0, s, d, W_out_dev);            \
+  }
+  if (pu == 1) MPQ_DQ_LAUNCH(1) else if (pu == 2) MPQ_DQ_LAUNCH(2) else MPQ_DQ_LAUNCH(4)
+#undef MPQ_DQ_LAUNCH
+  if (add && !fused) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   return MPQ_OK;
 }
 
