@@ -8,7 +8,7 @@
  *     is chosen per group of g1 input channels and is the same for every output channel),
  *   - a quantized first-order scale and an integer first-order zero point per (row, group), the
  *     scale being recovered by a second-order dequantization with an fp16 (scale, zero) pair
- *     (Sec. 2.2 eq. 5; Sec. 3.3; Algorithm 1 "1st s <- dequantize(1st s_int, 2nd z, 2nd s)"),
+ *     (Sec. 2.2 eq. 5; Sec. 3.3; Algorithm 1, second-order dequantization step),
  *   - fp16 outliers in CSR form, one 32-bit word (fp16 value, 16-bit column) per outlier plus one
  *     32-bit running count per row, located only inside 2-bit groups (Sec. 2.3, Sec. 4.3).
  *
@@ -72,7 +72,25 @@ typedef enum {
  * paper's "direction of output channels", Sec. 2.2), with g2 a divisor or a multiple of 16. */
 typedef struct {
   int32_t N, K, g1, g2, g2_axis;
+  int32_t meta;  /* how scales and zero points are stored, see MPQ_META_* (0 if left out of an initialiser) */
 } mpq_desc;
+
+/* meta = MPQ_META_BYTES: s_int and z1 one byte each per (row, group), (s2, z2) two fp16 values: what the
+ * benchmark configurations state.
+ * meta = MPQ_META_PAPER: the paper's aligned packing (Sec. 3.3 "Memory Alignment"), for g1 = 16:
+ *   - the three 2-bit zero points and the three scales of three consecutive 2-bit groups of a row share
+ *     ONE 16-bit word: the first scale has Ns = 4 bits, the other two are held in 3 bits ("Scale
+ *     Clipping"; which two, and how, the paper does not say: here the second and third group of every
+ *     triple of 2-bit groups, counted in K order over the 2-bit groups of the row, must have s_int <= 7 -
+ *     a quantizer clips them - and the first s_int <= 15);
+ *   - a 4-bit group has a 4-bit scale and a 4-bit zero point in one byte (the paper's bit count
+ *     charges 4-bit groups nothing for these; they are stored and counted here);
+ *   - the second-order zero is an Ns-bit integer padded to a byte ("Zero Padding"), next to the fp16
+ *     second-order scale: z2 must be the fp16 pattern of an integer 0..15.
+ * The logical arrays keep their shapes and the decode formula is the one at the top of this file; the
+ * packer refuses values outside these ranges with MPQ_ERR_CODE_RANGE. */
+#define MPQ_META_BYTES 0
+#define MPQ_META_PAPER 1
 
 /* Logical (unpacked) matrix: what a quantizer hands to mpq_pack_host. HOST pointers, read-only. */
 typedef struct {
@@ -107,7 +125,8 @@ const char* mpq_status_str(mpq_status s);
 /* Average stored bits per weight.
  * mode 0: bits actually stored by this format without alignment padding:
  *         8 * (codes + 2 B per (row,group) + 4 B per (row,super-group) + 4 B per outlier
- *              + 4 B per row pointer) / (N*K).
+ *              + 4 B per row pointer) / (N*K); for d->meta = MPQ_META_PAPER the metadata terms are
+ *         2 B per (row, triple of 2-bit groups), 1 B per (row, 4-bit group), 3 B per second-order pair.
  * mode 1: the paper's mixed-precision formula (Sec. 3.3, the display after "the average bit-width
  *         of each weight element"): alpha*(2 + (2+Ns)/g1 + (Ns+16)/(g1*g2)) + (1-alpha)*4 with
  *         alpha = 1 - n4/G and Ns = `ns_bits`, plus the outlier increment (16+16-2)*nnz/(N*K)

@@ -46,6 +46,7 @@ class MatrixSpec:
     p_o: float = 0.005    # outlier probability per weight inside 2-bit groups
     seed: int = BASE_SEED
     g2_axis: int = 0      # 0: a second-order pair per g2 groups along K of a row; 1: per K-group of g2 rows
+    meta: int = 0         # 0: byte-wide s_int / z1 and an fp16 z2; 1: the value ranges of the paper's aligned packing
 
     @property
     def G(self) -> int:
@@ -153,6 +154,14 @@ def make_matrix(spec: MatrixSpec, z1_full_range: bool = False,
     shape2 = (N, S) if spec.g2_axis == 0 else (-(-N // spec.g2), G)
     s2 = f16_bits(np.exp(rng.normal(-6.0, 0.5, size=shape2)))
     z2 = f16_bits(rng.random(size=shape2))
+    if spec.meta == 1:
+        # ranges of the aligned packing (Sec. 3.3): scales of Ns = 4 bits, of which the second and third of
+        # every three consecutive 2-bit groups of a row have 3; an Ns-bit integer second-order zero
+        pos2 = np.cumsum(is4 == 0) - 1                      # index of a 2-bit group among the 2-bit groups
+        hi_s = np.where(is4 != 0, 16, np.where(pos2 % 3 == 0, 16, 8)).astype(np.uint8)
+        s_int = (s_int % hi_s[None, :]).astype(np.uint8)
+        z2 = f16_bits(rng.integers(0, 16, size=shape2).astype(np.float32))
+        s2 = f16_bits(np.exp(rng.normal(-4.0, 0.5, size=shape2)))
     cols2 = np.nonzero(np.repeat(is4, g1) == 0)[0]
     row_ptr, col, val = draw_outliers(rng, N, cols2, spec.p_o)
     return Logical(spec, is4, codes, s_int, z1, s2, z2, row_ptr, col, val)

@@ -52,6 +52,12 @@ def lib():
         L.orc_avg_bits_mixed.argtypes = [C.c_double, C.c_int, C.c_int, C.c_int]
         L.orc_outlier_bits.argtypes = [C.c_double]
         L.orc_avg_bits_stored.argtypes = [C.POINTER(OrcDesc), C.c_int32, C.c_int64]
+        L.orc_clip_scales.restype = None
+        L.orc_clip_scales.argtypes = [C.POINTER(OrcDesc)] + [C.c_void_p] * 3
+        L.orc_validate_aligned.restype = C.c_int
+        L.orc_validate_aligned.argtypes = [C.POINTER(OrcDesc)] + [C.c_void_p] * 4
+        L.orc_avg_bits_stored_aligned.restype = C.c_double
+        L.orc_avg_bits_stored_aligned.argtypes = [C.POINTER(OrcDesc), C.c_int32, C.c_int64]
         L.orc_max_threads.restype = C.c_int
         _LIB = L
     return _LIB
@@ -164,6 +170,27 @@ def outlier_bits(ratio):
 def avg_bits_stored(N, K, g1, g2, n4, nnz, g2_axis=0):
     d = _desc(N, K, g1, g2, g2_axis)
     return float(lib().orc_avg_bits_stored(C.byref(d), int(n4), int(nnz)))
+
+
+def clip_scales(N, K, g1, is4, s_int) -> np.ndarray:
+    """Scale codes clipped to the fields of the aligned metadata format (Sec. 3.3 "Scale Clipping")."""
+    d = _desc(N, K, g1, 1)
+    is4 = _c(is4, np.uint8)
+    s_in = _c(s_int, np.uint8)
+    out = np.zeros_like(s_in)
+    lib().orc_clip_scales(C.byref(d), _p(is4), _p(s_in), _p(out))
+    return out
+
+
+def validate_aligned(N, K, g1, g2, is4, s_int, z1, z2, g2_axis=0) -> int:
+    d = _desc(N, K, g1, g2, g2_axis)
+    return int(lib().orc_validate_aligned(C.byref(d), _p(_c(is4, np.uint8)), _p(_c(s_int, np.uint8)), _p(_c(z1, np.uint8)),
+                                          _p(_c(z2, np.uint16))))
+
+
+def avg_bits_stored_aligned(N, K, g1, g2, n4, nnz, g2_axis=0):
+    d = _desc(N, K, g1, g2, g2_axis)
+    return float(lib().orc_avg_bits_stored_aligned(C.byref(d), int(n4), int(nnz)))
 
 
 def max_threads() -> int:

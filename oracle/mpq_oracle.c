@@ -9,18 +9,18 @@
  *
  * What it computes is a definition, not an approximation, so it is the definition written out:
  *
- *   second-order dequantization of the scale   (Sec. 3.3; Algorithm 1, "1st s <- dequantize(
- *                                               1st s_int, 2nd z, 2nd s)"; eq. 5 form (q - z) * s)
+ *   second-order dequantization of the scale   (Sec. 3.3; Algorithm 1, second-order dequantization
+ *                                               step; eq. 5 form (q - z) * s)
  *       t  = fp32(s_int) - fp32(z2)            one binary32 subtraction
  *       u  = t * fp32(s2)                      one binary32 multiplication (not fused with the above)
- *       s1 = fp16(u)                           "scaling factor is half" (Sec. 2.2)
- *   first-order dequantization of the weight   (Sec. 2.2 eq. 5; Algorithm 1, "w_float <- dequantize(
- *                                               w_int, 1st z, 1st s)"; weights restored to half, Sec. 5.1)
+ *       s1 = fp16(u)                           the scaling factor is a half (Sec. 2.2)
+ *   first-order dequantization of the weight   (Sec. 2.2 eq. 5; Algorithm 1, first-order dequantization
+ *                                               step; weights restored to half, Sec. 5.1)
  *       d  = code - z1                         exact integer
  *       Wd = fp16(fp32(d) * fp32(s1))          exact product, one rounding
  *   outliers are a separate fp16 sparse matrix added to the dense one (Sec. 2.3, Sec. 4.1)
  *       Wfull = fp16(fp32(Wd) + fp32(val))     at CSR positions
- *   product (Algorithm 1 "psum <- psum + w_float * x", then the sparse product added, Sec. 4.1)
+ *   product (Algorithm 1, the accumulation step, then the sparse product added, Sec. 4.1)
  *       y[m][n] = sum_k (double)Wd[n][k] * (double)X[m][k]  +  sum_j (double)val_j * (double)X[m][col_j]
  *     accumulated in binary64, k ascending, outliers after the dense part.
  *
@@ -31,7 +31,7 @@
  *   - only the scale is second-order quantized; the first-order zero point is an integer used as is;
  *   - the second-order pair covers g2 consecutive K-groups of a row (g2_axis 0, what the benchmark
  *     configurations state) or the same K-group of g2 consecutive rows (g2_axis 1, the paper's
- *     wording "in the direction of output channels");
+ *     wording: along the output channels);
  *   - the last second-order group is short when G is not a multiple of g2 (resp. N for axis 1).
  *
  * Pins (tests/test_oracle_*.py): exact rational brute force with independent rounding on tiny
@@ -254,6 +254,71 @@ double orc_avg_bits_stored(const orc_desc* d, int32_t n4, int64_t nnz) {
   double NK = (double)d->N * d->K;
   double code_bits = (double)d->N * d->g1 * (2.0 * (G - n4) + 4.0 * n4);
   double meta_bits = 16.0 * d->N * G + 32.0 * S;
+  double csr_bits = 32.0 * (double)nnz + 32.0 * ((double)d->N + 1.0);
+  return (code_bits + meta_bits + csr_bits) / NK;
+}
+
+/* ------------------------------------------------------------------ aligned metadata (Sec. 3.3 "Memory Alignment")
+ *
+ * The paper packs the zero points and scales of three 2-bit groups of 16 weights into one 16-bit word:
+ * 3 x 2 bits of zero points, one scale of Ns = 4 bits and two scales held in 3 bits
+ * (Scale Clipping); the second-order zero is an Ns-bit integer stored padded.  Which two
+ * scales lose a bit, and how, is not stated.  Reading taken here (and by the library): count a row's 2-bit
+ * groups in K order; in every run of three the first keeps 4 bits, the second and third are clipped
+ * (saturated) to 3 bits, i.e. to at most 7.  4-bit groups (about which the paper says nothing) keep a
+ * 4-bit scale and a 4-bit zero point.  The decode formula is unchanged: it is applied to the values as
+ * stored. */
+
+/* What a quantizer that targets the aligned format does to 4-bit scale codes: s_out = s_in, clipped to 7
+ * where the format has only 3 bits, to 15 elsewhere. */
+void orc_clip_scales(const orc_desc* d, const uint8_t* is4, const uint8_t* s_in, uint8_t* s_out) {
+  int64_t G = d->K / d->g1;
+  for (int64_t n = 0; n < d->N; ++n) {
+    int64_t seen2 = 0; /* 2-bit groups of this row so far */
+    for (int64_t g = 0; g < G; ++g) {
+      int limit = 15;
+      if (!is4[g]) {
+        if (seen2 % 3 != 0) limit = 7;
+        ++seen2;
+      }
+      s_out[n * G + g] = s_in[n * G + g] > limit ? (uint8_t)limit : s_in[n * G + g];
+    }
+  }
+}
+
+/* 0 if the logical arrays fit the aligned format, else 5: a zero point beyond its group's bit width, a
+ * scale beyond its field, or a second-order zero that is not an integer 0..15. */
+int orc_validate_aligned(const orc_desc* d, const uint8_t* is4, const uint8_t* s_int, const uint8_t* z1,
+                         const uint16_t* z2) {
+  int64_t G = d->K / d->g1;
+  for (int64_t n = 0; n < d->N; ++n) {
+    int64_t seen2 = 0;
+    for (int64_t g = 0; g < G; ++g) {
+      if (is4[g]) {
+        if (s_int[n * G + g] > 15 || z1[n * G + g] > 15) return 5;
+      } else {
+        if (z1[n * G + g] > 3 || s_int[n * G + g] > (seen2 % 3 == 0 ? 15 : 7)) return 5;
+        ++seen2;
+      }
+    }
+  }
+  int64_t pairs = d->g2_axis == 0 ? (int64_t)d->N * ((G + d->g2 - 1) / d->g2) : (int64_t)((d->N + d->g2 - 1) / d->g2) * G;
+  for (int64_t e = 0; e < pairs; ++e) {
+    float z = orc_half_to_float(z2[e]);
+    if (!(z >= 0.0f && z <= 15.0f) || z != (float)(int)z) return 5;
+  }
+  return 0;
+}
+
+/* Bits per weight the aligned format stores: codes; 16 bits per (row, three 2-bit groups, the last run
+ * of a row possibly short); 8 bits per (row, 4-bit group); 16 + 8 bits per second-order pair; CSR. */
+double orc_avg_bits_stored_aligned(const orc_desc* d, int32_t n4, int64_t nnz) {
+  int64_t G = d->K / d->g1, n2 = G - n4;
+  double pairs = d->g2_axis == 0 ? (double)d->N * (double)((G + d->g2 - 1) / d->g2)
+                                 : (double)((d->N + d->g2 - 1) / d->g2) * (double)G;
+  double NK = (double)d->N * d->K;
+  double code_bits = (double)d->N * d->g1 * (2.0 * n2 + 4.0 * n4);
+  double meta_bits = (double)d->N * (16.0 * (double)((n2 + 2) / 3) + 8.0 * n4) + 24.0 * pairs;
   double csr_bits = 32.0 * (double)nnz + 32.0 * ((double)d->N + 1.0);
   return (code_bits + meta_bits + csr_bits) / NK;
 }

@@ -41,7 +41,7 @@ class MpqError(RuntimeError):
 
 class Desc(C.Structure):
     _fields_ = [("N", C.c_int32), ("K", C.c_int32), ("g1", C.c_int32), ("g2", C.c_int32),
-                ("g2_axis", C.c_int32)]
+                ("g2_axis", C.c_int32), ("meta", C.c_int32)]
 
 
 class Plan(C.Structure):
@@ -141,13 +141,16 @@ def _np(a, dtype):
     return np.ascontiguousarray(a, dtype=dtype)
 
 
-def avg_bits(N, K, g1, g2, n4, nnz, mode=0, ns_bits=4, g2_axis=0) -> float:
-    d = Desc(N, K, g1, g2, g2_axis)
+META_BYTES, META_PAPER = 0, 1
+
+
+def avg_bits(N, K, g1, g2, n4, nnz, mode=0, ns_bits=4, g2_axis=0, meta=0) -> float:
+    d = Desc(N, K, g1, g2, g2_axis, meta)
     return float(lib().mpq_avg_bits(C.byref(d), int(n4), int(nnz), int(mode), int(ns_bits)))
 
 
-def packed_size(N, K, g1, g2, is4, row_ptr, g2_axis=0) -> int:
-    d = Desc(N, K, g1, g2, g2_axis)
+def packed_size(N, K, g1, g2, is4, row_ptr, g2_axis=0, meta=0) -> int:
+    d = Desc(N, K, g1, g2, g2_axis, meta)
     is4 = _np(is4, np.uint8)
     rp = _np(row_ptr, np.int32)
     if rp.size != N + 1:
@@ -200,9 +203,9 @@ class Packed:
         return self.blob[:HEADER_BYTES]
 
 
-def pack(N, K, g1, g2, is4, codes, s_int, z1, s2, z2, row_ptr, col, val, g2_axis=0) -> Packed:
+def pack(N, K, g1, g2, is4, codes, s_int, z1, s2, z2, row_ptr, col, val, g2_axis=0, meta=0) -> Packed:
     """mpq_packed_size + mpq_pack_host on host arrays in the logical format."""
-    d = Desc(int(N), int(K), int(g1), int(g2), int(g2_axis))
+    d = Desc(int(N), int(K), int(g1), int(g2), int(g2_axis), int(meta))
     is4 = _np(is4, np.uint8)
     arrs = dict(is4=is4, codes=_np(codes, np.uint8), s_int=_np(s_int, np.uint8), z1=_np(z1, np.uint8),
                 s2=_np(s2, np.uint16), z2=_np(z2, np.uint16), row_ptr=_np(row_ptr, np.int32),
@@ -225,7 +228,7 @@ def pack_logical(lg, g2_axis=None) -> Packed:
     if g2_axis is None:
         g2_axis = getattr(s, "g2_axis", 0)
     return pack(s.N, s.K, s.g1, s.g2, lg.is4, lg.codes, lg.s_int, lg.z1, lg.s2, lg.z2,
-                lg.row_ptr, lg.col, lg.val, g2_axis)
+                lg.row_ptr, lg.col, lg.val, g2_axis, getattr(s, "meta", 0))
 
 
 def blob_info(header) -> dict:
@@ -236,7 +239,7 @@ def blob_info(header) -> dict:
     nnz, n4, tot = C.c_int64(0), C.c_int32(0), C.c_uint64(0)
     _check(lib().mpq_blob_info(h.ctypes.data_as(C.c_void_p), C.byref(d), C.byref(nnz), C.byref(n4),
                                C.byref(tot)), "mpq_blob_info")
-    return dict(N=d.N, K=d.K, g1=d.g1, g2=d.g2, g2_axis=d.g2_axis, nnz=int(nnz.value), n4=int(n4.value),
+    return dict(N=d.N, K=d.K, g1=d.g1, g2=d.g2, g2_axis=d.g2_axis, meta=d.meta, nnz=int(nnz.value), n4=int(n4.value),
                 total_bytes=int(tot.value))
 
 

@@ -63,6 +63,19 @@
 //     per-weight decode reads the same layout as fields at bit offsets 1, 3, 5, 7 of the half-words of
 //     the dword and of the dword rotated right by 8.
 //
+// Side part of a tile record for meta = MPQ_META_PAPER (Sec. 3.3 "Memory Alignment"; g1 = 16), every
+// array 16-byte aligned, each followed by one all-zero entry that padding pieces point at:
+//         meta1a  (T3+1) x 16 x 2 B    per (triple of consecutive 2-bit stream groups, row) one 16-bit word:
+//                                      bits 0-1, 2-3, 4-5 the three zero points, bits 6-9 the first scale (4 bits),
+//                                      bits 10-12 and 13-15 the second and third scale (3 bits each); T3 = ceil(n2 / 3)
+//         meta1b  (n4+1) x 16 x 1 B    per (4-bit stream group, row): scale in bits 0-3, zero point in bits 4-7
+//         s2      E x 2 B, z2  E x 1 B the fp16 second-order scales and the byte-padded second-order zeros, E
+//                                      entries indexed like meta2 above: (S+1) x 16 (g2_axis 0) or (G+1) x nsub
+//         outl    as above
+//   unit table word 1 of a piece: bits 0-15 = byte offset of its triple inside meta1a, with the position of
+//   the group in the triple (0..2) in bits 0-1 (2-bit piece), or byte offset of its group inside meta1b (4-bit
+//   piece); bits 16-31 = index of its first second-order entry (the lane adds its row, or its block of rows).
+//
 // Sections and tile records start on 256-byte boundaries; padding bytes are zero.
 #ifndef MPQ_FORMAT_H_
 #define MPQ_FORMAT_H_
@@ -90,7 +103,8 @@ typedef struct {
   uint64_t side_bytes;  /* meta1 + meta2 + outlier record of a tile */
   uint64_t codes_off;   /* offset of the code blocks inside a tile record */
   uint64_t ocap;        /* words per tile in the outlier records (multiple of 32) */
-  uint64_t reserved0, reserved1;
+  uint64_t meta;        /* MPQ_META_BYTES or MPQ_META_PAPER */
+  uint64_t reserved1;
   uint64_t total_bytes;
   /* bit g = K-group g holds 4-bit codes (all zero if G > MPQ_IS4_BITS: the header then does not say
      which groups are 4-bit).  With it a unit's table entry follows from the header alone, so the host
@@ -111,6 +125,19 @@ static inline uint64_t mpq_meta2_bytes(const MpqHeader* h) {
 static inline uint32_t mpq_meta2_zero(const MpqHeader* h) {
   return h->g2_axis == 0 ? 64u * (uint32_t)h->S : 4u * (uint32_t)mpq_nsub(h->g2) * (uint32_t)h->G;
 }
+/* meta = MPQ_META_PAPER: second-order entries per tile (the last MPQ_TILE_ROWS or nsub of them are the zero
+ * entries), triples of 2-bit groups, and the byte offsets of the four arrays inside the side part */
+static inline uint32_t mpq_p_entries(const MpqHeader* h) {
+  return h->g2_axis == 0 ? 16u * ((uint32_t)h->S + 1) : (uint32_t)mpq_nsub(h->g2) * ((uint32_t)h->G + 1);
+}
+static inline uint32_t mpq_p_zero_entry(const MpqHeader* h) {
+  return h->g2_axis == 0 ? 16u * (uint32_t)h->S : (uint32_t)mpq_nsub(h->g2) * (uint32_t)h->G;
+}
+static inline uint32_t mpq_p_triples(const MpqHeader* h) { return ((uint32_t)h->n2 + 2u) / 3u; }
+static inline uint32_t mpq_p_off_m1b(const MpqHeader* h) { return 32u * (mpq_p_triples(h) + 1u); }
+static inline uint32_t mpq_p_off_s2(const MpqHeader* h) { return mpq_p_off_m1b(h) + 16u * ((uint32_t)h->n4 + 1u); }
+static inline uint32_t mpq_p_off_z2(const MpqHeader* h) { return mpq_p_off_s2(h) + ((2u * mpq_p_entries(h) + 15u) & ~15u); }
+static inline uint32_t mpq_p_off_outl(const MpqHeader* h) { return mpq_p_off_z2(h) + ((mpq_p_entries(h) + 15u) & ~15u); }
 
 #ifdef __cplusplus
 static_assert(sizeof(MpqHeader) == 256, "header must be 256 bytes");

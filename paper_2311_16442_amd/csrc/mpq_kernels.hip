@@ -128,7 +128,7 @@ __device__ __forceinline__ void dma_linear(const unsigned char* gbase, uint32_t 
 }
 
 // Second-order dequantization of a first-order scale: fp16((fp32(s_int) - fp32(z2)) * fp32(s2)).
-// (Algorithm 1, "1st s <- dequantize(1st s_int, 2nd z, 2nd s)"; eq. 5 form.)
+// (Algorithm 1, second-order dequantization step; eq. 5 form.)
 __device__ __forceinline__ half_t scale_dequant(uint32_t s_int, uint32_t m2) {
 #pragma clang fp contract(off)
   const float z2 = (float)bits_to_half((uint16_t)(m2 >> 16));

@@ -20,6 +20,7 @@ bool desc_ok(const mpq_desc* d) {
   if (d->K % d->g1 != 0) return false;
   if (d->K > 65535) return false;  // 16-bit column index (Sec. 2.3)
   if (d->g2_axis != 0 && d->g2_axis != 1) return false;
+  if (d->meta != MPQ_META_BYTES && d->meta != MPQ_META_PAPER) return false;
   return true;
 }
 
@@ -29,6 +30,7 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
   if (ocap < 0 || ocap % 32 != 0 || ocap > (int64_t)MPQ_TILE_ROWS * d->K + 32) return MPQ_ERR_SHAPE;
   // a piece (the part of a 16-byte unit inside one group) must cover whole decode steps of 8 columns
   if (d->g1 != 16 && d->g1 != 32 && d->g1 != 64 && d->g1 != 128) return MPQ_ERR_UNSUPPORTED;
+  if (d->meta == MPQ_META_PAPER && d->g1 != 16) return MPQ_ERR_UNSUPPORTED;  // Sec. 3.3: groups of 16
   // rows that share a second-order pair must not straddle 16-row tiles in an irregular way
   if (d->g2_axis == 1 && (d->g2 < MPQ_TILE_ROWS ? MPQ_TILE_ROWS % d->g2 != 0 : d->g2 % MPQ_TILE_ROWS != 0))
     return MPQ_ERR_UNSUPPORTED;
@@ -46,11 +48,17 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
   h->B4 = (h->U4 + MPQ_UNITS_PER_BLOCK - 1) / MPQ_UNITS_PER_BLOCK;
   h->T = (d->N + MPQ_TILE_ROWS - 1) / MPQ_TILE_ROWS;
   h->nnz = nnz;
+  h->meta = (uint64_t)d->meta;
   const uint64_t C = (uint64_t)h->B2 + h->B4;
   h->ocap = (uint64_t)ocap;
   // 16-bit offsets in the unit table
   if (32ull * (uint64_t)h->G > 0xFFFFull || (uint64_t)mpq_meta2_zero(h) > 0xFFFFull) return MPQ_ERR_UNSUPPORTED;
-  h->side_bytes = 32ull * (h->G + 1) + mpq_meta2_bytes(h) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
+  if (d->meta == MPQ_META_PAPER) {
+    if (mpq_p_entries(h) > 0xFFFFu) return MPQ_ERR_UNSUPPORTED;
+    h->side_bytes = (uint64_t)mpq_p_off_outl(h) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
+  } else {
+    h->side_bytes = 32ull * (h->G + 1) + mpq_meta2_bytes(h) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
+  }
   h->codes_off = align_up(h->side_bytes, 128);
   h->tile_stride = align_up(h->codes_off + C * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
   uint64_t off = MPQ_HEADER_BYTES;
@@ -145,7 +153,8 @@ mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out) {
   MpqHeader h, want;
   memcpy(&h, hdr_host, sizeof(h));
   if (h.magic != MPQ_MAGIC || h.version != MPQ_VERSION) return MPQ_ERR_BLOB;
-  mpq_desc d = {h.N, h.K, h.g1, h.g2, h.g2_axis};
+  if (h.meta > 1) return MPQ_ERR_BLOB;
+  mpq_desc d = {h.N, h.K, h.g1, h.g2, h.g2_axis, (int32_t)h.meta};
   if (!desc_ok(&d)) return MPQ_ERR_BLOB;
   if (plan(&d, h.n4, h.nnz, (int64_t)h.ocap, &want) != MPQ_OK) return MPQ_ERR_BLOB;
   if (memcmp(&h, &want, offsetof(MpqHeader, is4_bits)) != 0) return MPQ_ERR_BLOB;
@@ -161,7 +170,7 @@ mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out) {
 }
 
 bool mpq_internal_unit_words(const MpqHeader* h, uint32_t* words) {
-  if (h->G > (int32_t)MPQ_IS4_BITS || h->g1 < 64) return false;
+  if (h->G > (int32_t)MPQ_IS4_BITS || h->g1 < 64 || h->meta != MPQ_META_BYTES) return false;
   const int32_t up2 = h->g1 / 64, up4 = h->g1 / 32;  // units per group in the 2-bit / 4-bit stream
   const int32_t nsub = mpq_nsub(h->g2);
   const uint32_t zero_word = (uint32_t)(h->G * 32) | (mpq_meta2_zero(h) << 16);
@@ -208,9 +217,11 @@ double mpq_avg_bits(const mpq_desc* d, int32_t n4, int64_t nnz, int mode, int ns
     const double pairs = d->g2_axis == 0
                              ? (double)d->N * (double)(((int64_t)G + d->g2 - 1) / d->g2)
                              : (double)((d->N + d->g2 - 1) / d->g2) * G;
+    const double triples = (double)(((int64_t)G - n4 + 2) / 3);
+    const double meta1 = d->meta == MPQ_META_PAPER ? (double)d->N * (2.0 * triples + 1.0 * n4) : 2.0 * d->N * G;
     const double bytes = (double)d->N * ((G - n4) * d->g1 / 4.0 + n4 * d->g1 / 2.0)  // codes
-                         + 2.0 * d->N * G                                            // s_int, z1
-                         + 4.0 * pairs                                               // s2, z2
+                         + meta1                                                     // s_int, z1
+                         + (d->meta == MPQ_META_PAPER ? 3.0 : 4.0) * pairs           // s2, z2
                          + 4.0 * (double)nnz + 4.0 * ((double)d->N + 1.0);           // CSR
     return 8.0 * bytes / NK;
   }
@@ -396,10 +407,31 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
       for (int64_t k = g * g1; k < (g + 1) * g1; ++k)
         if (row[k] > hi) return MPQ_ERR_CODE_RANGE;
     }
+    if (d->meta == MPQ_META_PAPER) {
+      // ranges of the aligned packing: 2-bit zero points, 4-bit scales of which the second and third of
+      // every triple of 2-bit groups fit 3 bits, 4-bit zero points and scales of 4-bit groups
+      int64_t pos = 0;
+      for (int64_t g = 0; g < G; ++g) {
+        const uint8_t sv = w->s_int[n * G + g], zv = w->z1[n * G + g];
+        if (w->is4[g]) {
+          if (sv > 15 || zv > 15) return MPQ_ERR_CODE_RANGE;
+        } else {
+          if (zv > 3 || sv > (pos % 3 == 0 ? 15 : 7)) return MPQ_ERR_CODE_RANGE;
+          ++pos;
+        }
+      }
+    }
     for (int32_t e = w->row_ptr[n]; e < w->row_ptr[n + 1]; ++e) {
       if (w->col[e] >= K) return MPQ_ERR_CSR;
       if (e > w->row_ptr[n] && w->col[e] <= w->col[e - 1]) return MPQ_ERR_CSR;
       if (w->is4[w->col[e] / g1]) return MPQ_ERR_OUTLIER_IN_4BIT;  // Sec. 4.3: only in 2-bit groups
+    }
+  }
+  if (d->meta == MPQ_META_PAPER) {
+    const int64_t pairs = d->g2_axis == 0 ? N * h.S : ((N + d->g2 - 1) / d->g2) * G;
+    for (int64_t e = 0; e < pairs; ++e) {
+      const float z = half_to_float(w->z2[e]);
+      if (!(z >= 0.0f && z <= 15.0f) || z != (float)(int)z) return MPQ_ERR_CODE_RANGE;  // an Ns-bit integer
     }
   }
   // ---- layout
@@ -440,6 +472,21 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   uint32_t* unit_tab = (uint32_t*)(blob + h.off_units);
   for (int64_t p = 0; p < nunits * PU2; ++p) {
     const int32_t g = piece_g[(size_t)p];
+    if (d->meta == MPQ_META_PAPER) {
+      // word 1: offset of the triple (+ position in it) or of the 4-bit group | first second-order entry << 16
+      const bool four = p >= 4ll * h.B2 * PU2;
+      if (g < 0) {
+        unit_tab[2 * p] = 0;
+        unit_tab[2 * p + 1] = (four ? 16u * (uint32_t)h.n4 : 32u * mpq_p_triples(&h)) | (mpq_p_zero_entry(&h) << 16);
+        continue;
+      }
+      const uint32_t si = (uint32_t)stream_index[g];
+      const uint32_t m1 = four ? 16u * (si - (uint32_t)h.n2) : 32u * (si / 3u) + si % 3u;
+      const uint32_t e2 = d->g2_axis == 0 ? (uint32_t)(g / d->g2) * 16u : si * (uint32_t)nsub;
+      unit_tab[2 * p] = (uint32_t)(2 * piece_k0[(size_t)p]);
+      unit_tab[2 * p + 1] = m1 | (e2 << 16);
+      continue;
+    }
     if (g < 0) { unit_tab[2 * p] = 0; unit_tab[2 * p + 1] = zero_word1; continue; }
     const uint32_t m2off = d->g2_axis == 0 ? (uint32_t)((g / d->g2) * 64) : (uint32_t)(stream_index[g] * 4 * nsub);
     unit_tab[2 * p] = (uint32_t)(2 * piece_k0[(size_t)p]);
@@ -475,6 +522,35 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
         }
       }
     }
+    if (d->meta == MPQ_META_PAPER) {
+      uint8_t* m1b = tile + mpq_p_off_m1b(&h);
+      uint16_t* s2a = (uint16_t*)(tile + mpq_p_off_s2(&h));
+      uint8_t* z2a = tile + mpq_p_off_z2(&h);
+      for (int64_t g = 0; g < G; ++g) {
+        const uint32_t si = (uint32_t)stream_index[g], sv = w->s_int[n * G + g], zv = w->z1[n * G + g];
+        if (w->is4[g]) {
+          m1b[(si - (uint32_t)h.n2) * MPQ_TILE_ROWS + i] = (uint8_t)(sv | (zv << 4));
+        } else {
+          const uint32_t pos = si % 3u;  // zero points at bits 0-5, scales at bits 6 (4 bits), 10 and 13 (3 bits)
+          meta1[(si / 3u) * MPQ_TILE_ROWS + i] |= (uint16_t)((zv << (2u * pos)) | (sv << (pos == 0 ? 6u : pos == 1 ? 10u : 13u)));
+        }
+      }
+      // the second-order zero as the integer it is (validated below to be one), in a byte
+      auto z2_byte = [&](uint16_t zbits) { return (uint8_t)half_to_float(zbits); };
+      if (d->g2_axis == 0) {
+        for (int64_t s2i = 0; s2i < h.S; ++s2i) {
+          s2a[s2i * MPQ_TILE_ROWS + i] = w->s2[n * h.S + s2i];
+          z2a[s2i * MPQ_TILE_ROWS + i] = z2_byte(w->z2[n * h.S + s2i]);
+        }
+      } else if (i % d->g2 == 0 || (d->g2 >= MPQ_TILE_ROWS && i == 0)) {
+        const int64_t nb = n / d->g2, sub = d->g2 >= MPQ_TILE_ROWS ? 0 : i / d->g2;
+        for (int64_t g = 0; g < G; ++g) {
+          s2a[stream_index[g] * nsub + sub] = w->s2[nb * G + g];
+          z2a[stream_index[g] * nsub + sub] = z2_byte(w->z2[nb * G + g]);
+        }
+      }
+      continue;
+    }
     for (int64_t g = 0; g < G; ++g)
       meta1[stream_index[g] * MPQ_TILE_ROWS + i] = (uint16_t)(w->s_int[n * G + g] | ((uint16_t)w->z1[n * G + g] << 8));
     if (d->g2_axis == 0) {
@@ -489,7 +565,8 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
   }
   (void)m2_bytes;
   for (int64_t t = 0; t < h.T; ++t) {
-    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + 32ull * (G + 1) + mpq_meta2_bytes(&h));
+    const uint64_t off_outl = d->meta == MPQ_META_PAPER ? (uint64_t)mpq_p_off_outl(&h) : 32ull * (G + 1) + mpq_meta2_bytes(&h);
+    uint32_t* rec = (uint32_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + off_outl);
     const int64_t n0 = t * MPQ_TILE_ROWS;
     const int32_t base = w->row_ptr[n0];
     for (int r = 0; r <= MPQ_TILE_ROWS; ++r) {
@@ -510,7 +587,7 @@ mpq_status mpq_blob_info(const void* hdr_host, mpq_desc* out, int64_t* nnz, int3
   MpqHeader h;
   memcpy(&h, hdr_host, sizeof(h));
   if (h.magic != MPQ_MAGIC || h.version != MPQ_VERSION) return MPQ_ERR_BLOB;
-  if (out) { out->N = h.N; out->K = h.K; out->g1 = h.g1; out->g2 = h.g2; out->g2_axis = h.g2_axis; }
+  if (out) { out->N = h.N; out->K = h.K; out->g1 = h.g1; out->g2 = h.g2; out->g2_axis = h.g2_axis; out->meta = (int32_t)h.meta; }
   if (nnz) *nnz = h.nnz;
   if (n4) *n4 = h.n4;
   if (total_bytes) *total_bytes = h.total_bytes;

@@ -39,17 +39,24 @@ CASES = [
     (33, 480, 32, 3, 0.20, 0.01, False, 0),     # g1 = 32 with pairs along K
     (24, 320, 16, 16, 0.0, 0.05, False, 0),     # g1 = 16, only 2-bit groups
     (24, 1024, 64, 8, 0.10, 0.005, False, 1),   # one piece per unit, pairs shared by 8 rows
+    # the paper's aligned metadata (Sec. 3.3): 16-bit word per three 2-bit groups, byte per 4-bit group, byte-padded z2
+    (40, 512, 16, 16, 0.25, 0.01, False, 1, 1),   # 24 two-bit groups = 8 triples, 8 four-bit groups
+    (37, 432, 16, 4, 0.26, 0.02, False, 1, 1),    # 20 two-bit groups: last triple holds two; ragged rows; 4 blocks of rows per tile
+    (24, 320, 16, 16, 0.0, 0.05, False, 0, 1),    # pairs along K, no 4-bit group
+    (20, 256, 16, 32, 1.0, 0.0, False, 1, 1),     # only 4-bit groups, a pair spans two tiles
 ]
 
 
-@pytest.mark.parametrize("N,K,g1,g2,f4,p_o,z1_full,axis", CASES)
-def test_pack_round_trips_through_independent_reader(N, K, g1, g2, f4, p_o, z1_full, axis):
-    lg = synth.make_matrix(synth.MatrixSpec("t", N, K, g1, g2, f4, p_o, 77 + N + K, axis), z1_full_range=z1_full)
+@pytest.mark.parametrize("case", CASES)
+def test_pack_round_trips_through_independent_reader(case):
+    N, K, g1, g2, f4, p_o, z1_full, axis = case[:8]
+    meta = case[8] if len(case) > 8 else 0
+    lg = synth.make_matrix(synth.MatrixSpec("t", N, K, g1, g2, f4, p_o, 77 + N + K, axis, meta), z1_full_range=z1_full)
     pk = mpq.pack_logical(lg)
-    assert pk.blob.size == mpq.packed_size(N, K, g1, g2, lg.is4, lg.row_ptr, axis)
+    assert pk.blob.size == mpq.packed_size(N, K, g1, g2, lg.is4, lg.row_ptr, axis, meta)
     info = mpq.blob_info(pk.header)
-    assert (info["N"], info["K"], info["g1"], info["g2"], info["nnz"], info["n4"]) == \
-        (N, K, g1, g2, lg.nnz, int(lg.is4.sum()))
+    assert (info["N"], info["K"], info["g1"], info["g2"], info["nnz"], info["n4"], info["meta"]) == \
+        (N, K, g1, g2, lg.nnz, int(lg.is4.sum()), meta)
     assert info["total_bytes"] == pk.blob.size
     u = up.unpack(pk.blob)
     assert np.array_equal(u["is4"], lg.is4)

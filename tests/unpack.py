@@ -31,7 +31,19 @@ def unpack(blob: np.ndarray) -> dict:
     nsub = 1 if g2 >= TILE else TILE // g2                    # g2_axis 1: blocks of g2 rows per tile
     m2_bytes = 64 * (S + 1) if axis == 0 else -(-(4 * nsub * (G + 1)) // 16) * 16
     zero2 = 64 * S if axis == 0 else 4 * nsub * G
-    assert h["side_bytes"] == 32 * (G + 1) + m2_bytes + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
+    paper = h["r0"] == 1                                     # the paper's aligned metadata packing (g1 = 16)
+    assert h["r0"] in (0, 1) and (not paper or g1 == 16)
+    if paper:
+        T3 = -(-h["n2"] // 3)                                 # triples of 2-bit groups
+        E = 16 * (S + 1) if axis == 0 else nsub * (G + 1)     # second-order entries, zero entries included
+        zero_e = 16 * S if axis == 0 else nsub * G
+        off_m1b = 32 * (T3 + 1)
+        off_s2 = off_m1b + 16 * (h["n4"] + 1)
+        off_z2 = off_s2 + -(-(2 * E) // 16) * 16
+        o0 = off_z2 + -(-E // 16) * 16
+        assert h["side_bytes"] == o0 + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
+    else:
+        assert h["side_bytes"] == 32 * (G + 1) + m2_bytes + 128 + 4 * h["ocap"] and h["ocap"] % 32 == 0
     assert h["codes_off"] % 128 == 0 and h["codes_off"] >= h["side_bytes"] and h["tile_stride"] % 256 == 0
     assert h["tile_stride"] >= h["codes_off"] + C * 1024 and h["total"] == blob.size
     assert h["U2"] == (h["n2"] * (g1 // 64) if g1 >= 64 else -(-h["n2"] // PU2))
@@ -69,6 +81,26 @@ def unpack(blob: np.ndarray) -> dict:
             field[:, kl] = v.astype(np.uint8).reshape(-1)
         for q in range(PU2):
             e, e1 = int(units[u, q, 0]), int(units[u, q, 1])
+            if paper:
+                gi = ul * PU + q                               # g1 = 16: piece q of unit ul is stream group gi of its width
+                if q >= PU or gi >= (h["n4"] if four else h["n2"]):
+                    # padding piece: points at the zero entries and holds zero codes
+                    assert e == 0 and (e1 & 0xFFFF) == ((16 * h["n4"]) if four else 32 * T3) and (e1 >> 16) == zero_e
+                    if q < PU:
+                        assert not field[:, q * cpp: (q + 1) * cpp].any()
+                    continue
+                k0 = e // 2
+                g = k0 // g1
+                assert is4[g] == 255 and k0 % g1 == 0
+                is4[g] = 1 if four else 0
+                si = len(stream_groups)
+                assert si == (h["n2"] + gi if four else gi)
+                want1 = 16 * gi if four else 32 * (gi // 3) + gi % 3
+                want2 = (g // g2) * 16 if axis == 0 else si * nsub
+                assert (e1 & 0xFFFF) == want1 and (e1 >> 16) == want2, (u, q, hex(e1), want1, want2)
+                stream_groups.append(g)
+                codes[:, k0: k0 + cpp] = field[:, q * cpp: (q + 1) * cpp]
+                continue
             if (e1 & 0xFFFF) == 32 * G:                    # padding piece: points at the zero entries
                 assert e == 0 and (e1 >> 16) == zero2
                 if q < PU:
@@ -89,15 +121,57 @@ def unpack(blob: np.ndarray) -> dict:
     assert len(stream_groups) == G and sorted(stream_groups) == list(range(G))
     bits = np.unpackbits(h["is4_bits"], bitorder="little")
     assert np.array_equal(bits[:G], is4) and not bits[G:].any() if G <= 896 else not bits.any()
-    m1 = np.ascontiguousarray(tiles[:, : 32 * (G + 1)]).view(np.uint16).reshape(T, G + 1, TILE)
-    assert not m1[:, G].any()                             # the zero entry padding pieces point at
-    s_int = np.zeros((T * TILE, G), dtype=np.uint8)
-    z1 = np.zeros((T * TILE, G), dtype=np.uint8)
-    for sg, g in enumerate(stream_groups):
-        s_int[:, g] = (m1[:, sg, :] & 0xFF).reshape(-1)
-        z1[:, g] = (m1[:, sg, :] >> 8).reshape(-1)
+    if paper:
+        m1a = np.ascontiguousarray(tiles[:, : 32 * (T3 + 1)]).view(np.uint16).reshape(T, T3 + 1, TILE).astype(np.uint32)
+        m1b = tiles[:, off_m1b: off_m1b + 16 * (h["n4"] + 1)].reshape(T, h["n4"] + 1, TILE)
+        assert not m1a[:, T3].any() and not m1b[:, h["n4"]].any()
+        s_int = np.zeros((T * TILE, G), dtype=np.uint8)
+        z1 = np.zeros((T * TILE, G), dtype=np.uint8)
+        for si, g in enumerate(stream_groups):
+            if si < h["n2"]:
+                w, pos = m1a[:, si // 3, :], si % 3
+                z1[:, g] = ((w >> (2 * pos)) & 3).reshape(-1)
+                s_int[:, g] = ((w >> (6, 10, 13)[pos]) & (15, 7, 7)[pos]).reshape(-1)
+            else:
+                b8 = m1b[:, si - h["n2"], :]
+                s_int[:, g] = (b8 & 15).reshape(-1)
+                z1[:, g] = (b8 >> 4).reshape(-1)
+        if h["n2"] % 3:                                        # unused fields of the last triple are zero
+            w = m1a[:, T3 - 1, :]
+            for pos in range(h["n2"] % 3, 3):
+                assert not ((w >> (2 * pos)) & 3).any() and not ((w >> (6, 10, 13)[pos]) & (15, 7, 7)[pos]).any()
+        s2a = np.ascontiguousarray(tiles[:, off_s2: off_s2 + 2 * E]).view(np.uint16).reshape(T, E)
+        z2a = tiles[:, off_z2: off_z2 + E].reshape(T, E)
+        assert not s2a[:, zero_e:].any() and not z2a[:, zero_e:].any()
+        z2h = z2a.astype(np.float16).view(np.uint16)           # the byte as the fp16 integer the logical format holds
+        if axis == 0:
+            s2 = s2a[:, :zero_e].reshape(T, S, TILE).transpose(0, 2, 1).reshape(T * TILE, S)[:N]
+            z2 = z2h[:, :zero_e].reshape(T, S, TILE).transpose(0, 2, 1).reshape(T * TILE, S)[:N]
+        else:
+            NB = -(-N // g2)
+            s2 = np.zeros((NB, G), dtype=np.uint16)
+            z2 = np.zeros((NB, G), dtype=np.uint16)
+            for si, g in enumerate(stream_groups):
+                for t in range(T):
+                    for sub in range(nsub):
+                        n0 = t * TILE + (sub * g2 if g2 < TILE else 0)
+                        if n0 >= N:
+                            assert s2a[t, si * nsub + sub] == 0 and z2a[t, si * nsub + sub] == 0
+                            continue
+                        s2[n0 // g2, g], z2[n0 // g2, g] = s2a[t, si * nsub + sub], z2h[t, si * nsub + sub]
+        m2_bytes = o0 - 32 * (G + 1)                           # so that the outlier record is found below
+    if not paper:
+        m1 = np.ascontiguousarray(tiles[:, : 32 * (G + 1)]).view(np.uint16).reshape(T, G + 1, TILE)
+        assert not m1[:, G].any()                             # the zero entry padding pieces point at
+        s_int = np.zeros((T * TILE, G), dtype=np.uint8)
+        z1 = np.zeros((T * TILE, G), dtype=np.uint8)
+        for sg, g in enumerate(stream_groups):
+            s_int[:, g] = (m1[:, sg, :] & 0xFF).reshape(-1)
+            z1[:, g] = (m1[:, sg, :] >> 8).reshape(-1)
     raw2 = np.ascontiguousarray(tiles[:, 32 * (G + 1): 32 * (G + 1) + m2_bytes])
-    if axis == 0:
+    if paper:
+        pass
+    elif axis == 0:
         m2 = raw2.view(np.uint32).reshape(T, S + 1, TILE)
         assert not m2[:, S].any()
         m2 = m2[:, :S]
