@@ -238,6 +238,9 @@ def main():
     ap.add_argument("--g2", type=int, default=None, help="second-order group size instead of the configuration's")
     ap.add_argument("--g2-axis", type=int, default=None, choices=[0, 1],
                     help="0 = second-order pairs along K (the configurations), 1 = shared by g2 rows (the paper's axis)")
+    ap.add_argument("--meta", type=int, default=None, choices=[0, 1],
+                    help="1 = the paper's aligned metadata (16-bit word per three 2-bit groups, byte-padded second-order "
+                         "zero; needs --g1 16), 0 = byte-wide scales and zero points (the configurations)")
     ap.add_argument("--f4", type=float, default=None, help="fraction of 4-bit groups instead of the configuration's")
     ap.add_argument("--p-o", type=float, default=None, help="outlier probability instead of the configuration's")
     ap.add_argument("--multi", action="store_true",
@@ -299,7 +302,7 @@ def main():
     copies = 80 if args.config == 4 else 32
     distinct = "rotated" if args.config == 4 else "seeds" if args.token else "copies"
     specs = synth.config_specs(args.config, f4=args.f4, p_o=args.p_o)
-    over = {k: v for k, v in (("g1", args.g1), ("g2", args.g2), ("g2_axis", args.g2_axis)) if v is not None}
+    over = {k: v for k, v in (("g1", args.g1), ("g2", args.g2), ("g2_axis", args.g2_axis), ("meta", args.meta)) if v is not None}
     specs = [dataclasses.replace(sp, **over) for sp in specs]
     head = None
     if args.token and args.config == 3:      # the head is used once per token, not once per layer
@@ -397,7 +400,7 @@ def main():
         residency = "byte-identical layer copies rotated (cold last-level cache)"
     workload = ("configs[%d]: %s %s, %d launches per step (%s), batch M=%d, g1=%d g2=%d%s f4=%.0f%% p_o=%.1f%%, %d %s" % (
         args.config, MODEL[args.config], what, launches // steps, shapes, M, spec0.g1, spec0.g2,
-        " (pairs shared by g2 rows)" if spec0.g2_axis == 1 else "", 100 * spec0.f4, 100 * spec0.p_o, copies, residency))
+        (" (pairs shared by g2 rows)" if spec0.g2_axis == 1 else "") + (" aligned metadata (Sec. 3.3)" if spec0.meta == 1 else ""), 100 * spec0.f4, 100 * spec0.p_o, copies, residency))
     config = {"workload": workload, "bytes_per_step": step_bytes,
               "launch": "hipGraph replay" if graphed else "python", "pct_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
               "requested": {"steps": args.steps, "warmup": args.warmup},

@@ -205,10 +205,12 @@ def stored_bytes(spec: MatrixSpec, n4: int, nnz: int) -> Dict[str, int]:
     """Bytes the format must move for one product, by section (no alignment padding)."""
     N, K, g1, G, S = spec.N, spec.K, spec.g1, spec.G, spec.S
     n2 = G - n4
+    pairs = N * S if spec.g2_axis == 0 else (-(-N // spec.g2)) * G
+    aligned = getattr(spec, "meta", 0) == 1   # 16 bits per three 2-bit groups, 8 per 4-bit group, 24 per pair
     out = {
         "codes": N * (n2 * g1 // 4 + n4 * g1 // 2),
-        "s_int_z1": 2 * N * G,
-        "s2_z2": 4 * N * S if spec.g2_axis == 0 else 4 * (-(-N // spec.g2)) * G,
+        "s_int_z1": N * (2 * (-(-n2 // 3)) + n4) if aligned else 2 * N * G,
+        "s2_z2": (3 if aligned else 4) * pairs,
         "outliers": 4 * nnz,
         "row_ptr": 4 * (N + 1),
     }

@@ -44,6 +44,8 @@ struct DevBlob {
   uint32_t codes_off;          // offset of the code blocks inside a tile record
   uint32_t off_m2, off_ot;     // offsets of meta2 and of the outlier record inside the side part
   uint32_t m2_shift;           // lane part of a meta2 address = 4 * (row >> m2_shift)
+  uint32_t off_m1b, off_s2, off_z2;  // aligned metadata (Sec. 3.3): bytes of the 4-bit groups, second-order scales, zeros
+  uint32_t pad_entry;                // bits 16-31 of the table word of a padding piece (the zero second-order entry)
   int32_t N, K, G, S, B2, C, T;
 };
 
@@ -221,6 +223,37 @@ __device__ __forceinline__ void finish_pieces(const uint2 (&ent)[NP], const unsi
   }
 }
 
+// The same for the aligned metadata of Sec. 3.3 ("Memory Alignment"): a 2-bit piece finds its 2-bit zero
+// point and its 4- or 3-bit scale in the 16-bit word that three consecutive 2-bit groups of the row share
+// (zero points at bits 0-5, scales at bits 6, 10, 13), a 4-bit piece both in one byte; the second-order zero
+// is an integer in a byte next to the fp16 second-order scale.  `side` = the tile's side part, row = 0..15.
+template <int NP, bool FOUR>
+__device__ __forceinline__ void pieces_aligned(const uint2 (&ent)[NP], const unsigned char* side, const DevBlob& b,
+                                               const uint32_t row, half2_t (&s1p)[NP], half_t (&zb)[NP], uint32_t (&xoff)[NP]) {
+#pragma unroll
+  for (int q = 0; q < NP; ++q) {
+    const uint2 e = ent[q];
+    uint32_t s_int, z1;
+    if (FOUR) {
+      const uint32_t w = *(const uint8_t*)(side + b.off_m1b + (e.y & 0xFFFFu) + row);
+      s_int = w & 15u;
+      z1 = w >> 4;
+    } else {
+      const uint32_t pos = e.y & 3u;
+      const uint32_t w = *(const uint16_t*)(side + (e.y & 0xFFFCu) + 2u * row);
+      z1 = (w >> (2u * pos)) & 3u;
+      s_int = pos == 0 ? (w >> 6) & 15u : (w >> (pos == 1 ? 10u : 13u)) & 7u;
+    }
+    const uint32_t idx = (e.y >> 16) + (row >> b.m2_shift);
+    const uint32_t s2 = *(const uint16_t*)(side + b.off_s2 + 2u * idx);
+    const half_t z2 = (half_t)(float)*(const uint8_t*)(side + b.off_z2 + idx);  // 0..15: exact
+    const half_t s1 = scale_dequant(s_int, s2 | ((uint32_t)half_to_bits(z2) << 16));  // exactly 0 for a padding piece
+    s1p[q] = half2_t{s1, s1};
+    zb[q] = bits_to_half((uint16_t)(0x6400u | z1));  // 1024 + z1
+    xoff[q] = e.x;
+  }
+}
+
 template <int NP>
 __device__ __forceinline__ void load_pieces(const unsigned char* ue, const unsigned char* m1i, const unsigned char* m2i,
                                             half2_t (&s1p)[NP], half_t (&zb)[NP], uint32_t (&xoff)[NP]) {
@@ -270,7 +303,7 @@ __device__ __forceinline__ void load_pieces(const unsigned char* ue, const unsig
 // the 32 wave slots of a compute unit with fewer workgroups (less LDS for staged operands per
 // wave) and keep every SIMD busy when the matrix has few row tiles (4096 rows = 256 tiles = one
 // tile per compute unit).
-template <int NT, int PD, int LDSB, int WV = 4, int PU = 1>
+template <int NT, int PD, int LDSB, int WV = 4, int PU = 1, bool AL = false>
 __global__ void __launch_bounds__(WV * 64)
 mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int M) {
 #pragma clang fp contract(off)
@@ -362,7 +395,7 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   }
 // Fetch of the next block of this wave (wait, read its ring slot, refill the slot) and the
 // per-piece set-up; the 2-bit blocks of a tile come first in the wave's sequence, then the 4-bit ones.
-#define MPQ_MM_BLOCK_HEAD(NP)                                                                          \
+#define MPQ_MM_BLOCK_HEAD(NP, FOUR)                                                                    \
   /* Requests younger than the block needed now: the other blocks in flight (stricter than            \
      necessary when a side-record request sits between them, never laxer). */                         \
   if (inflight == PD) MPQ_VMCNT(PD - 1); else if (PD == 2) MPQ_VMCNT(0); else wait_vm((int)inflight - 1); \
@@ -380,17 +413,23 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
   half2_t s1p[NP];                                                                                    \
   half_t zb[NP];                                                                                      \
   uint32_t xoff[NP];                                                                                  \
-  load_pieces<NP>(unitj + c * (32u * PU), m1i, m2i, s1p, zb, xoff);                                   \
+  if constexpr (AL) {                                                                                 \
+    uint2 ent[NP];                                                                                    \
+    _Pragma("unroll") for (int qq = 0; qq < NP; ++qq) ent[qq] = *(const uint2*)(unitj + c * (32u * PU) + 8 * qq); \
+    pieces_aligned<NP, FOUR>(ent, side, b, i, s1p, zb, xoff);                                         \
+  } else {                                                                                            \
+    load_pieces<NP>(unitj + c * (32u * PU), m1i, m2i, s1p, zb, xoff);                                 \
+  }                                                                                                   \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     uint32_t c = wv;
     for (; c < (uint32_t)b.B2; c += W) {
-      MPQ_MM_BLOCK_HEAD(PU)
+      MPQ_MM_BLOCK_HEAD(PU, false)
       const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_MM_STEP(true, 0) MPQ_MM_STEP(true, 1) MPQ_MM_STEP(true, 2) MPQ_MM_STEP(true, 3)
       MPQ_MM_STEP(true, 4) MPQ_MM_STEP(true, 5) MPQ_MM_STEP(true, 6) MPQ_MM_STEP(true, 7)
     }
     for (; c < C; c += W) {
-      MPQ_MM_BLOCK_HEAD(PU4)
+      MPQ_MM_BLOCK_HEAD(PU4, true)
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_MM_STEP(false, 0) MPQ_MM_STEP(false, 1) MPQ_MM_STEP(false, 2) MPQ_MM_STEP(false, 3)
     }
@@ -908,7 +947,7 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
 //   ONE code block per wave first; the second ring slot only after the first barrier - with every
 //   request of every workgroup issued at once the memory system serves workgroup after workgroup
 //   and the last ones start late.
-template <int PD, int LDSB, int WV, int PU>
+template <int PD, int LDSB, int WV, int PU, bool AL = false>
 __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
                                                const int n_arg, const uint32_t wg) {
 #pragma clang fp contract(off)
@@ -1005,7 +1044,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
                                                   __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
   }
-#define MPQ_GEMV_BLOCK_HEAD(NP)                                                                        \
+#define MPQ_GEMV_BLOCK_HEAD(NP, FOUR)                                                                  \
   __builtin_amdgcn_s_setprio(0);                                                                      \
   /* the block's unit table entries are requested first: the wait inside the ring read below covers  \
      them, so the scale words can be requested right after it */                                     \
@@ -1027,17 +1066,18 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   half2_t s1p[NP];                                                                                    \
   half_t zb[NP];                                                                                      \
   uint32_t xoff[NP];                                                                                  \
-  finish_pieces<NP>(ent, m1i, m2i, s1p, zb, xoff);                                                    \
+  if constexpr (AL) pieces_aligned<NP, FOUR>(ent, side, b, i, s1p, zb, xoff);                         \
+  else finish_pieces<NP>(ent, m1i, m2i, s1p, zb, xoff);                                               \
   if (decode_first) __builtin_amdgcn_s_setprio(2);                                                    \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     for (; c < (uint32_t)b.B2; c += W) {
-      MPQ_GEMV_BLOCK_HEAD(PU)
+      MPQ_GEMV_BLOCK_HEAD(PU, false)
       const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_GEMV_STEP(true, 0) MPQ_GEMV_STEP(true, 1) MPQ_GEMV_STEP(true, 2) MPQ_GEMV_STEP(true, 3)
       MPQ_GEMV_STEP(true, 4) MPQ_GEMV_STEP(true, 5) MPQ_GEMV_STEP(true, 6) MPQ_GEMV_STEP(true, 7)
     }
     for (; c < C; c += W) {
-      MPQ_GEMV_BLOCK_HEAD(PU4)
+      MPQ_GEMV_BLOCK_HEAD(PU4, true)
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_GEMV_STEP(false, 0) MPQ_GEMV_STEP(false, 1) MPQ_GEMV_STEP(false, 2) MPQ_GEMV_STEP(false, 3)
     }
@@ -1062,10 +1102,10 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   }
 }
 
-template <int PD, int LDSB, int WV, int PU = 1>
+template <int PD, int LDSB, int WV, int PU = 1, bool AL = false>
 __global__ void __launch_bounds__(WV * 64)
 mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg) {
-  gemv_workgroup<PD, LDSB, WV, PU>(b, X, Y, n_arg, blockIdx.x);
+  gemv_workgroup<PD, LDSB, WV, PU, AL>(b, X, Y, n_arg, blockIdx.x);
 }
 
 // Several independent matrix-vector products in one launch (separate projections of a layer, the
@@ -1488,7 +1528,7 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 // covers whole 64-byte segments instead of 64 scattered 16-byte pieces.  20 KiB of LDS per
 // workgroup, so that 32 waves share a compute unit.  The kernel is bound by HBM writes: 2 bytes
 // out per weight against 0.33 bytes in.
-template <int PU, bool ADD>
+template <int PU, bool ADD, bool AL = false>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 #pragma clang fp contract(off)
@@ -1511,11 +1551,12 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   // the blocks of a tile are shared by gridDim.y workgroups (matrices with few row tiles)
   const int c0 = (int)blockIdx.y * 4 + wv, cstep = 4 * (int)gridDim.y;
   const uint32_t g1_shift = 31u - (uint32_t)__builtin_clz((uint32_t)(b.K / b.G));
+  const uint32_t pad_entry = b.pad_entry;  // what bits 16-31 of a padding piece's table word hold
   if (ADD) {
     // every piece of a 2-bit unit names its K-group through its first column
     for (int p = tid; p < 4 * b.B2 * PU; p += 256) {
       const uint2 e = units[p];
-      if ((e.y & 0xFFFFu) != 32u * (uint32_t)b.G) gblock[(e.x >> 1) >> g1_shift] = (uint16_t)(p / (4 * PU));
+      if ((e.y >> 16) != pad_entry) gblock[(e.x >> 1) >> g1_shift] = (uint16_t)(p / (4 * PU));
     }
   }
   uint4 qn = c0 < b.C ? codes[c0 * 64 + lane] : uint4{0, 0, 0, 0};
@@ -1535,7 +1576,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
     const uint2 pu = units[(4 * c + (pair >> 4)) * PU + cg / (SPP)]; /* the step's piece */               \
     const uint4 v = *(const uint4*)(mine + pair * PAIR + chunk * 16);                                    \
     /* padding pieces point at the zero scale entries; padding rows lie beyond N */                      \
-    if ((pu.y & 0xFFFFu) != 32u * (uint32_t)b.G && prow < b.N)                                           \
+    if ((pu.y >> 16) != pad_entry && prow < b.N)                                                         \
       *(uint4*)((unsigned char*)Wout + ((size_t)prow * b.K) * 2 + pu.x + (cg % (SPP)) * 16) = v;          \
   }                                                                                                      \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* reads done before the area is overwritten */
@@ -1548,7 +1589,14 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
       half2_t s1p[PU];
       half_t zb[PU];
       uint32_t xoff[PU];
-      load_pieces<PU>(ue, m1i, m2i, s1p, zb, xoff);
+      if constexpr (AL) {
+        uint2 ent[PU];
+#pragma unroll
+        for (int qq = 0; qq < PU; ++qq) ent[qq] = *(const uint2*)(ue + 8 * qq);
+        pieces_aligned<PU, false>(ent, tile, b, (uint32_t)i, s1p, zb, xoff);
+      } else {
+        load_pieces<PU>(ue, m1i, m2i, s1p, zb, xoff);
+      }
       const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
       MPQ_DQ_STORE_HALF(0, 8 / PU)
@@ -1558,7 +1606,14 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
       half2_t s1p[PU4];
       half_t zb[PU4];
       uint32_t xoff[PU4];
-      load_pieces<PU4>(ue, m1i, m2i, s1p, zb, xoff);
+      if constexpr (AL) {
+        uint2 ent[PU4];
+#pragma unroll
+        for (int qq = 0; qq < PU4; ++qq) ent[qq] = *(const uint2*)(ue + 8 * qq);
+        pieces_aligned<PU4, true>(ent, tile, b, (uint32_t)i, s1p, zb, xoff);
+      } else {
+        load_pieces<PU4>(ue, m1i, m2i, s1p, zb, xoff);
+      }
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
       MPQ_DQ_STORE_HALF(0, 4 / PU4)
@@ -1662,6 +1717,15 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   d->codes_off = (uint32_t)h->codes_off;
   d->off_m2 = 32u * ((uint32_t)h->G + 1);
   d->off_ot = d->off_m2 + (uint32_t)mpq_meta2_bytes(h);
+  d->off_m1b = d->off_s2 = d->off_z2 = 0;
+  d->pad_entry = mpq_meta2_zero(h);
+  if (h->meta == MPQ_META_PAPER) {
+    d->off_m1b = mpq_p_off_m1b(h);
+    d->off_s2 = mpq_p_off_s2(h);
+    d->off_z2 = mpq_p_off_z2(h);
+    d->off_ot = mpq_p_off_outl(h);
+    d->pad_entry = mpq_p_zero_entry(h);
+  }
   d->m2_shift = 0;  // g2_axis 0: one pair per row; g2_axis 1: one pair per block of g2 rows
   if (h->g2_axis == 1)
     for (int g = h->g2 < MPQ_TILE_ROWS ? h->g2 : MPQ_TILE_ROWS; g > 1; g >>= 1) ++d->m2_shift;
@@ -1718,24 +1782,24 @@ size_t gemv_lds_bytes(const MpqHeader& h, int PD, int waves, int n) {
          32ull * mpq_pu2(h.g1) * (h.B2 + h.B4) + 2ull * h.K;
 }
 
-template <int PD, int LDSB, int WV, int PU>
+template <int PD, int LDSB, int WV, int PU, bool AL = false>
 mpq_status launch_gemv(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
   const unsigned grid = (unsigned)((c.h.T + n - 1) / n);
-  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU>), dim3(grid), dim3(WV * 64), 0, c.s, c.d, X, Y, n);
+  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU, AL>), dim3(grid), dim3(WV * 64), 0, c.s, c.d, X, Y, n);
   note(c, MPQ_KERNEL_GEMV_DECODE, 1, WV, n, grid);
   return MPQ_OK;
 }
 
 // GEMV with WV waves per workgroup and n tiles per workgroup in the smallest LDS class that holds
 // it.  Two code blocks per wave in flight: deeper rings were measured and change nothing.
-template <int WV, int PU>
+template <int WV, int PU, bool AL = false>
 mpq_status gemv_class(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
   const size_t need = gemv_lds_bytes(c.h, 2, WV, n);
-  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU>(c, X, Y, n);
-  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU>(c, X, Y, n);
-  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV, PU>(c, X, Y, n);
-  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU>(c, X, Y, n);
-  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU>(c, X, Y, n);
+  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU, AL>(c, X, Y, n);
+  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU, AL>(c, X, Y, n);
+  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV, PU, AL>(c, X, Y, n);
+  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU, AL>(c, X, Y, n);
+  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU, AL>(c, X, Y, n);
   return MPQ_ERR_UNSUPPORTED;
 }
 
@@ -1744,7 +1808,7 @@ mpq_status gemv_waves(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
   switch (mpq_pu2(c.h.g1)) {  // first-order groups per 2-bit unit
     case 1: return gemv_class<WV, 1>(c, X, Y, n);
     case 2: return gemv_class<WV, 2>(c, X, Y, n);
-    default: return gemv_class<WV, 4>(c, X, Y, n);
+    default: return c.h.meta == MPQ_META_PAPER ? gemv_class<WV, 4, true>(c, X, Y, n) : gemv_class<WV, 4>(c, X, Y, n);
   }
 }
 
@@ -1857,7 +1921,7 @@ mpq_status gemv_planes(const Ctx& c, const uint16_t* X, uint16_t* Y) {
 // ---------------------------------------------------------------- 2 <= M <= 32
 
 // Persistent batch kernel with WV waves per workgroup; one or two workgroups per compute unit.
-template <int NT, int PD, int LDSB, int WV, int PU = 1>
+template <int NT, int PD, int LDSB, int WV, int PU = 1, bool AL = false>
 mpq_status launch_batch(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   size_t per_cu = kLdsPerCu / LDSB;
   if (per_cu * WV > 32) per_cu = 32 / WV;
@@ -1865,13 +1929,13 @@ mpq_status launch_batch(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   long grid = (long)c.cus * (long)per_cu;
   if (c.plan.max_workgroups > 0 && grid > c.plan.max_workgroups) grid = c.plan.max_workgroups;
   if (grid > c.h.T) grid = c.h.T;
-  MPQ_LAUNCH((mpq_mm_kernel<NT, PD, LDSB, WV, PU>), dim3((unsigned)grid), dim3(WV * 64), 0, c.s, c.d, X, Y, M);
+  MPQ_LAUNCH((mpq_mm_kernel<NT, PD, LDSB, WV, PU, AL>), dim3((unsigned)grid), dim3(WV * 64), 0, c.s, c.d, X, Y, M);
   note(c, MPQ_KERNEL_BATCH_RESIDENT, 1, WV, 0, grid);
   return MPQ_OK;
 }
 
 // Persistent batch kernel with 4 waves per workgroup (the most workgroups per compute unit).
-template <int NT, int PD, int LDSB, int PU = 1>
+template <int NT, int PD, int LDSB, int PU = 1, bool AL = false>
 mpq_status launch_mm(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   size_t per_cu = kLdsPerCu / LDSB;  // as many workgroups as fit at once (LDS, 32 waves per compute unit)
   if (per_cu > 8) per_cu = 8;
@@ -1879,7 +1943,7 @@ mpq_status launch_mm(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   long grid = (long)c.cus * (long)per_cu;
   if (c.plan.max_workgroups > 0 && grid > c.plan.max_workgroups) grid = c.plan.max_workgroups;
   if (grid > c.h.T) grid = c.h.T;
-  MPQ_LAUNCH((mpq_mm_kernel<NT, PD, LDSB, 4, PU>), dim3((unsigned)grid), dim3(256), 0, c.s, c.d, X, Y, M);
+  MPQ_LAUNCH((mpq_mm_kernel<NT, PD, LDSB, 4, PU, AL>), dim3((unsigned)grid), dim3(256), 0, c.s, c.d, X, Y, M);
   note(c, MPQ_KERNEL_BATCH_RESIDENT, 1, 4, 0, grid);
   return MPQ_OK;
 }
@@ -1892,14 +1956,17 @@ mpq_status mm_chunk(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
   const int bw = c.plan.batch_waves;
   if (mpq_pu2(h.g1) > 1) {
     // first-order groups shorter than a unit (g1 = 16, 32): persistent workgroups in a few classes
-    const bool four = mpq_pu2(h.g1) == 4;
-#define MPQ_PIECES(CALL2, CALL4) return four ? CALL4 : CALL2
+    const bool four = mpq_pu2(h.g1) == 4, al = h.meta == MPQ_META_PAPER;  // the aligned metadata comes with g1 = 16
+#define MPQ_PIECES(CALL2, CALL4, CALL4A) return !four ? CALL2 : al ? CALL4A : CALL4
     if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024)
-      MPQ_PIECES((launch_batch<NT, 2, 80 * 1024, 8, 2>(c, X, Y, M)), (launch_batch<NT, 2, 80 * 1024, 8, 4>(c, X, Y, M)));
+      MPQ_PIECES((launch_batch<NT, 2, 80 * 1024, 8, 2>(c, X, Y, M)), (launch_batch<NT, 2, 80 * 1024, 8, 4>(c, X, Y, M)),
+                 (launch_batch<NT, 2, 80 * 1024, 8, 4, true>(c, X, Y, M)));
     if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024)
-      MPQ_PIECES((launch_batch<NT, 3, 160 * 1024, 8, 2>(c, X, Y, M)), (launch_batch<NT, 3, 160 * 1024, 8, 4>(c, X, Y, M)));
+      MPQ_PIECES((launch_batch<NT, 3, 160 * 1024, 8, 2>(c, X, Y, M)), (launch_batch<NT, 3, 160 * 1024, 8, 4>(c, X, Y, M)),
+                 (launch_batch<NT, 3, 160 * 1024, 8, 4, true>(c, X, Y, M)));
     if (mm_lds_bytes(h, M, 3) <= 160 * 1024)
-      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, 2>(c, X, Y, M)), (launch_mm<NT, 3, 160 * 1024, 4>(c, X, Y, M)));
+      MPQ_PIECES((launch_mm<NT, 3, 160 * 1024, 2>(c, X, Y, M)), (launch_mm<NT, 3, 160 * 1024, 4>(c, X, Y, M)),
+                 (launch_mm<NT, 3, 160 * 1024, 4, true>(c, X, Y, M)));
 #undef MPQ_PIECES
     return MPQ_ERR_UNSUPPORTED;
   }
@@ -1977,6 +2044,7 @@ mpq_status launch_slices(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, vo
   // operands of a position and up to 8 x NT accumulators stay in registers); 16 waves, with half
   // the registers and a third less LDS for the activations, measured equal or slower on every shape
   const int pu = mpq_pu2(h.g1);
+  if (h.meta != MPQ_META_BYTES) return MPQ_ERR_UNSUPPORTED;  // the K-range kernel gathers byte-wide scale words
   if (!plan_slices(h, c.plan, c.cus, M, 8, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   size_t p_bytes = 0;
   if (!ws || ((uintptr_t)ws & 255u) != 0 || ws_bytes < slice_workspace_bytes(h, pl, NT, XR, &p_bytes)) return MPQ_ERR_UNSUPPORTED;
@@ -2130,7 +2198,7 @@ mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, cons
   SlicePlan pl;
   int XR = 0;
   size_t p_bytes = 0;
-  if (M > 1 && plan_slices(h, plan ? *plan : kAutoPlan, cus, M, 8, 160 * 1024, &pl, &XR))
+  if (M > 1 && h.meta == MPQ_META_BYTES && plan_slices(h, plan ? *plan : kAutoPlan, cus, M, 8, 160 * 1024, &pl, &XR))
     *bytes = slice_workspace_bytes(h, pl, M > 16 ? 2 : 1, XR, &p_bytes);
   return MPQ_OK;
 }
@@ -2160,6 +2228,7 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
     if (st != MPQ_OK) return st;
     if ((((uintptr_t)x_dev[p] | (uintptr_t)y_dev[p]) & 15u) != 0) return MPQ_ERR_ALIGN;
     if (p > 0 && mpq_pu2(h.g1) != pu) return MPQ_ERR_UNSUPPORTED;
+    if (h.meta != MPQ_META_BYTES) return MPQ_ERR_UNSUPPORTED;
     pu = mpq_pu2(h.g1);
     const size_t lds = gemv_lds_bytes(h, 2, 8, 1);
     need = lds > need ? lds : need;
@@ -2227,7 +2296,10 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
     if (fused) MPQ_LAUNCH((mpq_dequant_kernel<PUV, true>), grid, dim3(256), 0, s, d, W_out_dev);       \
     else MPQ_LAUNCH((mpq_dequant_kernel<PUV, false>), grid, dim3(256), 0, s, d, W_out_dev);            \
   }
-  if (pu == 1) MPQ_DQ_LAUNCH(1) else if (pu == 2) MPQ_DQ_LAUNCH(2) else MPQ_DQ_LAUNCH(4)
+  if (pu == 1) MPQ_DQ_LAUNCH(1)
+  else if (pu == 2) MPQ_DQ_LAUNCH(2)
+  else if (h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, false, true>), grid, dim3(256), 0, s, d, W_out_dev);
+  else MPQ_DQ_LAUNCH(4)
 #undef MPQ_DQ_LAUNCH
   if (add && !fused) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   return MPQ_OK;

@@ -145,11 +145,13 @@ def test_llama2_7b_gate_up_at_the_heavy_sweep_corner(torch, M):
     check_products(torch, lg, pk, blob, [M], all_rows=False)
 
 
+@pytest.mark.parametrize("meta", [0, 1])
 @pytest.mark.parametrize("idx", [1, 3])
-def test_llama2_7b_shapes_at_the_papers_operating_point(torch, idx):
-    # g1 = g2 = 16, second-order pairs shared by 16 rows (Sec. 2.2), 25 % 4-bit groups (Sec. 3.3)
+def test_llama2_7b_shapes_at_the_papers_operating_point(torch, idx, meta):
+    # g1 = g2 = 16, second-order pairs shared by 16 rows (Sec. 2.2), 25 % 4-bit groups (Sec. 3.3); with byte-wide
+    # scales and zero points, and with the paper's aligned metadata (Sec. 3.3 "Memory Alignment")
     base = synth.config_specs(1)[idx]
-    spec = synth.MatrixSpec(base.name, base.N, base.K, 16, 16, 0.25, 0.005, base.seed, 1)
+    spec = synth.MatrixSpec(base.name, base.N, base.K, 16, 16, 0.25, 0.005, base.seed, 1, meta)
     lg = synth.make_matrix(spec)
     pk = mpq.pack_logical(lg)
     blob = to_dev(torch, pk.blob)

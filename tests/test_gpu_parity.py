@@ -37,13 +37,20 @@ CASES = [
     ("g32_rows32", 208, 2048, 32, 32, 0.15, 0.005, True, 1),     # a pair spans two tiles
     ("g16_along_k", 272, 1520, 16, 16, 0.10, 0.01, False, 0),    # 95 groups: ragged units in both streams
     ("g64_rows4", 100, 1024, 64, 4, 0.10, 0.005, True, 1),       # four blocks of rows per tile
+    # the paper's aligned metadata (Sec. 3.3 "Memory Alignment"; last field 1): a 16-bit word per three 2-bit
+    # groups with two 3-bit scales, a byte per 4-bit group, a byte-padded integer second-order zero
+    ("aligned_paper_point", 1000, 1024, 16, 16, 0.25, 0.005, False, 1, 1),  # g1 = g2 = 16, pairs shared by 16 rows
+    ("aligned_along_k", 272, 1520, 16, 4, 0.10, 0.01, False, 0, 1),         # 95 groups: a short last triple, ragged units
+    ("aligned_rows4", 100, 2048, 16, 4, 0.30, 0.005, False, 1, 1),          # four blocks of rows per tile
 ]
+BYTE_META_CASES = [c for c in CASES if len(c) < 10 or c[9] == 0]
 
 
 def make(case):
     name, N, K, g1, g2, f4, p_o, z1_full = case[:8]
     axis = case[8] if len(case) > 8 else 0
-    lg = synth.make_matrix(synth.MatrixSpec(name, N, K, g1, g2, f4, p_o, 4242 + N + K, axis), z1_full_range=z1_full)
+    meta = case[9] if len(case) > 9 else 0
+    lg = synth.make_matrix(synth.MatrixSpec(name, N, K, g1, g2, f4, p_o, 4242 + N + K, axis, meta), z1_full_range=z1_full)
     return lg, oracle.Matrix.from_logical(lg), mpq.pack_logical(lg)
 
 
@@ -251,9 +258,25 @@ def test_plane_sum_kernel_with_wide_ranging_activations(torch):
     assert e_floor <= TOL, (e_floor, e_max)
 
 
+@pytest.mark.parametrize("M", [2, 5, 16, 32])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_gemm_on_every_case(torch, case, M):
+    # the batch product the library chooses by itself, on every format of the parity set
+    lg, om, pk = make(case)
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(300 + M, M, pk.K)
+    Y = Guarded(torch, M * pk.N)
+    ws = Workspace(torch, mpq, pk.header, M)
+    mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, workspace=ws.view)
+    got = Y.check_and_get().reshape(M, pk.N)
+    ws.check()
+    e_floor, e_max = rel_err(got, om.gemm(X, threads=8))
+    assert e_floor <= TOL, (M, e_floor, e_max)
+
+
 @pytest.mark.parametrize("min_h", [0, 3])
 @pytest.mark.parametrize("M", [2, 7, 8, 9, 16, 17, 32])
-@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+@pytest.mark.parametrize("case", BYTE_META_CASES, ids=[c[0] for c in BYTE_META_CASES])
 def test_large_batch_kernel_within_tolerance(torch, case, M, min_h):
     # the kernel that keeps one K-range of the activations resident per workgroup and writes partial
     # sums that a second kernel adds up, forced for every batch size through a launch plan (by
