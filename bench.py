@@ -72,6 +72,7 @@ class Layer:
         self.mats = []
         self.copies = copies
         self.multi = False   # True: the layer's products go out as one multi-problem launch
+        self.dequant = None  # 0 / 1: the steps dequantize (without / with outliers) instead of multiplying
         t0 = time.time()
         for mi, spec in enumerate(specs):
             lg = synth.make_matrix(spec)
@@ -133,6 +134,10 @@ class Layer:
         return names
 
     def launch_layer(self, mpq, layer, stream, stream_only=False):
+        if self.dequant is not None and not stream_only:
+            for m in self.mats:
+                mpq.dequant(m["hdrs"][layer], m["blobs"][layer], self.wout, add_outliers=bool(self.dequant), stream=stream)
+            return
         if stream_only:   # the same bytes in the same launch pattern, read and nothing else
             for m in self.mats:
                 mpq.stream_probe(m["blobs"][layer], stream=stream)
@@ -232,6 +237,9 @@ def main():
     ap.add_argument("--token", action="store_true",
                     help="configs 1 and 3: one step = a decode step over 32 layers drawn with their own seeds "
                          "(+ lm_head for config 3) as one graph; reports ms per token")
+    ap.add_argument("--dequant", type=int, default=None, choices=[0, 1],
+                    help="time mpq_dequant (0 = dense part, 1 = with the outliers added) on the layer's matrices instead of "
+                         "the product; bytes = packed bytes read + 2 bytes per weight written")
     ap.add_argument("--sweep", action="store_true",
                     help="configs[2]: M x 4-bit fraction x outlier fraction on the Llama2-7B layer")
     ap.add_argument("--g1", type=int, default=None, help="first-order group size instead of the configuration's (16, 32, 64, 128)")
@@ -312,6 +320,13 @@ def main():
     layer = Layer(torch, mpq, synth, specs, copies, M, dev, distinct=distinct, config=args.config)
     layer.multi = bool(args.multi)
     kernel_names = ["mpq_gemv_multi_kernel"] if args.multi else layer.kernels(torch, mpq)
+    if args.dequant is not None:
+        layer.dequant = args.dequant
+        layer.wout = torch.zeros(max(m["spec"].N * m["spec"].K for m in layer.mats), dtype=torch.int16, device=dev)
+        kernel_names = ["mpq_dequant_kernel"] * len(layer.mats)
+        for m in layer.mats:      # what a dequantization moves: the packed bytes in, two bytes per weight out
+            m["bytes"] = m["bytes"] - M * (2 * m["spec"].K + 2 * m["spec"].N) + 2 * m["spec"].N * m["spec"].K
+        layer.step_bytes = sum(m["bytes"] for m in layer.mats)
     log(f"[setup] {copies} layers resident: {copies * layer.packed_bytes / 1e9:.2f} GB; "
         f"algorithmic bytes per layer {layer.step_bytes / 1e6:.3f} MB; kernels {kernel_names}")
 
@@ -358,7 +373,7 @@ def main():
                                           "read from the file, not measured in this run")
         except Exception:  # noqa: BLE001 - a malformed note must not break the benchmark line
             pass
-    if not args.no_ceiling and not args.multi:
+    if not args.no_ceiling and not args.multi and args.dequant is None:
         roofline["ceiling"] = measure_ceiling(torch, mpq, layer, stream, dev, layer_steps, use_graph)
         roofline["ceiling"]["frac_of_same_launches_read_only"] = round(value / roofline["ceiling"]["same_launches_read_only_GBs"], 4)
 
@@ -375,6 +390,7 @@ def main():
             reps += 1
         cpu_s = (time.perf_counter() - tc) / reps
         # correctness of what is timed: one more product on copy 0 (the copy the oracle holds)
+        layer.dequant = None
         y0 = torch.zeros(M * sample["spec"].N, dtype=torch.int16, device=dev)
         mpq.gemm(sample["hdr"], sample["blobs"][0], sample["x"], y0, M, workspace=layer.workspace)
         torch.cuda.synchronize()
@@ -409,6 +425,9 @@ def main():
         config["ms_per_token"] = round(ms_per_step, 5)
     if args.multi:
         config["note"] = "one launch for the four products: only legitimate for products that do not depend on each other"
+    if args.dequant is not None:
+        config["note"] = ("mpq_dequant %s outliers instead of the product: bytes = packed bytes read + 2 bytes per weight written"
+                          % ("with" if args.dequant else "without"))
     if sweep is not None:
         config["sweep"] = sweep
     out = {"metric": METRIC, "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warm,
