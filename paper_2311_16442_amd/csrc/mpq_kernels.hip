@@ -450,12 +450,26 @@ mpq_mm_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restr
       const uint32_t* ostart = (const uint32_t*)(side + b.off_ot);
       const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
       const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
-      for (uint32_t e = rp0 + oes; e < rp1; e += ostride) {
-        const uint32_t word = owords[e];
-        const uint32_t off = (word & 0xFFFFu) * 2u;
-        const float v = (float)bits_to_half((uint16_t)(word >> 16));
-        oa0 += v * (float)*(const half_t*)(xo0 + off);
-        if (NT > 1) oa1 += v * (float)*(const half_t*)(xo1 + off);
+      // four words per lane in flight: the chain word -> activation is two LDS round trips, and the other
+      // waves of the workgroup wait at the barrier below meanwhile (a word beyond the row's end counts as
+      // value 0 at column 0).  Sharing the words between all waves of the workgroup was measured too:
+      // 3 us per Llama2-7B layer faster at 1.5 % outliers and M = 4, 1 us slower at 0 and 0.5 %.
+      for (uint32_t e = rp0 + oes; e < rp1; e += 4u * ostride) {
+        uint32_t word[4];
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) word[u] = e + u * ostride < rp1 ? owords[e + u * ostride] : 0u;
+        half_t x0[4], x1[4];
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+          x0[u] = *(const half_t*)(xo0 + (word[u] & 0xFFFFu) * 2u);
+          if (NT > 1) x1[u] = *(const half_t*)(xo1 + (word[u] & 0xFFFFu) * 2u);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < 4; ++u) {
+          const float v = (float)bits_to_half((uint16_t)(word[u] >> 16));
+          oa0 += v * (float)x0[u];
+          if (NT > 1) oa1 += v * (float)x1[u];
+        }
       }
       for (uint32_t off = Mp; off < 16; off <<= 1) {
         oa0 += __shfl_xor(oa0, off);
