@@ -1186,6 +1186,9 @@ struct PlanePlan {
   uint32_t off_park, off_units, off_xs, off_utab, off_pieces, off_zero, off_obuf;  // LDS byte offsets (ring at 0)
   uint32_t obuf_bytes;  // outlier record of a tile: 128 + 4 * ocap
   uint32_t n;           // tiles per workgroup (<= WV)
+  uint32_t x_lds;       // 1: the whole activation vector is staged at off_xs; 0 (rows too long for that): only the
+                        //    columns of the 4-bit units are copied there (64 bytes per unit), the split and the
+                        //    outliers read the activations from memory
   // Dealing of the workgroup's blocks: wave w takes the run [N cum[w] / cum[W], N cum[w + 1] / cum[W]) of
   // its N blocks.  Older waves (lower numbers; waves w, w + 4, ... share a SIMD) win the issue arbitration
   // and run faster; they get longer runs so that all waves end together.
@@ -1259,7 +1262,9 @@ mpq_gemvp_kernel(const PlaneArgs a) {
   // ---- (1) requests: the staged operands (activations first: everything waits for them), then the
   //      wave's first two blocks, whose unit words come from the kernel arguments
   const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
-  dma_linear<W>((const unsigned char*)a.X, lds_addr(xs), 2u * b.K, wv, lane16);
+  const unsigned char* const xg = (const unsigned char*)a.X;
+  const bool x_lds = pl.x_lds != 0;
+  if (x_lds) dma_linear<W>(xg, lds_addr(xs), 2u * b.K, wv, lane16);
   dma_linear<W>(b.units, lds_addr(units), 32u * C, wv, lane16);
   // outliers of tile t: waves og * t .. og * t + og - 1 counted from the last wave down (the first waves
   // have the activations to split); the first wave of a group fetches the tile's record
@@ -1334,8 +1339,12 @@ mpq_gemvp_kernel(const PlaneArgs a) {
       const uint2 ue = *(const uint2*)(units + u * 8u);
       const bool real = (ue.y & 0xFFFFu) != 32u * (uint32_t)b.G;  // padding units point at the zero entries
       // slot 8 d + nn of the half unit <-> column 8 (nn % 4) + 2 d + nn / 4
-      const unsigned char* xa = xs + ue.x + 64u * pass + 32u * hf + 4u * d;
-      const uint32_t x0 = real ? *(const uint32_t*)xa : 0u, x1 = real ? *(const uint32_t*)(xa + 16u) : 0u;
+      const uint32_t xat = ue.x + 64u * pass + 32u * hf + 4u * d;
+      uint32_t x0 = 0u, x1 = 0u;
+      if (real) {
+        if (x_lds) { x0 = *(const uint32_t*)(xs + xat); x1 = *(const uint32_t*)(xs + xat + 16u); }
+        else { x0 = *(const uint32_t*)(xg + xat); x1 = *(const uint32_t*)(xg + xat + 16u); }  // ordinary loads: waited for in full
+      }
       float sum = ((float)as_h2(x0).x + (float)as_h2(x0).y) + ((float)as_h2(x1).x + (float)as_h2(x1).y);
       typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
       const ushort2_t m2 = __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, x0 & 0x7FFF7FFFu), __builtin_bit_cast(ushort2_t, x1 & 0x7FFF7FFFu));
@@ -1384,6 +1393,14 @@ mpq_gemvp_kernel(const PlaneArgs a) {
       // per unit: the sum of its activations and the exponent byte of piece 0's scale, 2^(E - 22)
       if ((it & 15u) == 0) *(uint2*)(utab + u * 8u) = uint2{__builtin_bit_cast(uint32_t, sum), 105u + E};
     }
+    if (!x_lds) {
+      // the activations of the 4-bit units (32 columns = 64 bytes each), where the 4-bit blocks will look for them
+      for (uint32_t it = tid; it < 16u * (C - B2); it += W * 64u) {
+        const uint32_t u4 = it >> 2, part = it & 3u;
+        const uint32_t k0x2 = *(const uint32_t*)(units + (4u * B2 + u4) * 8u);
+        *(uint4*)(xs + u4 * 64u + part * 16u) = *(const uint4*)(xg + k0x2 + part * 16u);
+      }
+    }
   }
 
   // ---- (3) outliers (Sec. 4.3, fused): og waves per tile, 64 og / 16 lanes per row, two words per
@@ -1398,7 +1415,8 @@ mpq_gemvp_kernel(const PlaneArgs a) {
     float oa = 0.f, ob = 0.f;
     for (uint32_t e = rp0 + oq; e < rp1; e += 2u * lpr) {
       const uint32_t wa = owords[e], wb = e + lpr < rp1 ? owords[e + lpr] : 0u;
-      const float xa = (float)*(const half_t*)(xs + (wa & 0xFFFFu) * 2u), xb = (float)*(const half_t*)(xs + (wb & 0xFFFFu) * 2u);
+      const unsigned char* xo = x_lds ? xs : xg;
+      const float xa = (float)*(const half_t*)(xo + (wa & 0xFFFFu) * 2u), xb = (float)*(const half_t*)(xo + (wb & 0xFFFFu) * 2u);
       oa = __builtin_fmaf((float)bits_to_half((uint16_t)(wa >> 16)), xa, oa);
       ob = __builtin_fmaf((float)bits_to_half((uint16_t)(wb >> 16)), xb, ob);
     }
@@ -1482,7 +1500,7 @@ mpq_gemvp_kernel(const PlaneArgs a) {
         yacc = __builtin_fmaf(dl, Sg, yacc);
       } else {
         // a 4-bit block: every weight decoded (eq. 5), the f16 matrix instruction multiplies and adds
-        const uint32_t xoff = *(const uint32_t*)(lds + unit_lane + c * 32u);
+        const uint32_t xoff = x_lds ? *(const uint32_t*)(lds + unit_lane + c * 32u) : (4u * (c - B2) + j) * 64u;
         const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
         const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
 #define MPQ_P_STEP4(P)                                                                                \
@@ -1862,13 +1880,14 @@ mpq_status gemv_decode(const Ctx& c, const uint16_t* X, uint16_t* Y) {
 // ---------------------------------------------------------------- M = 1, plane-sum kernel
 
 // LDS layout of the plane-sum GEMV for n tiles per workgroup of W waves; false if it does not fit.
-bool plane_layout(const MpqHeader& h, uint32_t W, uint32_t PD, uint32_t n, uint32_t budget, PlanePlan* pl) {
+bool plane_layout(const MpqHeader& h, uint32_t W, uint32_t PD, uint32_t n, bool x_lds, uint32_t budget, PlanePlan* pl) {
   const uint32_t C = (uint32_t)(h.B2 + h.B4);
   uint32_t off = W * PD * 1536u;                        // ring: PD slots of codes + two meta words per lane
   pl->off_park = off;   off += n * (2u * W + 1u) * 64u;
   pl->off_units = off;  off += 32u * C;                  // unit table
   off = (off + 15u) & ~15u;
-  pl->off_xs = off;     off += (2u * (uint32_t)h.K + 15u) & ~15u;
+  pl->off_xs = off;     off += x_lds ? (2u * (uint32_t)h.K + 15u) & ~15u : 256u * (uint32_t)h.B4;
+  pl->x_lds = x_lds ? 1u : 0u;
   pl->off_utab = off;   off += 32u * (uint32_t)h.B2;     // 8 bytes per 2-bit unit
   pl->off_pieces = off; off += 768u * (uint32_t)h.B2;    // 192 bytes per 2-bit unit
   pl->off_zero = off;   off += 128u;
@@ -1915,11 +1934,12 @@ mpq_status gemv_planes(const Ctx& c, const uint16_t* X, uint16_t* Y) {
   uint32_t n = 0;
   if (c.plan.gemv_tiles > 0) {
     n = (uint32_t)c.plan.gemv_tiles > W ? W : (uint32_t)c.plan.gemv_tiles;
-    if (!plane_layout(h, W, 2, n, 160 * 1024, &a.pl)) return MPQ_ERR_UNSUPPORTED;
+    if (!plane_layout(h, W, 2, n, true, 160 * 1024, &a.pl) && !plane_layout(h, W, 2, n, false, 160 * 1024, &a.pl)) return MPQ_ERR_UNSUPPORTED;
   } else {
+    // the whole activation vector on chip if it fits next to its fp8 pieces, else (K = 28672) only the pieces
     for (uint32_t gens = 1;; ++gens) {
       n = ((uint32_t)h.T + gens * (uint32_t)c.cus - 1u) / (gens * (uint32_t)c.cus);
-      if (n <= W && plane_layout(h, W, 2, n, 160 * 1024, &a.pl)) break;
+      if (n <= W && (plane_layout(h, W, 2, n, true, 160 * 1024, &a.pl) || plane_layout(h, W, 2, n, false, 160 * 1024, &a.pl))) break;
       if (n <= 1) return MPQ_ERR_UNSUPPORTED;
     }
   }
@@ -2084,11 +2104,14 @@ mpq_status launch_slices(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, vo
 
 // Which batch-1 kernel: the plane-sum kernel pays a fixed price per workgroup (the activations are split
 // into fp8 pieces, two more barriers) and needs 40 % fewer vector instructions per block; measured on
-// the Llama2-7B / Llama3-8B / Llama2-70B shapes it wins from about eight 16-row tiles per compute unit
-// on (57344 x 8192: 35 against 41 us, 128256 x 4096: 42 against 46 us) and loses below (12288 x 4096:
-// 8.7 against 7.0 us).
+// the Llama2-7B / Llama3-8B / Llama2-70B shapes it wins from about 200 code blocks per compute unit on
+// (57344 x 8192, 504 blocks: 35 against 41 us; 128256 x 4096, 595: 42 against 46 us) and loses below
+// (12288 x 4096, 54 blocks: 8.7 against 7.0 us; 28672 x 4096, 133: 13.0 against 12.1 us).  Rows too
+// long to stage the activations next to their pieces (8192 x 28672: 24.2 against 23.2 us, the split then
+// reads them from memory) stay with the per-weight kernel unless a plan asks otherwise.
 mpq_status gemv_all(const Ctx& c, const uint16_t* X, uint16_t* Y) {
-  const bool planes = c.plan.gemv_path == 1 || (c.plan.gemv_path == 0 && c.h.T >= 8 * c.cus);
+  const bool planes = c.plan.gemv_path == 1 || (c.plan.gemv_path == 0 && c.h.K <= 16384 &&
+                                                (int64_t)c.h.T * (c.h.B2 + c.h.B4) >= 200ll * c.cus);
   if (planes) {
     const mpq_status st = gemv_planes(c, X, Y);
     if (st != MPQ_ERR_UNSUPPORTED || c.plan.gemv_path == 1) return st;

@@ -219,7 +219,8 @@ def test_both_gemv_kernels_on_every_case(torch, case):
             rep = mpq.gemm_planned(pk.header, blob, x, y.view, 1, plan=mpq.Plan(gemv_path=path))
         except mpq.MpqError as e:
             # groups shorter than a unit, or rows so long that the split activations do not fit on chip
-            assert path == mpq.KERNEL_GEMV_PLANES and e.status == mpq.MPQ_ERR_UNSUPPORTED and (pk.g1 < 64 or pk.K > 16384)
+            # groups shorter than a unit
+            assert path == mpq.KERNEL_GEMV_PLANES and e.status == mpq.MPQ_ERR_UNSUPPORTED and pk.g1 < 64
             continue
         got = y.check_and_get()
         e_floor, e_max = rel_err(got, ref)
@@ -229,7 +230,7 @@ def test_both_gemv_kernels_on_every_case(torch, case):
         assert np.array_equal(y2.check_and_get(), got)
         ran.append((path, rep.kernel))
     planes_ran = (mpq.KERNEL_GEMV_PLANES, mpq.KERNEL_GEMV_PLANES) in ran
-    assert planes_ran == (pk.g1 >= 64 and pk.K <= 16384), ran
+    assert planes_ran == (pk.g1 >= 64), ran      # also K = 28672, where only the fp8 pieces of the activations are on chip
     assert ran[0][1] == mpq.KERNEL_GEMV_DECODE, ran
     assert (mpq.KERNEL_GEMV_DECODE, mpq.KERNEL_GEMV_DECODE) in ran
 
