@@ -36,6 +36,27 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
+// Phase stamps of the timeline build (-DMPQ_TIMELINE, a second library next to the product): wall-clock
+// reads (s_memrealtime, 100 MHz) at the phase boundaries of the batch-1 kernels.  The first and the last
+// wave of every workgroup write theirs to a buffer of 2 x 16 words per workgroup that the measuring
+// program hands over with mpq_timeline_buffer.  The product build compiles all of it away.
+#ifdef MPQ_TIMELINE
+__device__ unsigned long long* mpq_timeline_buf;
+#define MPQ_TL_DECL unsigned long long tl_[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#define MPQ_STAMP(k) tl_[k] = __builtin_amdgcn_s_memrealtime();
+#define MPQ_TL_NOTE(k, v) tl_[k] = (unsigned long long)(v);
+#define MPQ_TL_FLUSH(WG, WAVE, LASTWAVE, LANE)                                                          \
+  if (mpq_timeline_buf && (LANE) == 0 && ((WAVE) == 0 || (WAVE) == (LASTWAVE))) {                      \
+    unsigned long long* o_ = mpq_timeline_buf + ((size_t)(WG) * 2 + ((WAVE) == 0 ? 0 : 1)) * 16;        \
+    _Pragma("unroll") for (int q_ = 0; q_ < 16; ++q_) o_[q_] = tl_[q_];                                 \
+  }
+#else
+#define MPQ_TL_DECL
+#define MPQ_STAMP(k)
+#define MPQ_TL_NOTE(k, v)
+#define MPQ_TL_FLUSH(WG, WAVE, LASTWAVE, LANE)
+#endif
+
 struct DevBlob {
   const unsigned char* tiles;  // first tile record
   const unsigned char* units;  // unit table (2-bit units, then 4-bit units), 8 bytes per unit
@@ -963,17 +984,22 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
 //   and the last ones start late.
 template <int PD, int LDSB, int WV, int PU, bool AL = false>
 __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
-                                               const int n_arg, const uint32_t wg) {
+                                               const int n_arg, const uint32_t wg, const uint32_t n_lo, const uint32_t n_more) {
 #pragma clang fp contract(off)
   static_assert(PD >= 1 && PD <= 8 && WV >= 4 && WV <= 16, "ring depth / waves");
   __shared__ __align__(16) unsigned char lds[LDSB];
   constexpr uint32_t W = WV;
+  MPQ_TL_DECL
+  MPQ_STAMP(0)
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
-  const uint32_t C = b.C, T = b.T;
-  const uint32_t tile0 = wg * (uint32_t)n_arg;
-  const uint32_t n = T - tile0 < (uint32_t)n_arg ? T - tile0 : (uint32_t)n_arg;  // tiles of this workgroup
+  const uint32_t C = b.C;
+  // The tiles are dealt evenly: the first n_more workgroups own n_lo + 1 consecutive tiles, the others n_lo
+  // (n_arg = the most any of them gets).  No division here: every instruction of the prologue is paid by
+  // every wave of the launch - two integer divisions at this place cost 5 % of a Llama2-7B layer.
+  const uint32_t tile0 = wg * n_lo + (wg < n_more ? wg : n_more);
+  const uint32_t n = n_lo + (wg < n_more ? 1u : 0u);  // tiles of this workgroup
   // LDS layout: ring | partial sums [n][W + 1][16] | side records [n] | unit table | activations
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;  // pieces per 2-bit unit (PU) and per 4-bit unit
   const uint32_t units_bytes = 32u * PU * C;
@@ -1004,8 +1030,11 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }     \
   }
   MPQ_GEMV_FILL(0)
+  MPQ_STAMP(1)
   wait_vm_upto<PD>((int)inflight);  // the staged operands have landed; the code block may still be in flight
+  MPQ_STAMP(2)
   lds_barrier();
+  MPQ_STAMP(3)
   // The other ring slots are requested only now.  With every request of every workgroup issued in
   // its first instructions, the memory system serves workgroup after workgroup and the last ones
   // sit idle for most of the burst; this way every workgroup gets its first block early
@@ -1037,6 +1066,10 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
       if (oq == 15) red[(t * (W + 1) + W) * 16 + orow] = oa;
     }
   }
+  MPQ_STAMP(4)
+#ifdef MPQ_TIMELINE
+  uint32_t tl_blocks = 0;
+#endif
   const unsigned char* unitj = units + j * (8 * PU);
   const uint32_t ringl = ring0 + lane16;
   // With three or more blocks per wave, waves in their decode steps go before waves that fetch
@@ -1058,6 +1091,19 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, av),                    \
                                                   __builtin_bit_cast(half8_t, bv0), acc0, 0, 0, 0);   \
   }
+#ifdef MPQ_TIMELINE
+// (constant indices only: the stamps are wave-uniform and stay in scalar registers, so the timeline build
+// keeps the vector register count, and with it the number of resident waves, of the product build)
+#define MPQ_TL_BLOCK                                                                                    \
+  {                                                                                                     \
+    if (tl_blocks == 0) tl_[5] = __builtin_amdgcn_s_memrealtime();                                      \
+    else if (tl_blocks == 1) tl_[6] = __builtin_amdgcn_s_memrealtime();                                 \
+    else if (tl_blocks == 2) tl_[7] = __builtin_amdgcn_s_memrealtime();                                 \
+    ++tl_blocks;                                                                                        \
+  }
+#else
+#define MPQ_TL_BLOCK
+#endif
 #define MPQ_GEMV_BLOCK_HEAD(NP, FOUR)                                                                  \
   __builtin_amdgcn_s_setprio(0);                                                                      \
   /* the block's unit table entries are requested first: the wait inside the ring read below covers  \
@@ -1083,6 +1129,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   if constexpr (AL) pieces_aligned<NP, FOUR>(ent, side, b, i, s1p, zb, xoff);                         \
   else finish_pieces<NP>(ent, m1i, m2i, s1p, zb, xoff);                                               \
   if (decode_first) __builtin_amdgcn_s_setprio(2);                                                    \
+  MPQ_TL_BLOCK                                                                                        \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
     for (; c < (uint32_t)b.B2; c += W) {
       MPQ_GEMV_BLOCK_HEAD(PU, false)
@@ -1103,7 +1150,9 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     if (i == 0) *(float4_t*)(red + (t * (W + 1) + wv) * 16 + 4 * j) = acc0;
   }
 
+  MPQ_STAMP(8)
   lds_barrier();
+  MPQ_STAMP(9)
   // ---- (3) row r of tile t: the outlier term and the W partial sums, in a fixed order
   if (tid < 16 * n) {
     const uint32_t t = tid >> 4, r = tid & 15u;
@@ -1114,12 +1163,18 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     const uint32_t row = (tile0 + t) * 16 + r;
     if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)sum);
   }
+  MPQ_STAMP(10)
+#ifdef MPQ_TIMELINE
+  MPQ_TL_NOTE(11, tl_blocks)
+#endif
+  MPQ_TL_FLUSH(wg, wv, W - 1, lane)
 }
 
 template <int PD, int LDSB, int WV, int PU = 1, bool AL = false>
 __global__ void __launch_bounds__(WV * 64)
-mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg) {
-  gemv_workgroup<PD, LDSB, WV, PU, AL>(b, X, Y, n_arg, blockIdx.x);
+mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg, const uint32_t n_lo,
+                const uint32_t n_more) {
+  gemv_workgroup<PD, LDSB, WV, PU, AL>(b, X, Y, n_arg, blockIdx.x, n_lo, n_more);
 }
 
 // Several independent matrix-vector products in one launch (separate projections of a layer, the
@@ -1139,7 +1194,7 @@ mpq_gemv_multi_kernel(const MultiArgs a) {
   uint32_t p = 0;
   while ((int32_t)p + 1 < a.count && blockIdx.x >= a.first[p + 1]) ++p;
   const DevBlob b = a.b[p];
-  gemv_workgroup<PD, LDSB, WV, PU>(b, a.X[p], a.Y[p], 1, blockIdx.x - a.first[p]);
+  gemv_workgroup<PD, LDSB, WV, PU>(b, a.X[p], a.Y[p], 1, blockIdx.x - a.first[p], 1u, 0u);
 }
 
 // ------------------------------------------------------------------------------------ GEMV, plane sums
@@ -1244,6 +1299,8 @@ mpq_gemvp_kernel(const PlaneArgs a) {
   // written to need few of either.
   constexpr uint32_t W = WV, SLOTB = 1536;
   __shared__ __align__(16) unsigned char lds[LDSB];
+  MPQ_TL_DECL
+  MPQ_STAMP(0)
   const DevBlob& b = a.b;
   const PlanePlan& pl = a.pl;
   const uint32_t tid = threadIdx.x;
@@ -1323,10 +1380,13 @@ mpq_gemvp_kernel(const PlaneArgs a) {
     MPQ_P_REQUEST(j == 0 ? u0[0] : j == 1 ? u0[1] : j == 2 ? u0[2] : u0[3])
     MPQ_P_REQUEST(j == 0 ? u1[0] : j == 1 ? u1[1] : j == 2 ? u1[2] : u1[3])
   }
+  MPQ_STAMP(1)
   if (tid < 32) ((uint32_t*)(lds + pl.off_zero))[tid] = 0u;  // what inactive lanes of the A operand read
   for (uint32_t o = tid; o < n * (2u * W + 1u) * 16u; o += W * 64u) red[o] = 0.f;  // a wave parks sums only for the tiles it touches
   if (k1 > k0) MPQ_VMCNT(6); else MPQ_VMCNT(0);  // what is older than the two blocks has landed: activations, unit table, outlier record
+  MPQ_STAMP(2)
   lds_barrier();
+  MPQ_STAMP(3)
 
   // ---- (2) split the activations of every 2-bit unit into three fp8 pieces, in the order of the
   //      instruction's contraction slots.  16 lanes per unit: lane (pass, d, hf) takes the two dwords of
@@ -1403,6 +1463,7 @@ mpq_gemvp_kernel(const PlaneArgs a) {
     }
   }
 
+  MPQ_STAMP(4)
   // ---- (3) outliers (Sec. 4.3, fused): og waves per tile, 64 og / 16 lanes per row, two words per
   //      lane in flight
   if (ot < n) {
@@ -1430,7 +1491,9 @@ mpq_gemvp_kernel(const PlaneArgs a) {
       red[(ot * (2 * W + 1) + 2 * W) * 16 + orow] = oa;
     }
   }
+  MPQ_STAMP(5)
   lds_barrier();
+  MPQ_STAMP(6)
 
   // ---- (4) this wave's blocks, in order
   // A operand of lane (j, m = 4 g + p): piece p of unit g of the block on the 16 slots this lane
@@ -1513,6 +1576,9 @@ mpq_gemvp_kernel(const PlaneArgs a) {
         MPQ_P_STEP4(0) MPQ_P_STEP4(1) MPQ_P_STEP4(2) MPQ_P_STEP4(3)
 #undef MPQ_P_STEP4
       }
+#ifdef MPQ_TIMELINE
+      if (todo == k1 - k0) MPQ_STAMP(7)
+#endif
       if (++c == C || todo == 1) {
         // end of the tile (or of the wave's run): park the rows of the 2-bit part, added over the four
         // units of a block position in a fixed order, and batch column 0 of the 4-bit accumulator
@@ -1531,8 +1597,10 @@ mpq_gemvp_kernel(const PlaneArgs a) {
     }
   }
 #undef MPQ_P_REQUEST
+  MPQ_STAMP(8)
   MPQ_VMCNT(0);  // the re-requested blocks past the end of the run
   lds_barrier();
+  MPQ_STAMP(9)
 
   // ---- (5) row r of tile t: 16 lanes add the 2 W partial sums and the outlier term, always in the same order
   for (uint32_t o = tid; o < 256u * n; o += W * 64u) {
@@ -1548,6 +1616,9 @@ mpq_gemvp_kernel(const PlaneArgs a) {
     const uint32_t row = (tile0 + t) * 16 + r;
     if (k == 15u && row < (uint32_t)b.N) a.Y[row] = half_to_bits((half_t)sum);
   }
+  MPQ_STAMP(10)
+  MPQ_TL_NOTE(11, k1 - k0)
+  MPQ_TL_FLUSH(blockIdx.x, wv, W - 1, lane)
 }
 
 // ------------------------------------------------------------------------------------ dequant
@@ -1805,6 +1876,9 @@ size_t mm_lds_bytes(const MpqHeader& h, int M, int PD, int waves = 4) {
 }
 
 constexpr size_t kLdsPerCu = 160 * 1024;  // LDS of one gfx950 compute unit
+// Static LDS size of which three workgroups fit a compute unit: 52 KiB (of 53 KiB only two do: measured, the
+// third workgroup of 10240 x 8192 waited for a place and the launch took 7 % longer).
+#define MPQ_LDS_THIRD (52 * 1024)
 
 // ---------------------------------------------------------------- M = 1, per-weight decode kernel
 
@@ -1814,10 +1888,12 @@ size_t gemv_lds_bytes(const MpqHeader& h, int PD, int waves, int n) {
          32ull * mpq_pu2(h.g1) * (h.B2 + h.B4) + 2ull * h.K;
 }
 
+// n = the most tiles a workgroup gets; the kernel deals the tiles evenly to the grid's workgroups.
 template <int PD, int LDSB, int WV, int PU, bool AL = false>
-mpq_status launch_gemv(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
-  const unsigned grid = (unsigned)((c.h.T + n - 1) / n);
-  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU, AL>), dim3(grid), dim3(WV * 64), 0, c.s, c.d, X, Y, n);
+mpq_status launch_gemv(const Ctx& c, const uint16_t* X, uint16_t* Y, int n, unsigned grid) {
+  const uint32_t n_lo = (uint32_t)c.h.T / grid, n_more = (uint32_t)c.h.T - n_lo * grid;
+  if (n_lo + (n_more ? 1u : 0u) > (uint32_t)n) return MPQ_ERR_UNSUPPORTED;
+  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU, AL>), dim3(grid), dim3(WV * 64), 0, c.s, c.d, X, Y, n, n_lo, n_more);
   note(c, MPQ_KERNEL_GEMV_DECODE, 1, WV, n, grid);
   return MPQ_OK;
 }
@@ -1825,22 +1901,22 @@ mpq_status launch_gemv(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
 // GEMV with WV waves per workgroup and n tiles per workgroup in the smallest LDS class that holds
 // it.  Two code blocks per wave in flight: deeper rings were measured and change nothing.
 template <int WV, int PU, bool AL = false>
-mpq_status gemv_class(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
+mpq_status gemv_class(const Ctx& c, const uint16_t* X, uint16_t* Y, int n, unsigned grid) {
   const size_t need = gemv_lds_bytes(c.h, 2, WV, n);
-  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU, AL>(c, X, Y, n);
-  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU, AL>(c, X, Y, n);
-  if (need <= 53 * 1024) return launch_gemv<2, 53 * 1024, WV, PU, AL>(c, X, Y, n);
-  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU, AL>(c, X, Y, n);
-  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU, AL>(c, X, Y, n);
+  if (need <= 32 * 1024) return launch_gemv<2, 32 * 1024, WV, PU, AL>(c, X, Y, n, grid);
+  if (need <= 40 * 1024) return launch_gemv<2, 40 * 1024, WV, PU, AL>(c, X, Y, n, grid);
+  if (need <= MPQ_LDS_THIRD) return launch_gemv<2, MPQ_LDS_THIRD, WV, PU, AL>(c, X, Y, n, grid);
+  if (need <= 80 * 1024) return launch_gemv<2, 80 * 1024, WV, PU, AL>(c, X, Y, n, grid);
+  if (need <= 160 * 1024) return launch_gemv<2, 160 * 1024, WV, PU, AL>(c, X, Y, n, grid);
   return MPQ_ERR_UNSUPPORTED;
 }
 
 template <int WV>
-mpq_status gemv_waves(const Ctx& c, const uint16_t* X, uint16_t* Y, int n) {
+mpq_status gemv_waves(const Ctx& c, const uint16_t* X, uint16_t* Y, int n, unsigned grid) {
   switch (mpq_pu2(c.h.g1)) {  // first-order groups per 2-bit unit
-    case 1: return gemv_class<WV, 1>(c, X, Y, n);
-    case 2: return gemv_class<WV, 2>(c, X, Y, n);
-    default: return c.h.meta == MPQ_META_PAPER ? gemv_class<WV, 4, true>(c, X, Y, n) : gemv_class<WV, 4>(c, X, Y, n);
+    case 1: return gemv_class<WV, 1>(c, X, Y, n, grid);
+    case 2: return gemv_class<WV, 2>(c, X, Y, n, grid);
+    default: return c.h.meta == MPQ_META_PAPER ? gemv_class<WV, 4, true>(c, X, Y, n, grid) : gemv_class<WV, 4>(c, X, Y, n, grid);
   }
 }
 
@@ -1864,17 +1940,18 @@ mpq_status gemv_decode(const Ctx& c, const uint16_t* X, uint16_t* Y) {
       waves = 16;
       n = 2;
     } else {
-      waves = gemv_lds_bytes(h, 2, 8, 1) <= 53 * 1024 ? 8 : 16;
+      waves = gemv_lds_bytes(h, 2, 8, 1) <= MPQ_LDS_THIRD ? 8 : 16;
     }
   }
   if (c.plan.gemv_waves > 0) waves = c.plan.gemv_waves;
   if (c.plan.gemv_tiles > 0) n = c.plan.gemv_tiles > 8 ? 8 : c.plan.gemv_tiles;
   while (n > 1 && gemv_lds_bytes(h, 2, waves, n) > kLdsPerCu) --n;
+  const unsigned grid = (unsigned)((h.T + n - 1) / n);
   if (waves == 16) {
-    const mpq_status st = gemv_waves<16>(c, X, Y, n);
+    const mpq_status st = gemv_waves<16>(c, X, Y, n, grid);
     if (st != MPQ_ERR_UNSUPPORTED) return st;
   }
-  return gemv_waves<8>(c, X, Y, n);
+  return gemv_waves<8>(c, X, Y, n, grid);
 }
 
 // ---------------------------------------------------------------- M = 1, plane-sum kernel
@@ -2014,13 +2091,13 @@ mpq_status mm_chunk(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
       const bool two_of_8 = bw == 0 && mm_lds_bytes(h, M, 2, 8) <= 80 * 1024 && 2 * h.T >= 3 * c.cus;
       if (!two_of_8 && mm_lds_bytes(h, M, 2, 16) <= 160 * 1024) return launch_batch<NT, 2, 160 * 1024, 16>(c, X, Y, M);
     }
-    if (mm_lds_bytes(h, M, 2, 8) <= 53 * 1024) return launch_batch<NT, 2, 53 * 1024, 8>(c, X, Y, M);
+    if (mm_lds_bytes(h, M, 2, 8) <= MPQ_LDS_THIRD) return launch_batch<NT, 2, MPQ_LDS_THIRD, 8>(c, X, Y, M);
     if (mm_lds_bytes(h, M, 2, 8) <= 80 * 1024) return launch_batch<NT, 2, 80 * 1024, 8>(c, X, Y, M);
     if (mm_lds_bytes(h, M, 3, 8) <= 160 * 1024) return launch_batch<NT, 3, 160 * 1024, 8>(c, X, Y, M);
   }
   if (mm_lds_bytes(h, M, 3) <= 32 * 1024) return launch_mm<NT, 3, 32 * 1024>(c, X, Y, M);
   if (mm_lds_bytes(h, M, 3) <= 40 * 1024) return launch_mm<NT, 3, 40 * 1024>(c, X, Y, M);
-  if (mm_lds_bytes(h, M, 4) <= 53 * 1024) return launch_mm<NT, 4, 53 * 1024>(c, X, Y, M);
+  if (mm_lds_bytes(h, M, 4) <= MPQ_LDS_THIRD) return launch_mm<NT, 4, MPQ_LDS_THIRD>(c, X, Y, M);
   if (mm_lds_bytes(h, M, 6) <= 80 * 1024) return launch_mm<NT, 6, 80 * 1024>(c, X, Y, M);
   if (mm_lds_bytes(h, M, 8) <= 160 * 1024) return launch_mm<NT, 8, 160 * 1024>(c, X, Y, M);
   if (mm_lds_bytes(h, M, 3) <= 160 * 1024) return launch_mm<NT, 3, 160 * 1024>(c, X, Y, M);
@@ -2288,6 +2365,14 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
 #undef MPQ_MULTI_CLASS
   return MPQ_ERR_UNSUPPORTED;
 }
+
+#ifdef MPQ_TIMELINE
+// Timeline build only: where the batch-1 kernels write their phase stamps (NULL = nowhere).  buf_dev: device
+// memory of 2 x 16 x 8 bytes per workgroup of the launches that follow.  Synchronous.
+mpq_status mpq_timeline_buffer(void* buf_dev) {
+  return hipMemcpyToSymbol(HIP_SYMBOL(mpq_timeline_buf), &buf_dev, sizeof(buf_dev)) == hipSuccess ? MPQ_OK : MPQ_ERR_HIP;
+}
+#endif
 
 mpq_status mpq_stream_probe(const void* src_dev, size_t bytes, uint32_t* sink_dev, void* stream) {
   if (!src_dev) return MPQ_ERR_NULL;

@@ -25,6 +25,18 @@ def test_library_exports_every_declared_symbol():
     assert mpq.status_str(0) == "ok" and mpq.status_str(5).startswith("outlier")
 
 
+def test_timeline_build_adds_only_its_buffer_call():
+    """The timeline build is the product sources plus phase stamps: the same exports and mpq_timeline_buffer."""
+    import ctypes
+    path = os.path.join(os.path.dirname(mpq.LIB_PATH), "libmpq_timeline.so")
+    if not os.path.exists(path):
+        pytest.skip("timeline library not built")
+    L = ctypes.CDLL(path)
+    for name in list(mpq.EXPORTS) + ["mpq_timeline_buffer"]:
+        assert hasattr(L, name), name
+    assert not hasattr(mpq.lib(), "mpq_timeline_buffer")
+
+
 CASES = [
     # N, K, g1, g2, f4, p_o, z1_full, g2_axis
     (48, 1024, 64, 16, 0.10, 0.005, False, 0),

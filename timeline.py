@@ -1,0 +1,117 @@
+#!/usr/bin/env python3
+"""Phase timeline of the batch-1 kernels on one MI355X, from the timeline build of the library.
+
+The timeline build (paper_2311_16442_amd/libmpq_timeline.so: the product sources compiled with
+-DMPQ_TIMELINE) reads the 100 MHz wall clock at the phase boundaries of the two matrix-vector kernels;
+the first and the last wave of every workgroup write their stamps to a buffer.  This program runs the
+products of a decoder layer as bench.py does (copies of every matrix rotated so that the last-level
+cache holds other data, the other products of the layer launched in between), collects the stamps of
+one launch per repetition and prints, per shape and phase, the median and the 5 % .. 95 % range over
+workgroups and repetitions, in microseconds after the first wave of the launch started.
+
+  python timeline.py [--config 1|3|4] [--path 0|1|2] [--waves W] [--tiles n] [--reps 40]
+
+--path: 0 = the library's choice per shape, 1 = plane-sum kernel, 2 = per-weight kernel.
+"""
+import argparse
+import ctypes as C
+import os
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PHASES = {
+    2: ["start", "requests issued", "staged operands landed", "barrier 1", "outliers done", "block 1 fetched", "block 2 fetched",
+        "block 3 fetched", "blocks done", "barrier 2", "end"],
+    1: ["start", "requests issued", "staged operands landed", "barrier 1", "activations split", "outliers done", "barrier 2",
+        "block 1 done", "blocks done", "barrier 3", "end"],
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=1, choices=[1, 3, 4])
+    ap.add_argument("--path", type=int, default=0, choices=[0, 1, 2])
+    ap.add_argument("--reps", type=int, default=40)
+    ap.add_argument("--waves", type=int, default=0, help="waves per workgroup (0 = the library's choice)")
+    ap.add_argument("--tiles", type=int, default=0, help="tiles per workgroup (0 = the library's choice)")
+    args = ap.parse_args()
+    import torch
+    import mpq_synth as synth
+    import paper_2311_16442_amd as mpq
+    lib_path = os.path.join(os.path.dirname(mpq.LIB_PATH), "libmpq_timeline.so")
+    if not os.path.exists(lib_path):
+        raise SystemExit(f"{lib_path} is missing: python paper_2311_16442_amd/build.py --timeline")
+    L = C.CDLL(lib_path)
+    L.mpq_gemm_planned.restype = C.c_int
+    L.mpq_gemm_planned.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                   C.POINTER(mpq.Plan), C.POINTER(mpq.Report)]
+    L.mpq_timeline_buffer.restype = C.c_int
+    L.mpq_timeline_buffer.argtypes = [C.c_void_p]
+    shapes = []
+    for spec in synth.config_specs(args.config):
+        if spec.name == "lm_head":
+            continue
+        pk = mpq.pack_logical(synth.make_matrix(spec))
+        copies = max(3, min(12, int(1.5e9 // pk.blob.size)))
+        blobs = [torch.from_numpy(pk.blob).cuda() for _ in range(copies)]
+        X = torch.from_numpy(synth.make_x(1, 1, spec.K).view(np.int16).copy()).cuda()
+        Y = torch.zeros(spec.N, dtype=torch.int16, device="cuda")
+        shapes.append((spec, np.ascontiguousarray(pk.header), blobs, X, Y))
+    buf = torch.zeros(8192 * 32, dtype=torch.int64, device="cuda")
+    plan = mpq.Plan(gemv_path=args.path, gemv_waves=args.waves, gemv_tiles=args.tiles)
+    rep = mpq.Report()
+
+    def launch(sh, i):
+        spec, hdr, blobs, X, Y = sh
+        st = L.mpq_gemm_planned(hdr.ctypes.data, blobs[i % len(blobs)].data_ptr(), X.data_ptr(), Y.data_ptr(), 1, None, 0, None,
+                                C.byref(plan), C.byref(rep))
+        assert st == 0, st
+
+    print(f"# config {args.config}, gemv_path {args.path}, {args.reps} repetitions (the first 10 left out); microseconds after the first wave of the launch started")
+    print("# median [5 % .. 95 %] over workgroups and repetitions; first wave / last wave of a workgroup")
+    for sh in shapes:
+        spec = sh[0]
+        acc = []
+        for i in range(args.reps):
+            assert L.mpq_timeline_buffer(None) == 0
+            for other in shapes:
+                launch(other, i + 1)
+            torch.cuda.synchronize()
+            buf.zero_()
+            torch.cuda.synchronize()
+            assert L.mpq_timeline_buffer(buf.data_ptr()) == 0
+            launch(sh, i)
+            torch.cuda.synchronize()
+            if 2 * rep.workgroups * 16 > buf.numel():
+                raise SystemExit("stamp buffer too small")
+            if i >= 10:
+                acc.append(buf.cpu().numpy().reshape(-1, 16)[: 2 * rep.workgroups].astype(np.float64))
+        names = PHASES[rep.kernel]
+        kernel = {1: "plane-sum kernel", 2: "per-weight kernel"}[rep.kernel]
+        spans = np.array([(d[:, 10].max() - d[:, 0].min()) / 100.0 for d in acc])
+        early = np.median([np.sum((d[0::2, 0] - d[:, 0].min()) / 100.0 < 3.0) for d in acc])  # a second generation starts later
+        print(f"\n{spec.name} {spec.N}x{spec.K}: {kernel}, {rep.waves} waves x {rep.workgroups} workgroups, {rep.tiles_per_workgroup} tile(s) each; "
+              f"first start to last end {np.median(spans):.2f} us [{spans.min():.2f} .. {spans.max():.2f}]; "
+              f"{early:.0f} workgroups started within 3 us of the first")
+        for wsel, label in ((0, "first wave"), (1, "last wave")):
+            rows = []
+            for d in acc:
+                dd = (d[wsel::2, :11] - d[:, 0].min()) / 100.0
+                dd[d[wsel::2, :11] == 0] = np.nan
+                rows.append(dd)
+            dd = np.concatenate(rows, axis=0)
+            nb = np.concatenate([d[wsel::2, 11] for d in acc])
+            print(f"  {label} ({np.median(nb):.0f} blocks, at most {nb.max():.0f}):")
+            for k, nm in enumerate(names):
+                col = dd[:, k]
+                if np.all(np.isnan(col)):
+                    continue
+                print(f"    {nm:24s} {np.nanmedian(col):6.2f}  [{np.nanpercentile(col, 5):5.2f} .. {np.nanpercentile(col, 95):5.2f}]")
+
+
+if __name__ == "__main__":
+    main()
