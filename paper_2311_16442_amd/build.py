@@ -10,7 +10,9 @@ OUT = os.path.join(HERE, "libmpq.so")
 OUT_TIMELINE = os.path.join(HERE, "libmpq_timeline.so")
 SOURCES = ["mpq_pack.cpp", "mpq_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument",
+         # the leading scalar arguments of a kernel (up to 14 dwords) are placed in registers by the loader
+         "-mllvm", "-amdgpu-kernarg-preload-count=14"]
 
 
 def build(verbose: bool = False, extra=(), timeline: bool = False) -> str:

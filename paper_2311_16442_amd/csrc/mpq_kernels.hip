@@ -141,13 +141,10 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 template <uint32_t NW>
 __device__ __forceinline__ void dma_linear(const unsigned char* gbase, uint32_t lds, uint32_t bytes, uint32_t wv,
                                            uint32_t lane16) {
-  for (uint32_t off = wv * 1024u; off < bytes; off += NW * 1024u) {
-    if (off + 1024u <= bytes) {
-      dma16(gbase + off, lane16, lds + off);
-    } else if (off + lane16 < bytes) {
-      dma16(gbase + off, lane16, lds + off);
-    }
-  }
+  // one form for whole and partial pieces: the lanes beyond the end are masked off (fewer instructions than a
+  // branch between the two, and these run in the prologue of every wave)
+  for (uint32_t off = wv * 1024u; off < bytes; off += NW * 1024u)
+    if (off + lane16 < bytes) dma16(gbase + off, lane16, lds + off);
 }
 
 // Second-order dequantization of a first-order scale: fp16((fp32(s_int) - fp32(z2)) * fp32(s2)).
@@ -982,9 +979,19 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
 //   ONE code block per wave first; the second ring slot only after the first barrier - with every
 //   request of every workgroup issued at once the memory system serves workgroup after workgroup
 //   and the last ones start late.
+// What the first requests of a workgroup need.  mpq_gemv_kernel takes these as its leading scalar arguments
+// (14 dwords), which the loader places in registers before the first instruction: the requests go out
+// without waiting for a load of the argument block (about 0.15 us per launch).
+struct GemvLead {
+  const unsigned char* tiles;
+  const unsigned char* units;
+  const uint16_t* X;
+  uint32_t tile_stride, side_bytes, codes_off, C, K;
+  uint32_t n_arg, n_lo, n_more;  // tiles per workgroup: at most n_arg; the first n_more workgroups n_lo + 1, the others n_lo
+};
+
 template <int PD, int LDSB, int WV, int PU, bool AL = false>
-__device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
-                                               const int n_arg, const uint32_t wg, const uint32_t n_lo, const uint32_t n_more) {
+__device__ __forceinline__ void gemv_workgroup(const GemvLead& lead, const DevBlob& b, uint16_t* __restrict__ Y_arg, const uint32_t wg) {
 #pragma clang fp contract(off)
   static_assert(PD >= 1 && PD <= 8 && WV >= 4 && WV <= 16, "ring depth / waves");
   __shared__ __align__(16) unsigned char lds[LDSB];
@@ -994,7 +1001,16 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & 63u, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint32_t i = lane & 15u, j = lane >> 4, lane16 = lane * 16u;
-  const uint32_t C = b.C;
+  const unsigned char* const arg_tiles = lead.tiles;
+  const unsigned char* const arg_units = lead.units;
+  const uint16_t* const X = lead.X;
+  const uint32_t arg_stride = lead.tile_stride, arg_side = lead.side_bytes, arg_codes = lead.codes_off, arg_K = lead.K;
+  const uint32_t n_arg = lead.n_arg, n_lo = lead.n_lo, n_more = lead.n_more;
+  // the rest of the arguments in ONE batch of scalar loads, needed only after the first requests (the compiler
+  // would fetch each field where it is first used, one dependent round trip of about 0.1 us after the other)
+  uint32_t arg_m2 = b.off_m2, arg_ot = b.off_ot, arg_shift = b.m2_shift, arg_N = (uint32_t)b.N, arg_B2 = (uint32_t)b.B2;
+  uint16_t* Y = Y_arg;
+  const uint32_t C = lead.C;
   // The tiles are dealt evenly: the first n_more workgroups own n_lo + 1 consecutive tiles, the others n_lo
   // (n_arg = the most any of them gets).  No division here: every instruction of the prologue is paid by
   // every wave of the launch - two integer divisions at this place cost 5 % of a Llama2-7B layer.
@@ -1006,30 +1022,31 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   unsigned char* const ring = lds;
   float* const red = (float*)(lds + W * PD * 1024);
   unsigned char* const side0 = lds + W * PD * 1024 + (uint32_t)n_arg * (W + 1) * 64;
-  unsigned char* const units = side0 + (uint32_t)n_arg * b.side_bytes;
+  unsigned char* const units = side0 + (uint32_t)n_arg * arg_side;
   unsigned char* const xs = units + units_bytes;
   const DecodeConsts kc = make_consts();
 
   // ---- (1) requests, oldest first: staged operands, then this wave's first code blocks
-  const unsigned char* tileptr = b.tiles + (size_t)tile0 * b.tile_stride;
+  const unsigned char* tileptr = arg_tiles + (size_t)tile0 * arg_stride;
   for (uint32_t t = 0; t < n; ++t)
-    dma_linear<W>(tileptr + (size_t)t * b.tile_stride, lds_addr(side0) + t * b.side_bytes, b.side_bytes, wv, lane16);
-  dma_linear<W>(b.units, lds_addr(units), units_bytes, wv, lane16);
-  dma_linear<W>((const unsigned char*)X, lds_addr(xs), 2u * b.K, wv, lane16);
+    dma_linear<W>(tileptr + (size_t)t * arg_stride, lds_addr(side0) + t * arg_side, arg_side, wv, lane16);
+  dma_linear<W>(arg_units, lds_addr(units), units_bytes, wv, lane16);
+  dma_linear<W>((const unsigned char*)X, lds_addr(xs), 2u * arg_K, wv, lane16);
   // this wave's blocks: positions wv, wv + W, wv + 2W, ... of the n*C blocks of the workgroup
   const uint32_t ring0 = lds_addr(ring) + wv * (PD * 1024);
-  const unsigned char* rbase = tileptr + b.codes_off;  // code blocks of the tile being requested
+  const unsigned char* rbase = tileptr + arg_codes;  // code blocks of the tile being requested
   uint32_t rc = wv, rt = 0;                            // next request: block rc of tile rt (rt = n: none left)
-  while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }
+  while (rc >= C && rt < n) { rc -= C; ++rt; rbase += arg_stride; }
   uint32_t inflight = 0;
 #define MPQ_GEMV_FILL(R)                                                     \
   if (rt < n) {                                                              \
     dma16(rbase + rc * 1024u, lane16, ring0 + (R) * 1024u);                  \
     ++inflight;                                                              \
     rc += W;                                                                 \
-    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }     \
+    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += arg_stride; }     \
   }
   MPQ_GEMV_FILL(0)
+  asm volatile("; argument block" : "+s"(arg_m2), "+s"(arg_ot), "+s"(arg_shift), "+s"(arg_N), "+s"(arg_B2), "+s"(Y));
   MPQ_STAMP(1)
   wait_vm_upto<PD>((int)inflight);  // the staged operands have landed; the code block may still be in flight
   MPQ_STAMP(2)
@@ -1049,7 +1066,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   {
     const uint32_t otid = tid & 255u, orow = otid >> 4, oq = otid & 15u;
     for (uint32_t t = wv >> 2; t < n && wv < (W / 4) * 4; t += W / 4) {
-      const uint32_t* ostart = (const uint32_t*)(side0 + t * b.side_bytes + b.off_ot);
+      const uint32_t* ostart = (const uint32_t*)(side0 + t * arg_side + arg_ot);
       const uint32_t* owords = ostart + MPQ_OTILE_HEAD / 4;
       const uint32_t rp0 = ostart[orow], rp1 = ostart[orow + 1];
       float oa = 0.f;
@@ -1079,9 +1096,9 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   uint32_t slot = 0;  // ring slot of the next block to consume
   uint32_t c = wv;    // next block of this wave inside the current tile (>= C: none in this tile)
   for (uint32_t t = 0; t < n; ++t) {
-    const unsigned char* side = side0 + t * b.side_bytes;
+    const unsigned char* side = side0 + t * arg_side;
     const unsigned char* m1i = side + i * 2;
-    const unsigned char* m2i = side + b.off_m2 + (i >> b.m2_shift) * 4;
+    const unsigned char* m2i = side + arg_m2 + (i >> arg_shift) * 4;
     float4_t acc0 = {0.f, 0.f, 0.f, 0.f};
 #define MPQ_GEMV_STEP(TWO, P)                                                                         \
   {                                                                                                   \
@@ -1120,7 +1137,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
     dma16(rbase + rc * 1024u, lane16, ring0 + slot * 1024u);                                          \
     ++inflight;                                                                                       \
     rc += W;                                                                                          \
-    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += b.tile_stride; }                              \
+    while (rc >= C && rt < n) { rc -= C; ++rt; rbase += arg_stride; }                              \
   }                                                                                                   \
   slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
   half2_t s1p[NP];                                                                                    \
@@ -1131,7 +1148,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
   if (decode_first) __builtin_amdgcn_s_setprio(2);                                                    \
   MPQ_TL_BLOCK                                                                                        \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-    for (; c < (uint32_t)b.B2; c += W) {
+    for (; c < arg_B2; c += W) {
       MPQ_GEMV_BLOCK_HEAD(PU, false)
       const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
       MPQ_GEMV_STEP(true, 0) MPQ_GEMV_STEP(true, 1) MPQ_GEMV_STEP(true, 2) MPQ_GEMV_STEP(true, 3)
@@ -1161,7 +1178,7 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
 #pragma unroll
     for (uint32_t w2 = 0; w2 < W; ++w2) sum += rt0[w2 * 16];
     const uint32_t row = (tile0 + t) * 16 + r;
-    if (row < (uint32_t)b.N) Y[row] = half_to_bits((half_t)sum);
+    if (row < arg_N) Y[row] = half_to_bits((half_t)sum);
   }
   MPQ_STAMP(10)
 #ifdef MPQ_TIMELINE
@@ -1172,9 +1189,11 @@ __device__ __forceinline__ void gemv_workgroup(const DevBlob& b, const uint16_t*
 
 template <int PD, int LDSB, int WV, int PU = 1, bool AL = false>
 __global__ void __launch_bounds__(WV * 64)
-mpq_gemv_kernel(const DevBlob b, const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, const int n_arg, const uint32_t n_lo,
-                const uint32_t n_more) {
-  gemv_workgroup<PD, LDSB, WV, PU, AL>(b, X, Y, n_arg, blockIdx.x, n_lo, n_more);
+mpq_gemv_kernel(const unsigned char* __restrict__ tiles, const unsigned char* __restrict__ units, const uint16_t* __restrict__ X,
+                const uint32_t tile_stride, const uint32_t side_bytes, const uint32_t codes_off, const uint32_t C, const uint32_t K,
+                const uint32_t n_arg, const uint32_t n_lo, const uint32_t n_more, const DevBlob b, uint16_t* __restrict__ Y) {
+  const GemvLead lead = {tiles, units, X, tile_stride, side_bytes, codes_off, C, K, n_arg, n_lo, n_more};
+  gemv_workgroup<PD, LDSB, WV, PU, AL>(lead, b, Y, blockIdx.x);
 }
 
 // Several independent matrix-vector products in one launch (separate projections of a layer, the
@@ -1194,7 +1213,8 @@ mpq_gemv_multi_kernel(const MultiArgs a) {
   uint32_t p = 0;
   while ((int32_t)p + 1 < a.count && blockIdx.x >= a.first[p + 1]) ++p;
   const DevBlob b = a.b[p];
-  gemv_workgroup<PD, LDSB, WV, PU>(b, a.X[p], a.Y[p], 1, blockIdx.x - a.first[p], 1u, 0u);
+  const GemvLead lead = {b.tiles, b.units, a.X[p], b.tile_stride, b.side_bytes, b.codes_off, (uint32_t)b.C, (uint32_t)b.K, 1u, 1u, 0u};
+  gemv_workgroup<PD, LDSB, WV, PU>(lead, b, a.Y[p], blockIdx.x - a.first[p]);
 }
 
 // ------------------------------------------------------------------------------------ GEMV, plane sums
@@ -1893,7 +1913,8 @@ template <int PD, int LDSB, int WV, int PU, bool AL = false>
 mpq_status launch_gemv(const Ctx& c, const uint16_t* X, uint16_t* Y, int n, unsigned grid) {
   const uint32_t n_lo = (uint32_t)c.h.T / grid, n_more = (uint32_t)c.h.T - n_lo * grid;
   if (n_lo + (n_more ? 1u : 0u) > (uint32_t)n) return MPQ_ERR_UNSUPPORTED;
-  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU, AL>), dim3(grid), dim3(WV * 64), 0, c.s, c.d, X, Y, n, n_lo, n_more);
+  MPQ_LAUNCH((mpq_gemv_kernel<PD, LDSB, WV, PU, AL>), dim3(grid), dim3(WV * 64), 0, c.s, c.d.tiles, c.d.units, X, c.d.tile_stride,
+             c.d.side_bytes, c.d.codes_off, (uint32_t)c.d.C, (uint32_t)c.d.K, (uint32_t)n, n_lo, n_more, c.d, Y);
   note(c, MPQ_KERNEL_GEMV_DECODE, 1, WV, n, grid);
   return MPQ_OK;
 }
