@@ -34,6 +34,7 @@ typedef _Float16 half_t;
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 // Phase stamps of the timeline build (-DMPQ_TIMELINE, a second library next to the product): wall-clock
@@ -1644,18 +1645,28 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 // ------------------------------------------------------------------------------------ dequant
 //
 // Row-major fp16 copy of the dense part: W_out[n][k] = fp16((code - z1) * s1), bit-exact eq. 5.
-// One or several workgroups per tile, blocks round-robin over their waves, the next block's codes
-// requested before the current one is decoded.  A lane decodes its unit (64 or 32 columns of one row) four
-// steps at a time; the wave turns those 64 bytes per lane through a small LDS area so that four
-// neighbouring lanes write the 64 contiguous bytes of one (row, half unit) and a store instruction
-// covers whole 64-byte segments instead of 64 scattered 16-byte pieces.  20 KiB of LDS per
-// workgroup, so that 32 waves share a compute unit.  The kernel is bound by HBM writes: 2 bytes
-// out per weight against 0.33 bytes in.
+// One or several workgroups per tile, blocks round-robin over their waves.  A lane decodes its unit (64 or
+// 32 columns of one row); the wave turns the decoded bytes through a small LDS area so that neighbouring
+// lanes write contiguous bytes: eight lanes the whole 128-byte line of a (row, 2-bit unit) when a unit is
+// one piece (first-order groups of 64 columns or more), four lanes a 64-byte half unit otherwise.
+//
+// The kernel writes 2 bytes per weight against 0.33 read, so what counts is that a wave never waits for a
+// store.  Loads and stores of a wave complete in one order, so a wait for any load that was requested
+// after a store also waits for that store to be acknowledged by the memory side (one to two microseconds
+// under load).  Hence: (1) everything block n + 1 needs (codes, first- and second-order scale words) and the
+// unit table entries of block n + 2 are requested BEFORE the stores of block n and first used after them;
+// (2) the store rounds read no memory: the unit table entry that says where a (row, unit) goes comes out of
+// the registers of the lane that decoded it (v_readlane, the unit is the same for the whole wave in a
+// round); (3) the stores are buffer stores on the tile's 16 output rows: rows past the end of the matrix
+// and padding pieces (offset 2 GiB) fail the range check and are dropped by the hardware, so the rounds
+// hold no branch, and the compiler, which counts outstanding requests along straight code only, leaves
+// the stores in flight.
 template <int PU, bool ADD, bool AL = false>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 #pragma clang fp contract(off)
-  constexpr int PAIR = 80;  // LDS bytes per (row, half unit): 64 + 16 so that lanes fall into different banks
+  constexpr bool WHOLE = PU == 1;
+  constexpr int PAIR = WHOLE ? 144 : 80;  // LDS bytes per (row, unit) or (row, half unit): + 16 so that lanes fall into different banks
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
   __shared__ uint16_t gblock[ADD ? 2048 : 2];  // ADD: code block that holds the 2-bit K-group g
@@ -1670,11 +1681,16 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const unsigned char* m1i = tile + i * 2;
   const unsigned char* m2i = tile + b.off_m2 + (i >> b.m2_shift) * 4;
   uint4* dst = (uint4*)(mine + lane * PAIR);
-  const int chunk = lane & 3;  // 16-byte chunk (decode step) of a half unit that this lane stores
   // the blocks of a tile are shared by gridDim.y workgroups (matrices with few row tiles)
+  const int C = b.C;
   const int c0 = (int)blockIdx.y * 4 + wv, cstep = 4 * (int)gridDim.y;
   const uint32_t g1_shift = 31u - (uint32_t)__builtin_clz((uint32_t)(b.K / b.G));
   const uint32_t pad_entry = b.pad_entry;  // what bits 16-31 of a padding piece's table word hold
+  const uint32_t row_bytes = 2u * (uint32_t)b.K;
+  const int rows_here = b.N - (int)blockIdx.x * 16 < 16 ? b.N - (int)blockIdx.x * 16 : 16;
+  const __amdgpu_buffer_rsrc_t out_rows = __builtin_amdgcn_make_buffer_rsrc(
+      (unsigned char*)Wout + (size_t)blockIdx.x * 16 * row_bytes, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
+  constexpr uint32_t DROPPED = 0x80000000u;  // beyond any tile's 16 rows (at most 2 MiB)
   if (ADD) {
     // every piece of a 2-bit unit names its K-group through its first column
     for (int p = tid; p < 4 * b.B2 * PU; p += 256) {
@@ -1682,68 +1698,136 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
       if ((e.y >> 16) != pad_entry) gblock[(e.x >> 1) >> g1_shift] = (uint16_t)(p / (4 * PU));
     }
   }
-  uint4 qn = c0 < b.C ? codes[c0 * 64 + lane] : uint4{0, 0, 0, 0};
-  for (int c = c0; c < b.C; c += cstep) {
+  // table entries of the lane's unit in block CC; the words of its pieces' scales (first order: 8-bit
+  // quantized scale and zero point of the lane's row, second order: scale and zero point of its row group)
+#define MPQ_DQ_ENT(E, CC)                                                          \
+  {                                                                                \
+    const unsigned char* ue_ = b.units + (size_t)(4 * (CC) + j) * (8 * PU);        \
+    _Pragma("unroll") for (int q_ = 0; q_ < PU; ++q_) E[q_] = *(const uint2*)(ue_ + 8 * q_); \
+  }
+#define MPQ_DQ_META(E, M1, M2)                                                     \
+  _Pragma("unroll") for (int q_ = 0; q_ < PU; ++q_) {                              \
+    M1[q_] = *(const uint16_t*)(m1i + (E[q_].y & 0xFFFFu));                        \
+    M2[q_] = *(const uint32_t*)(m2i + (E[q_].y >> 16));                            \
+  }
+  uint2 e_cur[PU], e_nxt[PU], e_nn[PU];
+  uint32_t m1_cur[PU], m2_cur[PU], m1_nxt[PU], m2_nxt[PU];
+  uint4 q_cur = uint4{0, 0, 0, 0}, q_nxt;
+  if (c0 < C) {
+    const int c1 = c0 + cstep < C ? c0 + cstep : C - 1;
+    MPQ_DQ_ENT(e_cur, c0)
+    q_cur = codes[c0 * 64 + lane];
+    MPQ_DQ_ENT(e_nxt, c1)
+    if constexpr (!AL) MPQ_DQ_META(e_cur, m1_cur, m2_cur)
+    // nothing in flight at the head of the loop on the way in: the compiler places one wait there for both
+    // ways in, and what this way left open would make it a wait for everything, stores of the last turn included
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  }
+  for (int c = c0; c < C; c += cstep) {
     const bool two = c < b.B2;
-    const uint4 q = qn;
-    if (c + cstep < b.C) qn = codes[(c + cstep) * 64 + lane];
-    const unsigned char* ue = b.units + (size_t)(4 * c + j) * (8 * PU);
+    const uint4 q = q_cur;
     const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-    // stores of one half: (row, unit) pairs 16*s .. 16*s + 15 in round s, four lanes per pair
-#define MPQ_DQ_STORE_HALF(HALF, SPP)                                                                     \
+    // blocks past the wave's last one: its last block again (in bounds, not used)
+    const int cn = c + cstep < C ? c + cstep : C - 1, cnn = c + 2 * cstep < C ? c + 2 * cstep : C - 1;
+    // requests for the next block and the one after it; the asm keeps them ahead of the stores
+#define MPQ_DQ_REQUEST                                                \
+  q_nxt = codes[cn * 64 + lane];                                      \
+  if constexpr (!AL) MPQ_DQ_META(e_nxt, m1_nxt, m2_nxt)               \
+  MPQ_DQ_ENT(e_nn, cnn)                                               \
+  asm volatile("" ::: "memory");
+    // word W (x or y) of piece Q of unit U of the block: from the first lane that decoded that unit
+#define MPQ_DQ_WORD(Q, W, U) (uint32_t)__builtin_amdgcn_readlane((int)e_cur[Q].W, 16 * (U))
+    // stores of one half: (row, unit) pairs 16*s .. 16*s + 15 in round s (= unit s), four lanes per pair
+#define MPQ_DQ_STORE_HALF(HALF, SPP)                                                                      \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* the wave's own LDS area: lanes run in lockstep */ \
-  for (int s = 0; s < 4; ++s) {                                                                          \
-    const int pair = (lane >> 2) + s * 16; /* lane index (unit * 16 + row) that decoded it */            \
-    const int prow = blockIdx.x * 16 + (pair & 15);                                                      \
-    const int cg = (HALF) * 4 + chunk;     /* step inside the unit */                                    \
-    const uint2 pu = units[(4 * c + (pair >> 4)) * PU + cg / (SPP)]; /* the step's piece */               \
-    const uint4 v = *(const uint4*)(mine + pair * PAIR + chunk * 16);                                    \
-    /* padding pieces point at the zero scale entries; padding rows lie beyond N */                      \
-    if ((pu.y >> 16) != pad_entry && prow < b.N)                                                         \
-      *(uint4*)((unsigned char*)Wout + ((size_t)prow * b.K) * 2 + pu.x + (cg % (SPP)) * 16) = v;          \
-  }                                                                                                      \
+  _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                         \
+    const int pair = (lane >> 2) + s * 16; /* lane index (unit * 16 + row) that decoded it */             \
+    const int chunk = lane & 3, cg = (HALF) * 4 + chunk; /* step inside the half, inside the unit */      \
+    constexpr int QA = ((HALF) * 4) / (SPP);             /* the piece of the half's first step */         \
+    uint32_t ex = MPQ_DQ_WORD(QA, x, s), ey = MPQ_DQ_WORD(QA, y, s);                                      \
+    if constexpr ((SPP) < 4) { /* two pieces per half */                                                  \
+      constexpr int QB = QA + 1 < PU ? QA + 1 : QA;                                                       \
+      const uint32_t exb = MPQ_DQ_WORD(QB, x, s), eyb = MPQ_DQ_WORD(QB, y, s);                            \
+      if (chunk >> 1) { ex = exb; ey = eyb; }                                                             \
+    }                                                                                                     \
+    const uint4 v = *(const uint4*)(mine + pair * PAIR + chunk * 16);                                     \
+    /* padding pieces point at the zero scale entries */                                                  \
+    const uint32_t at = (ey >> 16) != pad_entry ? (uint32_t)(pair & 15) * row_bytes + ex + (uint32_t)(cg % (SPP)) * 16u : DROPPED; \
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, 0);         \
+  }                                                                                                       \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* reads done before the area is overwritten */
+    // stores of a whole 2-bit unit: (row, unit) pairs 8*s .. 8*s + 7 in round s (unit s / 2), eight lanes per pair
+#define MPQ_DQ_STORE_UNIT                                                                                 \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                      \
+  _Pragma("unroll") for (int s = 0; s < 8; ++s) {                                                         \
+    const int pair = (lane >> 3) + s * 8;                                                                 \
+    const int ch = lane & 7; /* decode step = 16-byte chunk of the unit */                                \
+    const uint32_t ex = MPQ_DQ_WORD(0, x, s >> 1), ey = MPQ_DQ_WORD(0, y, s >> 1);                        \
+    const uint4 v = *(const uint4*)(mine + pair * PAIR + ch * 16);                                        \
+    const uint32_t at = (ey >> 16) != pad_entry ? (uint32_t)(pair & 15) * row_bytes + ex + (uint32_t)ch * 16u : DROPPED; \
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, 0);         \
+  }                                                                                                       \
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#define MPQ_DQ_PIECES(NP, FOUR)                                                               \
+  half2_t s1p[NP];                                                                            \
+  half_t zb[NP];                                                                              \
+  if constexpr (AL) {                                                                         \
+    uint2 ent_[NP];                                                                           \
+    uint32_t xoff_[NP];                                                                       \
+    _Pragma("unroll") for (int q_ = 0; q_ < NP; ++q_) ent_[q_] = e_cur[q_];                   \
+    pieces_aligned<NP, FOUR>(ent_, tile, b, (uint32_t)i, s1p, zb, xoff_);                     \
+  } else {                                                                                    \
+    _Pragma("unroll") for (int q_ = 0; q_ < NP; ++q_) {                                       \
+      const half_t s1_ = scale_dequant(m1_cur[q_] & 0xFFu, m2_cur[q_]); /* exactly 0 for a padding piece */ \
+      s1p[q_] = half2_t{s1_, s1_};                                                            \
+      zb[q_] = bits_to_half((uint16_t)(0x6400u | (m1_cur[q_] >> 8))); /* 1024 + z1 */         \
+    }                                                                                         \
+  }
+#define MPQ_DQ_STEP8(P) dst[(P)] = decode_step<true, P>(lo, hi, s1p[0], zb[0], kc);
 #define MPQ_DQ_STEP(TWO, P)                                                                   \
   {                                                                                           \
     constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                  \
     dst[(P) & 3] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                            \
   }
     if (two) {
-      half2_t s1p[PU];
-      half_t zb[PU];
-      uint32_t xoff[PU];
-      if constexpr (AL) {
-        uint2 ent[PU];
-#pragma unroll
-        for (int qq = 0; qq < PU; ++qq) ent[qq] = *(const uint2*)(ue + 8 * qq);
-        pieces_aligned<PU, false>(ent, tile, b, (uint32_t)i, s1p, zb, xoff);
-      } else {
-        load_pieces<PU>(ue, m1i, m2i, s1p, zb, xoff);
-      }
+      MPQ_DQ_PIECES(PU, false)
       const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
-      MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
-      MPQ_DQ_STORE_HALF(0, 8 / PU)
-      MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
-      MPQ_DQ_STORE_HALF(1, 8 / PU)
-    } else {
-      half2_t s1p[PU4];
-      half_t zb[PU4];
-      uint32_t xoff[PU4];
-      if constexpr (AL) {
-        uint2 ent[PU4];
-#pragma unroll
-        for (int qq = 0; qq < PU4; ++qq) ent[qq] = *(const uint2*)(ue + 8 * qq);
-        pieces_aligned<PU4, true>(ent, tile, b, (uint32_t)i, s1p, zb, xoff);
+      if constexpr (WHOLE) {
+        MPQ_DQ_STEP8(0) MPQ_DQ_STEP8(1) MPQ_DQ_STEP8(2) MPQ_DQ_STEP8(3)
+        MPQ_DQ_STEP8(4) MPQ_DQ_STEP8(5) MPQ_DQ_STEP8(6) MPQ_DQ_STEP8(7)
+        MPQ_DQ_REQUEST
+        MPQ_DQ_STORE_UNIT
       } else {
-        load_pieces<PU4>(ue, m1i, m2i, s1p, zb, xoff);
+        MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
+        MPQ_DQ_REQUEST
+        MPQ_DQ_STORE_HALF(0, 8 / PU)
+        MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
+        MPQ_DQ_STORE_HALF(1, 8 / PU)
       }
+    } else {
+      MPQ_DQ_PIECES(PU4, true)
       const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
       MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
+      MPQ_DQ_REQUEST
       MPQ_DQ_STORE_HALF(0, 4 / PU4)
     }
+    q_cur = q_nxt;
+#pragma unroll
+    for (int q_ = 0; q_ < PU; ++q_) {
+      e_cur[q_] = e_nxt[q_];
+      e_nxt[q_] = e_nn[q_];
+      if constexpr (!AL) { m1_cur[q_] = m1_nxt[q_]; m2_cur[q_] = m2_nxt[q_]; }
+    }
 #undef MPQ_DQ_STEP
+#undef MPQ_DQ_STEP8
+#undef MPQ_DQ_PIECES
+#undef MPQ_DQ_STORE_UNIT
 #undef MPQ_DQ_STORE_HALF
+#undef MPQ_DQ_WORD
+#undef MPQ_DQ_REQUEST
   }
+#undef MPQ_DQ_META
+#undef MPQ_DQ_ENT
   if (ADD) {
     // Dense + sparse (Sec. 2.3) without a second launch: when the workgroup's weights are on their way to
     // memory, it adds the tile's outliers that lie in ITS blocks (native fp16 add = the definition's fp32
@@ -1751,6 +1835,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
     // compute unit's write-through L1 into the L2 both accesses go to: the barrier's wait for the stores
     // is all the ordering needed (a device-scope fence would write back the whole L2), and the load goes
     // past the L1, which has never held the line.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const int orow = tid >> 4, oq = tid & 15;
     const int row = blockIdx.x * 16 + orow;
