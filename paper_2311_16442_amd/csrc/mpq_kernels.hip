@@ -1645,99 +1645,100 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 // ------------------------------------------------------------------------------------ dequant
 //
 // Row-major fp16 copy of the dense part: W_out[n][k] = fp16((code - z1) * s1), bit-exact eq. 5.
-// One or several workgroups per tile, blocks round-robin over their waves.  A lane decodes its unit (64 or
-// 32 columns of one row); the wave turns the decoded bytes through a small LDS area so that neighbouring
-// lanes write contiguous bytes: eight lanes the whole 128-byte line of a (row, 2-bit unit) when a unit is
-// one piece (first-order groups of 64 columns or more), four lanes a 64-byte half unit otherwise.
+// A lane decodes its unit (64 or 32 columns of one row); the wave turns the decoded bytes through a small
+// LDS area so that neighbouring lanes write contiguous bytes: eight lanes the whole 128-byte line of a
+// (row, 2-bit unit) when a unit is one piece (first-order groups of 64 columns or more), four lanes a
+// 64-byte half unit otherwise.
 //
-// The kernel writes 2 bytes per weight against 0.33 read, so what counts is that a wave never waits for a
-// store.  Loads and stores of a wave complete in one order, so a wait for any load that was requested
-// after a store also waits for that store to be acknowledged by the memory side (one to two microseconds
-// under load).  Hence: (1) everything block n + 1 needs (codes, first- and second-order scale words) and the
-// unit table entries of block n + 2 are requested BEFORE the stores of block n and first used after them;
-// (2) the store rounds read no memory: the unit table entry that says where a (row, unit) goes comes out of
-// the registers of the lane that decoded it (v_readlane, the unit is the same for the whole wave in a
-// round); (3) the stores are buffer stores on the tile's 16 output rows: rows past the end of the matrix
-// and padding pieces (offset 2 GiB) fail the range check and are dropped by the hardware, so the rounds
-// hold no branch, and the compiler, which counts outstanding requests along straight code only, leaves
-// the stores in flight.
-template <int PU, bool ADD, bool AL = false>
+// The kernel writes 2 bytes per weight against 0.33 read; what was measured on the way to its shape:
+//   - Loads and stores of a wave complete in one order, so a wait for a load that was requested after a
+//     store also waits for that store, and a load that comes out of HBM while every compute unit streams
+//     stores takes 5 to 25 microseconds.  Hence batches: a wave requests everything its next D blocks need
+//     (table entries and code words, then the scale words the entries point at), and only then decodes
+//     and stores those blocks with no load in between.  With the D blocks per wave that most matrices
+//     leave, all reads of the launch happen before its first store.
+//   - The store rounds read no memory: the table entry that says where a (row, unit) goes comes out of
+//     the registers of the lane that decoded it (v_readlane; the unit is the same for the whole wave in a
+//     round).  The stores are buffer stores on the tile's 16 output rows: rows past the end of the
+//     matrix and padding pieces (offset 2 GiB) fail the range check and are dropped by the hardware,
+//     so the rounds hold no branch.
+//   - No block depends on another: the blocks of the whole matrix (tile-major) are dealt round-robin over
+//     all waves of a grid that is resident at once and a multiple of the number of compute units
+//     (a compute unit with four workgroups where others have three ends a third later): wave w takes
+//     blocks w, w + W, w + 2W, ... (dc, dt = W mod C, W div C: the step without a division).
+template <int PU, bool AL = false>
 __global__ void __launch_bounds__(256)
-mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
+mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, const int dt) {
 #pragma clang fp contract(off)
+  MPQ_TL_DECL
+  MPQ_STAMP(0)
   constexpr bool WHOLE = PU == 1;
   constexpr int PAIR = WHOLE ? 144 : 80;  // LDS bytes per (row, unit) or (row, half unit): + 16 so that lanes fall into different banks
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
+  constexpr int D = PU == 1 ? 8 : 4;      // blocks per batch (10 or 4 + 6 PU registers per block)
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
-  __shared__ uint16_t gblock[ADD ? 2048 : 2];  // ADD: code block that holds the 2-bit K-group g
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wv = tid >> 6;
+  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i = lane & 15, j = lane >> 4;
-  const unsigned char* tile = b.tiles + (size_t)blockIdx.x * b.tile_stride;
-  const uint2* units = (const uint2*)b.units;
-  const uint4* codes = (const uint4*)(tile + b.codes_off);
   const DecodeConsts kc = make_consts();
   unsigned char* mine = turn[wv];
-  const unsigned char* m1i = tile + i * 2;
-  const unsigned char* m2i = tile + b.off_m2 + (i >> b.m2_shift) * 4;
+  const uint32_t m1_lane = (uint32_t)i * 2u, m2_lane = b.off_m2 + ((uint32_t)i >> b.m2_shift) * 4u;
   uint4* dst = (uint4*)(mine + lane * PAIR);
-  // the blocks of a tile are shared by gridDim.y workgroups (matrices with few row tiles)
-  const int C = b.C;
-  const int c0 = (int)blockIdx.y * 4 + wv, cstep = 4 * (int)gridDim.y;
-  const uint32_t g1_shift = 31u - (uint32_t)__builtin_clz((uint32_t)(b.K / b.G));
+  const int C = b.C, T = b.T;
   const uint32_t pad_entry = b.pad_entry;  // what bits 16-31 of a padding piece's table word hold
   const uint32_t row_bytes = 2u * (uint32_t)b.K;
-  const int rows_here = b.N - (int)blockIdx.x * 16 < 16 ? b.N - (int)blockIdx.x * 16 : 16;
-  const __amdgpu_buffer_rsrc_t out_rows = __builtin_amdgcn_make_buffer_rsrc(
-      (unsigned char*)Wout + (size_t)blockIdx.x * 16 * row_bytes, 0, (uint32_t)rows_here * row_bytes, 0x00020000);
   constexpr uint32_t DROPPED = 0x80000000u;  // beyond any tile's 16 rows (at most 2 MiB)
-  if (ADD) {
-    // every piece of a 2-bit unit names its K-group through its first column
-    for (int p = tid; p < 4 * b.B2 * PU; p += 256) {
-      const uint2 e = units[p];
-      if ((e.y >> 16) != pad_entry) gblock[(e.x >> 1) >> g1_shift] = (uint16_t)(p / (4 * PU));
+  // the wave's first block (tile, block of the tile) and how many it has
+  const int waves = 4 * (int)gridDim.x, w0 = (int)blockIdx.x * 4 + wv;
+  int t_pre = w0 / C, c_pre = w0 - t_pre * C;  // walks ahead of the blocks being decoded; stays on the wave's last block
+  int left = t_pre < T ? (int)(((long long)T * C - w0 + waves - 1) / waves) : 0;
+  uint4 qs[D];
+  uint32_t m1s[D][PU], m2s[D][PU];
+  uint2 es[D][PU];
+  int ts[D], cs[D];
+  for (; left > 0; left -= D) {
+    // ---- everything the next D blocks need (past the wave's last block: that block again, in bounds, not used)
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      ts[d] = t_pre;
+      cs[d] = c_pre;
+      const unsigned char* ue = b.units + (size_t)(4 * c_pre + j) * (8 * PU);  // table entries of the lane's unit
+#pragma unroll
+      for (int q_ = 0; q_ < PU; ++q_) es[d][q_] = *(const uint2*)(ue + 8 * q_);
+      qs[d] = ((const uint4*)(b.tiles + (size_t)t_pre * b.tile_stride + b.codes_off))[c_pre * 64 + lane];
+      int c2 = c_pre + dc, t2 = t_pre + dt;
+      if (c2 >= C) { c2 -= C; ++t2; }
+      if (t2 < T) { t_pre = t2; c_pre = c2; }
     }
-  }
-  // table entries of the lane's unit in block CC; the words of its pieces' scales (first order: 8-bit
-  // quantized scale and zero point of the lane's row, second order: scale and zero point of its row group)
-#define MPQ_DQ_ENT(E, CC)                                                          \
-  {                                                                                \
-    const unsigned char* ue_ = b.units + (size_t)(4 * (CC) + j) * (8 * PU);        \
-    _Pragma("unroll") for (int q_ = 0; q_ < PU; ++q_) E[q_] = *(const uint2*)(ue_ + 8 * q_); \
-  }
-#define MPQ_DQ_META(E, M1, M2)                                                     \
-  _Pragma("unroll") for (int q_ = 0; q_ < PU; ++q_) {                              \
-    M1[q_] = *(const uint16_t*)(m1i + (E[q_].y & 0xFFFFu));                        \
-    M2[q_] = *(const uint32_t*)(m2i + (E[q_].y >> 16));                            \
-  }
-  uint2 e_cur[PU], e_nxt[PU], e_nn[PU];
-  uint32_t m1_cur[PU], m2_cur[PU], m1_nxt[PU], m2_nxt[PU];
-  uint4 q_cur = uint4{0, 0, 0, 0}, q_nxt;
-  if (c0 < C) {
-    const int c1 = c0 + cstep < C ? c0 + cstep : C - 1;
-    MPQ_DQ_ENT(e_cur, c0)
-    q_cur = codes[c0 * 64 + lane];
-    MPQ_DQ_ENT(e_nxt, c1)
-    if constexpr (!AL) MPQ_DQ_META(e_cur, m1_cur, m2_cur)
-    // nothing in flight at the head of the loop on the way in: the compiler places one wait there for both
-    // ways in, and what this way left open would make it a wait for everything, stores of the last turn included
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-  }
-  for (int c = c0; c < C; c += cstep) {
-    const bool two = c < b.B2;
-    const uint4 q = q_cur;
-    const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
-    // blocks past the wave's last one: its last block again (in bounds, not used)
-    const int cn = c + cstep < C ? c + cstep : C - 1, cnn = c + 2 * cstep < C ? c + 2 * cstep : C - 1;
-    // requests for the next block and the one after it; the asm keeps them ahead of the stores
-#define MPQ_DQ_REQUEST                                                \
-  q_nxt = codes[cn * 64 + lane];                                      \
-  if constexpr (!AL) MPQ_DQ_META(e_nxt, m1_nxt, m2_nxt)               \
-  MPQ_DQ_ENT(e_nn, cnn)                                               \
-  asm volatile("" ::: "memory");
-    // word W (x or y) of piece Q of unit U of the block: from the first lane that decoded that unit
-#define MPQ_DQ_WORD(Q, W, U) (uint32_t)__builtin_amdgcn_readlane((int)e_cur[Q].W, 16 * (U))
-    // stores of one half: (row, unit) pairs 16*s .. 16*s + 15 in round s (= unit s), four lanes per pair
+    if constexpr (!AL) {
+      // the words of its pieces' scales (first order: 8-bit quantized scale and zero point of the lane's row,
+      // second order: scale and zero point of its row group)
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const unsigned char* side = b.tiles + (size_t)ts[d] * b.tile_stride;
+#pragma unroll
+        for (int q_ = 0; q_ < PU; ++q_) {
+          m1s[d][q_] = *(const uint16_t*)(side + (m1_lane + (es[d][q_].y & 0xFFFFu)));
+          m2s[d][q_] = *(const uint32_t*)(side + (m2_lane + (es[d][q_].y >> 16)));
+        }
+      }
+    }
+    MPQ_STAMP(1)
+    // ---- decode, turn, store
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (d >= left) break;
+      const int t_cur = ts[d], c_cur = cs[d];
+      const bool two = c_cur < b.B2;
+      const uint4 q = qs[d];
+      const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+      // the tile's 16 rows of the output as a buffer
+      const int rows_left = b.N - t_cur * 16;
+      const __amdgpu_buffer_rsrc_t out_rows = __builtin_amdgcn_make_buffer_rsrc(
+          (unsigned char*)Wout + (size_t)t_cur * 16 * row_bytes, 0, (uint32_t)(rows_left < 16 ? rows_left : 16) * row_bytes, 0x00020000);
+      // word W (x or y) of piece Q of unit U of the block: from the first lane that decoded that unit
+#define MPQ_DQ_WORD(Q, W, U) (uint32_t)__builtin_amdgcn_readlane((int)es[d][Q].W, 16 * (U))
+      // stores of one half: (row, unit) pairs 16*s .. 16*s + 15 in round s (= unit s), four lanes per pair
 #define MPQ_DQ_STORE_HALF(HALF, SPP)                                                                      \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* the wave's own LDS area: lanes run in lockstep */ \
   _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                         \
@@ -1756,7 +1757,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
     __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, 0);         \
   }                                                                                                       \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); /* reads done before the area is overwritten */
-    // stores of a whole 2-bit unit: (row, unit) pairs 8*s .. 8*s + 7 in round s (unit s / 2), eight lanes per pair
+      // stores of a whole 2-bit unit: (row, unit) pairs 8*s .. 8*s + 7 in round s (unit s / 2), eight lanes per pair
 #define MPQ_DQ_STORE_UNIT                                                                                 \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                                                      \
   _Pragma("unroll") for (int s = 0; s < 8; ++s) {                                                         \
@@ -1774,13 +1775,13 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   if constexpr (AL) {                                                                         \
     uint2 ent_[NP];                                                                           \
     uint32_t xoff_[NP];                                                                       \
-    _Pragma("unroll") for (int q_ = 0; q_ < NP; ++q_) ent_[q_] = e_cur[q_];                   \
-    pieces_aligned<NP, FOUR>(ent_, tile, b, (uint32_t)i, s1p, zb, xoff_);                     \
+    _Pragma("unroll") for (int q_ = 0; q_ < NP; ++q_) ent_[q_] = es[d][q_];                   \
+    pieces_aligned<NP, FOUR>(ent_, b.tiles + (size_t)t_cur * b.tile_stride, b, (uint32_t)i, s1p, zb, xoff_); \
   } else {                                                                                    \
     _Pragma("unroll") for (int q_ = 0; q_ < NP; ++q_) {                                       \
-      const half_t s1_ = scale_dequant(m1_cur[q_] & 0xFFu, m2_cur[q_]); /* exactly 0 for a padding piece */ \
+      const half_t s1_ = scale_dequant(m1s[d][q_] & 0xFFu, m2s[d][q_]); /* exactly 0 for a padding piece */ \
       s1p[q_] = half2_t{s1_, s1_};                                                            \
-      zb[q_] = bits_to_half((uint16_t)(0x6400u | (m1_cur[q_] >> 8))); /* 1024 + z1 */         \
+      zb[q_] = bits_to_half((uint16_t)(0x6400u | (m1s[d][q_] >> 8))); /* 1024 + z1 */         \
     }                                                                                         \
   }
 #define MPQ_DQ_STEP8(P) dst[(P)] = decode_step<true, P>(lo, hi, s1p[0], zb[0], kc);
@@ -1789,69 +1790,38 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
     constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                  \
     dst[(P) & 3] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                            \
   }
-    if (two) {
-      MPQ_DQ_PIECES(PU, false)
-      const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
-      if constexpr (WHOLE) {
-        MPQ_DQ_STEP8(0) MPQ_DQ_STEP8(1) MPQ_DQ_STEP8(2) MPQ_DQ_STEP8(3)
-        MPQ_DQ_STEP8(4) MPQ_DQ_STEP8(5) MPQ_DQ_STEP8(6) MPQ_DQ_STEP8(7)
-        MPQ_DQ_REQUEST
-        MPQ_DQ_STORE_UNIT
+      if (two) {
+        MPQ_DQ_PIECES(PU, false)
+        const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
+        if constexpr (WHOLE) {
+          MPQ_DQ_STEP8(0) MPQ_DQ_STEP8(1) MPQ_DQ_STEP8(2) MPQ_DQ_STEP8(3)
+          MPQ_DQ_STEP8(4) MPQ_DQ_STEP8(5) MPQ_DQ_STEP8(6) MPQ_DQ_STEP8(7)
+          MPQ_DQ_STORE_UNIT
+        } else {
+          MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
+          MPQ_DQ_STORE_HALF(0, 8 / PU)
+          MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
+          MPQ_DQ_STORE_HALF(1, 8 / PU)
+        }
       } else {
-        MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
-        MPQ_DQ_REQUEST
-        MPQ_DQ_STORE_HALF(0, 8 / PU)
-        MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
-        MPQ_DQ_STORE_HALF(1, 8 / PU)
+        MPQ_DQ_PIECES(PU4, true)
+        const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+        MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
+        MPQ_DQ_STORE_HALF(0, 4 / PU4)
       }
-    } else {
-      MPQ_DQ_PIECES(PU4, true)
-      const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
-      MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
-      MPQ_DQ_REQUEST
-      MPQ_DQ_STORE_HALF(0, 4 / PU4)
-    }
-    q_cur = q_nxt;
-#pragma unroll
-    for (int q_ = 0; q_ < PU; ++q_) {
-      e_cur[q_] = e_nxt[q_];
-      e_nxt[q_] = e_nn[q_];
-      if constexpr (!AL) { m1_cur[q_] = m1_nxt[q_]; m2_cur[q_] = m2_nxt[q_]; }
-    }
 #undef MPQ_DQ_STEP
 #undef MPQ_DQ_STEP8
 #undef MPQ_DQ_PIECES
 #undef MPQ_DQ_STORE_UNIT
 #undef MPQ_DQ_STORE_HALF
 #undef MPQ_DQ_WORD
-#undef MPQ_DQ_REQUEST
+    }
+    MPQ_STAMP(2)
   }
-#undef MPQ_DQ_META
-#undef MPQ_DQ_ENT
-  if (ADD) {
-    // Dense + sparse (Sec. 2.3) without a second launch: when the workgroup's weights are on their way to
-    // memory, it adds the tile's outliers that lie in ITS blocks (native fp16 add = the definition's fp32
-    // add and one rounding), 16 lanes per row.  The weight was written by this workgroup, i.e. through this
-    // compute unit's write-through L1 into the L2 both accesses go to: the barrier's wait for the stores
-    // is all the ordering needed (a device-scope fence would write back the whole L2), and the load goes
-    // past the L1, which has never held the line.
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    const int orow = tid >> 4, oq = tid & 15;
-    const int row = blockIdx.x * 16 + orow;
-    const uint32_t* rec = (const uint32_t*)(tile + b.off_ot);
-    const uint32_t* words = rec + MPQ_OTILE_HEAD / 4;
-    const uint32_t rp0 = rec[orow], rp1 = rec[orow + 1];
-    if (row < b.N)
-      for (uint32_t e = rp0 + oq; e < rp1; e += 16) {
-        const uint32_t word = words[e];
-        const uint32_t col = word & 0xFFFFu, blk = gblock[col >> g1_shift];
-        if ((blk % (uint32_t)cstep) / 4u != blockIdx.y) continue;  // another workgroup wrote that weight
-        uint16_t* at = Wout + (size_t)row * b.K + col;
-        const half_t sum = bits_to_half(__builtin_nontemporal_load(at)) + bits_to_half((uint16_t)(word >> 16));
-        *at = half_to_bits(sum);
-      }
-  }
+  MPQ_STAMP(3)
+  MPQ_TL_NOTE(12, __builtin_amdgcn_s_getreg((31 << 11) | 4))   // HW_ID: where the wave ran
+  MPQ_TL_NOTE(13, __builtin_amdgcn_s_getreg((31 << 11) | 20))  // XCC_ID
+  MPQ_TL_FLUSH(blockIdx.x, wv, 3, lane)
 }
 
 // W[row][col] = fp16(W[row][col] + val) for every outlier word of the tile (native fp16 add = the
@@ -2506,30 +2476,24 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   if ((st = cu_count(&cus)) != MPQ_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   const int pu = mpq_pu2(h.g1);
-  // enough workgroups for eight per compute unit: tiles with many blocks are shared
-  int slices = (8 * cus + h.T - 1) / h.T;
-  const int most = (h.B2 + h.B4 + 3) / 4;
-  slices = slices > most ? most : slices;
-  slices = slices > 8 ? 8 : slices < 1 ? 1 : slices;
-  const dim3 grid((unsigned)h.T, (unsigned)slices);
-  // The outliers are added at the end of the same kernel when a 128-byte line of the output belongs to ONE
-  // unit (g1 >= 64: 64 columns of a row), so that no other workgroup of the compute unit ever touches a
-  // line this workgroup reads back; shorter groups get them from a second kernel.  Measured: the same
-  // time either way (22016 x 4096: 55 us without outliers, 70 us with) - what costs is the scattered
-  // two-byte read-modify-write itself, one per outlier, not the launch.
-  const bool add = add_outliers && h.nnz > 0;
-  const bool fused = add && pu == 1 && h.G <= 2048;
-#define MPQ_DQ_LAUNCH(PUV)                                                                             \
-  {                                                                                                    \
-    if (fused) MPQ_LAUNCH((mpq_dequant_kernel<PUV, true>), grid, dim3(256), 0, s, d, W_out_dev);       \
-    else MPQ_LAUNCH((mpq_dequant_kernel<PUV, false>), grid, dim3(256), 0, s, d, W_out_dev);            \
-  }
-  if (pu == 1) MPQ_DQ_LAUNCH(1)
-  else if (pu == 2) MPQ_DQ_LAUNCH(2)
-  else if (h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, false, true>), grid, dim3(256), 0, s, d, W_out_dev);
-  else MPQ_DQ_LAUNCH(4)
-#undef MPQ_DQ_LAUNCH
-  if (add && !fused) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  // every block of the matrix dealt over the waves of at most four workgroups per compute unit (what 37 KiB
+  // of LDS leave resident), the same number on every compute unit, as few as leave a wave at most one batch
+  const long long blocks = (long long)h.T * (h.B2 + h.B4);
+  if (blocks == 0) return MPQ_OK;
+  const int batch = pu == 1 ? 8 : 4;
+  long long per_cu = (blocks + 4ll * batch * cus - 1) / (4ll * batch * cus);
+  per_cu = per_cu > 4 ? 4 : per_cu;
+  const dim3 grid((unsigned)(per_cu * cus));
+  const int dc = (int)((4ll * grid.x) % (h.B2 + h.B4)), dt = (int)((4ll * grid.x) / (h.B2 + h.B4));
+  if (pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else MPQ_LAUNCH((mpq_dequant_kernel<4>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  // The outliers (dense + sparse, Sec. 2.3): a second kernel.  Adding them at the end of the first one, by the
+  // workgroup that wrote the weights, needs workgroups that own tiles and wait for their stores, which costs
+  // more than the second launch (22016 x 4096, 0.5 % outliers: 82 us against 63 us).  What the pass costs is the
+  // memory side's read-modify-write of one 64-byte piece per outlier, not the launch.
+  if (add_outliers && h.nnz > 0) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   return MPQ_OK;
 }
 
