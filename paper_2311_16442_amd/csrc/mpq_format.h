@@ -46,6 +46,13 @@
 //                                 row pointer: no dependent load.
 //       codes at codes_off (128-byte aligned): (B2 + B4) x 64 x 16 B, the 2-bit blocks then the 4-bit
 //                                 blocks of the tile, [block][lane] 16-byte units
+//       oidx at oidx_off (64-byte aligned; only for g1 >= 64, byte metadata, 0 < ocap <= 65535):
+//                                 uint16 [B2 + 1][16]: entry [c][r] = index, among the tile's outlier words, of
+//                                 the first word of row r whose column lies in 2-bit block c or a later one
+//                                 ([B2][r] = end of row r).  The 2-bit stream is in K order and outliers live
+//                                 in 2-bit groups only (Sec. 4.3), so the words of (row r, block c) are
+//                                 [c][r] .. [c + 1][r] - 1: whoever decodes a block finds its outliers with two
+//                                 loads and no search.  Derived from the outlier record; not counted as stored bits.
 //
 // Bit positions inside a unit (4 little-endian dwords).  A decode step P covers the 8 columns
 // k0 + 8P .. k0 + 8P + 7; column 8P + 2d + h (d = 0..3, h = 0, 1) lives in dword d, in its low (h = 0)
@@ -83,7 +90,7 @@
 #include <stdint.h>
 
 #define MPQ_MAGIC 0x3151504Du /* "MPQ1" */
-#define MPQ_VERSION 8u
+#define MPQ_VERSION 9u
 #define MPQ_TILE_ROWS 16
 #define MPQ_UNITS_PER_BLOCK 4
 #define MPQ_BLOCK_BYTES 1024
@@ -104,7 +111,7 @@ typedef struct {
   uint64_t codes_off;   /* offset of the code blocks inside a tile record */
   uint64_t ocap;        /* words per tile in the outlier records (multiple of 32) */
   uint64_t meta;        /* MPQ_META_BYTES or MPQ_META_PAPER */
-  uint64_t reserved1;
+  uint64_t oidx_off;    /* offset of the outlier block index inside a tile record; 0 = the blob has none */
   uint64_t total_bytes;
   /* bit g = K-group g holds 4-bit codes (all zero if G > MPQ_IS4_BITS: the header then does not say
      which groups are 4-bit).  With it a unit's table entry follows from the header alone, so the host

@@ -68,6 +68,7 @@ struct DevBlob {
   uint32_t m2_shift;           // lane part of a meta2 address = 4 * (row >> m2_shift)
   uint32_t off_m1b, off_s2, off_z2;  // aligned metadata (Sec. 3.3): bytes of the 4-bit groups, second-order scales, zeros
   uint32_t pad_entry;                // bits 16-31 of the table word of a padding piece (the zero second-order entry)
+  uint32_t off_oidx, ocap;           // outlier block index inside a tile record (0 = none); words per outlier record
   int32_t N, K, G, S, B2, C, T;
 };
 
@@ -1661,12 +1662,19 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 //     the registers of the lane that decoded it (v_readlane; the unit is the same for the whole wave in a
 //     round).  The stores are buffer stores on the tile's 16 output rows: rows past the end of the
 //     matrix and padding pieces (offset 2 GiB) fail the range check and are dropped by the hardware,
-//     so the rounds hold no branch.
+//     so the rounds hold no branch.  Whole lines are written with the non-temporal bit when nothing reads
+//     them back (NT: no outliers to add afterwards): 3 to 17 % faster; behind it the outlier pass is slower.
 //   - No block depends on another: the blocks of the whole matrix (tile-major) are dealt round-robin over
 //     all waves of a grid that is resident at once and a multiple of the number of compute units
 //     (a compute unit with four workgroups where others have three ends a third later): wave w takes
 //     blocks w, w + W, w + 2W, ... (dc, dt = W mod C, W div C: the step without a division).
-template <int PU, bool AL = false>
+//   - The outliers (dense + sparse, Sec. 2.3).  A second kernel that adds them to the finished matrix makes the
+//     memory side read and write one 64-byte piece per outlier (22016 x 4096, 0.5 %: + 20 us).  ADD adds
+//     them while the decoded block is in LDS: the tile's outlier block index names the words of (row, block),
+//     lane (row r, j) takes words j and j + 4 of row r (both requested with the batch's other loads; further
+//     ones, which are rare, with loads of their own), finds the unit by comparing the column with the four
+//     units' first columns and adds in place (native fp16 add = the definition's fp32 add and one rounding).
+template <int PU, bool NT, bool AL = false, bool ADD = false>
 __global__ void __launch_bounds__(256)
 mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, const int dt) {
 #pragma clang fp contract(off)
@@ -1677,9 +1685,18 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   constexpr int D = PU == 1 ? 8 : 4;      // blocks per batch (10 or 4 + 6 PU registers per block)
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
+  // the unit table, when it fits (K up to 28672 for one piece per unit): a wave's first requests then depend
+  // on no other load, and go out before any wave of the launch has stored anything
+  constexpr int TABLE = PU == 1 ? 4096 : 16384;
+  __shared__ __align__(16) unsigned char table[TABLE];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i = lane & 15, j = lane >> 4;
+  const bool staged = 32 * PU * b.C <= TABLE;
+  if (staged) {
+    for (int o = tid * 16; o < 32 * PU * b.C; o += 256 * 16) *(uint4*)(table + o) = *(const uint4*)(b.units + o);
+    __syncthreads();
+  }
   const DecodeConsts kc = make_consts();
   unsigned char* mine = turn[wv];
   const uint32_t m1_lane = (uint32_t)i * 2u, m2_lane = b.off_m2 + ((uint32_t)i >> b.m2_shift) * 4u;
@@ -1692,20 +1709,34 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
   const int waves = 4 * (int)gridDim.x, w0 = (int)blockIdx.x * 4 + wv;
   int t_pre = w0 / C, c_pre = w0 - t_pre * C;  // walks ahead of the blocks being decoded; stays on the wave's last block
   int left = t_pre < T ? (int)(((long long)T * C - w0 + waves - 1) / waves) : 0;
+  static_assert(!ADD || (PU == 1 && !AL), "outliers are added in LDS only where a lane's area holds its whole unit");
   uint4 qs[D];
   uint32_t m1s[D][PU], m2s[D][PU];
   uint2 es[D][PU];
   int ts[D], cs[D];
+  uint32_t ofirst[D], ocount[D], oword[D][2];  // ADD: first word and number of words of (block, row i); words j and j + 4
   for (; left > 0; left -= D) {
+#ifdef MPQ_TIMELINE
+    // per wave, summed over its batches and blocks: [1] requests issued, [2] wait for a block's words, [3] decode,
+    // turn and stores, [11] blocks
+    const unsigned long long tl_r = __builtin_amdgcn_s_memrealtime();
+#endif
     // ---- everything the next D blocks need (past the wave's last block: that block again, in bounds, not used)
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       ts[d] = t_pre;
       cs[d] = c_pre;
-      const unsigned char* ue = b.units + (size_t)(4 * c_pre + j) * (8 * PU);  // table entries of the lane's unit
+      const uint32_t ue = (uint32_t)(4 * c_pre + j) * (8 * PU);  // table entries of the lane's unit
 #pragma unroll
-      for (int q_ = 0; q_ < PU; ++q_) es[d][q_] = *(const uint2*)(ue + 8 * q_);
+      for (int q_ = 0; q_ < PU; ++q_) es[d][q_] = staged ? *(const uint2*)(table + ue + 8 * q_) : *(const uint2*)(b.units + ue + 8 * q_);
       qs[d] = ((const uint4*)(b.tiles + (size_t)t_pre * b.tile_stride + b.codes_off))[c_pre * 64 + lane];
+      if constexpr (ADD) {
+        // a 4-bit block: the entries of the last 2-bit block, and no words
+        const int cx = c_pre < b.B2 ? c_pre : b.B2 - 1;
+        const uint16_t* ox = (const uint16_t*)(b.tiles + (size_t)t_pre * b.tile_stride + b.off_oidx) + cx * 16 + i;
+        ofirst[d] = ox[0];
+        ocount[d] = ox[16];
+      }
       int c2 = c_pre + dc, t2 = t_pre + dt;
       if (c2 >= C) { c2 -= C; ++t2; }
       if (t2 < T) { t_pre = t2; c_pre = c2; }
@@ -1721,9 +1752,18 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
           m1s[d][q_] = *(const uint16_t*)(side + (m1_lane + (es[d][q_].y & 0xFFFFu)));
           m2s[d][q_] = *(const uint32_t*)(side + (m2_lane + (es[d][q_].y >> 16)));
         }
+        if constexpr (ADD) {
+          const uint32_t* words = (const uint32_t*)(side + b.off_ot + MPQ_OTILE_HEAD);
+          ocount[d] = cs[d] < b.B2 ? ocount[d] - ofirst[d] : 0u;
+          const uint32_t w0 = ofirst[d] + (uint32_t)j, w1 = w0 + 4u;
+          oword[d][0] = words[w0 < b.ocap ? w0 : 0u];
+          oword[d][1] = words[w1 < b.ocap ? w1 : 0u];
+        }
       }
     }
-    MPQ_STAMP(1)
+#ifdef MPQ_TIMELINE
+    tl_[1] += __builtin_amdgcn_s_memrealtime() - tl_r;
+#endif
     // ---- decode, turn, store
 #pragma unroll
     for (int d = 0; d < D; ++d) {
@@ -1731,6 +1771,11 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
       const int t_cur = ts[d], c_cur = cs[d];
       const bool two = c_cur < b.B2;
       const uint4 q = qs[d];
+#ifdef MPQ_TIMELINE
+      const unsigned long long tl_a = __builtin_amdgcn_s_memrealtime();
+      if constexpr (!AL) asm volatile("" ::"v"(q.x), "v"(m1s[d][0]), "v"(m2s[d][0]));
+      const unsigned long long tl_b = __builtin_amdgcn_s_memrealtime();
+#endif
       const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
       // the tile's 16 rows of the output as a buffer
       const int rows_left = b.N - t_cur * 16;
@@ -1766,7 +1811,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
     const uint32_t ex = MPQ_DQ_WORD(0, x, s >> 1), ey = MPQ_DQ_WORD(0, y, s >> 1);                        \
     const uint4 v = *(const uint4*)(mine + pair * PAIR + ch * 16);                                        \
     const uint32_t at = (ey >> 16) != pad_entry ? (uint32_t)(pair & 15) * row_bytes + ex + (uint32_t)ch * 16u : DROPPED; \
-    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, 0);         \
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, NT ? 2 : 0); \
   }                                                                                                       \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #define MPQ_DQ_PIECES(NP, FOUR)                                                               \
@@ -1796,6 +1841,27 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
         if constexpr (WHOLE) {
           MPQ_DQ_STEP8(0) MPQ_DQ_STEP8(1) MPQ_DQ_STEP8(2) MPQ_DQ_STEP8(3)
           MPQ_DQ_STEP8(4) MPQ_DQ_STEP8(5) MPQ_DQ_STEP8(6) MPQ_DQ_STEP8(7)
+          if constexpr (ADD) {
+            // byte offsets of the four units' first columns in a row; a padding unit (offset 0) comes after the
+            // real ones, and no word of this block lies in it
+            const uint32_t x0 = MPQ_DQ_WORD(0, x, 0), x1 = MPQ_DQ_WORD(0, x, 1), x2 = MPQ_DQ_WORD(0, x, 2), x3 = MPQ_DQ_WORD(0, x, 3);
+            auto add_outlier = [&](const uint32_t word) {
+              const uint32_t at = 2u * (word & 0xFFFFu);
+              const uint32_t d0 = at - x0, d1 = at - x1, d2 = at - x2, d3 = at - x3;
+              const uint32_t u = d0 < 128u ? 0u : d1 < 128u ? 1u : d2 < 128u ? 2u : 3u;
+              const uint32_t du = d0 < 128u ? d0 : d1 < 128u ? d1 : d2 < 128u ? d2 : d3;
+              if (du < 128u) {
+                uint16_t* w16 = (uint16_t*)(mine + (u * 16u + (uint32_t)i) * PAIR + du);
+                *w16 = half_to_bits(bits_to_half(*w16) + bits_to_half((uint16_t)(word >> 16)));
+              }
+            };
+            if ((uint32_t)j < ocount[d]) add_outlier(oword[d][0]);
+            if ((uint32_t)j + 4u < ocount[d]) add_outlier(oword[d][1]);
+            if (ocount[d] > 8u) {  // more than eight outliers of a row in 256 columns
+              const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)t_cur * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD);
+              for (uint32_t e = 8u + (uint32_t)j; e < ocount[d]; e += 4u) add_outlier(words[ofirst[d] + e]);
+            }
+          }
           MPQ_DQ_STORE_UNIT
         } else {
           MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
@@ -1815,10 +1881,14 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
 #undef MPQ_DQ_STORE_UNIT
 #undef MPQ_DQ_STORE_HALF
 #undef MPQ_DQ_WORD
+#ifdef MPQ_TIMELINE
+      tl_[2] += tl_b - tl_a;
+      tl_[3] += __builtin_amdgcn_s_memrealtime() - tl_b;
+      tl_[11] += 1;
+#endif
     }
-    MPQ_STAMP(2)
   }
-  MPQ_STAMP(3)
+  MPQ_STAMP(4)
   MPQ_TL_NOTE(12, __builtin_amdgcn_s_getreg((31 << 11) | 4))   // HW_ID: where the wave ran
   MPQ_TL_NOTE(13, __builtin_amdgcn_s_getreg((31 << 11) | 20))  // XCC_ID
   MPQ_TL_FLUSH(blockIdx.x, wv, 3, lane)
@@ -1907,6 +1977,8 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
   d->m2_shift = 0;  // g2_axis 0: one pair per row; g2_axis 1: one pair per block of g2 rows
   if (h->g2_axis == 1)
     for (int g = h->g2 < MPQ_TILE_ROWS ? h->g2 : MPQ_TILE_ROWS; g > 1; g >>= 1) ++d->m2_shift;
+  d->off_oidx = (uint32_t)h->oidx_off;
+  d->ocap = (uint32_t)h->ocap;
   d->N = h->N; d->K = h->K; d->G = h->G; d->S = h->S; d->B2 = h->B2; d->C = h->B2 + h->B4; d->T = h->T;
   if (h->tile_stride > 0xFFFFFFFFull) return MPQ_ERR_UNSUPPORTED;
   return MPQ_OK;
@@ -2485,15 +2557,18 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   per_cu = per_cu > 4 ? 4 : per_cu;
   const dim3 grid((unsigned)(per_cu * cus));
   const int dc = (int)((4ll * grid.x) % (h.B2 + h.B4)), dt = (int)((4ll * grid.x) / (h.B2 + h.B4));
-  if (pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else MPQ_LAUNCH((mpq_dequant_kernel<4>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  // The outliers (dense + sparse, Sec. 2.3): a second kernel.  Adding them at the end of the first one, by the
-  // workgroup that wrote the weights, needs workgroups that own tiles and wait for their stores, which costs
-  // more than the second launch (22016 x 4096, 0.5 % outliers: 82 us against 63 us).  What the pass costs is the
-  // memory side's read-modify-write of one 64-byte piece per outlier, not the launch.
-  if (add_outliers && h.nnz > 0) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+  const bool add = add_outliers && h.nnz > 0;
+  const bool in_lds = add && pu == 1 && h.oidx_off != 0;  // the blob has the outlier block index
+  if (in_lds) MPQ_LAUNCH((mpq_dequant_kernel<1, true, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (pu == 1 && !add) MPQ_LAUNCH((mpq_dequant_kernel<1, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else MPQ_LAUNCH((mpq_dequant_kernel<4, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  // Outliers of the other formats (dense + sparse, Sec. 2.3): a second kernel.  Adding them at the end of the
+  // first one, by the workgroup that wrote the weights, needs workgroups that own tiles and wait for their
+  // stores, which costs more than the second launch (22016 x 4096, 0.5 % outliers: 82 us against 63 us).
+  if (add && !in_lds) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   return MPQ_OK;
 }
 

@@ -60,7 +60,12 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
     h->side_bytes = 32ull * (h->G + 1) + mpq_meta2_bytes(h) + MPQ_OTILE_HEAD + 4ull * (uint64_t)ocap;
   }
   h->codes_off = align_up(h->side_bytes, 128);
-  h->tile_stride = align_up(h->codes_off + C * MPQ_BLOCK_BYTES, MPQ_SECTION_ALIGN);
+  uint64_t tile_end = h->codes_off + C * MPQ_BLOCK_BYTES;
+  if (mpq_pu2(d->g1) == 1 && d->meta == MPQ_META_BYTES && ocap > 0 && ocap <= 65535) {
+    h->oidx_off = align_up(tile_end, 64);
+    tile_end = h->oidx_off + 32ull * ((uint64_t)h->B2 + 1);
+  }
+  h->tile_stride = align_up(tile_end, MPQ_SECTION_ALIGN);
   uint64_t off = MPQ_HEADER_BYTES;
   h->off_units = off; off = align_up(off + 8ull * mpq_pu2(d->g1) * 4 * C, MPQ_SECTION_ALIGN);
   h->off_tiles = off; off = align_up(off + (uint64_t)h->T * h->tile_stride, MPQ_SECTION_ALIGN);
@@ -577,6 +582,25 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     uint32_t* words = rec + MPQ_OTILE_HEAD / 4;
     for (int32_t e = base; e < w->row_ptr[nend]; ++e)
       words[e - base] = (uint32_t)w->col[e] | ((uint32_t)w->val[e] << 16);
+    if (h.oidx_off) {
+      // one piece per unit here: the 2-bit block of a column follows from its group's place in the 2-bit stream
+      uint16_t* oidx = (uint16_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + h.oidx_off);
+      const int64_t upg = g1 / 64;  // units per group
+      for (int r = 0; r < MPQ_TILE_ROWS; ++r) {
+        const int64_t n = n0 + r < N ? n0 + r : N;
+        const int64_t n1 = n0 + r + 1 < N ? n0 + r + 1 : N;
+        int32_t e = w->row_ptr[n];
+        for (int64_t c = 0; c <= h.B2; ++c) {
+          while (e < w->row_ptr[n1]) {
+            const int64_t k = w->col[e], g = k / g1;
+            const int64_t blk = ((int64_t)stream_index[g] * upg + (k % g1) / 64) / MPQ_UNITS_PER_BLOCK;
+            if (blk >= c) break;
+            ++e;
+          }
+          oidx[c * MPQ_TILE_ROWS + r] = (uint16_t)((c == h.B2 ? w->row_ptr[n1] : e) - base);
+        }
+      }
+    }
   }
   return MPQ_OK;
 }

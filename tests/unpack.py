@@ -22,7 +22,7 @@ def read_header(blob: np.ndarray) -> dict:
 
 def unpack(blob: np.ndarray) -> dict:
     h = read_header(blob)
-    assert h["version"] == 8
+    assert h["version"] == 9
     N, K, g1, g2, G, S, T = h["N"], h["K"], h["g1"], h["g2"], h["G"], h["S"], h["T"]
     axis = h["g2_axis"]
     B2, B4 = h["B2"], h["B4"]
@@ -50,8 +50,17 @@ def unpack(blob: np.ndarray) -> dict:
     assert h["U4"] == (h["n4"] * (g1 // 32) if g1 >= 32 else -(-h["n4"] // PU4))
     units = blob[h["off_units"]: h["off_units"] + 32 * PU2 * C].view(np.uint32).reshape(4 * C, PU2, 2)
     tiles = blob[h["off_tiles"]: h["off_tiles"] + T * h["tile_stride"]].reshape(T, h["tile_stride"])
-    # gaps inside a tile record are zero
-    assert not tiles[:, h["side_bytes"]: h["codes_off"]].any() and not tiles[:, h["codes_off"] + C * 1024:].any()
+    # gaps inside a tile record are zero; the outlier block index (r1 = its offset, 0 = none) follows the codes
+    oidx_off, codes_end = h["r1"], h["codes_off"] + C * 1024
+    want_index = PU2 == 1 and not paper and 0 < h["ocap"] <= 65535
+    assert (oidx_off != 0) == want_index
+    assert not tiles[:, h["side_bytes"]: h["codes_off"]].any()
+    if oidx_off:
+        assert oidx_off % 64 == 0 and codes_end <= oidx_off < codes_end + 64
+        assert h["tile_stride"] == -(-(oidx_off + 32 * (B2 + 1)) // 256) * 256
+        assert not tiles[:, codes_end: oidx_off].any() and not tiles[:, oidx_off + 32 * (B2 + 1):].any()
+    else:
+        assert h["tile_stride"] == -(-codes_end // 256) * 256 and not tiles[:, codes_end:].any()
     cw = np.ascontiguousarray(tiles[:, h["codes_off"]: h["codes_off"] + C * 1024]).view(np.uint32).reshape(T, C, 4, 16, 4)
     codes = np.zeros((T * TILE, K), dtype=np.uint8)
     is4 = np.full(G, 255, dtype=np.uint8)
@@ -217,6 +226,25 @@ def unpack(blob: np.ndarray) -> dict:
                 assert start[r + 1] == start[r]                         # rows beyond N are empty
         words.append(recs[t, 32: 32 + cnt])
     assert h["ocap"] == -(-fullest // 32) * 32
+    if oidx_off:
+        # entry [c][r]: how many words of the tile come before the first word of row r that lies in 2-bit block c
+        # or later = words of earlier rows + words of row r in blocks < c (brute force over the unit table)
+        oidx = np.ascontiguousarray(tiles[:, oidx_off: oidx_off + 32 * (B2 + 1)]).view(np.uint16).reshape(T, B2 + 1, TILE)
+        block_of_col = np.full(K, -1, dtype=np.int64)
+        for u in range(4 * B2):
+            e, e1 = int(units[u, 0, 0]), int(units[u, 0, 1])
+            if (e1 & 0xFFFF) != 32 * G:
+                block_of_col[e // 2: e // 2 + 64] = u // 4
+        for t in range(T):
+            start = recs[t, :17].astype(np.int64)
+            cols = (recs[t, 32: 32 + int(start[16])] & 0xFFFF).astype(np.int64)
+            assert np.all(block_of_col[cols] >= 0)                      # outliers only in 2-bit groups
+            for r in range(TILE):
+                blk = block_of_col[cols[start[r]: start[r + 1]]]
+                assert np.all(np.diff(blk) >= 0)                        # K order = block order inside a row
+                for c in range(B2 + 1):
+                    want = start[r + 1] if c == B2 else start[r] + int(np.sum(blk < c))
+                    assert oidx[t, c, r] == want, (t, c, r, oidx[t, c, r], want)
     outl = np.concatenate(words) if words else np.zeros(0, np.uint32)
     assert outl.size == h["nnz"]
     return dict(h=h, is4=is4, codes=codes[:N], s_int=s_int[:N], z1=z1[:N], s2=s2, z2=z2,

@@ -10,8 +10,12 @@ one launch per repetition and prints, per shape and phase, the median and the 5 
 workgroups and repetitions, in microseconds after the first wave of the launch started.
 
   python timeline.py [--config 1|3|4] [--path 0|1|2] [--waves W] [--tiles n] [--reps 40]
+  python timeline.py --dequant 0|1 [--config 1|3|4]
 
 --path: 0 = the library's choice per shape, 1 = plane-sum kernel, 2 = per-weight kernel.
+--dequant: the dequantization kernel instead (0 = dense part, 1 = with the outliers): per wave, the time it
+spends issuing its batches' requests, waiting for a block's words, and decoding, turning and storing; when
+the waves end, by how many workgroups shared their compute unit.
 """
 import argparse
 import ctypes as C
@@ -38,6 +42,7 @@ def main():
     ap.add_argument("--reps", type=int, default=40)
     ap.add_argument("--waves", type=int, default=0, help="waves per workgroup (0 = the library's choice)")
     ap.add_argument("--tiles", type=int, default=0, help="tiles per workgroup (0 = the library's choice)")
+    ap.add_argument("--dequant", type=int, default=None, choices=[0, 1])
     args = ap.parse_args()
     import torch
     import mpq_synth as synth
@@ -51,6 +56,8 @@ def main():
                                    C.POINTER(mpq.Plan), C.POINTER(mpq.Report)]
     L.mpq_timeline_buffer.restype = C.c_int
     L.mpq_timeline_buffer.argtypes = [C.c_void_p]
+    if args.dequant is not None:
+        return dequant_timeline(args, torch, synth, mpq, L)
     shapes = []
     for spec in synth.config_specs(args.config):
         if spec.name == "lm_head":
@@ -111,6 +118,48 @@ def main():
                 if np.all(np.isnan(col)):
                     continue
                 print(f"    {nm:24s} {np.nanmedian(col):6.2f}  [{np.nanpercentile(col, 5):5.2f} .. {np.nanpercentile(col, 95):5.2f}]")
+
+
+def dequant_timeline(args, torch, synth, mpq, L):
+    L.mpq_dequant.restype = C.c_int
+    L.mpq_dequant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+    us = lambda ticks: ticks / 100.0
+    print(f"# config {args.config}, mpq_dequant with add_outliers = {args.dequant}: stamps of the first and the last wave of every workgroup,")
+    print("# one launch after three others on rotating copies of blob and output; microseconds")
+    for spec in synth.config_specs(args.config):
+        if spec.name == "lm_head":
+            continue
+        pk = mpq.pack_logical(synth.make_matrix(spec))
+        hdr = np.ascontiguousarray(pk.header)
+        blobs = [torch.from_numpy(pk.blob).cuda() for _ in range(4)]
+        outs = [torch.empty(spec.N * spec.K, dtype=torch.int16, device="cuda") for _ in range(4)]
+        buf = torch.zeros(4096 * 2 * 16, dtype=torch.int64, device="cuda")
+        for rnd in range(2):
+            for i in range(4):
+                if rnd == 1 and i == 3:
+                    torch.cuda.synchronize()
+                    assert L.mpq_timeline_buffer(buf.data_ptr()) == 0
+                assert L.mpq_dequant(hdr.ctypes.data, blobs[i].data_ptr(), outs[i].data_ptr(), args.dequant, None) == 0
+        torch.cuda.synchronize()
+        assert L.mpq_timeline_buffer(None) == 0
+        a = buf.cpu().numpy().reshape(-1, 16)
+        a = a[a[:, 11] > 0]
+        t0 = a[:, 0].min()
+        end = us(a[:, 4] - t0)
+        print(f"\n{spec.name} {spec.N}x{spec.K}: {len(a)} waves recorded, {a[:, 11].min()} to {a[:, 11].max()} blocks each; "
+              f"start median {us(np.median(a[:, 0] - t0)):.2f} max {us((a[:, 0] - t0).max()):.2f}; "
+              f"end median {np.median(end):.2f}, 5 % {np.percentile(end, 5):.2f}, 95 % {np.percentile(end, 95):.2f}, max {end.max():.2f}")
+        for k, name in ((1, "issuing the batches' requests"), (2, "waiting for blocks' words"), (3, "decode, turn, stores")):
+            tot = us(a[:, k])
+            print(f"  {name:32s} per wave: median {np.median(tot):6.2f}  [5 % {np.percentile(tot, 5):6.2f} .. 95 % {np.percentile(tot, 95):6.2f}]"
+                  f"   per block {np.median(us(a[:, k]) / a[:, 11]):.2f}")
+        # where the waves ran (HW_ID: compute unit bits 8-11, shader array bit 12, shader engine bits 13-15; XCC_ID bits 0-3)
+        hw, xcc = a[:, 12], a[:, 13] & 0xF
+        cu = xcc * 1000 + ((hw >> 13) & 7) * 100 + ((hw >> 12) & 1) * 50 + ((hw >> 8) & 0xF)
+        ids, cnt = np.unique(cu, return_counts=True)
+        for n in np.unique(cnt):
+            sel = np.isin(cu, ids[cnt == n])
+            print(f"  {np.sum(cnt == n):3d} compute units with {n // 2} workgroups: their waves end at median {np.median(end[sel]):.2f}, max {end[sel].max():.2f}")
 
 
 if __name__ == "__main__":
