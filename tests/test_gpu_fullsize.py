@@ -68,16 +68,19 @@ def check_dequant_rows(torch, lg, pk, blob):
     s = lg.spec
     if s.N * s.K > 550e6:      # keep the fp16 output near 1 GB at most (the largest matrix of the benchmark is 470e6 weights)
         return
-    rows = sample_rows(s.N, 48, s.seed + 7)
-    out = Guarded(torch, s.N * s.K)
-    mpq.dequant(pk.header, blob, out.view, add_outliers=True)
-    torch.cuda.synchronize()
-    got = out.buf[128:128 + s.N * s.K].view(s.N, s.K)[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16)
-    host_head = out.buf[:128].cpu().numpy().view(np.uint16)
-    host_tail = out.buf[128 + s.N * s.K:].cpu().numpy().view(np.uint16)
-    assert np.all(host_head == 0x7B7B) and np.all(host_tail == 0x7B7B)
-    ref = sub_matrix(lg, rows).dequant(True)
-    assert np.array_equal(got, ref), s.name
+    # every row where the oracle needs a few seconds (the Llama2-7B shapes), 48 sampled rows of larger matrices
+    rows = np.arange(s.N) if s.N * s.K <= 100e6 else sample_rows(s.N, 48, s.seed + 7)
+    sub = sub_matrix(lg, rows)
+    for add in ((True, False) if rows.size == s.N else (True,)):   # the dense part alone takes other stores
+        out = Guarded(torch, s.N * s.K)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+        torch.cuda.synchronize()
+        got = out.buf[128:128 + s.N * s.K].view(s.N, s.K)[torch.from_numpy(rows).cuda()].cpu().numpy().view(np.uint16)
+        host_head = out.buf[:128].cpu().numpy().view(np.uint16)
+        host_tail = out.buf[128 + s.N * s.K:].cpu().numpy().view(np.uint16)
+        assert np.all(host_head == 0x7B7B) and np.all(host_tail == 0x7B7B)
+        assert np.array_equal(got, sub.dequant(add)), (s.name, add)
+        del out, got
 
 
 @pytest.mark.parametrize("idx", [0, 1, 2, 3])
