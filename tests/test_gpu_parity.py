@@ -68,6 +68,19 @@ def test_dequant_bit_exact(torch, case):
         assert bad.size == 0, (add, bad[:5], got[tuple(bad[0])], ref[tuple(bad[0])])
 
 
+def test_dequant_with_a_unit_table_too_long_to_stage(torch):
+    # K = 40960: 142 blocks per tile, a unit table of 4.4 KiB, which the kernel reads from memory instead of LDS
+    case = ("longest", 48, 40960, 64, 16, 0.10, 0.01, False)
+    lg, om, pk = make(case)
+    assert 32 * (pk.header.view(np.int32)[13] + pk.header.view(np.int32)[14]) > 4096   # B2 + B4 blocks, 32 bytes of table each
+    blob = to_dev(torch, pk.blob)
+    for add in (False, True):
+        out = Guarded(torch, pk.N * pk.K)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+        got = out.check_and_get().reshape(pk.N, pk.K)
+        assert np.array_equal(got, om.dequant(add)), add
+
+
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_gemv_within_tolerance(torch, case):
     lg, om, pk = make(case)
