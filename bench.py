@@ -365,7 +365,7 @@ def main():
                     f"{m['spec'].name} {k}" for m, k in zip(layer.mats, kernel_names)) + ")" if not args.multi else kernel_names[0],
                 "avg_launch_us": round(avg_launch_us, 3), "bytes_per_launch": round(bytes_per_launch)}
     default_workload = (args.config == 1 and M == 1 and not over and not args.multi and not args.token
-                        and args.f4 is None and args.p_o is None)
+                        and args.f4 is None and args.p_o is None and args.dequant is None)
     if default_workload and os.path.exists(os.path.join(ROOT, TRAFFIC_FILE)):
         try:
             roofline["traffic"] = json.load(open(os.path.join(ROOT, TRAFFIC_FILE))).get("hbm_bytes_per_launch")
