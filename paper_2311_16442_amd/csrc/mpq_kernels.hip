@@ -613,10 +613,13 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   unsigned char* const xbuf = lds + pl.off_xbuf;
   const DecodeConsts kc = make_consts();
 
+  MPQ_TL_DECL
+  MPQ_STAMP(0)
   // ---- once per workgroup: unit table
   dma_linear<W>(b.units, lds_addr(units), 32u * PU * C, wv, lane16);
   MPQ_VMCNT(0);
   lds_barrier();
+  MPQ_STAMP(1)
 
   // ---- the activations of the range: every lane fills one 16-byte slot per request
   {
@@ -643,6 +646,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
     }
   }
 
+  MPQ_STAMP(9)
   // ---- requests of code blocks: the enumeration (group, tile, block of the range) that the
   //      consumption below follows, restricted to every W-th block
   const uint32_t ring0 = lds_addr(lds) + wv * (PD * SLOTB);
@@ -700,9 +704,12 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #pragma unroll
   for (uint32_t r = 0; r < PD; ++r)
     if (r_g < ngroups) MPQ_S_REQUEST(r)
+  MPQ_STAMP(2)
   // the activations were requested first: they have landed when at most the block requests are left
   wait_vm((int)(OPS * inflight));
+  MPQ_STAMP(3)
   lds_barrier();
+  MPQ_STAMP(4)
 
   // ---- this workgroup's share of the transposed activations XT[k][XR] that the second kernel
   //      gathers for the outliers: the bands of a range take the range's slots in turn
@@ -732,6 +739,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
     }
   }
 
+  MPQ_STAMP(5)
   const uint32_t slot_lane = ring0 + lane16, meta_lane = ring0 + 1024u + lane * 4u;
   const unsigned char* xb2 = xbuf + j * (8u * XR * 16u) + (i % XR) * 16u;                        // + block * 512 * XR + step * 16 * XR
   const unsigned char* xb4 = xbuf + n2 * (512u * XR) + j * (4u * XR * 16u) + (i % XR) * 16u;      // + block * 256 * XR + step * 16 * XR
@@ -818,6 +826,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
       ++c;
     }
 
+    MPQ_STAMP(6)
     // ---- park the accumulators (lane l holds Y[m = l % 16 (+16)][rows 4*(l/16) .. +3] of a tile), TP
     //      tiles at a time: [wave][tile of the step][batch half][m][row]; then every output of those
     //      tiles is summed over the waves in a fixed order
@@ -825,6 +834,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
     for (uint32_t st = 0; st < RMAX / TP; ++st) {
       if (st * TP >= Rn) break;
       lds_barrier();  // everybody is done reading what was parked before
+      if (st == 0) { MPQ_STAMP(8) }
       float* park = park0 + wv * (TP * NT * 256u) + i * 16u + 4u * j;
       if (NT == 1) {
         *(float4_t*)(park) = acc[st * TP][0];
@@ -846,6 +856,8 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
       }
     }
   }
+  MPQ_STAMP(7)
+  MPQ_TL_FLUSH(blockIdx.x, wv, W - 1, lane)
 #undef MPQ_S_HEAD
 #undef MPQ_S_STEP
 #undef MPQ_S_REQUEST
@@ -864,6 +876,8 @@ __global__ void __launch_bounds__(256)
 mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const float* __restrict__ P,
                       uint16_t* __restrict__ Y, const int M, const int H, const uint32_t ocap) {
 #pragma clang fp contract(off)
+  MPQ_TL_DECL
+  MPQ_STAMP(8)
   constexpr uint32_t WCAP = 2048;      // outlier words of the tile kept in LDS (the rest is read from memory)
   __shared__ float osum[MP][16];       // [batch column][row]
   __shared__ uint32_t wlds[WCAP];
@@ -890,6 +904,7 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
     pfirst[nt][1] = hi4 + 16u * nt < (uint32_t)M && H > 1 ? p[nt * 256u + hs] : 0.f;
   }
   __syncthreads();
+  MPQ_STAMP(9)
   {
     const uint32_t row = hi4, q = lo4;
     float acc[MP];
@@ -936,6 +951,7 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
       if (q == 15) osum[m][row] = oa;
     }
   }
+  MPQ_STAMP(10)
   __syncthreads();
   const uint32_t m = hi4, row = lo4, grow = tile * 16u + row;
 #pragma unroll
@@ -954,6 +970,9 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
     for (; hh < (uint32_t)H; ++hh) sum += pn[hh * hs];
     if (grow < (uint32_t)b.N) Y[(size_t)gm * b.N + grow] = half_to_bits((half_t)sum);
   }
+  MPQ_STAMP(12)
+  // stamps of the second kernel: after those of 4096 workgroups of the first
+  MPQ_TL_FLUSH(4096u + blockIdx.x, threadIdx.x >> 6, 3u, threadIdx.x & 63u)
 }
 
 // ------------------------------------------------------------------------------------ GEMV

@@ -11,8 +11,12 @@ workgroups and repetitions, in microseconds after the first wave of the launch s
 
   python timeline.py [--config 1|3|4] [--path 0|1|2] [--waves W] [--tiles n] [--reps 40]
   python timeline.py --dequant 0|1 [--config 1|3|4]
+  python timeline.py --batch M [--config 1|3|4]
 
 --path: 0 = the library's choice per shape, 1 = plane-sum kernel, 2 = per-weight kernel.
+--batch: the two kernels of the K-range batch path (shapes that the library routes there at that M): when the
+unit table, the gathered activations and the first block are there, when the blocks are done, when the partial sums
+are written; and the phases of the second kernel (outlier product, sum over the ranges).
 --dequant: the dequantization kernel instead (0 = dense part, 1 = with the outliers): per wave, the time it
 spends issuing its batches' requests, waiting for a block's words, and decoding, turning and storing; when
 the waves end, by how many workgroups shared their compute unit.
@@ -43,6 +47,7 @@ def main():
     ap.add_argument("--waves", type=int, default=0, help="waves per workgroup (0 = the library's choice)")
     ap.add_argument("--tiles", type=int, default=0, help="tiles per workgroup (0 = the library's choice)")
     ap.add_argument("--dequant", type=int, default=None, choices=[0, 1])
+    ap.add_argument("--batch", type=int, default=None)
     args = ap.parse_args()
     import torch
     import mpq_synth as synth
@@ -58,6 +63,8 @@ def main():
     L.mpq_timeline_buffer.argtypes = [C.c_void_p]
     if args.dequant is not None:
         return dequant_timeline(args, torch, synth, mpq, L)
+    if args.batch is not None:
+        return batch_timeline(args, torch, synth, mpq, L)
     shapes = []
     for spec in synth.config_specs(args.config):
         if spec.name == "lm_head":
@@ -118,6 +125,59 @@ def main():
                 if np.all(np.isnan(col)):
                     continue
                 print(f"    {nm:24s} {np.nanmedian(col):6.2f}  [{np.nanpercentile(col, 5):5.2f} .. {np.nanpercentile(col, 95):5.2f}]")
+
+
+def batch_timeline(args, torch, synth, mpq, L):
+    M = args.batch
+    L.mpq_gemm_workspace_size.restype = C.c_int
+    L.mpq_gemm_workspace_size.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_size_t)]
+    us = lambda ticks: ticks / 100.0
+    first = ["start", "unit table there", "requests issued", "own gather landed", "barrier: activations there",
+             "transposed activations written", "blocks done (last group)", "partial sums written", "all waves' blocks done (last group)", "gather requests issued"]
+    print(f"# config {args.config}, batch {M}: K-range kernel (first and last wave of every workgroup) and its second kernel;")
+    print("# microseconds after the first wave of the first kernel started; median [5 % .. 95 %]")
+    for spec in synth.config_specs(args.config):
+        if spec.name == "lm_head":
+            continue
+        pk = mpq.pack_logical(synth.make_matrix(spec))
+        hdr = np.ascontiguousarray(pk.header)
+        blobs = [torch.from_numpy(pk.blob).cuda() for _ in range(4)]
+        X = torch.from_numpy(synth.make_x(1, M, spec.K).view(np.int16).copy()).cuda()
+        Y = torch.zeros(M * spec.N, dtype=torch.int16, device="cuda")
+        need = C.c_size_t(0)
+        assert L.mpq_gemm_workspace_size(hdr.ctypes.data, M, C.byref(need)) == 0
+        ws = torch.empty(max(256, need.value), dtype=torch.uint8, device="cuda")
+        rep = mpq.Report()
+        buf = torch.zeros(8192 * 2 * 16, dtype=torch.int64, device="cuda")
+        for rnd in range(2):
+            for i in range(4):
+                if rnd == 1 and i == 3:
+                    torch.cuda.synchronize()
+                    assert L.mpq_timeline_buffer(buf.data_ptr()) == 0
+                st = L.mpq_gemm_planned(hdr.ctypes.data, blobs[i].data_ptr(), X.data_ptr(), Y.data_ptr(), M, ws.data_ptr(), ws.numel(),
+                                        None, None, C.byref(rep))
+                assert st == 0, st
+        torch.cuda.synchronize()
+        assert L.mpq_timeline_buffer(None) == 0
+        if rep.kernel != 4:
+            print(f"\n{spec.name} {spec.N}x{spec.K}: not routed to the K-range kernel at this batch size")
+            continue
+        a = buf.cpu().numpy().reshape(-1, 16).astype(np.float64)
+        k1, k2 = a[: 2 * 4096], a[2 * 4096:]
+        n1 = int(rep.workgroups)
+        k1, k2 = k1[: 2 * n1], k2[k2[:, 8] > 0]
+        t0 = k1[:, 0].min()
+        print(f"\n{spec.name} {spec.N}x{spec.K}: {rep.workgroups} workgroups of {rep.waves} waves; first kernel ends {us(k1[:, 7].max() - t0):.2f}, "
+              f"second kernel starts {us(k2[:, 8].min() - t0):.2f} and ends {us(k2[:, 12].max() - t0):.2f}")
+        w_first, w_last = k1[0::2], k1[1::2]   # records alternate: first wave, last wave of a workgroup
+        for k, nm in enumerate(first):
+            ca, cb = us(w_first[:, k] - t0), us(w_last[:, k] - t0)
+            print(f"    {nm:32s} first wave {np.median(ca):6.2f}  [{np.percentile(ca, 5):5.2f} .. {np.percentile(ca, 95):5.2f}]"
+                  f"   last wave {np.median(cb):6.2f}  [{np.percentile(cb, 5):5.2f} .. {np.percentile(cb, 95):5.2f}]")
+        t2 = k2[:, 8].min()
+        for k, nm in ((8, "second kernel: start"), (9, "words, row starts, first sums there"), (10, "outlier product done"), (12, "end")):
+            col = us(k2[:, k] - t2)
+            print(f"    {nm:32s} {np.median(col):6.2f}  [{np.percentile(col, 5):5.2f} .. {np.percentile(col, 95):5.2f}]   (after the second kernel's first wave)")
 
 
 def dequant_timeline(args, torch, synth, mpq, L):
