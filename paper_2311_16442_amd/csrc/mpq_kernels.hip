@@ -897,11 +897,13 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
   }
   const float* p = P + (size_t)tile * (NT * 256u) + threadIdx.x;  // + nt * 256 + range * hs
   const size_t hs = (size_t)b.T * (NT * 256u);
-  float pfirst[NT][2];
+  constexpr uint32_t PF = 6;  // partial sums requested up front (more ranges than that: the rest after the outliers)
+  float pfirst[NT][PF];
 #pragma unroll
   for (uint32_t nt = 0; nt < NT; ++nt) {
-    pfirst[nt][0] = hi4 + 16u * nt < (uint32_t)M ? p[nt * 256u] : 0.f;
-    pfirst[nt][1] = hi4 + 16u * nt < (uint32_t)M && H > 1 ? p[nt * 256u + hs] : 0.f;
+#pragma unroll
+    for (uint32_t hh = 0; hh < PF; ++hh)
+      pfirst[nt][hh] = hi4 + 16u * nt < (uint32_t)M && hh < (uint32_t)H ? p[nt * 256u + hh * hs] : 0.f;
   }
   __syncthreads();
   MPQ_STAMP(9)
@@ -959,10 +961,11 @@ mpq_mms_finish_kernel(const DevBlob b, const uint16_t* __restrict__ XT, const fl
     const uint32_t gm = m + 16u * nt;
     if (gm >= (uint32_t)M) continue;
     float sum = osum[gm % MP][row];
-    sum += pfirst[nt][0];
-    if (H > 1) sum += pfirst[nt][1];
+#pragma unroll
+    for (uint32_t hh = 0; hh < PF; ++hh)
+      if (hh < (uint32_t)H) sum += pfirst[nt][hh];
     const float* pn = p + nt * 256u;
-    uint32_t hh = 2;
+    uint32_t hh = PF;
     for (; hh + 4 <= (uint32_t)H; hh += 4) {  // four loads in flight, added in order
       const float p0 = pn[hh * hs], p1 = pn[(hh + 1) * hs], p2 = pn[(hh + 2) * hs], p3 = pn[(hh + 3) * hs];
       sum += p0; sum += p1; sum += p2; sum += p3;
