@@ -46,7 +46,7 @@
 //                                 row pointer: no dependent load.
 //       codes at codes_off (128-byte aligned): (B2 + B4) x 64 x 16 B, the 2-bit blocks then the 4-bit
 //                                 blocks of the tile, [block][lane] 16-byte units
-//       oidx at oidx_off (64-byte aligned; only for g1 >= 64, byte metadata, 0 < ocap <= 65535):
+//       oidx at oidx_off (64-byte aligned; only for 0 < ocap <= 65535):
 //                                 uint16 [B2 + 1][16]: entry [c][r] = index, among the tile's outlier words, of
 //                                 the first word of row r whose column lies in 2-bit block c or a later one
 //                                 ([B2][r] = end of row r).  The 2-bit stream is in K order and outliers live

@@ -1731,7 +1731,6 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
   const int waves = 4 * (int)gridDim.x, w0 = (int)blockIdx.x * 4 + wv;
   int t_pre = w0 / C, c_pre = w0 - t_pre * C;  // walks ahead of the blocks being decoded; stays on the wave's last block
   int left = t_pre < T ? (int)(((long long)T * C - w0 + waves - 1) / waves) : 0;
-  static_assert(!ADD || (PU == 1 && !AL), "outliers are added in LDS only where a lane's area holds its whole unit");
   uint4 qs[D];
   uint32_t m1s[D][PU], m2s[D][PU];
   uint2 es[D][PU];
@@ -1774,13 +1773,16 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
           m1s[d][q_] = *(const uint16_t*)(side + (m1_lane + (es[d][q_].y & 0xFFFFu)));
           m2s[d][q_] = *(const uint32_t*)(side + (m2_lane + (es[d][q_].y >> 16)));
         }
-        if constexpr (ADD) {
-          const uint32_t* words = (const uint32_t*)(side + b.off_ot + MPQ_OTILE_HEAD);
-          ocount[d] = cs[d] < b.B2 ? ocount[d] - ofirst[d] : 0u;
-          const uint32_t w0 = ofirst[d] + (uint32_t)j, w1 = w0 + 4u;
-          oword[d][0] = words[w0 < b.ocap ? w0 : 0u];
-          oword[d][1] = words[w1 < b.ocap ? w1 : 0u];
-        }
+      }
+    }
+    if constexpr (ADD) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)ts[d] * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD);
+        ocount[d] = cs[d] < b.B2 ? ocount[d] - ofirst[d] : 0u;
+        const uint32_t w0 = ofirst[d] + (uint32_t)j, w1 = w0 + 4u;
+        oword[d][0] = words[w0 < b.ocap ? w0 : 0u];
+        oword[d][1] = words[w1 < b.ocap ? w1 : 0u];
       }
     }
 #ifdef MPQ_TIMELINE
@@ -1857,6 +1859,55 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
     constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                  \
     dst[(P) & 3] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                            \
   }
+      // outliers of a block whose units are several pieces: where a word's weight lies while its half is in LDS
+      // (half << 16 | byte offset in the wave's area).  The pieces are compared in block order from the back, so
+      // that the first match stays: padding pieces (offset 0) come after the real ones, and every word of the
+      // block lies in a real one.
+      constexpr uint32_t NOWHERE = 0xFFFF0000u;
+      constexpr uint32_t PB = 128u / PU;  // bytes of a piece in a row
+      uint32_t px[4][PU];
+      if constexpr (ADD && !WHOLE) {
+#pragma unroll
+        for (int u_ = 0; u_ < 4; ++u_) {
+#pragma unroll
+          for (int q_ = 0; q_ < PU; ++q_) px[u_][q_] = MPQ_DQ_WORD(q_, x, u_);
+        }
+      }
+      auto place = [&](const uint32_t word) {
+        const uint32_t at = 2u * (word & 0xFFFFu);
+        uint32_t r = NOWHERE;
+#pragma unroll
+        for (int u_ = 3; u_ >= 0; --u_) {
+#pragma unroll
+          for (int q_ = PU - 1; q_ >= 0; --q_) {
+            const uint32_t dq = at - px[u_][q_];
+            constexpr int HP = PU > 1 ? PU / 2 : 1;  // pieces per half
+            if (dq < PB) r = ((uint32_t)(q_ / HP) << 16) | (((uint32_t)u_ * 16u + (uint32_t)i) * PAIR + (uint32_t)(q_ % HP) * PB + dq);
+          }
+        }
+        return r;
+      };
+      auto add_at = [&](const uint32_t where, const uint32_t word) {
+        uint16_t* w16 = (uint16_t*)(mine + (where & 0xFFFFu));
+        *w16 = half_to_bits(bits_to_half(*w16) + bits_to_half((uint16_t)(word >> 16)));
+      };
+      uint32_t opl0 = NOWHERE, opl1 = NOWHERE;
+      if constexpr (ADD && !WHOLE) {
+        if ((uint32_t)j < ocount[d]) opl0 = place(oword[d][0]);
+        if ((uint32_t)j + 4u < ocount[d]) opl1 = place(oword[d][1]);
+      }
+#define MPQ_DQ_ADD_HALF(HALF)                                                                             \
+  if constexpr (ADD) {                                                                                    \
+    if ((opl0 >> 16) == (HALF)) add_at(opl0, oword[d][0]);                                                \
+    if ((opl1 >> 16) == (HALF)) add_at(opl1, oword[d][1]);                                                \
+    if (ocount[d] > 8u) { /* more than eight outliers of a row in the block's columns */                  \
+      const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)t_cur * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD); \
+      for (uint32_t e = 8u + (uint32_t)j; e < ocount[d]; e += 4u) {                                       \
+        const uint32_t word = words[ofirst[d] + e], where = place(word);                                  \
+        if ((where >> 16) == (HALF)) add_at(where, word);                                                 \
+      }                                                                                                   \
+    }                                                                                                     \
+  }
       if (two) {
         MPQ_DQ_PIECES(PU, false)
         const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
@@ -1887,8 +1938,10 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
           MPQ_DQ_STORE_UNIT
         } else {
           MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
+          MPQ_DQ_ADD_HALF(0)
           MPQ_DQ_STORE_HALF(0, 8 / PU)
           MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
+          MPQ_DQ_ADD_HALF(1)
           MPQ_DQ_STORE_HALF(1, 8 / PU)
         }
       } else {
@@ -1897,6 +1950,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
         MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
         MPQ_DQ_STORE_HALF(0, 4 / PU4)
       }
+#undef MPQ_DQ_ADD_HALF
 #undef MPQ_DQ_STEP
 #undef MPQ_DQ_STEP8
 #undef MPQ_DQ_PIECES
@@ -2580,8 +2634,11 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   const dim3 grid((unsigned)(per_cu * cus));
   const int dc = (int)((4ll * grid.x) % (h.B2 + h.B4)), dt = (int)((4ll * grid.x) / (h.B2 + h.B4));
   const bool add = add_outliers && h.nnz > 0;
-  const bool in_lds = add && pu == 1 && h.oidx_off != 0;  // the blob has the outlier block index
-  if (in_lds) MPQ_LAUNCH((mpq_dequant_kernel<1, true, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  const bool in_lds = add && h.oidx_off != 0;  // the blob has the outlier block index
+  if (in_lds && pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1, true, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (in_lds && pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2, false, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (in_lds && h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, false, true, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
+  else if (in_lds) MPQ_LAUNCH((mpq_dequant_kernel<4, false, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
   else if (pu == 1 && !add) MPQ_LAUNCH((mpq_dequant_kernel<1, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
   else if (pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
   else if (pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);

@@ -61,7 +61,7 @@ mpq_status plan(const mpq_desc* d, int32_t n4, int64_t nnz, int64_t ocap, MpqHea
   }
   h->codes_off = align_up(h->side_bytes, 128);
   uint64_t tile_end = h->codes_off + C * MPQ_BLOCK_BYTES;
-  if (mpq_pu2(d->g1) == 1 && d->meta == MPQ_META_BYTES && ocap > 0 && ocap <= 65535) {
+  if (ocap > 0 && ocap <= 65535) {
     h->oidx_off = align_up(tile_end, 64);
     tile_end = h->oidx_off + 32ull * ((uint64_t)h->B2 + 1);
   }
@@ -583,9 +583,10 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
     for (int32_t e = base; e < w->row_ptr[nend]; ++e)
       words[e - base] = (uint32_t)w->col[e] | ((uint32_t)w->val[e] << 16);
     if (h.oidx_off) {
-      // one piece per unit here: the 2-bit block of a column follows from its group's place in the 2-bit stream
+      // the 2-bit block of a column follows from its group's place in the 2-bit stream: g1 / 64 units per group, or
+      // PU2 groups per unit
       uint16_t* oidx = (uint16_t*)(blob + h.off_tiles + (uint64_t)t * h.tile_stride + h.oidx_off);
-      const int64_t upg = g1 / 64;  // units per group
+      const int64_t upg = g1 / 64;
       for (int r = 0; r < MPQ_TILE_ROWS; ++r) {
         const int64_t n = n0 + r < N ? n0 + r : N;
         const int64_t n1 = n0 + r + 1 < N ? n0 + r + 1 : N;
@@ -593,7 +594,8 @@ mpq_status mpq_pack_host(const mpq_desc* d, const mpq_logical* w, void* blob_hos
         for (int64_t c = 0; c <= h.B2; ++c) {
           while (e < w->row_ptr[n1]) {
             const int64_t k = w->col[e], g = k / g1;
-            const int64_t blk = ((int64_t)stream_index[g] * upg + (k % g1) / 64) / MPQ_UNITS_PER_BLOCK;
+            const int64_t unit = g1 >= 64 ? (int64_t)stream_index[g] * upg + (k % g1) / 64 : (int64_t)stream_index[g] / PU2;
+            const int64_t blk = unit / MPQ_UNITS_PER_BLOCK;
             if (blk >= c) break;
             ++e;
           }

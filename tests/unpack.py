@@ -52,7 +52,7 @@ def unpack(blob: np.ndarray) -> dict:
     tiles = blob[h["off_tiles"]: h["off_tiles"] + T * h["tile_stride"]].reshape(T, h["tile_stride"])
     # gaps inside a tile record are zero; the outlier block index (r1 = its offset, 0 = none) follows the codes
     oidx_off, codes_end = h["r1"], h["codes_off"] + C * 1024
-    want_index = PU2 == 1 and not paper and 0 < h["ocap"] <= 65535
+    want_index = 0 < h["ocap"] <= 65535
     assert (oidx_off != 0) == want_index
     assert not tiles[:, h["side_bytes"]: h["codes_off"]].any()
     if oidx_off:
@@ -231,10 +231,12 @@ def unpack(blob: np.ndarray) -> dict:
         # or later = words of earlier rows + words of row r in blocks < c (brute force over the unit table)
         oidx = np.ascontiguousarray(tiles[:, oidx_off: oidx_off + 32 * (B2 + 1)]).view(np.uint16).reshape(T, B2 + 1, TILE)
         block_of_col = np.full(K, -1, dtype=np.int64)
+        pad_word = (32 * T3) if paper else 32 * G        # what word 1 of a padding 2-bit piece holds in bits 0-15
         for u in range(4 * B2):
-            e, e1 = int(units[u, 0, 0]), int(units[u, 0, 1])
-            if (e1 & 0xFFFF) != 32 * G:
-                block_of_col[e // 2: e // 2 + 64] = u // 4
+            for q in range(PU2):
+                e, e1 = int(units[u, q, 0]), int(units[u, q, 1])
+                if (e1 & 0xFFFF) != pad_word:
+                    block_of_col[e // 2: e // 2 + 64 // PU2] = u // 4
         for t in range(T):
             start = recs[t, :17].astype(np.int64)
             cols = (recs[t, 32: 32 + int(start[16])] & 0xFFFF).astype(np.int64)
