@@ -6,7 +6,7 @@
 //   mpq_mm_kernel        the same product for a batch of 2..32 activation rows that fit the LDS.
 //   mpq_mms_kernel       the same for batches that do not: one K-range of the activations resident
 //                        per workgroup, partial sums added up by mpq_mms_finish_kernel.
-//   mpq_dequant_kernel   eq. 5 applied twice (scale, then weight), written out as row-major fp16.
+//   mpq_dequant_kernel, mpq_dequant_lines_kernel   eq. 5 applied twice (scale, then weight), written out as row-major fp16.
 //   mpq_outlier_add_kernel  adds the CSR values to a dequantized matrix (dense + sparse, Sec. 2.3).
 //
 // Mapping shared by the kernels.  A wavefront load of 1 KiB is one block: lane = j*16 + i holds the
@@ -1669,9 +1669,10 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 //
 // Row-major fp16 copy of the dense part: W_out[n][k] = fp16((code - z1) * s1), bit-exact eq. 5.
 // A lane decodes its unit (64 or 32 columns of one row); the wave turns the decoded bytes through a small
-// LDS area so that neighbouring lanes write contiguous bytes: eight lanes the whole 128-byte line of a
-// (row, 2-bit unit) when a unit is one piece (first-order groups of 64 columns or more), four lanes a
-// 64-byte half unit otherwise.
+// LDS area so that neighbouring lanes write contiguous bytes: eight lanes the 128 bytes of a (row, 2-bit
+// unit), which are a whole line when a unit is one piece (first-order groups of 64 columns or more) and
+// the unit's pieces otherwise; four lanes the 64 bytes of a (row, 4-bit unit).  Narrower groups go through
+// mpq_dequant_lines_kernel below whenever their unit table fits its LDS; this kernel is what is left for them.
 //
 // The kernel writes 2 bytes per weight against 0.33 read; what was measured on the way to its shape:
 //   - Loads and stores of a wave complete in one order, so a wait for a load that was requested after a
@@ -1694,27 +1695,27 @@ mpq_gemvp_kernel(const PlaneArgs a) {
 //     memory side read and write one 64-byte piece per outlier (22016 x 4096, 0.5 %: + 20 us).  ADD adds
 //     them while the decoded block is in LDS: the tile's outlier block index names the words of (row, block),
 //     lane (row r, j) takes words j and j + 4 of row r (both requested with the batch's other loads; further
-//     ones, which are rare, with loads of their own), finds the unit by comparing the column with the four
-//     units' first columns and adds in place (native fp16 add = the definition's fp32 add and one rounding).
+//     ones, which are rare, with loads of their own), finds the piece by comparing the column with the first
+//     columns of the block's pieces and adds in place (native fp16 add = the definition's fp32 add and one
+//     rounding).
 template <int PU, bool NT, bool AL = false, bool ADD = false>
 __global__ void __launch_bounds__(256)
-mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, const int dt) {
+mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, const int dt, const int table_bytes) {
 #pragma clang fp contract(off)
   MPQ_TL_DECL
   MPQ_STAMP(0)
   constexpr bool WHOLE = PU == 1;
-  constexpr int PAIR = WHOLE ? 144 : 80;  // LDS bytes per (row, unit) or (row, half unit): + 16 so that lanes fall into different banks
+  constexpr int PAIR = 144;  // LDS bytes per (row, unit): + 16 so that lanes fall into different banks
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   constexpr int D = PU == 1 ? 8 : 4;      // blocks per batch (10 or 4 + 6 PU registers per block)
   __shared__ __align__(16) unsigned char turn[4][64 * PAIR];
   // the unit table, when it fits (K up to 28672 for one piece per unit): a wave's first requests then depend
   // on no other load, and go out before any wave of the launch has stored anything
-  constexpr int TABLE = PU == 1 ? 4096 : 16384;
-  __shared__ __align__(16) unsigned char table[TABLE];
+  extern __shared__ __align__(16) unsigned char table[];  // table_bytes of it, or nothing
   const int tid = threadIdx.x;
   const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int i = lane & 15, j = lane >> 4;
-  const bool staged = 32 * PU * b.C <= TABLE;
+  const bool staged = table_bytes != 0;
   if (staged) {
     for (int o = tid * 16; o < 32 * PU * b.C; o += 256 * 16) *(uint4*)(table + o) = *(const uint4*)(b.units + o);
     __syncthreads();
@@ -1832,9 +1833,13 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
   _Pragma("unroll") for (int s = 0; s < 8; ++s) {                                                         \
     const int pair = (lane >> 3) + s * 8;                                                                 \
     const int ch = lane & 7; /* decode step = 16-byte chunk of the unit */                                \
-    const uint32_t ex = MPQ_DQ_WORD(0, x, s >> 1), ey = MPQ_DQ_WORD(0, y, s >> 1);                        \
+    uint32_t ex = MPQ_DQ_WORD(0, x, s >> 1), ey = MPQ_DQ_WORD(0, y, s >> 1);                              \
+    _Pragma("unroll") for (int q_ = 1; q_ < PU; ++q_) { /* the piece of the lane's step */                \
+      const uint32_t exq = MPQ_DQ_WORD(q_, x, s >> 1), eyq = MPQ_DQ_WORD(q_, y, s >> 1);                  \
+      if (ch / (8 / PU) == q_) { ex = exq; ey = eyq; }                                                    \
+    }                                                                                                     \
     const uint4 v = *(const uint4*)(mine + pair * PAIR + ch * 16);                                        \
-    const uint32_t at = (ey >> 16) != pad_entry ? (uint32_t)(pair & 15) * row_bytes + ex + (uint32_t)ch * 16u : DROPPED; \
+    const uint32_t at = (ey >> 16) != pad_entry ? (uint32_t)(pair & 15) * row_bytes + ex + (uint32_t)(ch % (8 / PU)) * 16u : DROPPED; \
     __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, NT ? 2 : 0); \
   }                                                                                                       \
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -1853,104 +1858,58 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
       zb[q_] = bits_to_half((uint16_t)(0x6400u | (m1s[d][q_] >> 8))); /* 1024 + z1 */         \
     }                                                                                         \
   }
-#define MPQ_DQ_STEP8(P) dst[(P)] = decode_step<true, P>(lo, hi, s1p[0], zb[0], kc);
+#define MPQ_DQ_STEP8(P) dst[(P)] = decode_step<true, P>(lo, hi, s1p[(P) / (8 / PU)], zb[(P) / (8 / PU)], kc);
 #define MPQ_DQ_STEP(TWO, P)                                                                   \
   {                                                                                           \
     constexpr int SPP = ((TWO) ? 8 : 4) / ((TWO) ? PU : PU4), Q = (P) / SPP;                  \
     dst[(P) & 3] = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                            \
   }
-      // outliers of a block whose units are several pieces: where a word's weight lies while its half is in LDS
-      // (half << 16 | byte offset in the wave's area).  The pieces are compared in block order from the back, so
-      // that the first match stays: padding pieces (offset 0) come after the real ones, and every word of the
-      // block lies in a real one.
-      constexpr uint32_t NOWHERE = 0xFFFF0000u;
-      constexpr uint32_t PB = 128u / PU;  // bytes of a piece in a row
-      uint32_t px[4][PU];
-      if constexpr (ADD && !WHOLE) {
-#pragma unroll
-        for (int u_ = 0; u_ < 4; ++u_) {
-#pragma unroll
-          for (int q_ = 0; q_ < PU; ++q_) px[u_][q_] = MPQ_DQ_WORD(q_, x, u_);
-        }
-      }
-      auto place = [&](const uint32_t word) {
-        const uint32_t at = 2u * (word & 0xFFFFu);
-        uint32_t r = NOWHERE;
-#pragma unroll
-        for (int u_ = 3; u_ >= 0; --u_) {
-#pragma unroll
-          for (int q_ = PU - 1; q_ >= 0; --q_) {
-            const uint32_t dq = at - px[u_][q_];
-            constexpr int HP = PU > 1 ? PU / 2 : 1;  // pieces per half
-            if (dq < PB) r = ((uint32_t)(q_ / HP) << 16) | (((uint32_t)u_ * 16u + (uint32_t)i) * PAIR + (uint32_t)(q_ % HP) * PB + dq);
-          }
-        }
-        return r;
-      };
-      auto add_at = [&](const uint32_t where, const uint32_t word) {
-        uint16_t* w16 = (uint16_t*)(mine + (where & 0xFFFFu));
-        *w16 = half_to_bits(bits_to_half(*w16) + bits_to_half((uint16_t)(word >> 16)));
-      };
-      uint32_t opl0 = NOWHERE, opl1 = NOWHERE;
-      if constexpr (ADD && !WHOLE) {
-        if ((uint32_t)j < ocount[d]) opl0 = place(oword[d][0]);
-        if ((uint32_t)j + 4u < ocount[d]) opl1 = place(oword[d][1]);
-      }
-#define MPQ_DQ_ADD_HALF(HALF)                                                                             \
-  if constexpr (ADD) {                                                                                    \
-    if ((opl0 >> 16) == (HALF)) add_at(opl0, oword[d][0]);                                                \
-    if ((opl1 >> 16) == (HALF)) add_at(opl1, oword[d][1]);                                                \
-    if (ocount[d] > 8u) { /* more than eight outliers of a row in the block's columns */                  \
-      const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)t_cur * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD); \
-      for (uint32_t e = 8u + (uint32_t)j; e < ocount[d]; e += 4u) {                                       \
-        const uint32_t word = words[ofirst[d] + e], where = place(word);                                  \
-        if ((where >> 16) == (HALF)) add_at(where, word);                                                 \
-      }                                                                                                   \
-    }                                                                                                     \
-  }
       if (two) {
         MPQ_DQ_PIECES(PU, false)
         const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
-        if constexpr (WHOLE) {
-          MPQ_DQ_STEP8(0) MPQ_DQ_STEP8(1) MPQ_DQ_STEP8(2) MPQ_DQ_STEP8(3)
-          MPQ_DQ_STEP8(4) MPQ_DQ_STEP8(5) MPQ_DQ_STEP8(6) MPQ_DQ_STEP8(7)
-          if constexpr (ADD) {
-            // byte offsets of the four units' first columns in a row; a padding unit (offset 0) comes after the
-            // real ones, and no word of this block lies in it
-            const uint32_t x0 = MPQ_DQ_WORD(0, x, 0), x1 = MPQ_DQ_WORD(0, x, 1), x2 = MPQ_DQ_WORD(0, x, 2), x3 = MPQ_DQ_WORD(0, x, 3);
-            auto add_outlier = [&](const uint32_t word) {
-              const uint32_t at = 2u * (word & 0xFFFFu);
-              const uint32_t d0 = at - x0, d1 = at - x1, d2 = at - x2, d3 = at - x3;
-              const uint32_t u = d0 < 128u ? 0u : d1 < 128u ? 1u : d2 < 128u ? 2u : 3u;
-              const uint32_t du = d0 < 128u ? d0 : d1 < 128u ? d1 : d2 < 128u ? d2 : d3;
-              if (du < 128u) {
-                uint16_t* w16 = (uint16_t*)(mine + (u * 16u + (uint32_t)i) * PAIR + du);
-                *w16 = half_to_bits(bits_to_half(*w16) + bits_to_half((uint16_t)(word >> 16)));
-              }
-            };
-            if ((uint32_t)j < ocount[d]) add_outlier(oword[d][0]);
-            if ((uint32_t)j + 4u < ocount[d]) add_outlier(oword[d][1]);
-            if (ocount[d] > 8u) {  // more than eight outliers of a row in 256 columns
-              const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)t_cur * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD);
-              for (uint32_t e = 8u + (uint32_t)j; e < ocount[d]; e += 4u) add_outlier(words[ofirst[d] + e]);
-            }
+        MPQ_DQ_STEP8(0) MPQ_DQ_STEP8(1) MPQ_DQ_STEP8(2) MPQ_DQ_STEP8(3)
+        MPQ_DQ_STEP8(4) MPQ_DQ_STEP8(5) MPQ_DQ_STEP8(6) MPQ_DQ_STEP8(7)
+        if constexpr (ADD) {
+          // byte offsets of the first columns of the block's pieces in a row.  They are compared from the back, so
+          // that the first match stays: padding pieces (offset 0) come after the real ones, and every word of
+          // the block lies in a real one.
+          constexpr uint32_t PB = 128u / PU;  // bytes of a piece in a row
+          uint32_t px[4][PU];
+#pragma unroll
+          for (int u_ = 0; u_ < 4; ++u_) {
+#pragma unroll
+            for (int q_ = 0; q_ < PU; ++q_) px[u_][q_] = MPQ_DQ_WORD(q_, x, u_);
           }
-          MPQ_DQ_STORE_UNIT
-        } else {
-          MPQ_DQ_STEP(true, 0) MPQ_DQ_STEP(true, 1) MPQ_DQ_STEP(true, 2) MPQ_DQ_STEP(true, 3)
-          MPQ_DQ_ADD_HALF(0)
-          MPQ_DQ_STORE_HALF(0, 8 / PU)
-          MPQ_DQ_STEP(true, 4) MPQ_DQ_STEP(true, 5) MPQ_DQ_STEP(true, 6) MPQ_DQ_STEP(true, 7)
-          MPQ_DQ_ADD_HALF(1)
-          MPQ_DQ_STORE_HALF(1, 8 / PU)
+          auto add_outlier = [&](const uint32_t word) {
+            const uint32_t at = 2u * (word & 0xFFFFu);
+            uint32_t where = 0xFFFFFFFFu;
+#pragma unroll
+            for (int u_ = 3; u_ >= 0; --u_) {
+#pragma unroll
+              for (int q_ = PU - 1; q_ >= 0; --q_) {
+                const uint32_t dq = at - px[u_][q_];
+                if (dq < PB) where = ((uint32_t)u_ * 16u + (uint32_t)i) * PAIR + (uint32_t)q_ * PB + dq;
+              }
+            }
+            if (where != 0xFFFFFFFFu) {
+              uint16_t* w16 = (uint16_t*)(mine + where);
+              *w16 = half_to_bits(bits_to_half(*w16) + bits_to_half((uint16_t)(word >> 16)));
+            }
+          };
+          if ((uint32_t)j < ocount[d]) add_outlier(oword[d][0]);
+          if ((uint32_t)j + 4u < ocount[d]) add_outlier(oword[d][1]);
+          if (ocount[d] > 8u) {  // more than eight outliers of a row in the block's columns
+            const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)t_cur * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD);
+            for (uint32_t e = 8u + (uint32_t)j; e < ocount[d]; e += 4u) add_outlier(words[ofirst[d] + e]);
+          }
         }
+        MPQ_DQ_STORE_UNIT
       } else {
         MPQ_DQ_PIECES(PU4, true)
         const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
         MPQ_DQ_STEP(false, 0) MPQ_DQ_STEP(false, 1) MPQ_DQ_STEP(false, 2) MPQ_DQ_STEP(false, 3)
         MPQ_DQ_STORE_HALF(0, 4 / PU4)
       }
-#undef MPQ_DQ_ADD_HALF
 #undef MPQ_DQ_STEP
 #undef MPQ_DQ_STEP8
 #undef MPQ_DQ_PIECES
@@ -1968,6 +1927,245 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
   MPQ_TL_NOTE(12, __builtin_amdgcn_s_getreg((31 << 11) | 4))   // HW_ID: where the wave ran
   MPQ_TL_NOTE(13, __builtin_amdgcn_s_getreg((31 << 11) | 20))  // XCC_ID
   MPQ_TL_FLUSH(blockIdx.x, wv, 3, lane)
+}
+
+// Dequantization where a group is narrower than a 128-byte line of the output (groups of 16 or 32 columns).
+// There a line holds pieces of several units, 2-bit and 4-bit ones, that lie far apart in the code streams.
+// Written piece by piece the memory side sees 32- and 64-byte fragments whose other parts come from other waves
+// at other times: a 32-byte half of a 64-byte segment that finds its other half gone from the L2 costs a
+// read-modify-write (measured: 1.9 TB/s instead of 4.5 to 5.4), and such fragments cannot carry the non-temporal
+// bit, which is worth a third.  So a workgroup here owns 16 rows x KC columns of the output: its waves decode
+// every unit that has a piece in those columns (both streams are in K order: the pieces of a column range are a
+// range of each stream, found by bisection of the unit table once per workgroup) into an LDS image of the
+// output, add the outliers there (the address is the column, no search), and write whole lines, 1 KiB of a row per
+// instruction, non-temporal.  Units that straddle a range are decoded by both neighbours, each keeping its own
+// pieces.  The requests of the next range go out before the stores of this one.
+template <int PU, bool AL, bool ADD, int KC, int TB>
+__global__ void __launch_bounds__(256)
+mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int np2, const int np4, const uint32_t pad_y2,
+                         const uint32_t pad_y4) {
+#pragma clang fp contract(off)
+  constexpr int PP2 = PU, PP4 = PU > 1 ? PU / 2 : 1;  // pieces of a 2-bit and of a 4-bit unit
+  constexpr int ROWB = 2 * KC + 16;                   // bytes of a row of the image: + 16 so that rows start in different banks
+  constexpr int D = 4;                                // passes of a wave whose words are requested together
+  constexpr uint32_t DROPPED = 0x80000000u;
+  __shared__ __align__(16) unsigned char out[16 * ROWB];
+  __shared__ __align__(16) unsigned char table[TB];
+  __shared__ uint16_t cut2[68], cut4[68];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int i = lane & 15, j = lane >> 4;
+  for (int o = tid * 16; o < 32 * PU * b.C; o += 256 * 16) *(uint4*)(table + o) = *(const uint4*)(b.units + o);
+  __syncthreads();
+  // cut[k] = the first piece of the stream whose first column is not before column k KC
+  const int nch = (b.K + KC - 1) / KC;
+  for (int idx = tid; idx < 2 * (nch + 1); idx += 256) {
+    const int four = idx > nch, k = four ? idx - nch - 1 : idx;
+    const uint32_t x_k = (uint32_t)k * (2u * KC);
+    int lo = 0, hi = four ? np4 : np2;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      const uint32_t at = four ? (uint32_t)(4 * b.B2 + mid / PP4) * (8 * PU) + 8u * (uint32_t)(mid % PP4)
+                               : (uint32_t)(mid / PP2) * (8 * PU) + 8u * (uint32_t)(mid % PP2);
+      if (*(const uint32_t*)(table + at) < x_k) lo = mid + 1;
+      else hi = mid;
+    }
+    (four ? cut4 : cut2)[k] = (uint16_t)lo;
+  }
+  __syncthreads();
+  const DecodeConsts kc = make_consts();
+  const uint32_t m1_lane = (uint32_t)i * 2u, m2_lane = b.off_m2 + ((uint32_t)i >> b.m2_shift) * 4u;
+  const uint32_t pad_entry = b.pad_entry;
+  const uint32_t row_bytes = 2u * (uint32_t)b.K;
+  const int total = b.T * nch;
+  const int orow = tid >> 4, om = tid & 15;  // outliers: 16 threads per row, the rows of a wave are the ones it stores
+
+  uint4 qs[D];
+  uint2 es[D][PU];
+  uint32_t ma[D][PU], mb[D][PU], mc[D][PU];
+  bool live[D], two[D];
+  uint32_t x0_req = 0, ofirst = 0, ocount = 0, oword[2] = {0u, 0u};
+
+  // requests what passes wv + 4 (d + D * batch), d = 0 .. D - 1, of the range need
+  auto request = [&](const int item, const int batch) {
+    const int t = item / nch, k = item - t * nch;
+    const int c2lo = __builtin_amdgcn_readfirstlane(cut2[k]), c2hi = __builtin_amdgcn_readfirstlane(cut2[k + 1]);
+    const int c4lo = __builtin_amdgcn_readfirstlane(cut4[k]), c4hi = __builtin_amdgcn_readfirstlane(cut4[k + 1]);
+    const int u2lo = c2lo / PP2, n2u = c2hi > c2lo ? (c2hi + PP2 - 1) / PP2 - u2lo : 0, p2 = (n2u + 3) >> 2;
+    const int u4lo = c4lo / PP4, n4u = c4hi > c4lo ? (c4hi + PP4 - 1) / PP4 - u4lo : 0, p4 = (n4u + 3) >> 2;
+    const unsigned char* side = b.tiles + (size_t)t * b.tile_stride;
+    x0_req = (uint32_t)k * (2u * KC);
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const int pass = wv + 4 * (d + D * batch);
+      live[d] = pass < p2 + p4;
+      two[d] = pass < p2;
+      if (!live[d]) continue;
+      if (two[d]) {
+        const int v = u2lo + 4 * pass + j, vv = v < u2lo + n2u ? v : u2lo;
+        const uint32_t ue = (uint32_t)vv * (8 * PU);
+#pragma unroll
+        for (int q_ = 0; q_ < PU; ++q_) {
+          const int idx = v * PP2 + q_;
+          const uint2 e = *(const uint2*)(table + ue + 8 * q_);
+          es[d][q_] = (idx >= c2lo && idx < c2hi) ? e : uint2{0u, pad_y2};
+        }
+        qs[d] = ((const uint4*)(side + b.codes_off))[(vv >> 2) * 64 + (vv & 3) * 16 + i];
+      } else {
+        const int v = u4lo + 4 * (pass - p2) + j, vv = v < u4lo + n4u ? v : u4lo;
+        const uint32_t ue = (uint32_t)(4 * b.B2 + vv) * (8 * PU);
+#pragma unroll
+        for (int q_ = 0; q_ < PU; ++q_) {
+          const int idx = v * PP4 + q_;
+          const uint2 e = *(const uint2*)(table + ue + 8 * (q_ < PP4 ? q_ : 0));
+          es[d][q_] = (q_ < PP4 && idx >= c4lo && idx < c4hi) ? e : uint2{0u, pad_y4};
+        }
+        qs[d] = ((const uint4*)(side + b.codes_off))[(b.B2 + (vv >> 2)) * 64 + (vv & 3) * 16 + i];
+      }
+    }
+    if constexpr (ADD) {
+      if (batch == 0) {
+        const int cA = c2lo / (4 * PP2), cB = c2hi > c2lo ? (c2hi - 1) / (4 * PP2) + 1 : cA;
+        const uint16_t* ox = (const uint16_t*)(side + b.off_oidx) + orow;
+        ofirst = ox[cA * 16];
+        ocount = ox[cB * 16];
+      }
+    }
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (!live[d]) continue;
+#pragma unroll
+      for (int q_ = 0; q_ < PU; ++q_) {
+        const uint32_t y = es[d][q_].y;
+        if constexpr (AL) {
+          const uint32_t idx = (y >> 16) + ((uint32_t)i >> b.m2_shift);
+          ma[d][q_] = two[d] ? (uint32_t)*(const uint16_t*)(side + (y & 0xFFFCu) + 2u * (uint32_t)i)
+                             : (uint32_t)*(const uint8_t*)(side + b.off_m1b + (y & 0xFFFFu) + (uint32_t)i);
+          mb[d][q_] = *(const uint16_t*)(side + b.off_s2 + 2u * idx);
+          mc[d][q_] = *(const uint8_t*)(side + b.off_z2 + idx);
+        } else {
+          ma[d][q_] = *(const uint16_t*)(side + (m1_lane + (y & 0xFFFFu)));
+          mb[d][q_] = *(const uint32_t*)(side + (m2_lane + (y >> 16)));
+        }
+      }
+    }
+    if constexpr (ADD) {
+      if (batch == 0) {
+        const uint32_t* words = (const uint32_t*)(side + b.off_ot + MPQ_OTILE_HEAD);
+        ocount -= ofirst;
+        const uint32_t w0 = ofirst + (uint32_t)om, w1 = w0 + 16u;
+        oword[0] = words[w0 < b.ocap ? w0 : 0u];
+        oword[1] = words[w1 < b.ocap ? w1 : 0u];
+      }
+    }
+  };
+
+  // decodes the requested passes into the image
+  auto decode = [&]() {
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      if (!live[d]) continue;
+      const uint4 q = qs[d];
+      const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
+      half2_t s1p[PU];
+      half_t zb[PU];
+      uint32_t at[PU];  // where the piece starts in the lane's row of the image; DROPPED for none
+#pragma unroll
+      for (int q_ = 0; q_ < PU; ++q_) {
+        const uint2 e = es[d][q_];
+        uint32_t s_int, z1, m2;
+        if constexpr (AL) {
+          const uint32_t w = ma[d][q_];
+          if (two[d]) {
+            const uint32_t pos = e.y & 3u;
+            z1 = (w >> (2u * pos)) & 3u;
+            s_int = pos == 0 ? (w >> 6) & 15u : (w >> (pos == 1 ? 10u : 13u)) & 7u;
+          } else {
+            s_int = w & 15u;
+            z1 = w >> 4;
+          }
+          const half_t z2 = (half_t)(float)mc[d][q_];  // 0..15: exact
+          m2 = mb[d][q_] | ((uint32_t)half_to_bits(z2) << 16);
+        } else {
+          s_int = ma[d][q_] & 0xFFu;
+          z1 = ma[d][q_] >> 8;
+          m2 = mb[d][q_];
+        }
+        const half_t s1 = scale_dequant(s_int, m2);
+        s1p[q_] = half2_t{s1, s1};
+        zb[q_] = bits_to_half((uint16_t)(0x6400u | z1));  // 1024 + z1
+        at[q_] = (e.y >> 16) != pad_entry ? (uint32_t)i * ROWB + (e.x - x0_req) : DROPPED;
+      }
+#define MPQ_DL_STEP(TWO, P)                                                                      \
+  {                                                                                              \
+    constexpr int SPP = (TWO) ? 8 / PP2 : 4 / PP4, Q = (P) / SPP;                                \
+    const uint4 v = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                              \
+    if (at[Q] != DROPPED) *(uint4*)(out + at[Q] + ((P) % SPP) * 16) = v;                         \
+  }
+      if (two[d]) {
+        const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
+        MPQ_DL_STEP(true, 0) MPQ_DL_STEP(true, 1) MPQ_DL_STEP(true, 2) MPQ_DL_STEP(true, 3)
+        MPQ_DL_STEP(true, 4) MPQ_DL_STEP(true, 5) MPQ_DL_STEP(true, 6) MPQ_DL_STEP(true, 7)
+      } else {
+        const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
+        MPQ_DL_STEP(false, 0) MPQ_DL_STEP(false, 1) MPQ_DL_STEP(false, 2) MPQ_DL_STEP(false, 3)
+      }
+#undef MPQ_DL_STEP
+    }
+  };
+
+  int item = blockIdx.x;
+  if (item < total) request(item, 0);
+  for (; item < total; item += gridDim.x) {
+    const int t = item / nch, k = item - t * nch;
+    decode();
+    {  // ranges of more than 16 passes (most of a long range 4-bit)
+      const int c2lo = cut2[k], c2hi = cut2[k + 1], c4lo = cut4[k], c4hi = cut4[k + 1];
+      const int n2u = c2hi > c2lo ? (c2hi + PP2 - 1) / PP2 - c2lo / PP2 : 0, n4u = c4hi > c4lo ? (c4hi + PP4 - 1) / PP4 - c4lo / PP4 : 0;
+      const int passes = ((n2u + 3) >> 2) + ((n4u + 3) >> 2);
+      for (int batch = 1; batch * 4 * D < passes; ++batch) {
+        request(item, batch);
+        decode();
+      }
+    }
+    lds_barrier();
+    const uint32_t x0 = (uint32_t)k * (2u * KC);
+    const uint32_t of_cur = ofirst, oc_cur = ocount, ow0 = oword[0], ow1 = oword[1];
+    if (item + (int)gridDim.x < total) request(item + (int)gridDim.x, 0);
+    if constexpr (ADD) {
+      auto add_outlier = [&](const uint32_t word) {
+        const uint32_t rel = (word & 0xFFFFu) - (uint32_t)k * KC;
+        if (rel < (uint32_t)KC) {
+          uint16_t* w16 = (uint16_t*)(out + orow * ROWB + 2u * rel);
+          *w16 = half_to_bits(bits_to_half(*w16) + bits_to_half((uint16_t)(word >> 16)));
+        }
+      };
+      if ((uint32_t)om < oc_cur) add_outlier(ow0);
+      if ((uint32_t)om + 16u < oc_cur) add_outlier(ow1);
+      if (oc_cur > 32u) {
+        const uint32_t* words = (const uint32_t*)(b.tiles + (size_t)t * b.tile_stride + b.off_ot + MPQ_OTILE_HEAD);
+        for (uint32_t e = 32u + (uint32_t)om; e < oc_cur; e += 16u) add_outlier(words[of_cur + e]);
+      }
+    }
+    // the wave's four rows, 1 KiB per instruction
+    const int rows_left = b.N - t * 16;
+    const __amdgpu_buffer_rsrc_t out_rows = __builtin_amdgcn_make_buffer_rsrc(
+        (unsigned char*)Wout + (size_t)t * 16 * row_bytes, 0, (uint32_t)(rows_left < 16 ? rows_left : 16) * row_bytes, 0x00020000);
+    const uint32_t cb = row_bytes - x0 < 2u * KC ? row_bytes - x0 : 2u * KC;  // bytes of a row in this range
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const uint32_t r = (uint32_t)(4 * wv + rr);
+#pragma unroll
+      for (int n = 0; n < 2 * KC / 1024; ++n) {
+        const uint32_t o = (uint32_t)n * 1024u + (uint32_t)lane * 16u;
+        const uint4 v = *(const uint4*)(out + r * ROWB + o);
+        const uint32_t at = o < cb ? r * row_bytes + x0 + o : DROPPED;
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, 2);
+      }
+    }
+    lds_barrier();
+  }
 }
 
 // W[row][col] = fp16(W[row][col] + val) for every outlier word of the tile (native fp16 add = the
@@ -2629,23 +2827,53 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
   const long long blocks = (long long)h.T * (h.B2 + h.B4);
   if (blocks == 0) return MPQ_OK;
   const int batch = pu == 1 ? 8 : 4;
+  // the unit table in LDS when it leaves three workgroups on a compute unit (four when it is at most 4 KiB)
+  const int table_all = 32 * pu * (h.B2 + h.B4);
+  const int table_bytes = table_all <= 16384 ? table_all : 0;
+  const int fit = table_bytes <= 4096 ? 4 : 3;
   long long per_cu = (blocks + 4ll * batch * cus - 1) / (4ll * batch * cus);
-  per_cu = per_cu > 4 ? 4 : per_cu;
+  per_cu = per_cu > fit ? fit : per_cu;
   const dim3 grid((unsigned)(per_cu * cus));
-  const int dc = (int)((4ll * grid.x) % (h.B2 + h.B4)), dt = (int)((4ll * grid.x) / (h.B2 + h.B4));
+  const int items = h.B2 + h.B4;
+  const int dc = (int)((4ll * grid.x) % items), dt = (int)((4ll * grid.x) / items);
   const bool add = add_outliers && h.nnz > 0;
   const bool in_lds = add && h.oidx_off != 0;  // the blob has the outlier block index
-  if (in_lds && pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1, true, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (in_lds && pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2, false, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (in_lds && h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, false, true, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (in_lds) MPQ_LAUNCH((mpq_dequant_kernel<4, false, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (pu == 1 && !add) MPQ_LAUNCH((mpq_dequant_kernel<1, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (pu == 1) MPQ_LAUNCH((mpq_dequant_kernel<1, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (pu == 2) MPQ_LAUNCH((mpq_dequant_kernel<2, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else if (h.meta == MPQ_META_PAPER) MPQ_LAUNCH((mpq_dequant_kernel<4, false, true>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  else MPQ_LAUNCH((mpq_dequant_kernel<4, false>), grid, dim3(256), 0, s, d, W_out_dev, dc, dt);
-  // Outliers of the other formats (dense + sparse, Sec. 2.3): a second kernel.  Adding them at the end of the
-  // first one, by the workgroup that wrote the weights, needs workgroups that own tiles and wait for their
+  // Groups narrower than a line of the output: workgroups that own 16 rows x 2048 columns and write whole lines,
+  // two of them on a compute unit (64 KiB of output image and up to 14 KiB of unit table each).
+  constexpr int KC = 2048, TB = 14336;
+  const int nch = (h.K + KC - 1) / KC;
+  if (pu >= 2 && table_all <= TB && nch <= 64) {
+    const int np2 = (int)h.n2, np4 = (int)h.n4;  // pieces of the two streams = groups
+    // word 1 of the table entry of a piece that is not there (the packer's padding pieces hold the same)
+    const uint32_t py2 = h.meta == MPQ_META_PAPER ? (32u * mpq_p_triples(&h)) | (mpq_p_zero_entry(&h) << 16)
+                                                  : (32u * (uint32_t)h.G) | (mpq_meta2_zero(&h) << 16);
+    const uint32_t py4 = h.meta == MPQ_META_PAPER ? (16u * (uint32_t)h.n4) | (mpq_p_zero_entry(&h) << 16) : py2;
+    const long long total = (long long)h.T * nch;
+    const dim3 lgrid((unsigned)(total < 2ll * cus ? total : 2ll * cus));
+#define MPQ_DL_LAUNCH(PUV, ALV, ADDV) \
+  MPQ_LAUNCH((mpq_dequant_lines_kernel<PUV, ALV, ADDV, KC, TB>), lgrid, dim3(256), 0, s, d, W_out_dev, np2, np4, py2, py4)
+    if (pu == 2) { if (in_lds) MPQ_DL_LAUNCH(2, false, true); else MPQ_DL_LAUNCH(2, false, false); }
+    else if (h.meta == MPQ_META_PAPER) { if (in_lds) MPQ_DL_LAUNCH(4, true, true); else MPQ_DL_LAUNCH(4, true, false); }
+    else { if (in_lds) MPQ_DL_LAUNCH(4, false, true); else MPQ_DL_LAUNCH(4, false, false); }
+#undef MPQ_DL_LAUNCH
+    if (add && !in_lds) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
+    return MPQ_OK;
+  }
+  // One piece per unit, and rows too long for the above.  Lines are whole and carry the non-temporal bit where
+  // nothing reads them back; with four pieces per unit they are fragments, which it would slow down.
+#define MPQ_DQ_LAUNCH(...) \
+  MPQ_LAUNCH((mpq_dequant_kernel<__VA_ARGS__>), grid, dim3(256), (size_t)table_bytes, s, d, W_out_dev, dc, dt, table_bytes)
+  if (in_lds && pu == 1) MPQ_DQ_LAUNCH(1, true, false, true);
+  else if (in_lds && pu == 2) MPQ_DQ_LAUNCH(2, true, false, true);
+  else if (in_lds && h.meta == MPQ_META_PAPER) MPQ_DQ_LAUNCH(4, false, true, true);
+  else if (in_lds) MPQ_DQ_LAUNCH(4, false, false, true);
+  else if (pu == 1) { if (add) MPQ_DQ_LAUNCH(1, false); else MPQ_DQ_LAUNCH(1, true); }
+  else if (pu == 2) { if (add) MPQ_DQ_LAUNCH(2, false); else MPQ_DQ_LAUNCH(2, true); }
+  else if (h.meta == MPQ_META_PAPER) MPQ_DQ_LAUNCH(4, false, true);
+  else MPQ_DQ_LAUNCH(4, false);
+#undef MPQ_DQ_LAUNCH
+  // Outliers of tiles without a block index (dense + sparse, Sec. 2.3): a second kernel.  Adding them at the end
+  // of the first one, by the workgroup that wrote the weights, needs workgroups that own tiles and wait for their
   // stores, which costs more than the second launch (22016 x 4096, 0.5 % outliers: 82 us against 63 us).
   if (add && !in_lds) MPQ_LAUNCH(mpq_outlier_add_kernel, dim3(h.T), dim3(256), 0, s, d, W_out_dev);
   return MPQ_OK;

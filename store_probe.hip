@@ -12,6 +12,14 @@
 //                     dealt round-robin over all waves; per block: 1 KiB loaded D blocks ahead, 160 dependent
 //                     multiply-adds, the decoded bytes turned through LDS (8 x 16-byte writes per lane, 8 reads),
 //                     eight store instructions of whole lines
+//   split D / PART  : 1024 four-wave workgroups; a job = 16 rows x 1 KiB = 16 store instructions of 16 rows x 64 bytes,
+//                     i.e. every 128-byte line is written as two halves (or every 64-byte segment as two 32-byte
+//                     halves, two segments per row and instruction).  D = lines whose first halves a wave writes
+//                     before it writes their second halves (1: the halves follow each other; 8: a job's 8 first
+//                     halves, then its 8 second halves; 32: four jobs').  PART = who writes the second halves: the
+//                     same wave, the wave next to it in the workgroup, the same wave of a workgroup on the same die
+//                     (workgroups go to the eight dies in turn), or of a workgroup on the next die; the two work
+//                     through the same jobs in the same order, one half each.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -101,6 +109,51 @@ __global__ void __launch_bounds__(256) wave_model(unsigned char* out, const u32x
   if (a0 == 12345.678f) sink[0] = a0 + a1 + a2 + a3;
 }
 
+constexpr int JOBS = (N / 16) * (ROW / 1024);
+
+// One store instruction: 16 rows x 64 bytes.  PB = 64: half `par` of line l of the job's strip.  PB = 32: the 32-byte
+// half `par` of the two 64-byte segments of line l (lanes in pairs).
+template <int PB>
+__device__ __forceinline__ void store_piece(unsigned char* out, const int job, const int l, const int par, const int lane) {
+  const int t = job / (ROW / 1024), strip = job - t * (ROW / 1024);
+  const u32x4 v = {(unsigned)lane, (unsigned)l, (unsigned)job, 7u};
+  const int at = PB == 64 ? l * 128 + par * 64 + (lane & 3) * 16 : l * 128 + ((lane >> 1) & 1) * 64 + par * 32 + (lane & 1) * 16;
+  *(u32x4*)(out + ((size_t)t * 16 + (lane >> 2)) * ROW + (size_t)strip * 1024 + at) = v;
+}
+
+template <int D, int PB>
+__global__ void __launch_bounds__(256) split_same_wave(unsigned char* out) {
+  const int lane = threadIdx.x & 63, gw = blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = gridDim.x * 4;
+  constexpr int G = D > 8 ? D / 8 : 1;  // jobs whose halves are interleaved
+  for (int base = 0; gw + base * nwaves < JOBS; base += G) {
+#pragma unroll
+    for (int lg = 0; lg < 8 * G; lg += D) {
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+#pragma unroll
+        for (int l = lg; l < lg + D; ++l) {
+          const int job = gw + (base + l / 8) * nwaves;
+          if (job < JOBS) store_piece<PB>(out, job, l % 8, par, lane);
+        }
+      }
+    }
+  }
+}
+
+// PART 1: the wave next to it in the workgroup; 2: a workgroup on the same die; 3: a workgroup on the next die
+template <int PART, int PB>
+__global__ void __launch_bounds__(256) split_other(unsigned char* out) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, b = blockIdx.x;
+  int par, first, step;
+  if (PART == 1) { par = wv & 1; first = b * 2 + (wv >> 1); step = gridDim.x * 2; }
+  else if (PART == 2) { par = (b >> 3) & 1; first = ((b & 7) | ((b >> 4) << 3)) * 4 + wv; step = gridDim.x * 2; }
+  else { par = b & 1; first = (b >> 1) * 4 + wv; step = gridDim.x * 2; }
+  for (int job = first; job < JOBS; job += step) {
+#pragma unroll
+    for (int l = 0; l < 8; ++l) store_piece<PB>(out, job, l, par, lane);
+  }
+}
+
 int main() {
   unsigned char* out[6];
   u32x4* src[6];
@@ -149,5 +202,17 @@ int main() {
   MODEL(7, 768, "six inputs (from memory)")
   MODEL(1, 256, "one input (cached)")
   MODEL(1, 64, "one input (cached)")
+#define SPLIT(PB, WHAT)                                                                                                \
+  run("split " WHAT ", the two parts follow each other", [&](int i) { split_same_wave<1, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", 2 first parts, then their second parts", [&](int i) { split_same_wave<2, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", 4 first parts, then their second parts", [&](int i) { split_same_wave<4, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", 8 first parts, then their second parts", [&](int i) { split_same_wave<8, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", 16 first parts, then their second parts", [&](int i) { split_same_wave<16, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", 32 first parts, then their second parts", [&](int i) { split_same_wave<32, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", second parts by the next wave of the workgroup", [&](int i) { split_other<1, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", second parts by a workgroup on the same die", [&](int i) { split_other<2, PB><<<1024, 256>>>(out[i]); }); \
+  run("split " WHAT ", second parts by a workgroup on the next die", [&](int i) { split_other<3, PB><<<1024, 256>>>(out[i]); });
+  SPLIT(64, "128-byte lines into halves")
+  SPLIT(32, "64-byte segments into halves")
   return 0;
 }

@@ -81,6 +81,37 @@ def test_dequant_with_a_unit_table_too_long_to_stage(torch):
         assert np.array_equal(got, om.dequant(add)), add
 
 
+# Groups narrower than a 128-byte line of the output: workgroups own 16 rows x 2048 columns and decode every unit
+# with a piece in them, as long as the unit table fits their LDS (14 KiB); longer rows take the per-block kernel.
+NARROW_CASES = [
+    ("g16_ranges", 100, 5008, 16, 16, 0.25, 0.02, True, 1),              # two ranges and a ragged third; > 32 outliers per (row, range)
+    ("g16_ranges_aligned", 100, 5008, 16, 16, 0.25, 0.02, False, 1, 1),  # the same with the aligned metadata
+    ("g32_ranges", 72, 6176, 32, 16, 0.10, 0.02, True, 0),
+    ("g16_mostly_4bit", 40, 4112, 16, 16, 0.97, 0.01, False, 1),         # 17 passes of 4-bit units in a range: a second batch
+    ("g16_no_4bit", 24, 4096, 16, 16, 0.0, 0.01, False, 0),
+    ("g16_long", 32, 24576, 16, 16, 0.25, 0.01, False, 1),               # unit table of 15 KiB: per-block kernel, table in LDS
+    ("g16_long_aligned", 32, 24576, 16, 16, 0.25, 0.01, False, 1, 1),
+    ("g32_longest", 16, 65504, 32, 16, 0.10, 0.005, False, 0),           # 21 KiB: per-block kernel, table read from memory
+]
+
+
+@pytest.mark.parametrize("case", NARROW_CASES, ids=[c[0] for c in NARROW_CASES])
+def test_dequant_of_narrow_groups(torch, case):
+    lg, om, pk = make(case)
+    print("case", case, flush=True)
+    hdr = pk.header.view(np.int32)
+    table = 32 * (64 // case[3]) * (hdr[13] + hdr[14])   # bytes per block of the table x (B2 + B4)
+    assert (table > 14336) == ("long" in case[0]), table
+    blob = to_dev(torch, pk.blob)
+    for add in (False, True):
+        out = Guarded(torch, pk.N * pk.K)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+        got = out.check_and_get().reshape(pk.N, pk.K)
+        ref = om.dequant(add)
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, (add, bad[:5], got[tuple(bad[0])], ref[tuple(bad[0])])
+
+
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_gemv_within_tolerance(torch, case):
     lg, om, pk = make(case)
