@@ -1980,121 +1980,121 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
   const int total = b.T * nch;
   const int orow = tid >> 4, om = tid & 15;  // outliers: 16 threads per row, the rows of a wave are the ones it stores
 
-  uint4 qs[D];
-  uint2 es[D][PU];
-  uint32_t ma[D][PU], mb[D][PU], mc[D][PU];
-  bool live[D], two[D];
-  uint32_t x0_req = 0, ofirst = 0, ocount = 0, oword[2] = {0u, 0u};
+  // What a wave holds of one range between its requests and its decode: two such sets, so that the requests of the
+  // range after the next are on their way while this one is decoded and stored (a load that leaves while every
+  // compute unit streams stores takes 5 to 25 microseconds; the four matrices of a Llama2-7B layer with their
+  // input from memory: 139 -> 119 us with byte-wide, 157 -> 146 us with aligned metadata).
+  struct Set {
+    uint4 qs[D];
+    uint32_t at[D][PU];  // where the piece starts in the lane's row of the image (aligned metadata: | position in its triple); DROPPED: no piece
+    uint32_t ma[D][PU], mb[D][PU], mc[D][AL ? PU : 1];
+    bool live[D], two[D];
+    uint32_t ofirst, ocount, oword[2];
+  };
 
   // requests what passes wv + 4 (d + D * batch), d = 0 .. D - 1, of the range need
-  auto request = [&](const int item, const int batch) {
+  auto request = [&](Set& r, const int item, const int batch) {
     const int t = item / nch, k = item - t * nch;
     const int c2lo = __builtin_amdgcn_readfirstlane(cut2[k]), c2hi = __builtin_amdgcn_readfirstlane(cut2[k + 1]);
     const int c4lo = __builtin_amdgcn_readfirstlane(cut4[k]), c4hi = __builtin_amdgcn_readfirstlane(cut4[k + 1]);
     const int u2lo = c2lo / PP2, n2u = c2hi > c2lo ? (c2hi + PP2 - 1) / PP2 - u2lo : 0, p2 = (n2u + 3) >> 2;
     const int u4lo = c4lo / PP4, n4u = c4hi > c4lo ? (c4hi + PP4 - 1) / PP4 - u4lo : 0, p4 = (n4u + 3) >> 2;
     const unsigned char* side = b.tiles + (size_t)t * b.tile_stride;
-    x0_req = (uint32_t)k * (2u * KC);
+    const uint32_t x0 = (uint32_t)k * (2u * KC);
+    uint32_t ys[D][PU];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       const int pass = wv + 4 * (d + D * batch);
-      live[d] = pass < p2 + p4;
-      two[d] = pass < p2;
-      if (!live[d]) continue;
-      if (two[d]) {
-        const int v = u2lo + 4 * pass + j, vv = v < u2lo + n2u ? v : u2lo;
-        const uint32_t ue = (uint32_t)vv * (8 * PU);
+      r.live[d] = pass < p2 + p4;
+      r.two[d] = pass < p2;
+      if (!r.live[d]) continue;
+      const int ulo = r.two[d] ? u2lo : u4lo, nu = r.two[d] ? n2u : n4u, pp = r.two[d] ? PP2 : PP4;
+      const int clo = r.two[d] ? c2lo : c4lo, chi = r.two[d] ? c2hi : c4hi;
+      const int v = ulo + 4 * (r.two[d] ? pass : pass - p2) + j, vv = v < ulo + nu ? v : ulo;  // a unit past the range's: its first, no piece kept
+      const int vb = r.two[d] ? vv : 4 * b.B2 + vv;  // place in the table and in the tile's code blocks
+      const uint32_t ue = (uint32_t)vb * (8 * PU);
 #pragma unroll
-        for (int q_ = 0; q_ < PU; ++q_) {
-          const int idx = v * PP2 + q_;
-          const uint2 e = *(const uint2*)(table + ue + 8 * q_);
-          es[d][q_] = (idx >= c2lo && idx < c2hi) ? e : uint2{0u, pad_y2};
-        }
-        qs[d] = ((const uint4*)(side + b.codes_off))[(vv >> 2) * 64 + (vv & 3) * 16 + i];
-      } else {
-        const int v = u4lo + 4 * (pass - p2) + j, vv = v < u4lo + n4u ? v : u4lo;
-        const uint32_t ue = (uint32_t)(4 * b.B2 + vv) * (8 * PU);
-#pragma unroll
-        for (int q_ = 0; q_ < PU; ++q_) {
-          const int idx = v * PP4 + q_;
-          const uint2 e = *(const uint2*)(table + ue + 8 * (q_ < PP4 ? q_ : 0));
-          es[d][q_] = (q_ < PP4 && idx >= c4lo && idx < c4hi) ? e : uint2{0u, pad_y4};
-        }
-        qs[d] = ((const uint4*)(side + b.codes_off))[(b.B2 + (vv >> 2)) * 64 + (vv & 3) * 16 + i];
+      for (int q_ = 0; q_ < PU; ++q_) {
+        const int idx = v * pp + q_;
+        const uint2 e = *(const uint2*)(table + ue + 8 * (q_ < pp ? q_ : 0));
+        const bool mine = q_ < pp && idx >= clo && idx < chi;
+        ys[d][q_] = mine ? e.y : (r.two[d] ? pad_y2 : pad_y4);
+        r.at[d][q_] = mine ? ((uint32_t)i * ROWB + (e.x - x0)) | (AL ? e.y & 3u : 0u) : DROPPED;
       }
+      r.qs[d] = ((const uint4*)(side + b.codes_off))[(vb >> 2) * 64 + (vb & 3) * 16 + i];
     }
     if constexpr (ADD) {
       if (batch == 0) {
         const int cA = c2lo / (4 * PP2), cB = c2hi > c2lo ? (c2hi - 1) / (4 * PP2) + 1 : cA;
         const uint16_t* ox = (const uint16_t*)(side + b.off_oidx) + orow;
-        ofirst = ox[cA * 16];
-        ocount = ox[cB * 16];
+        r.ofirst = ox[cA * 16];
+        r.ocount = ox[cB * 16];
       }
     }
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      if (!live[d]) continue;
+      if (!r.live[d]) continue;
 #pragma unroll
       for (int q_ = 0; q_ < PU; ++q_) {
-        const uint32_t y = es[d][q_].y;
+        const uint32_t y = ys[d][q_];
         if constexpr (AL) {
           const uint32_t idx = (y >> 16) + ((uint32_t)i >> b.m2_shift);
-          ma[d][q_] = two[d] ? (uint32_t)*(const uint16_t*)(side + (y & 0xFFFCu) + 2u * (uint32_t)i)
-                             : (uint32_t)*(const uint8_t*)(side + b.off_m1b + (y & 0xFFFFu) + (uint32_t)i);
-          mb[d][q_] = *(const uint16_t*)(side + b.off_s2 + 2u * idx);
-          mc[d][q_] = *(const uint8_t*)(side + b.off_z2 + idx);
+          r.ma[d][q_] = r.two[d] ? (uint32_t)*(const uint16_t*)(side + (y & 0xFFFCu) + 2u * (uint32_t)i)
+                                 : (uint32_t)*(const uint8_t*)(side + b.off_m1b + (y & 0xFFFFu) + (uint32_t)i);
+          r.mb[d][q_] = *(const uint16_t*)(side + b.off_s2 + 2u * idx);
+          r.mc[d][q_] = *(const uint8_t*)(side + b.off_z2 + idx);
         } else {
-          ma[d][q_] = *(const uint16_t*)(side + (m1_lane + (y & 0xFFFFu)));
-          mb[d][q_] = *(const uint32_t*)(side + (m2_lane + (y >> 16)));
+          r.ma[d][q_] = *(const uint16_t*)(side + (m1_lane + (y & 0xFFFFu)));
+          r.mb[d][q_] = *(const uint32_t*)(side + (m2_lane + (y >> 16)));
         }
       }
     }
     if constexpr (ADD) {
       if (batch == 0) {
         const uint32_t* words = (const uint32_t*)(side + b.off_ot + MPQ_OTILE_HEAD);
-        ocount -= ofirst;
-        const uint32_t w0 = ofirst + (uint32_t)om, w1 = w0 + 16u;
-        oword[0] = words[w0 < b.ocap ? w0 : 0u];
-        oword[1] = words[w1 < b.ocap ? w1 : 0u];
+        r.ocount -= r.ofirst;
+        const uint32_t w0 = r.ofirst + (uint32_t)om, w1 = w0 + 16u;
+        r.oword[0] = words[w0 < b.ocap ? w0 : 0u];
+        r.oword[1] = words[w1 < b.ocap ? w1 : 0u];
       }
     }
   };
 
   // decodes the requested passes into the image
-  auto decode = [&]() {
+  auto decode = [&](const Set& r) {
 #pragma unroll
     for (int d = 0; d < D; ++d) {
-      if (!live[d]) continue;
-      const uint4 q = qs[d];
+      if (!r.live[d]) continue;
+      const uint4 q = r.qs[d];
       const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
       half2_t s1p[PU];
       half_t zb[PU];
-      uint32_t at[PU];  // where the piece starts in the lane's row of the image; DROPPED for none
+      uint32_t at[PU];
 #pragma unroll
       for (int q_ = 0; q_ < PU; ++q_) {
-        const uint2 e = es[d][q_];
         uint32_t s_int, z1, m2;
+        at[q_] = r.at[d][q_];
         if constexpr (AL) {
-          const uint32_t w = ma[d][q_];
-          if (two[d]) {
-            const uint32_t pos = e.y & 3u;
+          const uint32_t w = r.ma[d][q_];
+          if (r.two[d]) {
+            const uint32_t pos = at[q_] & 3u;
             z1 = (w >> (2u * pos)) & 3u;
             s_int = pos == 0 ? (w >> 6) & 15u : (w >> (pos == 1 ? 10u : 13u)) & 7u;
           } else {
             s_int = w & 15u;
             z1 = w >> 4;
           }
-          const half_t z2 = (half_t)(float)mc[d][q_];  // 0..15: exact
-          m2 = mb[d][q_] | ((uint32_t)half_to_bits(z2) << 16);
+          if (at[q_] != DROPPED) at[q_] &= ~3u;
+          const half_t z2 = (half_t)(float)r.mc[d][q_];  // 0..15: exact
+          m2 = r.mb[d][q_] | ((uint32_t)half_to_bits(z2) << 16);
         } else {
-          s_int = ma[d][q_] & 0xFFu;
-          z1 = ma[d][q_] >> 8;
-          m2 = mb[d][q_];
+          s_int = r.ma[d][q_] & 0xFFu;
+          z1 = r.ma[d][q_] >> 8;
+          m2 = r.mb[d][q_];
         }
         const half_t s1 = scale_dequant(s_int, m2);
         s1p[q_] = half2_t{s1, s1};
         zb[q_] = bits_to_half((uint16_t)(0x6400u | z1));  // 1024 + z1
-        at[q_] = (e.y >> 16) != pad_entry ? (uint32_t)i * ROWB + (e.x - x0_req) : DROPPED;
       }
 #define MPQ_DL_STEP(TWO, P)                                                                      \
   {                                                                                              \
@@ -2102,7 +2102,7 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
     const uint4 v = decode_step<TWO, P>(lo, hi, s1p[Q], zb[Q], kc);                              \
     if (at[Q] != DROPPED) *(uint4*)(out + at[Q] + ((P) % SPP) * 16) = v;                         \
   }
-      if (two[d]) {
+      if (r.two[d]) {
         const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
         MPQ_DL_STEP(true, 0) MPQ_DL_STEP(true, 1) MPQ_DL_STEP(true, 2) MPQ_DL_STEP(true, 3)
         MPQ_DL_STEP(true, 4) MPQ_DL_STEP(true, 5) MPQ_DL_STEP(true, 6) MPQ_DL_STEP(true, 7)
@@ -2114,24 +2114,24 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
     }
   };
 
-  int item = blockIdx.x;
-  if (item < total) request(item, 0);
-  for (; item < total; item += gridDim.x) {
+  // one range: decode, the set's next requests, outliers, stores
+  const int step = (int)gridDim.x;
+  auto range = [&](Set& r, const int item) {
     const int t = item / nch, k = item - t * nch;
-    decode();
+    decode(r);
     {  // ranges of more than 16 passes (most of a long range 4-bit)
       const int c2lo = cut2[k], c2hi = cut2[k + 1], c4lo = cut4[k], c4hi = cut4[k + 1];
       const int n2u = c2hi > c2lo ? (c2hi + PP2 - 1) / PP2 - c2lo / PP2 : 0, n4u = c4hi > c4lo ? (c4hi + PP4 - 1) / PP4 - c4lo / PP4 : 0;
       const int passes = ((n2u + 3) >> 2) + ((n4u + 3) >> 2);
-      for (int batch = 1; batch * 4 * D < passes; ++batch) {
-        request(item, batch);
-        decode();
+      for (int batch = 1; batch * 4 * D < passes; ++batch) {  // (leaves the set's outlier words alone)
+        request(r, item, batch);
+        decode(r);
       }
     }
     lds_barrier();
     const uint32_t x0 = (uint32_t)k * (2u * KC);
-    const uint32_t of_cur = ofirst, oc_cur = ocount, ow0 = oword[0], ow1 = oword[1];
-    if (item + (int)gridDim.x < total) request(item + (int)gridDim.x, 0);
+    const uint32_t of_cur = r.ofirst, oc_cur = r.ocount, ow0 = r.oword[0], ow1 = r.oword[1];
+    if (item + 2 * step < total) request(r, item + 2 * step, 0);
     if constexpr (ADD) {
       auto add_outlier = [&](const uint32_t word) {
         const uint32_t rel = (word & 0xFFFFu) - (uint32_t)k * KC;
@@ -2155,16 +2155,25 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
     for (int rr = 0; rr < 4; ++rr) {
-      const uint32_t r = (uint32_t)(4 * wv + rr);
+      const uint32_t row = (uint32_t)(4 * wv + rr);
 #pragma unroll
       for (int n = 0; n < 2 * KC / 1024; ++n) {
         const uint32_t o = (uint32_t)n * 1024u + (uint32_t)lane * 16u;
-        const uint4 v = *(const uint4*)(out + r * ROWB + o);
-        const uint32_t at = o < cb ? r * row_bytes + x0 + o : DROPPED;
+        const uint4 v = *(const uint4*)(out + row * ROWB + o);
+        const uint32_t at = o < cb ? row * row_bytes + x0 + o : DROPPED;
         __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{v.x, v.y, v.z, v.w}, out_rows, (int)at, 0, 2);
       }
     }
     lds_barrier();
+  };
+
+  Set sa, sb;
+  int item = blockIdx.x;
+  if (item < total) request(sa, item, 0);
+  if (item + step < total) request(sb, item + step, 0);
+  for (; item < total; item += 2 * step) {
+    range(sa, item);
+    if (item + step < total) range(sb, item + step);
   }
 }
 
