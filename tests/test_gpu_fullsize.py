@@ -161,3 +161,14 @@ def test_llama2_7b_shapes_at_the_papers_operating_point(torch, idx, meta):
     check_products(torch, lg, pk, blob, [1], all_rows=True)
     check_products(torch, lg, pk, blob, [4, 8, 32], all_rows=False)   # four pieces per unit in the batch kernels
     check_dequant_rows(torch, lg, pk, blob)
+
+
+@pytest.mark.parametrize("fmt", [(16, 16, 0.25, 1, 0), (16, 16, 0.25, 1, 1), (32, 16, 0.10, 0, 0)], ids=["g16", "g16_aligned", "g32"])
+def test_dequant_of_gate_up_with_narrow_groups(torch, fmt):
+    # 22016 x 4096, every row: 43 ranges of 16 rows x 2048 columns per workgroup, the launch that bench.py times
+    g1, g2, f4, axis, meta = fmt
+    base = synth.config_specs(1)[2]
+    lg = synth.make_matrix(synth.MatrixSpec(base.name, base.N, base.K, g1, g2, f4, 0.005, base.seed, axis, meta))
+    pk = mpq.pack_logical(lg)
+    check_dequant_rows(torch, lg, pk, to_dev(torch, pk.blob))
+
