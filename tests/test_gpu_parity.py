@@ -92,6 +92,7 @@ NARROW_CASES = [
     ("g16_long", 32, 24576, 16, 16, 0.25, 0.01, False, 1),               # unit table of 15 KiB: per-block kernel, table in LDS
     ("g16_long_aligned", 32, 24576, 16, 16, 0.25, 0.01, False, 1, 1),
     ("g32_longest", 16, 65504, 32, 16, 0.10, 0.005, False, 0),           # 21 KiB: per-block kernel, table read from memory
+    ("g16_only_4bit", 40, 2064, 16, 16, 1.0, 0.0, False, 1),             # no 2-bit stream at all
 ]
 
 
@@ -110,6 +111,20 @@ def test_dequant_of_narrow_groups(torch, case):
         ref = om.dequant(add)
         bad = np.argwhere(got != ref)
         assert bad.size == 0, (add, bad[:5], got[tuple(bad[0])], ref[tuple(bad[0])])
+
+
+@pytest.mark.parametrize("case", [("beyond_index", 16, 8192, 64, 16, 0.0, 0.6, False),
+                                  ("g16_beyond_index", 16, 8192, 16, 16, 0.1, 0.65, False, 1)], ids=["g64", "g16"])
+def test_dequant_of_a_tile_with_more_outliers_than_its_block_index_can_count(torch, case):
+    # more than 65535 outliers in one 16-row tile: the blob carries no outlier block index (16-bit entries), and the
+    # outliers are added to the finished matrix by a second kernel
+    lg, om, pk = make(case)
+    assert lg.row_ptr[-1] > 65535 and pk.header.view(np.uint64)[16] == 0   # oidx_off
+    blob = to_dev(torch, pk.blob)
+    for add in (False, True):
+        out = Guarded(torch, pk.N * pk.K)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+        assert np.array_equal(out.check_and_get().reshape(pk.N, pk.K), om.dequant(add)), add
 
 
 @pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
