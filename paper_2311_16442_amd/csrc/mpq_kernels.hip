@@ -1704,7 +1704,6 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
 #pragma clang fp contract(off)
   MPQ_TL_DECL
   MPQ_STAMP(0)
-  constexpr bool WHOLE = PU == 1;
   constexpr int PAIR = 144;  // LDS bytes per (row, unit): + 16 so that lanes fall into different banks
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;
   constexpr int D = PU == 1 ? 8 : 4;      // blocks per batch (10 or 4 + 6 PU registers per block)
@@ -1975,7 +1974,6 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
   __syncthreads();
   const DecodeConsts kc = make_consts();
   const uint32_t m1_lane = (uint32_t)i * 2u, m2_lane = b.off_m2 + ((uint32_t)i >> b.m2_shift) * 4u;
-  const uint32_t pad_entry = b.pad_entry;
   const uint32_t row_bytes = 2u * (uint32_t)b.K;
   const int total = b.T * nch;
   const int orow = tid >> 4, om = tid & 15;  // outliers: 16 threads per row, the rows of a wave are the ones it stores
