@@ -323,7 +323,12 @@ def main():
     if args.dequant is not None:
         layer.dequant = args.dequant
         layer.wout = torch.zeros(max(m["spec"].N * m["spec"].K for m in layer.mats), dtype=torch.int16, device=dev)
-        kernel_names = ["mpq_dequant_kernel"] * len(layer.mats)
+        # groups of 16 or 32 columns go through the kernel that writes whole output lines (unit tables of up to 14 KiB)
+        def dequant_kernel(m):
+            h = np.asarray(m["hdrs"][0]).view(np.int32)
+            table = 32 * (64 // m["spec"].g1) * int(h[13] + h[14]) if m["spec"].g1 < 64 else 0   # 32 bytes per piece and block
+            return "mpq_dequant_lines_kernel" if 0 < table <= 14336 else "mpq_dequant_kernel"
+        kernel_names = [dequant_kernel(m) for m in layer.mats]
         for m in layer.mats:      # what a dequantization moves: the packed bytes in, two bytes per weight out
             m["bytes"] = m["bytes"] - M * (2 * m["spec"].K + 2 * m["spec"].N) + 2 * m["spec"].N * m["spec"].K
         layer.step_bytes = sum(m["bytes"] for m in layer.mats)
