@@ -113,6 +113,30 @@ def test_dequant_of_narrow_groups(torch, case):
         assert bad.size == 0, (add, bad[:5], got[tuple(bad[0])], ref[tuple(bad[0])])
 
 
+def test_dequant_of_seeded_random_shapes(torch):
+    # 40 shapes drawn from a fixed seed: group widths, both axes and packings, group counts around the 2048-column
+    # ranges of the whole-line kernel (127 .. 130, 256, 257 groups of 16), rows from 1 to 100, 4-bit shares from 0 to 1
+    rng = np.random.default_rng(20231116)
+    for c in range(40):
+        g1 = int(rng.choice([16, 16, 32, 32, 64]))
+        meta = int(rng.integers(0, 2)) if g1 == 16 else 0
+        axis = int(rng.integers(0, 2))
+        g2 = int(rng.choice([4, 16] if axis == 1 else [1, 2, 4, 16]))
+        G = int(rng.choice([1, 2, 3, 5, 64, 127, 128, 129, 130, 200, 256, 257, 300, 384, 400, 512, 640]))
+        G = min(G, 160) if g1 == 64 else G
+        N = int(rng.choice([1, 5, 16, 17, 31, 32, 48, 100]))
+        f4 = float(rng.choice([0.0, 0.05, 0.25, 0.5, 0.9, 1.0]))
+        p_o = float(rng.choice([0.0, 0.005, 0.02, 0.1]))
+        case = (f"r{c}", N, G * g1, g1, g2, f4, p_o, False, axis, meta)
+        print("case", case, flush=True)
+        lg, om, pk = make(case)
+        blob = to_dev(torch, pk.blob)
+        for add in (False, True):
+            out = Guarded(torch, pk.N * pk.K)
+            mpq.dequant(pk.header, blob, out.view, add_outliers=add)
+            assert np.array_equal(out.check_and_get().reshape(pk.N, pk.K), om.dequant(add)), (case, add)
+
+
 @pytest.mark.parametrize("case", [("beyond_index", 16, 8192, 64, 16, 0.0, 0.6, False),
                                   ("g16_beyond_index", 16, 8192, 16, 16, 0.1, 0.65, False, 1)], ids=["g64", "g16"])
 def test_dequant_of_a_tile_with_more_outliers_than_its_block_index_can_count(torch, case):
