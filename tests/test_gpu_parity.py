@@ -170,6 +170,41 @@ def test_gemv_within_tolerance(torch, case):
     assert np.array_equal(y2.check_and_get(), got)
 
 
+def test_products_of_seeded_random_shapes(torch):
+    # 30 shapes drawn from a fixed seed, each at M = 1 and two batch sizes from 2 to 32: every group width, both axes
+    # and packings, 1 to 4096 rows, K from one group to 25600 columns, 4-bit shares from 0 to 1
+    rng = np.random.default_rng(2311_16442)
+    worst = 0.0
+    for c in range(30):
+        g1 = int(rng.choice([16, 32, 64, 64, 128]))
+        meta = int(rng.integers(0, 2)) if g1 == 16 else 0
+        axis = int(rng.integers(0, 2))
+        g2 = int(rng.choice([4, 16] if axis == 1 else [1, 2, 4, 16]))
+        G = int(rng.choice([1, 2, 3, 5, 16, 31, 64, 65, 100, 128, 172, 200]))
+        N = int(rng.choice([1, 5, 16, 17, 48, 100, 256, 1000, 4096]))
+        N = 256 if N * G * g1 > 40e6 else N
+        f4 = float(rng.choice([0.0, 0.1, 0.25, 0.5, 1.0]))
+        p_o = float(rng.choice([0.0, 0.005, 0.015]))
+        Ms = [1] + [int(m) for m in rng.choice([2, 3, 4, 7, 8, 9, 12, 16, 17, 24, 31, 32], size=2, replace=False)]
+        case = (f"r{c}", N, G * g1, g1, g2, f4, p_o, False, axis, meta)
+        print("case", case, Ms, flush=True)
+        lg, om, pk = make(case)
+        blob = to_dev(torch, pk.blob)
+        for M in Ms:
+            X = synth.make_x(77 + c + M, M, pk.K)
+            Y = Guarded(torch, M * pk.N)
+            if M == 1:
+                mpq.gemv(pk.header, blob, to_dev(torch, X[0].view(np.int16)), Y.view)
+            else:
+                ws = Workspace(torch, mpq, pk.header, M)
+                mpq.gemm(pk.header, blob, to_dev(torch, X.view(np.int16)), Y.view, M, workspace=ws.view)
+                ws.check()
+            e_floor, e_max = rel_err(Y.check_and_get().reshape(M, pk.N), om.gemm(X, threads=8))
+            worst = max(worst, e_floor)
+            assert e_floor <= TOL, (case, M, e_floor, e_max)
+    print("worst error", worst)
+
+
 def test_gemv_exact_for_integer_problem(torch):
     # identity scales and small integer activations: y = codes @ x in integers, exactly representable
     lg = synth.make_matrix(synth.MatrixSpec("int", 64, 256, 64, 2, 0.25, 0.0, 31))
