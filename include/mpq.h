@@ -197,7 +197,11 @@ mpq_status mpq_dequant(const void* hdr_host, const void* blob_dev, uint16_t* W_o
 
 /* Algorithm 1 (GEMV with asynchronous dequantization) with the outlier product of Sec. 4.3 fused
  * in: y[n] = fp16( sum_k Wd[n][k] x[k] + sum_j val_j x[col_j] ), fp32 accumulation.
- * x_dev: K fp16 values, y_dev: N fp16 values (overwritten), both 16-byte aligned, not aliased. */
+ * x_dev: K fp16 values, y_dev: N fp16 values (overwritten), both 16-byte aligned, not aliased.
+ * The kernels stage a tile's scale words and outlier words (4 bytes per outlier, the fullest 16-row tile of the
+ * matrix counts) in on-chip memory next to the activations: a matrix whose fullest tile does not fit there -
+ * tens of thousands of outliers in 16 rows, far beyond the 0.2-0.5 % of Sec. 4.3 - is MPQ_ERR_UNSUPPORTED in
+ * mpq_gemv and the batch products (nothing is launched); mpq_dequant has no such limit. */
 mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* x_dev,
                     uint16_t* y_dev, void* stream);
 
