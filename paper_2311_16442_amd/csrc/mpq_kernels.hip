@@ -1938,7 +1938,7 @@ mpq_dequant_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int dc, c
 // range of each stream, found by bisection of the unit table once per workgroup) into an LDS image of the
 // output, add the outliers there (the address is the column, no search), and write whole lines, 1 KiB of a row per
 // instruction, non-temporal.  Units that straddle a range are decoded by both neighbours, each keeping its own
-// pieces.  The requests of the next range go out before the stores of this one.
+// pieces.  The requests of a range go out while the range before the previous one is stored (two register sets).
 template <int PU, bool AL, bool ADD, int KC, int TB>
 __global__ void __launch_bounds__(256)
 mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int np2, const int np4, const uint32_t pad_y2,
