@@ -33,7 +33,8 @@
  *
  * Errors.  Every entry point returns an mpq_status; nothing is launched unless all arguments
  * validate.  No entry point throws or aborts.  MPQ_ERR_HIP reports the status of the call's own
- * launches only (an error an earlier HIP call of the caller left pending is cleared, not reported);
+ * launches only, taken from the launch calls' return values: the thread's HIP last-error state is neither
+ * read nor cleared, so an error an earlier HIP call of the caller left pending is not reported and stays pending;
  * after MPQ_ERR_HIP the output buffer is undefined, since an entry point that needs two kernels may
  * have enqueued the first.
  */

@@ -2224,13 +2224,22 @@ namespace {
 
 const mpq_plan kAutoPlan = {};
 
-// Launch status of THIS launch only: an error some earlier HIP call of the caller left behind is
-// cleared before the launch and so neither reported as ours nor lost to a later check of theirs.
+// Launch status of THIS launch only, from the launch call's own return value: the library neither reads nor
+// clears the thread's last-error state, so an error some earlier HIP call of the caller left behind is not
+// reported as ours and is still there for the caller to find.
+template <typename T>
+struct SameType {
+  using type = T;
+};
+template <typename... KArgs>
+inline hipError_t launch_kernel(void (*kernel)(KArgs...), const dim3 grid, const dim3 block, const size_t lds_bytes, hipStream_t stream,
+                                typename SameType<KArgs>::type... args) {
+  void* ptrs[] = {(void*)&args...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, stream);
+}
 #define MPQ_LAUNCH(...)                                                   \
   do {                                                                    \
-    (void)hipGetLastError();                                              \
-    hipLaunchKernelGGL(__VA_ARGS__);                                      \
-    if (hipGetLastError() != hipSuccess) return MPQ_ERR_HIP;              \
+    if (launch_kernel(__VA_ARGS__) != hipSuccess) return MPQ_ERR_HIP;     \
   } while (0)
 
 mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, DevBlob* d) {
@@ -2269,10 +2278,8 @@ mpq_status make_dev(const void* hdr_host, const void* blob_dev, MpqHeader* h, De
 mpq_status cu_count(int* cus) {
   int dev = 0, n = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      n <= 0) {
-    (void)hipGetLastError();
+      n <= 0)
     return MPQ_ERR_HIP;
-  }
   *cus = n;
   return MPQ_OK;
 }
@@ -2699,16 +2706,10 @@ std::atomic<void*> g_scratch_addr[kMaxDevices];  // device address of `scratch` 
 
 mpq_status static_scratch(void** out) {
   int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-    (void)hipGetLastError();
-    return MPQ_ERR_HIP;
-  }
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MPQ_ERR_HIP;
   void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
   if (!p) {
-    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
-      (void)hipGetLastError();
-      return MPQ_ERR_HIP;
-    }
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MPQ_ERR_HIP;
     g_scratch_addr[dev].store(p, std::memory_order_release);  // every thread that asks gets the same answer
   }
   *out = p;

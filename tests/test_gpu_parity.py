@@ -464,6 +464,34 @@ def test_large_batch_kernel_in_a_graph_and_without_workspace(torch):
         assert rel_err(Yn.check_and_get().reshape(M, pk.N), ref)[0] <= TOL
 
 
+def test_a_pending_hip_error_of_the_caller_is_neither_reported_nor_cleared(torch):
+    # the library judges its launches by the launch calls' return values and leaves the thread's last-error state alone
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipSetDevice.restype = hip.hipGetLastError.restype = hip.hipPeekAtLastError.restype = ctypes.c_int
+    lg, om, pk = make(CASES[0])
+    blob = to_dev(torch, pk.blob)
+    X = synth.make_x(5, 4, pk.K)
+    x = to_dev(torch, X.view(np.int16))
+    ws = Workspace(torch, mpq, pk.header, 4)
+    y, Y, out, x1 = Guarded(torch, pk.N), Guarded(torch, 4 * pk.N), Guarded(torch, pk.N * pk.K), x[:pk.K].contiguous()
+    torch.cuda.synchronize()
+    hip.hipGetLastError()                                 # start from a clean state
+    err = hip.hipSetDevice(9999)                          # refused on the host: no such device
+    assert err != 0 and hip.hipPeekAtLastError() == err
+    # (no torch call from here to the caller's own hipGetLastError: torch would find the error and raise)
+    try:
+        mpq.gemv(pk.header, blob, x1, y.view)             # raises on any status other than MPQ_OK
+        mpq.gemm(pk.header, blob, x, Y.view, 4, workspace=ws.view)
+        mpq.dequant(pk.header, blob, out.view, add_outliers=True)
+    finally:
+        pending, after = hip.hipGetLastError(), hip.hipGetLastError()   # the caller's own check, which clears it
+    assert pending == err and after == 0                  # it was still there for the caller
+    assert rel_err(y.check_and_get(), om.gemm(X[:1], threads=8)[0])[0] <= TOL
+    assert rel_err(Y.check_and_get().reshape(4, pk.N), om.gemm(X, threads=8))[0] <= TOL
+    assert np.array_equal(out.check_and_get().reshape(pk.N, pk.K), om.dequant(True))
+
+
 def test_workspace_sizes_on_the_device(torch):
     # nothing for M = 1, partial sums for every range plus the transposed activations otherwise, growing
     # with the batch and with the number of ranges a plan asks for
