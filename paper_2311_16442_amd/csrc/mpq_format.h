@@ -149,12 +149,13 @@ static inline uint32_t mpq_p_off_outl(const MpqHeader* h) { return mpq_p_off_z2(
 #ifdef __cplusplus
 static_assert(sizeof(MpqHeader) == 256, "header must be 256 bytes");
 #include "../../include/mpq.h"
+// (The two functions below are shared by the library's two source files and are not exported.)
 // Accepts a header only if it is byte for byte what the packer writes for the shape it records
 // (the bitmap of 4-bit groups must have n4 bits set, none at or beyond G).
-mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out);
+__attribute__((visibility("hidden"))) mpq_status mpq_internal_check_header(const void* hdr_host, MpqHeader* out);
 // Word 1 (meta1 offset | meta2 offset << 16) of the table entries of the 4 * (B2 + B4) units, from the
 // header alone; false if the header carries no bitmap or a unit holds several groups (g1 < 64).
-bool mpq_internal_unit_words(const MpqHeader* h, uint32_t* words);
+__attribute__((visibility("hidden"))) bool mpq_internal_unit_words(const MpqHeader* h, uint32_t* words);
 #endif
 
 #endif /* MPQ_FORMAT_H_ */

@@ -2177,7 +2177,7 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
 
 // W[row][col] = fp16(W[row][col] + val) for every outlier word of the tile (native fp16 add = the
 // fp32 add followed by one rounding that the definition states); 16 threads per row.
-__global__ void __launch_bounds__(256)
+static __global__ void __launch_bounds__(256)
 mpq_outlier_add_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
   const int orow = threadIdx.x >> 4, oq = threadIdx.x & 15;
   const int row = blockIdx.x * 16 + orow;
@@ -2198,7 +2198,7 @@ mpq_outlier_add_kernel(const DevBlob b, uint16_t* __restrict__ Wout) {
 // Reads `n16` 16-byte words once and does nothing else: what the memory system delivers to a kernel of
 // this size and launch pattern, the figure the product kernels' throughput is set against.  Every
 // workgroup walks its own contiguous part, eight 16-byte loads per lane in flight.
-__global__ void __launch_bounds__(256)
+static __global__ void __launch_bounds__(256)
 mpq_stream_kernel(const uint4* __restrict__ src, const size_t n16, uint32_t* __restrict__ sink) {
   const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
   const size_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
@@ -2704,7 +2704,7 @@ namespace {
 constexpr int kMaxDevices = 64;
 std::atomic<void*> g_scratch_addr[kMaxDevices];  // device address of `scratch` on each device, once known
 
-mpq_status static_scratch(void** out) {
+static mpq_status static_scratch(void** out) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MPQ_ERR_HIP;
   void* p = g_scratch_addr[dev].load(std::memory_order_acquire);

@@ -25,6 +25,18 @@ def test_library_exports_every_declared_symbol():
     assert mpq.status_str(0) == "ok" and mpq.status_str(5).startswith("outlier")
 
 
+def test_library_exports_no_other_function():
+    """Nothing but the calls that mpq.h declares is a global function of the shared object (the kernels' weak
+    handles, which the HIP runtime registers, are not functions a caller could link against)."""
+    import shutil
+    import subprocess
+    if not shutil.which("nm"):
+        pytest.skip("nm not available")
+    out = subprocess.run(["nm", "-D", "--defined-only", mpq.LIB_PATH], check=True, capture_output=True, text=True).stdout
+    functions = sorted(line.split()[2] for line in out.splitlines() if len(line.split()) == 3 and line.split()[1] == "T")
+    assert functions == sorted(mpq.EXPORTS)
+
+
 def test_timeline_build_adds_only_its_buffer_call():
     """The timeline build is the product sources plus phase stamps: the same exports and mpq_timeline_buffer."""
     import ctypes
