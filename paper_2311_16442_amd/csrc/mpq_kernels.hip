@@ -2645,9 +2645,13 @@ mpq_status mm_all(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, void* ws,
     // pass over the weights per chunk and a per-column outlier loop that weighs from M = 9 on.
     // Measured on the Llama2-7B and Llama2-70B shapes, M = 2..32, outlier fractions 0 / 0.5 / 1.5 %:
     // up to M = 8 the large-batch kernel wins from three chunks on, and with two chunks unless the
-    // matrix is small; above, whenever there are two chunks or the matrix is not small.
+    // matrix is small; above, whenever there are two chunks or the matrix is not small.  "Small" is below 12 MB,
+    // and below 24 MB where the whole batch fits next to 8 or 16 waves in one chunk (M = 9 to 14 at K = 4096:
+    // 12288 x 4096, 17.7 MB, 13.4-13.9 us with 16 waves and 15.3 with 8 against 16.3-16.5 us; 22016 x 4096, 31.7 MB,
+    // 23.1-23.8 and 26.2 against 23.8-24.4 us).
     const int chunks = (M + Mc - 1) / Mc;
-    const bool large = h.total_bytes >= (12u << 20);
+    const bool many_waves = mpq_pu2(h.g1) == 1 && (mm_lds_bytes(h, M, 2, 16) <= 160 * 1024 || mm_lds_bytes(h, M, 3, 8) <= 160 * 1024);
+    const bool large = h.total_bytes >= ((M > 8 && chunks == 1 && many_waves ? 24u : 12u) << 20);
     const bool better = M <= 8 ? chunks >= 3 || (chunks == 2 && large) : chunks >= 2 || large;
     if (c.plan.large_batch == 0 ? better : c.plan.large_batch > 0) {
       const mpq_status st = launch_slices(c, X, Y, M, ws, ws_bytes);

@@ -172,3 +172,11 @@ def test_dequant_of_gate_up_with_narrow_groups(torch, fmt):
     pk = mpq.pack_logical(lg)
     check_dequant_rows(torch, lg, pk, to_dev(torch, pk.blob))
 
+
+
+@pytest.mark.parametrize("M", [9, 12, 14])
+def test_llama2_7b_qkv_at_batches_that_fit_one_chunk(torch, M):
+    # 12288 x 4096 (17.7 MB) with 9 to 14 activation rows: the resident-activation kernel with 16 or 8 waves
+    lg = synth.make_matrix(synth.config_specs(1)[0])
+    pk = mpq.pack_logical(lg)
+    check_products(torch, lg, pk, to_dev(torch, pk.blob), [M], all_rows=False)
