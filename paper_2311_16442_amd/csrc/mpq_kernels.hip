@@ -584,7 +584,36 @@ __device__ __forceinline__ void ring_read(uint32_t code_addr, uint32_t meta_addr
   }
 }
 
-template <int NT, int XR, int LDSB, int WV, int PU>
+// The same for the aligned metadata (groups of 16 columns, four pieces per 2-bit unit and two per 4-bit unit): three
+// dwords per piece - the one that holds its 16-bit triple word or its 4-bit group's byte, the one that holds its
+// fp16 second-order scale and the one that holds its second-order zero byte - at byte 1024 + 256 q,
+// 1024 + 256 (4 + q) and 1024 + 256 (8 + q) of the slot.
+template <int NP>
+__device__ __forceinline__ void ring_read_aligned(uint32_t code_addr, uint32_t meta_addr, uint4& q, uint32_t (&w1)[NP],
+                                                  uint32_t (&w2)[NP], uint32_t (&w3)[NP]) {
+  static_assert(NP == 2 || NP == 4, "pieces per unit");
+  if constexpr (NP == 2) {
+    asm volatile("ds_read_b128 %0, %7\n\tds_read_b32 %1, %8\n\tds_read_b32 %2, %8 offset:256\n\t"
+                 "ds_read_b32 %3, %8 offset:1024\n\tds_read_b32 %4, %8 offset:1280\n\t"
+                 "ds_read_b32 %5, %8 offset:2048\n\tds_read_b32 %6, %8 offset:2304\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(q), "=&v"(w1[0]), "=&v"(w1[1]), "=&v"(w2[0]), "=&v"(w2[1]), "=&v"(w3[0]), "=&v"(w3[1])
+                 : "v"(code_addr), "v"(meta_addr)
+                 : "memory");
+  } else {
+    asm volatile("ds_read_b128 %0, %13\n\tds_read_b32 %1, %14\n\tds_read_b32 %2, %14 offset:256\n\t"
+                 "ds_read_b32 %3, %14 offset:512\n\tds_read_b32 %4, %14 offset:768\n\t"
+                 "ds_read_b32 %5, %14 offset:1024\n\tds_read_b32 %6, %14 offset:1280\n\t"
+                 "ds_read_b32 %7, %14 offset:1536\n\tds_read_b32 %8, %14 offset:1792\n\t"
+                 "ds_read_b32 %9, %14 offset:2048\n\tds_read_b32 %10, %14 offset:2304\n\t"
+                 "ds_read_b32 %11, %14 offset:2560\n\tds_read_b32 %12, %14 offset:2816\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(q), "=&v"(w1[0]), "=&v"(w1[1]), "=&v"(w1[2]), "=&v"(w1[3]), "=&v"(w2[0]), "=&v"(w2[1]), "=&v"(w2[2]),
+                   "=&v"(w2[3]), "=&v"(w3[0]), "=&v"(w3[1]), "=&v"(w3[2]), "=&v"(w3[3])
+                 : "v"(code_addr), "v"(meta_addr)
+                 : "memory");
+  }
+}
+
+template <int NT, int XR, int LDSB, int WV, int PU, bool AL = false>
 __global__ void __launch_bounds__(WV * 64)
 mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restrict__ P, uint16_t* __restrict__ XT,
                const int M, const SlicePlan pl) {
@@ -593,8 +622,10 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   static_assert(XR == 8 || XR == 16 * NT, "staged rows");
   constexpr uint32_t W = WV, PD = 2, RMAX = 8;
   constexpr int PU4 = PU > 1 ? PU / 2 : 1;            // pieces per 2-bit unit (PU) and per 4-bit unit
-  constexpr uint32_t SLOTB = 1024 + 512 * PU;          // ring slot: codes | PU meta1 dwords per lane | PU meta2 dwords per lane
-  constexpr uint32_t OPS = 1 + 2 * PU;                 // direct loads per block
+  static_assert(!AL || PU == 4, "the aligned metadata comes with groups of 16 columns");
+  constexpr uint32_t MW = AL ? 3 : 2;                  // dwords of scale words per lane and piece
+  constexpr uint32_t SLOTB = 1024 + 256 * MW * PU;     // ring slot: codes | PU meta1 dwords per lane | PU meta2 dwords per lane (| PU more)
+  constexpr uint32_t OPS = 1 + MW * PU;                // direct loads per block
   constexpr uint32_t TP = 2 / NT;  // tiles parked at a time (2 KiB per wave)
   __shared__ __align__(16) unsigned char lds[LDSB];
   const uint32_t tid = threadIdx.x;
@@ -686,8 +717,16 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
        others are padding entries that point at the zero words of the tile) */          \
     _Pragma("unroll") for (uint32_t qq = 0; qq < (uint32_t)PU; ++qq) {                  \
       const uint32_t uy = *(const uint32_t*)(units + ((blk * 4u + j) * PU + qq) * 8u + 4u); \
-      dma4(tb, ((uy & 0xFFFFu) + i * 2u) & ~3u, dst + 1024u + qq * 256u);               \
-      dma4(tb, m2lane + (uy >> 16), dst + 1024u + PU * 256u + qq * 256u);               \
+      if constexpr (AL) { /* Sec. 3.3 "Memory Alignment": triple word or 4-bit group's byte, second-order scale, zero byte */ \
+        const uint32_t a1 = r_c < n2 ? (uy & 0xFFFCu) + i * 2u : b.off_m1b + (uy & 0xFFFFu) + i; \
+        const uint32_t idx = (uy >> 16) + (i >> b.m2_shift);                            \
+        dma4(tb, a1 & ~3u, dst + 1024u + qq * 256u);                                    \
+        dma4(tb, (b.off_s2 + 2u * idx) & ~3u, dst + 1024u + PU * 256u + qq * 256u);     \
+        dma4(tb, (b.off_z2 + idx) & ~3u, dst + 1024u + 2u * PU * 256u + qq * 256u);     \
+      } else {                                                                          \
+        dma4(tb, ((uy & 0xFFFFu) + i * 2u) & ~3u, dst + 1024u + qq * 256u);             \
+        dma4(tb, m2lane + (uy >> 16), dst + 1024u + PU * 256u + qq * 256u);             \
+      }                                                                                 \
     }                                                                                   \
     ++inflight;                                                                         \
     ++r_s;                                                                              \
@@ -757,22 +796,45 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
   }
 // Fetch of the wave's next block: wait for it, read codes and the NP meta word pairs from its ring
 // slot, refill the slot, reconstruct (s1, z1) of every piece.
-#define MPQ_S_HEAD(NP)                                                                                 \
+#define MPQ_S_HEAD(NP, TWO)                                                                            \
   if (inflight == PD) MPQ_VMCNT(OPS * (PD - 1));                                                      \
   else MPQ_VMCNT(0); /* PD = 2: nothing else of this wave can be in flight */                         \
   uint4 q;                                                                                            \
-  uint32_t w1[NP], w2[NP];                                                                            \
-  ring_read<NP, PU>(slot_lane + slot * SLOTB, meta_lane + slot * SLOTB, q, w1, w2);                   \
+  uint32_t w1[NP], w2[NP], w3[AL ? NP : 1];                                                           \
+  if constexpr (AL) ring_read_aligned<NP>(slot_lane + slot * SLOTB, meta_lane + slot * SLOTB, q, w1, w2, w3); \
+  else ring_read<NP, PU>(slot_lane + slot * SLOTB, meta_lane + slot * SLOTB, q, w1, w2);              \
   --inflight;                                                                                         \
   if (r_g < ngroups) MPQ_S_REQUEST(slot)                                                              \
   slot = slot + 1 == PD ? 0 : slot + 1;                                                               \
   half2_t s1p[NP];                                                                                    \
   half_t zb[NP];                                                                                      \
   _Pragma("unroll") for (int qq = 0; qq < NP; ++qq) {                                                 \
-    const uint32_t m1 = (i & 1u) ? w1[qq] >> 16 : w1[qq] & 0xFFFFu;                                   \
-    const half_t s1 = scale_dequant(m1 & 0xFFu, w2[qq]);  /* exactly 0 for a padding piece */          \
-    s1p[qq] = half2_t{s1, s1};                                                                        \
-    zb[qq] = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                           \
+    if constexpr (AL) {                                                                               \
+      /* the piece's table word again: where in its dwords the lane's values sit */                   \
+      const uint32_t blk_ = (TWO) ? a2 + c : B2 + a4 + (c - n2);                                      \
+      const uint32_t uy = *(const uint32_t*)(units + ((blk_ * 4u + j) * PU + qq) * 8u + 4u);          \
+      const uint32_t idx = (uy >> 16) + (i >> b.m2_shift);                                            \
+      uint32_t s_int, z1;                                                                             \
+      if (TWO) {                                                                                      \
+        const uint32_t w = (i & 1u) ? w1[qq] >> 16 : w1[qq] & 0xFFFFu, pos = uy & 3u;                  \
+        z1 = (w >> (2u * pos)) & 3u;                                                                  \
+        s_int = pos == 0 ? (w >> 6) & 15u : (w >> (pos == 1 ? 10u : 13u)) & 7u;                       \
+      } else {                                                                                        \
+        const uint32_t w = (w1[qq] >> (8u * ((b.off_m1b + (uy & 0xFFFFu) + i) & 3u))) & 0xFFu;        \
+        s_int = w & 15u;                                                                              \
+        z1 = w >> 4;                                                                                  \
+      }                                                                                               \
+      const uint32_t s2 = ((b.off_s2 + 2u * idx) & 2u) ? w2[qq] >> 16 : w2[qq] & 0xFFFFu;             \
+      const half_t z2 = (half_t)(float)((w3[qq] >> (8u * ((b.off_z2 + idx) & 3u))) & 0xFFu); /* 0..15: exact */ \
+      const half_t s1 = scale_dequant(s_int, s2 | ((uint32_t)half_to_bits(z2) << 16));  /* exactly 0 for a padding piece */ \
+      s1p[qq] = half2_t{s1, s1};                                                                      \
+      zb[qq] = bits_to_half((uint16_t)(0x6400u | z1));                                                \
+    } else {                                                                                          \
+      const uint32_t m1 = (i & 1u) ? w1[qq] >> 16 : w1[qq] & 0xFFFFu;                                 \
+      const half_t s1 = scale_dequant(m1 & 0xFFu, w2[qq]);  /* exactly 0 for a padding piece */        \
+      s1p[qq] = half2_t{s1, s1};                                                                      \
+      zb[qq] = bits_to_half((uint16_t)(0x6400u | (m1 >> 8)));                                         \
+    }                                                                                                 \
   }                                                                                                   \
   const uint32_t lo[4] = {q.x, q.y, q.z, q.w};
 
@@ -796,7 +858,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #pragma unroll
         for (uint32_t tt = 0; tt < RMAX; ++tt) {
           if (tt >= t && tt < t_end) {
-            MPQ_S_HEAD(PU)
+            MPQ_S_HEAD(PU, true)
             const uint32_t hi[4] = {rotr8(q.x), rotr8(q.y), rotr8(q.z), rotr8(q.w)};
             MPQ_S_STEP(true, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 1, acc[tt][0], acc[tt][1])
             MPQ_S_STEP(true, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(true, 3, acc[tt][0], acc[tt][1])
@@ -814,7 +876,7 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
 #pragma unroll
         for (uint32_t tt = 0; tt < RMAX; ++tt) {
           if (tt >= t && tt < t_end) {
-            MPQ_S_HEAD(PU4)
+            MPQ_S_HEAD(PU4, false)
             const uint32_t hi[4] = {q.x >> 8, q.y >> 8, q.z >> 8, q.w >> 8};
             MPQ_S_STEP(false, 0, acc[tt][0], acc[tt][1]) MPQ_S_STEP(false, 1, acc[tt][0], acc[tt][1])
             MPQ_S_STEP(false, 2, acc[tt][0], acc[tt][1]) MPQ_S_STEP(false, 3, acc[tt][0], acc[tt][1])
@@ -2546,11 +2608,12 @@ mpq_status mm_chunk(const Ctx& c, const uint16_t* X, uint16_t* Y, int M) {
 bool plan_slices(const MpqHeader& h, const mpq_plan& plan, int cus_i, int M, uint32_t W, uint32_t budget, SlicePlan* pl,
                  int* XR_out) {
   const uint32_t PU = (uint32_t)mpq_pu2(h.g1);
+  const uint32_t MW = h.meta == MPQ_META_PAPER ? 3u : 2u;  // dwords of scale words per lane and piece in a ring slot
   const uint32_t NT = M > 16 ? 2 : 1, XR = M <= 8 ? 8 : 16 * NT;
   const uint32_t B2 = (uint32_t)h.B2, B4 = (uint32_t)h.B4;
   const uint32_t maxH = B2 > B4 ? B2 : B4;
   const uint32_t cus = (uint32_t)cus_i;
-  uint32_t off = W * 2u * (1024u + 512u * PU);
+  uint32_t off = W * 2u * (1024u + 256u * MW * PU);
   pl->off_units = off; off += (32u * PU * (B2 + B4) + 15u) & ~15u;
   pl->off_park = off;  off += W * 2048u;
   off = (off + 1023u) & ~1023u;
@@ -2591,7 +2654,6 @@ mpq_status launch_slices(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, vo
   // operands of a position and up to 8 x NT accumulators stay in registers); 16 waves, with half
   // the registers and a third less LDS for the activations, measured equal or slower on every shape
   const int pu = mpq_pu2(h.g1);
-  if (h.meta != MPQ_META_BYTES) return MPQ_ERR_UNSUPPORTED;  // the K-range kernel gathers byte-wide scale words
   if (!plan_slices(h, c.plan, c.cus, M, 8, 160 * 1024, &pl, &XR)) return MPQ_ERR_UNSUPPORTED;
   size_t p_bytes = 0;
   if (!ws || ((uintptr_t)ws & 255u) != 0 || ws_bytes < slice_workspace_bytes(h, pl, NT, XR, &p_bytes)) return MPQ_ERR_UNSUPPORTED;
@@ -2603,7 +2665,13 @@ mpq_status launch_slices(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, vo
   MPQ_LAUNCH((mpq_mms_kernel<NTV, XRV, 160 * 1024, WV, PUV>), grid, dim3(WV * 64), 0, s, d, X, P, XT, M, pl)
 #define MPQ_LAUNCH_S8(PUV) \
   { if (XR == 8) MPQ_LAUNCH_S(1, 8, 8, PUV); else if (NT == 1) MPQ_LAUNCH_S(1, 16, 8, PUV); else MPQ_LAUNCH_S(2, 32, 8, PUV); }
-  if (pu == 1) MPQ_LAUNCH_S8(1) else if (pu == 2) MPQ_LAUNCH_S8(2) else MPQ_LAUNCH_S8(4)
+  if (pu == 1) MPQ_LAUNCH_S8(1) else if (pu == 2) MPQ_LAUNCH_S8(2) else if (h.meta != MPQ_META_PAPER) MPQ_LAUNCH_S8(4)
+  else {
+#define MPQ_LAUNCH_SA(NTV, XRV) \
+  MPQ_LAUNCH((mpq_mms_kernel<NTV, XRV, 160 * 1024, 8, 4, true>), grid, dim3(8 * 64), 0, s, d, X, P, XT, M, pl)
+    if (XR == 8) MPQ_LAUNCH_SA(1, 8); else if (NT == 1) MPQ_LAUNCH_SA(1, 16); else MPQ_LAUNCH_SA(2, 32);
+#undef MPQ_LAUNCH_SA
+  }
 #undef MPQ_LAUNCH_S8
 #undef MPQ_LAUNCH_S
   // from here on Y is undefined if the second launch fails: the first kernel is already enqueued
@@ -2650,8 +2718,13 @@ mpq_status mm_all(const Ctx& c, const uint16_t* X, uint16_t* Y, int M, void* ws,
     // 12288 x 4096, 17.7 MB, 13.4-13.9 us with 16 waves and 15.3 with 8 against 16.3-16.5 us; 22016 x 4096, 31.7 MB,
     // 23.1-23.8 and 26.2 against 23.8-24.4 us).
     const int chunks = (M + Mc - 1) / Mc;
-    const bool many_waves = mpq_pu2(h.g1) == 1 && (mm_lds_bytes(h, M, 2, 16) <= 160 * 1024 || mm_lds_bytes(h, M, 3, 8) <= 160 * 1024);
-    const bool large = h.total_bytes >= ((M > 8 && chunks == 1 && many_waves ? 24u : 12u) << 20);
+    // (groups of 16 or 32 columns: 8 waves; 12288 x 4096 at M = 12 with groups of 16, 22.8 MB: 16.6 against 18.7 us)
+    const bool many_waves = (mpq_pu2(h.g1) == 1 && mm_lds_bytes(h, M, 2, 16) <= 160 * 1024) || mm_lds_bytes(h, M, 3, 8) <= 160 * 1024;
+    // With the aligned metadata the K-range kernel gathers three words per piece instead of two and the bounds are
+    // 24 and 40 MB (22016 x 4096, 33.5 MB, at M = 12: 28.3 against 31.6 us; 12288 x 4096, 18.7 MB, at M = 16: 20.4
+    // against 21.7; 4096 x 11008, 16.7 MB, at M = 8 in two chunks: 20.3 against 22.5).
+    const bool al = h.meta == MPQ_META_PAPER;
+    const bool large = h.total_bytes >= ((M > 8 && chunks == 1 && many_waves ? (al ? 40u : 24u) : (al ? 24u : 12u)) << 20);
     // one chunk that leaves room for four waves only (M = 8 at K = 8192): 10240 x 8192, 25 MB, 24.9 against 20.5 us;
     // 8192 x 8192, 20 MB, 18.1 against 17.9; 4096 x 11008 at M = 5, 15.5 MB, 12.8 against 15.3
     const bool four_waves = mpq_pu2(h.g1) == 1 && chunks == 1 && !many_waves && h.total_bytes >= (20u << 20);
@@ -2749,7 +2822,7 @@ mpq_status mpq_gemm_workspace_size_planned(const void* hdr_host, int32_t M, cons
   SlicePlan pl;
   int XR = 0;
   size_t p_bytes = 0;
-  if (M > 1 && h.meta == MPQ_META_BYTES && plan_slices(h, plan ? *plan : kAutoPlan, cus, M, 8, 160 * 1024, &pl, &XR))
+  if (M > 1 && plan_slices(h, plan ? *plan : kAutoPlan, cus, M, 8, 160 * 1024, &pl, &XR))
     *bytes = slice_workspace_bytes(h, pl, M > 16 ? 2 : 1, XR, &p_bytes);
   return MPQ_OK;
 }

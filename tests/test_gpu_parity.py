@@ -43,7 +43,6 @@ CASES = [
     ("aligned_along_k", 272, 1520, 16, 4, 0.10, 0.01, False, 0, 1),         # 95 groups: a short last triple, ragged units
     ("aligned_rows4", 100, 2048, 16, 4, 0.30, 0.005, False, 1, 1),          # four blocks of rows per tile
 ]
-BYTE_META_CASES = [c for c in CASES if len(c) < 10 or c[9] == 0]
 
 
 def make(case):
@@ -395,7 +394,7 @@ def test_gemm_on_every_case(torch, case, M):
 
 @pytest.mark.parametrize("min_h", [0, 3])
 @pytest.mark.parametrize("M", [2, 7, 8, 9, 16, 17, 32])
-@pytest.mark.parametrize("case", BYTE_META_CASES, ids=[c[0] for c in BYTE_META_CASES])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
 def test_large_batch_kernel_within_tolerance(torch, case, M, min_h):
     # the kernel that keeps one K-range of the activations resident per workgroup and writes partial
     # sums that a second kernel adds up, forced for every batch size through a launch plan (by
