@@ -211,7 +211,7 @@ mpq_status mpq_gemv(const void* hdr_host, const void* blob_dev, const uint16_t* 
  * products that do not depend on each other - separate projections of a layer, the experts a token
  * is routed to - this saves the fixed cost of a launch per product.  The four arrays are HOST
  * arrays of `count` entries: header pointers (HOST), blob / x / y pointers (DEVICE).  The matrices
- * may differ in shape but must have the same g1; no y may alias anything else.
+ * may differ in shape but must have the same g1 and the same meta; no y may alias anything else.
  * MPQ_ERR_UNSUPPORTED if the products cannot share one launch configuration. */
 mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void* const* blob_dev,
                           const uint16_t* const* x_dev, uint16_t* const* y_dev, void* stream);

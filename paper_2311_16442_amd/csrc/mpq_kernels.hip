@@ -1293,14 +1293,14 @@ struct MultiArgs {
   int32_t count;
 };
 
-template <int PD, int LDSB, int WV, int PU = 1>
+template <int PD, int LDSB, int WV, int PU = 1, bool AL = false>
 __global__ void __launch_bounds__(WV * 64)
 mpq_gemv_multi_kernel(const MultiArgs a) {
   uint32_t p = 0;
   while ((int32_t)p + 1 < a.count && blockIdx.x >= a.first[p + 1]) ++p;
   const DevBlob b = a.b[p];
   const GemvLead lead = {b.tiles, b.units, a.X[p], b.tile_stride, b.side_bytes, b.codes_off, (uint32_t)b.C, (uint32_t)b.K, 1u, 1u, 0u};
-  gemv_workgroup<PD, LDSB, WV, PU>(lead, b, a.Y[p], blockIdx.x - a.first[p]);
+  gemv_workgroup<PD, LDSB, WV, PU, AL>(lead, b, a.Y[p], blockIdx.x - a.first[p]);
 }
 
 // ------------------------------------------------------------------------------------ GEMV, plane sums
@@ -2845,15 +2845,16 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
   a.count = count;
   size_t need = 0;
   int pu = 0;
+  uint64_t meta = 0;
   for (int p = 0; p < count; ++p) {
     if (!x_dev[p] || !y_dev[p]) return MPQ_ERR_NULL;
     MpqHeader h;
     mpq_status st = make_dev(hdr_host[p], blob_dev[p], &h, &a.b[p]);
     if (st != MPQ_OK) return st;
     if ((((uintptr_t)x_dev[p] | (uintptr_t)y_dev[p]) & 15u) != 0) return MPQ_ERR_ALIGN;
-    if (p > 0 && mpq_pu2(h.g1) != pu) return MPQ_ERR_UNSUPPORTED;
-    if (h.meta != MPQ_META_BYTES) return MPQ_ERR_UNSUPPORTED;
+    if (p > 0 && (mpq_pu2(h.g1) != pu || h.meta != meta)) return MPQ_ERR_UNSUPPORTED;  // one kernel for all of them
     pu = mpq_pu2(h.g1);
+    meta = h.meta;
     const size_t lds = gemv_lds_bytes(h, 2, 8, 1);
     need = lds > need ? lds : need;
     a.X[p] = x_dev[p];
@@ -2866,7 +2867,8 @@ mpq_status mpq_gemv_multi(int32_t count, const void* const* hdr_host, const void
   if (need <= (BYTES)) {                                                                                \
     if (pu == 1) MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 1>), grid, block, 0, s, a);           \
     else if (pu == 2) MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 2>), grid, block, 0, s, a);      \
-    else MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 4>), grid, block, 0, s, a);                   \
+    else if (meta != MPQ_META_PAPER) MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 4>), grid, block, 0, s, a); \
+    else MPQ_LAUNCH((mpq_gemv_multi_kernel<2, (BYTES), 8, 4, true>), grid, block, 0, s, a);             \
     return MPQ_OK;                                                                                      \
   }
   MPQ_MULTI_CLASS(40 * 1024)

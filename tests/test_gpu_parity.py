@@ -532,6 +532,20 @@ def test_several_products_in_one_launch(torch):
     mpq.gemv_multi([pk16.header], [b16], [x16], [y16.view])  # and g1 = 16 on its own
     e_floor, e_max = rel_err(y16.check_and_get(), om16.gemm(synth.make_x(1, 1, pk16.K), threads=8)[0])
     assert e_floor <= TOL, (e_floor, e_max)
+    # the aligned metadata: three matrices in one launch; next to byte-wide metadata there is no common configuration
+    al = [make(c) for c in CASES if len(c) > 9 and c[9] == 1]
+    assert len(al) == 3
+    bl = [to_dev(torch, pk.blob) for _, _, pk in al]
+    Xa = [synth.make_x(950 + p, 1, pk.K) for p, (_, _, pk) in enumerate(al)]
+    xa = [to_dev(torch, X[0].view(np.int16)) for X in Xa]
+    ya = [Guarded(torch, pk.N) for _, _, pk in al]
+    mpq.gemv_multi([pk.header for _, _, pk in al], bl, xa, [y.view for y in ya])
+    for (lg, om, pk), X, y in zip(al, Xa, ya):
+        e_floor, e_max = rel_err(y.check_and_get(), om.gemm(X, threads=8)[0])
+        assert e_floor <= TOL, (lg.spec.name, e_floor, e_max)
+    with pytest.raises(mpq.MpqError) as e:
+        mpq.gemv_multi([pk16.header, al[0][2].header], [b16, bl[0]], [x16, xa[0]], [y16.view, ya[0].view])
+    assert e.value.status == mpq.MPQ_ERR_UNSUPPORTED
 
 
 def test_quantized_float_weights_end_to_end(torch):
