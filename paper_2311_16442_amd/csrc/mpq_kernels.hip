@@ -164,6 +164,16 @@ __device__ __forceinline__ half_t scale_dequant(uint32_t s_int, uint32_t m2) {
   return (half_t)u;
 }
 
+// The same where the second-order zero is stored as an integer 0..15 (aligned metadata, Sec. 3.3 "Zero Padding"):
+// s_int and z2 are small integers, so fp32(s_int) - fp32(z2) is the integer difference converted once.
+__device__ __forceinline__ half_t scale_dequant_int_zero(uint32_t s_int, uint32_t z2, uint32_t s2_bits) {
+#pragma clang fp contract(off)
+  const float t = (float)((int32_t)s_int - (int32_t)z2);
+  float u = t * (float)bits_to_half((uint16_t)s2_bits);
+  asm volatile("" : "+v"(u));  // two roundings, as in scale_dequant
+  return (half_t)u;
+}
+
 // Constants of the decode kept in scalar registers so that v_and_or_b32 / v_pk_fma_f16 can take
 // them as operands (VOP3 encodings on gfx9 have no literal operands).
 __device__ __forceinline__ uint32_t sgpr_const(uint32_t v) {
@@ -266,8 +276,8 @@ __device__ __forceinline__ void pieces_aligned(const uint2 (&ent)[NP], const uns
     }
     const uint32_t idx = (e.y >> 16) + (row >> b.m2_shift);
     const uint32_t s2 = *(const uint16_t*)(side + b.off_s2 + 2u * idx);
-    const half_t z2 = (half_t)(float)*(const uint8_t*)(side + b.off_z2 + idx);  // 0..15: exact
-    const half_t s1 = scale_dequant(s_int, s2 | ((uint32_t)half_to_bits(z2) << 16));  // exactly 0 for a padding piece
+    const uint32_t z2 = *(const uint8_t*)(side + b.off_z2 + idx);  // 0..15
+    const half_t s1 = scale_dequant_int_zero(s_int, z2, s2);       // exactly 0 for a padding piece
     s1p[q] = half2_t{s1, s1};
     zb[q] = bits_to_half((uint16_t)(0x6400u | z1));  // 1024 + z1
     xoff[q] = e.x;
@@ -825,8 +835,8 @@ mpq_mms_kernel(const DevBlob b, const uint16_t* __restrict__ X, float* __restric
         z1 = w >> 4;                                                                                  \
       }                                                                                               \
       const uint32_t s2 = ((b.off_s2 + 2u * idx) & 2u) ? w2[qq] >> 16 : w2[qq] & 0xFFFFu;             \
-      const half_t z2 = (half_t)(float)((w3[qq] >> (8u * ((b.off_z2 + idx) & 3u))) & 0xFFu); /* 0..15: exact */ \
-      const half_t s1 = scale_dequant(s_int, s2 | ((uint32_t)half_to_bits(z2) << 16));  /* exactly 0 for a padding piece */ \
+      const uint32_t z2 = (w3[qq] >> (8u * ((b.off_z2 + idx) & 3u))) & 0xFFu; /* 0..15 */             \
+      const half_t s1 = scale_dequant_int_zero(s_int, z2, s2);  /* exactly 0 for a padding piece */    \
       s1p[qq] = half2_t{s1, s1};                                                                      \
       zb[qq] = bits_to_half((uint16_t)(0x6400u | z1));                                                \
     } else {                                                                                          \
@@ -2132,7 +2142,7 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
       uint32_t at[PU];
 #pragma unroll
       for (int q_ = 0; q_ < PU; ++q_) {
-        uint32_t s_int, z1, m2;
+        uint32_t s_int, z1, m2 = 0;
         at[q_] = r.at[d][q_];
         if constexpr (AL) {
           const uint32_t w = r.ma[d][q_];
@@ -2145,14 +2155,12 @@ mpq_dequant_lines_kernel(const DevBlob b, uint16_t* __restrict__ Wout, const int
             z1 = w >> 4;
           }
           if (at[q_] != DROPPED) at[q_] &= ~3u;
-          const half_t z2 = (half_t)(float)r.mc[d][q_];  // 0..15: exact
-          m2 = r.mb[d][q_] | ((uint32_t)half_to_bits(z2) << 16);
         } else {
           s_int = r.ma[d][q_] & 0xFFu;
           z1 = r.ma[d][q_] >> 8;
           m2 = r.mb[d][q_];
         }
-        const half_t s1 = scale_dequant(s_int, m2);
+        const half_t s1 = AL ? scale_dequant_int_zero(s_int, r.mc[d][AL ? q_ : 0], r.mb[d][q_]) : scale_dequant(s_int, m2);
         s1p[q_] = half2_t{s1, s1};
         zb[q_] = bits_to_half((uint16_t)(0x6400u | z1));  // 1024 + z1
       }
